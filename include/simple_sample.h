@@ -1,0 +1,165 @@
+/*
+ * simple_sample.h -- C boundary of the decision-plane sampling epilogue for AMD MI355X (gfx950).
+ *
+ * One call turns a [B, V] logits matrix that is resident in device memory into B next-token
+ * ids, entirely on the GPU:
+ *
+ *   (1) logits adjustment  Z' = ApplyPenalty(Z, Y_<s)                 (paper section 2.1 Eq. (1);
+ *       repetition / frequency / presence penalties from each row's    penalty algorithm section 2.2;
+ *       token history, touching only the penalised columns             column-wise penalties, 5.2)
+ *   (2) p~ = softmax(Filter(Z' / tau; k, p_nuc, min_p))               (section 2.1 Eq. (2);
+ *       the filter is applied before any normalisation                 truncation-first filtering, 5.2)
+ *   (3) y ~ Categorical(p~), by inverse CDF with a counter-based       (section 2.1 (3); deterministic
+ *       uniform keyed by (seed, row, step)                             random numbers, section 5.1)
+ *   and, when a hot set H is given, speculative hot-vocab sampling:    (section 5.3, Eq. (6)-(9))
+ *       accept a draw from the hot proposal with probability alpha_b, else draw from the tail
+ *       proposal, which reproduces p~ exactly.
+ *
+ * Conventions the paper leaves open (they are the same ones the CPU oracle of this repository
+ * states, so ids can be compared one to one):
+ *   - repetition is sign-aware (z > 0 ? z / rep : z * rep); frequency subtracts freq * count and
+ *     presence subtracts pres on tokens *generated* so far; repetition also sees prompt tokens;
+ *   - temperature 0 selects greedy decoding: argmax of the penalised logits, lowest id on ties;
+ *   - y = z' / tau is an IEEE float32 division; survivors are a prefix of the total order
+ *     (y descending, token id ascending): top-k keeps exactly k, min-p keeps
+ *     y >= fl32(y_max + fl32(ln min_p)), top-p keeps the shortest prefix of the top-k prefix whose
+ *     mass reaches top_p times the top-k prefix mass; the shortest of the three wins, never empty;
+ *   - one Philox4x32-10 block per (row, step): key = (seed lo, seed hi), counter =
+ *     (row_offset + row, step lo, step hi, 0); word w -> (x >> 8) * 2^-24; word 0 drives the draw,
+ *     word 1 the SHVS acceptance test (accept iff u * S_K <= S_H), word 2 the SHVS tail draw;
+ *   - every CDF walk (full, hot, tail) runs in ascending token id and returns the first id whose
+ *     running mass exceeds u * total.
+ *
+ * All pointers named *_dev are DEVICE pointers owned by the caller; the library never frees or
+ * retains them beyond the call.  logits are read-only and never modified.  All work is enqueued
+ * on the given HIP stream and the calls return without synchronising.  Nothing is allocated on
+ * the sampling path: the only allocation happens in simple_create.
+ *
+ * Errors: host-checkable argument errors return a negative code, enqueue nothing and leave
+ * out_ids untouched.  Data errors that only the device can see (NaN or +inf logit, all -inf row,
+ * negative temperature, non-positive repetition penalty, history longer than the context's
+ * capacity) make that row's id -1 and set bits in its diagnostics record; a history id outside
+ * [0, V) is ignored and flagged.
+ *
+ * Determinism: ids depend only on (logits, params, history, hot set, seed, step, global row
+ * index), never on launch geometry or on how a batch is split into calls.
+ */
+#ifndef SIMPLE_SAMPLE_H
+#define SIMPLE_SAMPLE_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct simple_ctx simple_ctx; /* opaque; owns the hot-set bitmap */
+
+enum { SIMPLE_F32 = 0, SIMPLE_BF16 = 1 };
+
+enum {
+  SIMPLE_OK = 0,
+  SIMPLE_EINVAL = -1,    /* bad argument */
+  SIMPLE_ENOMEM = -2,    /* device allocation failed in simple_create */
+  SIMPLE_EDEVICE = -3,   /* a HIP runtime call failed */
+  SIMPLE_ECAPACITY = -4  /* sizes exceed what the context was created for, or the LDS of a CU */
+};
+
+/* One row's sampling controls (32 bytes, device memory, array of B). */
+typedef struct {
+  float temperature;  /* tau; 0 => greedy; must be >= 0 */
+  int32_t top_k;      /* <= 0 or >= V => disabled */
+  float top_p;        /* p_nuc; >= 1 => disabled; <= 0 keeps one token */
+  float min_p;        /* <= 0 => disabled */
+  float rep_penalty;  /* lambda_rep; 1 => disabled; must be > 0 */
+  float freq_penalty; /* 0 => disabled */
+  float pres_penalty; /* 0 => disabled */
+  int32_t n_prompt;   /* the first n_prompt ids of the row's history are prompt tokens (repetition
+                         only); the rest are generated tokens (all three penalties) */
+} simple_row_params;
+
+/* Optional per-row diagnostics (32 bytes, device memory, array of B). */
+typedef struct {
+  double alpha;        /* SHVS hot mass alpha_b = S_H / S_K (Eq. (7)); NaN without a hot set */
+  double s_k;          /* mass of the top-k prefix relative to the row maximum */
+  float p_chosen;      /* p~ of the returned id */
+  int32_t n_survivors; /* |K_b| */
+  uint32_t flags;      /* SIMPLE_DIAG_* */
+  uint32_t reserved;
+} simple_row_diag;
+
+enum {
+  SIMPLE_DIAG_ERROR = 1u << 0,         /* id is -1 */
+  SIMPLE_DIAG_GREEDY = 1u << 1,
+  SIMPLE_DIAG_WIDE = 1u << 2,          /* K_b did not fit the on-chip candidate list: multi-pass route */
+  SIMPLE_DIAG_SHVS = 1u << 3,          /* a hot set was used */
+  SIMPLE_DIAG_ACCEPTED = 1u << 4,      /* SHVS hot candidate accepted */
+  SIMPLE_DIAG_CAREFUL = 1u << 5,       /* candidate list overflowed: segment replayed in small pieces */
+  SIMPLE_DIAG_BAD_PARAM = 1u << 8,
+  SIMPLE_DIAG_BAD_LOGIT = 1u << 9,     /* NaN or +inf logit, or every logit -inf */
+  SIMPLE_DIAG_BAD_HISTORY_ID = 1u << 10, /* ignored */
+  SIMPLE_DIAG_HISTORY_TOO_LONG = 1u << 11,
+  SIMPLE_DIAG_BAD_HOT_SET = 1u << 12   /* hot id outside [0, V) or duplicated (ignored) */
+};
+
+/*
+ * Create a context on HIP device `device` for calls with at most max_V vocabulary entries and at
+ * most max_nnz_per_row history ids per row (0 if no history will ever be passed).  Allocates the
+ * hot-set membership bitmap (max_V bits) in device memory.  Returns SIMPLE_ECAPACITY if one row's
+ * on-chip state (history bitmap, counts, candidate list) cannot fit the LDS of one compute unit.
+ * Host pointers: out.
+ */
+int simple_create(simple_ctx** out, int device, int64_t max_V, int64_t max_nnz_per_row);
+
+/* Free the context (synchronises the device it lives on).  NULL is accepted. */
+void simple_destroy(simple_ctx* ctx);
+
+/*
+ * Install a hot set H (section 5.3) for later calls that pass H = -1: builds the V-bit membership
+ * bitmap on `stream`.  hot_ids_dev: H distinct ids in [0, V), any order (device).  Out-of-range or
+ * duplicate ids are ignored and reported through SIMPLE_DIAG_BAD_HOT_SET on later rows.
+ */
+int simple_set_hot_set(simple_ctx* ctx, const int32_t* hot_ids_dev, int32_t H, int64_t V, void* hip_stream);
+
+/*
+ * The sampling call (section 2.1 steps (1)-(3); section 5.3 when a hot set is in force).
+ *
+ *  logits_dev        [B, row_stride_elems] row-major, dtype SIMPLE_F32 (float) or SIMPLE_BF16
+ *                    (bfloat16 bit patterns, uint16); only the first V columns of a row are read
+ *  params_dev        [B] simple_row_params
+ *  hist_ptr_dev      [B+1] CSR offsets into hist_ids_dev, or NULL for "no history"
+ *  hist_ids_dev      token ids of every row's history (prompt first), or NULL with hist_ptr_dev
+ *  hot_ids_dev, H    hot set for this call: (ptr, H > 0) builds the bitmap on the stream first;
+ *                    (NULL, 0) disables SHVS; (NULL, -1) uses the set installed by
+ *                    simple_set_hot_set for this V
+ *  seed, step        key and counter words of the random numbers; row b uses global row index
+ *                    row_offset + b, so a batch may be split into calls without changing ids
+ *  out_ids_dev       [B] int32 token ids (-1 for a row with a data error)
+ *  diag_dev          [B] simple_row_diag, or NULL
+ *  hip_stream        hipStream_t (NULL = the default stream)
+ *
+ * B = 0 is a no-op that returns SIMPLE_OK.  Returns SIMPLE_EINVAL for NULL required pointers,
+ * B < 0, V <= 0, row_stride_elems < V, an unknown dtype, H < -1, H > V, H = -1 without an
+ * installed set of that V, or hist_ptr_dev given without hist_ids_dev; SIMPLE_ECAPACITY for
+ * V > max_V or history given to a context created with max_nnz_per_row = 0.
+ */
+int simple_sample(simple_ctx* ctx, const void* logits_dev, int64_t B, int64_t V, int dtype,
+                  int64_t row_stride_elems, const simple_row_params* params_dev,
+                  const int64_t* hist_ptr_dev, const int32_t* hist_ids_dev,
+                  const int32_t* hot_ids_dev, int32_t H, uint64_t seed, uint64_t step,
+                  uint64_t row_offset, int32_t* out_ids_dev, simple_row_diag* diag_dev,
+                  void* hip_stream);
+
+/* Bytes of LDS one row's workgroup uses for the given context (for occupancy reasoning). */
+int64_t simple_lds_bytes(const simple_ctx* ctx);
+
+/* Static description of an error code. */
+const char* simple_strerror(int code);
+
+/* Library version: major * 10000 + minor * 100 + patch. */
+int simple_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SIMPLE_SAMPLE_H */

@@ -1,0 +1,172 @@
+// C boundary of the sampling library: argument checks, context, stream-ordered launches.
+// No torch types; every pointer marked *_dev is a device pointer owned by the caller.
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <stdlib.h>
+
+#include <new>
+
+#include "simple_device.hpp"
+#include "simple_kernels.hpp"
+#include "simple_sample.h"
+
+struct simple_ctx {
+  int device;
+  int64_t max_V, max_nnz;
+  uint32_t* hot_bits;   // device, max_V bits
+  uint32_t* hot_flags;  // device, one word
+  int64_t hot_V;        // V the installed hot set was built for, 0 if none
+  int32_t hot_H;
+  int lds_limit;
+};
+
+namespace simple {
+
+static uint32_t align16(uint32_t x) { return (x + 15u) & ~15u; }
+
+LdsLayout make_layout(int64_t V, int64_t max_nnz, bool with_history) {
+  LdsLayout L{};
+  uint32_t off = 0;
+  const uint32_t n_words = (uint32_t)((V + 31) / 32);
+  const uint32_t n_grp = (n_words + 7u) / 8u;
+  L.bitmap = off; if (with_history) off = align16(off + n_grp * 8u * 4u);
+  L.grp = off;    if (with_history) off = align16(off + n_grp * 4u);
+  L.counts = off; if (with_history) off = align16(off + (uint32_t)((max_nnz + 2) / 2) * 4u);
+  L.cand = off;   off = align16(off + (uint32_t)CAP * 8u);
+  L.hist = off;   off = align16(off + (uint32_t)NBINS * 4u);
+  L.total = off;
+  return L;
+}
+
+struct DeviceGuard {
+  int prev = -1; bool ok = false;
+  explicit DeviceGuard(int dev) {
+    if (hipGetDevice(&prev) != hipSuccess) return;
+    ok = (prev == dev) || (hipSetDevice(dev) == hipSuccess);
+    if (prev == dev) prev = -1;
+  }
+  ~DeviceGuard() { if (prev >= 0) (void)hipSetDevice(prev); }
+};
+
+}  // namespace simple
+
+extern "C" {
+
+int simple_version(void) { return 100; }
+
+const char* simple_strerror(int code) {
+  switch (code) {
+    case SIMPLE_OK: return "ok";
+    case SIMPLE_EINVAL: return "invalid argument";
+    case SIMPLE_ENOMEM: return "device allocation failed";
+    case SIMPLE_EDEVICE: return "HIP runtime call failed";
+    case SIMPLE_ECAPACITY: return "size exceeds the context's capacity or the LDS of a compute unit";
+    default: return "unknown error code";
+  }
+}
+
+int simple_create(simple_ctx** out, int device, int64_t max_V, int64_t max_nnz_per_row) {
+  if (!out) return SIMPLE_EINVAL;
+  *out = nullptr;
+  if (max_V <= 0 || max_V >= (int64_t)1 << 30 || max_nnz_per_row < 0 || device < 0) return SIMPLE_EINVAL;
+  if (max_nnz_per_row > 65535) return SIMPLE_ECAPACITY;  // 16-bit per-token counts
+  int n_dev = 0;
+  if (hipGetDeviceCount(&n_dev) != hipSuccess || device >= n_dev) return SIMPLE_EDEVICE;
+  simple::DeviceGuard guard(device);
+  if (!guard.ok) return SIMPLE_EDEVICE;
+  int lds = 0;
+  if (hipDeviceGetAttribute(&lds, hipDeviceAttributeMaxSharedMemoryPerBlock, device) != hipSuccess) return SIMPLE_EDEVICE;
+  const simple::LdsLayout L = simple::make_layout(max_V, max_nnz_per_row, max_nnz_per_row > 0);
+  if ((int64_t)L.total + 1024 > (int64_t)lds) return SIMPLE_ECAPACITY;
+  if (simple::set_max_lds((unsigned)lds - 1024u) != hipSuccess) return SIMPLE_EDEVICE;
+  simple_ctx* c = new (std::nothrow) simple_ctx();
+  if (!c) return SIMPLE_ENOMEM;
+  c->device = device; c->max_V = max_V; c->max_nnz = max_nnz_per_row; c->lds_limit = lds;
+  c->hot_V = 0; c->hot_H = 0; c->hot_bits = nullptr; c->hot_flags = nullptr;
+  const size_t words = (size_t)((max_V + 31) / 32) + 1;
+  if (hipMalloc(reinterpret_cast<void**>(&c->hot_bits), (words + 1) * sizeof(uint32_t)) != hipSuccess) {
+    delete c;
+    return SIMPLE_ENOMEM;
+  }
+  c->hot_flags = c->hot_bits + words;
+  if (hipMemset(c->hot_bits, 0, (words + 1) * sizeof(uint32_t)) != hipSuccess) {
+    (void)hipFree(c->hot_bits);
+    delete c;
+    return SIMPLE_EDEVICE;
+  }
+  *out = c;
+  return SIMPLE_OK;
+}
+
+void simple_destroy(simple_ctx* ctx) {
+  if (!ctx) return;
+  {
+    simple::DeviceGuard guard(ctx->device);
+    if (guard.ok) {
+      (void)hipDeviceSynchronize();
+      if (ctx->hot_bits) (void)hipFree(ctx->hot_bits);
+    }
+  }
+  delete ctx;
+}
+
+int64_t simple_lds_bytes(const simple_ctx* ctx) {
+  if (!ctx) return SIMPLE_EINVAL;
+  return (int64_t)simple::make_layout(ctx->max_V, ctx->max_nnz, ctx->max_nnz > 0).total;
+}
+
+int simple_set_hot_set(simple_ctx* ctx, const int32_t* hot_ids_dev, int32_t H, int64_t V, void* hip_stream) {
+  if (!ctx || !hot_ids_dev || H <= 0 || V <= 0 || H > V) return SIMPLE_EINVAL;
+  if (V > ctx->max_V) return SIMPLE_ECAPACITY;
+  simple::DeviceGuard guard(ctx->device);
+  if (!guard.ok) return SIMPLE_EDEVICE;
+  if (simple::launch_hot_build(hot_ids_dev, H, (int)V, ctx->hot_bits, ctx->hot_flags,
+                               static_cast<hipStream_t>(hip_stream)) != hipSuccess)
+    return SIMPLE_EDEVICE;
+  ctx->hot_V = V; ctx->hot_H = H;
+  return SIMPLE_OK;
+}
+
+int simple_sample(simple_ctx* ctx, const void* logits_dev, int64_t B, int64_t V, int dtype,
+                  int64_t row_stride_elems, const simple_row_params* params_dev,
+                  const int64_t* hist_ptr_dev, const int32_t* hist_ids_dev,
+                  const int32_t* hot_ids_dev, int32_t H, uint64_t seed, uint64_t step,
+                  uint64_t row_offset, int32_t* out_ids_dev, simple_row_diag* diag_dev,
+                  void* hip_stream) {
+  if (!ctx || B < 0 || V <= 0) return SIMPLE_EINVAL;
+  if (dtype != SIMPLE_F32 && dtype != SIMPLE_BF16) return SIMPLE_EINVAL;
+  if (row_stride_elems < V) return SIMPLE_EINVAL;
+  if (H < -1 || (int64_t)H > V) return SIMPLE_EINVAL;
+  if (hot_ids_dev && H <= 0) return SIMPLE_EINVAL;
+  if (!hot_ids_dev && H > 0) return SIMPLE_EINVAL;
+  if (H == -1 && ctx->hot_V != V) return SIMPLE_EINVAL;
+  if (hist_ptr_dev && !hist_ids_dev) return SIMPLE_EINVAL;
+  if (B == 0) return SIMPLE_OK;
+  if (!logits_dev || !params_dev || !out_ids_dev) return SIMPLE_EINVAL;
+  if (B > (int64_t)0x7FFFFFFF) return SIMPLE_EINVAL;
+  if (V > ctx->max_V) return SIMPLE_ECAPACITY;
+  if (hist_ptr_dev && ctx->max_nnz == 0) return SIMPLE_ECAPACITY;
+  simple::DeviceGuard guard(ctx->device);
+  if (!guard.ok) return SIMPLE_EDEVICE;
+  hipStream_t st = static_cast<hipStream_t>(hip_stream);
+  const bool use_hot = (H != 0);
+  if (hot_ids_dev) {
+    if (simple::launch_hot_build(hot_ids_dev, H, (int)V, ctx->hot_bits, ctx->hot_flags, st) != hipSuccess)
+      return SIMPLE_EDEVICE;
+    ctx->hot_V = V; ctx->hot_H = H;
+  }
+  simple::SampleArgs a{};
+  a.logits = logits_dev; a.stride = row_stride_elems; a.V = (int)V; a.B = (int)B;
+  a.params = params_dev; a.hist_ptr = hist_ptr_dev; a.hist_ids = hist_ids_dev;
+  a.hot_bits = use_hot ? ctx->hot_bits : nullptr;
+  a.hot_flags = use_hot ? ctx->hot_flags : nullptr;
+  a.seed = seed; a.step = step; a.row_offset = row_offset;
+  a.out = out_ids_dev; a.diag = diag_dev; a.max_nnz = (int)ctx->max_nnz;
+  a.L = simple::make_layout(V, ctx->max_nnz, hist_ptr_dev != nullptr);
+  const size_t esz = (dtype == SIMPLE_F32) ? 4 : 2;
+  const bool vec = ((reinterpret_cast<uintptr_t>(logits_dev) & 15u) == 0) && (((size_t)row_stride_elems * esz) % 16 == 0);
+  if (simple::launch_sample(a, dtype, vec, st) != hipSuccess) return SIMPLE_EDEVICE;
+  return SIMPLE_OK;
+}
+
+}  // extern "C"

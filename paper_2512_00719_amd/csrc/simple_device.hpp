@@ -1,0 +1,208 @@
+// Device-side building blocks shared by the sampling kernels: orderable float keys, wave/block
+// scans and reductions, the counter-based random numbers, and the per-row history state that
+// drives the penalties.  gfx950 only (wave64).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "simple_sample.h"
+
+namespace simple {
+
+constexpr int NT = 512;        // threads per row workgroup
+constexpr int NW = NT / 64;    // waves per workgroup
+constexpr int CAP = 4096;      // candidate-list capacity (entries)
+constexpr int KMAX = 1024;     // largest prefix the candidate list certifies
+constexpr int NBINS = 2048;    // radix histogram bins (11 bits)
+constexpr int UNROLL = 4;      // 16-byte loads in flight per lane
+constexpr int QBITS = 43;      // fixed-point scale of probability mass on the multi-pass route
+
+__device__ __forceinline__ int lane_id() { return threadIdx.x & 63; }
+__device__ __forceinline__ int wave_id() { return threadIdx.x >> 6; }
+
+// Order-preserving map float -> uint32 (larger float, larger key); -0 and +0 share a key.
+// Keys of non-NaN values lie in [key(-inf), key(+inf)] = [0x007FFFFF, 0xFF800000]; 0 is free and
+// serves as the "dropped entry" mark.
+__device__ __forceinline__ uint32_t fkey(float f) {
+  uint32_t b = __float_as_uint(f);
+  if (b == 0x80000000u) b = 0u;
+  return (b & 0x80000000u) ? ~b : (b | 0x80000000u);
+}
+__device__ __forceinline__ float keyf(uint32_t k) {
+  uint32_t b = (k & 0x80000000u) ? (k & 0x7FFFFFFFu) : ~k;
+  return __uint_as_float(b);
+}
+constexpr uint32_t KEY_NEG_INF = 0x007FFFFFu;
+constexpr uint32_t KEY_POS_INF = 0xFF800000u;
+
+// ---------------------------------------------------------------- wave / block collectives ----
+template <typename T>
+__device__ __forceinline__ T wave_incl_scan(T v) {
+  const int l = lane_id();
+#pragma unroll
+  for (int o = 1; o < 64; o <<= 1) {
+    T t = __shfl_up(v, o, 64);
+    if (l >= o) v += t;
+  }
+  return v;
+}
+template <typename T>
+__device__ __forceinline__ T wave_sum(T v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+  return v;
+}
+__device__ __forceinline__ float wave_max(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
+  return v;
+}
+
+// Block-wide inclusive scan; `ws` is LDS scratch of NW+1 elements.  All threads must call.
+template <typename T>
+__device__ inline T block_incl_scan(T v, T* ws, T& total) {
+  T incl = wave_incl_scan(v);
+  __syncthreads();
+  if (lane_id() == 63) ws[wave_id()] = incl;
+  __syncthreads();
+  T base = 0, tot = 0;
+#pragma unroll
+  for (int w = 0; w < NW; ++w) {
+    T x = ws[w];
+    if (w < wave_id()) base += x;
+    tot += x;
+  }
+  total = tot;
+  return incl + base;
+}
+// Block-wide sum with a fixed reduction tree (bit-reproducible).
+template <typename T>
+__device__ inline T block_sum(T v, T* ws) {
+  T s = wave_sum(v);
+  __syncthreads();
+  if (lane_id() == 0) ws[wave_id()] = s;
+  __syncthreads();
+  T tot = 0;
+#pragma unroll
+  for (int w = 0; w < NW; ++w) tot += ws[w];
+  return tot;
+}
+__device__ inline float block_max(float v, float* ws) {
+  float s = wave_max(v);
+  __syncthreads();
+  if (lane_id() == 0) ws[wave_id()] = s;
+  __syncthreads();
+  float m = ws[0];
+#pragma unroll
+  for (int w = 1; w < NW; ++w) m = fmaxf(m, ws[w]);
+  return m;
+}
+
+// ---------------------------------------------------------------- random numbers --------------
+// Philox4x32 with 10 rounds (Salmon et al., SC'11), one block per (row, step); see the header
+// for the key/counter convention (deterministic random numbers, paper section 5.1).
+__device__ inline void philox4x32_10(uint32_t c0, uint32_t c1, uint32_t c2, uint32_t c3,
+                                     uint32_t k0, uint32_t k1, uint32_t (&out)[4]) {
+  constexpr uint32_t M0 = 0xD2511F53u, M1 = 0xCD9E8D57u, W0 = 0x9E3779B9u, W1 = 0xBB67AE85u;
+#pragma unroll
+  for (int r = 0; r < 10; ++r) {
+    const uint32_t hi0 = __umulhi(M0, c0), lo0 = M0 * c0;
+    const uint32_t hi1 = __umulhi(M1, c2), lo1 = M1 * c2;
+    const uint32_t n0 = hi1 ^ c1 ^ k0, n2 = hi0 ^ c3 ^ k1;
+    c0 = n0; c1 = lo1; c2 = n2; c3 = lo0;
+    if (r < 9) { k0 += W0; k1 += W1; }
+  }
+  out[0] = c0; out[1] = c1; out[2] = c2; out[3] = c3;
+}
+__device__ inline void row_uniforms(uint64_t seed, uint64_t row, uint64_t step, double (&u)[3]) {
+  uint32_t x[4];
+  philox4x32_10((uint32_t)row, (uint32_t)step, (uint32_t)(step >> 32), 0u, (uint32_t)seed,
+                (uint32_t)(seed >> 32), x);
+#pragma unroll
+  for (int i = 0; i < 3; ++i) u[i] = (double)(x[i] >> 8) * 0x1p-24;
+}
+
+// ---------------------------------------------------------------- per-row history state -------
+// The histograms of section 2.2 are never materialised over V.  A row keeps, in LDS:
+//   bits  : V-bit presence mask  M_p or M_o            (which columns are penalised at all)
+//   grp   : number of set bits before each group of 8 mask words (rank directory)
+//   cnt   : 16-bit generated-token counts C_o, indexed by the rank of the id among the set bits
+// so a column's penalty is found in O(1) from its id, and columns outside the history are never
+// touched (column-wise penalties, section 5.2).
+struct History {
+  uint32_t* bits;
+  uint32_t* grp;
+  uint32_t* cnt;  // two 16-bit counters per word
+  int n_words;
+  int distinct;
+  float rep, freq, pres;
+  bool active;
+
+  __device__ __forceinline__ bool test(int id) const { return (bits[id >> 5] >> (id & 31)) & 1u; }
+  __device__ inline int rank(int id) const {
+    const int w = id >> 5, g = w >> 3;
+    int r = grp[g];
+    for (int j = g << 3; j < w; ++j) r += __popc(bits[j]);
+    return r + __popc(bits[w] & ((1u << (id & 31)) - 1u));
+  }
+  __device__ __forceinline__ uint32_t count_at(int r) const { return (cnt[r >> 1] >> ((r & 1) * 16)) & 0xFFFFu; }
+  // Z' for a column that is in the history: repetition (sign-aware), frequency, presence; each
+  // operation rounded to float32 on its own (the file is built with FP contraction off).
+  __device__ __noinline__ float penalise(float z, int id) const {
+    const uint32_t c = count_at(rank(id));
+    z = (z > 0.0f) ? z / rep : z * rep;
+    if (c > 0u) {
+      const float t = freq * (float)c;
+      z = z - t;
+      z = z - pres;
+    }
+    return z;
+  }
+};
+
+// Builds the history state of one row.  hist points at the row's ids (nnz of them, the first
+// n_prompt are prompt tokens).  Returns false (all threads) if some id is outside [0, V).
+__device__ inline bool build_history(History& H, const int32_t* __restrict__ hist, int nnz,
+                                     int n_prompt, int V, uint32_t* scan_ws, uint32_t* flag_ws) {
+  const int tid = threadIdx.x;
+  const int n_grp = (H.n_words + 7) >> 3;
+  for (int i = tid; i < n_grp * 8; i += NT) H.bits[i] = 0u;
+  for (int i = tid; i < (nnz + 1) / 2; i += NT) H.cnt[i] = 0u;
+  if (tid == 0) *flag_ws = 0u;
+  __syncthreads();
+  for (int i = tid; i < nnz; i += NT) {
+    const int id = hist[i];
+    if ((unsigned)id < (unsigned)V) atomicOr(&H.bits[id >> 5], 1u << (id & 31));
+    else atomicOr(flag_ws, 1u);
+  }
+  __syncthreads();
+  // rank directory: exclusive scan of per-group popcounts, NT groups at a time
+  uint32_t carry = 0;
+  for (int g0 = 0; g0 < n_grp; g0 += NT) {
+    const int g = g0 + tid;
+    uint32_t pc = 0;
+    if (g < n_grp) {
+#pragma unroll
+      for (int j = 0; j < 8; ++j) pc += __popc(H.bits[g * 8 + j]);
+    }
+    uint32_t total;
+    const uint32_t incl = block_incl_scan(pc, scan_ws, total);
+    if (g < n_grp) H.grp[g] = carry + incl - pc;
+    carry += total;
+  }
+  H.distinct = (int)carry;
+  __syncthreads();
+  n_prompt = min(max(n_prompt, 0), nnz);
+  for (int i = n_prompt + tid; i < nnz; i += NT) {
+    const int id = hist[i];
+    if ((unsigned)id < (unsigned)V) {
+      const int r = H.rank(id);
+      atomicAdd(&H.cnt[r >> 1], 1u << ((r & 1) * 16));
+    }
+  }
+  __syncthreads();
+  return *flag_ws == 0u;
+}
+
+}  // namespace simple

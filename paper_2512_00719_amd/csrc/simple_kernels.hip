@@ -1,0 +1,995 @@
+// Row sampling kernel for gfx950: one workgroup per logits row.
+//
+// Route taken by a row (all inside one launch):
+//   history state (bitmap + rank directory + counts in LDS)            -- penalties, section 2.2 / 5.2
+//   one coalesced stream over the row that keeps, in an LDS candidate list, every element that
+//   can still belong to the top-k prefix (threshold raised as the list is compacted), and, for
+//   rows whose nucleus is taken over the whole vocabulary, the row's exp-sum   -- truncation first, 5.2
+//   exact selection, softmax and inverse-CDF draw on the candidate list       -- Eq. (2), step (3)
+//   SHVS accept / hot draw / tail draw on the same survivors                  -- section 5.3
+// Rows whose survivor set cannot be certified from the candidate list (top-k above KMAX, a very
+// wide nucleus, no truncation at all) take a multi-pass radix descent over the row instead; it is
+// exact for every input.
+#include <hip/hip_runtime.h>
+#include <math.h>
+#include <stdint.h>
+
+#include "simple_device.hpp"
+#include "simple_kernels.hpp"
+
+namespace simple {
+
+// ------------------------------------------------------------------ element access -------------
+template <typename DT> struct Elem;
+template <> struct Elem<float> {
+  static constexpr int EPL = 4;
+  __device__ static __forceinline__ float one(const float* p) { return *p; }
+  template <bool VEC>
+  __device__ static __forceinline__ void vec(const float* p, float (&z)[4]) {
+    if (VEC) {
+      const float4 v = *reinterpret_cast<const float4*>(p);
+      z[0] = v.x; z[1] = v.y; z[2] = v.z; z[3] = v.w;
+    } else {
+#pragma unroll
+      for (int e = 0; e < 4; ++e) z[e] = p[e];
+    }
+  }
+};
+template <> struct Elem<uint16_t> {  // bfloat16 bit patterns; the upcast to float32 is exact
+  static constexpr int EPL = 8;
+  __device__ static __forceinline__ float one(const uint16_t* p) { return __uint_as_float((uint32_t)(*p) << 16); }
+  template <bool VEC>
+  __device__ static __forceinline__ void vec(const uint16_t* p, float (&z)[8]) {
+    if (VEC) {
+      const uint4 v = *reinterpret_cast<const uint4*>(p);
+      const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        z[2 * i] = __uint_as_float(w[i] << 16);
+        z[2 * i + 1] = __uint_as_float(w[i] & 0xFFFF0000u);
+      }
+    } else {
+#pragma unroll
+      for (int e = 0; e < 8; ++e) z[e] = one(p + e);
+    }
+  }
+};
+
+// ------------------------------------------------------------------ shared row state -----------
+struct Shared {
+  float tau, c_hi, c_lo;
+  int greedy, k_on, k_sel, top_k;
+  float top_p, min_p;
+  unsigned cand_count, n_conv, stage_count, min_key;
+  float g_pass;
+  unsigned flags;
+  unsigned sel_digit, sel_need, sel_cnt, sel_found;
+  unsigned long long sel_above_mass;
+  unsigned sel_above_cnt;
+  unsigned scan_u32[NW + 1];
+  unsigned long long scan_u64[NW + 1];
+  double scan_d[NW + 1];
+  float red_f[NW + 1];
+  unsigned flag_ws;
+  unsigned found_lo, found_hi;
+  int walk_chunk, tie_chunk;
+  unsigned long long walk_base;
+  unsigned walk_ties_before, adm_split[2];
+  int out_id;
+  float out_p;
+};
+
+// Smallest float z with (greedy ? z : z / tau) > yk, found by bisection over the orderable keys
+// (the map z -> fl(z / tau) is monotone).  yk is finite or -inf.
+__device__ inline float min_z_exceeding(float yk, float tau, bool greedy) {
+  uint32_t lo = KEY_NEG_INF, hi = KEY_POS_INF;  // predicate false at lo, true at hi
+  auto pred = [&](uint32_t k) {
+    const float z = keyf(k);
+    return (greedy ? z : z / tau) > yk;
+  };
+  const float guess = greedy ? yk : yk * tau;
+  if (guess > -INFINITY && guess < INFINITY) {  // gallop around the algebraic inverse first
+    const uint32_t c = fkey(guess);
+    uint32_t step = 2;
+    uint32_t a = c, b = c;
+    while (true) {  // walk down until the predicate is false
+      a = (a - KEY_NEG_INF > step) ? a - step : KEY_NEG_INF;
+      if (!pred(a) || a == KEY_NEG_INF) break;
+      step <<= 1;
+    }
+    step = 2;
+    while (true) {  // walk up until it is true
+      b = (KEY_POS_INF - b > step) ? b + step : KEY_POS_INF;
+      if (pred(b) || b == KEY_POS_INF) break;
+      step <<= 1;
+    }
+    lo = a; hi = b;
+  }
+  while (hi - lo > 1u) {
+    const uint32_t mid = lo + ((hi - lo) >> 1);
+    if (pred(mid)) hi = mid; else lo = mid;
+  }
+  return keyf(hi);
+}
+
+// ------------------------------------------------------------------ the stream -----------------
+// Appends the elements flagged in `pm` (bit u*EPL+e) to the candidate list as (float bits, id).
+template <int EPL>
+__device__ inline void append_candidates(Shared& S, uint32_t* ck, uint32_t* ci, unsigned pm,
+                                         const float (&z)[UNROLL][EPL], int tile_base) {
+  const int lane = lane_id();
+  const unsigned my = __popc(pm);
+  const unsigned incl = wave_incl_scan(my);
+  const unsigned total = __shfl(incl, 63, 64);
+  unsigned base = 0;
+  if (lane == 63) base = atomicAdd(&S.cand_count, total);
+  base = __shfl(base, 63, 64);
+  unsigned slot = base + incl - my;
+#pragma unroll
+  for (int u = 0; u < UNROLL; ++u) {
+#pragma unroll
+    for (int e = 0; e < EPL; ++e) {
+      if ((pm >> (u * EPL + e)) & 1u) {
+        if (slot < (unsigned)CAP) {
+          ck[slot] = __float_as_uint(z[u][e]);
+          ci[slot] = (uint32_t)(tile_base + u * 64 * EPL + lane * EPL + e);
+        }
+        ++slot;
+      }
+    }
+  }
+}
+
+// Streams columns [seg0, seg1) of the row once.  Every element with !(z < g) goes to the
+// candidate list.  FULL: penalties are applied to every element before the test and the row's
+// running (max, exp-sum) is updated (needed when the nucleus is taken over all of V).  Otherwise
+// the raw logit is tested -- valid because the penalties of such rows can only lower a logit --
+// and the penalty is applied when the list is compacted.
+template <typename DT, bool VEC, bool FULL>
+__device__ inline void stream_range(const DT* __restrict__ rowp, int seg0, int seg1, float g,
+                                    const History& H, bool do_sum, float c_hi, float c_lo,
+                                    float& m_t, double& s_t, Shared& S, uint32_t* ck, uint32_t* ci) {
+  constexpr int EPL = Elem<DT>::EPL;
+  constexpr int T = 64 * EPL * UNROLL;
+  const int lane = lane_id();
+  for (int tb = seg0 + wave_id() * T; tb < seg1; tb += NW * T) {
+    float z[UNROLL][EPL];
+    const bool full = (tb + T <= seg1);
+    if (full) {
+#pragma unroll
+      for (int u = 0; u < UNROLL; ++u) Elem<DT>::template vec<VEC>(rowp + tb + u * 64 * EPL + lane * EPL, z[u]);
+    } else {
+#pragma unroll
+      for (int u = 0; u < UNROLL; ++u) {
+#pragma unroll
+        for (int e = 0; e < EPL; ++e) {
+          const int idx = tb + u * 64 * EPL + lane * EPL + e;
+          z[u][e] = (idx < seg1) ? Elem<DT>::one(rowp + idx) : -INFINITY;
+        }
+      }
+    }
+    if (FULL) {
+#pragma unroll
+      for (int u = 0; u < UNROLL; ++u) {
+        const int idx0 = tb + u * 64 * EPL + lane * EPL;
+        if (H.active && idx0 < seg1) {
+          const unsigned bits = (H.bits[idx0 >> 5] >> (idx0 & 31)) & ((1u << EPL) - 1u);
+          if (bits) {
+#pragma unroll
+            for (int e = 0; e < EPL; ++e)
+              if (((bits >> e) & 1u) && idx0 + e < seg1) z[u][e] = H.penalise(z[u][e], idx0 + e);
+          }
+        }
+        if (do_sum) {
+          float vmax = z[u][0];
+#pragma unroll
+          for (int e = 1; e < EPL; ++e) vmax = fmaxf(vmax, z[u][e]);
+          if (vmax > m_t) {
+            const float d = m_t - vmax;
+            s_t *= (double)__builtin_amdgcn_exp2f(fmaf(d, c_hi, d * c_lo));
+            m_t = vmax;
+          }
+          float ps = 0.0f;
+#pragma unroll
+          for (int e = 0; e < EPL; ++e) {
+            const float d = z[u][e] - m_t;
+            ps += __builtin_amdgcn_exp2f(fmaf(d, c_hi, d * c_lo));
+          }
+          s_t += (double)ps;
+        }
+      }
+    }
+    unsigned long long any = 0ull;
+#pragma unroll
+    for (int u = 0; u < UNROLL; ++u) {
+#pragma unroll
+      for (int e = 0; e < EPL; ++e) any |= __ballot(!(z[u][e] < g));
+    }
+    if (any) {
+      unsigned pm = 0u;
+#pragma unroll
+      for (int u = 0; u < UNROLL; ++u) {
+#pragma unroll
+        for (int e = 0; e < EPL; ++e) {
+          const int idx = tb + u * 64 * EPL + lane * EPL + e;
+          if (!(z[u][e] < g) && (full || idx < seg1)) pm |= 1u << (u * EPL + e);
+        }
+      }
+      if (__ballot(pm != 0u)) append_candidates<EPL>(S, ck, ci, pm, z, tb);
+    }
+  }
+}
+
+// Element-at-a-time replay of [p0, p1) used only after the candidate list overflowed.
+template <typename DT, bool FULL>
+__device__ inline void stream_careful(const DT* __restrict__ rowp, int p0, int p1, float g,
+                                      const History& H, Shared& S, uint32_t* ck, uint32_t* ci) {
+  for (int idx = p0 + (int)threadIdx.x; idx < p1; idx += NT) {
+    float z = Elem<DT>::one(rowp + idx);
+    if (FULL && H.active && H.test(idx)) z = H.penalise(z, idx);
+    if (!(z < g)) {
+      const unsigned slot = atomicAdd(&S.cand_count, 1u);
+      if (slot < (unsigned)CAP) { ck[slot] = __float_as_uint(z); ci[slot] = (uint32_t)idx; }
+    }
+  }
+}
+
+// ------------------------------------------------------------------ candidate list -------------
+__device__ __forceinline__ unsigned long long composite(uint32_t key, uint32_t id) {
+  return ((unsigned long long)key << 32) | (unsigned long long)(0xFFFFFFFFu - id);
+}
+
+// Converts freshly appended entries to orderable keys of y = z'/tau, then keeps exactly the best
+// min(k_sel, valid) entries in the order (y descending, id ascending) and raises the stream
+// threshold to the smallest logit that can still beat the worst kept entry.  Entries arrive in
+// ascending id, so a later element never wins a tie: the threshold is strict.
+__device__ inline void compact(Shared& S, uint32_t* ck, uint32_t* ci, uint32_t* hist,
+                               const History& H, bool apply_pen) {
+  const int tid = threadIdx.x;
+  __syncthreads();
+  const unsigned n = min(S.cand_count, (unsigned)CAP);
+  const unsigned n_conv = S.n_conv;
+  unsigned my_valid = 0;
+  for (unsigned i = n_conv + tid; i < n; i += NT) {
+    float z = __uint_as_float(ck[i]);
+    const int id = (int)ci[i];
+    if (apply_pen && H.active && H.test(id)) z = H.penalise(z, id);
+    uint32_t key = 0u;
+    if (z != z || z == INFINITY) {
+      atomicOr(&S.flags, SIMPLE_DIAG_ERROR | SIMPLE_DIAG_BAD_LOGIT);
+    } else {
+      const float y = S.greedy ? z : z / S.tau;
+      if (y == INFINITY) atomicOr(&S.flags, SIMPLE_DIAG_ERROR | SIMPLE_DIAG_BAD_LOGIT);
+      else key = fkey(y);
+    }
+    ck[i] = key;
+    my_valid += (key != 0u);
+  }
+  const unsigned n_valid = n_conv + block_sum(my_valid, S.scan_u32);
+  const unsigned k_sel = (unsigned)S.k_sel;
+  unsigned long long prefix = 0ull;
+  int shift = 64;
+  if (n_valid > k_sel) {  // radix select of the k_sel-th largest composite
+    unsigned need = k_sel;
+    const int widths[6] = {11, 11, 10, 11, 11, 10};
+    for (int lvl = 0; lvl < 6; ++lvl) {
+      const int w = widths[lvl];
+      shift -= w;
+      for (int i = tid; i < NBINS; i += NT) hist[i] = 0u;
+      __syncthreads();
+      for (unsigned i = tid; i < n; i += NT) {
+        const uint32_t key = ck[i];
+        if (!key) continue;
+        const unsigned long long c = composite(key, ci[i]);
+        if (lvl == 0 || (c >> (shift + w)) == prefix) atomicAdd(&hist[(unsigned)(c >> shift) & ((1u << w) - 1u)], 1u);
+      }
+      __syncthreads();
+      unsigned local[4], tsum = 0;
+#pragma unroll
+      for (int j = 0; j < 4; ++j) { local[j] = hist[4 * tid + j]; tsum += local[j]; }
+      unsigned total;
+      const unsigned incl = block_incl_scan(tsum, S.scan_u32, total);
+      unsigned above = total - incl;
+#pragma unroll
+      for (int j = 3; j >= 0; --j) {
+        if (above < need && need <= above + local[j]) {
+          S.sel_digit = 4 * tid + j; S.sel_need = need - above; S.sel_cnt = local[j];
+        }
+        above += local[j];
+      }
+      __syncthreads();
+      prefix = (prefix << w) | S.sel_digit;
+      need = S.sel_need;
+      const bool take_all = (S.sel_cnt == need);
+      if (take_all) break;
+    }
+  }
+  __syncthreads();
+  if (tid == 0) { S.stage_count = 0u; S.min_key = 0xFFFFFFFFu; }
+  __syncthreads();
+  uint32_t* stage_key = hist;
+  uint32_t* stage_id = hist + KMAX;
+  for (unsigned i = tid; i < n; i += NT) {
+    const uint32_t key = ck[i];
+    if (!key) continue;
+    const uint32_t id = ci[i];
+    if (shift == 64 || (composite(key, id) >> shift) >= prefix) {
+      const unsigned slot = atomicAdd(&S.stage_count, 1u);
+      stage_key[slot] = key; stage_id[slot] = id;
+      atomicMin(&S.min_key, key);
+    }
+  }
+  __syncthreads();
+  const unsigned kept = S.stage_count;
+  for (unsigned i = tid; i < kept; i += NT) { ck[i] = stage_key[i]; ci[i] = stage_id[i]; }
+  if (tid == 0) {
+    S.cand_count = kept; S.n_conv = kept;
+    S.g_pass = (kept == k_sel) ? min_z_exceeding(keyf(S.min_key), S.tau, S.greedy) : -INFINITY;
+  }
+  __syncthreads();
+}
+
+// Bitonic sort of n (power of two) entries by composite; descending when `desc`.
+__device__ inline void bitonic_sort(uint32_t* key, uint32_t* id, unsigned n, bool desc) {
+  for (unsigned k = 2; k <= n; k <<= 1) {
+    for (unsigned j = k >> 1; j > 0; j >>= 1) {
+      for (unsigned i = threadIdx.x; i < n; i += NT) {
+        const unsigned p = i ^ j;
+        if (p > i) {
+          const unsigned long long a = composite(key[i], id[i]), b = composite(key[p], id[p]);
+          const bool up = ((i & k) == 0) == desc;  // this pair wants the larger composite first
+          if (up ? (a < b) : (a > b)) {
+            const uint32_t tk = key[i], ti = id[i];
+            key[i] = key[p]; id[i] = id[p]; key[p] = tk; id[p] = ti;
+          }
+        }
+      }
+      __syncthreads();
+    }
+  }
+}
+
+struct Draws { double u_draw, u_acc, u_tail; };
+
+// Exact selection, softmax and draw on the compacted candidate list (<= KMAX entries, the best of
+// the row).  Returns false when the list cannot certify the survivor set K_b.
+__device__ inline bool finalize_small(Shared& S, uint32_t* ck, uint32_t* ci, int V, double S_total,
+                                      const Draws& U, const uint32_t* __restrict__ hot_bits,
+                                      simple_row_diag& dg) {
+  const int tid = threadIdx.x;
+  const unsigned n_c = S.cand_count;
+  if (n_c == 0u || (S.flags & SIMPLE_DIAG_ERROR)) { if (tid == 0) S.flags |= SIMPLE_DIAG_ERROR | SIMPLE_DIAG_BAD_LOGIT; return true; }
+  unsigned npad = 2;
+  while (npad < n_c) npad <<= 1;
+  for (unsigned i = n_c + tid; i < npad; i += NT) { ck[i] = 0u; ci[i] = 0xFFFFFFFFu; }
+  __syncthreads();
+  bitonic_sort(ck, ci, npad, true);
+  if (ck[0] == KEY_NEG_INF) { if (tid == 0) S.flags |= SIMPLE_DIAG_ERROR | SIMPLE_DIAG_BAD_LOGIT; return true; }
+  if (S.greedy) {
+    if (tid == 0) { S.out_id = (int)ci[0]; S.out_p = 1.0f; }
+    dg.n_survivors = 1;
+    return true;
+  }
+  double* wv = reinterpret_cast<double*>(ck + KMAX);  // weights in sorted order (8 KB)
+  const float y0 = keyf(ck[0]);
+  // two consecutive entries per thread
+  const unsigned i0 = 2u * tid, i1 = i0 + 1u;
+  const double w0 = (i0 < n_c) ? exp((double)keyf(ck[i0]) - (double)y0) : 0.0;
+  const double w1 = (i1 < n_c) ? exp((double)keyf(ck[i1]) - (double)y0) : 0.0;
+  if (i0 < n_c) wv[i0] = w0;
+  if (i1 < n_c) wv[i1] = w1;
+  double tot;
+  const double incl = block_incl_scan(w0 + w1, S.scan_d, tot);
+  const double cum0 = incl - w1, cum1 = incl;  // inclusive prefix masses in sorted order
+  const bool complete = S.k_on || (n_c == (unsigned)V);
+  const double S_k = complete ? tot : S_total;
+  // min-p: how many listed entries satisfy y >= fl32(y_max + fl32(ln min_p))
+  unsigned n_m = n_c;
+  bool known = complete;
+  if (S.min_p > 0.0f) {
+    const float thr = y0 + (float)log((double)S.min_p);
+    unsigned c = 0;
+    if (i0 < n_c && keyf(ck[i0]) >= thr) ++c;
+    if (i1 < n_c && keyf(ck[i1]) >= thr) ++c;
+    n_m = block_sum(c, S.scan_u32);
+    if (n_m < n_c) known = true;
+  }
+  unsigned n_p = n_c;
+  if (S.top_p < 1.0f) {
+    if (S.top_p <= 0.0f) { n_p = 1; known = true; }
+    else {
+      const double target = (double)S.top_p * S_k;
+      unsigned c = 0;
+      if (i0 < n_c && cum0 < target) ++c;
+      if (i1 < n_c && cum1 < target) ++c;
+      const unsigned n_lt = block_sum(c, S.scan_u32);
+      if (n_lt < n_c) { n_p = n_lt + 1u; known = true; }
+    }
+  }
+  if (!known) return false;
+  const unsigned n = max(1u, min(n_c, min(n_m, n_p)));
+  dg.n_survivors = (int)n;
+  dg.s_k = S_k;
+  // survivors -> ascending token id, payload = position in the sorted order
+  __syncthreads();
+  unsigned np2 = 2;
+  while (np2 < n) np2 <<= 1;
+  for (unsigned i = tid; i < np2; i += NT) {
+    if (i < n) ck[i] = i; else { ck[i] = 0u; ci[i] = 0xFFFFFFFFu; }
+  }
+  __syncthreads();
+  // ascending id == ascending composite of (key = 0, id) inverted: sort on id only
+  for (unsigned k = 2; k <= np2; k <<= 1) {
+    for (unsigned j = k >> 1; j > 0; j >>= 1) {
+      for (unsigned i = tid; i < np2; i += NT) {
+        const unsigned p = i ^ j;
+        if (p > i) {
+          const bool asc = ((i & k) == 0);
+          const uint32_t a = ci[i], b = ci[p];
+          if (asc ? (a > b) : (a < b)) {
+            ci[i] = b; ci[p] = a;
+            const uint32_t t = ck[i]; ck[i] = ck[p]; ck[p] = t;
+          }
+        }
+      }
+      __syncthreads();
+    }
+  }
+  const bool use_hot = hot_bits != nullptr;
+  double a0 = 0.0, a1 = 0.0;  // weights of this thread's two entries, ascending id
+  bool h0 = false, h1 = false;
+  if (i0 < n) { a0 = wv[ck[i0]]; if (use_hot) h0 = (hot_bits[ci[i0] >> 5] >> (ci[i0] & 31)) & 1u; }
+  if (i1 < n) { a1 = wv[ck[i1]]; if (use_hot) h1 = (hot_bits[ci[i1] >> 5] >> (ci[i1] & 31)) & 1u; }
+  double S_K;
+  block_incl_scan(a0 + a1, S.scan_d, S_K);
+  bool pick_hot = false;
+  double S_H = 0.0, S_T = 0.0;
+  if (use_hot) {
+    block_incl_scan((h0 ? a0 : 0.0) + (h1 ? a1 : 0.0), S.scan_d, S_H);
+    block_incl_scan((h0 ? 0.0 : a0) + (h1 ? 0.0 : a1), S.scan_d, S_T);
+    pick_hot = (S_H > 0.0) && (U.u_acc * S_K <= S_H);
+    dg.alpha = S_H / S_K;
+    dg.flags |= SIMPLE_DIAG_SHVS | (pick_hot ? SIMPLE_DIAG_ACCEPTED : 0u);
+  }
+  // the walk: entries of the chosen class in ascending id, first running mass above the target
+  const bool in0 = use_hot ? (h0 == pick_hot) : true, in1 = use_hot ? (h1 == pick_hot) : true;
+  const double b0 = in0 ? a0 : 0.0, b1 = in1 ? a1 : 0.0;
+  double cls_total;
+  const double inclw = block_incl_scan(b0 + b1, S.scan_d, cls_total);
+  const double total = use_hot ? (pick_hot ? S_H : S_T) : S_K;
+  const double target = (use_hot ? (pick_hot ? U.u_draw : U.u_tail) : U.u_draw) * total;
+  if (tid == 0) { S.found_lo = 0xFFFFFFFFu; S.found_hi = 0u; }
+  __syncthreads();
+  const double c0 = inclw - b1, c1 = inclw;
+  if (i0 < n && in0 && b0 > 0.0) { if (c0 > target) atomicMin(&S.found_lo, i0); atomicMax(&S.found_hi, i0 + 1u); }
+  if (i1 < n && in1 && b1 > 0.0) { if (c1 > target) atomicMin(&S.found_lo, i1); atomicMax(&S.found_hi, i1 + 1u); }
+  __syncthreads();
+  if (tid == 0) {
+    unsigned pos = S.found_lo;
+    if (pos == 0xFFFFFFFFu) pos = S.found_hi ? S.found_hi - 1u : 0u;  // rounding: last id of positive weight
+    S.out_id = (int)ci[pos];
+    S.out_p = (float)(wv[ck[pos]] / S_K);
+  }
+  return true;
+}
+
+// ------------------------------------------------------------------ multi-pass route -----------
+template <typename DT>
+struct RowReader {
+  const DT* p; int V; float tau; bool greedy; const History* H;
+  __device__ __forceinline__ uint32_t ykey(int idx) const {  // 0 for a NaN / +inf element
+    float z = Elem<DT>::one(p + idx);
+    if (H->active && H->test(idx)) z = H->penalise(z, idx);
+    if (z != z || z == INFINITY) return 0u;
+    const float y = greedy ? z : z / tau;
+    return (y == INFINITY) ? 0u : fkey(y);
+  }
+};
+template <typename DT, class F>
+__device__ __forceinline__ void scan_row(const RowReader<DT>& R, F f) {
+  const int lane = lane_id();
+  for (int base = wave_id() * 512; base < R.V; base += NW * 512) {
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      const int idx = base + j * 64 + lane;
+      if (idx < R.V) f(R.ykey(idx), idx);
+    }
+  }
+}
+
+struct Cut {  // the prefix {key > t} plus the first r (by id) of {key == t}
+  uint32_t t; uint32_t cnt_gt; unsigned long long mass_gt; uint32_t cnt_eq; uint32_t r; unsigned long long q_t;
+};
+
+__device__ __forceinline__ unsigned long long qmass(uint32_t key, float ymax) {
+  const double w = exp((double)keyf(key) - (double)ymax);
+  return (unsigned long long)__double2ull_rn(w * (double)(1ull << QBITS));
+}
+
+// Radix descent over the 32-bit key of y (three levels: 11, 11, 10 bits) with exact integer
+// count and fixed-point mass histograms.  by_mass = false: finds the key of the need_cnt-th
+// largest element.  by_mass = true: finds the key at which the running mass (largest first)
+// reaches T.  `lim` (optional) restricts the descent to the prefix described by another cut.
+template <typename DT>
+__device__ inline Cut descend(const RowReader<DT>& R, Shared& S, uint32_t* hcnt,
+                              unsigned long long* hmass, float ymax, bool by_mass,
+                              uint32_t need_cnt, double T, const Cut* lim) {
+  const int tid = threadIdx.x;
+  uint32_t prefix = 0u, base_c = 0u;
+  unsigned long long base_m = 0ull;
+  uint32_t need = need_cnt;
+  const int widths[3] = {11, 11, 10};
+  int shift = 32;
+  for (int lvl = 0; lvl < 3; ++lvl) {
+    const int w = widths[lvl];
+    shift -= w;
+    for (int i = tid; i < NBINS; i += NT) { hcnt[i] = 0u; hmass[i] = 0ull; }
+    if (tid == 0) S.sel_found = 0u;
+    __syncthreads();
+    scan_row(R, [&](uint32_t key, int) {
+      if (!key) return;
+      if (lim && key < lim->t) return;
+      if (lvl > 0 && (key >> (shift + w)) != prefix) return;
+      const unsigned d = (key >> shift) & ((1u << w) - 1u);
+      atomicAdd(&hcnt[d], 1u);
+      atomicAdd(&hmass[d], qmass(key, ymax));
+    });
+    __syncthreads();
+    if (lim && tid == 0 && (lvl == 0 || (lim->t >> (shift + w)) == prefix)) {
+      const unsigned d = (lim->t >> shift) & ((1u << w) - 1u);  // ties beyond the limit's r do not count
+      hcnt[d] -= (lim->cnt_eq - lim->r);
+      hmass[d] -= (unsigned long long)(lim->cnt_eq - lim->r) * lim->q_t;
+    }
+    __syncthreads();
+    unsigned lc[4], tc = 0;
+    unsigned long long lm[4], tm = 0;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) { lc[j] = hcnt[4 * tid + j]; lm[j] = hmass[4 * tid + j]; tc += lc[j]; tm += lm[j]; }
+    unsigned totc; unsigned long long totm;
+    const unsigned ic = block_incl_scan(tc, S.scan_u32, totc);
+    const unsigned long long im = block_incl_scan(tm, S.scan_u64, totm);
+    unsigned above_c = totc - ic;
+    unsigned long long above_m = totm - im;
+#pragma unroll
+    for (int j = 3; j >= 0; --j) {
+      bool hit;
+      if (by_mass) hit = ((double)(base_m + above_m) < T) && (T <= (double)(base_m + above_m + lm[j]));
+      else hit = (above_c < need) && (need <= above_c + lc[j]);
+      if (hit) {
+        S.sel_digit = 4 * tid + j; S.sel_above_cnt = above_c; S.sel_above_mass = above_m;
+        S.sel_cnt = lc[j]; S.sel_found = 1u;
+      }
+      above_c += lc[j]; above_m += lm[j];
+    }
+    __syncthreads();
+    if (!S.sel_found) {  // cannot happen for consistent inputs; fail the row rather than guess
+      if (tid == 0) S.flags |= SIMPLE_DIAG_ERROR;
+      Cut bad = {KEY_POS_INF, 0u, 0ull, 0u, 0u, 0ull};
+      return bad;
+    }
+    prefix = (prefix << w) | S.sel_digit;
+    base_c += S.sel_above_cnt;
+    base_m += S.sel_above_mass;
+    if (!by_mass) need -= S.sel_above_cnt;
+  }
+  Cut c;
+  c.t = prefix; c.cnt_gt = base_c; c.mass_gt = base_m; c.cnt_eq = S.sel_cnt; c.q_t = qmass(prefix, ymax);
+  c.r = 0u;
+  __syncthreads();
+  return c;
+}
+
+// Exact route for any row: survivor set as a cut (t, r), then the inverse-CDF walk in ascending
+// id through per-chunk masses.  `lds` is the candidate-list region (32 KB), free on this route.
+template <typename DT>
+__device__ inline void wide_route(const RowReader<DT>& R, Shared& S, uint32_t* hist, unsigned char* lds,
+                                  const Draws& U, const uint32_t* __restrict__ hot_bits,
+                                  simple_row_diag& dg) {
+  const int tid = threadIdx.x, lane = lane_id(), V = R.V;
+  unsigned long long* hmass = reinterpret_cast<unsigned long long*>(lds);  // 16 KB
+  // pass A: row maximum and validity
+  uint32_t mk = 0u; unsigned bad = 0u;
+  scan_row(R, [&](uint32_t key, int) { if (!key) bad = 1u; mk = max(mk, key); });
+  {
+    __syncthreads();
+    if (tid == 0) { S.found_hi = 0u; S.flag_ws = 0u; }
+    __syncthreads();
+    atomicMax(&S.found_hi, mk);
+    if (bad) atomicOr(&S.flag_ws, 1u);
+    __syncthreads();
+  }
+  const uint32_t maxkey = S.found_hi;
+  if (S.flag_ws || maxkey <= KEY_NEG_INF) { if (tid == 0) S.flags |= SIMPLE_DIAG_ERROR | SIMPLE_DIAG_BAD_LOGIT; return; }
+  const float ymax = keyf(maxkey);
+  if (S.greedy) {  // lowest id attaining the maximum
+    if (tid == 0) S.found_lo = 0xFFFFFFFFu;
+    __syncthreads();
+    scan_row(R, [&](uint32_t key, int idx) { if (key == maxkey) atomicMin(&S.found_lo, (unsigned)idx); });
+    __syncthreads();
+    if (tid == 0) { S.out_id = (int)S.found_lo; S.out_p = 1.0f; }
+    dg.n_survivors = 1;
+    return;
+  }
+  // pass D: total mass, and count / mass of the min-p prefix
+  const uint32_t thr_key = (S.min_p > 0.0f) ? fkey(ymax + (float)log((double)S.min_p)) : KEY_NEG_INF;
+  unsigned c_ge = 0; unsigned long long m_ge = 0ull, m_all = 0ull;
+  scan_row(R, [&](uint32_t key, int) {
+    const unsigned long long q = qmass(key, ymax);
+    m_all += q;
+    if (key >= thr_key) { ++c_ge; m_ge += q; }
+  });
+  const unsigned n_m = block_sum(c_ge, S.scan_u32);
+  const unsigned long long mass_m = block_sum(m_ge, S.scan_u64);
+  const unsigned long long mass_all = block_sum(m_all, S.scan_u64);
+  // top-k prefix
+  Cut ck_;
+  unsigned long long S_k;
+  if (S.k_on) {
+    ck_ = descend(R, S, hist, hmass, ymax, false, (uint32_t)S.top_k, 0.0, nullptr);
+    if (S.flags & SIMPLE_DIAG_ERROR) return;
+    ck_.r = (uint32_t)S.top_k - ck_.cnt_gt;
+    S_k = ck_.mass_gt + (unsigned long long)ck_.r * ck_.q_t;
+  } else {
+    S_k = mass_all;
+  }
+  const unsigned n_k = S.k_on ? (unsigned)S.top_k : (unsigned)V;
+  // nucleus inside the top-k prefix
+  Cut cp_; unsigned n_p = n_k;
+  bool have_p = false;
+  if (S.top_p < 1.0f && S.top_p > 0.0f) {
+    const double T = (double)S.top_p * (double)S_k;
+    cp_ = descend(R, S, hist, hmass, ymax, true, 0u, T, S.k_on ? &ck_ : nullptr);
+    if (S.flags & SIMPLE_DIAG_ERROR) return;
+    // smallest r >= 1 with mass_gt + r * q_t >= T
+    double rr = ceil((T - (double)cp_.mass_gt) / (double)cp_.q_t);
+    unsigned r = (rr < 1.0) ? 1u : (rr > (double)cp_.cnt_eq ? cp_.cnt_eq : (unsigned)rr);
+    while (r > 1u && (double)(cp_.mass_gt + (unsigned long long)(r - 1u) * cp_.q_t) >= T) --r;
+    while (r < cp_.cnt_eq && (double)(cp_.mass_gt + (unsigned long long)r * cp_.q_t) < T) ++r;
+    cp_.r = r;
+    n_p = cp_.cnt_gt + r;
+    have_p = true;
+  } else if (S.top_p <= 0.0f) {
+    n_p = 1u;
+  }
+  const unsigned n = max(1u, min(n_k, min(n_m, n_p)));
+  Cut cut;
+  if (n == 1u && !(have_p && n_p == 1u) && !(S.k_on && n_k == 1u)) {
+    cut = Cut{maxkey, 0u, 0ull, 1u, 1u, 1ull << QBITS};  // the single best token: lowest id at the maximum
+  } else if (have_p && n == n_p) {
+    cut = cp_;
+  } else if (S.k_on && n == n_k) {
+    cut = ck_;
+  } else {  // the min-p prefix {key >= thr_key}, or everything
+    cut = Cut{thr_key - 1u, n_m, mass_m, 0u, 0u, 0ull};
+  }
+  dg.n_survivors = (int)n;
+  dg.s_k = (double)S_k * (1.0 / (double)(1ull << QBITS));
+  __syncthreads();
+  // pass F1: per-chunk survivor mass (class 0 = tail / everything, class 1 = hot) and tie counts
+  const bool use_hot = hot_bits != nullptr;
+  int J = 8;
+  while ((long long)64 * J * 1024 < (long long)V) J <<= 1;
+  const int CH = 64 * J, NC = (V + CH - 1) / CH;
+  unsigned long long* cm = reinterpret_cast<unsigned long long*>(lds);  // [2][NC]
+  unsigned* ct = reinterpret_cast<unsigned*>(lds + (size_t)16 * NC);   // [2][NC]
+  for (int c = wave_id(); c < NC; c += NW) {
+    unsigned long long m[2] = {0ull, 0ull}; unsigned t[2] = {0u, 0u};
+    for (int j = 0; j < J; ++j) {
+      const int idx = c * CH + j * 64 + lane;
+      if (idx < V) {
+        const uint32_t key = R.ykey(idx);
+        if (key >= cut.t && key) {
+          const int cls = use_hot ? ((hot_bits[idx >> 5] >> (idx & 31)) & 1u) : 0;
+          if (key > cut.t) m[cls] += qmass(key, ymax); else t[cls] += 1u;
+        }
+      }
+    }
+#pragma unroll
+    for (int x = 0; x < 2; ++x) { m[x] = wave_sum(m[x]); t[x] = wave_sum(t[x]); }
+    if (lane == 0) { cm[c] = m[0]; cm[NC + c] = m[1]; ct[c] = t[0]; ct[NC + c] = t[1]; }
+  }
+  __syncthreads();
+  // which chunk holds the r-th tie (ties are admitted in ascending id)
+  if (tid == 0) {
+    int tc = NC;  // all ties admitted
+    unsigned seen = 0;
+    if (cut.r < cut.cnt_eq) {
+      tc = -1;
+      for (int c = 0; c < NC; ++c) {
+        const unsigned here = ct[c] + ct[NC + c];
+        if (seen + here > cut.r) { tc = c; break; }
+        seen += here;
+      }
+      if (tc < 0) tc = NC;
+    }
+    S.tie_chunk = tc; S.walk_ties_before = seen; S.adm_split[0] = 0u; S.adm_split[1] = 0u;
+  }
+  __syncthreads();
+  const int tie_chunk = S.tie_chunk;
+  if (tie_chunk < NC && wave_id() == 0) {  // split of the admitted ties of that chunk by class
+    unsigned left = cut.r - S.walk_ties_before, a[2] = {0u, 0u};
+    for (int j = 0; j < J; ++j) {
+      const int idx = tie_chunk * CH + j * 64 + lane;
+      const bool tie = (idx < V) && (R.ykey(idx) == cut.t);
+      const unsigned long long mask = __ballot(tie);
+      const unsigned rank = __popcll(mask & ((1ull << lane) - 1ull));
+      if (tie && rank < left) {
+        const int cls = use_hot ? ((hot_bits[idx >> 5] >> (idx & 31)) & 1u) : 0;
+        a[cls] += 1u;
+      }
+      const unsigned here = __popcll(mask);
+      left = (here >= left) ? 0u : left - here;
+    }
+    a[0] = wave_sum(a[0]); a[1] = wave_sum(a[1]);
+    if (lane == 0) { S.adm_split[0] = a[0]; S.adm_split[1] = a[1]; }
+  }
+  __syncthreads();
+  unsigned long long part[2] = {0ull, 0ull};
+  for (int c = tid; c < NC; c += NT) {
+#pragma unroll
+    for (int x = 0; x < 2; ++x) {
+      const unsigned adm = (c < tie_chunk) ? ct[x * NC + c] : (c == tie_chunk ? S.adm_split[x] : 0u);
+      const unsigned long long tot = cm[x * NC + c] + (unsigned long long)adm * cut.q_t;
+      cm[x * NC + c] = tot;
+      part[x] += tot;
+    }
+  }
+  const unsigned long long S0 = block_sum(part[0], S.scan_u64);
+  const unsigned long long S1 = block_sum(part[1], S.scan_u64);
+  const unsigned long long SK = S0 + S1;
+  int cls = 0;
+  double u = U.u_draw;
+  if (use_hot) {
+    const bool acc = (S1 > 0ull) && (U.u_acc * (double)SK <= (double)S1);
+    cls = acc ? 1 : 0;
+    u = acc ? U.u_draw : U.u_tail;
+    dg.alpha = (double)S1 / (double)SK;
+    dg.flags |= SIMPLE_DIAG_SHVS | (acc ? SIMPLE_DIAG_ACCEPTED : 0u);
+  }
+  const unsigned long long Scls = cls ? S1 : S0;
+  const double target = u * (double)Scls;
+  if (tid == 0) {
+    unsigned long long cum = 0ull; unsigned ties = 0u;
+    int wc = -1, last_c = 0; unsigned long long last_cum = 0ull; unsigned last_ties = 0u;
+    for (int c = 0; c < NC; ++c) {
+      const unsigned long long here = cm[cls * NC + c];
+      if (here > 0ull) { last_c = c; last_cum = cum; last_ties = ties; }
+      if ((double)(cum + here) > target) { wc = c; break; }
+      cum += here;
+      ties += ct[c] + ct[NC + c];
+    }
+    if (wc < 0) { wc = last_c; cum = last_cum; ties = last_ties; }  // rounding: last chunk with mass
+    S.walk_chunk = wc; S.walk_base = cum; S.walk_ties_before = ties; S.out_id = -1;
+  }
+  __syncthreads();
+  if (wave_id() == 0) {  // pass F2: walk inside one chunk
+    const int wc = S.walk_chunk;
+    unsigned long long base = S.walk_base;
+    unsigned ties_before = S.walk_ties_before;
+    bool done = false;
+    int last_id = -1; unsigned long long last_q = 0ull;
+    for (int j = 0; j < J && !done; ++j) {
+      const int idx = wc * CH + j * 64 + lane;
+      uint32_t key = 0u;
+      if (idx < V) key = R.ykey(idx);
+      const bool tie = key && (key == cut.t);
+      const unsigned long long tmask = __ballot(tie);
+      const unsigned trank = ties_before + __popcll(tmask & ((1ull << lane) - 1ull));
+      unsigned long long q = 0ull;
+      if (key) {
+        const int c = use_hot ? ((hot_bits[idx >> 5] >> (idx & 31)) & 1u) : 0;
+        if (c == cls) {
+          if (key > cut.t) q = qmass(key, ymax);
+          else if (tie && trank < cut.r) q = cut.q_t;
+        }
+      }
+      const unsigned long long incl = wave_incl_scan(q);
+      const bool hit = (q > 0ull) && ((double)(base + incl) > target);
+      const unsigned long long hmask = __ballot(hit);
+      if (hmask) {
+        const int src = __ffsll((long long)hmask) - 1;
+        const int id = __shfl(idx, src, 64);
+        const unsigned long long qq = __shfl(q, src, 64);
+        if (lane == 0) { S.out_id = id; S.out_p = (float)((double)qq / (double)SK); }
+        done = true;
+      } else {
+        const unsigned long long pmask = __ballot(q > 0ull);
+        if (pmask) {
+          const int src = 63 - __clzll((long long)pmask);
+          last_id = __shfl(idx, src, 64); last_q = __shfl(q, src, 64);
+        }
+        base += __shfl(incl, 63, 64);
+        ties_before += __popcll(tmask);
+      }
+    }
+    if (!done && lane == 0 && last_id >= 0) { S.out_id = last_id; S.out_p = (float)((double)last_q / (double)SK); }
+  }
+  __syncthreads();
+  if (S.out_id < 0 && tid == 0) S.flags |= SIMPLE_DIAG_ERROR;
+}
+
+// ------------------------------------------------------------------ the kernel -----------------
+template <typename DT, bool VEC>
+__global__ __launch_bounds__(NT) void sample_rows_kernel(const SampleArgs a) {
+  extern __shared__ __align__(16) unsigned char lds[];
+  __shared__ Shared S;
+  const int tid = threadIdx.x;
+  const int row = blockIdx.x;
+  const int V = a.V;
+  const DT* rowp = reinterpret_cast<const DT*>(a.logits) + (size_t)row * (size_t)a.stride;
+  const simple_row_params par = a.params[row];
+  uint32_t* ck = reinterpret_cast<uint32_t*>(lds + a.L.cand);
+  uint32_t* ci = ck + CAP;
+  uint32_t* hist = reinterpret_cast<uint32_t*>(lds + a.L.hist);
+
+  simple_row_diag dg;
+  dg.alpha = __longlong_as_double(0x7FF8000000000000ll);
+  dg.s_k = 0.0; dg.p_chosen = 0.0f; dg.n_survivors = 0; dg.flags = 0u; dg.reserved = 0u;
+
+  // ---- row configuration (identical in every thread) ----
+  const bool bad_par = !(par.temperature >= 0.0f) || !(par.rep_penalty > 0.0f);
+  const bool greedy = par.temperature == 0.0f;
+  const bool k_on = par.top_k >= 1 && par.top_k < V;
+  long long h0 = 0; int nnz = 0;
+  if (a.hist_ptr) { h0 = a.hist_ptr[row]; const long long h1 = a.hist_ptr[row + 1]; nnz = (int)min(max(h1 - h0, 0ll), (long long)a.max_nnz + 1); }
+  const bool too_long = nnz > a.max_nnz;
+  const bool pen_on = par.rep_penalty != 1.0f || par.freq_penalty != 0.0f || par.pres_penalty != 0.0f;
+  const bool lowering = par.rep_penalty >= 1.0f && par.freq_penalty >= 0.0f && par.pres_penalty >= 0.0f;
+  if (tid == 0) {
+    S.tau = greedy ? 1.0f : par.temperature;
+    S.greedy = greedy; S.k_on = k_on; S.top_k = par.top_k;
+    S.k_sel = greedy ? 1 : (k_on ? min(par.top_k, KMAX) : KMAX);
+    S.top_p = par.top_p; S.min_p = par.min_p;
+    S.cand_count = 0u; S.n_conv = 0u; S.g_pass = -INFINITY; S.flags = 0u; S.out_id = -1; S.out_p = 0.0f;
+    const double c = 1.4426950408889634 / (double)(greedy ? 1.0f : par.temperature);
+    float chi = (float)c;
+    if ((double)chi > c) chi = __uint_as_float(__float_as_uint(chi) - 1u);  // round down (c > 0)
+    S.c_hi = chi; S.c_lo = fmaxf((float)(c - (double)chi), 1e-30f);
+  }
+  __syncthreads();
+  if (bad_par || too_long) {
+    if (tid == 0) {
+      a.out[row] = -1;
+      if (a.diag) { dg.flags = SIMPLE_DIAG_ERROR | (bad_par ? SIMPLE_DIAG_BAD_PARAM : 0u) | (too_long ? SIMPLE_DIAG_HISTORY_TOO_LONG : 0u); a.diag[row] = dg; }
+    }
+    return;
+  }
+  // ---- history state ----
+  History H;
+  H.bits = reinterpret_cast<uint32_t*>(lds + a.L.bitmap);
+  H.grp = reinterpret_cast<uint32_t*>(lds + a.L.grp);
+  H.cnt = reinterpret_cast<uint32_t*>(lds + a.L.counts);
+  H.n_words = (V + 31) >> 5;
+  H.distinct = 0;
+  H.rep = par.rep_penalty; H.freq = par.freq_penalty; H.pres = par.pres_penalty;
+  H.active = (nnz > 0) && pen_on;
+  if (H.active) {
+    if (!build_history(H, a.hist_ids + h0, nnz, par.n_prompt, V, S.scan_u32, &S.flag_ws)) dg.flags |= SIMPLE_DIAG_BAD_HISTORY_ID;
+  }
+  if (a.hot_bits && a.hot_flags && *a.hot_flags) dg.flags |= SIMPLE_DIAG_BAD_HOT_SET;
+  const uint32_t* hot_bits = greedy ? nullptr : a.hot_bits;
+
+  Draws U;
+  { double u[3]; row_uniforms(a.seed, a.row_offset + (uint64_t)row, a.step, u); U.u_draw = u[0]; U.u_acc = u[1]; U.u_tail = u[2]; }
+
+  const bool need_sum = !greedy && !k_on && par.top_p < 1.0f && par.top_p > 0.0f;
+  const bool full_mode = need_sum || (H.active && !lowering);
+  const bool list_ok = greedy || (k_on && par.top_k <= KMAX) ||
+                       (!k_on && (par.top_p < 1.0f || par.min_p > 0.0f || V <= KMAX));
+  bool done = false;
+  if (list_ok) {
+    constexpr int T = 64 * Elem<DT>::EPL * UNROLL;
+    float m_t = -3.4028234663852886e38f; double s_t = 0.0;
+    int pos = 0;
+    bool careful_used = false;
+    while (pos < V) {
+      const unsigned count0 = S.cand_count;
+      const int k_sel = S.k_sel;
+      // segment length: expected appends (k_sel * len / seen) stay below half the free space
+      long long len;
+      if (pos == 0) len = CAP;
+      else len = (long long)(CAP - (int)count0) * (long long)pos / (2ll * (long long)k_sel);
+      len = max((len / T) * T, (long long)T);
+      const int seg1 = (int)min((long long)V, (long long)pos + len);
+      const float g = S.g_pass;
+      if (full_mode) stream_range<DT, VEC, true>(rowp, pos, seg1, g, H, need_sum, S.c_hi, S.c_lo, m_t, s_t, S, ck, ci);
+      else stream_range<DT, VEC, false>(rowp, pos, seg1, g, H, false, 0.f, 0.f, m_t, s_t, S, ck, ci);
+      __syncthreads();
+      if (S.cand_count > (unsigned)CAP) {  // overflow: replay the segment in pieces that cannot overflow
+        careful_used = true;
+        __syncthreads();
+        if (tid == 0) S.cand_count = count0;
+        __syncthreads();
+        int p0 = pos;
+        while (p0 < seg1) {
+          const int p1 = min(seg1, p0 + (CAP - (int)S.cand_count));
+          const float g2 = S.g_pass;
+          if (full_mode) stream_careful<DT, true>(rowp, p0, p1, g2, H, S, ck, ci);
+          else stream_careful<DT, false>(rowp, p0, p1, g2, H, S, ck, ci);
+          compact(S, ck, ci, hist, H, !full_mode);
+          p0 = p1;
+        }
+      } else {
+        compact(S, ck, ci, hist, H, !full_mode);
+      }
+      pos = seg1;
+    }
+    if (careful_used) dg.flags |= SIMPLE_DIAG_CAREFUL;
+    double S_total = 0.0;
+    if (need_sum) {
+      const float M = block_max(m_t, S.red_f);
+      const float d = m_t - M;
+      const double sc = (double)__builtin_amdgcn_exp2f(fmaf(d, S.c_hi, d * S.c_lo));
+      S_total = block_sum(s_t * sc, S.scan_d);
+    }
+    __syncthreads();
+    done = finalize_small(S, ck, ci, V, S_total, U, hot_bits, dg);
+    __syncthreads();
+  }
+  if (!done) {
+    dg.flags |= SIMPLE_DIAG_WIDE;
+    RowReader<DT> R{rowp, V, S.tau, greedy, &H};
+    wide_route<DT>(R, S, hist, lds + a.L.cand, U, hot_bits, dg);
+    __syncthreads();
+  }
+  if (tid == 0) {
+    const unsigned f = S.flags;
+    const bool err = (f & SIMPLE_DIAG_ERROR) != 0u;
+    a.out[row] = err ? -1 : S.out_id;
+    if (a.diag) {
+      dg.flags |= f | (greedy ? SIMPLE_DIAG_GREEDY : 0u);
+      dg.p_chosen = err ? 0.0f : S.out_p;
+      a.diag[row] = dg;
+    }
+  }
+}
+
+// Hot-set membership bitmap (section 5.3): V bits, built from the id list.
+__global__ void hot_clear_kernel(uint32_t* bits, int n_words, uint32_t* flags) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n_words) bits[i] = 0u;
+  if (i == 0) *flags = 0u;
+}
+__global__ void hot_scatter_kernel(const int32_t* __restrict__ ids, int H, int V, uint32_t* bits, uint32_t* flags) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= H) return;
+  const int id = ids[i];
+  if ((unsigned)id >= (unsigned)V) { atomicOr(flags, 1u); return; }
+  const uint32_t bit = 1u << (id & 31);
+  if (atomicOr(&bits[id >> 5], bit) & bit) atomicOr(flags, 2u);
+}
+
+}  // namespace simple
+
+// ------------------------------------------------------------------ launchers ------------------
+namespace simple {
+
+template <typename DT, bool VEC>
+static hipError_t launch_one(const SampleArgs& a, hipStream_t st) {
+  auto k = sample_rows_kernel<DT, VEC>;
+  hipLaunchKernelGGL(k, dim3((unsigned)a.B), dim3(NT), a.L.total, st, a);
+  return hipGetLastError();
+}
+
+hipError_t launch_sample(const SampleArgs& a, int dtype, bool vec, hipStream_t st) {
+  if (dtype == SIMPLE_F32) return vec ? launch_one<float, true>(a, st) : launch_one<float, false>(a, st);
+  return vec ? launch_one<uint16_t, true>(a, st) : launch_one<uint16_t, false>(a, st);
+}
+
+hipError_t set_max_lds(unsigned bytes) {
+  hipError_t e;
+  e = hipFuncSetAttribute(reinterpret_cast<const void*>(sample_rows_kernel<float, true>), hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes); if (e != hipSuccess) return e;
+  e = hipFuncSetAttribute(reinterpret_cast<const void*>(sample_rows_kernel<float, false>), hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes); if (e != hipSuccess) return e;
+  e = hipFuncSetAttribute(reinterpret_cast<const void*>(sample_rows_kernel<uint16_t, true>), hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes); if (e != hipSuccess) return e;
+  e = hipFuncSetAttribute(reinterpret_cast<const void*>(sample_rows_kernel<uint16_t, false>), hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
+  return e;
+}
+
+hipError_t launch_hot_build(const int32_t* ids, int H, int V, uint32_t* bits, uint32_t* flags, hipStream_t st) {
+  const int n_words = (V + 31) >> 5;
+  hipLaunchKernelGGL(hot_clear_kernel, dim3((n_words + 255) / 256), dim3(256), 0, st, bits, n_words, flags);
+  if (H > 0) hipLaunchKernelGGL(hot_scatter_kernel, dim3((H + 255) / 256), dim3(256), 0, st, ids, H, V, bits, flags);
+  return hipGetLastError();
+}
+
+}  // namespace simple
