@@ -95,6 +95,7 @@ enum {
   SIMPLE_DIAG_SHVS = 1u << 3,          /* a hot set was used */
   SIMPLE_DIAG_ACCEPTED = 1u << 4,      /* SHVS hot candidate accepted */
   SIMPLE_DIAG_CAREFUL = 1u << 5,       /* candidate list overflowed: segment replayed in small pieces */
+  SIMPLE_DIAG_REPLAY = 1u << 6,        /* sampled threshold missed: row streamed again with a rising one */
   SIMPLE_DIAG_BAD_PARAM = 1u << 8,
   SIMPLE_DIAG_BAD_LOGIT = 1u << 9,     /* NaN or +inf logit, or every logit -inf */
   SIMPLE_DIAG_BAD_HISTORY_ID = 1u << 10, /* ignored */

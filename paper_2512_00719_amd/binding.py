@@ -12,6 +12,7 @@ import os
 from typing import Optional
 
 import numpy as np
+import torch  # noqa: F401  imported first so that the library binds to the HIP runtime PyTorch loads
 
 _PKG = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_PKG, "libsimple_sample.so")
@@ -19,7 +20,7 @@ LIB_PATH = os.path.join(_PKG, "libsimple_sample.so")
 SIMPLE_F32, SIMPLE_BF16 = 0, 1
 SIMPLE_OK, SIMPLE_EINVAL, SIMPLE_ENOMEM, SIMPLE_EDEVICE, SIMPLE_ECAPACITY = 0, -1, -2, -3, -4
 
-DIAG_ERROR, DIAG_GREEDY, DIAG_WIDE, DIAG_SHVS, DIAG_ACCEPTED, DIAG_CAREFUL = (1 << i for i in range(6))
+DIAG_ERROR, DIAG_GREEDY, DIAG_WIDE, DIAG_SHVS, DIAG_ACCEPTED, DIAG_CAREFUL, DIAG_REPLAY = (1 << i for i in range(7))
 DIAG_BAD_PARAM, DIAG_BAD_LOGIT, DIAG_BAD_HISTORY_ID, DIAG_HISTORY_TOO_LONG, DIAG_BAD_HOT_SET = (
     1 << i for i in range(8, 13))
 

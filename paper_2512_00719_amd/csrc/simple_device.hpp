@@ -163,7 +163,7 @@ struct History {
 
 // Builds the history state of one row.  hist points at the row's ids (nnz of them, the first
 // n_prompt are prompt tokens).  Returns false (all threads) if some id is outside [0, V).
-__device__ inline bool build_history(History& H, const int32_t* __restrict__ hist, int nnz,
+__device__ __noinline__ bool build_history(History& H, const int32_t* __restrict__ hist, int nnz,
                                      int n_prompt, int V, uint32_t* scan_ws, uint32_t* flag_ws) {
   const int tid = threadIdx.x;
   const int n_grp = (H.n_words + 7) >> 3;

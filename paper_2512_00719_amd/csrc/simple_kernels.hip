@@ -2,14 +2,17 @@
 //
 // Route taken by a row (all inside one launch):
 //   history state (bitmap + rank directory + counts in LDS)            -- penalties, section 2.2 / 5.2
-//   one coalesced stream over the row that keeps, in an LDS candidate list, every element that
-//   can still belong to the top-k prefix (threshold raised as the list is compacted), and, for
-//   rows whose nucleus is taken over the whole vocabulary, the row's exp-sum   -- truncation first, 5.2
-//   exact selection, softmax and inverse-CDF draw on the candidate list       -- Eq. (2), step (3)
-//   SHVS accept / hot draw / tail draw on the same survivors                  -- section 5.3
-// Rows whose survivor set cannot be certified from the candidate list (top-k above KMAX, a very
-// wide nucleus, no truncation at all) take a multi-pass radix descent over the row instead; it is
-// exact for every input.
+//   a few sample tiles spread over the row fix a threshold that is expected to admit a small
+//   multiple of the top-k prefix; one coalesced stream over the rest of the row keeps, in an LDS
+//   candidate list, every element at or above it, and, for rows whose nucleus is taken over the
+//   whole vocabulary, the row's exp-sum                                 -- truncation first, 5.2
+//   exact selection, softmax and inverse-CDF draw on the candidate list -- Eq. (2), step (3)
+//   SHVS accept / hot draw / tail draw on the same survivors            -- section 5.3
+// The list certifies its own completeness (every element at or above the threshold is in it).
+// When the sampled threshold admitted too few or too many elements the row is streamed again
+// with a threshold that rises monotonically and cannot fail; rows whose survivor set does not
+// fit the list at all (top-k above KMAX, a very wide nucleus, no truncation) take a multi-pass
+// radix descent over the row, which is exact for every input.
 #include <hip/hip_runtime.h>
 #include <math.h>
 #include <stdint.h>
@@ -19,6 +22,16 @@
 
 namespace simple {
 
+#ifdef SIMPLE_PHASE_TIMES  // profiling builds only: per-row phase timestamps (100 MHz wall clock)
+__device__ unsigned long long g_phase_times[8192 * 8];
+#define PHASE_MARK(i) do { if (threadIdx.x == 0 && blockIdx.x < 8192) g_phase_times[blockIdx.x * 8 + (i)] = wall_clock64(); } while (0)
+#else
+#define PHASE_MARK(i) do { } while (0)
+#endif
+
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
 // ------------------------------------------------------------------ element access -------------
 template <typename DT> struct Elem;
 template <> struct Elem<float> {
@@ -26,8 +39,8 @@ template <> struct Elem<float> {
   __device__ static __forceinline__ float one(const float* p) { return *p; }
   template <bool VEC>
   __device__ static __forceinline__ void vec(const float* p, float (&z)[4]) {
-    if (VEC) {
-      const float4 v = *reinterpret_cast<const float4*>(p);
+    if (VEC) {  // streamed once: non-temporal so the row does not displace what the L2 should keep
+      const f32x4 v = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(p));
       z[0] = v.x; z[1] = v.y; z[2] = v.z; z[3] = v.w;
     } else {
 #pragma unroll
@@ -41,7 +54,7 @@ template <> struct Elem<uint16_t> {  // bfloat16 bit patterns; the upcast to flo
   template <bool VEC>
   __device__ static __forceinline__ void vec(const uint16_t* p, float (&z)[8]) {
     if (VEC) {
-      const uint4 v = *reinterpret_cast<const uint4*>(p);
+      const u32x4 v = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(p));
       const uint32_t w[4] = {v.x, v.y, v.z, v.w};
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
@@ -60,7 +73,7 @@ struct Shared {
   float tau, c_hi, c_lo;
   int greedy, k_on, k_sel, top_k;
   float top_p, min_p;
-  unsigned cand_count, n_conv, stage_count, min_key;
+  unsigned cand_count, n_conv, min_key, max_key;
   float g_pass;
   unsigned flags;
   unsigned sel_digit, sel_need, sel_cnt, sel_found;
@@ -79,14 +92,17 @@ struct Shared {
   float out_p;
 };
 
-// Smallest float z with (greedy ? z : z / tau) > yk, found by bisection over the orderable keys
-// (the map z -> fl(z / tau) is monotone).  yk is finite or -inf.
-__device__ inline float min_z_exceeding(float yk, float tau, bool greedy) {
-  uint32_t lo = KEY_NEG_INF, hi = KEY_POS_INF;  // predicate false at lo, true at hi
+// Smallest float z (by bisection over the orderable keys) whose tempered value
+// y = (greedy ? z : z / tau) satisfies y > yk (strict) or y >= yk (!strict); the map z -> fl(z/tau)
+// is monotone.  yk is finite or -inf.
+__device__ inline float min_z_reaching(float yk, float tau, bool greedy, bool strict) {
+  uint32_t lo = KEY_NEG_INF, hi = KEY_POS_INF;  // predicate false at lo (unless yk = -inf, !strict), true at hi
   auto pred = [&](uint32_t k) {
     const float z = keyf(k);
-    return (greedy ? z : z / tau) > yk;
+    const float y = greedy ? z : z / tau;
+    return strict ? (y > yk) : (y >= yk);
   };
+  if (pred(lo)) return keyf(lo);
   const float guess = greedy ? yk : yk * tau;
   if (guess > -INFINITY && guess < INFINITY) {  // gallop around the algebraic inverse first
     const uint32_t c = fkey(guess);
@@ -113,42 +129,120 @@ __device__ inline float min_z_exceeding(float yk, float tau, bool greedy) {
 }
 
 // ------------------------------------------------------------------ the stream -----------------
-// Appends the elements flagged in `pm` (bit u*EPL+e) to the candidate list as (float bits, id).
-template <int EPL>
-__device__ inline void append_candidates(Shared& S, uint32_t* ck, uint32_t* ci, unsigned pm,
-                                         const float (&z)[UNROLL][EPL], int tile_base) {
+// Appends the lanes flagged in the wave mask `m` to the candidate list as (float bits, id).
+__device__ __forceinline__ void append_lanes(Shared& S, uint32_t* ck, uint32_t* ci,
+                                             unsigned long long m, float z, int idx) {
   const int lane = lane_id();
-  const unsigned my = __popc(pm);
-  const unsigned incl = wave_incl_scan(my);
-  const unsigned total = __shfl(incl, 63, 64);
   unsigned base = 0;
-  if (lane == 63) base = atomicAdd(&S.cand_count, total);
-  base = __shfl(base, 63, 64);
-  unsigned slot = base + incl - my;
+  if (lane == 0) base = atomicAdd(&S.cand_count, (unsigned)__popcll(m));
+  base = __shfl(base, 0, 64);
+  if ((m >> lane) & 1ull) {
+    const unsigned slot = base + __builtin_amdgcn_mbcnt_hi((uint32_t)(m >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)m, 0u));
+    if (slot < (unsigned)CAP) { ck[slot] = __float_as_uint(z); ci[slot] = (uint32_t)idx; }
+  }
+}
+
+// Running (max, exp-sum) of one thread, in logit space: s = sum exp2((z - m) * c), c = log2(e)/tau
+// split into c_hi + c_lo so the product keeps ~48 bits.
+struct ExpSum {
+  float m; double s; float c_hi, c_lo;
+  __device__ __forceinline__ float w(float z) const { const float d = z - m; return __builtin_amdgcn_exp2f(fmaf(d, c_hi, d * c_lo)); }
+  __device__ __forceinline__ void raise(float vmax) {
+    if (vmax > m) { const float d = m - vmax; s *= (double)__builtin_amdgcn_exp2f(fmaf(d, c_hi, d * c_lo)); m = vmax; }
+  }
+};
+
+// Processes one tile of the row (64 lanes x UNROLL loads x EPL elements, columns [tb, min(tb+T, V))).
+// FULL: columns that are in the history are masked out here (they are handled from the history
+// side afterwards) and the thread's (max, exp-sum) is updated.  ALL: every valid element is
+// appended (sample tiles); otherwise only elements with !(z < g).
+template <typename DT, bool VEC, bool FULL, bool ALL>
+__device__ __forceinline__ void process_tile(const DT* __restrict__ rowp, int tb, int V, float g,
+                                             const History& H, bool do_sum, ExpSum& E, Shared& S,
+                                             uint32_t* ck, uint32_t* ci) {
+  constexpr int EPL = Elem<DT>::EPL;
+  constexpr int T = 64 * EPL * UNROLL;
+  const int lane = lane_id();
+  float z[UNROLL][EPL];
+  const bool full = (tb + T <= V);
+  if (full) {
+#pragma unroll
+    for (int u = 0; u < UNROLL; ++u) Elem<DT>::template vec<VEC>(rowp + tb + u * 64 * EPL + lane * EPL, z[u]);
+  } else {
+#pragma unroll
+    for (int u = 0; u < UNROLL; ++u) {
+#pragma unroll
+      for (int e = 0; e < EPL; ++e) {
+        const int idx = tb + u * 64 * EPL + lane * EPL + e;
+        z[u][e] = (idx < V) ? Elem<DT>::one(rowp + idx) : -INFINITY;
+      }
+    }
+  }
+  unsigned skip[UNROLL];  // bit e set: element is not a candidate here (masked or out of range)
 #pragma unroll
   for (int u = 0; u < UNROLL; ++u) {
+    const int idx0 = tb + u * 64 * EPL + lane * EPL;
+    unsigned sk = 0u;
+    if (!full) {
 #pragma unroll
-    for (int e = 0; e < EPL; ++e) {
-      if ((pm >> (u * EPL + e)) & 1u) {
-        if (slot < (unsigned)CAP) {
-          ck[slot] = __float_as_uint(z[u][e]);
-          ci[slot] = (uint32_t)(tile_base + u * 64 * EPL + lane * EPL + e);
-        }
-        ++slot;
+      for (int e = 0; e < EPL; ++e) sk |= (idx0 + e < V) ? 0u : (1u << e);
+    }
+    if (FULL) {
+      if (H.active && idx0 < V) sk |= (H.bits[idx0 >> 5] >> (idx0 & 31)) & ((1u << EPL) - 1u);
+      if (sk) {
+#pragma unroll
+        for (int e = 0; e < EPL; ++e) if ((sk >> e) & 1u) z[u][e] = -INFINITY;
+      }
+      if (do_sum) {
+        float vmax = z[u][0];
+#pragma unroll
+        for (int e = 1; e < EPL; ++e) vmax = fmaxf(vmax, z[u][e]);
+        E.raise(vmax);
+        float ps = 0.0f;
+#pragma unroll
+        for (int e = 0; e < EPL; ++e) ps += E.w(z[u][e]);
+        E.s += (double)ps;
+      }
+    }
+    skip[u] = sk;
+  }
+  if (ALL || !full) {
+#pragma unroll
+    for (int u = 0; u < UNROLL; ++u) {
+#pragma unroll
+      for (int e = 0; e < EPL; ++e) {
+        const bool pass = !((skip[u] >> e) & 1u) && (ALL || !(z[u][e] < g));
+        const unsigned long long m = __ballot(pass);
+        if (m) append_lanes(S, ck, ci, m, z[u][e], tb + u * 64 * EPL + lane * EPL + e);
+      }
+    }
+  } else {
+    // masked elements are -inf and fail the test unless g is -inf, which only happens when the
+    // whole row was sampled (no tile reaches this branch then)
+#pragma unroll
+    for (int u = 0; u < UNROLL; ++u) {
+#pragma unroll
+      for (int e = 0; e < EPL; ++e) {
+        const unsigned long long m = __ballot(!(z[u][e] < g));
+        if (m) append_lanes(S, ck, ci, m, z[u][e], tb + u * 64 * EPL + lane * EPL + e);
       }
     }
   }
 }
 
-// Streams columns [seg0, seg1) of the row once.  Every element with !(z < g) goes to the
-// candidate list.  FULL: penalties are applied to every element before the test and the row's
-// running (max, exp-sum) is updated (needed when the nucleus is taken over all of V).  Otherwise
-// the raw logit is tested -- valid because the penalties of such rows can only lower a logit --
-// and the penalty is applied when the list is compacted.
+// Sample tiles: NS tiles spread evenly over the row (all tiles when the row has at most NS).
+__device__ __forceinline__ bool is_sample_tile(int ti, int ntiles, int NS) {
+  if (ntiles <= NS) return true;
+  const int stride = ntiles / NS;
+  return (ti % stride == 0) && (ti / stride < NS);
+}
+
+// Streams columns [seg0, seg1) of the row once in ascending tiles (used by the monotone-threshold
+// replay).  FULL here applies the penalties element by element.
 template <typename DT, bool VEC, bool FULL>
 __device__ inline void stream_range(const DT* __restrict__ rowp, int seg0, int seg1, float g,
-                                    const History& H, bool do_sum, float c_hi, float c_lo,
-                                    float& m_t, double& s_t, Shared& S, uint32_t* ck, uint32_t* ci) {
+                                    const History& H, bool do_sum, ExpSum& E, Shared& S,
+                                    uint32_t* ck, uint32_t* ci) {
   constexpr int EPL = Elem<DT>::EPL;
   constexpr int T = 64 * EPL * UNROLL;
   const int lane = lane_id();
@@ -184,38 +278,22 @@ __device__ inline void stream_range(const DT* __restrict__ rowp, int seg0, int s
           float vmax = z[u][0];
 #pragma unroll
           for (int e = 1; e < EPL; ++e) vmax = fmaxf(vmax, z[u][e]);
-          if (vmax > m_t) {
-            const float d = m_t - vmax;
-            s_t *= (double)__builtin_amdgcn_exp2f(fmaf(d, c_hi, d * c_lo));
-            m_t = vmax;
-          }
+          E.raise(vmax);
           float ps = 0.0f;
 #pragma unroll
-          for (int e = 0; e < EPL; ++e) {
-            const float d = z[u][e] - m_t;
-            ps += __builtin_amdgcn_exp2f(fmaf(d, c_hi, d * c_lo));
-          }
-          s_t += (double)ps;
+          for (int e = 0; e < EPL; ++e) ps += E.w(z[u][e]);
+          E.s += (double)ps;
         }
       }
     }
-    unsigned long long any = 0ull;
 #pragma unroll
     for (int u = 0; u < UNROLL; ++u) {
 #pragma unroll
-      for (int e = 0; e < EPL; ++e) any |= __ballot(!(z[u][e] < g));
-    }
-    if (any) {
-      unsigned pm = 0u;
-#pragma unroll
-      for (int u = 0; u < UNROLL; ++u) {
-#pragma unroll
-        for (int e = 0; e < EPL; ++e) {
-          const int idx = tb + u * 64 * EPL + lane * EPL + e;
-          if (!(z[u][e] < g) && (full || idx < seg1)) pm |= 1u << (u * EPL + e);
-        }
+      for (int e = 0; e < EPL; ++e) {
+        const int idx = tb + u * 64 * EPL + lane * EPL + e;
+        const unsigned long long m = __ballot(!(z[u][e] < g) && (full || idx < seg1));
+        if (m) append_lanes(S, ck, ci, m, z[u][e], idx);
       }
-      if (__ballot(pm != 0u)) append_candidates<EPL>(S, ck, ci, pm, z, tb);
     }
   }
 }
@@ -239,18 +317,13 @@ __device__ __forceinline__ unsigned long long composite(uint32_t key, uint32_t i
   return ((unsigned long long)key << 32) | (unsigned long long)(0xFFFFFFFFu - id);
 }
 
-// Converts freshly appended entries to orderable keys of y = z'/tau, then keeps exactly the best
-// min(k_sel, valid) entries in the order (y descending, id ascending) and raises the stream
-// threshold to the smallest logit that can still beat the worst kept entry.  Entries arrive in
-// ascending id, so a later element never wins a tie: the threshold is strict.
-__device__ inline void compact(Shared& S, uint32_t* ck, uint32_t* ci, uint32_t* hist,
-                               const History& H, bool apply_pen) {
-  const int tid = threadIdx.x;
-  __syncthreads();
-  const unsigned n = min(S.cand_count, (unsigned)CAP);
-  const unsigned n_conv = S.n_conv;
+// Turns entries [from, to) from (logit bits, id) into (orderable key of y = z'/tau, id); 0 marks a
+// dropped entry.  apply_pen: the stream tested raw logits, so the penalty is applied here.
+// Returns the number of valid entries among them (all threads).
+__device__ inline unsigned convert_entries(Shared& S, uint32_t* ck, const uint32_t* ci, unsigned from,
+                                           unsigned to, const History& H, bool apply_pen) {
   unsigned my_valid = 0;
-  for (unsigned i = n_conv + tid; i < n; i += NT) {
+  for (unsigned i = from + threadIdx.x; i < to; i += NT) {
     float z = __uint_as_float(ck[i]);
     const int id = (int)ci[i];
     if (apply_pen && H.active && H.test(id)) z = H.penalise(z, id);
@@ -265,66 +338,101 @@ __device__ inline void compact(Shared& S, uint32_t* ck, uint32_t* ci, uint32_t* 
     ck[i] = key;
     my_valid += (key != 0u);
   }
-  const unsigned n_valid = n_conv + block_sum(my_valid, S.scan_u32);
+  return block_sum(my_valid, S.scan_u32);
+}
+
+// Radix select over the 64-bit composite (key, ~id) of the valid entries [0, n): returns the cut
+// (prefix, shift) such that exactly `need` entries satisfy (composite >> shift) >= prefix.
+// Requires need <= number of valid entries.  `hist` holds NBINS words.
+__device__ inline void select_composite(Shared& S, const uint32_t* ck, const uint32_t* ci, unsigned n,
+                                        unsigned need, uint32_t* hist, unsigned long long& prefix, int& shift) {
+  const int tid = threadIdx.x;
+  prefix = 0ull; shift = 64;
+  const int widths[6] = {11, 11, 10, 11, 11, 10};
+  for (int lvl = 0; lvl < 6; ++lvl) {
+    const int w = widths[lvl];
+    shift -= w;
+    for (int i = tid; i < NBINS; i += NT) hist[i] = 0u;
+    __syncthreads();
+    for (unsigned i = tid; i < n; i += NT) {
+      const uint32_t key = ck[i];
+      if (!key) continue;
+      const unsigned long long c = composite(key, ci[i]);
+      if (lvl == 0 || (c >> (shift + w)) == prefix) atomicAdd(&hist[(unsigned)(c >> shift) & ((1u << w) - 1u)], 1u);
+    }
+    __syncthreads();
+    unsigned local[4], tsum = 0;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) { local[j] = hist[4 * tid + j]; tsum += local[j]; }
+    unsigned total;
+    const unsigned incl = block_incl_scan(tsum, S.scan_u32, total);
+    unsigned above = total - incl;
+#pragma unroll
+    for (int j = 3; j >= 0; --j) {
+      if (above < need && need <= above + local[j]) {
+        S.sel_digit = 4 * tid + j; S.sel_need = need - above; S.sel_cnt = local[j];
+      }
+      above += local[j];
+    }
+    __syncthreads();
+    prefix = (prefix << w) | S.sel_digit;
+    need = S.sel_need;
+    const bool take_all = (S.sel_cnt == need);
+    __syncthreads();
+    if (take_all) break;
+  }
+}
+
+// Keeps the entries of [0, n) for which pred(key, id) holds, packed to the front in their
+// original order; returns how many were kept (all threads).  Also leaves the smallest and the
+// largest kept key in S.min_key / S.max_key.  Each thread owns CAP / NT consecutive entries.
+template <class P>
+__device__ inline unsigned keep_entries(Shared& S, uint32_t* ck, uint32_t* ci, unsigned n, P pred) {
+  constexpr int PER = CAP / NT;
+  const int tid = threadIdx.x;
+  uint32_t k[PER], d[PER];
+  unsigned cnt = 0, lo = 0xFFFFFFFFu, hi = 0u;
+#pragma unroll
+  for (int j = 0; j < PER; ++j) {
+    const unsigned i = (unsigned)tid * PER + j;
+    k[j] = 0u; d[j] = 0u;
+    if (i < n) { k[j] = ck[i]; d[j] = ci[i]; }
+    if (k[j] && !pred(k[j], d[j])) k[j] = 0u;
+    if (k[j]) { ++cnt; lo = min(lo, k[j]); hi = max(hi, k[j]); }
+  }
+  if (tid == 0) { S.min_key = 0xFFFFFFFFu; S.max_key = 0u; }
+  unsigned total;
+  const unsigned incl = block_incl_scan(cnt, S.scan_u32, total);  // barriers inside: all reads done
+  if (cnt) { atomicMin(&S.min_key, lo); atomicMax(&S.max_key, hi); }
+  unsigned pos = incl - cnt;
+#pragma unroll
+  for (int j = 0; j < PER; ++j) {
+    if (k[j]) { ck[pos] = k[j]; ci[pos] = d[j]; ++pos; }
+  }
+  __syncthreads();
+  return total;
+}
+
+// Monotone-threshold list maintenance: converts the new entries, keeps exactly the best
+// min(k_sel, valid) in the order (y descending, id ascending) and raises the stream threshold to
+// the smallest logit that can still beat the worst kept entry.  Entries arrive in ascending id,
+// so a later element never wins a tie: the threshold is strict.
+__device__ inline void compact(Shared& S, uint32_t* ck, uint32_t* ci, uint32_t* hist,
+                               const History& H, bool apply_pen) {
+  __syncthreads();
+  const unsigned n = min(S.cand_count, (unsigned)CAP);
+  const unsigned n_conv = S.n_conv;
+  const unsigned n_valid = n_conv + convert_entries(S, ck, ci, n_conv, n, H, apply_pen);
   const unsigned k_sel = (unsigned)S.k_sel;
   unsigned long long prefix = 0ull;
   int shift = 64;
-  if (n_valid > k_sel) {  // radix select of the k_sel-th largest composite
-    unsigned need = k_sel;
-    const int widths[6] = {11, 11, 10, 11, 11, 10};
-    for (int lvl = 0; lvl < 6; ++lvl) {
-      const int w = widths[lvl];
-      shift -= w;
-      for (int i = tid; i < NBINS; i += NT) hist[i] = 0u;
-      __syncthreads();
-      for (unsigned i = tid; i < n; i += NT) {
-        const uint32_t key = ck[i];
-        if (!key) continue;
-        const unsigned long long c = composite(key, ci[i]);
-        if (lvl == 0 || (c >> (shift + w)) == prefix) atomicAdd(&hist[(unsigned)(c >> shift) & ((1u << w) - 1u)], 1u);
-      }
-      __syncthreads();
-      unsigned local[4], tsum = 0;
-#pragma unroll
-      for (int j = 0; j < 4; ++j) { local[j] = hist[4 * tid + j]; tsum += local[j]; }
-      unsigned total;
-      const unsigned incl = block_incl_scan(tsum, S.scan_u32, total);
-      unsigned above = total - incl;
-#pragma unroll
-      for (int j = 3; j >= 0; --j) {
-        if (above < need && need <= above + local[j]) {
-          S.sel_digit = 4 * tid + j; S.sel_need = need - above; S.sel_cnt = local[j];
-        }
-        above += local[j];
-      }
-      __syncthreads();
-      prefix = (prefix << w) | S.sel_digit;
-      need = S.sel_need;
-      const bool take_all = (S.sel_cnt == need);
-      if (take_all) break;
-    }
-  }
-  __syncthreads();
-  if (tid == 0) { S.stage_count = 0u; S.min_key = 0xFFFFFFFFu; }
-  __syncthreads();
-  uint32_t* stage_key = hist;
-  uint32_t* stage_id = hist + KMAX;
-  for (unsigned i = tid; i < n; i += NT) {
-    const uint32_t key = ck[i];
-    if (!key) continue;
-    const uint32_t id = ci[i];
-    if (shift == 64 || (composite(key, id) >> shift) >= prefix) {
-      const unsigned slot = atomicAdd(&S.stage_count, 1u);
-      stage_key[slot] = key; stage_id[slot] = id;
-      atomicMin(&S.min_key, key);
-    }
-  }
-  __syncthreads();
-  const unsigned kept = S.stage_count;
-  for (unsigned i = tid; i < kept; i += NT) { ck[i] = stage_key[i]; ci[i] = stage_id[i]; }
-  if (tid == 0) {
+  if (n_valid > k_sel) select_composite(S, ck, ci, n, k_sel, hist, prefix, shift);
+  const unsigned kept = keep_entries(S, ck, ci, n, [&](uint32_t key, uint32_t id) {
+    return shift == 64 || (composite(key, id) >> shift) >= prefix;
+  });
+  if (threadIdx.x == 0) {
     S.cand_count = kept; S.n_conv = kept;
-    S.g_pass = (kept == k_sel) ? min_z_exceeding(keyf(S.min_key), S.tau, S.greedy) : -INFINITY;
+    S.g_pass = (kept == k_sel) ? min_z_reaching(keyf(S.min_key), S.tau, S.greedy, true) : -INFINITY;
   }
   __syncthreads();
 }
@@ -352,8 +460,8 @@ __device__ inline void bitonic_sort(uint32_t* key, uint32_t* id, unsigned n, boo
 struct Draws { double u_draw, u_acc, u_tail; };
 
 // Exact selection, softmax and draw on the compacted candidate list (<= KMAX entries, the best of
-// the row).  Returns false when the list cannot certify the survivor set K_b.
-__device__ inline bool finalize_small(Shared& S, uint32_t* ck, uint32_t* ci, int V, double S_total,
+// the row; `complete`: they are all of the prefix that matters).  Returns false when the list cannot certify the survivor set K_b.
+__device__ inline bool finalize_small(Shared& S, uint32_t* ck, uint32_t* ci, bool complete, double S_total,
                                       const Draws& U, const uint32_t* __restrict__ hot_bits,
                                       simple_row_diag& dg) {
   const int tid = threadIdx.x;
@@ -381,7 +489,6 @@ __device__ inline bool finalize_small(Shared& S, uint32_t* ck, uint32_t* ci, int
   double tot;
   const double incl = block_incl_scan(w0 + w1, S.scan_d, tot);
   const double cum0 = incl - w1, cum1 = incl;  // inclusive prefix masses in sorted order
-  const bool complete = S.k_on || (n_c == (unsigned)V);
   const double S_k = complete ? tot : S_total;
   // min-p: how many listed entries satisfy y >= fl32(y_max + fl32(ln min_p))
   unsigned n_m = n_c;
@@ -473,6 +580,127 @@ __device__ inline bool finalize_small(Shared& S, uint32_t* ck, uint32_t* ci, int
   return true;
 }
 
+// ------------------------------------------------------------------ sampled-threshold route ----
+enum { ROUTE_DONE = 0, ROUTE_UNCERTIFIED = 1, ROUTE_RETRY = 2 };
+
+// Columns that are in the history, taken from the history side (FULL rows mask them out of the
+// stream): gather the raw logit, apply the penalties, add to the exp-sum and to the candidates.
+template <typename DT>
+__device__ inline void history_columns(const DT* __restrict__ rowp, const History& H, float g, bool do_sum,
+                                       ExpSum& E, Shared& S, uint32_t* ck, uint32_t* ci) {
+  for (int w = threadIdx.x; w < H.n_words; w += NT) {
+    uint32_t bits = H.bits[w];
+    if (!bits) continue;
+    int r = H.grp[w >> 3];
+    for (int j = w & ~7; j < w; ++j) r += __popc(H.bits[j]);
+    while (bits) {
+      const int b = __ffs((int)bits) - 1;
+      bits &= bits - 1u;
+      const int id = w * 32 + b;
+      const uint32_t c = H.count_at(r++);
+      float z = Elem<DT>::one(rowp + id);
+      z = (z > 0.0f) ? z / H.rep : z * H.rep;
+      if (c > 0u) { const float t = H.freq * (float)c; z = z - t; z = z - H.pres; }
+      if (do_sum) { E.raise(z); E.s += (double)E.w(z); }
+      if (!(z < g)) {
+        const unsigned slot = atomicAdd(&S.cand_count, 1u);
+        if (slot < (unsigned)CAP) { ck[slot] = __float_as_uint(z); ci[slot] = (uint32_t)id; }
+      }
+    }
+  }
+}
+
+__device__ inline double combine_exp_sums(Shared& S, const ExpSum& E) {
+  const float M = block_max(E.m, S.red_f);
+  const float d = E.m - M;
+  const double sc = (double)__builtin_amdgcn_exp2f(fmaf(d, E.c_hi, d * E.c_lo));
+  return block_sum(E.s * sc, S.scan_d);
+}
+
+// One pass over the row with a threshold fixed from sample tiles.  The list ends up holding every
+// element whose tempered value is >= y_f, so any prefix of the total order that ends at or above
+// y_f is known exactly.  ROUTE_RETRY: the sampled threshold admitted fewer than k_sel elements or
+// overflowed the list; ROUTE_UNCERTIFIED: K_b reaches below what the list holds.
+template <typename DT, bool VEC, bool FULL>
+__device__ inline int sampled_route(const DT* __restrict__ rowp, int V, const History& H, bool need_sum,
+                                    Shared& S, uint32_t* ck, uint32_t* ci, uint32_t* hist, const Draws& U,
+                                    const uint32_t* __restrict__ hot_bits, simple_row_diag& dg) {
+  constexpr int EPL = Elem<DT>::EPL;
+  constexpr int T = 64 * EPL * UNROLL;
+  constexpr int NS = CAP / T;
+  const int tid = threadIdx.x, wave = wave_id();
+  const int ntiles = (V + T - 1) / T;
+  const bool sampled_all = ntiles <= NS;
+  ExpSum E{-3.4028234663852886e38f, 0.0, S.c_hi, S.c_lo};
+  if (wave < min(NS, ntiles)) {
+    const int ti = sampled_all ? wave : wave * (ntiles / NS);
+    process_tile<DT, VEC, FULL, true>(rowp, ti * T, V, 0.0f, H, need_sum, E, S, ck, ci);
+  }
+  __syncthreads();
+  const unsigned n_s = S.cand_count;  // <= NS * T = CAP
+  const unsigned n_valid = convert_entries(S, ck, ci, 0u, n_s, H, !FULL);
+  uint32_t key_f = 0u;
+  float g = -INFINITY;
+  unsigned kept;
+  if (!sampled_all) {
+    // rank of the threshold element in the sample: 1.5 x the expected rank of the k_sel-th largest
+    // plus three standard deviations, so that the whole row holds >= k_sel elements above it
+    const float m = (float)S.k_sel * (float)n_s / (float)V;
+    const unsigned r = (unsigned)ceilf(1.5f * m + 3.0f * sqrtf(m) + 4.0f);
+    if (n_valid <= r) return (S.flags & SIMPLE_DIAG_ERROR) ? ROUTE_DONE : ROUTE_RETRY;
+    unsigned long long prefix; int shift;
+    select_composite(S, ck, ci, n_s, r, hist, prefix, shift);
+    key_f = (shift >= 32) ? (uint32_t)(prefix << (shift - 32)) : (uint32_t)(prefix >> (32 - shift));
+    if (key_f <= KEY_NEG_INF) return ROUTE_RETRY;
+    kept = keep_entries(S, ck, ci, n_s, [&](uint32_t key, uint32_t) { return key >= key_f; });
+    if (!S.k_on && !S.greedy && S.min_p > 0.0f) {
+      // min-p survivors lie within ln(min_p) of the row maximum, which is at least the sample's
+      const float thr_lb = keyf(S.max_key) + (float)log((double)S.min_p);
+      if (fkey(thr_lb) > key_f) {
+        key_f = fkey(thr_lb);
+        kept = keep_entries(S, ck, ci, kept, [&](uint32_t key, uint32_t) { return key >= key_f; });
+      }
+    }
+    if (tid == 0) S.g_pass = min_z_reaching(keyf(key_f), S.tau, S.greedy, false);
+  } else {
+    kept = keep_entries(S, ck, ci, n_s, [&](uint32_t, uint32_t) { return true; });
+    if (tid == 0) S.g_pass = -INFINITY;
+  }
+  if (tid == 0) { S.cand_count = kept; S.n_conv = kept; }
+  __syncthreads();
+  PHASE_MARK(2);
+  g = S.g_pass;
+  if (!sampled_all) {
+    for (int ti = wave; ti < ntiles; ti += NW) {
+      if (is_sample_tile(ti, ntiles, NS)) continue;
+      process_tile<DT, VEC, FULL, false>(rowp, ti * T, V, g, H, need_sum, E, S, ck, ci);
+    }
+  }
+  PHASE_MARK(3);
+  if (FULL && H.active) history_columns<DT>(rowp, H, g, need_sum, E, S, ck, ci);
+  __syncthreads();
+  PHASE_MARK(4);
+  const unsigned total = S.cand_count;
+  if (total > (unsigned)CAP) return ROUTE_RETRY;
+  convert_entries(S, ck, ci, kept, total, H, !FULL);
+  unsigned L = keep_entries(S, ck, ci, total, [&](uint32_t key, uint32_t) { return key >= key_f; });
+  if (S.flags & SIMPLE_DIAG_ERROR) L = 0u;  // finalize reports the error
+  const bool exact_k = S.k_on || S.greedy;
+  if (!(S.flags & SIMPLE_DIAG_ERROR) && exact_k && L < (unsigned)S.k_sel) return ROUTE_RETRY;
+  const unsigned n_keep = exact_k ? min(L, (unsigned)S.k_sel) : min(L, (unsigned)KMAX);
+  if (L > n_keep) {
+    unsigned long long prefix; int shift;
+    select_composite(S, ck, ci, L, n_keep, hist, prefix, shift);
+    keep_entries(S, ck, ci, L, [&](uint32_t key, uint32_t id) { return (composite(key, id) >> shift) >= prefix; });
+  }
+  if (tid == 0) { S.cand_count = n_keep; S.n_conv = n_keep; }
+  const double S_total = need_sum ? combine_exp_sums(S, E) : 0.0;
+  __syncthreads();
+  const bool complete = exact_k || (sampled_all && L <= (unsigned)KMAX);
+  PHASE_MARK(5);
+  return finalize_small(S, ck, ci, complete, S_total, U, hot_bits, dg) ? ROUTE_DONE : ROUTE_UNCERTIFIED;
+}
+
 // ------------------------------------------------------------------ multi-pass route -----------
 template <typename DT>
 struct RowReader {
@@ -511,7 +739,7 @@ __device__ __forceinline__ unsigned long long qmass(uint32_t key, float ymax) {
 // largest element.  by_mass = true: finds the key at which the running mass (largest first)
 // reaches T.  `lim` (optional) restricts the descent to the prefix described by another cut.
 template <typename DT>
-__device__ inline Cut descend(const RowReader<DT>& R, Shared& S, uint32_t* hcnt,
+__device__ __noinline__ Cut descend(const RowReader<DT>& R, Shared& S, uint32_t* hcnt,
                               unsigned long long* hmass, float ymax, bool by_mass,
                               uint32_t need_cnt, double T, const Cut* lim) {
   const int tid = threadIdx.x;
@@ -582,7 +810,7 @@ __device__ inline Cut descend(const RowReader<DT>& R, Shared& S, uint32_t* hcnt,
 // Exact route for any row: survivor set as a cut (t, r), then the inverse-CDF walk in ascending
 // id through per-chunk masses.  `lds` is the candidate-list region (32 KB), free on this route.
 template <typename DT>
-__device__ inline void wide_route(const RowReader<DT>& R, Shared& S, uint32_t* hist, unsigned char* lds,
+__device__ __noinline__ void wide_route(const RowReader<DT>& R, Shared& S, uint32_t* hist, unsigned char* lds,
                                   const Draws& U, const uint32_t* __restrict__ hot_bits,
                                   simple_row_diag& dg) {
   const int tid = threadIdx.x, lane = lane_id(), V = R.V;
@@ -810,7 +1038,7 @@ __device__ inline void wide_route(const RowReader<DT>& R, Shared& S, uint32_t* h
 
 // ------------------------------------------------------------------ the kernel -----------------
 template <typename DT, bool VEC>
-__global__ __launch_bounds__(NT) void sample_rows_kernel(const SampleArgs a) {
+__global__ __launch_bounds__(NT, 4) void sample_rows_kernel(const SampleArgs a) {
   extern __shared__ __align__(16) unsigned char lds[];
   __shared__ Shared S;
   const int tid = threadIdx.x;
@@ -825,6 +1053,7 @@ __global__ __launch_bounds__(NT) void sample_rows_kernel(const SampleArgs a) {
   simple_row_diag dg;
   dg.alpha = __longlong_as_double(0x7FF8000000000000ll);
   dg.s_k = 0.0; dg.p_chosen = 0.0f; dg.n_survivors = 0; dg.flags = 0u; dg.reserved = 0u;
+  PHASE_MARK(0);
 
   // ---- row configuration (identical in every thread) ----
   const bool bad_par = !(par.temperature >= 0.0f) || !(par.rep_penalty > 0.0f);
@@ -868,6 +1097,7 @@ __global__ __launch_bounds__(NT) void sample_rows_kernel(const SampleArgs a) {
   }
   if (a.hot_bits && a.hot_flags && *a.hot_flags) dg.flags |= SIMPLE_DIAG_BAD_HOT_SET;
   const uint32_t* hot_bits = greedy ? nullptr : a.hot_bits;
+  PHASE_MARK(1);
 
   Draws U;
   { double u[3]; row_uniforms(a.seed, a.row_offset + (uint64_t)row, a.step, u); U.u_draw = u[0]; U.u_acc = u[1]; U.u_tail = u[2]; }
@@ -878,54 +1108,61 @@ __global__ __launch_bounds__(NT) void sample_rows_kernel(const SampleArgs a) {
                        (!k_on && (par.top_p < 1.0f || par.min_p > 0.0f || V <= KMAX));
   bool done = false;
   if (list_ok) {
-    constexpr int T = 64 * Elem<DT>::EPL * UNROLL;
-    float m_t = -3.4028234663852886e38f; double s_t = 0.0;
-    int pos = 0;
-    bool careful_used = false;
-    while (pos < V) {
-      const unsigned count0 = S.cand_count;
-      const int k_sel = S.k_sel;
-      // segment length: expected appends (k_sel * len / seen) stay below half the free space
-      long long len;
-      if (pos == 0) len = CAP;
-      else len = (long long)(CAP - (int)count0) * (long long)pos / (2ll * (long long)k_sel);
-      len = max((len / T) * T, (long long)T);
-      const int seg1 = (int)min((long long)V, (long long)pos + len);
-      const float g = S.g_pass;
-      if (full_mode) stream_range<DT, VEC, true>(rowp, pos, seg1, g, H, need_sum, S.c_hi, S.c_lo, m_t, s_t, S, ck, ci);
-      else stream_range<DT, VEC, false>(rowp, pos, seg1, g, H, false, 0.f, 0.f, m_t, s_t, S, ck, ci);
+    int rc = full_mode ? sampled_route<DT, VEC, true>(rowp, V, H, need_sum, S, ck, ci, hist, U, hot_bits, dg)
+                       : sampled_route<DT, VEC, false>(rowp, V, H, need_sum, S, ck, ci, hist, U, hot_bits, dg);
+    if (rc == ROUTE_RETRY) {
+      // the threshold only rises here (strict, ids ascending), so this pass cannot fail
+      constexpr int T = 64 * Elem<DT>::EPL * UNROLL;
+      dg.flags |= SIMPLE_DIAG_REPLAY;
       __syncthreads();
-      if (S.cand_count > (unsigned)CAP) {  // overflow: replay the segment in pieces that cannot overflow
-        careful_used = true;
+      if (tid == 0) { S.cand_count = 0u; S.n_conv = 0u; S.g_pass = -INFINITY; }
+      __syncthreads();
+      ExpSum E{-3.4028234663852886e38f, 0.0, S.c_hi, S.c_lo};
+      int pos = 0;
+      bool careful_used = false;
+      while (pos < V) {
+        const unsigned count0 = S.cand_count;
+        const int k_sel = S.k_sel;
+        // segment length: expected appends (k_sel * len / seen) stay below half the free space
+        long long len;
+        if (pos == 0) len = CAP;
+        else len = (long long)(CAP - (int)count0) * (long long)pos / (2ll * (long long)k_sel);
+        len = max((len / T) * T, (long long)T);
+        const int seg1 = (int)min((long long)V, (long long)pos + len);
+        const float g = S.g_pass;
+        if (full_mode) stream_range<DT, VEC, true>(rowp, pos, seg1, g, H, need_sum, E, S, ck, ci);
+        else stream_range<DT, VEC, false>(rowp, pos, seg1, g, H, false, E, S, ck, ci);
         __syncthreads();
-        if (tid == 0) S.cand_count = count0;
-        __syncthreads();
-        int p0 = pos;
-        while (p0 < seg1) {
-          const int p1 = min(seg1, p0 + (CAP - (int)S.cand_count));
-          const float g2 = S.g_pass;
-          if (full_mode) stream_careful<DT, true>(rowp, p0, p1, g2, H, S, ck, ci);
-          else stream_careful<DT, false>(rowp, p0, p1, g2, H, S, ck, ci);
+        if (S.cand_count > (unsigned)CAP) {  // overflow: replay the segment in pieces that cannot overflow
+          careful_used = true;
+          __syncthreads();
+          if (tid == 0) S.cand_count = count0;
+          __syncthreads();
+          int p0 = pos;
+          while (p0 < seg1) {
+            const int p1 = min(seg1, p0 + (CAP - (int)S.cand_count));
+            const float g2 = S.g_pass;
+            if (full_mode) stream_careful<DT, true>(rowp, p0, p1, g2, H, S, ck, ci);
+            else stream_careful<DT, false>(rowp, p0, p1, g2, H, S, ck, ci);
+            compact(S, ck, ci, hist, H, !full_mode);
+            p0 = p1;
+          }
+        } else {
           compact(S, ck, ci, hist, H, !full_mode);
-          p0 = p1;
         }
-      } else {
-        compact(S, ck, ci, hist, H, !full_mode);
+        pos = seg1;
       }
-      pos = seg1;
+      if (careful_used) dg.flags |= SIMPLE_DIAG_CAREFUL;
+      const double S_total = need_sum ? combine_exp_sums(S, E) : 0.0;
+      __syncthreads();
+      const bool complete = k_on || greedy || (S.cand_count == (unsigned)V);
+      done = finalize_small(S, ck, ci, complete, S_total, U, hot_bits, dg);
+    } else {
+      done = (rc == ROUTE_DONE);
     }
-    if (careful_used) dg.flags |= SIMPLE_DIAG_CAREFUL;
-    double S_total = 0.0;
-    if (need_sum) {
-      const float M = block_max(m_t, S.red_f);
-      const float d = m_t - M;
-      const double sc = (double)__builtin_amdgcn_exp2f(fmaf(d, S.c_hi, d * S.c_lo));
-      S_total = block_sum(s_t * sc, S.scan_d);
-    }
-    __syncthreads();
-    done = finalize_small(S, ck, ci, V, S_total, U, hot_bits, dg);
     __syncthreads();
   }
+  PHASE_MARK(6);
   if (!done) {
     dg.flags |= SIMPLE_DIAG_WIDE;
     RowReader<DT> R{rowp, V, S.tau, greedy, &H};
@@ -942,6 +1179,7 @@ __global__ __launch_bounds__(NT) void sample_rows_kernel(const SampleArgs a) {
       a.diag[row] = dg;
     }
   }
+  PHASE_MARK(7);
 }
 
 // Hot-set membership bitmap (section 5.3): V bits, built from the id list.
@@ -960,6 +1198,12 @@ __global__ void hot_scatter_kernel(const int32_t* __restrict__ ids, int H, int V
 }
 
 }  // namespace simple
+
+#ifdef SIMPLE_PHASE_TIMES
+extern "C" int simple_debug_phase_times(unsigned long long* dst_host, int n_rows) {
+  return (int)hipMemcpyFromSymbol(dst_host, HIP_SYMBOL(simple::g_phase_times), sizeof(unsigned long long) * 8 * (size_t)n_rows);
+}
+#endif
 
 // ------------------------------------------------------------------ launchers ------------------
 namespace simple {
