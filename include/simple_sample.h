@@ -96,6 +96,7 @@ enum {
   SIMPLE_DIAG_ACCEPTED = 1u << 4,      /* SHVS hot candidate accepted */
   SIMPLE_DIAG_CAREFUL = 1u << 5,       /* candidate list overflowed: segment replayed in small pieces */
   SIMPLE_DIAG_REPLAY = 1u << 6,        /* sampled threshold missed: row streamed again with a rising one */
+  SIMPLE_DIAG_GENERAL = 1u << 7,       /* row left by the single-pass kernel and completed by the general kernel */
   SIMPLE_DIAG_BAD_PARAM = 1u << 8,
   SIMPLE_DIAG_BAD_LOGIT = 1u << 9,     /* NaN or +inf logit, or every logit -inf */
   SIMPLE_DIAG_BAD_HISTORY_ID = 1u << 10, /* ignored */

@@ -20,7 +20,8 @@ LIB_PATH = os.path.join(_PKG, "libsimple_sample.so")
 SIMPLE_F32, SIMPLE_BF16 = 0, 1
 SIMPLE_OK, SIMPLE_EINVAL, SIMPLE_ENOMEM, SIMPLE_EDEVICE, SIMPLE_ECAPACITY = 0, -1, -2, -3, -4
 
-DIAG_ERROR, DIAG_GREEDY, DIAG_WIDE, DIAG_SHVS, DIAG_ACCEPTED, DIAG_CAREFUL, DIAG_REPLAY = (1 << i for i in range(7))
+DIAG_ERROR, DIAG_GREEDY, DIAG_WIDE, DIAG_SHVS, DIAG_ACCEPTED, DIAG_CAREFUL, DIAG_REPLAY, DIAG_GENERAL = (
+    1 << i for i in range(8))
 DIAG_BAD_PARAM, DIAG_BAD_LOGIT, DIAG_BAD_HISTORY_ID, DIAG_HISTORY_TOO_LONG, DIAG_BAD_HOT_SET = (
     1 << i for i in range(8, 13))
 

@@ -18,6 +18,7 @@ struct simple_ctx {
   int64_t hot_V;        // V the installed hot set was built for, 0 if none
   int32_t hot_H;
   int lds_limit;
+  uint32_t* pend;       // device: queue of rows the single-pass kernel leaves to the general kernel
 };
 
 namespace simple {
@@ -36,6 +37,29 @@ LdsLayout make_layout(int64_t V, int64_t max_nnz, bool with_history) {
   L.hist = off;   off = align16(off + (uint32_t)NBINS * 4u);
   L.total = off;
   return L;
+}
+
+// The single-pass kernel needs 16-byte aligned rows, a vocabulary whose columns and per-bin counts fit
+// 18 bits, 16-bit token counts and at least two tiles per wave; its row state must fit the LDS so
+// that two workgroups of 512 threads (or one of 1024) share a compute unit.
+FastLayout make_fast_layout(int64_t V, int dtype, int64_t max_nnz, bool with_history, bool vec, int lds_limit) {
+  FastLayout F{};
+  if (!vec || V >= ((int64_t)1 << 18) || max_nnz > 65535) return F;
+  const int64_t tile = 64 * 4 * ((dtype == SIMPLE_F32) ? 4 : 8);
+  uint32_t off = 0;
+  const uint32_t n_words = (uint32_t)((V + 31) / 32);
+  F.bitmap = off; if (with_history) off = align16(off + n_words * 4u);
+  F.dir = off;    if (with_history) off = align16(off + n_words * 2u);
+  F.cnt = off;    if (with_history) off = align16(off + (uint32_t)((max_nnz + 2) / 2) * 4u);
+  F.cand = off;   off = align16(off + (uint32_t)CAPF * 8u);
+  F.scratch = off; off = align16(off + 16384u);
+  F.tiles = off;  off = align16(off + 4096u);
+  F.samp = off;   off = align16(off + 2048u);
+  F.threads = ((int64_t)off + 1024 <= (int64_t)lds_limit / 2) ? 512 : 1024;
+  if ((int64_t)off + 1024 > (int64_t)lds_limit) return F;  // total stays 0
+  if (V / tile < 2 * (F.threads / 64)) return F;
+  F.total = off;
+  return F;
 }
 
 struct DeviceGuard {
@@ -79,17 +103,20 @@ int simple_create(simple_ctx** out, int device, int64_t max_V, int64_t max_nnz_p
   const simple::LdsLayout L = simple::make_layout(max_V, max_nnz_per_row, max_nnz_per_row > 0);
   if ((int64_t)L.total + 1024 > (int64_t)lds) return SIMPLE_ECAPACITY;
   if (simple::set_max_lds((unsigned)lds - 1024u) != hipSuccess) return SIMPLE_EDEVICE;
+  if (simple::set_max_lds_fast((unsigned)lds - 1024u) != hipSuccess) return SIMPLE_EDEVICE;
   simple_ctx* c = new (std::nothrow) simple_ctx();
   if (!c) return SIMPLE_ENOMEM;
   c->device = device; c->max_V = max_V; c->max_nnz = max_nnz_per_row; c->lds_limit = lds;
-  c->hot_V = 0; c->hot_H = 0; c->hot_bits = nullptr; c->hot_flags = nullptr;
+  c->hot_V = 0; c->hot_H = 0; c->hot_bits = nullptr; c->hot_flags = nullptr; c->pend = nullptr;
   const size_t words = (size_t)((max_V + 31) / 32) + 1;
-  if (hipMalloc(reinterpret_cast<void**>(&c->hot_bits), (words + 1) * sizeof(uint32_t)) != hipSuccess) {
+  const size_t total_words = words + 1 + 2 + (size_t)simple::PEND_ROWS;
+  if (hipMalloc(reinterpret_cast<void**>(&c->hot_bits), total_words * sizeof(uint32_t)) != hipSuccess) {
     delete c;
     return SIMPLE_ENOMEM;
   }
   c->hot_flags = c->hot_bits + words;
-  if (hipMemset(c->hot_bits, 0, (words + 1) * sizeof(uint32_t)) != hipSuccess) {
+  c->pend = c->hot_flags + 1;
+  if (hipMemset(c->hot_bits, 0, total_words * sizeof(uint32_t)) != hipSuccess) {
     (void)hipFree(c->hot_bits);
     delete c;
     return SIMPLE_EDEVICE;
@@ -155,17 +182,31 @@ int simple_sample(simple_ctx* ctx, const void* logits_dev, int64_t B, int64_t V,
       return SIMPLE_EDEVICE;
     ctx->hot_V = V; ctx->hot_H = H;
   }
+  const size_t esz = (dtype == SIMPLE_F32) ? 4 : 2;
+  const bool vec = ((reinterpret_cast<uintptr_t>(logits_dev) & 15u) == 0) && (((size_t)row_stride_elems * esz) % 16 == 0);
   simple::SampleArgs a{};
-  a.logits = logits_dev; a.stride = row_stride_elems; a.V = (int)V; a.B = (int)B;
+  a.logits = logits_dev; a.stride = row_stride_elems; a.V = (int)V;
   a.params = params_dev; a.hist_ptr = hist_ptr_dev; a.hist_ids = hist_ids_dev;
   a.hot_bits = use_hot ? ctx->hot_bits : nullptr;
   a.hot_flags = use_hot ? ctx->hot_flags : nullptr;
-  a.seed = seed; a.step = step; a.row_offset = row_offset;
-  a.out = out_ids_dev; a.diag = diag_dev; a.max_nnz = (int)ctx->max_nnz;
+  a.seed = seed; a.step = step;
+  a.max_nnz = (int)ctx->max_nnz;
+  a.pend = ctx->pend;
   a.L = simple::make_layout(V, ctx->max_nnz, hist_ptr_dev != nullptr);
-  const size_t esz = (dtype == SIMPLE_F32) ? 4 : 2;
-  const bool vec = ((reinterpret_cast<uintptr_t>(logits_dev) & 15u) == 0) && (((size_t)row_stride_elems * esz) % 16 == 0);
-  if (simple::launch_sample(a, dtype, vec, st) != hipSuccess) return SIMPLE_EDEVICE;
+  a.F = simple::make_fast_layout(V, dtype, hist_ptr_dev ? ctx->max_nnz : 0, hist_ptr_dev != nullptr, vec, ctx->lds_limit);
+  a.gated = (a.F.total != 0u) ? 1 : 0;
+  // rows go out in launches of at most PEND_ROWS (the capacity of the pending-row queue)
+  for (int64_t b0 = 0; b0 < B; b0 += simple::PEND_ROWS) {
+    const int64_t nb = (B - b0 < simple::PEND_ROWS) ? (B - b0) : simple::PEND_ROWS;
+    a.B = (int)nb;
+    a.logits = static_cast<const char*>(logits_dev) + (size_t)b0 * (size_t)row_stride_elems * esz;
+    a.params = params_dev + b0;
+    a.hist_ptr = hist_ptr_dev ? hist_ptr_dev + b0 : nullptr;
+    a.row_offset = row_offset + (uint64_t)b0;
+    a.out = out_ids_dev + b0;
+    a.diag = diag_dev ? diag_dev + b0 : nullptr;
+    if (simple::launch_sample(a, dtype, vec, st) != hipSuccess) return SIMPLE_EDEVICE;
+  }
   return SIMPLE_OK;
 }
 

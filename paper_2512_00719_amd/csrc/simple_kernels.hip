@@ -1037,12 +1037,10 @@ __device__ __noinline__ void wide_route(const RowReader<DT>& R, Shared& S, uint3
 }
 
 // ------------------------------------------------------------------ the kernel -----------------
+// One row, start to finish (all threads of the workgroup call it with the same row).
 template <typename DT, bool VEC>
-__global__ __launch_bounds__(NT, 4) void sample_rows_kernel(const SampleArgs a) {
-  extern __shared__ __align__(16) unsigned char lds[];
-  __shared__ Shared S;
+__device__ inline void sample_row_body(const SampleArgs& a, const int row, unsigned char* lds, Shared& S) {
   const int tid = threadIdx.x;
-  const int row = blockIdx.x;
   const int V = a.V;
   const DT* rowp = reinterpret_cast<const DT*>(a.logits) + (size_t)row * (size_t)a.stride;
   const simple_row_params par = a.params[row];
@@ -1052,7 +1050,7 @@ __global__ __launch_bounds__(NT, 4) void sample_rows_kernel(const SampleArgs a) 
 
   simple_row_diag dg;
   dg.alpha = __longlong_as_double(0x7FF8000000000000ll);
-  dg.s_k = 0.0; dg.p_chosen = 0.0f; dg.n_survivors = 0; dg.flags = 0u; dg.reserved = 0u;
+  dg.s_k = 0.0; dg.p_chosen = 0.0f; dg.n_survivors = 0; dg.flags = a.gated ? SIMPLE_DIAG_GENERAL : 0u; dg.reserved = 0u;
   PHASE_MARK(0);
 
   // ---- row configuration (identical in every thread) ----
@@ -1182,6 +1180,35 @@ __global__ __launch_bounds__(NT, 4) void sample_rows_kernel(const SampleArgs a) 
   PHASE_MARK(7);
 }
 
+template <typename DT, bool VEC>
+__global__ __launch_bounds__(NT, 4) void sample_rows_kernel(const SampleArgs a) {
+  extern __shared__ __align__(16) unsigned char lds[];
+  __shared__ Shared S;
+  sample_row_body<DT, VEC>(a, (int)blockIdx.x, lds, S);
+}
+
+// Completes the rows the single-pass kernel queued: workgroup i takes queue entries i, i + grid, ...
+// The last workgroup to finish empties the queue for the next call on the stream.
+template <typename DT, bool VEC>
+__global__ __launch_bounds__(NT, 4) void pending_rows_kernel(const SampleArgs a) {
+  extern __shared__ __align__(16) unsigned char lds[];
+  __shared__ Shared S;
+  const unsigned n = min(__hip_atomic_load(&a.pend[0], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT), (unsigned)a.B);
+  for (unsigned i = blockIdx.x; i < n; i += gridDim.x) {
+    const int row = (int)a.pend[2 + i];
+    if (row >= 0 && row < a.B) sample_row_body<DT, VEC>(a, row, lds, S);
+    __syncthreads();
+  }
+  if (threadIdx.x == 0) {
+    __threadfence();
+    const unsigned t = atomicAdd(&a.pend[1], 1u);
+    if (t == gridDim.x - 1u) {
+      __hip_atomic_store(&a.pend[0], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      __hip_atomic_store(&a.pend[1], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+  }
+}
+
 // Hot-set membership bitmap (section 5.3): V bits, built from the id list.
 __global__ void hot_clear_kernel(uint32_t* bits, int n_words, uint32_t* flags) {
   const int i = blockIdx.x * blockDim.x + threadIdx.x;
@@ -1215,18 +1242,36 @@ static hipError_t launch_one(const SampleArgs& a, hipStream_t st) {
   return hipGetLastError();
 }
 
+template <typename DT, bool VEC>
+static hipError_t launch_pending(const SampleArgs& a, hipStream_t st) {
+  auto k = pending_rows_kernel<DT, VEC>;
+  const unsigned grid = (unsigned)(a.B < 256 ? a.B : 256);
+  hipLaunchKernelGGL(k, dim3(grid), dim3(NT), a.L.total, st, a);
+  return hipGetLastError();
+}
+
 hipError_t launch_sample(const SampleArgs& a, int dtype, bool vec, hipStream_t st) {
+  if (a.gated) {  // single-pass kernel first; the general kernel then completes the rows it queued
+    const hipError_t e = launch_fast(a, dtype, st);
+    if (e != hipSuccess) return e;
+    if (dtype == SIMPLE_F32) return vec ? launch_pending<float, true>(a, st) : launch_pending<float, false>(a, st);
+    return vec ? launch_pending<uint16_t, true>(a, st) : launch_pending<uint16_t, false>(a, st);
+  }
   if (dtype == SIMPLE_F32) return vec ? launch_one<float, true>(a, st) : launch_one<float, false>(a, st);
   return vec ? launch_one<uint16_t, true>(a, st) : launch_one<uint16_t, false>(a, st);
 }
 
 hipError_t set_max_lds(unsigned bytes) {
-  hipError_t e;
-  e = hipFuncSetAttribute(reinterpret_cast<const void*>(sample_rows_kernel<float, true>), hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes); if (e != hipSuccess) return e;
-  e = hipFuncSetAttribute(reinterpret_cast<const void*>(sample_rows_kernel<float, false>), hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes); if (e != hipSuccess) return e;
-  e = hipFuncSetAttribute(reinterpret_cast<const void*>(sample_rows_kernel<uint16_t, true>), hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes); if (e != hipSuccess) return e;
-  e = hipFuncSetAttribute(reinterpret_cast<const void*>(sample_rows_kernel<uint16_t, false>), hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
-  return e;
+  const void* fns[8] = {
+    reinterpret_cast<const void*>(sample_rows_kernel<float, true>), reinterpret_cast<const void*>(sample_rows_kernel<float, false>),
+    reinterpret_cast<const void*>(sample_rows_kernel<uint16_t, true>), reinterpret_cast<const void*>(sample_rows_kernel<uint16_t, false>),
+    reinterpret_cast<const void*>(pending_rows_kernel<float, true>), reinterpret_cast<const void*>(pending_rows_kernel<float, false>),
+    reinterpret_cast<const void*>(pending_rows_kernel<uint16_t, true>), reinterpret_cast<const void*>(pending_rows_kernel<uint16_t, false>)};
+  for (int i = 0; i < 8; ++i) {
+    const hipError_t e = hipFuncSetAttribute(fns[i], hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
+    if (e != hipSuccess) return e;
+  }
+  return hipSuccess;
 }
 
 hipError_t launch_hot_build(const int32_t* ids, int H, int V, uint32_t* bits, uint32_t* flags, hipStream_t st) {

@@ -8,7 +8,7 @@
 
 namespace simple {
 
-// Byte offsets of one row's LDS regions (dynamic shared memory of the row workgroup).
+// Byte offsets of one row's LDS regions in the general kernel's workgroup.
 struct LdsLayout {
   uint32_t bitmap;  // history presence mask, V bits rounded up to groups of 8 words
   uint32_t grp;     // rank directory, one word per group
@@ -17,6 +17,24 @@ struct LdsLayout {
   uint32_t hist;    // radix histogram / staging (8 KB)
   uint32_t total;
 };
+
+// Byte offsets of one row's LDS regions in the single-pass kernel's workgroup.
+struct FastLayout {
+  uint32_t bitmap;   // history presence mask, one bit per column (0 bytes without history)
+  uint32_t dir;      // 16-bit count of set bits before each mask word
+  uint32_t cnt;      // 16-bit generated-token counts, indexed by the rank of the id among the set bits
+  uint32_t cand;     // candidate list: CAPF value words then CAPF ids
+  uint32_t scratch;  // 16 KB: mass histogram of the stream, then the bucket tables of the epilogue
+  uint32_t tiles;    // per-tile masses of the two-pass nucleus route
+  uint32_t samp;     // threshold sample merge area
+  uint32_t total;
+  int threads;       // workgroup size the layout was made for (512 or 1024)
+};
+
+constexpr int CAPF = 3072;    // candidate-list capacity of the single-pass kernel
+constexpr int KMAXF = 1024;   // largest top-k its list certifies
+constexpr int32_t PENDING = -2;  // id left by the single-pass kernel on rows the general kernel completes
+constexpr int PEND_ROWS = 65536; // rows per launch (capacity of the pending-row queue)
 
 struct SampleArgs {
   const void* logits;
@@ -31,12 +49,19 @@ struct SampleArgs {
   int32_t* out;
   simple_row_diag* diag;
   int max_nnz;
+  int gated;       // 1: the single-pass kernel runs first and queues the rows it leaves
+  uint32_t* pend;  // [0] queued rows, [1] finished-workgroup ticket, [2 ..] row indices
   LdsLayout L;
+  FastLayout F;
 };
 
 LdsLayout make_layout(int64_t V, int64_t max_nnz, bool with_history);
+// Layout of the single-pass kernel; total = 0 when the call cannot use it.
+FastLayout make_fast_layout(int64_t V, int dtype, int64_t max_nnz, bool with_history, bool vec, int lds_limit);
 hipError_t launch_sample(const SampleArgs& a, int dtype, bool vec, hipStream_t st);
+hipError_t launch_fast(const SampleArgs& a, int dtype, hipStream_t st);
 hipError_t set_max_lds(unsigned bytes);
+hipError_t set_max_lds_fast(unsigned bytes);
 hipError_t launch_hot_build(const int32_t* ids, int H, int V, uint32_t* bits, uint32_t* flags, hipStream_t st);
 
 }  // namespace simple
