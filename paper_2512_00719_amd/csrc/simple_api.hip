@@ -39,26 +39,32 @@ LdsLayout make_layout(int64_t V, int64_t max_nnz, bool with_history) {
   return L;
 }
 
-// The single-pass kernel needs 16-byte aligned rows, a vocabulary whose columns and per-bin counts fit
-// 18 bits, 16-bit token counts and at least two tiles per wave; its row state must fit the LDS so
-// that two workgroups of 512 threads (or one of 1024) share a compute unit.
+// The single-pass kernel needs 16-byte aligned rows, a vocabulary whose columns fit 18 bits, 16-bit
+// token counts and at least two tiles per wave.  Its row state is sized so that four workgroups of
+// 256 threads share a compute unit when the history tables allow it, else 512 threads are used.
 FastLayout make_fast_layout(int64_t V, int dtype, int64_t max_nnz, bool with_history, bool vec, int lds_limit) {
   FastLayout F{};
   if (!vec || V >= ((int64_t)1 << 18) || max_nnz > 65535) return F;
   const int64_t tile = 64 * 4 * ((dtype == SIMPLE_F32) ? 4 : 8);
+  const uint32_t n_words = (uint32_t)((V + 31) / 32), n_pairs = (n_words + 1u) / 2u;
   uint32_t off = 0;
-  const uint32_t n_words = (uint32_t)((V + 31) / 32);
-  F.bitmap = off; if (with_history) off = align16(off + n_words * 4u);
-  F.dir = off;    if (with_history) off = align16(off + n_words * 2u);
-  F.cnt = off;    if (with_history) off = align16(off + (uint32_t)((max_nnz + 2) / 2) * 4u);
-  F.cand = off;   off = align16(off + (uint32_t)CAPF * 8u);
-  F.scratch = off; off = align16(off + 16384u);
-  F.tiles = off;  off = align16(off + 4096u);
-  F.samp = off;   off = align16(off + 2048u);
-  F.threads = ((int64_t)off + 1024 <= (int64_t)lds_limit / 2) ? 512 : 1024;
-  if ((int64_t)off + 1024 > (int64_t)lds_limit) return F;  // total stays 0
+  F.bitmap = 0;
+  if (with_history) {
+    off = align16(n_pairs * 8u);
+    F.dir = off; off = align16(off + n_pairs * 2u);
+    F.cnt = off; off = align16(off + (uint32_t)((max_nnz + 3) / 2) * 4u);
+  }
+  const uint32_t tables = 256u * 12u + 256u * 16u;           // bucket tables of the long-list epilogue
+  uint32_t body = off < 28672u ? 28672u : off;               // >= 14 KB of sorted-epilogue arrays, >= 3072-entry list
+  F.list_cap = body / 8u < (uint32_t)CAPF ? body / 8u : (uint32_t)CAPF;
+  F.long_cap = (body - tables) / 8u;
+  F.hist = body;
+  F.samp = body + 8192u;
+  const uint32_t total = body + 8192u + 1024u;
+  F.threads = ((int64_t)total + 1024 <= (int64_t)lds_limit / 4) ? 256 : 512;
+  if ((int64_t)total + 1024 > (int64_t)lds_limit) return F;  // total stays 0
   if (V / tile < 2 * (F.threads / 64)) return F;
-  F.total = off;
+  F.total = total;
   return F;
 }
 

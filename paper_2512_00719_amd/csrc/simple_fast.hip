@@ -1,30 +1,32 @@
 // Single-pass row kernel for gfx950: one workgroup per logits row, every logit read from HBM once.
 //
+// A row needs little LDS (one region is shared in time between the history tables and the
+// candidate list), so four row workgroups fit a compute unit and their latency-bound phases
+// overlap with the streaming of the others.
+//
 //   history   the row's token history becomes, in LDS, a presence bit per column, a 16-bit count
-//             of set bits before each mask word and 16-bit generated-token counts indexed by the
-//             rank of the id among the set bits.  The V-wide histograms of section 2.2 are never
-//             materialised; a column's penalty is looked up only where its bit is set, so
+//             of set bits before each pair of mask words and 16-bit generated-token counts indexed
+//             by the rank of the id among the set bits.  The V-wide histograms of section 2.2 are
+//             never materialised; a column's penalty is looked up only where its bit is set, so
 //             unpenalised columns are never touched (column-wise penalties, section 5.2).
-//   sample    every wave's first tile (penalised) gives, by wave-ballot radix selection, a value g
-//             that is expected to admit a small multiple of the requested prefix length.
-//   stream    one coalesced pass of 16-byte loads per lane.  Penalised values z' are formed in
-//             registers; columns with z' >= g go to an LDS candidate list; rows whose nucleus is
-//             taken over the whole vocabulary also accumulate exp((z' - g) / tau) below g and a
-//             histogram of that mass over bins that are linear in the tempered logit.
-//   epilogue  the list certifies itself: every column whose tempered value exceeds fl(g / tau) is
-//             in it, so any prefix of the total order (value descending, id ascending) that ends
-//             above that value is known exactly (truncation first, section 5.2).  Top-k, top-p and
-//             min-p cuts, the survivors' mass and the inverse-CDF draw (Eq. (2), step (3)) are
-//             found with bucket tables of integer (fixed-point) masses, so no result depends on
-//             the order in which waves appended candidates.  SHVS (section 5.3): acceptance test
-//             on the hot mass, then the draw walks the hot or the tail survivors only.
-//   nucleus   rows whose nucleus is wider than the list find the bin that contains the cut from
-//             the mass histogram and read the row a second time: masses of the columns surely
-//             inside are summed per tile, the columns of the boundary bins are resolved exactly,
-//             and one tile is read a third time to locate the drawn id.
-// Rows the kernel cannot certify (threshold missed, list overflow, ties wider than a bucket table,
-// parameter errors, no truncation at all) are queued for the general kernel, which runs next on
-// the same stream.
+//   sample    every wave's first two tiles (penalised) give, by wave-ballot radix selection, a
+//             value g that is expected to admit a small multiple of the requested prefix length.
+//   stream    one coalesced pass of 16-byte loads per lane over the raw logits.  Columns with
+//             z >= g go to an LDS candidate list that now occupies the history's region (penalties
+//             that only lower a logit keep z >= z', so nothing with z' >= g is missed); rows whose
+//             nucleus is taken over the whole vocabulary also accumulate exp((z - g) / tau) below g.
+//   epilogue  the list moves to registers, the history tables are rebuilt in the region and the
+//             listed columns are penalised; the mass below g is corrected, exactly, for the
+//             history columns.  The list then certifies itself: every column whose tempered value
+//             exceeds fl(g / tau) is in it, so any prefix of the total order (value descending, id
+//             ascending) that ends above that value is known exactly (truncation first, section
+//             5.2).  Top-k, top-p and min-p cuts, the survivors' mass and the inverse-CDF draw
+//             (Eq. (2), step (3)) use integer (fixed-point) masses, so no result depends on the
+//             order in which waves appended candidates.  SHVS (section 5.3): acceptance test on the
+//             hot mass, then the draw walks the hot or the tail survivors only.
+// Rows the kernel cannot certify (threshold missed, list overflow, ties wider than a table,
+// penalties that raise logits, parameter errors, a nucleus wider than the list) are queued for the
+// general kernel, which runs next on the same stream.
 #include <hip/hip_runtime.h>
 #include <math.h>
 #include <stdint.h>
@@ -35,15 +37,31 @@
 namespace simple {
 namespace fast {
 
+#ifdef SIMPLE_PHASE_TIMES  // profiling builds only: per-row phase timestamps (100 MHz wall clock)
+__device__ unsigned long long g_fast_phase_times[8192 * 16];
+#define FPHASE(i) do { if (threadIdx.x == 0 && blockIdx.x < 8192) g_fast_phase_times[blockIdx.x * 16 + (i)] = wall_clock64(); } while (0)
+#define FPHASE_HW() do { if (threadIdx.x == 0 && blockIdx.x < 8192) { g_fast_phase_times[blockIdx.x * 16 + 15] = __builtin_amdgcn_s_getreg(63492); g_fast_phase_times[blockIdx.x * 16 + 14] = __builtin_amdgcn_s_getreg(63508); } } while (0)
+#else
+#define FPHASE_HW() do { } while (0)
+#define FPHASE(i) do { } while (0)
+#endif
+
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef unsigned long long u64;
 
-constexpr int UNR = 4;      // 16-byte loads per lane and tile
-constexpr int SPW = 32;     // sample entries a wave hands to the merge
-constexpr int NBF = 512;    // buckets of the epilogue tables
-constexpr int MEMB = 512;   // members of one bucket that can be resolved exactly
+constexpr int UNR = 4;       // 16-byte loads per lane and tile
+constexpr int SPW = 48;      // sample entries a wave hands to the merge
+constexpr int NBF = 256;     // buckets of the long-list tables
+constexpr int MEMB = 512;    // entries the sorted epilogue handles
+constexpr int MEMB2 = 256;   // members of one bucket the long-list path resolves exactly
+constexpr int IDR = 16;      // history ids a thread keeps in registers
 constexpr double WSCALE = 17592186044416.0;  // 2^44: fixed-point scale of probability mass
+constexpr int NBW = 1024;               // bins of the mass histogram (whole-vocabulary nucleus)
+constexpr float BINS_PER_LOG2 = 32.0f;  // bin width: 1/32 of a factor two in probability
+constexpr float MSCALE = 268435456.0f;  // 2^28: fixed-point scale of masses relative to the one at g
+constexpr int RCAP = 1024;              // columns of the boundary bin that can be resolved exactly
+constexpr float L2E_HI = 1.44269502162933349609375f, L2E_LO = 1.925963033500011e-8f;  // log2(e), split
 
 template <typename DT> struct Io;
 template <> struct Io<float> {
@@ -77,7 +95,9 @@ struct FS {
   unsigned need_k, cab_k, cab_p, n_p;
   u64 mab_k, mab_p, mab_d, cut_k, cut_p, out_w;
   int out_id;
-  unsigned hist_flag;
+  unsigned n2, nunc;           // certified / uncertified entries of the list
+  unsigned e_n; int e_rc, e_acc;
+  u64 e_SK, e_SH, e_tfix, e_skfix;
   float wmax[16];
   unsigned wcnt[16];
   unsigned r32a[16], r32b[16];
@@ -142,35 +162,60 @@ __device__ inline void blk_excl_scan2(FS& S, unsigned c, u64 m, unsigned& ce, u6
   ce = cb + ci - c; me = mb + mi - m; ct = ctt; mt = mtt;
 }
 
-// q-th largest of the 64 x N keys held by a wave (N per lane): bitwise radix descent with wave
-// ballots; no LDS, no barrier.  need >= 1; if the wave holds fewer keys the result is 0.
-template <int N>
-__device__ __forceinline__ uint32_t wave_select_key(const uint32_t (&k)[N], unsigned need) {
-  uint32_t prefix = 0u;
-#pragma unroll 1
-  for (int bit = 31; bit >= 0; --bit) {
-    const uint32_t want = (prefix >> bit) | 1u;
-    unsigned c = 0;
+__device__ __forceinline__ uint32_t wave_max_u32(uint32_t v) {
 #pragma unroll
-    for (int j = 0; j < N; ++j) c += (unsigned)__popcll(__ballot((k[j] >> bit) == want));
-    if (c >= need) prefix |= (1u << bit); else need -= c;
-  }
-  return prefix;
+  for (int o = 32; o > 0; o >>= 1) v = max(v, (uint32_t)__shfl_xor((int)v, o, 64));
+  return v;
+}
+__device__ __forceinline__ uint32_t wave_min_u32(uint32_t v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v = min(v, (uint32_t)__shfl_xor((int)v, o, 64));
+  return v;
 }
 
-// Fixed-point weight exp(y - y_max) * 2^44 of an orderable key (section 2.1 Eq. (2), stable softmax).
-__device__ __forceinline__ u64 wfix(uint32_t key, double y_max) {
-  return (u64)__double2ull_rn(exp((double)keyf(key) - y_max) * WSCALE);
+// A key t with need <= #{keys >= t} among the 64 x N keys held by a wave (N per lane), found by
+// bisection between lo and hi with wave ballots; no LDS, no barrier.  Stops as soon as the count is
+// within need + slack, else converges to the need-th largest key.  Requires #{keys >= lo} >= need
+// and hi >= every key; returns lo unchanged if the interval is empty.
+template <int N>
+__device__ __forceinline__ uint32_t wave_threshold(const uint32_t (&k)[N], unsigned need, unsigned slack, uint32_t lo, uint32_t hi) {
+#pragma unroll 1
+  for (int it = 0; it < 34 && lo < hi; ++it) {
+    const uint32_t mid = lo + ((hi - lo + 1u) >> 1);
+    unsigned c = 0;
+#pragma unroll
+    for (int j = 0; j < N; ++j) c += (unsigned)__popcll(__ballot(k[j] >= mid));
+    if (c >= need) { lo = mid; if (c <= need + slack) break; } else hi = mid - 1u;
+  }
+  return lo;
+}
+
+// Fixed-point weight exp(y - y_max) * 2^44 (stable softmax numerator, section 2.1 Eq. (2)).  The
+// exponential is float32 with a split log2(e): relative error about 1e-7, far inside the 1e-5
+// tolerance on probabilities; the sums are exact integers.
+__device__ __forceinline__ u64 wfix(uint32_t key, float y_max) {
+  const float d = keyf(key) - y_max;
+  const float t = fmaf(d, L2E_HI, d * L2E_LO);
+  return (u64)__double2ull_rn((double)__builtin_amdgcn_exp2f(t) * WSCALE);
 }
 
 // ---------------------------------------------------------------- history ---------------------
 struct Hist {
-  const uint32_t* bm;
-  const uint16_t* dir;
-  const uint16_t* cnt;
+  uint32_t* bm;     // V bits
+  uint16_t* dir;    // set bits before each pair of mask words
+  uint32_t* cnt32;  // 16-bit counts by rank, two per word
+  int n_words;
   float rep, freq, pres;
   double inv_rep;
   bool active;
+  __device__ __forceinline__ const uint16_t* cnt() const { return reinterpret_cast<const uint16_t*>(cnt32); }
+  // Rank of column idx among the set bits (`word` is its mask word).
+  __device__ __forceinline__ unsigned rank(int idx, uint32_t word) const {
+    const int w = idx >> 5;
+    unsigned r = (unsigned)dir[w >> 1];
+    if (w & 1) r += (unsigned)__popc(bm[w - 1]);
+    return r + (unsigned)__popc(word & ((1u << (idx & 31)) - 1u));
+  }
   // Z' of a column that is in the history (section 2.2): repetition (sign-aware), then frequency,
   // then presence on generated tokens; one float32 rounding per operation.  z / rep is formed as
   // fl32(double(z) * fl64(1 / rep)), which equals the IEEE float32 quotient: the product is within
@@ -181,244 +226,378 @@ struct Hist {
     if (c > 0u) { const float t = freq * (float)c; z = z - t; z = z - pres; }
     return z;
   }
+  __device__ __forceinline__ float penalised_at(float z, int idx) const {
+    const uint32_t word = bm[idx >> 5];
+    if ((word >> (idx & 31)) & 1u) z = apply(z, (uint32_t)cnt()[rank(idx, word)]);
+    return z;
+  }
 };
 
-// Builds bitmap, rank directory and counts of one row.  Out-of-range ids are ignored and flagged.
+// Clears `bytes` (rounded up to 16; the regions are 16-byte aligned and padded) with 16-byte stores.
+__device__ __forceinline__ void zero16(void* p, int bytes, int tid, int nthr) {
+  u32x4* q = reinterpret_cast<u32x4*>(p);
+  const u32x4 z = {0u, 0u, 0u, 0u};
+  for (int i = tid; i < (bytes + 15) / 16; i += nthr) q[i] = z;
+}
+
+// The presence mask alone (enough for the threshold sample): ids[j] is history entry tid + j * NTHR.
 template <int NTHR>
-__device__ inline void build_history(FS& S, uint32_t* bm, uint16_t* dir, uint32_t* cnt32, const int32_t* __restrict__ hist,
-                                     int nnz, int n_prompt, int V) {
+__device__ inline void build_bitmap(FS& S, const Hist& H, const int (&ids)[IDR], const int32_t* __restrict__ hist, int nnz, int V) {
+  const int tid = threadIdx.x;
+  const int n_pairs = (H.n_words + 1) >> 1;
+  zero16(H.bm, n_pairs * 8, tid, NTHR);
+  __syncthreads();
+#pragma unroll
+  for (int j = 0; j < IDR; ++j) {
+    const int i = tid + j * NTHR;
+    if (i < nnz && (unsigned)ids[j] < (unsigned)V) atomicOr(&H.bm[ids[j] >> 5], 1u << (ids[j] & 31));
+  }
+  for (int i = tid + IDR * NTHR; i < nnz; i += NTHR) {
+    const int id = hist[i];
+    if ((unsigned)id < (unsigned)V) atomicOr(&H.bm[id >> 5], 1u << (id & 31));
+  }
+  __syncthreads();
+}
+
+// Builds bitmap, rank directory and counts of one row from the ids a thread holds in registers
+// (ids[j] is history entry tid + j * NTHR) and, beyond those, from global memory.  own gets bit j
+// set when this thread was the first to mark ids[j] (one owner per distinct id).  Out-of-range ids
+// are ignored and flagged.
+template <int NTHR>
+__device__ inline void build_history(FS& S, const Hist& H, const int (&ids)[IDR], const int32_t* __restrict__ hist,
+                                     int nnz, int n_prompt, int V, unsigned& own) {
   constexpr int NWV = NTHR / 64;
   const int tid = threadIdx.x;
-  const int n_words = (V + 31) >> 5;
-  for (int i = tid; i < n_words; i += NTHR) bm[i] = 0u;
-  for (int i = tid; i < (nnz + 1) / 2; i += NTHR) cnt32[i] = 0u;
+  const int n_pairs = (H.n_words + 1) >> 1;
+  zero16(H.bm, n_pairs * 8, tid, NTHR);
+  zero16(H.cnt32, ((nnz + 2) / 2) * 4, tid, NTHR);
   __syncthreads();
   bool bad = false;
-  for (int i = tid; i < nnz; i += NTHR) {
+  own = 0u;
+#pragma unroll
+  for (int j = 0; j < IDR; ++j) {
+    const int i = tid + j * NTHR;
+    if (i < nnz) {
+      if ((unsigned)ids[j] < (unsigned)V) {
+        const uint32_t bit = 1u << (ids[j] & 31);
+        if (!(atomicOr(&H.bm[ids[j] >> 5], bit) & bit)) own |= 1u << j;
+      } else bad = true;
+    }
+  }
+  for (int i = tid + IDR * NTHR; i < nnz; i += NTHR) {
     const int id = hist[i];
-    if ((unsigned)id < (unsigned)V) atomicOr(&bm[id >> 5], 1u << (id & 31)); else bad = true;
+    if ((unsigned)id < (unsigned)V) atomicOr(&H.bm[id >> 5], 1u << (id & 31)); else bad = true;
   }
   if (bad) atomicOr(&S.flags, SIMPLE_DIAG_BAD_HISTORY_ID);
   __syncthreads();
-  // directory: exclusive scan of the words' popcounts, NTHR * 8 words per round
+  FPHASE(7);
+  // directory: exclusive scan of the word pairs' popcounts, NTHR * 8 pairs per round
   unsigned carry = 0;
-  for (int w0 = 0; w0 < n_words; w0 += NTHR * 8) {
-    const int wb = w0 + tid * 8;
+  for (int p0 = 0; p0 < n_pairs; p0 += NTHR * 8) {
+    const int pb = p0 + tid * 8;
     unsigned pc[8], tot = 0;
 #pragma unroll
-    for (int j = 0; j < 8; ++j) { pc[j] = (wb + j < n_words) ? (unsigned)__popc(bm[wb + j]) : 0u; tot += pc[j]; }
-    unsigned ce, ct; u64 me, mt;
-    blk_excl_scan2<NWV>(S, tot, 0ull, ce, me, ct, mt);
-    unsigned run = carry + ce;
+    for (int j = 0; j < 8; ++j) {
+      pc[j] = (pb + j < n_pairs) ? (unsigned)(__popc(H.bm[2 * (pb + j)]) + __popc(H.bm[2 * (pb + j) + 1])) : 0u;
+      tot += pc[j];
+    }
+    const unsigned incl = wave_incl_scan(tot);
+    __syncthreads();
+    if (lane_id() == 63) S.r32a[wave_id()] = incl;
+    __syncthreads();
+    unsigned base = 0, all = 0;
 #pragma unroll
-    for (int j = 0; j < 8; ++j) { if (wb + j < n_words) dir[wb + j] = (uint16_t)run; run += pc[j]; }
-    carry += ct;
+    for (int w = 0; w < NWV; ++w) { const unsigned x = S.r32a[w]; if (w < wave_id()) base += x; all += x; }
+    unsigned run = carry + base + incl - tot;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) { if (pb + j < n_pairs) H.dir[pb + j] = (uint16_t)run; run += pc[j]; }
+    carry += all;
   }
   __syncthreads();
+  FPHASE(8);
   n_prompt = min(max(n_prompt, 0), nnz);
-  for (int i = n_prompt + tid; i < nnz; i += NTHR) {
-    const int id = hist[i];
+  auto count_one = [&](int id) {
     if ((unsigned)id < (unsigned)V) {
-      const uint32_t word = bm[id >> 5];
-      const unsigned r = (unsigned)dir[id >> 5] + (unsigned)__popc(word & ((1u << (id & 31)) - 1u));
-      atomicAdd(&cnt32[r >> 1], 1u << ((r & 1u) * 16u));
+      const unsigned r = H.rank(id, H.bm[id >> 5]);
+      atomicAdd(&H.cnt32[r >> 1], 1u << ((r & 1u) * 16u));
     }
-  }
+  };
+#pragma unroll
+  for (int j = 0; j < IDR; ++j) { const int i = tid + j * NTHR; if (i >= n_prompt && i < nnz) count_one(ids[j]); }
+  for (int i = tid + IDR * NTHR; i < nnz; i += NTHR) if (i >= n_prompt) count_one(hist[i]);
   __syncthreads();
 }
 
 // ---------------------------------------------------------------- stream ----------------------
 struct StreamCtx {
-  float g, c_hi, c_lo;
-  bool need_sum;
-  u64* hist;  // NBW bins of (count << 46 | mass * 2^28)
+  float g, y_g;    // candidate threshold on the logit, and its tempered value fl32(g / tau)
+  double inv_tau;
+  bool need_sum;   // the row needs the mass of the columns below g
+  u64* hist;       // NBW bins of (count << 46 | mass * 2^28) over the tempered logit below y_g
 };
-constexpr int NBW = 2048;
-constexpr float BINS_PER_LOG2 = 64.0f;
 
-// Unpacks one tile and applies the penalties to the columns whose history bit is set.
+// Mass of one column relative to the mass at y_g, w = exp(y - y_g) with y = fl32(z / tau), and the
+// bin of y (linear in y, so columns of equal y share a bin).  y is formed as fl32(double(z) * fl64(1 /
+// tau)): the IEEE float32 quotient (see Hist::apply).  float32 exponential, split log2(e).
+__device__ __forceinline__ float mass_term(float z, const StreamCtx& C, int& bin) {
+  const float y = (float)((double)z * C.inv_tau);
+  const float d = y - C.y_g;
+  const float t = fmaf(d, L2E_HI, d * L2E_LO);
+  bin = (int)fminf(fmaxf(-t * BINS_PER_LOG2, 0.0f), (float)(NBW - 1));
+  return __builtin_amdgcn_exp2f(t);
+}
+__device__ __forceinline__ u64 mass_fix(float w) { return (u64)(w * MSCALE + 0.5f); }
+__device__ __forceinline__ u64 hist_entry(float w) { return (1ull << 46) | mass_fix(w); }
+
+// Unpacks one 16-byte group of a sample tile; columns that are in the history are masked out, so
+// the threshold comes from unpenalised columns only (history columns can only add to the prefix).
 template <typename DT>
-__device__ __forceinline__ void prep_tile(const typename Io<DT>::Raw (&A)[UNR], int tb, const Hist& H,
-                                          float (&z)[UNR][Io<DT>::EPL]) {
+__device__ __forceinline__ void sample_group(const typename Io<DT>::Raw& A, int idx0, const Hist& H, float (&z)[Io<DT>::EPL]) {
   constexpr int EPL = Io<DT>::EPL;
   constexpr unsigned EMASK = (1u << EPL) - 1u;
+  Io<DT>::unpack(A, z);
+  if (H.active) {
+    const uint32_t nib = (H.bm[idx0 >> 5] >> ((unsigned)idx0 & 31u)) & EMASK;
+#pragma unroll
+    for (int e = 0; e < EPL; ++e) z[e] = (nib & (1u << e)) ? -INFINITY : z[e];
+  }
+}
+
+// Appends the flagged elements of one 16-byte group per lane with a single list reservation.
+template <int EPL>
+__device__ __forceinline__ void append_group(FS& S, uint32_t* lz, uint32_t* li, unsigned cap, const float (&z)[EPL], float g, int idx0) {
   const int lane = lane_id();
+  u64 m[EPL];
+  unsigned pre[EPL], tot = 0;
 #pragma unroll
-  for (int u = 0; u < UNR; ++u) {
-    Io<DT>::unpack(A[u], z[u]);
-    if (H.active) {
-      const int idx0 = tb + u * 64 * EPL + lane * EPL;
-      const uint32_t word = H.bm[idx0 >> 5];
-      const unsigned sh = (unsigned)idx0 & 31u;
-      const uint32_t nib = (word >> sh) & EMASK;
-      if (nib) {
-        const unsigned base = (unsigned)H.dir[idx0 >> 5] + (unsigned)__popc(word & ((1u << sh) - 1u));
+  for (int e = 0; e < EPL; ++e) { m[e] = __ballot(!(z[e] < g)); pre[e] = tot; tot += (unsigned)__popcll(m[e]); }
+  unsigned base = 0;
+  if (lane == 0) base = atomicAdd(&S.cand_count, tot);
+  base = __builtin_amdgcn_readfirstlane(base);
 #pragma unroll
-        for (int e = 0; e < EPL; ++e) {
-          if (nib & (1u << e)) {
-            const unsigned r = base + (unsigned)__popc(nib & ((1u << e) - 1u));
-            z[u][e] = H.apply(z[u][e], (uint32_t)H.cnt[r]);
-          }
-        }
-      }
+  for (int e = 0; e < EPL; ++e) {
+    if ((m[e] >> lane) & 1ull) {
+      const unsigned slot = base + pre[e] + lanes_before(m[e]);
+      if (slot < cap) { lz[slot] = __float_as_uint(z[e]); li[slot] = (uint32_t)(idx0 + e); }
     }
   }
 }
 
-__device__ __forceinline__ void append_lanes(FS& S, uint32_t* cz, uint32_t* ci, u64 m, float z, int idx) {
-  const int lane = lane_id();
-  unsigned base = 0;
-  if (lane == 0) base = atomicAdd(&S.cand_count, (unsigned)__popcll(m));
-  base = __shfl(base, 0, 64);
-  if ((m >> lane) & 1ull) {
-    const unsigned slot = base + lanes_before(m);
-    if (slot < (unsigned)CAPF) { cz[slot] = __float_as_uint(z); ci[slot] = (uint32_t)idx; }
-  }
-}
-
-// Mass of one column below g, relative to g: exp2((z - g) * log2(e) / tau), and its histogram bin.
-__device__ __forceinline__ float below_term(float z, const StreamCtx& C, bool do_hist) {
-  const float d = z - C.g;
-  const float t = fmaf(d, C.c_hi, d * C.c_lo);
-  const float w = (z < C.g) ? __builtin_amdgcn_exp2f(t) : 0.0f;
-  if (do_hist && z < C.g) {
-    const int b = min((int)(-t * BINS_PER_LOG2), NBW - 1);
-    atomicAdd(&C.hist[b], (1ull << 46) | (u64)(w * 268435456.0f + 0.5f));
-  }
-  return w;
-}
-
-// Candidate test and mass accumulation of one prepared tile.
+// One tile of the stream: raw logits against g; rows that need it also bin the mass below g.
 template <typename DT>
-__device__ __forceinline__ void consume_tile(const float (&z)[UNR][Io<DT>::EPL], int tb, const StreamCtx& C, double& acc,
-                                             FS& S, uint32_t* cz, uint32_t* ci) {
+__device__ __forceinline__ void stream_tile(const typename Io<DT>::Raw (&A)[UNR], int tb, const StreamCtx& C,
+                                            FS& S, uint32_t* lz, uint32_t* li, unsigned cap) {
   constexpr int EPL = Io<DT>::EPL;
   const int lane = lane_id();
 #pragma unroll
   for (int u = 0; u < UNR; ++u) {
+    float z[EPL];
+    Io<DT>::unpack(A[u], z);
+    const int idx0 = tb + u * 64 * EPL + lane * EPL;
     if (C.need_sum) {
-      float ps = 0.0f;
 #pragma unroll
-      for (int e = 0; e < EPL; ++e) ps += below_term(z[u][e], C, C.hist != nullptr);
-      acc += (double)ps;
+      for (int e = 0; e < EPL; ++e) {
+        int b;
+        const float w = mass_term(z[e], C, b);
+        if (z[e] < C.g) atomicAdd(&C.hist[b], hist_entry(w));
+      }
     }
     bool any = false;
 #pragma unroll
-    for (int e = 0; e < EPL; ++e) any = any || !(z[u][e] < C.g);
-    if (__ballot(any)) {
-#pragma unroll
-      for (int e = 0; e < EPL; ++e) {
-        const u64 m = __ballot(!(z[u][e] < C.g));
-        if (m) append_lanes(S, cz, ci, m, z[u][e], tb + u * 64 * EPL + lane * EPL + e);
-      }
-    }
+    for (int e = 0; e < EPL; ++e) any = any || !(z[e] < C.g);
+    if (__ballot(any)) append_group<EPL>(S, lz, li, cap, z, C.g, idx0);
   }
 }
 
-// ---------------------------------------------------------------- epilogue on the list --------
+// ---------------------------------------------------------------- epilogue --------------------
 enum { FIN_DONE = 0, FIN_PENDING = 1, FIN_WIDE = 2 };
 
-// Exact selection, softmax and draw on the candidate list (see the file comment).  On FIN_DONE the
-// result is in S.out_id / S.out_w (or the error flag is set); FIN_WIDE: the nucleus reaches below
-// the list; FIN_PENDING: the list cannot certify the row.
+__device__ __forceinline__ u64 pick8(const u64 (&a)[8], int j) {
+  u64 v = 0ull;
+#pragma unroll
+  for (int i = 0; i < 8; ++i) v = (i == j) ? a[i] : v;
+  return v;
+}
+
+// Mass of the top-k prefix when top-k is off: the whole row (list, uncertified entries, below g).
+__device__ __forceinline__ u64 whole_row_mass(u64 total_m, unsigned n_unc, uint32_t key_g, float y_max, float g, float tau,
+                                              double S_below) {
+  (void)g; (void)tau;
+  const double f0 = exp((double)keyf(key_g) - (double)y_max);  // S_below is relative to the mass at y_g
+  return total_m + (u64)n_unc * wfix(key_g, y_max) + (u64)__double2ull_rn(S_below * f0 * WSCALE);
+}
+
+// Survivors, masses and the draw for at most MEMB certified entries (the usual case).  The entries
+// arrive as composites in mc[0, n); they are ranked by counting, laid out in sorted order and one
+// wave takes every decision of Eq. (2) on that order; then all threads locate the drawn id.
 template <int NTHR>
-__device__ __noinline__ int finalize_list(FS& S, const RowCfg& R, uint32_t* cz, uint32_t* ci, unsigned char* scratch,
-                                          float g, double S_below, const uint32_t* __restrict__ hot_bits,
-                                          simple_row_diag& dg) {
-  constexpr int NWV = NTHR / 64;
-  constexpr int PER = CAPF / NTHR;
-  const int tid = threadIdx.x;
-  uint32_t* fcnt = reinterpret_cast<uint32_t*>(scratch);
-  u64* fmass = reinterpret_cast<u64*>(scratch + 2048);
-  u64* mc = reinterpret_cast<u64*>(scratch + 6144);
-  u64* mw = reinterpret_cast<u64*>(scratch + 10240);
-  const unsigned n = S.cand_count;
-  uint32_t key[PER], id[PER];
-  bool err = false;
-  uint32_t kloc = 0u;
-#pragma unroll
-  for (int j = 0; j < PER; ++j) {
-    const unsigned i = (unsigned)tid + (unsigned)j * NTHR;
-    key[j] = 0u; id[j] = 0u;
-    if (i < n) {
-      const float z = __uint_as_float(cz[i]);
-      id[j] = ci[i];
-      if (z != z || z == INFINITY) err = true;
-      else {
-        const float y = R.greedy ? z : z / R.tau;
-        if (y == INFINITY) err = true; else key[j] = fkey(y);
-      }
-    }
-    kloc = max(kloc, key[j]);
+__device__ __forceinline__ int finalize_small(FS& S, const RowCfg& R, unsigned n, unsigned n_unc, uint32_t kmax, uint32_t key_g,
+                                              float g, double S_below, const u64* mc, u64* sc, u64* sw, uint32_t* sid,
+                                              const uint32_t* __restrict__ hot_bits, simple_row_diag& dg) {
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const float y_max = keyf(kmax);
+  for (unsigned t = tid; t < n; t += NTHR) {
+    const u64 c = mc[t];
+    unsigned r = 0;
+    for (unsigned q = 0; q < n; ++q) r += (mc[q] > c) ? 1u : 0u;
+    sc[r] = c;
+    sw[r] = R.greedy ? 0ull : wfix((uint32_t)(c >> 32), y_max);
   }
-  if (kloc) atomicMax(&S.kmax, kloc);
-  if (err) atomicOr(&S.flags, SIMPLE_DIAG_ERROR | SIMPLE_DIAG_BAD_LOGIT);
   __syncthreads();
-  if (S.flags & SIMPLE_DIAG_ERROR) return FIN_DONE;
-  const uint32_t kmax = S.kmax;
-  const uint32_t key_g = fkey(R.greedy ? g : g / R.tau);
-  if (kmax <= key_g || kmax <= KEY_NEG_INF) return FIN_PENDING;
-  // certified entries: tempered value strictly above fl(g / tau)
-  unsigned ncl = 0, nul = 0;
-  u64 cl = 0ull, dummy = 0ull;
+  if (wave == 0) {
+    int rc = FIN_DONE;
+    if (R.greedy) {
+      if (lane == 0) { S.out_id = (int)(0xFFFFFFFFu - (uint32_t)sc[0]); S.out_w = 0ull; S.e_n = 1u; S.e_SK = 1ull; S.e_skfix = 0ull; S.e_SH = 0ull; S.e_acc = 0; }
+    } else {
+      u64 wl[8], cum[8];
+      uint32_t kl[8], il[8];
+      u64 loc = 0ull;
 #pragma unroll
-  for (int j = 0; j < PER; ++j) {
-    if (!key[j]) continue;
-    if (key[j] > key_g) { ++ncl; const u64 c = composite(key[j], id[j]); cl = (c > cl) ? c : cl; }
-    else { ++nul; key[j] = 0u; }
+      for (int j = 0; j < 8; ++j) {
+        const unsigned r = (unsigned)lane * 8u + (unsigned)j;
+        const u64 c = (r < n) ? sc[r] : 0ull;
+        wl[j] = (r < n) ? sw[r] : 0ull;
+        kl[j] = (uint32_t)(c >> 32); il[j] = 0xFFFFFFFFu - (uint32_t)c;
+        loc += wl[j];
+      }
+      const u64 incl = wave_incl_scan(loc);
+      const u64 total_m = __shfl(incl, 63, 64);
+      u64 run = incl - loc;
+#pragma unroll
+      for (int j = 0; j < 8; ++j) { run += wl[j]; cum[j] = run; }
+      const unsigned n_k = R.k_on ? (unsigned)R.top_k : n;  // n >= top_k was checked by the caller
+      const u64 S_klist = __shfl(pick8(cum, (int)((n_k - 1u) & 7u)), (int)((n_k - 1u) >> 3), 64);
+      const u64 S_k_fix = R.k_on ? S_klist : whole_row_mass(total_m, n_unc, key_g, y_max, g, R.tau, S_below);
+      u64 target = 0ull;
+      bool p_found = false;
+      if (R.p_le0) p_found = true;
+      else if (R.p_on) {
+        target = (u64)__double2ull_ru((double)R.top_p * (double)S_k_fix);
+        if (target == 0ull) target = 1ull;
+        p_found = S_klist >= target;
+      }
+      uint32_t key_thr = 0u;
+      bool m_cert = false;
+      if (R.minp_on) {
+        const float thr = y_max + (float)log((double)R.min_p);
+        key_thr = fkey(thr);
+        m_cert = key_thr > key_g;
+      }
+      const bool known = R.k_on || p_found || m_cert;
+      if (!known) rc = (R.need_sum && !R.minp_on) ? FIN_WIDE : FIN_PENDING;
+      // every cut is a prefix of the sorted order; the first entry always survives
+      const bool use_hot = hot_bits != nullptr;
+      unsigned okm = 0u, hotm = 0u;
+      unsigned cl = 0; u64 ml = 0ull, hl = 0ull;
+#pragma unroll
+      for (int j = 0; j < 8; ++j) {
+        const unsigned r = (unsigned)lane * 8u + (unsigned)j;
+        bool o = r < n_k;
+        if (R.p_le0) o = o && (r == 0u);
+        else if (R.p_on && p_found) o = o && (cum[j] - wl[j] < target);
+        if (m_cert) o = o && (kl[j] >= key_thr);
+        o = (o || r == 0u) && (r < n);
+        if (o) {
+          okm |= 1u << j; ++cl; ml += wl[j];
+          if (use_hot && ((hot_bits[il[j] >> 5] >> (il[j] & 31)) & 1u)) { hotm |= 1u << j; hl += wl[j]; }
+        }
+      }
+      const unsigned ns = wave_sum(cl);
+      const u64 S_K = wave_sum(ml);
+      const u64 S_H = use_hot ? wave_sum(hl) : 0ull;
+      bool pick_hot = false;
+      if (use_hot) pick_hot = (S_H > 0ull) && (R.u_acc * (double)S_K <= (double)S_H);
+      const u64 S_cls = use_hot ? (pick_hot ? S_H : S_K - S_H) : S_K;
+      const double u = use_hot ? (pick_hot ? R.u_draw : R.u_tail) : R.u_draw;
+      if (rc == FIN_DONE && S_cls == 0ull) rc = FIN_PENDING;  // the chosen class holds no mass here: general kernel
+      u64 tfix = (u64)__double2ull_rd(u * (double)S_cls);
+      if (S_cls > 0ull && tfix >= S_cls) tfix = S_cls - 1ull;
+#pragma unroll
+      for (int j = 0; j < 8; ++j) {
+        const unsigned r = (unsigned)lane * 8u + (unsigned)j;
+        const bool in_cls = ((okm >> j) & 1u) && (!use_hot || (((hotm >> j) & 1u) != 0u) == pick_hot);
+        if (r < n) sid[r] = in_cls ? il[j] : 0xFFFFFFFFu;
+      }
+      if (lane == 0) { S.e_n = ns; S.e_SK = S_K; S.e_SH = S_H; S.e_tfix = tfix; S.e_skfix = S_k_fix; S.e_acc = pick_hot ? 1 : 0; }
+    }
+    if (lane == 0) S.e_rc = rc;
   }
-  unsigned n_cert = ncl, n_unc = nul;
-  u64 cmax = cl;
-  blk_reduce<NWV>(S, n_cert, n_unc, cmax, dummy);
-  if (R.greedy) {
-    if (tid == 0) { S.out_id = (int)(0xFFFFFFFFu - (uint32_t)cmax); S.out_w = 0ull; }
-    dg.n_survivors = 1;
-    dg.p_chosen = 1.0f;
-    __syncthreads();
-    return FIN_DONE;
+  __syncthreads();
+  if (S.e_rc != FIN_DONE) return S.e_rc;
+  dg.n_survivors = (int)S.e_n;
+  if (R.greedy) { dg.p_chosen = 1.0f; return FIN_DONE; }
+  dg.s_k = (double)S.e_skfix / WSCALE;
+  if (hot_bits != nullptr) {
+    dg.alpha = (double)S.e_SH / (double)S.e_SK;
+    dg.flags |= SIMPLE_DIAG_SHVS | (S.e_acc ? SIMPLE_DIAG_ACCEPTED : 0u);
   }
-  const unsigned n_k = R.k_on ? (unsigned)R.top_k : (unsigned)R.V;
-  if (R.k_on && n_cert < n_k) return FIN_PENDING;  // the sampled threshold admitted too few
-  const double y_max = (double)keyf(kmax);
-  u64 wf[PER];
-  unsigned bkt[PER];
+  // inverse CDF in ascending token id over the survivors of the chosen class (they lie in [0, e_n))
+  const unsigned n_s = S.e_n;
+  const u64 tfix = S.e_tfix;
+  for (unsigned t = tid; t < n_s; t += NTHR) {
+    const uint32_t my = sid[t];
+    if (my == 0xFFFFFFFFu) continue;
+    u64 C = 0ull;
+    for (unsigned q = 0; q < n_s; ++q) C += (sid[q] <= my) ? sw[q] : 0ull;
+    if (C > tfix && C - sw[t] <= tfix) { S.out_id = (int)my; S.out_w = sw[t]; }
+  }
+  __syncthreads();
+  dg.p_chosen = (float)((double)S.out_w / (double)S.e_SK);
+  return (S.out_id >= 0) ? FIN_DONE : FIN_PENDING;
+}
+
+// Long lists (more than MEMB certified entries, in LDS as keys lk[] / ids li[]): bucket tables over
+// the key range locate each cut; only the bucket that holds a cut is resolved entry by entry.
+// Same decisions as finalize_small.
+template <int NTHR>
+__device__ __forceinline__ int finalize_long(FS& S, const RowCfg& R, unsigned n, unsigned n_unc, uint32_t kmax,
+                                             uint32_t key_g, float g, double S_below, const uint32_t* lk, const uint32_t* li,
+                                             unsigned char* tables, const uint32_t* __restrict__ hot_bits, simple_row_diag& dg) {
+  constexpr int NWV = NTHR / 64;
+  const int tid = threadIdx.x;
+  uint32_t* fcnt = reinterpret_cast<uint32_t*>(tables);             // NBF * 4
+  u64* fmass = reinterpret_cast<u64*>(tables + NBF * 4);             // NBF * 8
+  u64* mc = reinterpret_cast<u64*>(tables + NBF * 12);               // MEMB2 * 8
+  u64* mw = reinterpret_cast<u64*>(tables + NBF * 12 + MEMB2 * 8);   // MEMB2 * 8
+  const float y_max = keyf(kmax);
   const unsigned span = kmax - key_g;
-  const int bshift = max(0, 32 - (int)__clz(span) - 9);
+  const int bshift = max(0, 32 - (int)__clz(span) - 8);
+  u64 cl = 0ull;
+  for (unsigned i = tid; i < n; i += NTHR) { const u64 c = composite(lk[i], li[i]); cl = (c > cl) ? c : cl; }
+  unsigned da = 0, db = 0; u64 cmax = cl, dd = 0ull;
+  blk_reduce<NWV>(S, da, db, cmax, dd);
   for (int i = tid; i < NBF; i += NTHR) { fcnt[i] = 0u; fmass[i] = 0ull; }
   __syncthreads();
-#pragma unroll
-  for (int j = 0; j < PER; ++j) {
-    wf[j] = 0ull; bkt[j] = 0u;
-    if (key[j]) {
-      wf[j] = wfix(key[j], y_max);
-      bkt[j] = (kmax - key[j]) >> bshift;
-      atomicAdd(&fcnt[bkt[j]], 1u);
-      atomicAdd(&fmass[bkt[j]], wf[j]);
-    }
+  for (unsigned i = tid; i < n; i += NTHR) {
+    const uint32_t k = lk[i];
+    const unsigned b = (kmax - k) >> bshift;
+    atomicAdd(&fcnt[b], 1u);
+    atomicAdd(&fmass[b], wfix(k, y_max));
   }
   __syncthreads();
   const unsigned c = (tid < NBF) ? fcnt[tid] : 0u;
   const u64 m = (tid < NBF) ? fmass[tid] : 0ull;
   unsigned ce, total_c; u64 me, total_m;
   blk_excl_scan2<NWV>(S, c, m, ce, me, total_c, total_m);
+  const unsigned n_k = R.k_on ? (unsigned)R.top_k : (unsigned)R.V;
   // ---- top-k cut: the bucket that holds the n_k-th entry, then its members exactly ----
-  const bool kcut = R.k_on && n_cert > n_k;
+  const bool kcut = R.k_on && n > n_k;
   if (kcut && tid < NBF && c > 0u && ce < n_k && n_k <= ce + c) { S.bk = tid; S.need_k = n_k - ce; S.cab_k = ce; S.mab_k = me; }
   __syncthreads();
   u64 cut_k = 0ull, S_klist = total_m;
   int bk = -1;
   if (kcut) {
     bk = S.bk;
-#pragma unroll
-    for (int j = 0; j < PER; ++j) {
-      if (key[j] && (int)bkt[j] == bk) {
+    for (unsigned i = tid; i < n; i += NTHR) {
+      const uint32_t k = lk[i];
+      if ((int)((kmax - k) >> bshift) == bk) {
         const unsigned slot = atomicAdd(&S.memb, 1u);
-        if (slot < (unsigned)MEMB) { mc[slot] = composite(key[j], id[j]); mw[slot] = wf[j]; }
+        if (slot < (unsigned)MEMB2) { mc[slot] = composite(k, li[i]); mw[slot] = wfix(k, y_max); }
       }
     }
     __syncthreads();
     const unsigned nm = S.memb;
-    if (nm > (unsigned)MEMB) return FIN_PENDING;  // ties wider than the member table
+    if (nm > (unsigned)MEMB2) return FIN_PENDING;  // ties wider than the member table
     const unsigned need = S.need_k;
     for (unsigned mi = tid; mi < nm; mi += NTHR) {
       const u64 cm = mc[mi];
@@ -435,11 +614,7 @@ __device__ __noinline__ int finalize_list(FS& S, const RowCfg& R, uint32_t* cz, 
     __syncthreads();
   }
   // ---- mass of the top-k prefix (all of V when top-k is off) ----
-  u64 S_k_fix = S_klist;
-  if (!R.k_on) {
-    const double f0 = exp((double)g / (double)R.tau - y_max);
-    S_k_fix = total_m + (u64)n_unc * wfix(key_g, y_max) + (u64)__double2ull_rn(S_below * f0 * WSCALE);
-  }
+  const u64 S_k_fix = R.k_on ? S_klist : whole_row_mass(total_m, n_unc, key_g, y_max, g, R.tau, S_below);
   // ---- nucleus cut: shortest prefix whose mass reaches top_p * S_k ----
   u64 cut_p = 0ull;
   bool p_found = false;
@@ -454,16 +629,16 @@ __device__ __noinline__ int finalize_list(FS& S, const RowCfg& R, uint32_t* cz, 
     __syncthreads();
     const int bp = S.bp;
     if (bp >= 0) {
-#pragma unroll
-      for (int j = 0; j < PER; ++j) {
-        if (key[j] && (int)bkt[j] == bp && composite(key[j], id[j]) >= cut_k) {
+      for (unsigned i = tid; i < n; i += NTHR) {
+        const uint32_t k = lk[i];
+        if ((int)((kmax - k) >> bshift) == bp && composite(k, li[i]) >= cut_k) {
           const unsigned slot = atomicAdd(&S.memb, 1u);
-          if (slot < (unsigned)MEMB) { mc[slot] = composite(key[j], id[j]); mw[slot] = wf[j]; }
+          if (slot < (unsigned)MEMB2) { mc[slot] = composite(k, li[i]); mw[slot] = wfix(k, y_max); }
         }
       }
       __syncthreads();
       const unsigned nm = S.memb;
-      if (nm > (unsigned)MEMB) return FIN_PENDING;
+      if (nm > (unsigned)MEMB2) return FIN_PENDING;
       const u64 mab = S.mab_p;
       for (unsigned mi = tid; mi < nm; mi += NTHR) {
         const u64 cm = mc[mi], wm = mw[mi];
@@ -482,7 +657,7 @@ __device__ __noinline__ int finalize_list(FS& S, const RowCfg& R, uint32_t* cz, 
   u64 cut_m = 0ull;
   bool m_cert = false;
   if (R.minp_on) {
-    const float thr = keyf(kmax) + (float)log((double)R.min_p);
+    const float thr = y_max + (float)log((double)R.min_p);
     const uint32_t key_thr = fkey(thr);
     if (key_thr > key_g) { cut_m = (u64)key_thr << 32; m_cert = true; }
   }
@@ -495,18 +670,15 @@ __device__ __noinline__ int finalize_list(FS& S, const RowCfg& R, uint32_t* cz, 
   if (cut > cmax) cut = cmax;  // never empty
   // ---- survivors K_b, their mass, the hot split (Eq. (7)) ----
   const bool use_hot = hot_bits != nullptr;
-  bool surv[PER], hot[PER];
   unsigned ns = 0, nh = 0; u64 sk = 0ull, sh = 0ull, cdum = 0ull;
-#pragma unroll
-  for (int j = 0; j < PER; ++j) {
-    surv[j] = key[j] && composite(key[j], id[j]) >= cut;
-    hot[j] = false;
-    if (surv[j]) {
-      ++ns; sk += wf[j];
-      if (use_hot) { hot[j] = (hot_bits[id[j] >> 5] >> (id[j] & 31)) & 1u; if (hot[j]) { ++nh; sh += wf[j]; } }
+  for (unsigned i = tid; i < n; i += NTHR) {
+    const uint32_t k = lk[i];
+    if (composite(k, li[i]) >= cut) {
+      const u64 w = wfix(k, y_max);
+      ++ns; sk += w;
+      if (use_hot && ((hot_bits[li[i] >> 5] >> (li[i] & 31)) & 1u)) { ++nh; sh += w; }
     }
   }
-  // two reductions share the barriers: (ns, nh, -, sk) then sh
   blk_reduce<NWV>(S, ns, nh, cdum, sk);
   const u64 S_K = sk;
   u64 S_H = 0ull;
@@ -525,15 +697,15 @@ __device__ __noinline__ int finalize_list(FS& S, const RowCfg& R, uint32_t* cz, 
   // ---- inverse CDF in ascending token id: first id whose running mass exceeds u * S ----
   u64 tfix = (u64)__double2ull_rd(u * (double)S_cls);
   if (tfix >= S_cls) tfix = S_cls - 1ull;
-  const int ishift = max(0, 32 - (int)__clz((unsigned)(R.V - 1) | 1u) - 9);
+  const int ishift = max(0, 32 - (int)__clz((unsigned)(R.V - 1) | 1u) - 8);
   for (int i = tid; i < NBF; i += NTHR) fmass[i] = 0ull;
   __syncthreads();
-  bool incls[PER];
-#pragma unroll
-  for (int j = 0; j < PER; ++j) {
-    incls[j] = surv[j] && (!use_hot || hot[j] == pick_hot);
-    if (incls[j]) atomicAdd(&fmass[id[j] >> ishift], wf[j]);
-  }
+  auto in_class = [&](uint32_t k, uint32_t id) {
+    if (composite(k, id) < cut) return false;
+    if (!use_hot) return true;
+    return (((hot_bits[id >> 5] >> (id & 31)) & 1u) != 0u) == pick_hot;
+  };
+  for (unsigned i = tid; i < n; i += NTHR) if (in_class(lk[i], li[i])) atomicAdd(&fmass[li[i] >> ishift], wfix(lk[i], y_max));
   __syncthreads();
   {
     const u64 m2 = (tid < NBF) ? fmass[tid] : 0ull;
@@ -544,16 +716,16 @@ __device__ __noinline__ int finalize_list(FS& S, const RowCfg& R, uint32_t* cz, 
   __syncthreads();
   const int bd = S.bd;
   if (bd < 0) return FIN_PENDING;  // cannot happen: tfix < S_cls
-#pragma unroll
-  for (int j = 0; j < PER; ++j) {
-    if (incls[j] && (int)(id[j] >> ishift) == bd) {
+  for (unsigned i = tid; i < n; i += NTHR) {
+    if (in_class(lk[i], li[i]) && (int)(li[i] >> ishift) == bd) {
       const unsigned slot = atomicAdd(&S.memb, 1u);
-      if (slot < (unsigned)MEMB) { mc[slot] = (u64)id[j]; mw[slot] = wf[j]; }
+      if (slot < (unsigned)MEMB2) { mc[slot] = (u64)li[i]; mw[slot] = wfix(lk[i], y_max); }
     }
   }
   __syncthreads();
   {
-    const unsigned nm = S.memb;  // a bucket spans at most 512 ids
+    const unsigned nm = S.memb;
+    if (nm > (unsigned)MEMB2) return FIN_PENDING;
     const u64 mab = S.mab_d;
     for (unsigned mi = tid; mi < nm; mi += NTHR) {
       const u64 im = mc[mi], wm = mw[mi];
@@ -565,6 +737,287 @@ __device__ __noinline__ int finalize_list(FS& S, const RowCfg& R, uint32_t* cz, 
   __syncthreads();
   dg.p_chosen = (float)((double)S.out_w / (double)S_K);
   return (S.out_id >= 0) ? FIN_DONE : FIN_PENDING;
+}
+
+// Second pass, one column: a sure survivor adds its mass to its tile (returns 1); a column of the
+// boundary bin goes to the boundary table; anything else is dropped.
+__device__ __forceinline__ unsigned classify_col(float z, int idx, unsigned hot, const StreamCtx& C, int bstar, int T,
+                                                 u64* tiles, FS& S, u64* rl) {
+  int b;
+  const float w = mass_term(z, C, b);
+  if (!(z < C.g) || b < bstar) { atomicAdd(&tiles[hot * 256u + (unsigned)(idx / T)], mass_fix(w)); return 1u; }
+  if (b == bstar) {
+    const unsigned slot = atomicAdd(&S.memb, 1u);
+    if (slot < (unsigned)RCAP) rl[slot] = ((u64)__float_as_uint(z) << 32) | (u64)(uint32_t)idx;
+  }
+  return 0u;
+}
+
+// Whole-vocabulary nucleus wider than the candidate list (top-p over all of V, section 2.1 Eq. (2)).
+// The stream left a histogram of the mass below g over bins that are linear in the tempered logit
+// (corrected for the history columns).  The bin that holds the cut follows from the cumulated
+// masses; a second pass over the row sums, per tile, the masses of the columns surely inside and
+// collects the columns of that one bin, among which the cut is found exactly in the total order
+// (columns of equal tempered value share a bin).  The draw then walks the per-tile masses of its
+// class in ascending id and reads one tile a third time.  All masses are integers, so nothing
+// depends on summation order.  Returns false when a table overflows: the general kernel takes the row.
+template <typename DT, int NTHR>
+__device__ __noinline__ bool wide_route(FS& S, const RowCfg& R, const StreamCtx& C, const Hist& H, const FastLayout& F,
+                                        unsigned char* lds, const DT* __restrict__ rowp, int V, int t0, int t1,
+                                        const int (&ids)[IDR], unsigned own, const float (&zp)[IDR], u64 M_list,
+                                        u64 S_below_int, uint32_t kmax, const uint32_t* __restrict__ hot_bits,
+                                        simple_row_diag& dg) {
+  constexpr int NWV = NTHR / 64;
+  constexpr int EPL = Io<DT>::EPL;
+  constexpr int T = 64 * EPL * UNR;
+  constexpr unsigned EMASK = (1u << EPL) - 1u;
+  typedef typename Io<DT>::Raw Raw;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int nfull = V / T;
+  const bool use_hot = hot_bits != nullptr;
+  u64* tiles = C.hist;  // [2][256] per-tile masses of the survivors (tail / hot), once the bins are consumed
+  // region map: [0, rl_off) presence mask during the pass, then composites (8 KB), sub-bin tables (3 KB),
+  // member tables (4 KB); [rl_off, rl_off + 8 KB) boundary columns, later their masses, later the tile patch
+  const uint32_t rl_off = (H.active && F.dir > 16384u) ? F.dir : 16384u;  // behind the mask (F.dir is where it ends)
+  u64* rl = reinterpret_cast<u64*>(lds + rl_off);
+  u64* rcmp = reinterpret_cast<u64*>(lds);
+  uint32_t* fcnt = reinterpret_cast<uint32_t*>(lds + 8192);
+  u64* fmass = reinterpret_cast<u64*>(lds + 8192 + NBF * 4);
+  u64* mc = reinterpret_cast<u64*>(lds + 8192 + NBF * 12);
+  u64* mw = mc + MEMB2;
+  // -- the bin that holds the cut: cumulative mass from the top reaches top_p * total --
+  const u64 S_tot = M_list + S_below_int;
+  const u64 target = (u64)__double2ull_ru((double)R.top_p * (double)S_tot);
+  {
+    constexpr int BPT = (NBW + NTHR - 1) / NTHR;
+    u64 hm[BPT]; unsigned hc[BPT]; u64 loc = 0ull;
+#pragma unroll
+    for (int j = 0; j < BPT; ++j) {
+      const int b = tid * BPT + j;
+      const u64 e = (b < NBW) ? C.hist[b] : 0ull;
+      hm[j] = e & ((1ull << 46) - 1ull); hc[j] = (unsigned)(e >> 46); loc += hm[j];
+    }
+    unsigned ce, ct; u64 me, mt;
+    blk_excl_scan2<NWV>(S, 0u, loc, ce, me, ct, mt);
+    u64 run = M_list + me;
+#pragma unroll
+    for (int j = 0; j < BPT; ++j) {
+      const int b = tid * BPT + j;
+      if (b < NBW && run < target && run + hm[j] >= target) { S.bk = b; S.mab_k = run; S.need_k = hc[j]; }
+      run += hm[j];
+    }
+  }
+  __syncthreads();
+  const int bstar = S.bk;
+  const u64 m_above = S.mab_k;
+  if (bstar < 0 || S.need_k > (unsigned)RCAP || nfull + 1 > 256) return false;
+  for (int i = tid; i < 512; i += NTHR) tiles[i] = 0ull;
+  if (tid == 0) { S.memb = 0u; S.n2 = 0u; S.cut_k = 0ull; S.bd = -1; S.bp = -1; S.kmax = 0u; S.nunc = 0xFFFFFFFFu; }
+  __syncthreads();
+  unsigned n_sure = 0;
+  // history columns, from the owners' registers (the second pass masks them out)
+  if (H.active) {
+#pragma unroll
+    for (int j = 0; j < IDR; ++j) {
+      if ((own >> j) & 1u) {
+        const unsigned hot = use_hot ? ((hot_bits[ids[j] >> 5] >> (ids[j] & 31)) & 1u) : 0u;
+        n_sure += classify_col(zp[j], ids[j], hot, C, bstar, T, tiles, S, rl);
+      }
+    }
+  }
+  // the second pass: every other column, by its raw (= final) value
+  {
+    Raw A[UNR], Bf[UNR];
+    uint32_t hqA[UNR], hqB[UNR];
+#pragma unroll
+    for (int u = 0; u < UNR; ++u) {
+      A[u] = Io<DT>::load(rowp + (size_t)t0 * T + u * 64 * EPL + lane * EPL);
+      hqA[u] = use_hot ? hot_bits[(t0 * T + u * 64 * EPL + lane * EPL) >> 5] : 0u;
+    }
+    for (int cur = t0; cur < t1; ++cur) {
+      if (cur + 1 < t1) {
+#pragma unroll
+        for (int u = 0; u < UNR; ++u) {
+          Bf[u] = Io<DT>::load(rowp + (size_t)(cur + 1) * T + u * 64 * EPL + lane * EPL);
+          hqB[u] = use_hot ? hot_bits[((cur + 1) * T + u * 64 * EPL + lane * EPL) >> 5] : 0u;
+        }
+      }
+      u64 acc0 = 0ull, acc1 = 0ull;
+#pragma unroll
+      for (int u = 0; u < UNR; ++u) {
+        float z[EPL];
+        Io<DT>::unpack(A[u], z);
+        const int idx0 = cur * T + u * 64 * EPL + lane * EPL;
+        const uint32_t hnib = H.active ? ((H.bm[idx0 >> 5] >> ((unsigned)idx0 & 31u)) & EMASK) : 0u;
+        const uint32_t qnib = (hqA[u] >> ((unsigned)idx0 & 31u)) & EMASK;
+#pragma unroll
+        for (int e = 0; e < EPL; ++e) {
+          if (hnib & (1u << e)) continue;
+          int b;
+          const float w = mass_term(z[e], C, b);
+          if (!(z[e] < C.g) || b < bstar) {
+            const u64 m = mass_fix(w);
+            if (qnib & (1u << e)) acc1 += m; else acc0 += m;
+            ++n_sure;
+          } else if (b == bstar) {
+            const unsigned slot = atomicAdd(&S.memb, 1u);
+            if (slot < (unsigned)RCAP) rl[slot] = ((u64)__float_as_uint(z[e]) << 32) | (u64)(uint32_t)(idx0 + e);
+          }
+        }
+      }
+      const u64 s0 = wave_sum(acc0), s1 = wave_sum(acc1);
+      if (lane == 0) { atomicAdd(&tiles[cur], s0); atomicAdd(&tiles[256 + cur], s1); }
+#pragma unroll
+      for (int u = 0; u < UNR; ++u) { A[u] = Bf[u]; hqA[u] = hqB[u]; }
+    }
+  }
+  for (int idx = nfull * T + tid; idx < V; idx += NTHR) {
+    if (H.active && ((H.bm[idx >> 5] >> (idx & 31)) & 1u)) continue;
+    const unsigned hot = use_hot ? ((hot_bits[idx >> 5] >> (idx & 31)) & 1u) : 0u;
+    n_sure += classify_col(Io<DT>::one(rowp + idx), idx, hot, C, bstar, T, tiles, S, rl);
+  }
+  __syncthreads();  // the presence mask is dead from here
+  // -- the boundary bin, exactly: shortest prefix in the total order whose mass reaches the target --
+  const unsigned n_r = S.memb;
+  if (n_r > (unsigned)RCAP || n_r == 0u) return false;
+  for (int i = tid; i < NBF; i += NTHR) { fcnt[i] = 0u; fmass[i] = 0ull; }
+  for (unsigned t = tid; t < n_r; t += NTHR) {
+    const u64 e = rl[t];
+    const float z = __uint_as_float((uint32_t)(e >> 32));
+    int b;
+    const float w = mass_term(z, C, b);
+    const uint32_t key = fkey(z / R.tau);
+    rcmp[t] = composite(key, (uint32_t)e);
+    rl[t] = mass_fix(w);
+    atomicMax(&S.kmax, key);
+    atomicMin(&S.nunc, key);
+  }
+  __syncthreads();
+  const uint32_t kmx = S.kmax, kmn = S.nunc;
+  const int bshift = max(0, 32 - (int)__clz((kmx - kmn) | 1u) - 8);
+  for (unsigned t = tid; t < n_r; t += NTHR) {
+    const unsigned sb = (kmx - (uint32_t)(rcmp[t] >> 32)) >> bshift;
+    atomicAdd(&fcnt[sb], 1u);
+    atomicAdd(&fmass[sb], rl[t]);
+  }
+  __syncthreads();
+  {
+    const u64 m2 = (tid < NBF) ? fmass[tid] : 0ull;
+    unsigned ce2, ct2; u64 me2, mt2;
+    blk_excl_scan2<NWV>(S, 0u, m2, ce2, me2, ct2, mt2);
+    if (tid < NBF && m2 > 0ull && m_above + me2 < target && m_above + me2 + m2 >= target) { S.bp = tid; S.mab_p = m_above + me2; }
+  }
+  __syncthreads();
+  const int sbp = S.bp;
+  if (sbp < 0) return false;  // the masses of the two passes disagree: leave the row to the general kernel
+  for (unsigned t = tid; t < n_r; t += NTHR) {
+    if ((int)((kmx - (uint32_t)(rcmp[t] >> 32)) >> bshift) == sbp) {
+      const unsigned slot = atomicAdd(&S.n2, 1u);
+      if (slot < (unsigned)MEMB2) { mc[slot] = rcmp[t]; mw[slot] = rl[t]; }
+    }
+  }
+  __syncthreads();
+  const unsigned nm = S.n2;
+  if (nm > (unsigned)MEMB2) return false;
+  {
+    const u64 mab = S.mab_p;
+    for (unsigned mi = tid; mi < nm; mi += NTHR) {
+      const u64 cm = mc[mi], wm = mw[mi];
+      u64 G = mab;
+      for (unsigned q = 0; q < nm; ++q) G += (mc[q] >= cm) ? mw[q] : 0ull;
+      if (G >= target && G - wm < target) S.cut_k = cm;
+    }
+  }
+  __syncthreads();
+  const u64 cut_c = S.cut_k;
+  if (cut_c == 0ull) return false;
+  unsigned r_in = 0;
+  for (unsigned t = tid; t < n_r; t += NTHR) {
+    if (rcmp[t] >= cut_c) {
+      const uint32_t id = 0xFFFFFFFFu - (uint32_t)rcmp[t];
+      const unsigned hot = use_hot ? ((hot_bits[id >> 5] >> (id & 31)) & 1u) : 0u;
+      atomicAdd(&tiles[hot * 256u + id / (unsigned)T], rl[t]);
+      ++r_in;
+    }
+  }
+  unsigned ns = n_sure + r_in, dz = 0; u64 mx = 0ull, dsum = 0ull;
+  blk_reduce<NWV>(S, ns, dz, mx, dsum);  // barriers inside: the tile masses are complete after it
+  // -- masses of the classes, acceptance (section 5.3), the tile that holds the draw --
+  u64 p0 = 0ull, p1 = 0ull;
+  for (int i = tid; i < 256; i += NTHR) { p0 += tiles[i]; p1 += tiles[256 + i]; }
+  const u64 S0 = blk_sum_u64<NWV>(S, p0);
+  const u64 S1 = blk_sum_u64<NWV>(S, p1);
+  const u64 S_K = S0 + S1;
+  bool pick_hot = false;
+  if (use_hot) {
+    pick_hot = (S1 > 0ull) && (R.u_acc * (double)S_K <= (double)S1);
+    dg.alpha = (double)S1 / (double)S_K;
+    dg.flags |= SIMPLE_DIAG_SHVS | (pick_hot ? SIMPLE_DIAG_ACCEPTED : 0u);
+  }
+  const unsigned cls = pick_hot ? 1u : 0u;
+  const u64 S_cls = use_hot ? (pick_hot ? S1 : S0) : S_K;
+  const double u = use_hot ? (pick_hot ? R.u_draw : R.u_tail) : R.u_draw;
+  dg.n_survivors = (int)ns;
+  dg.s_k = (double)S_tot / (double)MSCALE * exp((double)C.y_g - (double)keyf(kmax));
+  if (S_cls == 0ull) return false;
+  u64 tfix = (u64)__double2ull_rd(u * (double)S_cls);
+  if (tfix >= S_cls) tfix = S_cls - 1ull;
+  {
+    u64 before = 0ull;
+    for (int i0 = 0; i0 < 256; i0 += NTHR) {  // one tile per thread and round
+      const int i = i0 + tid;
+      const u64 m2 = (i < 256) ? tiles[cls * 256u + (unsigned)i] : 0ull;
+      unsigned ce2, ct2; u64 me2, tot2;
+      blk_excl_scan2<NWV>(S, 0u, m2, ce2, me2, ct2, tot2);
+      me2 += before;
+      if (m2 > 0ull && me2 <= tfix && me2 + m2 > tfix) { S.bd = i; S.mab_d = me2; }
+      before += tot2;
+    }
+  }
+  __syncthreads();
+  const int tstar = S.bd;
+  if (tstar < 0) return false;
+  // -- the drawn id inside one tile: history columns come from their owners --
+  constexpr int EPT = T / NTHR;
+  float* patch = reinterpret_cast<float*>(lds + rl_off);  // T floats (the boundary tables are dead)
+  for (int i = tid; i < T; i += NTHR) patch[i] = __uint_as_float(0x7FC0DEADu);
+  __syncthreads();
+  if (H.active) {
+#pragma unroll
+    for (int j = 0; j < IDR; ++j)
+      if (((own >> j) & 1u) && ids[j] / T == tstar) patch[ids[j] - tstar * T] = zp[j];
+  }
+  __syncthreads();
+  u64 mloc[EPT]; u64 lsum = 0ull;
+#pragma unroll
+  for (int e = 0; e < EPT; ++e) {
+    const int idx = tstar * T + tid * EPT + e;
+    mloc[e] = 0ull;
+    if (idx < V) {
+      const float pv = patch[tid * EPT + e];
+      const float z = (__float_as_uint(pv) == 0x7FC0DEADu) ? Io<DT>::one(rowp + idx) : pv;
+      const unsigned hot = use_hot ? ((hot_bits[idx >> 5] >> (idx & 31)) & 1u) : 0u;
+      if (!use_hot || hot == cls) {
+        int b;
+        const float w = mass_term(z, C, b);
+        bool in = !(z < C.g) || b < bstar;
+        if (!in && b == bstar) in = composite(fkey(z / R.tau), (uint32_t)idx) >= cut_c;
+        if (in) mloc[e] = mass_fix(w);
+      }
+    }
+    lsum += mloc[e];
+  }
+  unsigned ce3, ct3; u64 me3, tot3;
+  blk_excl_scan2<NWV>(S, 0u, lsum, ce3, me3, ct3, tot3);
+  u64 run = S.mab_d + me3;
+#pragma unroll
+  for (int e = 0; e < EPT; ++e) {
+    if (mloc[e] > 0ull && run <= tfix && run + mloc[e] > tfix) { S.out_id = tstar * T + tid * EPT + e; S.out_w = mloc[e]; }
+    run += mloc[e];
+  }
+  __syncthreads();
+  dg.p_chosen = (float)((double)S.out_w / (double)S_K);
+  return S.out_id >= 0;
 }
 
 __device__ inline void queue_pending(const SampleArgs& a, int row) {
@@ -579,6 +1032,7 @@ __global__ __launch_bounds__(NTHR, 4) void fast_rows_kernel(const SampleArgs a) 
   constexpr int NWV = NTHR / 64;
   constexpr int EPL = Io<DT>::EPL;
   constexpr int T = 64 * EPL * UNR;
+  constexpr int PER = CAPF / NTHR;
   typedef typename Io<DT>::Raw Raw;
   extern __shared__ __align__(16) unsigned char lds[];
   __shared__ FS S;
@@ -586,13 +1040,17 @@ __global__ __launch_bounds__(NTHR, 4) void fast_rows_kernel(const SampleArgs a) 
   const int row = blockIdx.x;
   const int V = a.V;
   const DT* rowp = reinterpret_cast<const DT*>(a.logits) + (size_t)row * (size_t)a.stride;
+  // this wave's first two tiles (its threshold sample): issued before anything else
+  const int nfull = V / T;  // the host guarantees nfull >= 2 * NWV
+  const int t0 = (int)(((long long)wave * nfull) / NWV), t1 = (int)(((long long)(wave + 1) * nfull) / NWV);
+  Raw A[UNR], Bf[UNR];
+#pragma unroll
+  for (int u = 0; u < UNR; ++u) A[u] = Io<DT>::load(rowp + (size_t)t0 * T + u * 64 * EPL + lane * EPL);
+#pragma unroll
+  for (int u = 0; u < UNR; ++u) Bf[u] = Io<DT>::load(rowp + (size_t)(t0 + 1) * T + u * 64 * EPL + lane * EPL);
   const simple_row_params par = a.params[row];
-  uint32_t* bm = reinterpret_cast<uint32_t*>(lds + a.F.bitmap);
-  uint16_t* dir = reinterpret_cast<uint16_t*>(lds + a.F.dir);
-  uint32_t* cnt32 = reinterpret_cast<uint32_t*>(lds + a.F.cnt);
-  uint32_t* cz = reinterpret_cast<uint32_t*>(lds + a.F.cand);
-  uint32_t* ci = cz + CAPF;
-  unsigned char* scratch = lds + a.F.scratch;
+  FPHASE(0);
+  FPHASE_HW();
   uint32_t* samp = reinterpret_cast<uint32_t*>(lds + a.F.samp);
 
   // ---- row configuration (identical in every thread) ----
@@ -611,86 +1069,103 @@ __global__ __launch_bounds__(NTHR, 4) void fast_rows_kernel(const SampleArgs a) 
   if (a.hist_ptr) { h0 = a.hist_ptr[row]; const long long h1 = a.hist_ptr[row + 1]; nnz = (int)min(max(h1 - h0, 0ll), (long long)a.max_nnz + 1); }
   const bool too_long = nnz > a.max_nnz;
   const bool pen_on = par.rep_penalty != 1.0f || par.freq_penalty != 0.0f || par.pres_penalty != 0.0f;
+  const bool lowering = par.rep_penalty >= 1.0f && par.freq_penalty >= 0.0f && par.pres_penalty >= 0.0f;
+  const bool h_active = (nnz > 0) && pen_on;
   const bool no_trunc = !R.greedy && !R.k_on && !R.p_on && !R.minp_on;
-  const bool eligible = !bad_par && !too_long && !no_trunc && (R.greedy || !R.k_on || par.top_k <= KMAXF);
+  // the mass correction below needs every history id in the owners' registers
+  const bool sum_ok = !R.need_sum || !h_active || nnz <= IDR * NTHR;
+  const bool eligible = !bad_par && !too_long && !no_trunc && (!h_active || lowering) && sum_ok &&
+                        (R.greedy || !R.k_on || par.top_k <= KMAXF);
   if (!eligible) {  // the general kernel takes the row (it also reports parameter errors)
     if (tid == 0) queue_pending(a, row);
     return;
   }
   const int k_sel = R.greedy ? 1 : (R.k_on ? par.top_k : (R.p_le0 ? 1 : KMAXF));
-  {
-    double u[3];
-    row_uniforms(a.seed, a.row_offset + (uint64_t)row, a.step, u);
-    R.u_draw = u[0]; R.u_acc = u[1]; R.u_tail = u[2];
-  }
   if (tid == 0) {
     S.cand_count = 0u; S.flags = 0u; S.kmax = 0u; S.memb = 0u; S.bk = -1; S.bp = -1; S.bd = -1;
     S.need_k = 0u; S.cut_k = 0ull; S.cut_p = 0ull; S.n_p = 0u; S.out_id = -1; S.out_w = 0ull;
+    S.n2 = 0u; S.nunc = 0u; S.e_rc = FIN_PENDING; S.e_n = 0u;
   }
-  // ---- this wave's tiles; the first one is its sample ----
-  const int nfull = V / T;  // the host guarantees nfull >= 2 * NWV
-  const int t0 = (int)(((long long)wave * nfull) / NWV), t1 = (int)(((long long)(wave + 1) * nfull) / NWV);
-  Raw A[UNR], Bf[UNR];
-#pragma unroll
-  for (int u = 0; u < UNR; ++u) A[u] = Io<DT>::load(rowp + (size_t)t0 * T + u * 64 * EPL + lane * EPL);
-#pragma unroll
-  for (int u = 0; u < UNR; ++u) Bf[u] = Io<DT>::load(rowp + (size_t)(t0 + 1) * T + u * 64 * EPL + lane * EPL);
-  __syncthreads();
-
-  // ---- history state ----
+  // ---- loads first: history ids, then this wave's two sample tiles ----
+  const int32_t* hist = a.hist_ids + h0;
   Hist H;
-  H.bm = bm; H.dir = dir; H.cnt = reinterpret_cast<const uint16_t*>(cnt32);
+  H.bm = reinterpret_cast<uint32_t*>(lds + a.F.bitmap);
+  H.dir = reinterpret_cast<uint16_t*>(lds + a.F.dir);
+  H.cnt32 = reinterpret_cast<uint32_t*>(lds + a.F.cnt);
+  H.n_words = (V + 31) >> 5;
   H.rep = par.rep_penalty; H.freq = par.freq_penalty; H.pres = par.pres_penalty;
   H.inv_rep = 1.0 / (double)par.rep_penalty;
-  H.active = (nnz > 0) && pen_on;
-  if (H.active) build_history<NTHR>(S, bm, dir, cnt32, a.hist_ids + h0, nnz, par.n_prompt, V);
+  H.active = h_active;
+  {
+    int ids[IDR];
+#pragma unroll
+    for (int j = 0; j < IDR; ++j) { const int i = tid + j * NTHR; ids[j] = (h_active && i < nnz) ? hist[i] : -1; }
+    {
+      double u[3];
+      row_uniforms(a.seed, a.row_offset + (uint64_t)row, a.step, u);
+      R.u_draw = u[0]; R.u_acc = u[1]; R.u_tail = u[2];
+    }
+    __syncthreads();
+    // ---- presence mask of the history (in the shared region) ----
+    if (H.active) build_bitmap<NTHR>(S, H, ids, hist, nnz, V);
+  }
   const uint32_t* hot_bits = R.greedy ? nullptr : a.hot_bits;
+  FPHASE(1);
 
-  // ---- threshold from the sample: two largest penalised values per lane, wave select, merge ----
-  float z[UNR][EPL];
-  prep_tile<DT>(A, t0 * T, H, z);
-  float a1 = -INFINITY, a2 = -INFINITY;
+  // ---- threshold from the sample: three largest penalised values per lane, wave select, merge ----
+  float a1 = -INFINITY, a2 = -INFINITY, a3 = -INFINITY;  // branch-free insertion; a NaN is ignored here
+#define SIMPLE_TAKE3(v) do { const float v_ = (v); const float m1_ = fmaxf(a1, v_), l1_ = fminf(a1, v_); \
+    const float m2_ = fmaxf(a2, l1_), l2_ = fminf(a2, l1_); a3 = fmaxf(a3, l2_); a2 = m2_; a1 = m1_; } while (0)
 #pragma unroll
   for (int u = 0; u < UNR; ++u) {
+    float z[EPL];
+    sample_group<DT>(A[u], t0 * T + u * 64 * EPL + lane * EPL, H, z);
 #pragma unroll
-    for (int e = 0; e < EPL; ++e) {
-      const float v = z[u][e];
-      if (v > a1) { a2 = a1; a1 = v; } else if (v > a2) a2 = v;
-    }
+    for (int e = 0; e < EPL; ++e) SIMPLE_TAKE3(z[e]);
+    sample_group<DT>(Bf[u], (t0 + 1) * T + u * 64 * EPL + lane * EPL, H, z);
+#pragma unroll
+    for (int e = 0; e < EPL; ++e) SIMPLE_TAKE3(z[e]);
   }
+#undef SIMPLE_TAKE3
+  FPHASE(9);
   // rank in the sample whose value leaves, with high probability, >= k_sel columns above it in the row
-  const float m_exp = (float)k_sel * (float)(NWV * T) / (float)V;
-  const unsigned r_samp = (unsigned)ceilf(1.3f * m_exp + 3.0f * sqrtf(m_exp) + 3.0f);
+  const float m_exp = (float)k_sel * (float)(NWV * 2 * T) / (float)V;
+  const unsigned r_samp = (unsigned)ceilf(1.15f * m_exp + 3.2f * sqrtf(m_exp) + 3.5f);
   {
     const float r_w = (float)r_samp / (float)NWV;
-    const unsigned q = min((unsigned)SPW, (unsigned)ceilf(r_w + 3.0f * sqrtf(r_w) + 2.0f));
-    const uint32_t k2[2] = {fkey(a1), fkey(a2)};
-    const uint32_t Kw = wave_select_key<2>(k2, q);
+    const unsigned q = min((unsigned)(SPW * 3 / 4), (unsigned)ceilf(r_w + 3.0f * sqrtf(r_w) + 2.0f));
+    const uint32_t k3[3] = {fkey(a1), fkey(a2), fkey(a3)};
+    // every lane's largest is >= the smallest of the lanes' largest: at least 64 >= q keys qualify
+    const uint32_t Kw = wave_threshold<3>(k3, q, q / 4u + 1u, wave_min_u32(k3[0]), wave_max_u32(k3[0]));
     if (lane < SPW) samp[wave * SPW + lane] = 0u;
-    const u64 m1 = __ballot(k2[0] >= Kw);
-    const unsigned p1 = lanes_before(m1);
-    if (((m1 >> lane) & 1ull) && p1 < (unsigned)SPW) samp[wave * SPW + p1] = k2[0];
-    const unsigned n1 = min((unsigned)__popcll(m1), (unsigned)SPW);
-    const u64 m2 = __ballot(k2[1] >= Kw);
-    const unsigned p2 = n1 + lanes_before(m2);
-    if (((m2 >> lane) & 1ull) && p2 < (unsigned)SPW) samp[wave * SPW + p2] = k2[1];
-    const unsigned n2 = min(n1 + (unsigned)__popcll(m2), (unsigned)SPW);
+    unsigned have = 0;
+#pragma unroll
+    for (int j = 0; j < 3; ++j) {
+      const u64 m = __ballot(k3[j] >= Kw);
+      const unsigned p = have + lanes_before(m);
+      if (((m >> lane) & 1ull) && p < (unsigned)SPW) samp[wave * SPW + p] = k3[j];
+      have = min(have + (unsigned)__popcll(m), (unsigned)SPW);
+    }
     const float wp = wave_max(a1);
-    if (lane == 0) { S.wmax[wave] = wp; S.wcnt[wave] = n2; }
+    if (lane == 0) { S.wmax[wave] = wp; S.wcnt[wave] = have; }
   }
+  FPHASE(10);
   __syncthreads();
+  FPHASE(11);
   StreamCtx C;
   {
     constexpr int NS = (NWV * SPW) / 64;
-    uint32_t k4[NS];
+    uint32_t ks[NS];
     unsigned total = 0;
     float Mp = S.wmax[0];
 #pragma unroll
     for (int w = 0; w < NWV; ++w) { total += S.wcnt[w]; Mp = fmaxf(Mp, S.wmax[w]); }
+    uint32_t kmn = 0xFFFFFFFFu, kmx = 0u;
 #pragma unroll
-    for (int j = 0; j < NS; ++j) k4[j] = samp[j * 64 + lane];
-    const uint32_t Kg = wave_select_key<NS>(k4, max(1u, min(r_samp, total)));
-    float g = keyf(Kg);
+    for (int j = 0; j < NS; ++j) { ks[j] = samp[j * 64 + lane]; kmx = max(kmx, ks[j]); if (ks[j]) kmn = min(kmn, ks[j]); }
+    kmn = wave_min_u32(kmn); kmx = wave_max_u32(kmx);
+    const unsigned need = max(1u, min(r_samp, total));
+    float g = keyf(wave_threshold<NS>(ks, need, need / 8u + 1u, min(kmn, kmx), kmx));
     if (!R.greedy && !R.k_on && R.minp_on) {
       // min-p survivors lie within ln(min_p) of the row maximum, which is at least the sample's
       const float thr_lb = Mp / R.tau + (float)log((double)R.min_p);
@@ -698,17 +1173,25 @@ __global__ __launch_bounds__(NTHR, 4) void fast_rows_kernel(const SampleArgs a) 
       gm = gm - fabsf(gm) * 1e-6f - 1e-30f;
       g = fmaxf(g, gm);
     }
-    const double cd = 1.4426950408889634 / (double)R.tau;
-    float c_hi = (float)cd;
-    if ((double)c_hi > cd) c_hi = __uint_as_float(__float_as_uint(c_hi) - 1u);  // round down (cd > 0)
-    C.g = g; C.c_hi = c_hi; C.c_lo = (float)(cd - (double)c_hi);
+    C.g = g;
+    C.y_g = R.greedy ? g : g / R.tau;
+    C.inv_tau = 1.0 / (double)R.tau;
     C.need_sum = R.need_sum;
-    C.hist = nullptr;
+    C.hist = reinterpret_cast<u64*>(lds + a.F.hist);
+  }
+  // the history mask is dead from here (every wave passed the barrier above after its last lookup):
+  // the region becomes the candidate list
+  uint32_t* lz = reinterpret_cast<uint32_t*>(lds);
+  const unsigned cap = (unsigned)a.F.list_cap;
+  uint32_t* li = lz + cap;
+  if (R.need_sum) {
+    for (int i = tid; i < NBW; i += NTHR) C.hist[i] = 0ull;
+    __syncthreads();
   }
 
-  // ---- the stream ----
-  double acc = 0.0;
-  consume_tile<DT>(z, t0 * T, C, acc, S, cz, ci);
+  FPHASE(2);
+  // ---- the stream (raw logits) ----
+  stream_tile<DT>(A, t0 * T, C, S, lz, li, cap);
   for (int cur = t0 + 1; cur < t1; ++cur) {
 #pragma unroll
     for (int u = 0; u < UNR; ++u) A[u] = Bf[u];
@@ -716,26 +1199,24 @@ __global__ __launch_bounds__(NTHR, 4) void fast_rows_kernel(const SampleArgs a) 
 #pragma unroll
       for (int u = 0; u < UNR; ++u) Bf[u] = Io<DT>::load(rowp + (size_t)(cur + 1) * T + u * 64 * EPL + lane * EPL);
     }
-    prep_tile<DT>(A, cur * T, H, z);
-    consume_tile<DT>(z, cur * T, C, acc, S, cz, ci);
+    stream_tile<DT>(A, cur * T, C, S, lz, li, cap);
   }
+  FPHASE(3);
+  // the epilogue rebuilds the history tables: fetch the ids while the other waves finish
+  int ids[IDR];
+#pragma unroll
+  for (int j = 0; j < IDR; ++j) { const int i = tid + j * NTHR; ids[j] = (h_active && i < nnz) ? hist[i] : -1; }
   // ragged tail, element by element
   for (int idx = nfull * T + tid; idx < V; idx += NTHR) {
-    float zz = Io<DT>::one(rowp + idx);
-    if (H.active) {
-      const uint32_t word = bm[idx >> 5];
-      if ((word >> (idx & 31)) & 1u) {
-        const unsigned r = (unsigned)dir[idx >> 5] + (unsigned)__popc(word & ((1u << (idx & 31)) - 1u));
-        zz = H.apply(zz, (uint32_t)H.cnt[r]);
-      }
-    }
-    if (C.need_sum) acc += (double)below_term(zz, C, false);
+    const float zz = Io<DT>::one(rowp + idx);
+    if (C.need_sum && zz < C.g) { int b; const float w = mass_term(zz, C, b); atomicAdd(&C.hist[b], hist_entry(w)); }
     if (!(zz < C.g)) {
       const unsigned slot = atomicAdd(&S.cand_count, 1u);
-      if (slot < (unsigned)CAPF) { cz[slot] = __float_as_uint(zz); ci[slot] = (uint32_t)idx; }
+      if (slot < cap) { lz[slot] = __float_as_uint(zz); li[slot] = (uint32_t)idx; }
     }
   }
   __syncthreads();
+  FPHASE(4);
 
   // ---- epilogue ----
   simple_row_diag dg;
@@ -743,16 +1224,164 @@ __global__ __launch_bounds__(NTHR, 4) void fast_rows_kernel(const SampleArgs a) 
   dg.s_k = 0.0; dg.p_chosen = 0.0f; dg.n_survivors = 0; dg.flags = 0u; dg.reserved = 0u;
   if (a.hot_bits && a.hot_flags && *a.hot_flags) dg.flags |= SIMPLE_DIAG_BAD_HOT_SET;
   int rc = FIN_PENDING;
-  if (S.cand_count <= (unsigned)CAPF) {
-    const double S_below = R.need_sum ? blk_sum_f64<NWV>(S, acc) : 0.0;
-    rc = finalize_list<NTHR>(S, R, cz, ci, scratch, C.g, S_below, hot_bits, dg);
+  const unsigned n = S.cand_count;
+  if (n <= cap) {
+    // the list moves to registers; the region takes the history tables again
+    float ez[PER]; uint32_t eid[PER];
+#pragma unroll
+    for (int j = 0; j < PER; ++j) {
+      const unsigned i = (unsigned)tid + (unsigned)j * NTHR;
+      ez[j] = (i < n) ? __uint_as_float(lz[i]) : -INFINITY;
+      eid[j] = (i < n) ? li[i] : 0u;
+    }
+    float zp[IDR];  // penalised values of the history columns this thread owns (whole-vocabulary nucleus rows)
+    unsigned own = 0u;
+    __syncthreads();
+    FPHASE(12);
+    if (H.active) {
+      build_history<NTHR>(S, H, ids, hist, nnz, par.n_prompt, V, own);
+#pragma unroll
+      for (int j = 0; j < PER; ++j) {
+        const unsigned i = (unsigned)tid + (unsigned)j * NTHR;
+        if (i < n) ez[j] = H.penalised_at(ez[j], (int)eid[j]);
+      }
+      if (R.need_sum) {
+        // exact correction of the binned mass for the history columns (the stream binned their raw
+        // values); each distinct column is handled by the thread that first marked it
+        float zr[IDR];
+#pragma unroll
+        for (int j = 0; j < IDR; ++j) zr[j] = ((own >> j) & 1u) ? Io<DT>::one(rowp + ids[j]) : 0.0f;
+#pragma unroll
+        for (int j = 0; j < IDR; ++j) {
+          zp[j] = 0.0f;
+          if ((own >> j) & 1u) {
+            zp[j] = H.penalised_at(zr[j], ids[j]);
+            // columns at or above g are in the list: their terms are settled there
+            if (zr[j] < C.g) {
+              int b;
+              float w = mass_term(zr[j], C, b);
+              atomicAdd(&C.hist[b], 0ull - hist_entry(w));
+              w = mass_term(zp[j], C, b);
+              atomicAdd(&C.hist[b], hist_entry(w));
+            }
+          }
+        }
+      }
+      // the count tables are dead after this barrier; the presence mask stays for a second pass
+      __syncthreads();
+    }
+    FPHASE(13);
+    // keys of the tempered values; listed columns that fell below g return to the binned mass
+    uint32_t key[PER];
+    bool err = false, peaked = false;
+    uint32_t kloc = 0u;
+    u64 mlist = 0ull, mcert = 0ull;  // mass (relative to the one at y_g) of the listed / certified columns
+    const uint32_t key_g = fkey(C.y_g);
+#pragma unroll
+    for (int j = 0; j < PER; ++j) {
+      const unsigned i = (unsigned)tid + (unsigned)j * NTHR;
+      key[j] = 0u;
+      if (i < n) {
+        const float z = ez[j];
+        if (z != z || z == INFINITY) err = true;
+        else if (!(z < C.g)) {
+          const float y = R.greedy ? z : z / R.tau;
+          if (y == INFINITY) err = true;
+          else {
+            key[j] = fkey(y);
+            if (R.need_sum) {
+              int b;
+              const float w = mass_term(z, C, b);
+              if (w > 2097152.0f) peaked = true;  // 2^21: far too peaked for a wide nucleus
+              mlist += mass_fix(w);
+              if (key[j] > key_g) mcert += mass_fix(w);
+            }
+          }
+        } else if (R.need_sum) { int b; const float w = mass_term(z, C, b); atomicAdd(&C.hist[b], hist_entry(w)); }
+      }
+      kloc = max(kloc, key[j]);
+    }
+    if (kloc) atomicMax(&S.kmax, kloc);
+    if (err) atomicOr(&S.flags, SIMPLE_DIAG_ERROR | SIMPLE_DIAG_BAD_LOGIT);
+    if (peaked) atomicOr(&S.flags, 1u << 30);
+    __syncthreads();
+    // mass below g (integer, exact) and the decision between the list and the second pass
+    u64 S_below_int = 0ull, M_list = 0ull, M_cert = 0ull;
+    bool wide = false;
+    if (R.need_sum) {
+      u64 hb = 0ull;
+      for (int i = tid; i < NBW; i += NTHR) hb += C.hist[i] & ((1ull << 46) - 1ull);
+      unsigned d0 = 0, d1 = 0; u64 mx = 0ull;
+      blk_reduce<NWV>(S, d0, d1, mx, hb);
+      S_below_int = hb;
+      M_list = blk_sum_u64<NWV>(S, mlist);
+      M_cert = blk_sum_u64<NWV>(S, mcert);
+      const u64 target = (u64)__double2ull_ru((double)R.top_p * (double)(M_list + S_below_int));
+      wide = !R.minp_on && M_cert < target;
+    }
+    const double S_below = (double)S_below_int / (double)MSCALE;
+    const uint32_t kmax = S.kmax;
+    if (S.flags & SIMPLE_DIAG_ERROR) rc = FIN_DONE;
+    else if (kmax <= key_g || kmax <= KEY_NEG_INF) rc = FIN_PENDING;
+    else if (wide) {
+      rc = ((S.flags >> 30) & 1u) ? FIN_PENDING : FIN_WIDE;
+    } else {
+      // certified entries (tempered value strictly above fl(g / tau)) as composites
+      u64* mc = reinterpret_cast<u64*>(lds);                       // MEMB * 8
+      u64* sc = mc + MEMB;
+      u64* sw = sc + MEMB;
+      uint32_t* sid = reinterpret_cast<uint32_t*>(sw + MEMB);      // ends at 14 KB
+      unsigned nul = 0;
+#pragma unroll
+      for (int j = 0; j < PER; ++j) {
+        if (!key[j]) continue;
+        if (key[j] > key_g) {
+          const unsigned slot = atomicAdd(&S.n2, 1u);
+          if (slot < (unsigned)MEMB) mc[slot] = composite(key[j], eid[j]);
+        } else { ++nul; key[j] = 0u; }
+      }
+      if (nul) atomicAdd(&S.nunc, nul);
+      __syncthreads();
+      const unsigned n_cert = S.n2, n_unc = S.nunc;
+      if (R.k_on && !R.greedy && n_cert < (unsigned)R.top_k) rc = FIN_PENDING;  // the sampled threshold admitted too few
+      else if (n_cert <= (unsigned)MEMB) {
+        rc = finalize_small<NTHR>(S, R, n_cert, n_unc, kmax, key_g, C.g, S_below, mc, sc, sw, sid, hot_bits, dg);
+      } else if (n_cert <= (unsigned)a.F.long_cap) {
+        // long list: keys and ids go back to the region, the bucket tables behind them
+        const unsigned lcap = (unsigned)a.F.long_cap;
+        uint32_t* lk = reinterpret_cast<uint32_t*>(lds);
+        uint32_t* lid = lk + lcap;
+        __syncthreads();
+        if (tid == 0) S.n2 = 0u;
+        __syncthreads();
+#pragma unroll
+        for (int j = 0; j < PER; ++j) {
+          if (key[j]) { const unsigned slot = atomicAdd(&S.n2, 1u); lk[slot] = key[j]; lid[slot] = eid[j]; }
+        }
+        __syncthreads();
+        rc = finalize_long<NTHR>(S, R, n_cert, n_unc, kmax, key_g, C.g, S_below, lk, lid, lds + (size_t)lcap * 8u, hot_bits, dg);
+      }
+      if (rc == FIN_WIDE) rc = FIN_PENDING;  // the tables above overwrote the presence mask
+    }
+
+    // ---- whole-vocabulary nucleus wider than the list: second pass over the row ----
+    if (rc == FIN_WIDE) {
+      dg.flags |= SIMPLE_DIAG_WIDE;
+      // copies: only these escape to the out-of-line function, the originals stay in registers
+      int ids_w[IDR]; float zp_w[IDR];
+#pragma unroll
+      for (int j = 0; j < IDR; ++j) { ids_w[j] = ids[j]; zp_w[j] = zp[j]; }
+      rc = wide_route<DT, NTHR>(S, R, C, H, a.F, lds, rowp, V, t0, t1, ids_w, own, zp_w, M_list, S_below_int, kmax, hot_bits, dg)
+               ? FIN_DONE : FIN_PENDING;
+    }
   }
-  if (rc == FIN_WIDE) rc = FIN_PENDING;
+  FPHASE(5);
+  FPHASE(6);
   if (tid == 0) {
     if (rc != FIN_DONE) {
       queue_pending(a, row);
     } else {
-      const unsigned f = S.flags;
+      const unsigned f = S.flags & 0x3FFFFFFFu;
       const bool err = (f & SIMPLE_DIAG_ERROR) != 0u;
       a.out[row] = err ? -1 : S.out_id;
       if (a.diag) {
@@ -766,25 +1395,35 @@ __global__ __launch_bounds__(NTHR, 4) void fast_rows_kernel(const SampleArgs a) 
 
 }  // namespace fast
 
+}  // namespace simple
+#ifdef SIMPLE_PHASE_TIMES
+extern "C" int simple_debug_fast_phase_times(unsigned long long* dst_host, int n_rows) {
+  return (int)hipMemcpyFromSymbol(dst_host, HIP_SYMBOL(simple::fast::g_fast_phase_times), sizeof(unsigned long long) * 16 * (size_t)n_rows);
+}
+#endif
+namespace simple {
+
 hipError_t launch_fast(const SampleArgs& a, int dtype, hipStream_t st) {
   const dim3 grid((unsigned)a.B);
-  if (a.F.threads == 512) {
+  if (a.F.threads == 256) {
+    if (dtype == SIMPLE_F32) hipLaunchKernelGGL((fast::fast_rows_kernel<float, 256>), grid, dim3(256), a.F.total, st, a);
+    else hipLaunchKernelGGL((fast::fast_rows_kernel<uint16_t, 256>), grid, dim3(256), a.F.total, st, a);
+  } else {
     if (dtype == SIMPLE_F32) hipLaunchKernelGGL((fast::fast_rows_kernel<float, 512>), grid, dim3(512), a.F.total, st, a);
     else hipLaunchKernelGGL((fast::fast_rows_kernel<uint16_t, 512>), grid, dim3(512), a.F.total, st, a);
-  } else {
-    if (dtype == SIMPLE_F32) hipLaunchKernelGGL((fast::fast_rows_kernel<float, 1024>), grid, dim3(1024), a.F.total, st, a);
-    else hipLaunchKernelGGL((fast::fast_rows_kernel<uint16_t, 1024>), grid, dim3(1024), a.F.total, st, a);
   }
   return hipGetLastError();
 }
 
 hipError_t set_max_lds_fast(unsigned bytes) {
-  hipError_t e;
-  e = hipFuncSetAttribute(reinterpret_cast<const void*>(fast::fast_rows_kernel<float, 512>), hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes); if (e != hipSuccess) return e;
-  e = hipFuncSetAttribute(reinterpret_cast<const void*>(fast::fast_rows_kernel<uint16_t, 512>), hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes); if (e != hipSuccess) return e;
-  e = hipFuncSetAttribute(reinterpret_cast<const void*>(fast::fast_rows_kernel<float, 1024>), hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes); if (e != hipSuccess) return e;
-  e = hipFuncSetAttribute(reinterpret_cast<const void*>(fast::fast_rows_kernel<uint16_t, 1024>), hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
-  return e;
+  const void* fns[4] = {
+    reinterpret_cast<const void*>(fast::fast_rows_kernel<float, 256>), reinterpret_cast<const void*>(fast::fast_rows_kernel<uint16_t, 256>),
+    reinterpret_cast<const void*>(fast::fast_rows_kernel<float, 512>), reinterpret_cast<const void*>(fast::fast_rows_kernel<uint16_t, 512>)};
+  for (int i = 0; i < 4; ++i) {
+    const hipError_t e = hipFuncSetAttribute(fns[i], hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
+    if (e != hipSuccess) return e;
+  }
+  return hipSuccess;
 }
 
 }  // namespace simple

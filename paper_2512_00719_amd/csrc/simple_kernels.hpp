@@ -18,17 +18,19 @@ struct LdsLayout {
   uint32_t total;
 };
 
-// Byte offsets of one row's LDS regions in the single-pass kernel's workgroup.
+// LDS of the single-pass kernel's workgroup.  One region is shared in time: it holds the history
+// tables while the threshold is sampled and again in the epilogue, and the candidate list (later the
+// epilogue's tables) in between.
 struct FastLayout {
-  uint32_t bitmap;   // history presence mask, one bit per column (0 bytes without history)
-  uint32_t dir;      // 16-bit count of set bits before each mask word
-  uint32_t cnt;      // 16-bit generated-token counts, indexed by the rank of the id among the set bits
-  uint32_t cand;     // candidate list: CAPF value words then CAPF ids
-  uint32_t scratch;  // 16 KB: mass histogram of the stream, then the bucket tables of the epilogue
-  uint32_t tiles;    // per-tile masses of the two-pass nucleus route
-  uint32_t samp;     // threshold sample merge area
-  uint32_t total;
-  int threads;       // workgroup size the layout was made for (512 or 1024)
+  uint32_t bitmap;    // history presence mask, one bit per column (region offset 0)
+  uint32_t dir;       // 16-bit count of set bits before each pair of mask words
+  uint32_t cnt;       // 16-bit generated-token counts, indexed by the rank of the id among the set bits
+  uint32_t list_cap;  // entries of the candidate list (value word + id word each) the region holds
+  uint32_t long_cap;  // entries of a long certified list that fit beside its bucket tables
+  uint32_t hist;      // 8 KB behind the region: mass histogram of the stream, later per-tile masses
+  uint32_t samp;      // threshold sample merge area
+  uint32_t total;     // 0: the call cannot use the kernel
+  int threads;        // workgroup size the layout was made for (256 or 512)
 };
 
 constexpr int CAPF = 3072;    // candidate-list capacity of the single-pass kernel
