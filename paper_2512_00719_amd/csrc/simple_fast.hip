@@ -63,24 +63,35 @@ constexpr float MSCALE = 268435456.0f;  // 2^28: fixed-point scale of masses rel
 constexpr int RCAP = 1024;              // columns of the boundary bin that can be resolved exactly
 constexpr float L2E_HI = 1.44269502162933349609375f, L2E_LO = 1.925963033500011e-8f;  // log2(e), split
 
+// Global-memory view of a pointer.  Inside out-of-line device functions the compiler cannot tell that
+// a pointer parameter is global; generic (flat) loads would also count against the LDS wait counter and
+// so serialise the tile prefetch behind every LDS access.
+template <typename T>
+__device__ __forceinline__ const __attribute__((address_space(1))) T* as_global(const T* p) {
+  return (const __attribute__((address_space(1))) T*)p;
+}
+__device__ __forceinline__ unsigned hot_bit(const uint32_t* __restrict__ hot_bits, uint32_t id) {
+  return (as_global(hot_bits)[id >> 5] >> (id & 31u)) & 1u;
+}
+
 template <typename DT> struct Io;
 template <> struct Io<float> {
   static constexpr int EPL = 4;
   typedef f32x4 Raw;
-  __device__ static __forceinline__ Raw load(const float* p) { return __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(p)); }
+  __device__ static __forceinline__ Raw load(const float* p) { return __builtin_nontemporal_load(as_global(reinterpret_cast<const f32x4*>(p))); }
   __device__ static __forceinline__ void unpack(const Raw& r, float (&z)[4]) { z[0] = r.x; z[1] = r.y; z[2] = r.z; z[3] = r.w; }
-  __device__ static __forceinline__ float one(const float* p) { return *p; }
+  __device__ static __forceinline__ float one(const float* p) { return *as_global(p); }
 };
 template <> struct Io<uint16_t> {  // bfloat16 bit patterns; the upcast to float32 is exact
   static constexpr int EPL = 8;
   typedef u32x4 Raw;
-  __device__ static __forceinline__ Raw load(const uint16_t* p) { return __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(p)); }
+  __device__ static __forceinline__ Raw load(const uint16_t* p) { return __builtin_nontemporal_load(as_global(reinterpret_cast<const u32x4*>(p))); }
   __device__ static __forceinline__ void unpack(const Raw& r, float (&z)[8]) {
     const uint32_t w[4] = {r.x, r.y, r.z, r.w};
 #pragma unroll
     for (int i = 0; i < 4; ++i) { z[2 * i] = __uint_as_float(w[i] << 16); z[2 * i + 1] = __uint_as_float(w[i] & 0xFFFF0000u); }
   }
-  __device__ static __forceinline__ float one(const uint16_t* p) { return __uint_as_float((uint32_t)(*p) << 16); }
+  __device__ static __forceinline__ float one(const uint16_t* p) { return __uint_as_float((uint32_t)(*as_global(p)) << 16); }
 };
 
 __device__ __forceinline__ u64 composite(uint32_t key, uint32_t id) { return ((u64)key << 32) | (u64)(0xFFFFFFFFu - id); }
@@ -499,7 +510,7 @@ __device__ __forceinline__ int finalize_small(FS& S, const RowCfg& R, unsigned n
         o = (o || r == 0u) && (r < n);
         if (o) {
           okm |= 1u << j; ++cl; ml += wl[j];
-          if (use_hot && ((hot_bits[il[j] >> 5] >> (il[j] & 31)) & 1u)) { hotm |= 1u << j; hl += wl[j]; }
+          if (use_hot && hot_bit(hot_bits, il[j])) { hotm |= 1u << j; hl += wl[j]; }
         }
       }
       const unsigned ns = wave_sum(cl);
@@ -676,7 +687,7 @@ __device__ __forceinline__ int finalize_long(FS& S, const RowCfg& R, unsigned n,
     if (composite(k, li[i]) >= cut) {
       const u64 w = wfix(k, y_max);
       ++ns; sk += w;
-      if (use_hot && ((hot_bits[li[i] >> 5] >> (li[i] & 31)) & 1u)) { ++nh; sh += w; }
+      if (use_hot && hot_bit(hot_bits, li[i])) { ++nh; sh += w; }
     }
   }
   blk_reduce<NWV>(S, ns, nh, cdum, sk);
@@ -703,7 +714,7 @@ __device__ __forceinline__ int finalize_long(FS& S, const RowCfg& R, unsigned n,
   auto in_class = [&](uint32_t k, uint32_t id) {
     if (composite(k, id) < cut) return false;
     if (!use_hot) return true;
-    return (((hot_bits[id >> 5] >> (id & 31)) & 1u) != 0u) == pick_hot;
+    return (hot_bit(hot_bits, id) != 0u) == pick_hot;
   };
   for (unsigned i = tid; i < n; i += NTHR) if (in_class(lk[i], li[i])) atomicAdd(&fmass[li[i] >> ishift], wfix(lk[i], y_max));
   __syncthreads();
@@ -762,11 +773,24 @@ __device__ __forceinline__ unsigned classify_col(float z, int idx, unsigned hot,
 // class in ascending id and reads one tile a third time.  All masses are integers, so nothing
 // depends on summation order.  Returns false when a table overflows: the general kernel takes the row.
 template <typename DT, int NTHR>
-__device__ __noinline__ bool wide_route(FS& S, const RowCfg& R, const StreamCtx& C, const Hist& H, const FastLayout& F,
+__device__ __forceinline__ bool wide_route(FS& S, const RowCfg& R_in, const StreamCtx& C_in, const Hist& H_in, const FastLayout& F,
                                         unsigned char* lds, const DT* __restrict__ rowp, int V, int t0, int t1,
-                                        const int (&ids)[IDR], unsigned own, const float (&zp)[IDR], u64 M_list,
+                                        const int (&ids_in)[IDR], unsigned own, const float (&zp_in)[IDR], u64 M_list,
                                         u64 S_below_int, uint32_t kmax, const uint32_t* __restrict__ hot_bits,
                                         simple_row_diag& dg) {
+  // local copies: values behind the references would be re-read after every LDS or global store;
+  // LDS pointers are re-derived from the dynamic LDS symbol so that they are known to be LDS here
+  const RowCfg R = R_in;
+  StreamCtx C = C_in;
+  Hist H = H_in;
+  const uint32_t f_dir = F.dir;
+  C.hist = reinterpret_cast<u64*>(lds + F.hist);
+  H.bm = reinterpret_cast<uint32_t*>(lds + F.bitmap);
+  H.dir = reinterpret_cast<uint16_t*>(lds + F.dir);
+  H.cnt32 = reinterpret_cast<uint32_t*>(lds + F.cnt);
+  int ids[IDR]; float zp[IDR];
+#pragma unroll
+  for (int j = 0; j < IDR; ++j) { ids[j] = ids_in[j]; zp[j] = zp_in[j]; }
   constexpr int NWV = NTHR / 64;
   constexpr int EPL = Io<DT>::EPL;
   constexpr int T = 64 * EPL * UNR;
@@ -778,7 +802,7 @@ __device__ __noinline__ bool wide_route(FS& S, const RowCfg& R, const StreamCtx&
   u64* tiles = C.hist;  // [2][256] per-tile masses of the survivors (tail / hot), once the bins are consumed
   // region map: [0, rl_off) presence mask during the pass, then composites (8 KB), sub-bin tables (3 KB),
   // member tables (4 KB); [rl_off, rl_off + 8 KB) boundary columns, later their masses, later the tile patch
-  const uint32_t rl_off = (H.active && F.dir > 16384u) ? F.dir : 16384u;  // behind the mask (F.dir is where it ends)
+  const uint32_t rl_off = (H.active && f_dir > 16384u) ? f_dir : 16384u;  // behind the mask (F.dir is where it ends)
   u64* rl = reinterpret_cast<u64*>(lds + rl_off);
   u64* rcmp = reinterpret_cast<u64*>(lds);
   uint32_t* fcnt = reinterpret_cast<uint32_t*>(lds + 8192);
@@ -810,6 +834,7 @@ __device__ __noinline__ bool wide_route(FS& S, const RowCfg& R, const StreamCtx&
   __syncthreads();
   const int bstar = S.bk;
   const u64 m_above = S.mab_k;
+  FPHASE(7);
   if (bstar < 0 || S.need_k > (unsigned)RCAP || nfull + 1 > 256) return false;
   for (int i = tid; i < 512; i += NTHR) tiles[i] = 0ull;
   if (tid == 0) { S.memb = 0u; S.n2 = 0u; S.cut_k = 0ull; S.bd = -1; S.bp = -1; S.kmax = 0u; S.nunc = 0xFFFFFFFFu; }
@@ -820,7 +845,7 @@ __device__ __noinline__ bool wide_route(FS& S, const RowCfg& R, const StreamCtx&
 #pragma unroll
     for (int j = 0; j < IDR; ++j) {
       if ((own >> j) & 1u) {
-        const unsigned hot = use_hot ? ((hot_bits[ids[j] >> 5] >> (ids[j] & 31)) & 1u) : 0u;
+        const unsigned hot = use_hot ? hot_bit(hot_bits, (uint32_t)ids[j]) : 0u;
         n_sure += classify_col(zp[j], ids[j], hot, C, bstar, T, tiles, S, rl);
       }
     }
@@ -832,14 +857,14 @@ __device__ __noinline__ bool wide_route(FS& S, const RowCfg& R, const StreamCtx&
 #pragma unroll
     for (int u = 0; u < UNR; ++u) {
       A[u] = Io<DT>::load(rowp + (size_t)t0 * T + u * 64 * EPL + lane * EPL);
-      hqA[u] = use_hot ? hot_bits[(t0 * T + u * 64 * EPL + lane * EPL) >> 5] : 0u;
+      hqA[u] = use_hot ? as_global(hot_bits)[(t0 * T + u * 64 * EPL + lane * EPL) >> 5] : 0u;
     }
     for (int cur = t0; cur < t1; ++cur) {
       if (cur + 1 < t1) {
 #pragma unroll
         for (int u = 0; u < UNR; ++u) {
           Bf[u] = Io<DT>::load(rowp + (size_t)(cur + 1) * T + u * 64 * EPL + lane * EPL);
-          hqB[u] = use_hot ? hot_bits[((cur + 1) * T + u * 64 * EPL + lane * EPL) >> 5] : 0u;
+          hqB[u] = use_hot ? as_global(hot_bits)[((cur + 1) * T + u * 64 * EPL + lane * EPL) >> 5] : 0u;
         }
       }
       u64 acc0 = 0ull, acc1 = 0ull;
@@ -873,10 +898,11 @@ __device__ __noinline__ bool wide_route(FS& S, const RowCfg& R, const StreamCtx&
   }
   for (int idx = nfull * T + tid; idx < V; idx += NTHR) {
     if (H.active && ((H.bm[idx >> 5] >> (idx & 31)) & 1u)) continue;
-    const unsigned hot = use_hot ? ((hot_bits[idx >> 5] >> (idx & 31)) & 1u) : 0u;
+    const unsigned hot = use_hot ? hot_bit(hot_bits, (uint32_t)idx) : 0u;
     n_sure += classify_col(Io<DT>::one(rowp + idx), idx, hot, C, bstar, T, tiles, S, rl);
   }
   __syncthreads();  // the presence mask is dead from here
+  FPHASE(8);
   // -- the boundary bin, exactly: shortest prefix in the total order whose mass reaches the target --
   const unsigned n_r = S.memb;
   if (n_r > (unsigned)RCAP || n_r == 0u) return false;
@@ -930,12 +956,13 @@ __device__ __noinline__ bool wide_route(FS& S, const RowCfg& R, const StreamCtx&
   }
   __syncthreads();
   const u64 cut_c = S.cut_k;
+  FPHASE(9);
   if (cut_c == 0ull) return false;
   unsigned r_in = 0;
   for (unsigned t = tid; t < n_r; t += NTHR) {
     if (rcmp[t] >= cut_c) {
       const uint32_t id = 0xFFFFFFFFu - (uint32_t)rcmp[t];
-      const unsigned hot = use_hot ? ((hot_bits[id >> 5] >> (id & 31)) & 1u) : 0u;
+      const unsigned hot = use_hot ? hot_bit(hot_bits, id) : 0u;
       atomicAdd(&tiles[hot * 256u + id / (unsigned)T], rl[t]);
       ++r_in;
     }
@@ -976,6 +1003,7 @@ __device__ __noinline__ bool wide_route(FS& S, const RowCfg& R, const StreamCtx&
   }
   __syncthreads();
   const int tstar = S.bd;
+  FPHASE(10);
   if (tstar < 0) return false;
   // -- the drawn id inside one tile: history columns come from their owners --
   constexpr int EPT = T / NTHR;
@@ -996,7 +1024,7 @@ __device__ __noinline__ bool wide_route(FS& S, const RowCfg& R, const StreamCtx&
     if (idx < V) {
       const float pv = patch[tid * EPT + e];
       const float z = (__float_as_uint(pv) == 0x7FC0DEADu) ? Io<DT>::one(rowp + idx) : pv;
-      const unsigned hot = use_hot ? ((hot_bits[idx >> 5] >> (idx & 31)) & 1u) : 0u;
+      const unsigned hot = use_hot ? hot_bit(hot_bits, (uint32_t)idx) : 0u;
       if (!use_hot || hot == cls) {
         int b;
         const float w = mass_term(z, C, b);
@@ -1367,6 +1395,7 @@ __global__ __launch_bounds__(NTHR, 4) void fast_rows_kernel(const SampleArgs a) 
     // ---- whole-vocabulary nucleus wider than the list: second pass over the row ----
     if (rc == FIN_WIDE) {
       dg.flags |= SIMPLE_DIAG_WIDE;
+      FPHASE(11);
       // copies: only these escape to the out-of-line function, the originals stay in registers
       int ids_w[IDR]; float zp_w[IDR];
 #pragma unroll
