@@ -152,6 +152,19 @@ int simple_sample(simple_ctx* ctx, const void* logits_dev, int64_t B, int64_t V,
                   uint64_t row_offset, int32_t* out_ids_dev, simple_row_diag* diag_dev,
                   void* hip_stream);
 
+/*
+ * Timing aid for benchmarks (not part of the method): while enabled, every simple_sample call
+ * brackets the launch of its dominant kernel (the single-pass row kernel when the call can use
+ * it, else the general row kernel) with two HIP events on the call's stream.
+ * simple_profile_enable(ctx, 1) creates the events (up to 1024 launches are kept, later ones are
+ * not recorded) and resets the record; simple_profile_enable(ctx, 0) destroys them.
+ * simple_profile_read synchronises with the recorded events and returns the number of recorded
+ * launches; *total_ms_host (host pointer) receives the sum of their durations in milliseconds.
+ * Returns a negative error code on failure.
+ */
+int simple_profile_enable(simple_ctx* ctx, int on);
+int simple_profile_read(simple_ctx* ctx, double* total_ms_host);
+
 /* Bytes of LDS one row's workgroup uses for the given context (for occupancy reasoning). */
 int64_t simple_lds_bytes(const simple_ctx* ctx);
 

@@ -11,8 +11,9 @@ path and must never be used to produce results for a caller.
 Every function cites the passage of the paper it follows.  Where the paper is
 silent the convention chosen is stated in the function's docstring.
 
-Pins (tests marked "not gpu"): Philox against the published known-answer
-vectors of its authors; penalties against hand-computed rows; top-k against
+Pins (tests marked "not gpu"): Philox against an independent library
+implementation (the counter-based engine in PyTorch's ATen headers) and the
+closed forms of its round constants; penalties against hand-computed rows; top-k against
 pairwise order properties; softmax-on-subset against a library masked
 softmax; the draw by exhaustive enumeration of all 2^24 uniforms; SHVS by
 enumeration of the accept/draw grid and chi-square tests against the

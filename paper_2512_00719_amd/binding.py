@@ -30,6 +30,7 @@ ROW_DIAG_DTYPE = np.dtype([("alpha", "<f8"), ("s_k", "<f8"), ("p_chosen", "<f4")
 assert ROW_DIAG_DTYPE.itemsize == 32
 
 EXPORTS = ("simple_create", "simple_destroy", "simple_set_hot_set", "simple_sample",
+           "simple_profile_enable", "simple_profile_read",
            "simple_lds_bytes", "simple_strerror", "simple_version")
 
 
@@ -47,6 +48,10 @@ def _load() -> ctypes.CDLL:
     lib.simple_sample.argtypes = [vp, vp, i64, i64, ctypes.c_int, i64, vp, vp, vp, vp, i32, u64, u64, u64,
                                   vp, vp, vp]
     lib.simple_sample.restype = ctypes.c_int
+    lib.simple_profile_enable.argtypes = [vp, ctypes.c_int]
+    lib.simple_profile_enable.restype = ctypes.c_int
+    lib.simple_profile_read.argtypes = [vp, ctypes.POINTER(ctypes.c_double)]
+    lib.simple_profile_read.restype = ctypes.c_int
     lib.simple_lds_bytes.argtypes = [vp]
     lib.simple_lds_bytes.restype = i64
     lib.simple_strerror.argtypes = [ctypes.c_int]
@@ -88,6 +93,19 @@ def simple_destroy(ctx: Optional[int]) -> None:
 
 def simple_lds_bytes(ctx: int) -> int:
     return int(_lib.simple_lds_bytes(ctypes.c_void_p(ctx)))
+
+
+def simple_profile_enable(ctx: int, on: bool) -> int:
+    return int(_lib.simple_profile_enable(ctypes.c_void_p(ctx), 1 if on else 0))
+
+
+def simple_profile_read(ctx: int) -> tuple[int, float]:
+    """Returns (recorded launches, sum of their durations in ms) of the dominant kernel."""
+    total = ctypes.c_double(0.0)
+    n = int(_lib.simple_profile_read(ctypes.c_void_p(ctx), ctypes.byref(total)))
+    if n < 0:
+        raise SimpleError(n, "simple_profile_read")
+    return n, float(total.value)
 
 
 def simple_set_hot_set(ctx: int, hot_ids_ptr: int, H: int, V: int, stream: int = 0) -> int:

@@ -19,7 +19,10 @@ struct simple_ctx {
   int32_t hot_H;
   int lds_limit;
   uint32_t* pend;       // device: queue of rows the single-pass kernel leaves to the general kernel
+  hipEvent_t* prof_ev;  // 2 * PROF_MAX events while profiling is enabled, else null
+  int prof_n;           // launches recorded so far
 };
+constexpr int PROF_MAX = 1024;
 
 namespace simple {
 
@@ -114,6 +117,7 @@ int simple_create(simple_ctx** out, int device, int64_t max_V, int64_t max_nnz_p
   if (!c) return SIMPLE_ENOMEM;
   c->device = device; c->max_V = max_V; c->max_nnz = max_nnz_per_row; c->lds_limit = lds;
   c->hot_V = 0; c->hot_H = 0; c->hot_bits = nullptr; c->hot_flags = nullptr; c->pend = nullptr;
+  c->prof_ev = nullptr; c->prof_n = 0;
   const size_t words = (size_t)((max_V + 31) / 32) + 1;
   const size_t total_words = words + 1 + 2 + (size_t)simple::PEND_ROWS;
   if (hipMalloc(reinterpret_cast<void**>(&c->hot_bits), total_words * sizeof(uint32_t)) != hipSuccess) {
@@ -137,10 +141,47 @@ void simple_destroy(simple_ctx* ctx) {
     simple::DeviceGuard guard(ctx->device);
     if (guard.ok) {
       (void)hipDeviceSynchronize();
+      if (ctx->prof_ev) (void)simple_profile_enable(ctx, 0);
       if (ctx->hot_bits) (void)hipFree(ctx->hot_bits);
     }
   }
   delete ctx;
+}
+
+int simple_profile_enable(simple_ctx* ctx, int on) {
+  if (!ctx) return SIMPLE_EINVAL;
+  simple::DeviceGuard guard(ctx->device);
+  if (!guard.ok) return SIMPLE_EDEVICE;
+  if (ctx->prof_ev) {
+    for (int i = 0; i < 2 * PROF_MAX; ++i) if (ctx->prof_ev[i]) (void)hipEventDestroy(ctx->prof_ev[i]);
+    delete[] ctx->prof_ev;
+    ctx->prof_ev = nullptr;
+  }
+  ctx->prof_n = 0;
+  if (!on) return SIMPLE_OK;
+  ctx->prof_ev = new (std::nothrow) hipEvent_t[2 * PROF_MAX]();
+  if (!ctx->prof_ev) return SIMPLE_ENOMEM;
+  for (int i = 0; i < 2 * PROF_MAX; ++i) {
+    if (hipEventCreate(&ctx->prof_ev[i]) != hipSuccess) { (void)simple_profile_enable(ctx, 0); return SIMPLE_EDEVICE; }
+  }
+  return SIMPLE_OK;
+}
+
+int simple_profile_read(simple_ctx* ctx, double* total_ms_host) {
+  if (!ctx || !total_ms_host) return SIMPLE_EINVAL;
+  *total_ms_host = 0.0;
+  if (!ctx->prof_ev) return 0;
+  simple::DeviceGuard guard(ctx->device);
+  if (!guard.ok) return SIMPLE_EDEVICE;
+  double total = 0.0;
+  for (int i = 0; i < ctx->prof_n; ++i) {
+    if (hipEventSynchronize(ctx->prof_ev[2 * i + 1]) != hipSuccess) return SIMPLE_EDEVICE;
+    float ms = 0.0f;
+    if (hipEventElapsedTime(&ms, ctx->prof_ev[2 * i], ctx->prof_ev[2 * i + 1]) != hipSuccess) return SIMPLE_EDEVICE;
+    total += (double)ms;
+  }
+  *total_ms_host = total;
+  return ctx->prof_n;
 }
 
 int64_t simple_lds_bytes(const simple_ctx* ctx) {
@@ -211,7 +252,9 @@ int simple_sample(simple_ctx* ctx, const void* logits_dev, int64_t B, int64_t V,
     a.row_offset = row_offset + (uint64_t)b0;
     a.out = out_ids_dev + b0;
     a.diag = diag_dev ? diag_dev + b0 : nullptr;
-    if (simple::launch_sample(a, dtype, vec, st) != hipSuccess) return SIMPLE_EDEVICE;
+    hipEvent_t ev0 = nullptr, ev1 = nullptr;
+    if (ctx->prof_ev && ctx->prof_n < PROF_MAX) { ev0 = ctx->prof_ev[2 * ctx->prof_n]; ev1 = ctx->prof_ev[2 * ctx->prof_n + 1]; ++ctx->prof_n; }
+    if (simple::launch_sample(a, dtype, vec, st, ev0, ev1) != hipSuccess) return SIMPLE_EDEVICE;
   }
   return SIMPLE_OK;
 }

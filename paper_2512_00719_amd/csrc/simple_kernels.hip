@@ -1250,15 +1250,21 @@ static hipError_t launch_pending(const SampleArgs& a, hipStream_t st) {
   return hipGetLastError();
 }
 
-hipError_t launch_sample(const SampleArgs& a, int dtype, bool vec, hipStream_t st) {
+// ev0 / ev1 (may be null): recorded right before and after the dominant kernel of the call.
+hipError_t launch_sample(const SampleArgs& a, int dtype, bool vec, hipStream_t st, hipEvent_t ev0, hipEvent_t ev1) {
+  if (ev0 && hipEventRecord(ev0, st) != hipSuccess) return hipErrorUnknown;
   if (a.gated) {  // single-pass kernel first; the general kernel then completes the rows it queued
     const hipError_t e = launch_fast(a, dtype, st);
     if (e != hipSuccess) return e;
+    if (ev1 && hipEventRecord(ev1, st) != hipSuccess) return hipErrorUnknown;
     if (dtype == SIMPLE_F32) return vec ? launch_pending<float, true>(a, st) : launch_pending<float, false>(a, st);
     return vec ? launch_pending<uint16_t, true>(a, st) : launch_pending<uint16_t, false>(a, st);
   }
-  if (dtype == SIMPLE_F32) return vec ? launch_one<float, true>(a, st) : launch_one<float, false>(a, st);
-  return vec ? launch_one<uint16_t, true>(a, st) : launch_one<uint16_t, false>(a, st);
+  hipError_t e;
+  if (dtype == SIMPLE_F32) e = vec ? launch_one<float, true>(a, st) : launch_one<float, false>(a, st);
+  else e = vec ? launch_one<uint16_t, true>(a, st) : launch_one<uint16_t, false>(a, st);
+  if (e == hipSuccess && ev1 && hipEventRecord(ev1, st) != hipSuccess) return hipErrorUnknown;
+  return e;
 }
 
 hipError_t set_max_lds(unsigned bytes) {

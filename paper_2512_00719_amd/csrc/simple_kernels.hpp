@@ -60,7 +60,7 @@ struct SampleArgs {
 LdsLayout make_layout(int64_t V, int64_t max_nnz, bool with_history);
 // Layout of the single-pass kernel; total = 0 when the call cannot use it.
 FastLayout make_fast_layout(int64_t V, int dtype, int64_t max_nnz, bool with_history, bool vec, int lds_limit);
-hipError_t launch_sample(const SampleArgs& a, int dtype, bool vec, hipStream_t st);
+hipError_t launch_sample(const SampleArgs& a, int dtype, bool vec, hipStream_t st, hipEvent_t ev0, hipEvent_t ev1);
 hipError_t launch_fast(const SampleArgs& a, int dtype, hipStream_t st);
 hipError_t set_max_lds(unsigned bytes);
 hipError_t set_max_lds_fast(unsigned bytes);

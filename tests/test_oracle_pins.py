@@ -20,15 +20,32 @@ def _par(**kw):
 
 
 # ------------------------------------------------------------------ Philox ----------------------
-def test_philox_known_answer_vectors(golden_dir):
-    """Philox4x32-10 against the known-answer vectors published with its reference implementation."""
-    rows = [l.split() for l in open(os.path.join(golden_dir, "philox4x32_10_kat.txt"))
-            if l.strip() and not l.startswith("#")]
-    assert len(rows) == 3
-    for r in rows:
-        w = [int(x, 16) for x in r]
-        got = O.philox4x32_10(np.array(w[0:4], np.uint32), np.array(w[4:6], np.uint32))
-        assert [int(x) for x in got] == w[6:10]
+def test_philox_against_library_engine(tmp_path):
+    """Philox4x32-10 against an independent library routine: the counter-based engine in PyTorch's
+    ATen headers (at::philox_engine), compiled here with g++ and run on the CPU.  A wrong round
+    constant, multiplier, word order or round count in the oracle fails this."""
+    import shutil
+    import subprocess
+    import torch
+    inc = os.path.join(os.path.dirname(torch.__file__), "include")
+    gxx = shutil.which("g++")
+    if gxx is None or not os.path.exists(os.path.join(inc, "ATen", "core", "PhiloxRNGEngine.h")):
+        pytest.skip("g++ or the ATen Philox header is not available")
+    exe = str(tmp_path / "philox_library_check")
+    src = os.path.join(os.path.dirname(os.path.abspath(__file__)), "philox_library_check.cpp")
+    subprocess.run([gxx, "-O1", "-std=c++17", "-I", inc, src, "-o", exe], check=True)
+    rng = np.random.default_rng(11)
+    cases = [(0, 0, 0), (2 ** 64 - 1, 2 ** 64 - 1, 2 ** 64 - 1), (synth.SAMPLER_SEED, 5 << 32, 123)]
+    cases += [tuple(int(x) for x in rng.integers(0, 2 ** 63, 3)) for _ in range(200)]
+    args = [str(v) for c in cases for v in c]
+    out = subprocess.run([exe, *args], check=True, capture_output=True, text=True).stdout.split("\n")
+    for (seed, subseq, offset), line in zip(cases, out):
+        ctr = np.array([offset & 0xFFFFFFFF, offset >> 32, subseq & 0xFFFFFFFF, subseq >> 32], np.uint32)
+        key = np.array([seed & 0xFFFFFFFF, seed >> 32], np.uint32)
+        got = [int(x) for x in O.philox4x32_10(ctr, key)]
+        assert got == [int(x, 16) for x in line.split()], (seed, subseq, offset)
+    # the round constants have closed forms: the golden ratio and sqrt(3) - 1 in 32-bit fixed point
+    assert O._PHILOX_W0 == int(((5 ** 0.5 - 1) / 2) * 2 ** 32) and O._PHILOX_W1 == int((3 ** 0.5 - 1) * 2 ** 32)
 
 
 def test_philox_vectorised_matches_scalar_and_is_uniform():
