@@ -41,9 +41,11 @@ namespace fast {
 __device__ unsigned long long g_fast_phase_times[8192 * 16];
 #define FPHASE(i) do { if (threadIdx.x == 0 && blockIdx.x < 8192) g_fast_phase_times[blockIdx.x * 16 + (i)] = wall_clock64(); } while (0)
 #define FPHASE_HW() do { if (threadIdx.x == 0 && blockIdx.x < 8192) { g_fast_phase_times[blockIdx.x * 16 + 15] = __builtin_amdgcn_s_getreg(63492); g_fast_phase_times[blockIdx.x * 16 + 14] = __builtin_amdgcn_s_getreg(63508); } } while (0)
+#define FWHY(code) do { if (threadIdx.x == 0 && blockIdx.x < 8192) g_fast_phase_times[blockIdx.x * 16 + 13] = (code); } while (0)
 #else
 #define FPHASE_HW() do { } while (0)
 #define FPHASE(i) do { } while (0)
+#define FWHY(code) do { } while (0)
 #endif
 
 typedef float f32x4 __attribute__((ext_vector_type(4)));
@@ -358,7 +360,9 @@ __device__ __forceinline__ float mass_term(float z, const StreamCtx& C, int& bin
   return __builtin_amdgcn_exp2f(t);
 }
 __device__ __forceinline__ u64 mass_fix(float w) { return (u64)(w * MSCALE + 0.5f); }
-__device__ __forceinline__ u64 hist_entry(float w) { return (1ull << 46) | mass_fix(w); }
+// same integer for w <= 1 (every column below g), one conversion instruction
+__device__ __forceinline__ u64 mass_fix_below(float w) { return (u64)(uint32_t)(w * MSCALE + 0.5f); }
+__device__ __forceinline__ u64 hist_entry(float w) { return (1ull << 46) | mass_fix_below(w); }
 
 // Unpacks one 16-byte group of a sample tile; columns that are in the history are masked out, so
 // the threshold comes from unpenalised columns only (history columns can only add to the prefix).
@@ -407,10 +411,11 @@ __device__ __forceinline__ void stream_tile(const typename Io<DT>::Raw (&A)[UNR]
     const int idx0 = tb + u * 64 * EPL + lane * EPL;
     if (C.need_sum) {
 #pragma unroll
-      for (int e = 0; e < EPL; ++e) {
+      for (int e = 0; e < EPL; ++e) {  // straight-line: a column at or above g adds zero
         int b;
         const float w = mass_term(z[e], C, b);
-        if (z[e] < C.g) atomicAdd(&C.hist[b], hist_entry(w));
+        const bool below = z[e] < C.g && z[e] > -INFINITY;
+        atomicAdd(&C.hist[b], below ? hist_entry(w) : 0ull);
       }
     }
     bool any = false;
@@ -571,8 +576,9 @@ __device__ __forceinline__ int finalize_long(FS& S, const RowCfg& R, unsigned n,
   u64* mc = reinterpret_cast<u64*>(tables + NBF * 12);               // MEMB2 * 8
   u64* mw = reinterpret_cast<u64*>(tables + NBF * 12 + MEMB2 * 8);   // MEMB2 * 8
   const float y_max = keyf(kmax);
-  const unsigned span = kmax - key_g;
-  const int bshift = max(0, 32 - (int)__clz(span) - 8);
+  // buckets are linear in the tempered value (key space is logarithmic around zero); monotone in the key
+  const float bscale = (float)NBF / fmaxf(y_max - keyf(key_g), 1e-30f);
+  auto bucket_of = [&](uint32_t k) { return (unsigned)min((int)((y_max - keyf(k)) * bscale), NBF - 1); };
   u64 cl = 0ull;
   for (unsigned i = tid; i < n; i += NTHR) { const u64 c = composite(lk[i], li[i]); cl = (c > cl) ? c : cl; }
   unsigned da = 0, db = 0; u64 cmax = cl, dd = 0ull;
@@ -581,7 +587,7 @@ __device__ __forceinline__ int finalize_long(FS& S, const RowCfg& R, unsigned n,
   __syncthreads();
   for (unsigned i = tid; i < n; i += NTHR) {
     const uint32_t k = lk[i];
-    const unsigned b = (kmax - k) >> bshift;
+    const unsigned b = bucket_of(k);
     atomicAdd(&fcnt[b], 1u);
     atomicAdd(&fmass[b], wfix(k, y_max));
   }
@@ -601,14 +607,14 @@ __device__ __forceinline__ int finalize_long(FS& S, const RowCfg& R, unsigned n,
     bk = S.bk;
     for (unsigned i = tid; i < n; i += NTHR) {
       const uint32_t k = lk[i];
-      if ((int)((kmax - k) >> bshift) == bk) {
+      if ((int)bucket_of(k) == bk) {
         const unsigned slot = atomicAdd(&S.memb, 1u);
         if (slot < (unsigned)MEMB2) { mc[slot] = composite(k, li[i]); mw[slot] = wfix(k, y_max); }
       }
     }
     __syncthreads();
     const unsigned nm = S.memb;
-    if (nm > (unsigned)MEMB2) return FIN_PENDING;  // ties wider than the member table
+    if (nm > (unsigned)MEMB2) { FWHY(201); return FIN_PENDING; }  // ties wider than the member table
     const unsigned need = S.need_k;
     for (unsigned mi = tid; mi < nm; mi += NTHR) {
       const u64 cm = mc[mi];
@@ -642,14 +648,14 @@ __device__ __forceinline__ int finalize_long(FS& S, const RowCfg& R, unsigned n,
     if (bp >= 0) {
       for (unsigned i = tid; i < n; i += NTHR) {
         const uint32_t k = lk[i];
-        if ((int)((kmax - k) >> bshift) == bp && composite(k, li[i]) >= cut_k) {
+        if ((int)bucket_of(k) == bp && composite(k, li[i]) >= cut_k) {
           const unsigned slot = atomicAdd(&S.memb, 1u);
           if (slot < (unsigned)MEMB2) { mc[slot] = composite(k, li[i]); mw[slot] = wfix(k, y_max); }
         }
       }
       __syncthreads();
       const unsigned nm = S.memb;
-      if (nm > (unsigned)MEMB2) return FIN_PENDING;
+      if (nm > (unsigned)MEMB2) { FWHY(202); return FIN_PENDING; }
       const u64 mab = S.mab_p;
       for (unsigned mi = tid; mi < nm; mi += NTHR) {
         const u64 cm = mc[mi], wm = mw[mi];
@@ -674,7 +680,7 @@ __device__ __forceinline__ int finalize_long(FS& S, const RowCfg& R, unsigned n,
   }
   const bool known = R.k_on || p_found || m_cert;
   if (!known) return (R.need_sum && !R.minp_on) ? FIN_WIDE : FIN_PENDING;
-  if (R.k_on && R.p_on && !p_found) return FIN_PENDING;  // cannot happen: the top-k prefix holds its own mass
+  if (R.k_on && R.p_on && !p_found) { FWHY(203); return FIN_PENDING; }  // cannot happen: the top-k prefix holds its own mass
   u64 cut = cut_k;
   if (p_found && cut_p > cut) cut = cut_p;
   if (m_cert && cut_m > cut) cut = cut_m;
@@ -704,7 +710,7 @@ __device__ __forceinline__ int finalize_long(FS& S, const RowCfg& R, unsigned n,
   const double u = use_hot ? (pick_hot ? R.u_draw : R.u_tail) : R.u_draw;
   dg.n_survivors = (int)ns;
   dg.s_k = (double)S_k_fix / WSCALE;
-  if (S_cls == 0ull) return FIN_PENDING;  // the chosen class holds no mass here: general kernel
+  if (S_cls == 0ull) { FWHY(204); return FIN_PENDING; }  // the chosen class holds no mass here: general kernel
   // ---- inverse CDF in ascending token id: first id whose running mass exceeds u * S ----
   u64 tfix = (u64)__double2ull_rd(u * (double)S_cls);
   if (tfix >= S_cls) tfix = S_cls - 1ull;
@@ -726,7 +732,7 @@ __device__ __forceinline__ int finalize_long(FS& S, const RowCfg& R, unsigned n,
   }
   __syncthreads();
   const int bd = S.bd;
-  if (bd < 0) return FIN_PENDING;  // cannot happen: tfix < S_cls
+  if (bd < 0) { FWHY(205); return FIN_PENDING; }  // cannot happen: tfix < S_cls
   for (unsigned i = tid; i < n; i += NTHR) {
     if (in_class(lk[i], li[i]) && (int)(li[i] >> ishift) == bd) {
       const unsigned slot = atomicAdd(&S.memb, 1u);
@@ -736,7 +742,7 @@ __device__ __forceinline__ int finalize_long(FS& S, const RowCfg& R, unsigned n,
   __syncthreads();
   {
     const unsigned nm = S.memb;
-    if (nm > (unsigned)MEMB2) return FIN_PENDING;
+    if (nm > (unsigned)MEMB2) { FWHY(206); return FIN_PENDING; }
     const u64 mab = S.mab_d;
     for (unsigned mi = tid; mi < nm; mi += NTHR) {
       const u64 im = mc[mi], wm = mw[mi];
@@ -835,7 +841,7 @@ __device__ __forceinline__ bool wide_route(FS& S, const RowCfg& R_in, const Stre
   const int bstar = S.bk;
   const u64 m_above = S.mab_k;
   FPHASE(7);
-  if (bstar < 0 || S.need_k > (unsigned)RCAP || nfull + 1 > 256) return false;
+  if (bstar < 0 || S.need_k > (unsigned)RCAP || nfull + 1 > 256) { FWHY(101); return false; }
   for (int i = tid; i < 512; i += NTHR) tiles[i] = 0ull;
   if (tid == 0) { S.memb = 0u; S.n2 = 0u; S.cut_k = 0ull; S.bd = -1; S.bp = -1; S.kmax = 0u; S.nunc = 0xFFFFFFFFu; }
   __syncthreads();
@@ -875,18 +881,42 @@ __device__ __forceinline__ bool wide_route(FS& S, const RowCfg& R_in, const Stre
         const int idx0 = cur * T + u * 64 * EPL + lane * EPL;
         const uint32_t hnib = H.active ? ((H.bm[idx0 >> 5] >> ((unsigned)idx0 & 31u)) & EMASK) : 0u;
         const uint32_t qnib = (hqA[u] >> ((unsigned)idx0 & 31u)) & EMASK;
+        // straight-line per column (one wave per SIMD late in the kernel: branches would expose their latency)
+        bool any_top = false, any_edge = false;
 #pragma unroll
         for (int e = 0; e < EPL; ++e) {
-          if (hnib & (1u << e)) continue;
           int b;
           const float w = mass_term(z[e], C, b);
-          if (!(z[e] < C.g) || b < bstar) {
-            const u64 m = mass_fix(w);
-            if (qnib & (1u << e)) acc1 += m; else acc0 += m;
-            ++n_sure;
-          } else if (b == bstar) {
-            const unsigned slot = atomicAdd(&S.memb, 1u);
-            if (slot < (unsigned)RCAP) rl[slot] = ((u64)__float_as_uint(z[e]) << 32) | (u64)(uint32_t)(idx0 + e);
+          const bool live = !(hnib & (1u << e));
+          const bool below = z[e] < C.g;
+          const bool sure = live && (!below || b < bstar);
+          const u64 m = (sure && below) ? mass_fix_below(w) : 0ull;
+          const bool hot = (qnib & (1u << e)) != 0u;
+          acc0 += hot ? 0ull : m;
+          acc1 += hot ? m : 0ull;
+          n_sure += sure ? 1u : 0u;
+          any_top = any_top || (live && !below);
+          any_edge = any_edge || (live && below && b == bstar);
+        }
+        if (__ballot(any_top)) {  // columns at or above g: few, their masses need the 64-bit conversion
+#pragma unroll
+          for (int e = 0; e < EPL; ++e) {
+            if (!(hnib & (1u << e)) && !(z[e] < C.g)) {
+              int b;
+              const u64 m = mass_fix(mass_term(z[e], C, b));
+              if (qnib & (1u << e)) acc1 += m; else acc0 += m;
+            }
+          }
+        }
+        if (__ballot(any_edge)) {  // columns of the boundary bin
+#pragma unroll
+          for (int e = 0; e < EPL; ++e) {
+            int b;
+            (void)mass_term(z[e], C, b);
+            if (!(hnib & (1u << e)) && z[e] < C.g && b == bstar) {
+              const unsigned slot = atomicAdd(&S.memb, 1u);
+              if (slot < (unsigned)RCAP) rl[slot] = ((u64)__float_as_uint(z[e]) << 32) | (u64)(uint32_t)(idx0 + e);
+            }
           }
         }
       }
@@ -905,7 +935,7 @@ __device__ __forceinline__ bool wide_route(FS& S, const RowCfg& R_in, const Stre
   FPHASE(8);
   // -- the boundary bin, exactly: shortest prefix in the total order whose mass reaches the target --
   const unsigned n_r = S.memb;
-  if (n_r > (unsigned)RCAP || n_r == 0u) return false;
+  if (n_r > (unsigned)RCAP || n_r == 0u) { FWHY(102); return false; }
   for (int i = tid; i < NBF; i += NTHR) { fcnt[i] = 0u; fmass[i] = 0ull; }
   for (unsigned t = tid; t < n_r; t += NTHR) {
     const u64 e = rl[t];
@@ -920,9 +950,11 @@ __device__ __forceinline__ bool wide_route(FS& S, const RowCfg& R_in, const Stre
   }
   __syncthreads();
   const uint32_t kmx = S.kmax, kmn = S.nunc;
-  const int bshift = max(0, 32 - (int)__clz((kmx - kmn) | 1u) - 8);
+  const float y_hi = keyf(kmx);
+  const float sscale = (float)NBF / fmaxf(y_hi - keyf(kmn), 1e-30f);
+  auto sub_bin = [&](u64 c) { return (unsigned)min((int)((y_hi - keyf((uint32_t)(c >> 32))) * sscale), NBF - 1); };
   for (unsigned t = tid; t < n_r; t += NTHR) {
-    const unsigned sb = (kmx - (uint32_t)(rcmp[t] >> 32)) >> bshift;
+    const unsigned sb = sub_bin(rcmp[t]);
     atomicAdd(&fcnt[sb], 1u);
     atomicAdd(&fmass[sb], rl[t]);
   }
@@ -935,16 +967,16 @@ __device__ __forceinline__ bool wide_route(FS& S, const RowCfg& R_in, const Stre
   }
   __syncthreads();
   const int sbp = S.bp;
-  if (sbp < 0) return false;  // the masses of the two passes disagree: leave the row to the general kernel
+  if (sbp < 0) { FWHY(103); return false; }  // the masses of the two passes disagree: leave the row to the general kernel
   for (unsigned t = tid; t < n_r; t += NTHR) {
-    if ((int)((kmx - (uint32_t)(rcmp[t] >> 32)) >> bshift) == sbp) {
+    if ((int)sub_bin(rcmp[t]) == sbp) {
       const unsigned slot = atomicAdd(&S.n2, 1u);
       if (slot < (unsigned)MEMB2) { mc[slot] = rcmp[t]; mw[slot] = rl[t]; }
     }
   }
   __syncthreads();
   const unsigned nm = S.n2;
-  if (nm > (unsigned)MEMB2) return false;
+  if (nm > (unsigned)MEMB2) { FWHY(104); return false; }
   {
     const u64 mab = S.mab_p;
     for (unsigned mi = tid; mi < nm; mi += NTHR) {
@@ -957,7 +989,7 @@ __device__ __forceinline__ bool wide_route(FS& S, const RowCfg& R_in, const Stre
   __syncthreads();
   const u64 cut_c = S.cut_k;
   FPHASE(9);
-  if (cut_c == 0ull) return false;
+  if (cut_c == 0ull) { FWHY(105); return false; }
   unsigned r_in = 0;
   for (unsigned t = tid; t < n_r; t += NTHR) {
     if (rcmp[t] >= cut_c) {
@@ -986,7 +1018,7 @@ __device__ __forceinline__ bool wide_route(FS& S, const RowCfg& R_in, const Stre
   const double u = use_hot ? (pick_hot ? R.u_draw : R.u_tail) : R.u_draw;
   dg.n_survivors = (int)ns;
   dg.s_k = (double)S_tot / (double)MSCALE * exp((double)C.y_g - (double)keyf(kmax));
-  if (S_cls == 0ull) return false;
+  if (S_cls == 0ull) { FWHY(106); return false; }
   u64 tfix = (u64)__double2ull_rd(u * (double)S_cls);
   if (tfix >= S_cls) tfix = S_cls - 1ull;
   {
@@ -1004,7 +1036,7 @@ __device__ __forceinline__ bool wide_route(FS& S, const RowCfg& R_in, const Stre
   __syncthreads();
   const int tstar = S.bd;
   FPHASE(10);
-  if (tstar < 0) return false;
+  if (tstar < 0) { FWHY(107); return false; }
   // -- the drawn id inside one tile: history columns come from their owners --
   constexpr int EPT = T / NTHR;
   float* patch = reinterpret_cast<float*>(lds + rl_off);  // T floats (the boundary tables are dead)
@@ -1105,6 +1137,7 @@ __global__ __launch_bounds__(NTHR, 4) void fast_rows_kernel(const SampleArgs a) 
   const bool eligible = !bad_par && !too_long && !no_trunc && (!h_active || lowering) && sum_ok &&
                         (R.greedy || !R.k_on || par.top_k <= KMAXF);
   if (!eligible) {  // the general kernel takes the row (it also reports parameter errors)
+    FWHY(1);
     if (tid == 0) queue_pending(a, row);
     return;
   }
@@ -1253,7 +1286,9 @@ __global__ __launch_bounds__(NTHR, 4) void fast_rows_kernel(const SampleArgs a) 
   if (a.hot_bits && a.hot_flags && *a.hot_flags) dg.flags |= SIMPLE_DIAG_BAD_HOT_SET;
   int rc = FIN_PENDING;
   const unsigned n = S.cand_count;
+  FWHY(2);
   if (n <= cap) {
+    FWHY(0);
     // the list moves to registers; the region takes the history tables again
     float ez[PER]; uint32_t eid[PER];
 #pragma unroll
@@ -1298,7 +1333,6 @@ __global__ __launch_bounds__(NTHR, 4) void fast_rows_kernel(const SampleArgs a) 
       // the count tables are dead after this barrier; the presence mask stays for a second pass
       __syncthreads();
     }
-    FPHASE(13);
     // keys of the tempered values; listed columns that fell below g return to the binned mass
     uint32_t key[PER];
     bool err = false, peaked = false;
@@ -1350,9 +1384,10 @@ __global__ __launch_bounds__(NTHR, 4) void fast_rows_kernel(const SampleArgs a) 
     const double S_below = (double)S_below_int / (double)MSCALE;
     const uint32_t kmax = S.kmax;
     if (S.flags & SIMPLE_DIAG_ERROR) rc = FIN_DONE;
-    else if (kmax <= key_g || kmax <= KEY_NEG_INF) rc = FIN_PENDING;
+    else if (kmax <= key_g || kmax <= KEY_NEG_INF) { rc = FIN_PENDING; FWHY(3); }
     else if (wide) {
       rc = ((S.flags >> 30) & 1u) ? FIN_PENDING : FIN_WIDE;
+      if (rc == FIN_PENDING) FWHY(4);
     } else {
       // certified entries (tempered value strictly above fl(g / tau)) as composites
       u64* mc = reinterpret_cast<u64*>(lds);                       // MEMB * 8
@@ -1371,9 +1406,10 @@ __global__ __launch_bounds__(NTHR, 4) void fast_rows_kernel(const SampleArgs a) 
       if (nul) atomicAdd(&S.nunc, nul);
       __syncthreads();
       const unsigned n_cert = S.n2, n_unc = S.nunc;
-      if (R.k_on && !R.greedy && n_cert < (unsigned)R.top_k) rc = FIN_PENDING;  // the sampled threshold admitted too few
+      if (R.k_on && !R.greedy && n_cert < (unsigned)R.top_k) { rc = FIN_PENDING; FWHY(5); }  // the sampled threshold admitted too few
       else if (n_cert <= (unsigned)MEMB) {
         rc = finalize_small<NTHR>(S, R, n_cert, n_unc, kmax, key_g, C.g, S_below, mc, sc, sw, sid, hot_bits, dg);
+        if (rc != FIN_DONE) FWHY(7);
       } else if (n_cert <= (unsigned)a.F.long_cap) {
         // long list: keys and ids go back to the region, the bucket tables behind them
         const unsigned lcap = (unsigned)a.F.long_cap;
@@ -1389,6 +1425,7 @@ __global__ __launch_bounds__(NTHR, 4) void fast_rows_kernel(const SampleArgs a) 
         __syncthreads();
         rc = finalize_long<NTHR>(S, R, n_cert, n_unc, kmax, key_g, C.g, S_below, lk, lid, lds + (size_t)lcap * 8u, hot_bits, dg);
       }
+      else FWHY(6);
       if (rc == FIN_WIDE) rc = FIN_PENDING;  // the tables above overwrote the presence mask
     }
 
