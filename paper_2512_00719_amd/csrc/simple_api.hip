@@ -19,6 +19,10 @@ struct simple_ctx {
   int32_t hot_H;
   int lds_limit;
   uint32_t* pend;       // device: queue of rows the single-pass kernel leaves to the general kernel
+  uint32_t* wq;         // device: queue of rows for the whole-vocabulary-nucleus kernels
+  unsigned char* wws;   // device: their workspace, WIDE_SLOTS slots
+  uint32_t ws_stride;   // bytes per slot
+  int parity;           // which queue counters the next launch uses
   hipEvent_t* prof_ev;  // 2 * PROF_MAX events while profiling is enabled, else null
   int prof_n;           // launches recorded so far
 };
@@ -116,7 +120,7 @@ int simple_create(simple_ctx** out, int device, int64_t max_V, int64_t max_nnz_p
   simple_ctx* c = new (std::nothrow) simple_ctx();
   if (!c) return SIMPLE_ENOMEM;
   c->device = device; c->max_V = max_V; c->max_nnz = max_nnz_per_row; c->lds_limit = lds;
-  c->hot_V = 0; c->hot_H = 0; c->hot_bits = nullptr; c->hot_flags = nullptr; c->pend = nullptr;
+  c->hot_V = 0; c->hot_H = 0; c->hot_bits = nullptr; c->hot_flags = nullptr; c->pend = nullptr; c->wq = nullptr; c->wws = nullptr; c->ws_stride = 0; c->parity = 0;
   c->prof_ev = nullptr; c->prof_n = 0;
   const size_t words = (size_t)((max_V + 31) / 32) + 1;
   const size_t total_words = words + 1 + 2 + (size_t)simple::PEND_ROWS;
@@ -126,8 +130,22 @@ int simple_create(simple_ctx** out, int device, int64_t max_V, int64_t max_nnz_p
   }
   c->hot_flags = c->hot_bits + words;
   c->pend = c->hot_flags + 1;
-  if (hipMemset(c->hot_bits, 0, total_words * sizeof(uint32_t)) != hipSuccess) {
+  const size_t wq_bytes = 64 + 64 * (size_t)simple::WIDE_SLOTS;  // head, then one 64-byte record per slot
+  {  // a slot holds the fixed part and the largest history tables the single-pass kernel can have
+    const simple::FastLayout Fm = simple::make_fast_layout(max_V < ((int64_t)1 << 18) ? max_V : ((int64_t)1 << 18) - 1, SIMPLE_F32,
+                                                           max_nnz_per_row, max_nnz_per_row > 0, true, lds);
+    const uint32_t tables = (max_nnz_per_row > 0 && Fm.total) ? Fm.cnt + (uint32_t)((max_nnz_per_row + 3) / 2) * 4u + 16u : 0u;
+    c->ws_stride = (simple::WIDE_SLOT_FIXED + tables + 63u) & ~63u;
+  }
+  if (hipMalloc(reinterpret_cast<void**>(&c->wq), wq_bytes + (size_t)c->ws_stride * (size_t)simple::WIDE_SLOTS) != hipSuccess) {
     (void)hipFree(c->hot_bits);
+    delete c;
+    return SIMPLE_ENOMEM;
+  }
+  c->wws = reinterpret_cast<unsigned char*>(c->wq) + wq_bytes;
+  if (hipMemset(c->hot_bits, 0, total_words * sizeof(uint32_t)) != hipSuccess || hipMemset(c->wq, 0, wq_bytes) != hipSuccess) {
+    (void)hipFree(c->hot_bits);
+    (void)hipFree(c->wq);
     delete c;
     return SIMPLE_EDEVICE;
   }
@@ -143,6 +161,7 @@ void simple_destroy(simple_ctx* ctx) {
       (void)hipDeviceSynchronize();
       if (ctx->prof_ev) (void)simple_profile_enable(ctx, 0);
       if (ctx->hot_bits) (void)hipFree(ctx->hot_bits);
+      if (ctx->wq) (void)hipFree(ctx->wq);
     }
   }
   delete ctx;
@@ -239,6 +258,7 @@ int simple_sample(simple_ctx* ctx, const void* logits_dev, int64_t B, int64_t V,
   a.seed = seed; a.step = step;
   a.max_nnz = (int)ctx->max_nnz;
   a.pend = ctx->pend;
+  a.wq = ctx->wq; a.wws = ctx->wws; a.wide_slots = simple::WIDE_SLOTS; a.ws_stride = ctx->ws_stride;
   a.L = simple::make_layout(V, ctx->max_nnz, hist_ptr_dev != nullptr);
   a.F = simple::make_fast_layout(V, dtype, hist_ptr_dev ? ctx->max_nnz : 0, hist_ptr_dev != nullptr, vec, ctx->lds_limit);
   a.gated = (a.F.total != 0u) ? 1 : 0;
@@ -252,6 +272,8 @@ int simple_sample(simple_ctx* ctx, const void* logits_dev, int64_t B, int64_t V,
     a.row_offset = row_offset + (uint64_t)b0;
     a.out = out_ids_dev + b0;
     a.diag = diag_dev ? diag_dev + b0 : nullptr;
+    a.parity = ctx->parity;
+    if (a.gated) ctx->parity ^= 1;
     hipEvent_t ev0 = nullptr, ev1 = nullptr;
     if (ctx->prof_ev && ctx->prof_n < PROF_MAX) { ev0 = ctx->prof_ev[2 * ctx->prof_n]; ev1 = ctx->prof_ev[2 * ctx->prof_n + 1]; ++ctx->prof_n; }
     if (simple::launch_sample(a, dtype, vec, st, ev0, ev1) != hipSuccess) return SIMPLE_EDEVICE;

@@ -31,160 +31,22 @@
 #include <math.h>
 #include <stdint.h>
 
-#include "simple_device.hpp"
-#include "simple_kernels.hpp"
+#include "simple_rowdev.hpp"
 
 namespace simple {
 namespace fast {
 
 #ifdef SIMPLE_PHASE_TIMES  // profiling builds only: per-row phase timestamps (100 MHz wall clock)
-__device__ unsigned long long g_fast_phase_times[8192 * 16];
-#define FPHASE(i) do { if (threadIdx.x == 0 && blockIdx.x < 8192) g_fast_phase_times[blockIdx.x * 16 + (i)] = wall_clock64(); } while (0)
-#define FPHASE_HW() do { if (threadIdx.x == 0 && blockIdx.x < 8192) { g_fast_phase_times[blockIdx.x * 16 + 15] = __builtin_amdgcn_s_getreg(63492); g_fast_phase_times[blockIdx.x * 16 + 14] = __builtin_amdgcn_s_getreg(63508); } } while (0)
-#define FWHY(code) do { if (threadIdx.x == 0 && blockIdx.x < 8192) g_fast_phase_times[blockIdx.x * 16 + 13] = (code); } while (0)
+__device__ unsigned long long g_fast_phase_times[8192 * 32];
+#define FPHASE(i) do { if (threadIdx.x == 0 && blockIdx.x < 8192) g_fast_phase_times[blockIdx.x * 32 + (i)] = wall_clock64(); } while (0)
+#define FPHASE_HW() do { if (threadIdx.x == 0 && blockIdx.x < 8192) { g_fast_phase_times[blockIdx.x * 32 + 15] = __builtin_amdgcn_s_getreg(63492); g_fast_phase_times[blockIdx.x * 32 + 14] = __builtin_amdgcn_s_getreg(63508); } } while (0)
+#define FWHY(code) do { if (threadIdx.x == 0 && blockIdx.x < 8192) g_fast_phase_times[blockIdx.x * 32 + 13] = (code); } while (0)
 #else
 #define FPHASE_HW() do { } while (0)
 #define FPHASE(i) do { } while (0)
 #define FWHY(code) do { } while (0)
 #endif
 
-typedef float f32x4 __attribute__((ext_vector_type(4)));
-typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
-typedef unsigned long long u64;
-
-constexpr int UNR = 4;       // 16-byte loads per lane and tile
-constexpr int SPW = 48;      // sample entries a wave hands to the merge
-constexpr int NBF = 256;     // buckets of the long-list tables
-constexpr int MEMB = 512;    // entries the sorted epilogue handles
-constexpr int MEMB2 = 256;   // members of one bucket the long-list path resolves exactly
-constexpr int IDR = 16;      // history ids a thread keeps in registers
-constexpr double WSCALE = 17592186044416.0;  // 2^44: fixed-point scale of probability mass
-constexpr int NBW = 1024;               // bins of the mass histogram (whole-vocabulary nucleus)
-constexpr float BINS_PER_LOG2 = 32.0f;  // bin width: 1/32 of a factor two in probability
-constexpr float MSCALE = 268435456.0f;  // 2^28: fixed-point scale of masses relative to the one at g
-constexpr int RCAP = 1024;              // columns of the boundary bin that can be resolved exactly
-constexpr float L2E_HI = 1.44269502162933349609375f, L2E_LO = 1.925963033500011e-8f;  // log2(e), split
-
-// Global-memory view of a pointer.  Inside out-of-line device functions the compiler cannot tell that
-// a pointer parameter is global; generic (flat) loads would also count against the LDS wait counter and
-// so serialise the tile prefetch behind every LDS access.
-template <typename T>
-__device__ __forceinline__ const __attribute__((address_space(1))) T* as_global(const T* p) {
-  return (const __attribute__((address_space(1))) T*)p;
-}
-__device__ __forceinline__ unsigned hot_bit(const uint32_t* __restrict__ hot_bits, uint32_t id) {
-  return (as_global(hot_bits)[id >> 5] >> (id & 31u)) & 1u;
-}
-
-template <typename DT> struct Io;
-template <> struct Io<float> {
-  static constexpr int EPL = 4;
-  typedef f32x4 Raw;
-  __device__ static __forceinline__ Raw load(const float* p) { return __builtin_nontemporal_load(as_global(reinterpret_cast<const f32x4*>(p))); }
-  __device__ static __forceinline__ void unpack(const Raw& r, float (&z)[4]) { z[0] = r.x; z[1] = r.y; z[2] = r.z; z[3] = r.w; }
-  __device__ static __forceinline__ float one(const float* p) { return *as_global(p); }
-};
-template <> struct Io<uint16_t> {  // bfloat16 bit patterns; the upcast to float32 is exact
-  static constexpr int EPL = 8;
-  typedef u32x4 Raw;
-  __device__ static __forceinline__ Raw load(const uint16_t* p) { return __builtin_nontemporal_load(as_global(reinterpret_cast<const u32x4*>(p))); }
-  __device__ static __forceinline__ void unpack(const Raw& r, float (&z)[8]) {
-    const uint32_t w[4] = {r.x, r.y, r.z, r.w};
-#pragma unroll
-    for (int i = 0; i < 4; ++i) { z[2 * i] = __uint_as_float(w[i] << 16); z[2 * i + 1] = __uint_as_float(w[i] & 0xFFFF0000u); }
-  }
-  __device__ static __forceinline__ float one(const uint16_t* p) { return __uint_as_float((uint32_t)(*as_global(p)) << 16); }
-};
-
-__device__ __forceinline__ u64 composite(uint32_t key, uint32_t id) { return ((u64)key << 32) | (u64)(0xFFFFFFFFu - id); }
-__device__ __forceinline__ unsigned lanes_before(u64 m) {
-  return __builtin_amdgcn_mbcnt_hi((uint32_t)(m >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)m, 0u));
-}
-
-// Row-wide state in static LDS.
-struct FS {
-  unsigned cand_count, flags, kmax, memb;
-  int bk, bp, bd;
-  unsigned need_k, cab_k, cab_p, n_p;
-  u64 mab_k, mab_p, mab_d, cut_k, cut_p, out_w;
-  int out_id;
-  unsigned n2, nunc;           // certified / uncertified entries of the list
-  unsigned e_n; int e_rc, e_acc;
-  u64 e_SK, e_SH, e_tfix, e_skfix;
-  float wmax[16];
-  unsigned wcnt[16];
-  unsigned r32a[16], r32b[16];
-  u64 r64a[16], r64b[16];
-  double rd[16];
-};
-
-// Per-row constants, identical in every thread.
-struct RowCfg {
-  float tau, top_p, min_p;
-  int top_k, V;
-  bool greedy, k_on, p_on, p_le0, minp_on, need_sum;
-  double u_draw, u_acc, u_tail;
-};
-
-// ---------------------------------------------------------------- block collectives -----------
-template <int NWV>
-__device__ inline void blk_reduce(FS& S, unsigned& a, unsigned& b, u64& cmax, u64& d) {
-  a = wave_sum(a); b = wave_sum(b); d = wave_sum(d);
-#pragma unroll
-  for (int o = 32; o > 0; o >>= 1) { const u64 t = __shfl_xor(cmax, o, 64); cmax = (t > cmax) ? t : cmax; }
-  __syncthreads();
-  if (lane_id() == 0) { const int w = wave_id(); S.r32a[w] = a; S.r32b[w] = b; S.r64a[w] = cmax; S.r64b[w] = d; }
-  __syncthreads();
-  unsigned ta = 0, tb = 0; u64 tc = 0, td = 0;
-#pragma unroll
-  for (int w = 0; w < NWV; ++w) { ta += S.r32a[w]; tb += S.r32b[w]; const u64 x = S.r64a[w]; tc = (x > tc) ? x : tc; td += S.r64b[w]; }
-  a = ta; b = tb; cmax = tc; d = td;
-}
-template <int NWV>
-__device__ inline u64 blk_sum_u64(FS& S, u64 v) {
-  unsigned a = 0, b = 0; u64 c = 0;
-  blk_reduce<NWV>(S, a, b, c, v);
-  return v;
-}
-template <int NWV>
-__device__ inline double blk_sum_f64(FS& S, double v) {  // fixed tree: bit-reproducible
-  v = wave_sum(v);
-  __syncthreads();
-  if (lane_id() == 0) S.rd[wave_id()] = v;
-  __syncthreads();
-  double t = 0.0;
-#pragma unroll
-  for (int w = 0; w < NWV; ++w) t += S.rd[w];
-  return t;
-}
-// Exclusive scans of one (count, mass) pair per thread, with totals.
-template <int NWV>
-__device__ inline void blk_excl_scan2(FS& S, unsigned c, u64 m, unsigned& ce, u64& me, unsigned& ct, u64& mt) {
-  const unsigned ci = wave_incl_scan(c);
-  const u64 mi = wave_incl_scan(m);
-  __syncthreads();
-  if (lane_id() == 63) { S.r32a[wave_id()] = ci; S.r64a[wave_id()] = mi; }
-  __syncthreads();
-  unsigned cb = 0, ctt = 0; u64 mb = 0, mtt = 0;
-#pragma unroll
-  for (int w = 0; w < NWV; ++w) {
-    const unsigned x = S.r32a[w]; const u64 y = S.r64a[w];
-    if (w < wave_id()) { cb += x; mb += y; }
-    ctt += x; mtt += y;
-  }
-  ce = cb + ci - c; me = mb + mi - m; ct = ctt; mt = mtt;
-}
-
-__device__ __forceinline__ uint32_t wave_max_u32(uint32_t v) {
-#pragma unroll
-  for (int o = 32; o > 0; o >>= 1) v = max(v, (uint32_t)__shfl_xor((int)v, o, 64));
-  return v;
-}
-__device__ __forceinline__ uint32_t wave_min_u32(uint32_t v) {
-#pragma unroll
-  for (int o = 32; o > 0; o >>= 1) v = min(v, (uint32_t)__shfl_xor((int)v, o, 64));
-  return v;
-}
 
 // A key t with need <= #{keys >= t} among the 64 x N keys held by a wave (N per lane), found by
 // bisection between lo and hi with wave ballots; no LDS, no barrier.  Stops as soon as the count is
@@ -229,16 +91,7 @@ struct Hist {
     if (w & 1) r += (unsigned)__popc(bm[w - 1]);
     return r + (unsigned)__popc(word & ((1u << (idx & 31)) - 1u));
   }
-  // Z' of a column that is in the history (section 2.2): repetition (sign-aware), then frequency,
-  // then presence on generated tokens; one float32 rounding per operation.  z / rep is formed as
-  // fl32(double(z) * fl64(1 / rep)), which equals the IEEE float32 quotient: the product is within
-  // 2^-52 of the exact quotient, and the quotient of two 24-bit significands is never that close
-  // to a float32 rounding boundary.
-  __device__ __forceinline__ float apply(float z, uint32_t c) const {
-    z = (z > 0.0f) ? (float)((double)z * inv_rep) : z * rep;
-    if (c > 0u) { const float t = freq * (float)c; z = z - t; z = z - pres; }
-    return z;
-  }
+  __device__ __forceinline__ float apply(float z, uint32_t c) const { return apply_penalties(z, c, rep, inv_rep, freq, pres); }
   __device__ __forceinline__ float penalised_at(float z, int idx) const {
     const uint32_t word = bm[idx >> 5];
     if ((word >> (idx & 31)) & 1u) z = apply(z, (uint32_t)cnt()[rank(idx, word)]);
@@ -326,6 +179,7 @@ __device__ inline void build_history(FS& S, const Hist& H, const int (&ids)[IDR]
     for (int j = 0; j < 8; ++j) { if (pb + j < n_pairs) H.dir[pb + j] = (uint16_t)run; run += pc[j]; }
     carry += all;
   }
+  if (tid == 0) S.distinct = carry;
   __syncthreads();
   FPHASE(8);
   n_prompt = min(max(n_prompt, 0), nnz);
@@ -341,28 +195,6 @@ __device__ inline void build_history(FS& S, const Hist& H, const int (&ids)[IDR]
   __syncthreads();
 }
 
-// ---------------------------------------------------------------- stream ----------------------
-struct StreamCtx {
-  float g, y_g;    // candidate threshold on the logit, and its tempered value fl32(g / tau)
-  double inv_tau;
-  bool need_sum;   // the row needs the mass of the columns below g
-  u64* hist;       // NBW bins of (count << 46 | mass * 2^28) over the tempered logit below y_g
-};
-
-// Mass of one column relative to the mass at y_g, w = exp(y - y_g) with y = fl32(z / tau), and the
-// bin of y (linear in y, so columns of equal y share a bin).  y is formed as fl32(double(z) * fl64(1 /
-// tau)): the IEEE float32 quotient (see Hist::apply).  float32 exponential, split log2(e).
-__device__ __forceinline__ float mass_term(float z, const StreamCtx& C, int& bin) {
-  const float y = (float)((double)z * C.inv_tau);
-  const float d = y - C.y_g;
-  const float t = fmaf(d, L2E_HI, d * L2E_LO);
-  bin = (int)fminf(fmaxf(-t * BINS_PER_LOG2, 0.0f), (float)(NBW - 1));
-  return __builtin_amdgcn_exp2f(t);
-}
-__device__ __forceinline__ u64 mass_fix(float w) { return (u64)(w * MSCALE + 0.5f); }
-// same integer for w <= 1 (every column below g), one conversion instruction
-__device__ __forceinline__ u64 mass_fix_below(float w) { return (u64)(uint32_t)(w * MSCALE + 0.5f); }
-__device__ __forceinline__ u64 hist_entry(float w) { return (1ull << 46) | mass_fix_below(w); }
 
 // Unpacks one 16-byte group of a sample tile; columns that are in the history are masked out, so
 // the threshold comes from unpenalised columns only (history columns can only add to the prefix).
@@ -398,10 +230,10 @@ __device__ __forceinline__ void append_group(FS& S, uint32_t* lz, uint32_t* li, 
   }
 }
 
-// One tile of the stream: raw logits against g; rows that need it also bin the mass below g.
+// One tile of the stream: raw logits against g; rows that need it also sum the mass below g (per lane).
 template <typename DT>
 __device__ __forceinline__ void stream_tile(const typename Io<DT>::Raw (&A)[UNR], int tb, const StreamCtx& C,
-                                            FS& S, uint32_t* lz, uint32_t* li, unsigned cap) {
+                                            FS& S, uint32_t* lz, uint32_t* li, unsigned cap, u64& below_mass) {
   constexpr int EPL = Io<DT>::EPL;
   const int lane = lane_id();
 #pragma unroll
@@ -410,13 +242,10 @@ __device__ __forceinline__ void stream_tile(const typename Io<DT>::Raw (&A)[UNR]
     Io<DT>::unpack(A[u], z);
     const int idx0 = tb + u * 64 * EPL + lane * EPL;
     if (C.need_sum) {
+      uint32_t grp = 0u;  // straight-line: a column at or above g adds zero; <= 8 terms of <= 2^28
 #pragma unroll
-      for (int e = 0; e < EPL; ++e) {  // straight-line: a column at or above g adds zero
-        int b;
-        const float w = mass_term(z[e], C, b);
-        const bool below = z[e] < C.g && z[e] > -INFINITY;
-        atomicAdd(&C.hist[b], below ? hist_entry(w) : 0ull);
-      }
+      for (int e = 0; e < EPL; ++e) grp += (z[e] < C.g) ? below_term(z[e], C) : 0u;
+      below_mass += (u64)grp;
     }
     bool any = false;
 #pragma unroll
@@ -756,332 +585,8 @@ __device__ __forceinline__ int finalize_long(FS& S, const RowCfg& R, unsigned n,
   return (S.out_id >= 0) ? FIN_DONE : FIN_PENDING;
 }
 
-// Second pass, one column: a sure survivor adds its mass to its tile (returns 1); a column of the
-// boundary bin goes to the boundary table; anything else is dropped.
-__device__ __forceinline__ unsigned classify_col(float z, int idx, unsigned hot, const StreamCtx& C, int bstar, int T,
-                                                 u64* tiles, FS& S, u64* rl) {
-  int b;
-  const float w = mass_term(z, C, b);
-  if (!(z < C.g) || b < bstar) { atomicAdd(&tiles[hot * 256u + (unsigned)(idx / T)], mass_fix(w)); return 1u; }
-  if (b == bstar) {
-    const unsigned slot = atomicAdd(&S.memb, 1u);
-    if (slot < (unsigned)RCAP) rl[slot] = ((u64)__float_as_uint(z) << 32) | (u64)(uint32_t)idx;
-  }
-  return 0u;
-}
-
-// Whole-vocabulary nucleus wider than the candidate list (top-p over all of V, section 2.1 Eq. (2)).
-// The stream left a histogram of the mass below g over bins that are linear in the tempered logit
-// (corrected for the history columns).  The bin that holds the cut follows from the cumulated
-// masses; a second pass over the row sums, per tile, the masses of the columns surely inside and
-// collects the columns of that one bin, among which the cut is found exactly in the total order
-// (columns of equal tempered value share a bin).  The draw then walks the per-tile masses of its
-// class in ascending id and reads one tile a third time.  All masses are integers, so nothing
-// depends on summation order.  Returns false when a table overflows: the general kernel takes the row.
-template <typename DT, int NTHR>
-__device__ __forceinline__ bool wide_route(FS& S, const RowCfg& R_in, const StreamCtx& C_in, const Hist& H_in, const FastLayout& F,
-                                        unsigned char* lds, const DT* __restrict__ rowp, int V, int t0, int t1,
-                                        const int (&ids_in)[IDR], unsigned own, const float (&zp_in)[IDR], u64 M_list,
-                                        u64 S_below_int, uint32_t kmax, const uint32_t* __restrict__ hot_bits,
-                                        simple_row_diag& dg) {
-  // local copies: values behind the references would be re-read after every LDS or global store;
-  // LDS pointers are re-derived from the dynamic LDS symbol so that they are known to be LDS here
-  const RowCfg R = R_in;
-  StreamCtx C = C_in;
-  Hist H = H_in;
-  const uint32_t f_dir = F.dir;
-  C.hist = reinterpret_cast<u64*>(lds + F.hist);
-  H.bm = reinterpret_cast<uint32_t*>(lds + F.bitmap);
-  H.dir = reinterpret_cast<uint16_t*>(lds + F.dir);
-  H.cnt32 = reinterpret_cast<uint32_t*>(lds + F.cnt);
-  int ids[IDR]; float zp[IDR];
-#pragma unroll
-  for (int j = 0; j < IDR; ++j) { ids[j] = ids_in[j]; zp[j] = zp_in[j]; }
-  constexpr int NWV = NTHR / 64;
-  constexpr int EPL = Io<DT>::EPL;
-  constexpr int T = 64 * EPL * UNR;
-  constexpr unsigned EMASK = (1u << EPL) - 1u;
-  typedef typename Io<DT>::Raw Raw;
-  const int tid = threadIdx.x, lane = tid & 63;
-  const int nfull = V / T;
-  const bool use_hot = hot_bits != nullptr;
-  u64* tiles = C.hist;  // [2][256] per-tile masses of the survivors (tail / hot), once the bins are consumed
-  // region map: [0, rl_off) presence mask during the pass, then composites (8 KB), sub-bin tables (3 KB),
-  // member tables (4 KB); [rl_off, rl_off + 8 KB) boundary columns, later their masses, later the tile patch
-  const uint32_t rl_off = (H.active && f_dir > 16384u) ? f_dir : 16384u;  // behind the mask (F.dir is where it ends)
-  u64* rl = reinterpret_cast<u64*>(lds + rl_off);
-  u64* rcmp = reinterpret_cast<u64*>(lds);
-  uint32_t* fcnt = reinterpret_cast<uint32_t*>(lds + 8192);
-  u64* fmass = reinterpret_cast<u64*>(lds + 8192 + NBF * 4);
-  u64* mc = reinterpret_cast<u64*>(lds + 8192 + NBF * 12);
-  u64* mw = mc + MEMB2;
-  // -- the bin that holds the cut: cumulative mass from the top reaches top_p * total --
-  const u64 S_tot = M_list + S_below_int;
-  const u64 target = (u64)__double2ull_ru((double)R.top_p * (double)S_tot);
-  {
-    constexpr int BPT = (NBW + NTHR - 1) / NTHR;
-    u64 hm[BPT]; unsigned hc[BPT]; u64 loc = 0ull;
-#pragma unroll
-    for (int j = 0; j < BPT; ++j) {
-      const int b = tid * BPT + j;
-      const u64 e = (b < NBW) ? C.hist[b] : 0ull;
-      hm[j] = e & ((1ull << 46) - 1ull); hc[j] = (unsigned)(e >> 46); loc += hm[j];
-    }
-    unsigned ce, ct; u64 me, mt;
-    blk_excl_scan2<NWV>(S, 0u, loc, ce, me, ct, mt);
-    u64 run = M_list + me;
-#pragma unroll
-    for (int j = 0; j < BPT; ++j) {
-      const int b = tid * BPT + j;
-      if (b < NBW && run < target && run + hm[j] >= target) { S.bk = b; S.mab_k = run; S.need_k = hc[j]; }
-      run += hm[j];
-    }
-  }
-  __syncthreads();
-  const int bstar = S.bk;
-  const u64 m_above = S.mab_k;
-  FPHASE(7);
-  if (bstar < 0 || S.need_k > (unsigned)RCAP || nfull + 1 > 256) { FWHY(101); return false; }
-  for (int i = tid; i < 512; i += NTHR) tiles[i] = 0ull;
-  if (tid == 0) { S.memb = 0u; S.n2 = 0u; S.cut_k = 0ull; S.bd = -1; S.bp = -1; S.kmax = 0u; S.nunc = 0xFFFFFFFFu; }
-  __syncthreads();
-  unsigned n_sure = 0;
-  // history columns, from the owners' registers (the second pass masks them out)
-  if (H.active) {
-#pragma unroll
-    for (int j = 0; j < IDR; ++j) {
-      if ((own >> j) & 1u) {
-        const unsigned hot = use_hot ? hot_bit(hot_bits, (uint32_t)ids[j]) : 0u;
-        n_sure += classify_col(zp[j], ids[j], hot, C, bstar, T, tiles, S, rl);
-      }
-    }
-  }
-  // the second pass: every other column, by its raw (= final) value
-  {
-    Raw A[UNR], Bf[UNR];
-    uint32_t hqA[UNR], hqB[UNR];
-#pragma unroll
-    for (int u = 0; u < UNR; ++u) {
-      A[u] = Io<DT>::load(rowp + (size_t)t0 * T + u * 64 * EPL + lane * EPL);
-      hqA[u] = use_hot ? as_global(hot_bits)[(t0 * T + u * 64 * EPL + lane * EPL) >> 5] : 0u;
-    }
-    for (int cur = t0; cur < t1; ++cur) {
-      if (cur + 1 < t1) {
-#pragma unroll
-        for (int u = 0; u < UNR; ++u) {
-          Bf[u] = Io<DT>::load(rowp + (size_t)(cur + 1) * T + u * 64 * EPL + lane * EPL);
-          hqB[u] = use_hot ? as_global(hot_bits)[((cur + 1) * T + u * 64 * EPL + lane * EPL) >> 5] : 0u;
-        }
-      }
-      u64 acc0 = 0ull, acc1 = 0ull;
-#pragma unroll
-      for (int u = 0; u < UNR; ++u) {
-        float z[EPL];
-        Io<DT>::unpack(A[u], z);
-        const int idx0 = cur * T + u * 64 * EPL + lane * EPL;
-        const uint32_t hnib = H.active ? ((H.bm[idx0 >> 5] >> ((unsigned)idx0 & 31u)) & EMASK) : 0u;
-        const uint32_t qnib = (hqA[u] >> ((unsigned)idx0 & 31u)) & EMASK;
-        // straight-line per column (one wave per SIMD late in the kernel: branches would expose their latency)
-        bool any_top = false, any_edge = false;
-#pragma unroll
-        for (int e = 0; e < EPL; ++e) {
-          int b;
-          const float w = mass_term(z[e], C, b);
-          const bool live = !(hnib & (1u << e));
-          const bool below = z[e] < C.g;
-          const bool sure = live && (!below || b < bstar);
-          const u64 m = (sure && below) ? mass_fix_below(w) : 0ull;
-          const bool hot = (qnib & (1u << e)) != 0u;
-          acc0 += hot ? 0ull : m;
-          acc1 += hot ? m : 0ull;
-          n_sure += sure ? 1u : 0u;
-          any_top = any_top || (live && !below);
-          any_edge = any_edge || (live && below && b == bstar);
-        }
-        if (__ballot(any_top)) {  // columns at or above g: few, their masses need the 64-bit conversion
-#pragma unroll
-          for (int e = 0; e < EPL; ++e) {
-            if (!(hnib & (1u << e)) && !(z[e] < C.g)) {
-              int b;
-              const u64 m = mass_fix(mass_term(z[e], C, b));
-              if (qnib & (1u << e)) acc1 += m; else acc0 += m;
-            }
-          }
-        }
-        if (__ballot(any_edge)) {  // columns of the boundary bin
-#pragma unroll
-          for (int e = 0; e < EPL; ++e) {
-            int b;
-            (void)mass_term(z[e], C, b);
-            if (!(hnib & (1u << e)) && z[e] < C.g && b == bstar) {
-              const unsigned slot = atomicAdd(&S.memb, 1u);
-              if (slot < (unsigned)RCAP) rl[slot] = ((u64)__float_as_uint(z[e]) << 32) | (u64)(uint32_t)(idx0 + e);
-            }
-          }
-        }
-      }
-      const u64 s0 = wave_sum(acc0), s1 = wave_sum(acc1);
-      if (lane == 0) { atomicAdd(&tiles[cur], s0); atomicAdd(&tiles[256 + cur], s1); }
-#pragma unroll
-      for (int u = 0; u < UNR; ++u) { A[u] = Bf[u]; hqA[u] = hqB[u]; }
-    }
-  }
-  for (int idx = nfull * T + tid; idx < V; idx += NTHR) {
-    if (H.active && ((H.bm[idx >> 5] >> (idx & 31)) & 1u)) continue;
-    const unsigned hot = use_hot ? hot_bit(hot_bits, (uint32_t)idx) : 0u;
-    n_sure += classify_col(Io<DT>::one(rowp + idx), idx, hot, C, bstar, T, tiles, S, rl);
-  }
-  __syncthreads();  // the presence mask is dead from here
-  FPHASE(8);
-  // -- the boundary bin, exactly: shortest prefix in the total order whose mass reaches the target --
-  const unsigned n_r = S.memb;
-  if (n_r > (unsigned)RCAP || n_r == 0u) { FWHY(102); return false; }
-  for (int i = tid; i < NBF; i += NTHR) { fcnt[i] = 0u; fmass[i] = 0ull; }
-  for (unsigned t = tid; t < n_r; t += NTHR) {
-    const u64 e = rl[t];
-    const float z = __uint_as_float((uint32_t)(e >> 32));
-    int b;
-    const float w = mass_term(z, C, b);
-    const uint32_t key = fkey(z / R.tau);
-    rcmp[t] = composite(key, (uint32_t)e);
-    rl[t] = mass_fix(w);
-    atomicMax(&S.kmax, key);
-    atomicMin(&S.nunc, key);
-  }
-  __syncthreads();
-  const uint32_t kmx = S.kmax, kmn = S.nunc;
-  const float y_hi = keyf(kmx);
-  const float sscale = (float)NBF / fmaxf(y_hi - keyf(kmn), 1e-30f);
-  auto sub_bin = [&](u64 c) { return (unsigned)min((int)((y_hi - keyf((uint32_t)(c >> 32))) * sscale), NBF - 1); };
-  for (unsigned t = tid; t < n_r; t += NTHR) {
-    const unsigned sb = sub_bin(rcmp[t]);
-    atomicAdd(&fcnt[sb], 1u);
-    atomicAdd(&fmass[sb], rl[t]);
-  }
-  __syncthreads();
-  {
-    const u64 m2 = (tid < NBF) ? fmass[tid] : 0ull;
-    unsigned ce2, ct2; u64 me2, mt2;
-    blk_excl_scan2<NWV>(S, 0u, m2, ce2, me2, ct2, mt2);
-    if (tid < NBF && m2 > 0ull && m_above + me2 < target && m_above + me2 + m2 >= target) { S.bp = tid; S.mab_p = m_above + me2; }
-  }
-  __syncthreads();
-  const int sbp = S.bp;
-  if (sbp < 0) { FWHY(103); return false; }  // the masses of the two passes disagree: leave the row to the general kernel
-  for (unsigned t = tid; t < n_r; t += NTHR) {
-    if ((int)sub_bin(rcmp[t]) == sbp) {
-      const unsigned slot = atomicAdd(&S.n2, 1u);
-      if (slot < (unsigned)MEMB2) { mc[slot] = rcmp[t]; mw[slot] = rl[t]; }
-    }
-  }
-  __syncthreads();
-  const unsigned nm = S.n2;
-  if (nm > (unsigned)MEMB2) { FWHY(104); return false; }
-  {
-    const u64 mab = S.mab_p;
-    for (unsigned mi = tid; mi < nm; mi += NTHR) {
-      const u64 cm = mc[mi], wm = mw[mi];
-      u64 G = mab;
-      for (unsigned q = 0; q < nm; ++q) G += (mc[q] >= cm) ? mw[q] : 0ull;
-      if (G >= target && G - wm < target) S.cut_k = cm;
-    }
-  }
-  __syncthreads();
-  const u64 cut_c = S.cut_k;
-  FPHASE(9);
-  if (cut_c == 0ull) { FWHY(105); return false; }
-  unsigned r_in = 0;
-  for (unsigned t = tid; t < n_r; t += NTHR) {
-    if (rcmp[t] >= cut_c) {
-      const uint32_t id = 0xFFFFFFFFu - (uint32_t)rcmp[t];
-      const unsigned hot = use_hot ? hot_bit(hot_bits, id) : 0u;
-      atomicAdd(&tiles[hot * 256u + id / (unsigned)T], rl[t]);
-      ++r_in;
-    }
-  }
-  unsigned ns = n_sure + r_in, dz = 0; u64 mx = 0ull, dsum = 0ull;
-  blk_reduce<NWV>(S, ns, dz, mx, dsum);  // barriers inside: the tile masses are complete after it
-  // -- masses of the classes, acceptance (section 5.3), the tile that holds the draw --
-  u64 p0 = 0ull, p1 = 0ull;
-  for (int i = tid; i < 256; i += NTHR) { p0 += tiles[i]; p1 += tiles[256 + i]; }
-  const u64 S0 = blk_sum_u64<NWV>(S, p0);
-  const u64 S1 = blk_sum_u64<NWV>(S, p1);
-  const u64 S_K = S0 + S1;
-  bool pick_hot = false;
-  if (use_hot) {
-    pick_hot = (S1 > 0ull) && (R.u_acc * (double)S_K <= (double)S1);
-    dg.alpha = (double)S1 / (double)S_K;
-    dg.flags |= SIMPLE_DIAG_SHVS | (pick_hot ? SIMPLE_DIAG_ACCEPTED : 0u);
-  }
-  const unsigned cls = pick_hot ? 1u : 0u;
-  const u64 S_cls = use_hot ? (pick_hot ? S1 : S0) : S_K;
-  const double u = use_hot ? (pick_hot ? R.u_draw : R.u_tail) : R.u_draw;
-  dg.n_survivors = (int)ns;
-  dg.s_k = (double)S_tot / (double)MSCALE * exp((double)C.y_g - (double)keyf(kmax));
-  if (S_cls == 0ull) { FWHY(106); return false; }
-  u64 tfix = (u64)__double2ull_rd(u * (double)S_cls);
-  if (tfix >= S_cls) tfix = S_cls - 1ull;
-  {
-    u64 before = 0ull;
-    for (int i0 = 0; i0 < 256; i0 += NTHR) {  // one tile per thread and round
-      const int i = i0 + tid;
-      const u64 m2 = (i < 256) ? tiles[cls * 256u + (unsigned)i] : 0ull;
-      unsigned ce2, ct2; u64 me2, tot2;
-      blk_excl_scan2<NWV>(S, 0u, m2, ce2, me2, ct2, tot2);
-      me2 += before;
-      if (m2 > 0ull && me2 <= tfix && me2 + m2 > tfix) { S.bd = i; S.mab_d = me2; }
-      before += tot2;
-    }
-  }
-  __syncthreads();
-  const int tstar = S.bd;
-  FPHASE(10);
-  if (tstar < 0) { FWHY(107); return false; }
-  // -- the drawn id inside one tile: history columns come from their owners --
-  constexpr int EPT = T / NTHR;
-  float* patch = reinterpret_cast<float*>(lds + rl_off);  // T floats (the boundary tables are dead)
-  for (int i = tid; i < T; i += NTHR) patch[i] = __uint_as_float(0x7FC0DEADu);
-  __syncthreads();
-  if (H.active) {
-#pragma unroll
-    for (int j = 0; j < IDR; ++j)
-      if (((own >> j) & 1u) && ids[j] / T == tstar) patch[ids[j] - tstar * T] = zp[j];
-  }
-  __syncthreads();
-  u64 mloc[EPT]; u64 lsum = 0ull;
-#pragma unroll
-  for (int e = 0; e < EPT; ++e) {
-    const int idx = tstar * T + tid * EPT + e;
-    mloc[e] = 0ull;
-    if (idx < V) {
-      const float pv = patch[tid * EPT + e];
-      const float z = (__float_as_uint(pv) == 0x7FC0DEADu) ? Io<DT>::one(rowp + idx) : pv;
-      const unsigned hot = use_hot ? hot_bit(hot_bits, (uint32_t)idx) : 0u;
-      if (!use_hot || hot == cls) {
-        int b;
-        const float w = mass_term(z, C, b);
-        bool in = !(z < C.g) || b < bstar;
-        if (!in && b == bstar) in = composite(fkey(z / R.tau), (uint32_t)idx) >= cut_c;
-        if (in) mloc[e] = mass_fix(w);
-      }
-    }
-    lsum += mloc[e];
-  }
-  unsigned ce3, ct3; u64 me3, tot3;
-  blk_excl_scan2<NWV>(S, 0u, lsum, ce3, me3, ct3, tot3);
-  u64 run = S.mab_d + me3;
-#pragma unroll
-  for (int e = 0; e < EPT; ++e) {
-    if (mloc[e] > 0ull && run <= tfix && run + mloc[e] > tfix) { S.out_id = tstar * T + tid * EPT + e; S.out_w = mloc[e]; }
-    run += mloc[e];
-  }
-  __syncthreads();
-  dg.p_chosen = (float)((double)S.out_w / (double)S_K);
-  return S.out_id >= 0;
-}
-
 __device__ inline void queue_pending(const SampleArgs& a, int row) {
-  const unsigned slot = atomicAdd(&a.pend[0], 1u);
+  const unsigned slot = atomicAdd(&a.pend[a.parity], 1u);
   a.pend[2 + slot] = (uint32_t)row;
   a.out[row] = PENDING;
 }
@@ -1109,6 +614,7 @@ __global__ __launch_bounds__(NTHR, 4) void fast_rows_kernel(const SampleArgs a) 
 #pragma unroll
   for (int u = 0; u < UNR; ++u) Bf[u] = Io<DT>::load(rowp + (size_t)(t0 + 1) * T + u * 64 * EPL + lane * EPL);
   const simple_row_params par = a.params[row];
+  if (row == 0 && tid == 0) { a.pend[a.parity ^ 1] = 0u; a.wq[a.parity ^ 1] = 0u; }  // the previous launch's counts
   FPHASE(0);
   FPHASE_HW();
   uint32_t* samp = reinterpret_cast<uint32_t*>(lds + a.F.samp);
@@ -1238,21 +744,18 @@ __global__ __launch_bounds__(NTHR, 4) void fast_rows_kernel(const SampleArgs a) 
     C.y_g = R.greedy ? g : g / R.tau;
     C.inv_tau = 1.0 / (double)R.tau;
     C.need_sum = R.need_sum;
-    C.hist = reinterpret_cast<u64*>(lds + a.F.hist);
+    C.l2e_tau = (float)(1.4426950408889634 / (double)R.tau);
   }
   // the history mask is dead from here (every wave passed the barrier above after its last lookup):
   // the region becomes the candidate list
   uint32_t* lz = reinterpret_cast<uint32_t*>(lds);
   const unsigned cap = (unsigned)a.F.list_cap;
   uint32_t* li = lz + cap;
-  if (R.need_sum) {
-    for (int i = tid; i < NBW; i += NTHR) C.hist[i] = 0ull;
-    __syncthreads();
-  }
+  u64 below_mass = 0ull;  // this thread's share of the mass below g (integer: the total is order-free)
 
   FPHASE(2);
   // ---- the stream (raw logits) ----
-  stream_tile<DT>(A, t0 * T, C, S, lz, li, cap);
+  stream_tile<DT>(A, t0 * T, C, S, lz, li, cap, below_mass);
   for (int cur = t0 + 1; cur < t1; ++cur) {
 #pragma unroll
     for (int u = 0; u < UNR; ++u) A[u] = Bf[u];
@@ -1260,7 +763,7 @@ __global__ __launch_bounds__(NTHR, 4) void fast_rows_kernel(const SampleArgs a) 
 #pragma unroll
       for (int u = 0; u < UNR; ++u) Bf[u] = Io<DT>::load(rowp + (size_t)(cur + 1) * T + u * 64 * EPL + lane * EPL);
     }
-    stream_tile<DT>(A, cur * T, C, S, lz, li, cap);
+    stream_tile<DT>(A, cur * T, C, S, lz, li, cap, below_mass);
   }
   FPHASE(3);
   // the epilogue rebuilds the history tables: fetch the ids while the other waves finish
@@ -1270,7 +773,7 @@ __global__ __launch_bounds__(NTHR, 4) void fast_rows_kernel(const SampleArgs a) 
   // ragged tail, element by element
   for (int idx = nfull * T + tid; idx < V; idx += NTHR) {
     const float zz = Io<DT>::one(rowp + idx);
-    if (C.need_sum && zz < C.g) { int b; const float w = mass_term(zz, C, b); atomicAdd(&C.hist[b], hist_entry(w)); }
+    if (C.need_sum && zz < C.g) below_mass += (u64)below_term(zz, C);
     if (!(zz < C.g)) {
       const unsigned slot = atomicAdd(&S.cand_count, 1u);
       if (slot < cap) { lz[slot] = __float_as_uint(zz); li[slot] = (uint32_t)idx; }
@@ -1297,43 +800,36 @@ __global__ __launch_bounds__(NTHR, 4) void fast_rows_kernel(const SampleArgs a) 
       ez[j] = (i < n) ? __uint_as_float(lz[i]) : -INFINITY;
       eid[j] = (i < n) ? li[i] : 0u;
     }
-    float zp[IDR];  // penalised values of the history columns this thread owns (whole-vocabulary nucleus rows)
-    unsigned own = 0u;
     __syncthreads();
     FPHASE(12);
     if (H.active) {
+      unsigned own = 0u;
       build_history<NTHR>(S, H, ids, hist, nnz, par.n_prompt, V, own);
 #pragma unroll
       for (int j = 0; j < PER; ++j) {
         const unsigned i = (unsigned)tid + (unsigned)j * NTHR;
         if (i < n) ez[j] = H.penalised_at(ez[j], (int)eid[j]);
       }
+      FPHASE(16);
       if (R.need_sum) {
-        // exact correction of the binned mass for the history columns (the stream binned their raw
+        // exact correction of the mass below g for the history columns (the stream summed their raw
         // values); each distinct column is handled by the thread that first marked it
         float zr[IDR];
 #pragma unroll
         for (int j = 0; j < IDR; ++j) zr[j] = ((own >> j) & 1u) ? Io<DT>::one(rowp + ids[j]) : 0.0f;
 #pragma unroll
         for (int j = 0; j < IDR; ++j) {
-          zp[j] = 0.0f;
-          if ((own >> j) & 1u) {
-            zp[j] = H.penalised_at(zr[j], ids[j]);
-            // columns at or above g are in the list: their terms are settled there
-            if (zr[j] < C.g) {
-              int b;
-              float w = mass_term(zr[j], C, b);
-              atomicAdd(&C.hist[b], 0ull - hist_entry(w));
-              w = mass_term(zp[j], C, b);
-              atomicAdd(&C.hist[b], hist_entry(w));
-            }
+          // columns at or above g are in the list: their terms are settled there
+          if (((own >> j) & 1u) && zr[j] < C.g) {
+            below_mass -= (u64)below_term(zr[j], C);
+            below_mass += (u64)below_term(H.penalised_at(zr[j], ids[j]), C);
           }
         }
       }
-      // the count tables are dead after this barrier; the presence mask stays for a second pass
       __syncthreads();
     }
-    // keys of the tempered values; listed columns that fell below g return to the binned mass
+    FPHASE(17);
+    // keys of the tempered values; listed columns that fell below g return to the mass below g
     uint32_t key[PER];
     bool err = false, peaked = false;
     uint32_t kloc = 0u;
@@ -1359,7 +855,7 @@ __global__ __launch_bounds__(NTHR, 4) void fast_rows_kernel(const SampleArgs a) 
               if (key[j] > key_g) mcert += mass_fix(w);
             }
           }
-        } else if (R.need_sum) { int b; const float w = mass_term(z, C, b); atomicAdd(&C.hist[b], hist_entry(w)); }
+        } else if (R.need_sum) below_mass += (u64)below_term(z, C);
       }
       kloc = max(kloc, key[j]);
     }
@@ -1367,15 +863,12 @@ __global__ __launch_bounds__(NTHR, 4) void fast_rows_kernel(const SampleArgs a) 
     if (err) atomicOr(&S.flags, SIMPLE_DIAG_ERROR | SIMPLE_DIAG_BAD_LOGIT);
     if (peaked) atomicOr(&S.flags, 1u << 30);
     __syncthreads();
-    // mass below g (integer, exact) and the decision between the list and the second pass
+    FPHASE(18);
+    // mass below g (integer, exact) and the decision between the list and the kernels that follow
     u64 S_below_int = 0ull, M_list = 0ull, M_cert = 0ull;
     bool wide = false;
     if (R.need_sum) {
-      u64 hb = 0ull;
-      for (int i = tid; i < NBW; i += NTHR) hb += C.hist[i] & ((1ull << 46) - 1ull);
-      unsigned d0 = 0, d1 = 0; u64 mx = 0ull;
-      blk_reduce<NWV>(S, d0, d1, mx, hb);
-      S_below_int = hb;
+      S_below_int = blk_sum_u64<NWV>(S, below_mass);
       M_list = blk_sum_u64<NWV>(S, mlist);
       M_cert = blk_sum_u64<NWV>(S, mcert);
       const u64 target = (u64)__double2ull_ru((double)R.top_p * (double)(M_list + S_below_int));
@@ -1383,6 +876,7 @@ __global__ __launch_bounds__(NTHR, 4) void fast_rows_kernel(const SampleArgs a) 
     }
     const double S_below = (double)S_below_int / (double)MSCALE;
     const uint32_t kmax = S.kmax;
+    FPHASE(19);
     if (S.flags & SIMPLE_DIAG_ERROR) rc = FIN_DONE;
     else if (kmax <= key_g || kmax <= KEY_NEG_INF) { rc = FIN_PENDING; FWHY(3); }
     else if (wide) {
@@ -1406,6 +900,7 @@ __global__ __launch_bounds__(NTHR, 4) void fast_rows_kernel(const SampleArgs a) 
       if (nul) atomicAdd(&S.nunc, nul);
       __syncthreads();
       const unsigned n_cert = S.n2, n_unc = S.nunc;
+      FPHASE(20);
       if (R.k_on && !R.greedy && n_cert < (unsigned)R.top_k) { rc = FIN_PENDING; FWHY(5); }  // the sampled threshold admitted too few
       else if (n_cert <= (unsigned)MEMB) {
         rc = finalize_small<NTHR>(S, R, n_cert, n_unc, kmax, key_g, C.g, S_below, mc, sc, sw, sid, hot_bits, dg);
@@ -1426,19 +921,36 @@ __global__ __launch_bounds__(NTHR, 4) void fast_rows_kernel(const SampleArgs a) 
         rc = finalize_long<NTHR>(S, R, n_cert, n_unc, kmax, key_g, C.g, S_below, lk, lid, lds + (size_t)lcap * 8u, hot_bits, dg);
       }
       else FWHY(6);
-      if (rc == FIN_WIDE) rc = FIN_PENDING;  // the tables above overwrote the presence mask
+      if (rc == FIN_WIDE && (H.active || ((S.flags >> 30) & 1u))) rc = FIN_PENDING;  // the tables above overwrote the history
     }
 
-    // ---- whole-vocabulary nucleus wider than the list: second pass over the row ----
+    // ---- whole-vocabulary nucleus wider than the list: the row goes to the kernels that follow ----
     if (rc == FIN_WIDE) {
-      dg.flags |= SIMPLE_DIAG_WIDE;
-      FPHASE(11);
-      // copies: only these escape to the out-of-line function, the originals stay in registers
-      int ids_w[IDR]; float zp_w[IDR];
-#pragma unroll
-      for (int j = 0; j < IDR; ++j) { ids_w[j] = ids[j]; zp_w[j] = zp[j]; }
-      rc = wide_route<DT, NTHR>(S, R, C, H, a.F, lds, rowp, V, t0, t1, ids_w, own, zp_w, M_list, S_below_int, kmax, hot_bits, dg)
-               ? FIN_DONE : FIN_PENDING;
+      __syncthreads();
+      if (tid == 0) S.e_n = atomicAdd(&a.wq[a.parity], 1u);
+      __syncthreads();
+      const unsigned slot = S.e_n;
+      const unsigned hb = H.active ? (a.F.cnt + (unsigned)((nnz + 3) / 2) * 4u + 15u) / 16u : 0u;  // 16-byte units of history tables
+      if (slot < (unsigned)a.wide_slots && WS_HT + hb * 16u <= a.ws_stride) {
+        u32x4* ws = reinterpret_cast<u32x4*>(a.wws + (size_t)slot * a.ws_stride);
+        const u32x4 zero = {0u, 0u, 0u, 0u};
+        for (unsigned i = tid; i < WS_RL / 16u; i += NTHR) ws[i] = zero;
+        if (H.active) {  // the history tables, still in the region, go with the row
+          const u32x4* src = reinterpret_cast<const u32x4*>(lds);
+          for (unsigned i = tid; i < hb; i += NTHR) ws[WS_HT / 16u + i] = src[i];
+        }
+        if (tid == 0) {
+          WideRec rec;
+          rec.row = (uint32_t)row; rec.g = C.g; rec.kmax = kmax; rec.flags = S.flags & 0x3FFFFFFFu;
+          rec.tau = R.tau; rec.top_p = R.top_p; rec.rep = par.rep_penalty; rec.freq = par.freq_penalty;
+          rec.pres = par.pres_penalty; rec.nnz = nnz; rec.n_prompt = min(max(par.n_prompt, 0), nnz); rec.h_active = h_active ? 1 : 0;
+          rec.h0 = h0; rec.distinct = H.active ? S.distinct : 0u; rec.reserved = 0u;
+          reinterpret_cast<WideRec*>(a.wq + WQ_HEAD)[slot] = rec;
+          a.out[row] = PENDING;
+        }
+        return;
+      }
+      rc = FIN_PENDING;  // no free slot: the general kernel takes the row
     }
   }
   FPHASE(5);
@@ -1464,7 +976,7 @@ __global__ __launch_bounds__(NTHR, 4) void fast_rows_kernel(const SampleArgs a) 
 }  // namespace simple
 #ifdef SIMPLE_PHASE_TIMES
 extern "C" int simple_debug_fast_phase_times(unsigned long long* dst_host, int n_rows) {
-  return (int)hipMemcpyFromSymbol(dst_host, HIP_SYMBOL(simple::fast::g_fast_phase_times), sizeof(unsigned long long) * 16 * (size_t)n_rows);
+  return (int)hipMemcpyFromSymbol(dst_host, HIP_SYMBOL(simple::fast::g_fast_phase_times), sizeof(unsigned long long) * 32 * (size_t)n_rows);
 }
 #endif
 namespace simple {

@@ -1188,24 +1188,16 @@ __global__ __launch_bounds__(NT, 4) void sample_rows_kernel(const SampleArgs a) 
 }
 
 // Completes the rows the single-pass kernel queued: workgroup i takes queue entries i, i + grid, ...
-// The last workgroup to finish empties the queue for the next call on the stream.
+// The next launch's single-pass kernel clears the count.
 template <typename DT, bool VEC>
 __global__ __launch_bounds__(NT, 4) void pending_rows_kernel(const SampleArgs a) {
   extern __shared__ __align__(16) unsigned char lds[];
   __shared__ Shared S;
-  const unsigned n = min(__hip_atomic_load(&a.pend[0], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT), (unsigned)a.B);
+  const unsigned n = min(__hip_atomic_load(&a.pend[a.parity], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT), (unsigned)a.B);
   for (unsigned i = blockIdx.x; i < n; i += gridDim.x) {
     const int row = (int)a.pend[2 + i];
     if (row >= 0 && row < a.B) sample_row_body<DT, VEC>(a, row, lds, S);
     __syncthreads();
-  }
-  if (threadIdx.x == 0) {
-    __threadfence();
-    const unsigned t = atomicAdd(&a.pend[1], 1u);
-    if (t == gridDim.x - 1u) {
-      __hip_atomic_store(&a.pend[0], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-      __hip_atomic_store(&a.pend[1], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    }
   }
 }
 
@@ -1254,9 +1246,11 @@ static hipError_t launch_pending(const SampleArgs& a, hipStream_t st) {
 hipError_t launch_sample(const SampleArgs& a, int dtype, bool vec, hipStream_t st, hipEvent_t ev0, hipEvent_t ev1) {
   if (ev0 && hipEventRecord(ev0, st) != hipSuccess) return hipErrorUnknown;
   if (a.gated) {  // single-pass kernel first; the general kernel then completes the rows it queued
-    const hipError_t e = launch_fast(a, dtype, st);
+    hipError_t e = launch_fast(a, dtype, st);
     if (e != hipSuccess) return e;
     if (ev1 && hipEventRecord(ev1, st) != hipSuccess) return hipErrorUnknown;
+    e = launch_wide(a, dtype, st);  // rows whose nucleus spans more of the vocabulary than the list holds
+    if (e != hipSuccess) return e;
     if (dtype == SIMPLE_F32) return vec ? launch_pending<float, true>(a, st) : launch_pending<float, false>(a, st);
     return vec ? launch_pending<uint16_t, true>(a, st) : launch_pending<uint16_t, false>(a, st);
   }

@@ -37,6 +37,8 @@ constexpr int CAPF = 3072;    // candidate-list capacity of the single-pass kern
 constexpr int KMAXF = 1024;   // largest top-k its list certifies
 constexpr int32_t PENDING = -2;  // id left by the single-pass kernel on rows the general kernel completes
 constexpr int PEND_ROWS = 65536; // rows per launch (capacity of the pending-row queue)
+constexpr int WIDE_SLOTS = 2048; // rows per launch the whole-vocabulary-nucleus kernels can take
+constexpr uint32_t WIDE_SLOT_FIXED = 20544;  // workspace per such row, before its history tables
 
 struct SampleArgs {
   const void* logits;
@@ -52,7 +54,14 @@ struct SampleArgs {
   simple_row_diag* diag;
   int max_nnz;
   int gated;       // 1: the single-pass kernel runs first and queues the rows it leaves
-  uint32_t* pend;  // [0] queued rows, [1] finished-workgroup ticket, [2 ..] row indices
+  // Queues filled by the single-pass kernel.  Word [parity] counts the entries of this launch; the
+  // single-pass kernel clears word [parity ^ 1], which the previous launch on the stream used.
+  uint32_t* pend;  // rows left to the general kernel: [0], [1] counts, [2 ..] row indices
+  uint32_t* wq;    // rows with a whole-vocabulary nucleus wider than the list: [0], [1] counts, records from word 16
+  unsigned char* wws;  // one workspace slot per queued row
+  int wide_slots;
+  uint32_t ws_stride;  // bytes per slot: fixed part, then the row's history tables
+  int parity;
   LdsLayout L;
   FastLayout F;
 };
@@ -62,6 +71,7 @@ LdsLayout make_layout(int64_t V, int64_t max_nnz, bool with_history);
 FastLayout make_fast_layout(int64_t V, int dtype, int64_t max_nnz, bool with_history, bool vec, int lds_limit);
 hipError_t launch_sample(const SampleArgs& a, int dtype, bool vec, hipStream_t st, hipEvent_t ev0, hipEvent_t ev1);
 hipError_t launch_fast(const SampleArgs& a, int dtype, hipStream_t st);
+hipError_t launch_wide(const SampleArgs& a, int dtype, hipStream_t st);  // after launch_fast, before the general kernel
 hipError_t set_max_lds(unsigned bytes);
 hipError_t set_max_lds_fast(unsigned bytes);
 hipError_t launch_hot_build(const int32_t* ids, int H, int V, uint32_t* bits, uint32_t* flags, hipStream_t st);

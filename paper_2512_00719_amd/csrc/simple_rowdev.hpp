@@ -1,0 +1,213 @@
+// Device-side pieces shared by the single-pass row kernel and the kernels of the whole-vocabulary
+// nucleus: 16-byte row loads, row-wide LDS state, block collectives and the fixed-point mass of a
+// column relative to the candidate threshold.  gfx950 only (wave64).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <math.h>
+#include <stdint.h>
+
+#include "simple_device.hpp"
+#include "simple_kernels.hpp"
+
+namespace simple {
+namespace fast {
+
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef unsigned long long u64;
+
+constexpr int UNR = 4;       // 16-byte loads per lane and tile
+constexpr int SPW = 48;      // sample entries a wave hands to the merge
+constexpr int NBF = 256;     // buckets of the long-list tables
+constexpr int MEMB = 512;    // entries the sorted epilogue handles
+constexpr int MEMB2 = 256;   // members of one bucket the long-list path resolves exactly
+constexpr int IDR = 16;      // history ids a thread keeps in registers
+constexpr double WSCALE = 17592186044416.0;  // 2^44: fixed-point scale of probability mass
+constexpr int NBW = 1024;               // bins of the mass histogram (whole-vocabulary nucleus)
+constexpr float BINS_PER_LOG2 = 32.0f;  // bin width: 1/32 of a factor two in probability
+constexpr float MSCALE = 268435456.0f;  // 2^28: fixed-point scale of masses relative to the one at g
+constexpr int RCAP = 1024;              // columns of the boundary bin that can be resolved exactly
+constexpr float L2E_HI = 1.44269502162933349609375f, L2E_LO = 1.925963033500011e-8f;  // log2(e), split
+
+// Global-memory view of a pointer.  Inside out-of-line device functions the compiler cannot tell that
+// a pointer parameter is global; generic (flat) loads would also count against the LDS wait counter and
+// so serialise the tile prefetch behind every LDS access.
+template <typename T>
+__device__ __forceinline__ const __attribute__((address_space(1))) T* as_global(const T* p) {
+  return (const __attribute__((address_space(1))) T*)p;
+}
+__device__ __forceinline__ unsigned hot_bit(const uint32_t* __restrict__ hot_bits, uint32_t id) {
+  return (as_global(hot_bits)[id >> 5] >> (id & 31u)) & 1u;
+}
+
+template <typename DT> struct Io;
+template <> struct Io<float> {
+  static constexpr int EPL = 4;
+  typedef f32x4 Raw;
+  __device__ static __forceinline__ Raw load(const float* p) { return __builtin_nontemporal_load(as_global(reinterpret_cast<const f32x4*>(p))); }
+  __device__ static __forceinline__ void unpack(const Raw& r, float (&z)[4]) { z[0] = r.x; z[1] = r.y; z[2] = r.z; z[3] = r.w; }
+  __device__ static __forceinline__ float one(const float* p) { return *as_global(p); }
+};
+template <> struct Io<uint16_t> {  // bfloat16 bit patterns; the upcast to float32 is exact
+  static constexpr int EPL = 8;
+  typedef u32x4 Raw;
+  __device__ static __forceinline__ Raw load(const uint16_t* p) { return __builtin_nontemporal_load(as_global(reinterpret_cast<const u32x4*>(p))); }
+  __device__ static __forceinline__ void unpack(const Raw& r, float (&z)[8]) {
+    const uint32_t w[4] = {r.x, r.y, r.z, r.w};
+#pragma unroll
+    for (int i = 0; i < 4; ++i) { z[2 * i] = __uint_as_float(w[i] << 16); z[2 * i + 1] = __uint_as_float(w[i] & 0xFFFF0000u); }
+  }
+  __device__ static __forceinline__ float one(const uint16_t* p) { return __uint_as_float((uint32_t)(*as_global(p)) << 16); }
+};
+
+__device__ __forceinline__ u64 composite(uint32_t key, uint32_t id) { return ((u64)key << 32) | (u64)(0xFFFFFFFFu - id); }
+__device__ __forceinline__ unsigned lanes_before(u64 m) {
+  return __builtin_amdgcn_mbcnt_hi((uint32_t)(m >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)m, 0u));
+}
+
+// Row-wide state in static LDS.
+struct FS {
+  unsigned cand_count, flags, kmax, memb;
+  int bk, bp, bd;
+  unsigned need_k, cab_k, cab_p, n_p;
+  u64 mab_k, mab_p, mab_d, cut_k, cut_p, out_w;
+  int out_id;
+  unsigned n2, nunc;           // certified / uncertified entries of the list
+  unsigned e_n; int e_rc, e_acc;
+  unsigned distinct;           // distinct history columns of the row
+  u64 e_SK, e_SH, e_tfix, e_skfix;
+  float wmax[16];
+  unsigned wcnt[16];
+  unsigned r32a[16], r32b[16];
+  u64 r64a[16], r64b[16];
+  double rd[16];
+};
+
+// Per-row constants, identical in every thread.
+struct RowCfg {
+  float tau, top_p, min_p;
+  int top_k, V;
+  bool greedy, k_on, p_on, p_le0, minp_on, need_sum;
+  double u_draw, u_acc, u_tail;
+};
+
+// ---------------------------------------------------------------- block collectives -----------
+template <int NWV>
+__device__ inline void blk_reduce(FS& S, unsigned& a, unsigned& b, u64& cmax, u64& d) {
+  a = wave_sum(a); b = wave_sum(b); d = wave_sum(d);
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) { const u64 t = __shfl_xor(cmax, o, 64); cmax = (t > cmax) ? t : cmax; }
+  __syncthreads();
+  if (lane_id() == 0) { const int w = wave_id(); S.r32a[w] = a; S.r32b[w] = b; S.r64a[w] = cmax; S.r64b[w] = d; }
+  __syncthreads();
+  unsigned ta = 0, tb = 0; u64 tc = 0, td = 0;
+#pragma unroll
+  for (int w = 0; w < NWV; ++w) { ta += S.r32a[w]; tb += S.r32b[w]; const u64 x = S.r64a[w]; tc = (x > tc) ? x : tc; td += S.r64b[w]; }
+  a = ta; b = tb; cmax = tc; d = td;
+}
+template <int NWV>
+__device__ inline u64 blk_sum_u64(FS& S, u64 v) {
+  unsigned a = 0, b = 0; u64 c = 0;
+  blk_reduce<NWV>(S, a, b, c, v);
+  return v;
+}
+template <int NWV>
+__device__ inline double blk_sum_f64(FS& S, double v) {  // fixed tree: bit-reproducible
+  v = wave_sum(v);
+  __syncthreads();
+  if (lane_id() == 0) S.rd[wave_id()] = v;
+  __syncthreads();
+  double t = 0.0;
+#pragma unroll
+  for (int w = 0; w < NWV; ++w) t += S.rd[w];
+  return t;
+}
+// Exclusive scans of one (count, mass) pair per thread, with totals.
+template <int NWV>
+__device__ inline void blk_excl_scan2(FS& S, unsigned c, u64 m, unsigned& ce, u64& me, unsigned& ct, u64& mt) {
+  const unsigned ci = wave_incl_scan(c);
+  const u64 mi = wave_incl_scan(m);
+  __syncthreads();
+  if (lane_id() == 63) { S.r32a[wave_id()] = ci; S.r64a[wave_id()] = mi; }
+  __syncthreads();
+  unsigned cb = 0, ctt = 0; u64 mb = 0, mtt = 0;
+#pragma unroll
+  for (int w = 0; w < NWV; ++w) {
+    const unsigned x = S.r32a[w]; const u64 y = S.r64a[w];
+    if (w < wave_id()) { cb += x; mb += y; }
+    ctt += x; mtt += y;
+  }
+  ce = cb + ci - c; me = mb + mi - m; ct = ctt; mt = mtt;
+}
+
+__device__ __forceinline__ uint32_t wave_max_u32(uint32_t v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v = max(v, (uint32_t)__shfl_xor((int)v, o, 64));
+  return v;
+}
+__device__ __forceinline__ uint32_t wave_min_u32(uint32_t v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v = min(v, (uint32_t)__shfl_xor((int)v, o, 64));
+  return v;
+}
+
+// Z' of a column that is in the history (section 2.2): repetition (sign-aware), then frequency,
+// then presence on generated tokens (count > 0); one float32 rounding per operation.  z / rep is
+// formed as fl32(double(z) * fl64(1 / rep)), which equals the IEEE float32 quotient: the product is
+// within 2^-52 of the exact quotient, and the quotient of two 24-bit significands is never that
+// close to a float32 rounding boundary.
+__device__ __forceinline__ float apply_penalties(float z, uint32_t count, float rep, double inv_rep, float freq, float pres) {
+  z = (z > 0.0f) ? (float)((double)z * inv_rep) : z * rep;
+  if (count > 0u) { const float t = freq * (float)count; z = z - t; z = z - pres; }
+  return z;
+}
+
+// ---------------------------------------------------------------- stream ----------------------
+struct StreamCtx {
+  float g, y_g;    // candidate threshold on the logit, and its tempered value fl32(g / tau)
+  double inv_tau;
+  float l2e_tau;   // log2(e) / tau
+  bool need_sum;   // the row needs the mass of the columns below g
+};
+
+// Whole-vocabulary nucleus (top-p over all of V, section 2.1 Eq. (2)): rows whose nucleus is wider
+// than the candidate list are handed to three further kernels through a queue of records and one
+// workspace slot per queued row.
+struct WideRec {  // 64 bytes: everything the later kernels need to know about the row
+  uint32_t row; float g; uint32_t kmax, flags;
+  float tau, top_p, rep, freq;
+  float pres; int nnz, n_prompt, h_active;
+  long long h0; uint32_t distinct, reserved;
+};
+constexpr int WQ_HEAD = 16;             // words before the records
+constexpr uint32_t WS_HIST = 0u;        // u64[NBW]: (count << 46 | mass) of the columns below g, by bin
+constexpr uint32_t WS_TILES = 8192u;    // u64[2][256]: survivors' mass per tile, tail class then hot class
+constexpr uint32_t WS_SCAL = 12288u;    // u64 mass at or above g; u32 sure survivors; u32 boundary columns
+constexpr uint32_t WS_RL = 12352u;      // u64[RCAP]: columns of the boundary bin (value bits << 32 | id)
+constexpr uint32_t WS_HT = 20544u;      // the row's history tables as the single-pass kernel laid them out in LDS
+// [0, WS_RL) must be zero when a row is queued
+
+// Mass of one column relative to the mass at y_g, w = exp(y - y_g) with y = fl32(z / tau), and the
+// bin of y (linear in y, so columns of equal y share a bin).  y is formed as fl32(double(z) * fl64(1 /
+// tau)): the IEEE float32 quotient (see apply_penalties).  float32 exponential, split log2(e).
+__device__ __forceinline__ float mass_term(float z, const StreamCtx& C, int& bin) {
+  const float y = (float)((double)z * C.inv_tau);
+  const float d = y - C.y_g;
+  const float t = fmaf(d, L2E_HI, d * L2E_LO);
+  bin = (int)fminf(fmaxf(-t * BINS_PER_LOG2, 0.0f), (float)(NBW - 1));
+  return __builtin_amdgcn_exp2f(t);
+}
+__device__ __forceinline__ u64 mass_fix(float w) { return (u64)(w * MSCALE + 0.5f); }
+// same integer for w <= 1 (every column below g), one conversion instruction
+__device__ __forceinline__ u64 mass_fix_below(float w) { return (u64)(uint32_t)(w * MSCALE + 0.5f); }
+// Mass of a column below g for the single-pass kernel's running total: exp((z - g) / tau) without
+// the exactly rounded tempered value (relative error of the total about 1e-6, inside the 1e-5
+// tolerance on probabilities); only decides whether the nucleus fits the list, and the list's target.
+__device__ __forceinline__ uint32_t below_term(float z, const StreamCtx& C) {
+  return (uint32_t)(__builtin_amdgcn_exp2f((z - C.g) * C.l2e_tau) * MSCALE + 0.5f);
+}
+__device__ __forceinline__ u64 hist_entry(float w) { return (1ull << 46) | mass_fix_below(w); }
+
+}  // namespace fast
+}  // namespace simple
