@@ -6,11 +6,13 @@
 //
 //   bins      per slice, the penalised, tempered logits below g are binned (bins linear in the
 //             tempered logit, 1/32 of a factor two in probability wide) with their masses relative
-//             to the mass at g, as integers; the mass at or above g is summed beside them.
-//   classify  the bin that holds the cut follows from the cumulated masses; per tile, the masses of
-//             the columns surely inside are summed by class (tail / hot), and the columns of the
-//             cut's bin are collected.
-//   finish    one workgroup per row finds the cut exactly among the collected columns (total order:
+//             to the mass at g, at reduced precision (32-bit LDS atomics); the mass at or above g
+//             is summed beside them.  This pass only has to point at the bin that holds the cut.
+//   classify  that bin follows from the cumulated masses; per tile, the exact (integer) masses of
+//             the columns surely inside are summed by class (tail / hot), the columns of the
+//             cut's bin are collected, and the exact mass of the whole row is summed.
+//   finish    one workgroup per row checks that the cut does lie in the collected bin (else the
+//             general kernel takes the row), finds it exactly among those columns (total order:
 //             value descending, id ascending), applies the SHVS acceptance test (section 5.3), walks
 //             the per-tile masses of the drawn class in ascending id and reads one tile a last time
 //             to locate the drawn id (inverse CDF, step (3) of section 2.1).
@@ -25,9 +27,19 @@
 namespace simple {
 namespace fast {
 
+#ifdef SIMPLE_PHASE_TIMES  // profiling builds only: per-workgroup timestamps of the first kernel (100 MHz wall clock)
+__device__ unsigned long long g_wide_phase_times[2 * 8192 * 8];
+#define XPHASE(i) do { if (threadIdx.x == 0 && blockIdx.x < 8192) g_wide_phase_times[(8192 + blockIdx.x) * 8 + (i)] = wall_clock64(); } while (0)
+#define WPHASE(i) do { if (threadIdx.x == 0 && blockIdx.x < 8192) g_wide_phase_times[blockIdx.x * 8 + (i)] = wall_clock64(); } while (0)
+#else
+#define WPHASE(i) do { } while (0)
+#define XPHASE(i) do { } while (0)
+#endif
+
 constexpr int WT = 256;      // threads per workgroup
 constexpr int WNW = WT / 64;
 constexpr int SLC = 4096;    // columns per slice
+constexpr float BSCALE = 524288.0f;  // 2^19: scale of the first pass's masses
 static_assert(WS_HT == WIDE_SLOT_FIXED, "workspace slot size");
 static_assert(sizeof(WideRec) == 64, "queue record size");
 
@@ -59,32 +71,54 @@ __device__ __forceinline__ WideRow load_row(const SampleArgs& a, unsigned slot) 
   return W;
 }
 
-// A slice's part of the row's history tables, in LDS: the 128 mask words of its 4096 columns, the
-// rank at the start of each of its 64 word pairs (and of the next slice), and the counts of its
+// A slice's part of the row's history tables, in LDS: the mask words of its columns, the
+// rank at the start of each of its word pairs (and of the next slice), and the counts of its
 // columns, indexed by rank minus the slice's first rank.
 struct SliceTabs {
   uint32_t bm[SLC / 32];
   uint32_t dir[SLC / 64 + 2];
   uint16_t cnt[SLC];
 };
-// Loads the tables of the slice that starts at column c0.  Two barriers; ends with one.
-__device__ inline void load_slice(SliceTabs& T, const WideRow& W, const SampleArgs& a, int c0) {
+static_assert(WT == 256, "the finishing kernel maps one tile of each class to a thread");
+static_assert(SLC / 32 + SLC / 64 + 1 <= WT, "one mask word or directory entry per thread");
+// The tables of the slice that starts at column c0 come in two steps, so that their loads overlap
+// with the other loads of an item.  First this thread's mask word or directory entry (the addresses
+// follow from the slot alone):
+__device__ __forceinline__ uint32_t slice_fetch(const unsigned char* ws, const SampleArgs& a, int c0) {
   const int tid = threadIdx.x;
-  const unsigned char* ht = W.ws + WS_HT;
-  const uint32_t* gbm = reinterpret_cast<const uint32_t*>(ht);
-  const uint16_t* gdir = reinterpret_cast<const uint16_t*>(ht + a.F.dir);
-  const uint16_t* gcnt = reinterpret_cast<const uint16_t*>(ht + a.F.cnt);
+  const unsigned char* ht = ws + WS_HT;
   const int n_pairs = (((a.V + 31) >> 5) + 1) >> 1;  // the mask is stored in whole pairs of words
   const int w0 = c0 >> 5, p0 = c0 >> 6;
-  if (tid < SLC / 32) T.bm[tid] = (w0 + tid < 2 * n_pairs) ? as_global(gbm)[w0 + tid] : 0u;
+  uint32_t v = 0u;
+  if (tid < SLC / 32) { if (w0 + tid < 2 * n_pairs) v = as_global(reinterpret_cast<const uint32_t*>(ht))[w0 + tid]; }
   else if (tid < SLC / 32 + SLC / 64 + 1) {
     const int j = tid - SLC / 32;
-    T.dir[j] = (p0 + j < n_pairs) ? (uint32_t)as_global(gdir)[p0 + j] : W.distinct;
+    if (p0 + j < n_pairs) v = (uint32_t)as_global(reinterpret_cast<const uint16_t*>(ht + a.F.dir))[p0 + j];
   }
-  __syncthreads();
+  return v;
+}
+// ... stored to LDS (past the directory's end stands the number of distinct columns); a barrier must follow.
+__device__ __forceinline__ void slice_store(SliceTabs& T, uint32_t v, const SampleArgs& a, int c0, uint32_t distinct) {
+  const int tid = threadIdx.x;
+  const int n_pairs = (((a.V + 31) >> 5) + 1) >> 1;
+  if (tid < SLC / 32) T.bm[tid] = v;
+  else if (tid < SLC / 32 + SLC / 64 + 1) {
+    const int j = tid - SLC / 32;
+    T.dir[j] = ((c0 >> 6) + j < n_pairs) ? v : distinct;
+  }
+}
+// Then, once the directory is in LDS, the counts of the slice's columns; a barrier must follow.
+__device__ __forceinline__ void slice_counts(SliceTabs& T, const unsigned char* ws, const SampleArgs& a) {
+  const uint16_t* gcnt = reinterpret_cast<const uint16_t*>(ws + WS_HT + a.F.cnt);
   const unsigned r0 = T.dir[0];
   const unsigned nc = min(T.dir[SLC / 64] - r0, (unsigned)SLC);
-  for (unsigned t = tid; t < nc; t += WT) T.cnt[t] = as_global(gcnt)[r0 + t];
+  for (unsigned t = threadIdx.x; t < nc; t += WT) T.cnt[t] = as_global(gcnt)[r0 + t];
+}
+__device__ inline void load_slice(SliceTabs& T, const WideRow& W, const SampleArgs& a, int c0) {  // ends with a barrier
+  const uint32_t v = slice_fetch(W.ws, a, c0);
+  slice_store(T, v, a, c0, W.distinct);
+  __syncthreads();
+  slice_counts(T, W.ws, a);
   __syncthreads();
 }
 // Z' of column c0 + o, whose mask bit is set.
@@ -97,33 +131,50 @@ __device__ __forceinline__ float slice_value(float z, int o, const SliceTabs& T,
   return apply_penalties(z, (uint32_t)T.cnt[min(r, (unsigned)SLC - 1u)], W.rep, W.inv_rep, W.freq, W.pres);
 }
 __device__ __forceinline__ bool slice_bit(int o, const SliceTabs& T) { return (T.bm[o >> 5] >> (o & 31)) & 1u; }
+// The history columns of a slice, one mask word per thread: f(z', idx) for each, with its penalised
+// value.  The streaming loops skip these columns, so their main line carries no table lookups.
+template <typename DT, typename F>
+__device__ __forceinline__ void for_history_columns(const SliceTabs& T, const WideRow& W, const DT* rowp, int c0, int V, F&& f) {
+  const int tid = threadIdx.x;
+  if (tid < SLC / 32) {
+    uint32_t word = T.bm[tid];
+    unsigned r = T.dir[tid >> 1] - T.dir[0] + ((tid & 1) ? (unsigned)__popc(T.bm[tid - 1]) : 0u);
+    while (word) {
+      const int idx = c0 + 32 * tid + (__ffs((int)word) - 1);
+      word &= word - 1u;
+      if (idx < V) {
+        const float z = apply_penalties(Io<DT>::one(rowp + idx), (uint32_t)T.cnt[min(r, (unsigned)SLC - 1u)], W.rep, W.inv_rep, W.freq, W.pres);
+        f(z, idx);
+      }
+      ++r;
+    }
+  }
+}
 
-// The bin that holds the cut: cumulative mass from the top reaches top_p * total.  bstar < 0 if none.
-__device__ inline void find_cut(FS& S, const WideRow& W, int& bstar, u64& m_above, u64& target, u64& S_tot, unsigned& in_bin) {
+// The bin that should hold the cut, from the reduced-precision masses of the first pass: cumulative
+// mass from the top reaches top_p * total.  bstar < 0 if none.  Ends with a barrier.
+__device__ inline int find_cut(FS& S, const WideRow& W) {
   const int tid = threadIdx.x;
   constexpr int BPT = NBW / WT;
   const u64* gh = reinterpret_cast<const u64*>(W.ws + WS_HIST);
-  const u64 m_top = *reinterpret_cast<const u64*>(W.ws + WS_SCAL);
-  u64 hm[BPT]; unsigned hc[BPT]; u64 loc = 0ull;
+  const u64 m_top = as_global(reinterpret_cast<const u64*>(W.ws + WS_SCAL))[0];
+  u64 hm[BPT]; u64 loc = 0ull;
 #pragma unroll
-  for (int j = 0; j < BPT; ++j) {
-    const u64 e = as_global(gh)[tid * BPT + j];
-    hm[j] = e & ((1ull << 46) - 1ull); hc[j] = (unsigned)(e >> 46); loc += hm[j];
-  }
-  if (tid == 0) { S.bk = -1; S.mab_k = 0ull; S.need_k = 0u; }
+  for (int j = 0; j < BPT; ++j) { hm[j] = as_global(gh)[tid * BPT + j]; loc += hm[j]; }
+  if (tid == 0) S.bk = -1;
   unsigned ce, ct; u64 me, mt;
   blk_excl_scan2<WNW>(S, 0u, loc, ce, me, ct, mt);
-  S_tot = m_top + mt;
-  target = (u64)__double2ull_ru((double)W.top_p * (double)S_tot);
+  const u64 target = (u64)__double2ull_ru((double)W.top_p * (double)(m_top + mt));
   u64 run = m_top + me;
 #pragma unroll
   for (int j = 0; j < BPT; ++j) {
-    if (run < target && run + hm[j] >= target) { S.bk = tid * BPT + j; S.mab_k = run; S.need_k = hc[j]; }
+    if (run < target && run + hm[j] >= target) S.bk = tid * BPT + j;
     run += hm[j];
   }
   __syncthreads();
-  bstar = S.bk; m_above = S.mab_k; in_bin = S.need_k;
+  const int bstar = S.bk;
   __syncthreads();
+  return bstar;
 }
 
 // Work split: items are (queued row, slice) pairs in row-major order; a workgroup takes a
@@ -142,39 +193,43 @@ __device__ __forceinline__ Items my_items(const SampleArgs& a) {
 
 // ---------------------------------------------------------------- bins ------------------------
 template <typename DT>
-__global__ __launch_bounds__(WT) void wide_bins_kernel(const SampleArgs a) {
+__global__ __launch_bounds__(WT, 8) void wide_bins_kernel(const SampleArgs a) {
   constexpr int EPL = Io<DT>::EPL;
   constexpr int G = SLC / (WT * EPL);
   typedef typename Io<DT>::Raw Raw;
   __shared__ SliceTabs Tb;
-  __shared__ u64 lh[NBW];
+  __shared__ uint32_t lh[NBW];  // masses at 2^19: a slice's 4096 columns cannot overflow a bin
   __shared__ FS S;
   const int tid = threadIdx.x;
   const int V = a.V;
   const Items I = my_items(a);
   if (I.i0 >= I.i1) return;
+  WPHASE(0);
+#ifdef SIMPLE_PHASE_TIMES
+  if (threadIdx.x == 0 && blockIdx.x < 8192) { g_wide_phase_times[blockIdx.x * 8 + 5] = __builtin_amdgcn_s_getreg(63492); g_wide_phase_times[blockIdx.x * 8 + 6] = __builtin_amdgcn_s_getreg(63508); }
+#endif
   int cur = -1;
   WideRow W;
   u64 mtop = 0ull;
   auto flush = [&]() {
     __syncthreads();
     u64* gh = reinterpret_cast<u64*>(W.ws + WS_HIST);
-    for (int b = tid; b < NBW; b += WT) { const u64 v = lh[b]; if (v) atomicAdd(&gh[b], v); }
+    for (int b = tid; b < NBW; b += WT) { const uint32_t v = lh[b]; if (v) atomicAdd(&gh[b], (u64)v); }
     const u64 t = blk_sum_u64<WNW>(S, mtop);
     if (tid == 0 && t) atomicAdd(reinterpret_cast<u64*>(W.ws + WS_SCAL), t);
     mtop = 0ull;
   };
   for (unsigned it = I.i0; it < I.i1; ++it) {
     const int slot = (int)(it / I.n_sl), sl = (int)(it % I.n_sl);
+    const int c0 = sl * SLC;
+    const unsigned char* ws = a.wws + (size_t)slot * a.ws_stride;
+    const uint32_t pre = slice_fetch(ws, a, c0);  // in flight while the record arrives
     if (slot != cur) {
       if (cur >= 0) flush();
       W = load_row(a, (unsigned)slot);
       cur = slot;
-      __syncthreads();
-      for (int b = tid; b < NBW; b += WT) lh[b] = 0ull;
-      __syncthreads();
+      for (int b = tid; b < NBW; b += WT) lh[b] = 0u;
     }
-    const int c0 = sl * SLC;
     const DT* rowp = reinterpret_cast<const DT*>(a.logits) + (size_t)W.row * (size_t)a.stride;
     Raw A[G];
 #pragma unroll
@@ -182,14 +237,19 @@ __global__ __launch_bounds__(WT) void wide_bins_kernel(const SampleArgs a) {
       const int idx0 = c0 + (j * WT + tid) * EPL;
       if (idx0 + EPL <= V) A[j] = Io<DT>::load(rowp + idx0);
     }
-    if (W.h_active) load_slice(Tb, W, a, c0);
-    auto one = [&](float z, int idx) {
-      if (W.h_active && slice_bit(idx - c0, Tb)) z = slice_value(z, idx - c0, Tb, W);
+    WPHASE(1);
+    slice_store(Tb, pre, a, c0, W.distinct);
+    __syncthreads();
+    if (W.h_active) slice_counts(Tb, ws, a);
+    __syncthreads();
+    WPHASE(2);
+    auto one = [&](float z, int) {
       int b;
       const float w = mass_term(z, W.C, b);
-      if (z < W.C.g) { if (z > -INFINITY) atomicAdd(&lh[b], hist_entry(w)); }
-      else mtop += mass_fix(w);
+      if (z < W.C.g) atomicAdd(&lh[b], (uint32_t)(w * BSCALE + 0.5f));
+      else mtop += (u64)(w * BSCALE + 0.5f);
     };
+    if (W.h_active) for_history_columns<DT>(Tb, W, rowp, c0, V, one);
 #pragma unroll
     for (int j = 0; j < G; ++j) {
       const int idx0 = c0 + (j * WT + tid) * EPL;
@@ -197,46 +257,46 @@ __global__ __launch_bounds__(WT) void wide_bins_kernel(const SampleArgs a) {
         float z[EPL];
         Io<DT>::unpack(A[j], z);
         bool any_top = false;
-        if (W.h_active) {
+        if (W.h_active) {  // history columns were handled above: here they count as -inf (no mass)
           const uint32_t nib = (Tb.bm[(idx0 - c0) >> 5] >> ((unsigned)(idx0 - c0) & 31u)) & ((1u << EPL) - 1u);
-          if (nib) {
 #pragma unroll
-            for (int e = 0; e < EPL; ++e) if ((nib >> e) & 1u) z[e] = slice_value(z[e], idx0 - c0 + e, Tb, W);
-          }
+          for (int e = 0; e < EPL; ++e) z[e] = ((nib >> e) & 1u) ? -INFINITY : z[e];
         }
 #pragma unroll
         for (int e = 0; e < EPL; ++e) {  // straight-line: a column at or above g adds zero to its bin
           int b;
           const float w = mass_term(z[e], W.C, b);
           const bool below = z[e] < W.C.g;
-          atomicAdd(&lh[b], (below && z[e] > -INFINITY) ? hist_entry(w) : 0ull);
+          atomicAdd(&lh[b], below ? (uint32_t)(w * BSCALE + 0.5f) : 0u);
           any_top = any_top || !below;
         }
         if (__ballot(any_top)) {  // few columns: the 64-bit conversion stays out of the main line
 #pragma unroll
           for (int e = 0; e < EPL; ++e)
-            if (!(z[e] < W.C.g)) { int b; mtop += mass_fix(mass_term(z[e], W.C, b)); }
+            if (!(z[e] < W.C.g)) { int b; mtop += (u64)(mass_term(z[e], W.C, b) * BSCALE + 0.5f); }
         }
       } else {
-        for (int idx = idx0; idx < V; ++idx) one(Io<DT>::one(rowp + idx), idx);
+        for (int idx = idx0; idx < V; ++idx)
+          if (!(W.h_active && slice_bit(idx - c0, Tb))) one(Io<DT>::one(rowp + idx), idx);
       }
     }
     __syncthreads();  // the tables are reloaded by the next item
+    WPHASE(3);
   }
   flush();
+  WPHASE(4);
 }
 
 // ---------------------------------------------------------------- classify --------------------
 template <typename DT>
-__global__ __launch_bounds__(WT) void wide_classify_kernel(const SampleArgs a) {
+__global__ __launch_bounds__(WT, 6) void wide_classify_kernel(const SampleArgs a) {
   constexpr int EPL = Io<DT>::EPL;
-  constexpr int G = SLC / (WT * EPL);  // tiles per slice: one 16-byte group per thread covers a tile
-  constexpr int T = WT * EPL;
+  constexpr int G = SLC / (WT * EPL);  // 16-byte groups per thread and slice; a slice is one tile of the draw's walk
   constexpr unsigned EMASK = (1u << EPL) - 1u;
   typedef typename Io<DT>::Raw Raw;
   __shared__ SliceTabs Tb;
   __shared__ u64 lrl[RCAP];
-  __shared__ u64 ltile[2 * G];
+  __shared__ u64 ltile[2];
   __shared__ unsigned l_n, l_base;
   __shared__ FS S;
   const int tid = threadIdx.x, lane = tid & 63;
@@ -254,12 +314,12 @@ __global__ __launch_bounds__(WT) void wide_classify_kernel(const SampleArgs a) {
     if (slot != cur) {
       W = load_row(a, (unsigned)slot);
       cur = slot;
-      u64 m_above, target, S_tot; unsigned in_bin;
-      find_cut(S, W, bstar, m_above, target, S_tot, in_bin);
-      valid = bstar >= 0 && in_bin <= (unsigned)RCAP;
+      bstar = find_cut(S, W);
+      valid = bstar >= 0;
     }
     if (!valid) continue;  // the finishing kernel hands the row on
     const int c0 = sl * SLC;
+    const uint32_t pre = slice_fetch(W.ws, a, c0);
     const DT* rowp = reinterpret_cast<const DT*>(a.logits) + (size_t)W.row * (size_t)a.stride;
     Raw A[G];
     uint32_t hq[G];
@@ -270,59 +330,67 @@ __global__ __launch_bounds__(WT) void wide_classify_kernel(const SampleArgs a) {
       if (idx0 + EPL <= V) A[j] = Io<DT>::load(rowp + idx0);
       if (use_hot && idx0 < V) hq[j] = (as_global(hot_bits)[idx0 >> 5] >> ((unsigned)idx0 & 31u)) & EMASK;
     }
-    if (tid < 2 * G) ltile[tid] = 0ull;
+    if (tid < 2) ltile[tid] = 0ull;
     if (tid == 0) l_n = 0u;
-    if (W.h_active) load_slice(Tb, W, a, c0); else __syncthreads();
+    slice_store(Tb, pre, a, c0, W.distinct);
+    __syncthreads();
+    if (W.h_active) slice_counts(Tb, W.ws, a);
+    __syncthreads();
     unsigned n_sure = 0u;
+    u64 acc_all = 0ull;  // exact mass of every column of the slice
+    // one column the slow way: history columns and the ragged end of the row
+    auto one = [&](float z, int idx) {
+      int b;
+      const float w = mass_term(z, W.C, b);
+      const bool below = z < W.C.g;
+      const u64 m = below ? mass_fix_below(w) : mass_fix(w);
+      acc_all += m;
+      if (!below || b < bstar) {
+        const unsigned hot = use_hot ? hot_bit(hot_bits, (uint32_t)idx) : 0u;
+        atomicAdd(&ltile[hot], m);
+        ++n_sure;
+      } else if (b == bstar) {
+        const unsigned s = atomicAdd(&l_n, 1u);
+        if (s < (unsigned)RCAP) lrl[s] = ((u64)__float_as_uint(z) << 32) | (u64)(uint32_t)idx;
+      }
+    };
+    if (W.h_active) for_history_columns<DT>(Tb, W, rowp, c0, V, one);
+    u64 acc0 = 0ull, acc1 = 0ull;
 #pragma unroll
     for (int j = 0; j < G; ++j) {
       const int idx0 = c0 + (j * WT + tid) * EPL;
-      u64 acc0 = 0ull, acc1 = 0ull;
-      auto one = [&](float z, int idx, bool hot) {
-        if (W.h_active && slice_bit(idx - c0, Tb)) z = slice_value(z, idx - c0, Tb, W);
-        int b;
-        const float w = mass_term(z, W.C, b);
-        const bool below = z < W.C.g;
-        if (!below || b < bstar) {
-          const u64 m = below ? mass_fix_below(w) : mass_fix(w);
-          if (hot) acc1 += m; else acc0 += m;
-          ++n_sure;
-        } else if (b == bstar) {
-          const unsigned s = atomicAdd(&l_n, 1u);
-          if (s < (unsigned)RCAP) lrl[s] = ((u64)__float_as_uint(z) << 32) | (u64)(uint32_t)idx;
-        }
-      };
       if (idx0 + EPL <= V) {
         float z[EPL];
         Io<DT>::unpack(A[j], z);
         bool any_top = false, any_edge = false;
-        if (W.h_active) {
-          const uint32_t nib = (Tb.bm[(idx0 - c0) >> 5] >> ((unsigned)(idx0 - c0) & 31u)) & EMASK;
-          if (nib) {
-#pragma unroll
-            for (int e = 0; e < EPL; ++e) if ((nib >> e) & 1u) z[e] = slice_value(z[e], idx0 - c0 + e, Tb, W);
-          }
-        }
+        // history columns were handled above: here they are skipped
+        const uint32_t live = W.h_active ? ~((Tb.bm[(idx0 - c0) >> 5] >> ((unsigned)(idx0 - c0) & 31u)) & EMASK) : ~0u;
+        uint32_t g0 = 0u, g1 = 0u, gall = 0u;  // group sums: <= 8 masses of <= 2^28
 #pragma unroll
         for (int e = 0; e < EPL; ++e) {  // straight-line; the rare cases follow under wave-wide tests
+          if (!((live >> e) & 1u)) z[e] = -INFINITY;  // no mass, no bin of interest ...
           int b;
           const float w = mass_term(z[e], W.C, b);
           const bool below = z[e] < W.C.g;
-          const bool sure = !below || b < bstar;
-          const u64 m = (sure && below) ? mass_fix_below(w) : 0ull;
+          const bool sure = ((live >> e) & 1u) && (!below || b < bstar);
+          const uint32_t m = below ? (uint32_t)mass_fix_below(w) : 0u;
+          const uint32_t ms = sure ? m : 0u;
           const bool hot = ((hq[j] >> e) & 1u) != 0u;
-          acc0 += hot ? 0ull : m;
-          acc1 += hot ? m : 0ull;
+          gall += m;
+          g0 += hot ? 0u : ms;
+          g1 += hot ? ms : 0u;
           n_sure += sure ? 1u : 0u;
           any_top = any_top || !below;
-          any_edge = any_edge || (below && b == bstar);
+          any_edge = any_edge || (((live >> e) & 1u) && below && b == bstar);
         }
+        acc0 += (u64)g0; acc1 += (u64)g1; acc_all += (u64)gall;
         if (__ballot(any_top)) {
 #pragma unroll
           for (int e = 0; e < EPL; ++e) {
             if (!(z[e] < W.C.g)) {
               int b;
               const u64 m = mass_fix(mass_term(z[e], W.C, b));
+              acc_all += m;
               if ((hq[j] >> e) & 1u) acc1 += m; else acc0 += m;
             }
           }
@@ -332,29 +400,31 @@ __global__ __launch_bounds__(WT) void wide_classify_kernel(const SampleArgs a) {
           for (int e = 0; e < EPL; ++e) {
             int b;
             (void)mass_term(z[e], W.C, b);
-            if (z[e] < W.C.g && b == bstar) {
+            if (((live >> e) & 1u) && z[e] < W.C.g && b == bstar) {
               const unsigned s = atomicAdd(&l_n, 1u);
               if (s < (unsigned)RCAP) lrl[s] = ((u64)__float_as_uint(z[e]) << 32) | (u64)(uint32_t)(idx0 + e);
             }
           }
         }
       } else {
-        for (int idx = idx0; idx < V; ++idx) one(Io<DT>::one(rowp + idx), idx, (hq[j] >> (idx - idx0)) & 1u);
+        for (int idx = idx0; idx < V; ++idx)
+          if (!(W.h_active && slice_bit(idx - c0, Tb))) one(Io<DT>::one(rowp + idx), idx);
       }
-      const u64 s0 = wave_sum(acc0), s1 = wave_sum(acc1);
-      if (lane == 0) { if (s0) atomicAdd(&ltile[j], s0); if (s1) atomicAdd(&ltile[G + j], s1); }
     }
-    unsigned ns = n_sure, dz = 0u; u64 mx = 0ull, dsum = 0ull;
+    {
+      const u64 s0 = wave_sum(acc0);
+      if (lane == 0 && s0) atomicAdd(&ltile[0], s0);
+      if (use_hot) { const u64 s1 = wave_sum(acc1); if (lane == 0 && s1) atomicAdd(&ltile[1], s1); }
+    }
+    unsigned ns = n_sure, dz = 0u; u64 mx = 0ull, dsum = acc_all;
     blk_reduce<WNW>(S, ns, dz, mx, dsum);  // barriers inside: tile sums and the boundary list are complete
     u64* gt = reinterpret_cast<u64*>(W.ws + WS_TILES);
     uint32_t* sc = reinterpret_cast<uint32_t*>(W.ws + WS_SCAL);
-    if (tid < 2 * G) {
-      const int tile = c0 / T + (tid % G);
-      if (tile < 256) gt[(tid / G) * 256 + tile] = ltile[tid];
-    }
+    if (tid < 2 && sl < 256) gt[tid * 256 + sl] = ltile[tid];
     const unsigned nb = l_n;
     if (tid == 0) {
       if (ns) atomicAdd(&sc[2], ns);
+      if (dsum) atomicAdd(reinterpret_cast<u64*>(W.ws + WS_SCAL + 16), dsum);
       l_base = nb ? atomicAdd(&sc[3], nb) : 0u;
     }
     __syncthreads();
@@ -375,8 +445,8 @@ __device__ inline void hand_on(const SampleArgs& a, int row) {
 template <typename DT>
 __device__ inline bool finish_row(const SampleArgs& a, const WideRow& W, FS& S, SliceTabs& Tb, u64* rcmp, u64* rl,
                                   uint32_t* fcnt, u64* fmass, u64* mc, u64* mw, u64* tiles, simple_row_diag& dg) {
-  constexpr int EPL = Io<DT>::EPL;
-  constexpr int T = WT * EPL;
+  constexpr int T = SLC;            // a tile of the draw's walk is a slice
+  constexpr int EPT = T / WT;       // its columns per thread, contiguous
   const int tid = threadIdx.x;
   const int V = a.V;
   const StreamCtx& C = W.C;
@@ -385,27 +455,46 @@ __device__ inline bool finish_row(const SampleArgs& a, const WideRow& W, FS& S, 
   const DT* rowp = reinterpret_cast<const DT*>(a.logits) + (size_t)W.row * (size_t)a.stride;
   double u3[3];
   row_uniforms(a.seed, a.row_offset + (uint64_t)W.row, a.step, u3);
-  int bstar; u64 m_above, target, S_tot; unsigned in_bin;
-  find_cut(S, W, bstar, m_above, target, S_tot, in_bin);
-  if (bstar < 0 || in_bin > (unsigned)RCAP) return false;
+  // every value of the slot this workgroup needs is requested before the first barrier
   const uint32_t* sc = reinterpret_cast<const uint32_t*>(W.ws + WS_SCAL);
   const unsigned n_sure = as_global(sc)[2], n_r = as_global(sc)[3];
+  const u64 S_tot = as_global(reinterpret_cast<const u64*>(W.ws + WS_SCAL))[2];  // exact mass of the row
+  u64 tv[2], rv[RCAP / WT];
+#pragma unroll
+  for (int k = 0; k < 2; ++k) tv[k] = as_global(reinterpret_cast<const u64*>(W.ws + WS_TILES))[k * WT + tid];
+#pragma unroll
+  for (int k = 0; k < RCAP / WT; ++k) rv[k] = as_global(reinterpret_cast<const u64*>(W.ws + WS_RL))[k * WT + tid];  // stale beyond n_r
+  XPHASE(0);
+  const int bstar = find_cut(S, W);
+  XPHASE(1);
+  if (bstar < 0) return false;
   if (n_r > (unsigned)RCAP || n_r == 0u) return false;
   if (tid == 0) { S.n2 = 0u; S.cut_k = 0ull; S.bd = -1; S.bp = -1; S.kmax = 0u; S.nunc = 0xFFFFFFFFu; S.out_id = -1; S.out_w = 0ull; }
-  for (int i = tid; i < 512; i += WT) tiles[i] = as_global(reinterpret_cast<const u64*>(W.ws + WS_TILES))[i];
+  tiles[tid] = tv[0]; tiles[WT + tid] = tv[1];
+  const u64 msure = tv[0] + tv[1];
   for (int i = tid; i < NBF; i += WT) { fcnt[i] = 0u; fmass[i] = 0ull; }
-  __syncthreads();
+  // exact masses from here: the columns surely inside must stay below the target, the collected bin must reach it
+  const u64 m_above = blk_sum_u64<WNW>(S, msure);  // barriers inside
+  const u64 target = (u64)__double2ull_ru((double)W.top_p * (double)S_tot);
+  if (m_above >= target) return false;
   // -- the boundary bin, exactly: shortest prefix in the total order whose mass reaches the target --
-  for (unsigned t = tid; t < n_r; t += WT) {
-    const u64 e = as_global(reinterpret_cast<const u64*>(W.ws + WS_RL))[t];
-    const float z = __uint_as_float((uint32_t)(e >> 32));
-    int b;
-    const float w = mass_term(z, C, b);
-    const uint32_t key = fkey(z / W.tau);
-    rcmp[t] = composite(key, (uint32_t)e);
-    rl[t] = mass_fix_below(w);
-    atomicMax(&S.kmax, key);
-    atomicMin(&S.nunc, key);
+  {
+    uint32_t kmax_t = 0u, kmin_t = 0xFFFFFFFFu;
+#pragma unroll
+    for (int k = 0; k < RCAP / WT; ++k) {
+      const unsigned t = (unsigned)(k * WT + tid);
+      if (t >= n_r) continue;
+      const u64 e = rv[k];
+      const float z = __uint_as_float((uint32_t)(e >> 32));
+      int b;
+      const float w = mass_term(z, C, b);
+      const uint32_t key = fkey(z / W.tau);
+      rcmp[t] = composite(key, (uint32_t)e);
+      rl[t] = mass_fix_below(w);
+      kmax_t = max(kmax_t, key); kmin_t = min(kmin_t, key);
+    }
+    kmax_t = wave_max_u32(kmax_t); kmin_t = wave_min_u32(kmin_t);
+    if ((tid & 63) == 0) { atomicMax(&S.kmax, kmax_t); atomicMin(&S.nunc, kmin_t); }
   }
   __syncthreads();
   const uint32_t kmx = S.kmax, kmn = S.nunc;
@@ -447,6 +536,7 @@ __device__ inline bool finish_row(const SampleArgs& a, const WideRow& W, FS& S, 
   }
   __syncthreads();
   const u64 cut_c = S.cut_k;
+  XPHASE(2);
   if (cut_c == 0ull) return false;
   unsigned r_in = 0;
   for (unsigned t = tid; t < n_r; t += WT) {
@@ -487,17 +577,22 @@ __device__ inline bool finish_row(const SampleArgs& a, const WideRow& W, FS& S, 
   }
   __syncthreads();
   const int tstar = S.bd;
+  XPHASE(3);
   if (tstar < 0) return false;
   // -- the drawn id inside one tile --
-  const int c0 = (tstar * T / SLC) * SLC;
-  if (W.h_active) load_slice(Tb, W, a, c0);
-  u64 mloc[EPL]; u64 lsum = 0ull;
+  const int c0 = tstar * T;
+  float zv[EPT];  // requested before the tables' barriers
 #pragma unroll
-  for (int e = 0; e < EPL; ++e) {
-    const int idx = tstar * T + tid * EPL + e;
+  for (int e = 0; e < EPT; ++e) { const int idx = c0 + tid * EPT + e; zv[e] = (idx < V) ? Io<DT>::one(rowp + idx) : 0.0f; }
+  if (W.h_active) load_slice(Tb, W, a, c0);
+  XPHASE(4);
+  u64 mloc[EPT]; u64 lsum = 0ull;
+#pragma unroll
+  for (int e = 0; e < EPT; ++e) {
+    const int idx = c0 + tid * EPT + e;
     mloc[e] = 0ull;
     if (idx < V) {
-      float z = Io<DT>::one(rowp + idx);
+      float z = zv[e];
       if (W.h_active && slice_bit(idx - c0, Tb)) z = slice_value(z, idx - c0, Tb, W);
       const unsigned hot = use_hot ? hot_bit(hot_bits, (uint32_t)idx) : 0u;
       if (!use_hot || hot == cls) {
@@ -515,12 +610,13 @@ __device__ inline bool finish_row(const SampleArgs& a, const WideRow& W, FS& S, 
   blk_excl_scan2<WNW>(S, 0u, lsum, ce3, me3, ct3, tot3);
   u64 run = S.mab_d + me3;
 #pragma unroll
-  for (int e = 0; e < EPL; ++e) {
-    if (mloc[e] > 0ull && run <= tfix && run + mloc[e] > tfix) { S.out_id = tstar * T + tid * EPL + e; S.out_w = mloc[e]; }
+  for (int e = 0; e < EPT; ++e) {
+    if (mloc[e] > 0ull && run <= tfix && run + mloc[e] > tfix) { S.out_id = c0 + tid * EPT + e; S.out_w = mloc[e]; }
     run += mloc[e];
   }
   __syncthreads();
   dg.p_chosen = (float)((double)S.out_w / (double)S_K);
+  XPHASE(5);
   return S.out_id >= 0;
 }
 
@@ -557,6 +653,12 @@ __global__ __launch_bounds__(WT) void wide_finish_kernel(const SampleArgs a) {
 }
 
 }  // namespace fast
+
+#ifdef SIMPLE_PHASE_TIMES
+extern "C" int simple_debug_wide_phase_times(unsigned long long* dst_host, int n) {
+  return (int)hipMemcpyFromSymbol(dst_host, HIP_SYMBOL(simple::fast::g_wide_phase_times), sizeof(unsigned long long) * 8 * (size_t)n);  // n <= 2 * 8192
+}
+#endif
 
 hipError_t launch_wide(const SampleArgs& a, int dtype, hipStream_t st) {
   const dim3 grid(4096), fin(1024), blk(fast::WT);
