@@ -1,0 +1,166 @@
+"""GPU parity on the routes of the single-pass kernel and of the kernels behind it.
+
+Each case is built so that a known route must be taken (checked through the diagnostic flags) and
+the ids are compared with the CPU oracle row by row, to the bar of test_gpu_parity.py.  Routes:
+the sorted small-list epilogue, the long-list epilogue (top-k near the list's limit), the
+whole-vocabulary nucleus (sliced bins / classify / finish kernels; with history, SHVS, bf16, a
+ragged row end, more rows than workspace slots), and the rows the single-pass kernel must leave to
+the general kernel."""
+import numpy as np
+import pytest
+
+import parity_util as P
+from paper_2512_00719_amd import synth
+
+pytestmark = pytest.mark.gpu
+
+WIDE, SHVS, GENERAL = 4, 8, 128  # diagnostic flag bits of the C boundary
+
+
+def _head_history(z, lens, rng, head=300):
+    """History ids drawn (with repeats) from the head of each row's distribution."""
+    B = z.shape[0]
+    top = np.argsort(-z, axis=1)[:, :head]
+    hist_ptr = np.concatenate([[0], np.cumsum(lens)]).astype(np.int64)
+    ids = [rng.choice(top[b], int(lens[b])) for b in range(B)]
+    return hist_ptr, (np.concatenate(ids) if ids else np.zeros(0)).astype(np.int32)
+
+
+def _run(w, steps=(0, 1), sampler=None, dev=None):
+    out = []
+    for step in steps:
+        ids, dg = P.run_gpu(w, step, sampler=sampler, dev=dev)
+        P.compare(ids, dg, P.run_oracle(w, step), range(w.B))
+        out.append((ids, dg))
+    return out
+
+
+def _flat_logits(rng, B, V, sigma=1.2):
+    """Rows without a dominant head: a nucleus of 0.9 and more spans thousands of columns."""
+    return (rng.standard_normal((B, V)) * sigma).astype(np.float32)
+
+
+def test_whole_vocabulary_nucleus_with_history_f32_ragged_row_end():
+    import torch
+    rng = np.random.default_rng(21)
+    B, V, stride = 10, 33_001, 33_004  # V is no multiple of the vector width: the last group is partial
+    z = _flat_logits(rng, B, V)
+    lens = rng.integers(200, 1500, B)
+    hist_ptr, hist_ids = _head_history(z, lens, rng, head=2000)
+    params = synth.make_params(B, temperature=[1.0, 0.9, 1.1, 1.3, 0.8] * 2, top_p=[0.9, 0.95, 0.8, 0.99, 0.97] * 2,
+                               rep_penalty=[1.2, 1.05] * 5, freq_penalty=[0.3, 0.0] * 5, pres_penalty=[0.0, 0.2] * 5,
+                               n_prompt=[0, 100, 5000, 7, 300] * 2)
+    w = synth.Workload("wide-hist", B, V, "f32", z, params, hist_ptr, hist_ids)
+    padded = np.full((B, stride), 1e30, np.float32)  # padding must never be read as a logit
+    padded[:, :V] = z
+    dev = P.to_device(w)
+    dev["logits"] = torch.from_numpy(padded).cuda()
+    for ids, dg in _run(w, steps=(0, 1, 2), dev=dev):
+        f = dg["flags"]
+        assert ((f & WIDE) > 0).sum() >= 8
+        assert not ((f & WIDE) > 0)[(f & GENERAL) > 0].any()  # these rows were finished by the sliced kernels
+
+
+def test_whole_vocabulary_nucleus_bf16_shvs_history():
+    rng = np.random.default_rng(22)
+    B, V = 8, 40_000 + 8
+    z32 = _flat_logits(rng, B, V, sigma=1.5)
+    bits = synth.f32_to_bf16_bits(z32)  # many exact ties after rounding
+    zf = synth.bf16_bits_to_f32(bits)
+    lens = rng.integers(0, 1200, B)
+    hist_ptr, hist_ids = _head_history(zf, lens, rng, head=1000)
+    params = synth.make_params(B, temperature=[1.0, 0.7, 1.2, 1.0] * 2, top_p=[0.9, 0.97, 0.85, 0.999] * 2,
+                               rep_penalty=1.15, freq_penalty=0.1, pres_penalty=0.1, n_prompt=50)
+    hot = np.argsort(-zf.mean(axis=0))[:3000].astype(np.int32)
+    w = synth.Workload("wide-bf16-shvs", B, V, "bf16", bits, params, hist_ptr, hist_ids, hot_ids=np.sort(hot))
+    for ids, dg in _run(w, steps=(0, 1, 2, 3)):
+        f = dg["flags"]
+        assert ((f & WIDE) > 0).sum() >= 6 and ((f & SHVS) > 0).all()
+        assert not ((f & WIDE) > 0)[(f & GENERAL) > 0].any()
+
+
+def test_more_whole_vocabulary_rows_than_workspace_slots():
+    """Rows beyond the 2048 workspace slots of one launch fall to the general kernel; every id is still right."""
+    from paper_2512_00719_amd import binding
+    rng = np.random.default_rng(23)
+    B, V = 2100, 8192 + 64
+    z = _flat_logits(rng, B, V)
+    params = synth.make_params(B, temperature=1.0, top_p=0.9)
+    w = synth.Workload("wide-many", B, V, "f32", z, params, np.zeros(B + 1, np.int64), np.zeros(0, np.int32))
+    s = binding.Sampler(V, 0)
+    dev = P.to_device(w)
+    rows = sorted(set(rng.choice(B, 48, replace=False).tolist()) | {0, 1, B - 1})
+    ids, dg = P.run_gpu(w, 3, sampler=s, dev=dev)
+    P.compare(ids, dg, P.run_oracle(w, 3, rows=rows), rows)
+    f = dg["flags"]
+    assert (((f & WIDE) > 0) | ((f & GENERAL) > 0)).all() and ((f & WIDE) > 0).sum() >= 2048
+    assert B - 2048 <= ((f & GENERAL) > 0).sum() <= B - 2048 + 8
+    assert ids.min() >= 0 and ids.max() < V
+    ids2, _ = P.run_gpu(w, 3, sampler=s, dev=dev)
+    assert np.array_equal(ids, ids2)
+    s.close()
+
+
+def test_long_list_epilogue_top_k_near_the_limit():
+    rng = np.random.default_rng(24)
+    B, V = 12, 60_000
+    z = _flat_logits(rng, B, V, sigma=2.0)
+    lens = rng.integers(0, 800, B)
+    hist_ptr, hist_ids = _head_history(z, lens, rng, head=1500)
+    params = synth.make_params(B, temperature=[0.8, 1.0, 1.2] * 4, top_k=[1000, 1024, 700, 600, 900, 513] * 2,
+                               top_p=[1.0, 0.95, 0.9, 1.0, 0.99, 0.8] * 2, min_p=[0, 0, 0, 1e-4, 0, 0] * 2,
+                               rep_penalty=1.1, freq_penalty=0.2, pres_penalty=0.1)
+    w = synth.Workload("long-list", B, V, "f32", z, params, hist_ptr, hist_ids)
+    for ids, dg in _run(w, steps=(0, 1, 2)):
+        assert ((dg["flags"] & GENERAL) > 0).sum() <= 2  # the sampled threshold may miss now and then
+        assert dg["n_survivors"].max() > 512
+
+
+def test_rows_the_single_pass_kernel_must_leave_to_the_general_kernel():
+    rng = np.random.default_rng(25)
+    B, V = 8, 20_000
+    z = _flat_logits(rng, B, V, sigma=2.0)
+    lens = np.array([5000, 5000, 300, 300, 300, 0, 300, 300])
+    hist_ptr, hist_ids = _head_history(z, lens, rng, head=3000)
+    params = synth.make_params(
+        B, temperature=[1.0, 1.0, 1.0, 1.0, 0.9, 1.0, 1.0, 0.0],
+        top_k=[0, 50, 0, 40, 1500, 0, 0, 0],
+        top_p=[0.9, 0.9, 1.0, 0.9, 1.0, 1.0, 0.9, 1.0],
+        rep_penalty=[1.1, 1.1, 1.1, 0.9, 1.1, 1.0, 1.1, 1.2],       # row 3 raises logits
+        freq_penalty=[0.1, 0.1, 0.0, 0.0, 0.0, 0.0, -0.2, 0.0])     # row 6 too
+    w = synth.Workload("leave", B, V, "f32", z, params, hist_ptr, hist_ids)
+    for ids, dg in _run(w, steps=(0, 1)):
+        general = (dg["flags"] & GENERAL) > 0
+        # 0: nucleus over all of V with more history ids than the mass correction holds in registers;
+        # 2, 5: no truncation at all; 3, 6: penalties that raise logits; 4: top-k above the list's limit
+        assert general[[0, 2, 3, 4, 5, 6]].all()
+        assert not general[[1, 7]].any()
+
+
+def test_one_context_alternating_routes_call_after_call():
+    """The queues of a context alternate between launches: results must not depend on what the call before queued."""
+    from paper_2512_00719_amd import binding
+    rng = np.random.default_rng(26)
+    B, V = 16, 24_000
+    z = _flat_logits(rng, B, V)
+    empty = (np.zeros(B + 1, np.int64), np.zeros(0, np.int32))
+    wide = synth.Workload("a", B, V, "f32", z, synth.make_params(B, temperature=1.0, top_p=0.9), *empty)
+    topk = synth.Workload("b", B, V, "f32", z, synth.make_params(B, temperature=0.8, top_k=20, top_p=0.9), *empty)
+    plain = synth.Workload("c", B, V, "f32", z, synth.make_params(B, temperature=1.0), *empty)  # general kernel
+    s = binding.Sampler(V, 0)
+    want = {}
+    for step, w in enumerate([wide, topk, plain, wide, wide, plain, topk, topk, wide, plain, plain, wide]):
+        ids, dg = P.run_gpu(w, step % 3, sampler=s)
+        key = (w.name, step % 3)
+        if key not in want:
+            P.compare(ids, dg, P.run_oracle(w, step % 3), range(B))
+            want[key] = ids.copy()
+        assert np.array_equal(ids, want[key]), (step, w.name)
+        f = dg["flags"]
+        if w is wide:
+            assert ((f & WIDE) > 0).all() and not ((f & GENERAL) > 0).any()
+        if w is plain:
+            assert ((f & GENERAL) > 0).all()
+        if w is topk:
+            assert not ((f & (WIDE | GENERAL)) > 0).any()
+    s.close()
