@@ -283,12 +283,13 @@ __device__ __forceinline__ int finalize_small(FS& S, const RowCfg& R, unsigned n
   const float y_max = keyf(kmax);
   for (unsigned t = tid; t < n; t += NTHR) {
     const u64 c = mc[t];
-    unsigned r = 0;
-    for (unsigned q = 0; q < n; ++q) r += (mc[q] > c) ? 1u : 0u;
+    const unsigned r = count_greater(mc, n, c);
     sc[r] = c;
     sw[r] = R.greedy ? 0ull : wfix((uint32_t)(c >> 32), y_max);
   }
+  FPHASE(21);
   __syncthreads();
+  FPHASE(22);
   if (wave == 0) {
     int rc = FIN_DONE;
     if (R.greedy) {
@@ -367,7 +368,9 @@ __device__ __forceinline__ int finalize_small(FS& S, const RowCfg& R, unsigned n
     }
     if (lane == 0) S.e_rc = rc;
   }
+  FPHASE(23);
   __syncthreads();
+  FPHASE(24);
   if (S.e_rc != FIN_DONE) return S.e_rc;
   dg.n_survivors = (int)S.e_n;
   if (R.greedy) { dg.p_chosen = 1.0f; return FIN_DONE; }
@@ -382,8 +385,8 @@ __device__ __forceinline__ int finalize_small(FS& S, const RowCfg& R, unsigned n
   for (unsigned t = tid; t < n_s; t += NTHR) {
     const uint32_t my = sid[t];
     if (my == 0xFFFFFFFFu) continue;
-    u64 C = 0ull;
-    for (unsigned q = 0; q < n_s; ++q) C += (sid[q] <= my) ? sw[q] : 0ull;
+    unsigned dummy;
+    const u64 C = sum_where<false>(sid, sw, n_s, my, dummy);
     if (C > tfix && C - sw[t] <= tfix) { S.out_id = (int)my; S.out_w = sw[t]; }
   }
   __syncthreads();
@@ -447,8 +450,7 @@ __device__ __forceinline__ int finalize_long(FS& S, const RowCfg& R, unsigned n,
     const unsigned need = S.need_k;
     for (unsigned mi = tid; mi < nm; mi += NTHR) {
       const u64 cm = mc[mi];
-      unsigned r = 0;
-      for (unsigned q = 0; q < nm; ++q) r += (mc[q] > cm) ? 1u : 0u;
+      const unsigned r = count_greater(mc, nm, cm);
       if (r == need - 1u) S.cut_k = cm;
     }
     __syncthreads();
@@ -488,8 +490,8 @@ __device__ __forceinline__ int finalize_long(FS& S, const RowCfg& R, unsigned n,
       const u64 mab = S.mab_p;
       for (unsigned mi = tid; mi < nm; mi += NTHR) {
         const u64 cm = mc[mi], wm = mw[mi];
-        u64 G = mab; unsigned r = 0;
-        for (unsigned q = 0; q < nm; ++q) { const u64 cq = mc[q]; if (cq >= cm) G += mw[q]; if (cq > cm) ++r; }
+        unsigned r;
+        const u64 G = mab + sum_where<true>(mc, mw, nm, cm, r);
         if (G >= target && G - wm < target) { S.cut_p = cm; S.n_p = S.cab_p + r + 1u; }
       }
       __syncthreads();
@@ -575,8 +577,8 @@ __device__ __forceinline__ int finalize_long(FS& S, const RowCfg& R, unsigned n,
     const u64 mab = S.mab_d;
     for (unsigned mi = tid; mi < nm; mi += NTHR) {
       const u64 im = mc[mi], wm = mw[mi];
-      u64 C = mab;
-      for (unsigned q = 0; q < nm; ++q) if (mc[q] <= im) C += mw[q];
+      unsigned dummy;
+      const u64 C = mab + sum_where<false>(mc, mw, nm, im, dummy);
       if (C > tfix && C - wm <= tfix) { S.out_id = (int)im; S.out_w = wm; }
     }
   }

@@ -152,6 +152,37 @@ __device__ __forceinline__ uint32_t wave_min_u32(uint32_t v) {
   return v;
 }
 
+// All-pairs helpers over small LDS tables: eight entries are loaded before they are used, so the
+// reads overlap instead of each waiting out the LDS latency.
+// #{q < n : a[q] > c}
+__device__ __forceinline__ unsigned count_greater(const u64* a, unsigned n, u64 c) {
+  unsigned r = 0, q = 0;
+  for (; q + 8 <= n; q += 8) {
+    u64 v[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) v[j] = a[q + j];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) r += (v[j] > c) ? 1u : 0u;
+  }
+  for (; q < n; ++q) r += (a[q] > c) ? 1u : 0u;
+  return r;
+}
+// sum of w[q] over q < n with a[q] >= c (ge) or a[q] <= c (!ge); cnt_gt gets #{a[q] > c}
+template <bool GE, typename K>
+__device__ __forceinline__ u64 sum_where(const K* a, const u64* w, unsigned n, K c, unsigned& cnt_gt) {
+  u64 s = 0ull; unsigned r = 0, q = 0;
+  for (; q + 8 <= n; q += 8) {
+    K v[8]; u64 x[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) { v[j] = a[q + j]; x[j] = w[q + j]; }
+#pragma unroll
+    for (int j = 0; j < 8; ++j) { s += (GE ? v[j] >= c : v[j] <= c) ? x[j] : 0ull; r += (v[j] > c) ? 1u : 0u; }
+  }
+  for (; q < n; ++q) { const K v = a[q]; s += (GE ? v >= c : v <= c) ? w[q] : 0ull; r += (v > c) ? 1u : 0u; }
+  cnt_gt = r;
+  return s;
+}
+
 // Z' of a column that is in the history (section 2.2): repetition (sign-aware), then frequency,
 // then presence on generated tokens (count > 0); one float32 rounding per operation.  z / rep is
 // formed as fl32(double(z) * fl64(1 / rep)), which equals the IEEE float32 quotient: the product is
@@ -201,11 +232,13 @@ __device__ __forceinline__ float mass_term(float z, const StreamCtx& C, int& bin
 __device__ __forceinline__ u64 mass_fix(float w) { return (u64)(w * MSCALE + 0.5f); }
 // same integer for w <= 1 (every column below g), one conversion instruction
 __device__ __forceinline__ u64 mass_fix_below(float w) { return (u64)(uint32_t)(w * MSCALE + 0.5f); }
-// Mass of a column below g for the single-pass kernel's running total: exp((z - g) / tau) without
-// the exactly rounded tempered value (relative error of the total about 1e-6, inside the 1e-5
-// tolerance on probabilities); only decides whether the nucleus fits the list, and the list's target.
+// Mass of a column below g for the single-pass kernel's running total: exp((z - g) / tau) * 2^28
+// without the exactly rounded tempered value; the scale rides in the exponent and the conversion
+// truncates.  Relative error of the total below 1e-6 (rounding of the exponent at magnitude 28,
+// independent from column to column), inside the 1e-5 tolerance on probabilities; the total only
+// decides whether the nucleus fits the list, and the list's target.
 __device__ __forceinline__ uint32_t below_term(float z, const StreamCtx& C) {
-  return (uint32_t)(__builtin_amdgcn_exp2f((z - C.g) * C.l2e_tau) * MSCALE + 0.5f);
+  return (uint32_t)__builtin_amdgcn_exp2f(fmaf(z - C.g, C.l2e_tau, 28.0f));
 }
 __device__ __forceinline__ u64 hist_entry(float w) { return (1ull << 46) | mass_fix_below(w); }
 

@@ -529,8 +529,8 @@ __device__ inline bool finish_row(const SampleArgs& a, const WideRow& W, FS& S, 
     const u64 mab = S.mab_p;
     for (unsigned mi = tid; mi < nm; mi += WT) {
       const u64 cm = mc[mi], wm = mw[mi];
-      u64 Gm = mab;
-      for (unsigned q = 0; q < nm; ++q) Gm += (mc[q] >= cm) ? mw[q] : 0ull;
+      unsigned dummy;
+      const u64 Gm = mab + sum_where<true>(mc, mw, nm, cm, dummy);
       if (Gm >= target && Gm - wm < target) S.cut_k = cm;
     }
   }
