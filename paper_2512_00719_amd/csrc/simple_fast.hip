@@ -599,7 +599,7 @@ __global__ __launch_bounds__(NTHR, 4) void fast_rows_kernel(const SampleArgs a) 
   constexpr int NWV = NTHR / 64;
   constexpr int EPL = Io<DT>::EPL;
   constexpr int T = 64 * EPL * UNR;
-  constexpr int PER = CAPF / NTHR;
+  constexpr int PER = CAPF_PER_THREAD;
   typedef typename Io<DT>::Raw Raw;
   extern __shared__ __align__(16) unsigned char lds[];
   __shared__ FS S;

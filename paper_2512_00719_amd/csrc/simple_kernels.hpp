@@ -33,12 +33,12 @@ struct FastLayout {
   int threads;        // workgroup size the layout was made for (256 or 512)
 };
 
-constexpr int CAPF = 3072;    // candidate-list capacity of the single-pass kernel
+constexpr int CAPF_PER_THREAD = 12;  // candidate-list entries per thread the single-pass kernel's epilogue holds in registers
 constexpr int KMAXF = 1024;   // largest top-k its list certifies
 constexpr int32_t PENDING = -2;  // id left by the single-pass kernel on rows the general kernel completes
 constexpr int PEND_ROWS = 65536; // rows per launch (capacity of the pending-row queue)
-constexpr int WIDE_SLOTS = 2048; // rows per launch the whole-vocabulary-nucleus kernels can take
-constexpr uint32_t WIDE_SLOT_FIXED = 20544;  // workspace per such row, before its history tables
+constexpr int WIDE_SLOTS = 1024; // rows per launch the whole-vocabulary-nucleus kernels can take
+constexpr uint32_t WIDE_SLOT_FIXED = 53312;  // workspace per such row, before its history tables
 
 struct SampleArgs {
   const void* logits;

@@ -24,10 +24,10 @@ constexpr int MEMB = 512;    // entries the sorted epilogue handles
 constexpr int MEMB2 = 256;   // members of one bucket the long-list path resolves exactly
 constexpr int IDR = 16;      // history ids a thread keeps in registers
 constexpr double WSCALE = 17592186044416.0;  // 2^44: fixed-point scale of probability mass
-constexpr int NBW = 1024;               // bins of the mass histogram (whole-vocabulary nucleus)
-constexpr float BINS_PER_LOG2 = 32.0f;  // bin width: 1/32 of a factor two in probability
+constexpr int NBW = 2048;               // bins of the mass histogram (whole-vocabulary nucleus)
+constexpr float BINS_PER_LOG2 = 64.0f;  // bin width: 1/64 of a factor two in probability
 constexpr float MSCALE = 268435456.0f;  // 2^28: fixed-point scale of masses relative to the one at g
-constexpr int RCAP = 1024;              // columns of the boundary bin that can be resolved exactly
+constexpr int RCAP = 4096;              // columns of the boundary bin that can be resolved exactly
 constexpr float L2E_HI = 1.44269502162933349609375f, L2E_LO = 1.925963033500011e-8f;  // log2(e), split
 
 // Global-memory view of a pointer.  Inside out-of-line device functions the compiler cannot tell that
@@ -212,11 +212,11 @@ struct WideRec {  // 64 bytes: everything the later kernels need to know about t
   long long h0; uint32_t distinct, reserved;
 };
 constexpr int WQ_HEAD = 16;             // words before the records
-constexpr uint32_t WS_HIST = 0u;        // u64[NBW]: (count << 46 | mass) of the columns below g, by bin
-constexpr uint32_t WS_TILES = 8192u;    // u64[2][256]: survivors' mass per tile, tail class then hot class
-constexpr uint32_t WS_SCAL = 12288u;    // u64 mass at or above g; u32 sure survivors; u32 boundary columns
-constexpr uint32_t WS_RL = 12352u;      // u64[RCAP]: columns of the boundary bin (value bits << 32 | id)
-constexpr uint32_t WS_HT = 20544u;      // the row's history tables as the single-pass kernel laid them out in LDS
+constexpr uint32_t WS_HIST = 0u;        // u64[NBW]: reduced-precision mass of the columns below g, by bin
+constexpr uint32_t WS_TILES = 16384u;   // u64[2][256]: survivors' mass per tile, tail class then hot class
+constexpr uint32_t WS_SCAL = 20480u;    // u64 mass at or above g; u32 sure survivors; u32 boundary columns; u64 exact mass of the row
+constexpr uint32_t WS_RL = 20544u;      // u64[RCAP]: columns of the boundary bin (value bits << 32 | id)
+constexpr uint32_t WS_HT = 53312u;      // the row's history tables as the single-pass kernel laid them out in LDS
 // [0, WS_RL) must be zero when a row is queued
 
 // Mass of one column relative to the mass at y_g, w = exp(y - y_g) with y = fl32(z / tau), and the

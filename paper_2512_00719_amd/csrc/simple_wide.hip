@@ -5,14 +5,15 @@
 // here every queued row is cut into slices of 4096 columns that spread over the whole chip:
 //
 //   bins      per slice, the penalised, tempered logits below g are binned (bins linear in the
-//             tempered logit, 1/32 of a factor two in probability wide) with their masses relative
+//             tempered logit, 1/64 of a factor two in probability wide) with their masses relative
 //             to the mass at g, at reduced precision (32-bit LDS atomics); the mass at or above g
 //             is summed beside them.  This pass only has to point at the bin that holds the cut.
 //   classify  that bin follows from the cumulated masses; per tile, the exact (integer) masses of
 //             the columns surely inside are summed by class (tail / hot), the columns of the
 //             cut's bin are collected, and the exact mass of the whole row is summed.
 //   finish    one workgroup per row checks that the cut does lie in the collected bin (else the
-//             general kernel takes the row), finds it exactly among those columns (total order:
+//             general kernel takes the row), finds it exactly among those columns by a radix
+//             descent over (value, id) weighted by mass, however many of them tie (total order:
 //             value descending, id ascending), applies the SHVS acceptance test (section 5.3), walks
 //             the per-tile masses of the drawn class in ascending id and reads one tile a last time
 //             to locate the drawn id (inverse CDF, step (3) of section 2.1).
@@ -30,16 +31,19 @@ namespace fast {
 #ifdef SIMPLE_PHASE_TIMES  // profiling builds only: per-workgroup timestamps of the first kernel (100 MHz wall clock)
 __device__ unsigned long long g_wide_phase_times[2 * 8192 * 8];
 #define XPHASE(i) do { if (threadIdx.x == 0 && blockIdx.x < 8192) g_wide_phase_times[(8192 + blockIdx.x) * 8 + (i)] = wall_clock64(); } while (0)
+#define XWHY(code, v) do { if (threadIdx.x == 0 && blockIdx.x < 8192) { g_wide_phase_times[(8192 + blockIdx.x) * 8 + 6] = (code); g_wide_phase_times[(8192 + blockIdx.x) * 8 + 7] = (v); } } while (0)
 #define WPHASE(i) do { if (threadIdx.x == 0 && blockIdx.x < 8192) g_wide_phase_times[blockIdx.x * 8 + (i)] = wall_clock64(); } while (0)
 #else
 #define WPHASE(i) do { } while (0)
 #define XPHASE(i) do { } while (0)
+#define XWHY(code, v) do { } while (0)
 #endif
 
 constexpr int WT = 256;      // threads per workgroup
 constexpr int WNW = WT / 64;
 constexpr int SLC = 4096;    // columns per slice
 constexpr float BSCALE = 524288.0f;  // 2^19: scale of the first pass's masses
+constexpr int ICAP = 1024;   // columns of the boundary bin one slice can stage
 static_assert(WS_HT == WIDE_SLOT_FIXED, "workspace slot size");
 static_assert(sizeof(WideRec) == 64, "queue record size");
 
@@ -295,7 +299,7 @@ __global__ __launch_bounds__(WT, 6) void wide_classify_kernel(const SampleArgs a
   constexpr unsigned EMASK = (1u << EPL) - 1u;
   typedef typename Io<DT>::Raw Raw;
   __shared__ SliceTabs Tb;
-  __shared__ u64 lrl[RCAP];
+  __shared__ u64 lrl[ICAP];
   __shared__ u64 ltile[2];
   __shared__ unsigned l_n, l_base;
   __shared__ FS S;
@@ -351,7 +355,7 @@ __global__ __launch_bounds__(WT, 6) void wide_classify_kernel(const SampleArgs a
         ++n_sure;
       } else if (b == bstar) {
         const unsigned s = atomicAdd(&l_n, 1u);
-        if (s < (unsigned)RCAP) lrl[s] = ((u64)__float_as_uint(z) << 32) | (u64)(uint32_t)idx;
+        if (s < (unsigned)ICAP) lrl[s] = ((u64)__float_as_uint(z) << 32) | (u64)(uint32_t)idx;
       }
     };
     if (W.h_active) for_history_columns<DT>(Tb, W, rowp, c0, V, one);
@@ -402,7 +406,7 @@ __global__ __launch_bounds__(WT, 6) void wide_classify_kernel(const SampleArgs a
             (void)mass_term(z[e], W.C, b);
             if (((live >> e) & 1u) && z[e] < W.C.g && b == bstar) {
               const unsigned s = atomicAdd(&l_n, 1u);
-              if (s < (unsigned)RCAP) lrl[s] = ((u64)__float_as_uint(z[e]) << 32) | (u64)(uint32_t)(idx0 + e);
+              if (s < (unsigned)ICAP) lrl[s] = ((u64)__float_as_uint(z[e]) << 32) | (u64)(uint32_t)(idx0 + e);
             }
           }
         }
@@ -425,11 +429,13 @@ __global__ __launch_bounds__(WT, 6) void wide_classify_kernel(const SampleArgs a
     if (tid == 0) {
       if (ns) atomicAdd(&sc[2], ns);
       if (dsum) atomicAdd(reinterpret_cast<u64*>(W.ws + WS_SCAL + 16), dsum);
-      l_base = nb ? atomicAdd(&sc[3], nb) : 0u;
+      // more columns of the bin in one slice than the staging list holds: the count is pushed past
+      // the limit, so that the finishing kernel hands the row on
+      l_base = nb ? atomicAdd(&sc[3], nb > (unsigned)ICAP ? (unsigned)RCAP + 1u : nb) : 0u;
     }
     __syncthreads();
     const unsigned base = l_base;
-    for (unsigned t = tid; t < min(nb, (unsigned)RCAP); t += WT)
+    for (unsigned t = tid; t < min(nb, (unsigned)ICAP); t += WT)
       if (base + t < (unsigned)RCAP) reinterpret_cast<u64*>(W.ws + WS_RL)[base + t] = lrl[t];
     __syncthreads();
   }
@@ -443,8 +449,8 @@ __device__ inline void hand_on(const SampleArgs& a, int row) {
 }
 
 template <typename DT>
-__device__ inline bool finish_row(const SampleArgs& a, const WideRow& W, FS& S, SliceTabs& Tb, u64* rcmp, u64* rl,
-                                  uint32_t* fcnt, u64* fmass, u64* mc, u64* mw, u64* tiles, simple_row_diag& dg) {
+__device__ inline bool finish_row(const SampleArgs& a, const WideRow& W, FS& S, SliceTabs& Tb, u64* rcmp, uint32_t* rl,
+                                  u64* dmass, u64* tiles, simple_row_diag& dg) {
   constexpr int T = SLC;            // a tile of the draw's walk is a slice
   constexpr int EPT = T / WT;       // its columns per thread, contiguous
   const int tid = threadIdx.x;
@@ -459,91 +465,97 @@ __device__ inline bool finish_row(const SampleArgs& a, const WideRow& W, FS& S, 
   const uint32_t* sc = reinterpret_cast<const uint32_t*>(W.ws + WS_SCAL);
   const unsigned n_sure = as_global(sc)[2], n_r = as_global(sc)[3];
   const u64 S_tot = as_global(reinterpret_cast<const u64*>(W.ws + WS_SCAL))[2];  // exact mass of the row
-  u64 tv[2], rv[RCAP / WT];
+  u64 tv[2];
 #pragma unroll
   for (int k = 0; k < 2; ++k) tv[k] = as_global(reinterpret_cast<const u64*>(W.ws + WS_TILES))[k * WT + tid];
-#pragma unroll
-  for (int k = 0; k < RCAP / WT; ++k) rv[k] = as_global(reinterpret_cast<const u64*>(W.ws + WS_RL))[k * WT + tid];  // stale beyond n_r
   XPHASE(0);
   const int bstar = find_cut(S, W);
   XPHASE(1);
-  if (bstar < 0) return false;
-  if (n_r > (unsigned)RCAP || n_r == 0u) return false;
-  if (tid == 0) { S.n2 = 0u; S.cut_k = 0ull; S.bd = -1; S.bp = -1; S.kmax = 0u; S.nunc = 0xFFFFFFFFu; S.out_id = -1; S.out_w = 0ull; }
+  if (bstar < 0) { XWHY(1, 0); return false; }
+  if (n_r > (unsigned)RCAP || n_r == 0u) { XWHY(2, n_r); return false; }
+  if (tid == 0) { S.bd = -1; S.cut_k = 0ull; S.cut_p = ~0ull; S.out_id = -1; S.out_w = 0ull; }
   tiles[tid] = tv[0]; tiles[WT + tid] = tv[1];
   const u64 msure = tv[0] + tv[1];
-  for (int i = tid; i < NBF; i += WT) { fcnt[i] = 0u; fmass[i] = 0ull; }
   // exact masses from here: the columns surely inside must stay below the target, the collected bin must reach it
   const u64 m_above = blk_sum_u64<WNW>(S, msure);  // barriers inside
   const u64 target = (u64)__double2ull_ru((double)W.top_p * (double)S_tot);
-  if (m_above >= target) return false;
+  if (m_above >= target) { XWHY(3, 0); return false; }
   // -- the boundary bin, exactly: shortest prefix in the total order whose mass reaches the target --
   {
-    uint32_t kmax_t = 0u, kmin_t = 0xFFFFFFFFu;
+    u64 cmax_t = 0ull, cmin_t = ~0ull;
+    const u64* grl = reinterpret_cast<const u64*>(W.ws + WS_RL);
+    for (unsigned t0 = 0; t0 < n_r; t0 += 4u * WT) {  // four independent loads per thread and round
+      u64 e[4];
 #pragma unroll
-    for (int k = 0; k < RCAP / WT; ++k) {
-      const unsigned t = (unsigned)(k * WT + tid);
-      if (t >= n_r) continue;
-      const u64 e = rv[k];
-      const float z = __uint_as_float((uint32_t)(e >> 32));
-      int b;
-      const float w = mass_term(z, C, b);
-      const uint32_t key = fkey(z / W.tau);
-      rcmp[t] = composite(key, (uint32_t)e);
-      rl[t] = mass_fix_below(w);
-      kmax_t = max(kmax_t, key); kmin_t = min(kmin_t, key);
+      for (int k = 0; k < 4; ++k) { const unsigned t = t0 + (unsigned)(k * WT + tid); e[k] = (t < n_r) ? as_global(grl)[t] : 0ull; }
+#pragma unroll
+      for (int k = 0; k < 4; ++k) {
+        const unsigned t = t0 + (unsigned)(k * WT + tid);
+        if (t >= n_r) continue;
+        const float z = __uint_as_float((uint32_t)(e[k] >> 32));
+        int b;
+        const float w = mass_term(z, C, b);
+        const u64 c = composite(fkey(z / W.tau), (uint32_t)e[k]);
+        rcmp[t] = c;
+        rl[t] = (uint32_t)mass_fix_below(w);
+        cmax_t = (c > cmax_t) ? c : cmax_t; cmin_t = (c < cmin_t) ? c : cmin_t;
+      }
     }
-    kmax_t = wave_max_u32(kmax_t); kmin_t = wave_min_u32(kmin_t);
-    if ((tid & 63) == 0) { atomicMax(&S.kmax, kmax_t); atomicMin(&S.nunc, kmin_t); }
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) {
+      const u64 hi = __shfl_xor(cmax_t, o, 64), lo = __shfl_xor(cmin_t, o, 64);
+      cmax_t = (hi > cmax_t) ? hi : cmax_t; cmin_t = (lo < cmin_t) ? lo : cmin_t;
+    }
+    if ((tid & 63) == 0) { atomicMax(&S.cut_k, cmax_t); atomicMin(&S.cut_p, cmin_t); }
   }
   __syncthreads();
-  const uint32_t kmx = S.kmax, kmn = S.nunc;
-  const float y_hi = keyf(kmx);
-  const float sscale = (float)NBF / fmaxf(y_hi - keyf(kmn), 1e-30f);
-  auto sub_bin = [&](u64 c) { return (unsigned)min((int)((y_hi - keyf((uint32_t)(c >> 32))) * sscale), NBF - 1); };
-  for (unsigned t = tid; t < n_r; t += WT) {
-    const unsigned sb = sub_bin(rcmp[t]);
-    atomicAdd(&fcnt[sb], 1u);
-    atomicAdd(&fmass[sb], rl[t]);
-  }
-  __syncthreads();
+  // Radix descent, eight bits at a time from the top of (key, ~id): among the columns that share the
+  // digits fixed so far, the digit whose mass carries the running total over the target is fixed
+  // next.  Digits on which all columns agree are skipped; after the last one the cut column is known.
+  u64 cut_found = 0ull;
   {
-    const u64 m2 = (tid < NBF) ? fmass[tid] : 0ull;
-    unsigned ce2, ct2; u64 me2, mt2;
-    blk_excl_scan2<WNW>(S, 0u, m2, ce2, me2, ct2, mt2);
-    if (tid < NBF && m2 > 0ull && m_above + me2 < target && m_above + me2 + m2 >= target) { S.bp = tid; S.mab_p = m_above + me2; }
-  }
-  __syncthreads();
-  const int sbp = S.bp;
-  if (sbp < 0) return false;  // the masses of the passes disagree
-  for (unsigned t = tid; t < n_r; t += WT) {
-    if ((int)sub_bin(rcmp[t]) == sbp) {
-      const unsigned s = atomicAdd(&S.n2, 1u);
-      if (s < (unsigned)MEMB2) { mc[s] = rcmp[t]; mw[s] = rl[t]; }
+    const u64 cmax = S.cut_k, differ = S.cut_k ^ S.cut_p;
+    u64 prefix = 0ull, mask = 0ull, acc = m_above;
+    bool ok = true;
+    for (int shift = 56; shift >= 0; shift -= 8) {
+      if ((differ >> shift) == 0ull) {  // no column differs here or above
+        prefix |= cmax & (0xFFull << shift); mask |= 0xFFull << shift;
+        continue;
+      }
+      dmass[tid] = 0ull;
+      if (tid == 0) S.bp = -1;
+      __syncthreads();
+      for (unsigned t = tid; t < n_r; t += WT) {
+        const u64 c = rcmp[t];
+        if ((c & mask) == prefix) atomicAdd(&dmass[(unsigned)(c >> shift) & 0xFFu], (u64)rl[t]);
+      }
+      __syncthreads();
+      {  // thread i looks at digit 255 - i: the exclusive scan sums the digits above it
+        const u64 m = dmass[255 - tid];
+        unsigned ce2, ct2; u64 me2, mt2;
+        blk_excl_scan2<WNW>(S, 0u, m, ce2, me2, ct2, mt2);
+        if (m > 0ull && acc + me2 < target && acc + me2 + m >= target) { S.bp = 255 - tid; S.mab_p = acc + me2; }
+      }
+      __syncthreads();
+      const int d = S.bp;
+      if (d < 0) { ok = false; break; }  // the collected columns do not reach the target: the passes disagree
+      acc = S.mab_p;
+      prefix |= (u64)(unsigned)d << shift; mask |= 0xFFull << shift;
+      __syncthreads();
     }
+    if (differ == 0ull && m_above + (u64)rl[0] < target) ok = false;  // a single column, and it does not reach the target
+    if (!ok) { XWHY(4, 0); return false; }
+    cut_found = prefix;
   }
-  __syncthreads();
-  const unsigned nm = S.n2;
-  if (nm > (unsigned)MEMB2) return false;
-  {
-    const u64 mab = S.mab_p;
-    for (unsigned mi = tid; mi < nm; mi += WT) {
-      const u64 cm = mc[mi], wm = mw[mi];
-      unsigned dummy;
-      const u64 Gm = mab + sum_where<true>(mc, mw, nm, cm, dummy);
-      if (Gm >= target && Gm - wm < target) S.cut_k = cm;
-    }
-  }
-  __syncthreads();
-  const u64 cut_c = S.cut_k;
+  const u64 cut_c = cut_found;
   XPHASE(2);
-  if (cut_c == 0ull) return false;
+  if (cut_c == 0ull) { XWHY(6, 0); return false; }
   unsigned r_in = 0;
   for (unsigned t = tid; t < n_r; t += WT) {
     if (rcmp[t] >= cut_c) {
       const uint32_t id = 0xFFFFFFFFu - (uint32_t)rcmp[t];
       const unsigned hot = use_hot ? hot_bit(hot_bits, id) : 0u;
-      atomicAdd(&tiles[hot * 256u + id / (unsigned)T], rl[t]);
+      atomicAdd(&tiles[hot * 256u + id / (unsigned)T], (u64)rl[t]);
       ++r_in;
     }
   }
@@ -566,7 +578,7 @@ __device__ inline bool finish_row(const SampleArgs& a, const WideRow& W, FS& S, 
   const double u = use_hot ? (pick_hot ? u3[0] : u3[2]) : u3[0];
   dg.n_survivors = (int)ns;
   dg.s_k = (double)S_tot / (double)MSCALE * exp((double)C.y_g - (double)keyf(W.kmax));
-  if (S_cls == 0ull) return false;
+  if (S_cls == 0ull) { XWHY(7, 0); return false; }
   u64 tfix = (u64)__double2ull_rd(u * (double)S_cls);
   if (tfix >= S_cls) tfix = S_cls - 1ull;
   {
@@ -578,7 +590,7 @@ __device__ inline bool finish_row(const SampleArgs& a, const WideRow& W, FS& S, 
   __syncthreads();
   const int tstar = S.bd;
   XPHASE(3);
-  if (tstar < 0) return false;
+  if (tstar < 0) { XWHY(8, 0); return false; }
   // -- the drawn id inside one tile --
   const int c0 = tstar * T;
   float zv[EPT];  // requested before the tables' barriers
@@ -624,11 +636,8 @@ template <typename DT>
 __global__ __launch_bounds__(WT) void wide_finish_kernel(const SampleArgs a) {
   __shared__ SliceTabs Tb;
   __shared__ u64 rcmp[RCAP];
-  __shared__ u64 rl[RCAP];
-  __shared__ uint32_t fcnt[NBF];
-  __shared__ u64 fmass[NBF];
-  __shared__ u64 mc[MEMB2];
-  __shared__ u64 mw[MEMB2];
+  __shared__ uint32_t rl[RCAP];
+  __shared__ u64 dmass[256];
   __shared__ u64 tiles[512];
   __shared__ FS S;
   const int tid = threadIdx.x;
@@ -641,7 +650,7 @@ __global__ __launch_bounds__(WT) void wide_finish_kernel(const SampleArgs a) {
     dg.s_k = 0.0; dg.p_chosen = 0.0f; dg.n_survivors = 0; dg.reserved = 0u;
     dg.flags = SIMPLE_DIAG_WIDE | W.flags;
     if (a.hot_bits && a.hot_flags && *a.hot_flags) dg.flags |= SIMPLE_DIAG_BAD_HOT_SET;
-    const bool ok = finish_row<DT>(a, W, S, Tb, rcmp, rl, fcnt, fmass, mc, mw, tiles, dg);
+    const bool ok = finish_row<DT>(a, W, S, Tb, rcmp, rl, dmass, tiles, dg);
     if (tid == 0) {
       if (!ok) hand_on(a, W.row);
       else {
