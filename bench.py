@@ -30,6 +30,41 @@ def algorithmic_bytes(B: int, V: int, esize: int, nnz_total: int) -> int:
     return B * V * esize + 4 * nnz_total + 44 * B
 
 
+KERNEL_SOURCES = ("simple_fast.hip", "simple_rowdev.hpp", "simple_device.hpp", "simple_kernels.hpp")
+
+
+def kernel_source_hash() -> str:
+    """sha256 over the sources of the dominant kernel: recorded counter readings only hold for the
+    kernel they were taken on."""
+    import hashlib
+    h = hashlib.sha256()
+    for f in KERNEL_SOURCES:
+        with open(os.path.join(ROOT, "paper_2512_00719_amd", "csrc", f), "rb") as fh:
+            h.update(fh.read())
+    return h.hexdigest()
+
+
+def recorded_traffic(config: int):
+    """HBM bytes per launch of the dominant kernel from the rocprofv3 FETCH_SIZE / WRITE_SIZE runs
+    summarised under profiles/, or None if there is no summary for this workload or the kernel's
+    sources have changed since the counters were taken."""
+    path = os.path.join(ROOT, "profiles", f"fast_rows_kernel_C{config}_hbm_traffic.txt")
+    if not os.path.exists(path):
+        return None
+    fields = {}
+    with open(path) as fh:
+        for line in fh:
+            if ":" in line and not line.startswith("#"):
+                k, v = line.split(":", 1)
+                fields[k.strip()] = v.strip()
+    if fields.get("kernel_source_sha256") != kernel_source_hash():
+        return None
+    try:
+        return int(fields["traffic_bytes_per_launch"])
+    except (KeyError, ValueError):
+        return None
+
+
 def cpu_baseline(w, budget_s: float = 12.0) -> dict:
     """The CPU oracle, as it stands, timed on a bounded sample of rows of the same workload."""
     from oracle import simple_oracle as O
@@ -59,6 +94,9 @@ def main() -> int:
     ap.add_argument("--H", type=int, default=None, help="hot-set size for configs 4 and 5")
     ap.add_argument("--copies", type=int, default=0, help="distinct input copies to rotate over (0 = auto: >= 1 GiB)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-probe-mib", type=int, default=0,
+                    help="after the timed region, run one plain device copy of this many MiB (a kernel of known "
+                         "HBM traffic, to scale rocprofv3 FETCH_SIZE / WRITE_SIZE readings)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU; --gpus N with N > 1 is not supported "
@@ -141,6 +179,12 @@ def main() -> int:
         stats["H"] = int(w.hot_ids.size)
     achieved = alg_bytes / (kern_ms * 1e-3) / 1e9
     s.close()
+    if args.copy_probe_mib > 0:
+        src = torch.ones(args.copy_probe_mib << 18, dtype=torch.float32, device=dev)
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        dst.copy_(src)
+        torch.cuda.synchronize()
 
     result = {
         "metric": "sampled rows/sec + achieved HBM GB/s (fraction of peak), B=1024 V=128,256 fp32",
@@ -152,7 +196,7 @@ def main() -> int:
                                if args.config in (3, 5) else f"{w.name}: B={w.B} V={w.V} {w.dtype}, {nnz_max} history ids/row",
                    "input_copies_rotated": n_copies, **stats},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": PEAK_HBM_GBS, "unit": "GB/s",
-                     "frac": achieved / PEAK_HBM_GBS, "traffic": None,
+                     "frac": achieved / PEAK_HBM_GBS, "traffic": recorded_traffic(args.config),
                      "kernel": "simple::fast::fast_rows_kernel", "kernel_ms": kern_ms, "algorithmic_bytes": alg_bytes,
                      "step_ms": ms_per_step, "step_frac": alg_bytes / (ms_per_step * 1e-3) / 1e9 / PEAK_HBM_GBS},
     }
