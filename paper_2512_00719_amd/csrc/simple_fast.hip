@@ -9,7 +9,7 @@
 //             by the rank of the id among the set bits.  The V-wide histograms of section 2.2 are
 //             never materialised; a column's penalty is looked up only where its bit is set, so
 //             unpenalised columns are never touched (column-wise penalties, section 5.2).
-//   sample    every wave's first two tiles (penalised) give, by wave-ballot radix selection, a
+//   sample    every wave's first two tiles (history columns masked) give, by wave-ballot bisection, a
 //             value g that is expected to admit a small multiple of the requested prefix length.
 //   stream    one coalesced pass of 16-byte loads per lane over the raw logits.  Columns with
 //             z >= g go to an LDS candidate list that now occupies the history's region (penalties
@@ -24,9 +24,10 @@
 //             (Eq. (2), step (3)) use integer (fixed-point) masses, so no result depends on the
 //             order in which waves appended candidates.  SHVS (section 5.3): acceptance test on the
 //             hot mass, then the draw walks the hot or the tail survivors only.
-// Rows the kernel cannot certify (threshold missed, list overflow, ties wider than a table,
-// penalties that raise logits, parameter errors, a nucleus wider than the list) are queued for the
-// general kernel, which runs next on the same stream.
+// A row whose nucleus over the whole vocabulary is wider than the list is queued, with its threshold
+// and its history tables, for the sliced kernels that run next on the stream.  Rows the kernel
+// cannot certify (threshold missed, list overflow, ties wider than a table, penalties that raise
+// logits, parameter errors) are queued for the general kernel, which runs last.
 #include <hip/hip_runtime.h>
 #include <math.h>
 #include <stdint.h>
