@@ -91,7 +91,7 @@ typedef struct {
 enum {
   SIMPLE_DIAG_ERROR = 1u << 0,         /* id is -1 */
   SIMPLE_DIAG_GREEDY = 1u << 1,
-  SIMPLE_DIAG_WIDE = 1u << 2,          /* K_b did not fit the on-chip candidate list: multi-pass route */
+  SIMPLE_DIAG_WIDE = 1u << 2,          /* K_b did not fit the on-chip candidate list (or is all of V): multi-pass route */
   SIMPLE_DIAG_SHVS = 1u << 3,          /* a hot set was used */
   SIMPLE_DIAG_ACCEPTED = 1u << 4,      /* SHVS hot candidate accepted */
   SIMPLE_DIAG_CAREFUL = 1u << 5,       /* candidate list overflowed: segment replayed in small pieces */

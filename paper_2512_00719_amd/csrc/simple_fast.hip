@@ -331,7 +331,7 @@ __device__ __forceinline__ int finalize_small(FS& S, const RowCfg& R, unsigned n
         m_cert = key_thr > key_g;
       }
       const bool known = R.k_on || p_found || m_cert;
-      if (!known) rc = (R.need_sum && !R.minp_on) ? FIN_WIDE : FIN_PENDING;
+      if (!known) rc = ((R.need_sum && !R.minp_on) || (!R.k_on && !R.p_on && R.minp_on)) ? FIN_WIDE : FIN_PENDING;
       // every cut is a prefix of the sorted order; the first entry always survives
       const bool use_hot = hot_bits != nullptr;
       unsigned okm = 0u, hotm = 0u;
@@ -511,7 +511,7 @@ __device__ __forceinline__ int finalize_long(FS& S, const RowCfg& R, unsigned n,
     if (key_thr > key_g) { cut_m = (u64)key_thr << 32; m_cert = true; }
   }
   const bool known = R.k_on || p_found || m_cert;
-  if (!known) return (R.need_sum && !R.minp_on) ? FIN_WIDE : FIN_PENDING;
+  if (!known) return ((R.need_sum && !R.minp_on) || (!R.k_on && !R.p_on && R.minp_on)) ? FIN_WIDE : FIN_PENDING;
   if (R.k_on && R.p_on && !p_found) { FWHY(203); return FIN_PENDING; }  // cannot happen: the top-k prefix holds its own mass
   u64 cut = cut_k;
   if (p_found && cut_p > cut) cut = cut_p;
@@ -643,8 +643,11 @@ __global__ __launch_bounds__(NTHR, 4) void fast_rows_kernel(const SampleArgs a) 
   const bool no_trunc = !R.greedy && !R.k_on && !R.p_on && !R.minp_on;
   // the mass correction below needs every history id in the owners' registers
   const bool sum_ok = !R.need_sum || !h_active || nnz <= IDR * NTHR;
-  const bool eligible = !bad_par && !too_long && !no_trunc && (!h_active || lowering) && sum_ok &&
-                        (R.greedy || !R.k_on || par.top_k <= KMAXF);
+  // rows without any truncation keep no candidate list: they only pass through here on their way
+  // to the kernels of the whole-vocabulary routes
+  const bool eligible = no_trunc ? (!bad_par && !too_long)
+                                 : (!bad_par && !too_long && (!h_active || lowering) && sum_ok &&
+                                    (R.greedy || !R.k_on || par.top_k <= KMAXF));
   if (!eligible) {  // the general kernel takes the row (it also reports parameter errors)
     FWHY(1);
     if (tid == 0) queue_pending(a, row);
@@ -676,8 +679,11 @@ __global__ __launch_bounds__(NTHR, 4) void fast_rows_kernel(const SampleArgs a) 
       R.u_draw = u[0]; R.u_acc = u[1]; R.u_tail = u[2];
     }
     __syncthreads();
-    // ---- presence mask of the history (in the shared region) ----
-    if (H.active) build_bitmap<NTHR>(S, H, ids, hist, nnz, V);
+    // ---- presence mask of the history (in the shared region); all tables for a row that leaves early ----
+    if (H.active) {
+      if (no_trunc) { unsigned own; build_history<NTHR>(S, H, ids, hist, nnz, par.n_prompt, V, own); }
+      else build_bitmap<NTHR>(S, H, ids, hist, nnz, V);
+    }
   }
   const uint32_t* hot_bits = R.greedy ? nullptr : a.hot_bits;
   FPHASE(1);
@@ -749,6 +755,46 @@ __global__ __launch_bounds__(NTHR, 4) void fast_rows_kernel(const SampleArgs a) 
     C.need_sum = R.need_sum;
     C.l2e_tau = (float)(1.4426950408889634 / (double)R.tau);
   }
+  // Hands the row to the kernels of the whole-vocabulary routes: a queue record, a cleared workspace
+  // slot and the row's history tables (rebuilt first if the region no longer holds them).  False if
+  // no slot is free.  All threads call.
+  auto queue_wide = [&](uint32_t mode, bool tables_live) -> bool {
+    __syncthreads();
+    if (H.active && !tables_live) {
+      int ids2[IDR];
+#pragma unroll
+      for (int j = 0; j < IDR; ++j) { const int i = tid + j * NTHR; ids2[j] = (i < nnz) ? hist[i] : -1; }
+      unsigned own;
+      build_history<NTHR>(S, H, ids2, hist, nnz, par.n_prompt, V, own);
+    }
+    if (tid == 0) S.e_n = atomicAdd(&a.wq[a.parity], 1u);
+    __syncthreads();
+    const unsigned slot = S.e_n;
+    const unsigned hb = H.active ? (a.F.cnt + (unsigned)((nnz + 3) / 2) * 4u + 15u) / 16u : 0u;  // 16-byte units of history tables
+    if (slot >= (unsigned)a.wide_slots || WS_HT + hb * 16u > a.ws_stride) return false;
+    u32x4* ws = reinterpret_cast<u32x4*>(a.wws + (size_t)slot * a.ws_stride);
+    const u32x4 zero = {0u, 0u, 0u, 0u};
+    for (unsigned i = tid; i < WS_RL / 16u; i += NTHR) ws[i] = zero;
+    if (H.active) {
+      const u32x4* src = reinterpret_cast<const u32x4*>(lds);
+      for (unsigned i = tid; i < hb; i += NTHR) ws[WS_HT / 16u + i] = src[i];
+    }
+    if (tid == 0) {
+      WideRec rec;
+      rec.row = (uint32_t)row; rec.g = C.g; rec.mode = mode; rec.flags = S.flags & 0x3FFFFFFFu;
+      rec.tau = R.tau; rec.top_p = R.top_p; rec.rep = par.rep_penalty; rec.freq = par.freq_penalty;
+      rec.pres = par.pres_penalty; rec.nnz = nnz; rec.n_prompt = min(max(par.n_prompt, 0), nnz); rec.h_active = h_active ? 1 : 0;
+      rec.min_p = R.min_p; rec.reserved0 = 0u; rec.distinct = H.active ? S.distinct : 0u; rec.reserved1 = 0u;
+      reinterpret_cast<WideRec*>(a.wq + WQ_HEAD)[slot] = rec;
+      a.out[row] = PENDING;
+    }
+    return true;
+  };
+  if (no_trunc) {  // every column survives: nothing to select here
+    if (!queue_wide(WIDE_ALL, true) && tid == 0) queue_pending(a, row);
+    return;
+  }
+  const bool minp_only = !R.greedy && !R.k_on && !R.p_on && R.minp_on;
   // the history mask is dead from here (every wave passed the barrier above after its last lookup):
   // the region becomes the candidate list
   uint32_t* lz = reinterpret_cast<uint32_t*>(lds);
@@ -793,6 +839,11 @@ __global__ __launch_bounds__(NTHR, 4) void fast_rows_kernel(const SampleArgs a) 
   int rc = FIN_PENDING;
   const unsigned n = S.cand_count;
   FWHY(2);
+  if (n > cap && (R.need_sum || minp_only)) {
+    // more columns at or above g than the list holds, and a cut that the whole-vocabulary routes
+    // find without the list
+    if (queue_wide(R.need_sum ? WIDE_TOP_P : WIDE_MIN_P, false)) return;
+  }
   if (n <= cap) {
     FWHY(0);
     // the list moves to registers; the region takes the history tables again
@@ -880,10 +931,12 @@ __global__ __launch_bounds__(NTHR, 4) void fast_rows_kernel(const SampleArgs a) 
     const double S_below = (double)S_below_int / (double)MSCALE;
     const uint32_t kmax = S.kmax;
     FPHASE(19);
+    bool tables_live = false;  // the region still holds the history tables
     if (S.flags & SIMPLE_DIAG_ERROR) rc = FIN_DONE;
     else if (kmax <= key_g || kmax <= KEY_NEG_INF) { rc = FIN_PENDING; FWHY(3); }
     else if (wide) {
       rc = ((S.flags >> 30) & 1u) ? FIN_PENDING : FIN_WIDE;
+      tables_live = true;
       if (rc == FIN_PENDING) FWHY(4);
     } else {
       // certified entries (tempered value strictly above fl(g / tau)) as composites
@@ -924,35 +977,12 @@ __global__ __launch_bounds__(NTHR, 4) void fast_rows_kernel(const SampleArgs a) 
         rc = finalize_long<NTHR>(S, R, n_cert, n_unc, kmax, key_g, C.g, S_below, lk, lid, lds + (size_t)lcap * 8u, hot_bits, dg);
       }
       else FWHY(6);
-      if (rc == FIN_WIDE && (H.active || ((S.flags >> 30) & 1u))) rc = FIN_PENDING;  // the tables above overwrote the history
+      if (rc == FIN_WIDE && ((S.flags >> 30) & 1u)) rc = FIN_PENDING;
     }
 
-    // ---- whole-vocabulary nucleus wider than the list: the row goes to the kernels that follow ----
+    // ---- a cut below the list's reach: the row goes to the kernels that follow ----
     if (rc == FIN_WIDE) {
-      __syncthreads();
-      if (tid == 0) S.e_n = atomicAdd(&a.wq[a.parity], 1u);
-      __syncthreads();
-      const unsigned slot = S.e_n;
-      const unsigned hb = H.active ? (a.F.cnt + (unsigned)((nnz + 3) / 2) * 4u + 15u) / 16u : 0u;  // 16-byte units of history tables
-      if (slot < (unsigned)a.wide_slots && WS_HT + hb * 16u <= a.ws_stride) {
-        u32x4* ws = reinterpret_cast<u32x4*>(a.wws + (size_t)slot * a.ws_stride);
-        const u32x4 zero = {0u, 0u, 0u, 0u};
-        for (unsigned i = tid; i < WS_RL / 16u; i += NTHR) ws[i] = zero;
-        if (H.active) {  // the history tables, still in the region, go with the row
-          const u32x4* src = reinterpret_cast<const u32x4*>(lds);
-          for (unsigned i = tid; i < hb; i += NTHR) ws[WS_HT / 16u + i] = src[i];
-        }
-        if (tid == 0) {
-          WideRec rec;
-          rec.row = (uint32_t)row; rec.g = C.g; rec.kmax = kmax; rec.flags = S.flags & 0x3FFFFFFFu;
-          rec.tau = R.tau; rec.top_p = R.top_p; rec.rep = par.rep_penalty; rec.freq = par.freq_penalty;
-          rec.pres = par.pres_penalty; rec.nnz = nnz; rec.n_prompt = min(max(par.n_prompt, 0), nnz); rec.h_active = h_active ? 1 : 0;
-          rec.h0 = h0; rec.distinct = H.active ? S.distinct : 0u; rec.reserved = 0u;
-          reinterpret_cast<WideRec*>(a.wq + WQ_HEAD)[slot] = rec;
-          a.out[row] = PENDING;
-        }
-        return;
-      }
+      if (queue_wide(R.need_sum ? WIDE_TOP_P : WIDE_MIN_P, tables_live)) return;
       rc = FIN_PENDING;  // no free slot: the general kernel takes the row
     }
   }

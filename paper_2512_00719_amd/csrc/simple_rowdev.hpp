@@ -206,15 +206,20 @@ struct StreamCtx {
 // than the candidate list are handed to three further kernels through a queue of records and one
 // workspace slot per queued row.
 struct WideRec {  // 64 bytes: everything the later kernels need to know about the row
-  uint32_t row; float g; uint32_t kmax, flags;
+  uint32_t row; float g; uint32_t mode, flags;
   float tau, top_p, rep, freq;
   float pres; int nnz, n_prompt, h_active;
-  long long h0; uint32_t distinct, reserved;
+  float min_p; uint32_t reserved0; uint32_t distinct, reserved1;
 };
+// What delimits the survivors of a queued row (each is a prefix of the total order, section 5.2):
+enum { WIDE_TOP_P = 0,   // the shortest prefix whose mass reaches top_p of the row's mass
+       WIDE_ALL = 1,     // no truncation: every column
+       WIDE_MIN_P = 2 }; // tempered value >= fl(y_max + fl(ln min_p))
 constexpr int WQ_HEAD = 16;             // words before the records
 constexpr uint32_t WS_HIST = 0u;        // u64[NBW]: reduced-precision mass of the columns below g, by bin
 constexpr uint32_t WS_TILES = 16384u;   // u64[2][256]: survivors' mass per tile, tail class then hot class
-constexpr uint32_t WS_SCAL = 20480u;    // u64 mass at or above g; u32 sure survivors; u32 boundary columns; u64 exact mass of the row
+constexpr uint32_t WS_SCAL = 20480u;    // u64 mass at or above g; u32 sure survivors; u32 boundary columns; u64 exact mass
+                                        // of the row; u32 largest key of a tempered value
 constexpr uint32_t WS_RL = 20544u;      // u64[RCAP]: columns of the boundary bin (value bits << 32 | id)
 constexpr uint32_t WS_HT = 53312u;      // the row's history tables as the single-pass kernel laid them out in LDS
 // [0, WS_RL) must be zero when a row is queued
@@ -222,13 +227,16 @@ constexpr uint32_t WS_HT = 53312u;      // the row's history tables as the singl
 // Mass of one column relative to the mass at y_g, w = exp(y - y_g) with y = fl32(z / tau), and the
 // bin of y (linear in y, so columns of equal y share a bin).  y is formed as fl32(double(z) * fl64(1 /
 // tau)): the IEEE float32 quotient (see apply_penalties).  float32 exponential, split log2(e).
-__device__ __forceinline__ float mass_term(float z, const StreamCtx& C, int& bin) {
-  const float y = (float)((double)z * C.inv_tau);
+__device__ __forceinline__ float tempered(float z, const StreamCtx& C) { return (float)((double)z * C.inv_tau); }
+__device__ __forceinline__ float mass_term(float z, const StreamCtx& C, int& bin, float& y) {
+  y = (float)((double)z * C.inv_tau);
   const float d = y - C.y_g;
   const float t = fmaf(d, L2E_HI, d * L2E_LO);
   bin = (int)fminf(fmaxf(-t * BINS_PER_LOG2, 0.0f), (float)(NBW - 1));
   return __builtin_amdgcn_exp2f(t);
 }
+__device__ __forceinline__ float mass_term(float z, const StreamCtx& C, int& bin) { float y; return mass_term(z, C, bin, y); }
+constexpr float W_LIMIT = 2097152.0f;  // 2^21: largest mass relative to the one at g that the 2^28 fixed point carries
 __device__ __forceinline__ u64 mass_fix(float w) { return (u64)(w * MSCALE + 0.5f); }
 // same integer for w <= 1 (every column below g), one conversion instruction
 __device__ __forceinline__ u64 mass_fix_below(float w) { return (u64)(uint32_t)(w * MSCALE + 0.5f); }

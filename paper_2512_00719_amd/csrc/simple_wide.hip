@@ -1,4 +1,6 @@
-// Whole-vocabulary nucleus wider than the candidate list (top-p over all of V, section 2.1 Eq. (2)).
+// Rows whose survivors are not a short prefix that the single-pass kernel's candidate list can hold:
+// a nucleus over the whole vocabulary that is wider than the list (top-p over all of V, section 2.1
+// Eq. (2)), no truncation at all (every column survives), or a min-p cut below the list's reach.
 //
 // The single-pass kernel queues such rows with their threshold g.  Their remaining work is two more
 // reads of the row, which one workgroup per row would do at the latency of a single compute unit;
@@ -17,6 +19,9 @@
 //             value descending, id ascending), applies the SHVS acceptance test (section 5.3), walks
 //             the per-tile masses of the drawn class in ascending id and reads one tile a last time
 //             to locate the drawn id (inverse CDF, step (3) of section 2.1).
+//
+// Rows without truncation skip the first kernel and have no cut; rows with a min-p cut use the first
+// kernel for the row maximum only (the cut is a value).
 //
 // Penalties (section 2.2) are applied on the fly: the single-pass kernel leaves the row's history
 // tables (presence mask, rank directory, counts by rank) in the row's workspace slot, and a slice
@@ -51,8 +56,8 @@ static_assert(sizeof(WideRec) == 64, "queue record size");
 struct WideRow {
   int row;
   StreamCtx C;
-  float tau, top_p;
-  uint32_t kmax, flags;
+  float tau, top_p, min_p;
+  uint32_t mode, flags;
   bool h_active;
   float rep, freq, pres;
   double inv_rep;
@@ -63,8 +68,8 @@ struct WideRow {
 __device__ __forceinline__ WideRow load_row(const SampleArgs& a, unsigned slot) {
   WideRow W;
   const WideRec rec = reinterpret_cast<const WideRec*>(a.wq + WQ_HEAD)[slot];
-  W.row = (int)rec.row; W.kmax = rec.kmax; W.flags = rec.flags;
-  W.tau = rec.tau; W.top_p = rec.top_p;
+  W.row = (int)rec.row; W.mode = rec.mode; W.flags = rec.flags;
+  W.tau = rec.tau; W.top_p = rec.top_p; W.min_p = rec.min_p;
   W.C.g = rec.g; W.C.y_g = rec.g / rec.tau; W.C.inv_tau = 1.0 / (double)rec.tau; W.C.need_sum = true;
   W.C.l2e_tau = 0.0f;
   W.rep = rec.rep; W.freq = rec.freq; W.pres = rec.pres;
@@ -181,6 +186,24 @@ __device__ inline int find_cut(FS& S, const WideRow& W) {
   return bstar;
 }
 
+// How a column is classified, per route: it surely survives iff its tempered value reaches thr_y and it
+// lies at or above g or in a bin before bstar; columns of bin bstar are resolved one by one.
+struct RowCut { int bstar; float thr_y; bool valid; };
+__device__ inline RowCut row_cut(FS& S, const WideRow& W) {  // every thread calls; barriers inside on one route
+  RowCut c;
+  c.thr_y = -INFINITY; c.valid = true;
+  if (W.mode == WIDE_TOP_P) { c.bstar = find_cut(S, W); c.valid = c.bstar >= 0; }
+  else {
+    c.bstar = NBW;  // no bin holds a cut
+    if (W.mode == WIDE_MIN_P) {
+      const uint32_t kmax = as_global(reinterpret_cast<const uint32_t*>(W.ws + WS_SCAL))[6];
+      c.valid = kmax > KEY_NEG_INF;
+      c.thr_y = keyf(kmax) + (float)log((double)W.min_p);  // fl(y_max + fl(ln min_p)), as in the list's epilogue
+    }
+  }
+  return c;
+}
+
 // Work split: items are (queued row, slice) pairs in row-major order; a workgroup takes a
 // contiguous range, so that it meets few distinct rows.
 struct Items { unsigned i0, i1, n_sl; };
@@ -215,13 +238,19 @@ __global__ __launch_bounds__(WT, 8) void wide_bins_kernel(const SampleArgs a) {
   int cur = -1;
   WideRow W;
   u64 mtop = 0ull;
+  float ymax = -INFINITY;  // min-p rows: largest tempered value seen by this thread
   auto flush = [&]() {
     __syncthreads();
-    u64* gh = reinterpret_cast<u64*>(W.ws + WS_HIST);
-    for (int b = tid; b < NBW; b += WT) { const uint32_t v = lh[b]; if (v) atomicAdd(&gh[b], (u64)v); }
-    const u64 t = blk_sum_u64<WNW>(S, mtop);
-    if (tid == 0 && t) atomicAdd(reinterpret_cast<u64*>(W.ws + WS_SCAL), t);
-    mtop = 0ull;
+    if (W.mode == WIDE_TOP_P) {
+      u64* gh = reinterpret_cast<u64*>(W.ws + WS_HIST);
+      for (int b = tid; b < NBW; b += WT) { const uint32_t v = lh[b]; if (v) atomicAdd(&gh[b], (u64)v); }
+      const u64 t = blk_sum_u64<WNW>(S, mtop);
+      if (tid == 0 && t) atomicAdd(reinterpret_cast<u64*>(W.ws + WS_SCAL), t);
+    } else if (W.mode == WIDE_MIN_P) {
+      const float m = wave_max(ymax);
+      if ((tid & 63) == 0 && m > -INFINITY) atomicMax(reinterpret_cast<uint32_t*>(W.ws + WS_SCAL) + 6, fkey(m));
+    }
+    mtop = 0ull; ymax = -INFINITY;
   };
   for (unsigned it = I.i0; it < I.i1; ++it) {
     const int slot = (int)(it / I.n_sl), sl = (int)(it % I.n_sl);
@@ -234,6 +263,7 @@ __global__ __launch_bounds__(WT, 8) void wide_bins_kernel(const SampleArgs a) {
       cur = slot;
       for (int b = tid; b < NBW; b += WT) lh[b] = 0u;
     }
+    if (W.mode == WIDE_ALL) continue;  // every column survives: nothing to find in a first pass
     const DT* rowp = reinterpret_cast<const DT*>(a.logits) + (size_t)W.row * (size_t)a.stride;
     Raw A[G];
 #pragma unroll
@@ -248,12 +278,33 @@ __global__ __launch_bounds__(WT, 8) void wide_bins_kernel(const SampleArgs a) {
     __syncthreads();
     WPHASE(2);
     auto one = [&](float z, int) {
+      if (W.mode == WIDE_MIN_P) { ymax = fmaxf(ymax, tempered(z, W.C)); return; }
       int b;
       const float w = mass_term(z, W.C, b);
       if (z < W.C.g) atomicAdd(&lh[b], (uint32_t)(w * BSCALE + 0.5f));
       else mtop += (u64)(w * BSCALE + 0.5f);
     };
     if (W.h_active) for_history_columns<DT>(Tb, W, rowp, c0, V, one);
+    if (W.mode == WIDE_MIN_P) {  // the row maximum is all a value cut needs
+#pragma unroll
+      for (int j = 0; j < G; ++j) {
+        const int idx0 = c0 + (j * WT + tid) * EPL;
+        if (idx0 + EPL <= V) {
+          float z[EPL];
+          Io<DT>::unpack(A[j], z);
+          const uint32_t nib = W.h_active ? (Tb.bm[(idx0 - c0) >> 5] >> ((unsigned)(idx0 - c0) & 31u)) & ((1u << EPL) - 1u) : 0u;
+          float zm = -INFINITY;  // the tempered value is monotone in z: one division per group
+#pragma unroll
+          for (int e = 0; e < EPL; ++e) zm = ((nib >> e) & 1u) ? zm : fmaxf(zm, z[e]);
+          ymax = fmaxf(ymax, tempered(zm, W.C));
+        } else {
+          for (int idx = idx0; idx < V; ++idx)
+            if (!(W.h_active && slice_bit(idx - c0, Tb))) one(Io<DT>::one(rowp + idx), idx);
+        }
+      }
+      __syncthreads();
+      continue;
+    }
 #pragma unroll
     for (int j = 0; j < G; ++j) {
       const int idx0 = c0 + (j * WT + tid) * EPL;
@@ -312,14 +363,15 @@ __global__ __launch_bounds__(WT, 6) void wide_classify_kernel(const SampleArgs a
   int cur = -1;
   WideRow W;
   int bstar = -1;
+  float thr_y = -INFINITY;
   bool valid = false;
   for (unsigned it = I.i0; it < I.i1; ++it) {
     const int slot = (int)(it / I.n_sl), sl = (int)(it % I.n_sl);
     if (slot != cur) {
       W = load_row(a, (unsigned)slot);
       cur = slot;
-      bstar = find_cut(S, W);
-      valid = bstar >= 0;
+      const RowCut rc = row_cut(S, W);
+      bstar = rc.bstar; thr_y = rc.thr_y; valid = rc.valid;
     }
     if (!valid) continue;  // the finishing kernel hands the row on
     const int c0 = sl * SLC;
@@ -342,13 +394,18 @@ __global__ __launch_bounds__(WT, 6) void wide_classify_kernel(const SampleArgs a
     __syncthreads();
     unsigned n_sure = 0u;
     u64 acc_all = 0ull;  // exact mass of every column of the slice
+    float ymax = -INFINITY;  // largest tempered value
+    bool bad = false;        // a mass the fixed point cannot carry, or a NaN
     // one column the slow way: history columns and the ragged end of the row
     auto one = [&](float z, int idx) {
-      int b;
-      const float w = mass_term(z, W.C, b);
+      int b; float y;
+      const float w = mass_term(z, W.C, b, y);
       const bool below = z < W.C.g;
+      if (!below && !(w <= W_LIMIT)) { bad = true; return; }
       const u64 m = below ? mass_fix_below(w) : mass_fix(w);
       acc_all += m;
+      ymax = fmaxf(ymax, y);
+      if (!(y >= thr_y)) return;
       if (!below || b < bstar) {
         const unsigned hot = use_hot ? hot_bit(hot_bits, (uint32_t)idx) : 0u;
         atomicAdd(&ltile[hot], m);
@@ -373,10 +430,11 @@ __global__ __launch_bounds__(WT, 6) void wide_classify_kernel(const SampleArgs a
 #pragma unroll
         for (int e = 0; e < EPL; ++e) {  // straight-line; the rare cases follow under wave-wide tests
           if (!((live >> e) & 1u)) z[e] = -INFINITY;  // no mass, no bin of interest ...
-          int b;
-          const float w = mass_term(z[e], W.C, b);
+          int b; float y;
+          const float w = mass_term(z[e], W.C, b, y);
           const bool below = z[e] < W.C.g;
-          const bool sure = ((live >> e) & 1u) && (!below || b < bstar);
+          const bool sure = ((live >> e) & 1u) && y >= thr_y && (!below || b < bstar);
+          ymax = fmaxf(ymax, y);
           const uint32_t m = below ? (uint32_t)mass_fix_below(w) : 0u;
           const uint32_t ms = sure ? m : 0u;
           const bool hot = ((hq[j] >> e) & 1u) != 0u;
@@ -391,11 +449,13 @@ __global__ __launch_bounds__(WT, 6) void wide_classify_kernel(const SampleArgs a
         if (__ballot(any_top)) {
 #pragma unroll
           for (int e = 0; e < EPL; ++e) {
-            if (!(z[e] < W.C.g)) {
-              int b;
-              const u64 m = mass_fix(mass_term(z[e], W.C, b));
+            if (!(z[e] < W.C.g)) {  // not below the list's threshold: inside any top-p nucleus that got here
+              int b; float y;
+              const float w = mass_term(z[e], W.C, b, y);
+              if (!(w <= W_LIMIT)) { bad = true; continue; }
+              const u64 m = mass_fix(w);
               acc_all += m;
-              if ((hq[j] >> e) & 1u) acc1 += m; else acc0 += m;
+              if (y >= thr_y) { if ((hq[j] >> e) & 1u) acc1 += m; else acc0 += m; }
             }
           }
         }
@@ -425,6 +485,11 @@ __global__ __launch_bounds__(WT, 6) void wide_classify_kernel(const SampleArgs a
     u64* gt = reinterpret_cast<u64*>(W.ws + WS_TILES);
     uint32_t* sc = reinterpret_cast<uint32_t*>(W.ws + WS_SCAL);
     if (tid < 2 && sl < 256) gt[tid * 256 + sl] = ltile[tid];
+    {
+      const float m = wave_max(ymax);
+      if (lane == 0 && m > -INFINITY) atomicMax(&sc[6], fkey(m));
+      if (__ballot(bad) && lane == 0) atomicAdd(&sc[3], (unsigned)RCAP + 1u);  // the finishing kernel hands the row on
+    }
     const unsigned nb = l_n;
     if (tid == 0) {
       if (ns) atomicAdd(&sc[2], ns);
@@ -468,14 +533,22 @@ __device__ inline bool finish_row(const SampleArgs& a, const WideRow& W, FS& S, 
   u64 tv[2];
 #pragma unroll
   for (int k = 0; k < 2; ++k) tv[k] = as_global(reinterpret_cast<const u64*>(W.ws + WS_TILES))[k * WT + tid];
+  const uint32_t kmax = as_global(sc)[6];
   XPHASE(0);
-  const int bstar = find_cut(S, W);
+  const RowCut rcut = row_cut(S, W);
+  const int bstar = rcut.bstar;
+  const float thr_y = rcut.thr_y;
   XPHASE(1);
-  if (bstar < 0) { XWHY(1, 0); return false; }
-  if (n_r > (unsigned)RCAP || n_r == 0u) { XWHY(2, n_r); return false; }
+  if (!rcut.valid) { XWHY(1, 0); return false; }
+  const bool top_p_route = W.mode == WIDE_TOP_P;
+  // a count past the limit is also how the classifying pass reports a row it could not handle
+  if (n_r > (unsigned)RCAP || (n_r == 0u) == top_p_route) { XWHY(2, n_r); return false; }
   if (tid == 0) { S.bd = -1; S.cut_k = 0ull; S.cut_p = ~0ull; S.out_id = -1; S.out_w = 0ull; }
   tiles[tid] = tv[0]; tiles[WT + tid] = tv[1];
   const u64 msure = tv[0] + tv[1];
+  u64 cut_found = 0ull;  // every collected column at or after it in the order survives; 0: no collected columns
+  unsigned r_in = 0;
+  if (top_p_route) {
   // exact masses from here: the columns surely inside must stay below the target, the collected bin must reach it
   const u64 m_above = blk_sum_u64<WNW>(S, msure);  // barriers inside
   const u64 target = (u64)__double2ull_ru((double)W.top_p * (double)S_tot);
@@ -512,7 +585,6 @@ __device__ inline bool finish_row(const SampleArgs& a, const WideRow& W, FS& S, 
   // Radix descent, eight bits at a time from the top of (key, ~id): among the columns that share the
   // digits fixed so far, the digit whose mass carries the running total over the target is fixed
   // next.  Digits on which all columns agree are skipped; after the last one the cut column is known.
-  u64 cut_found = 0ull;
   {
     const u64 cmax = S.cut_k, differ = S.cut_k ^ S.cut_p;
     u64 prefix = 0ull, mask = 0ull, acc = m_above;
@@ -547,18 +619,18 @@ __device__ inline bool finish_row(const SampleArgs& a, const WideRow& W, FS& S, 
     if (!ok) { XWHY(4, 0); return false; }
     cut_found = prefix;
   }
-  const u64 cut_c = cut_found;
   XPHASE(2);
-  if (cut_c == 0ull) { XWHY(6, 0); return false; }
-  unsigned r_in = 0;
+  if (cut_found == 0ull) { XWHY(6, 0); return false; }
   for (unsigned t = tid; t < n_r; t += WT) {
-    if (rcmp[t] >= cut_c) {
+    if (rcmp[t] >= cut_found) {
       const uint32_t id = 0xFFFFFFFFu - (uint32_t)rcmp[t];
       const unsigned hot = use_hot ? hot_bit(hot_bits, id) : 0u;
       atomicAdd(&tiles[hot * 256u + id / (unsigned)T], (u64)rl[t]);
       ++r_in;
     }
   }
+  }  // top-p route
+  const u64 cut_c = cut_found;
   unsigned ns = r_in + (tid == 0 ? n_sure : 0u), dz = 0; u64 mx = 0ull, dsum = 0ull;
   blk_reduce<WNW>(S, ns, dz, mx, dsum);  // barriers inside: the tile masses are complete after it
   // -- masses of the classes, acceptance (section 5.3), the tile that holds the draw --
@@ -577,7 +649,7 @@ __device__ inline bool finish_row(const SampleArgs& a, const WideRow& W, FS& S, 
   const u64 S_cls = use_hot ? (pick_hot ? S1 : S0) : S_K;
   const double u = use_hot ? (pick_hot ? u3[0] : u3[2]) : u3[0];
   dg.n_survivors = (int)ns;
-  dg.s_k = (double)S_tot / (double)MSCALE * exp((double)C.y_g - (double)keyf(W.kmax));
+  dg.s_k = (double)S_tot / (double)MSCALE * exp((double)C.y_g - (double)keyf(kmax));
   if (S_cls == 0ull) { XWHY(7, 0); return false; }
   u64 tfix = (u64)__double2ull_rd(u * (double)S_cls);
   if (tfix >= S_cls) tfix = S_cls - 1ull;
@@ -608,12 +680,12 @@ __device__ inline bool finish_row(const SampleArgs& a, const WideRow& W, FS& S, 
       if (W.h_active && slice_bit(idx - c0, Tb)) z = slice_value(z, idx - c0, Tb, W);
       const unsigned hot = use_hot ? hot_bit(hot_bits, (uint32_t)idx) : 0u;
       if (!use_hot || hot == cls) {
-        int b;
-        const float w = mass_term(z, C, b);
+        int b; float y;
+        const float w = mass_term(z, C, b, y);
         const bool below = z < C.g;
         bool in = !below || b < bstar;
         if (!in && b == bstar) in = composite(fkey(z / W.tau), (uint32_t)idx) >= cut_c;
-        if (in) mloc[e] = below ? mass_fix_below(w) : mass_fix(w);
+        if (in && y >= thr_y) mloc[e] = below ? mass_fix_below(w) : mass_fix(w);
       }
     }
     lsum += mloc[e];

@@ -133,9 +133,10 @@ def test_rows_the_single_pass_kernel_must_leave_to_the_general_kernel():
     for ids, dg in _run(w, steps=(0, 1)):
         general = (dg["flags"] & GENERAL) > 0
         # 0: nucleus over all of V with more history ids than the mass correction holds in registers;
-        # 2, 5: no truncation at all; 3, 6: penalties that raise logits; 4: top-k above the list's limit
-        assert general[[0, 2, 3, 4, 5, 6]].all()
-        assert not general[[1, 7]].any()
+        # 3, 6: penalties that raise logits; 4: top-k above the list's limit
+        assert general[[0, 3, 4, 6]].all()
+        # 2, 5: no truncation at all: straight to the whole-vocabulary kernels
+        assert not general[[1, 2, 5, 7]].any() and ((dg["flags"] & WIDE) > 0)[[2, 5]].all()
 
 
 def test_one_context_alternating_routes_call_after_call():
@@ -147,7 +148,7 @@ def test_one_context_alternating_routes_call_after_call():
     empty = (np.zeros(B + 1, np.int64), np.zeros(0, np.int32))
     wide = synth.Workload("a", B, V, "f32", z, synth.make_params(B, temperature=1.0, top_p=0.9), *empty)
     topk = synth.Workload("b", B, V, "f32", z, synth.make_params(B, temperature=0.8, top_k=20, top_p=0.9), *empty)
-    plain = synth.Workload("c", B, V, "f32", z, synth.make_params(B, temperature=1.0), *empty)  # general kernel
+    plain = synth.Workload("c", B, V, "f32", z, synth.make_params(B, temperature=1.0, top_k=2000), *empty)  # general kernel
     s = binding.Sampler(V, 0)
     want = {}
     for step, w in enumerate([wide, topk, plain, wide, wide, plain, topk, topk, wide, plain, plain, wide]):
@@ -165,3 +166,67 @@ def test_one_context_alternating_routes_call_after_call():
         if w is topk:
             assert not ((f & (WIDE | GENERAL)) > 0).any()
     s.close()
+
+
+def test_no_truncation_rows_every_column_survives():
+    """temperature only: the rows skip the candidate list and go straight to the sliced kernels,
+    with any penalties (also ones that raise logits), history longer than the register budget, SHVS."""
+    rng = np.random.default_rng(27)
+    B, V = 12, 36_000 + 4
+    z = _flat_logits(rng, B, V, sigma=1.8)
+    z[3, 17] = -np.inf  # a masked token: probability zero, never drawn
+    lens = rng.integers(0, 1400, B)
+    lens[5] = 5000
+    hist_ptr, hist_ids = _head_history(z, lens, rng, head=2500)
+    params = synth.make_params(B, temperature=[1.0, 0.6, 1.4] * 4,
+                               rep_penalty=[1.0, 1.2, 0.85, 1.1] * 3, freq_penalty=[0.0, 0.3, -0.2] * 4,
+                               pres_penalty=[0.0, 0.1, 0.0, -0.1] * 3, n_prompt=[0, 40, 10_000] * 4)
+    hot = np.sort(np.argsort(-z.mean(axis=0))[:2000]).astype(np.int32)
+    for hot_ids in (None, hot):
+        w = synth.Workload("all", B, V, "f32", z, params, hist_ptr, hist_ids, hot_ids=hot_ids)
+        for ids, dg in _run(w, steps=(0, 1, 2)):
+            f = dg["flags"]
+            assert ((f & WIDE) > 0).all() and not ((f & GENERAL) > 0).any()
+            assert (dg["n_survivors"] == V).all() and ids[3] != 17
+
+
+def test_no_truncation_bf16_ties():
+    rng = np.random.default_rng(28)
+    B, V = 6, 48_000 + 16
+    bits = synth.f32_to_bf16_bits(_flat_logits(rng, B, V, sigma=1.0))
+    w = synth.Workload("all-bf16", B, V, "bf16", bits, synth.make_params(B, temperature=[1.0, 0.8, 1.3] * 2),
+                       np.zeros(B + 1, np.int64), np.zeros(0, np.int32))
+    for ids, dg in _run(w, steps=(0, 1, 2, 3)):
+        assert ((dg["flags"] & WIDE) > 0).all() and not ((dg["flags"] & GENERAL) > 0).any()
+
+
+def test_min_p_cut_below_the_reach_of_the_list():
+    """min-p alone with thousands of survivors: the cut is a value, found from the row maximum."""
+    rng = np.random.default_rng(29)
+    B, V = 10, 40_000
+    z = _flat_logits(rng, B, V, sigma=1.5)
+    lens = rng.integers(0, 900, B)
+    hist_ptr, hist_ids = _head_history(z, lens, rng, head=800)  # the history holds the largest logits: the maximum moves
+    params = synth.make_params(B, temperature=[1.0, 1.3, 0.8, 1.1, 1.0] * 2, min_p=[1e-3, 1e-4, 3e-3, 1e-5, 0.05] * 2,
+                               rep_penalty=1.2, freq_penalty=0.4, pres_penalty=0.2)
+    w = synth.Workload("minp", B, V, "f32", z, params, hist_ptr, hist_ids)
+    for ids, dg in _run(w, steps=(0, 1, 2)):
+        f = dg["flags"]
+        assert ((f & WIDE) > 0).sum() >= 6 and not ((f & GENERAL) > 0).any()
+        assert dg["n_survivors"].max() > 3072
+
+
+def test_nucleus_rows_whose_candidates_overflow_the_list():
+    """bf16 ties at the threshold put more columns at or above g than the list holds; rows with a nucleus
+    over all of V still finish in the sliced kernels."""
+    rng = np.random.default_rng(30)
+    B, V = 8, 64_000
+    z = np.round(_flat_logits(rng, B, V, sigma=1.0) * 4) / 4  # 0.25-spaced values: tie groups of thousands
+    bits = synth.f32_to_bf16_bits(z.astype(np.float32))
+    params = synth.make_params(B, temperature=[1.0, 0.9] * 4, top_p=[0.9, 0.95, 0.5, 0.99] * 2)
+    w = synth.Workload("overflow", B, V, "bf16", bits, params, np.zeros(B + 1, np.int64), np.zeros(0, np.int32))
+    for ids, dg in _run(w, steps=(0, 1)):
+        f = dg["flags"]
+        assert ((f & WIDE) > 0).all()
+        # tie groups wider than the boundary table may still need the general kernel
+        assert ((f & GENERAL) > 0).sum() <= B
