@@ -216,7 +216,7 @@ enum { WIDE_TOP_P = 0,   // the shortest prefix whose mass reaches top_p of the 
        WIDE_ALL = 1,     // no truncation: every column
        WIDE_MIN_P = 2 }; // tempered value >= fl(y_max + fl(ln min_p))
 constexpr int WQ_HEAD = 16;             // words before the records
-constexpr uint32_t WS_HIST = 0u;        // u64[NBW]: reduced-precision mass of the columns below g, by bin
+constexpr uint32_t WS_HIST = 0u;        // u64[NBW]: mass of the columns below g, by bin
 constexpr uint32_t WS_TILES = 16384u;   // u64[2][256]: survivors' mass per tile, tail class then hot class
 constexpr uint32_t WS_SCAL = 20480u;    // u64 mass at or above g; u32 sure survivors; u32 boundary columns; u64 exact mass
                                         // of the row; u32 largest key of a tempered value

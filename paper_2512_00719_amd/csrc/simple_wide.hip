@@ -8,8 +8,8 @@
 //
 //   bins      per slice, the penalised, tempered logits below g are binned (bins linear in the
 //             tempered logit, 1/64 of a factor two in probability wide) with their masses relative
-//             to the mass at g, at reduced precision (32-bit LDS atomics); the mass at or above g
-//             is summed beside them.  This pass only has to point at the bin that holds the cut.
+//             to the mass at g (integers, LDS atomics); the mass at or above g is summed beside
+//             them.  This pass points at the bin that holds the cut.
 //   classify  that bin follows from the cumulated masses; per tile, the exact (integer) masses of
 //             the columns surely inside are summed by class (tail / hot), the columns of the
 //             cut's bin are collected, and the exact mass of the whole row is summed.
@@ -47,7 +47,6 @@ __device__ unsigned long long g_wide_phase_times[2 * 8192 * 8];
 constexpr int WT = 256;      // threads per workgroup
 constexpr int WNW = WT / 64;
 constexpr int SLC = 4096;    // columns per slice
-constexpr float BSCALE = 524288.0f;  // 2^19: scale of the first pass's masses
 constexpr int ICAP = 1024;   // columns of the boundary bin one slice can stage
 static_assert(WS_HT == WIDE_SLOT_FIXED, "workspace slot size");
 static_assert(sizeof(WideRec) == 64, "queue record size");
@@ -160,8 +159,8 @@ __device__ __forceinline__ void for_history_columns(const SliceTabs& T, const Wi
   }
 }
 
-// The bin that should hold the cut, from the reduced-precision masses of the first pass: cumulative
-// mass from the top reaches top_p * total.  bstar < 0 if none.  Ends with a barrier.
+// The bin that holds the cut, from the masses of the first pass: cumulative mass from the top
+// reaches top_p * total.  bstar < 0 if none.  Ends with a barrier.
 __device__ inline int find_cut(FS& S, const WideRow& W) {
   const int tid = threadIdx.x;
   constexpr int BPT = NBW / WT;
@@ -225,7 +224,7 @@ __global__ __launch_bounds__(WT, 8) void wide_bins_kernel(const SampleArgs a) {
   constexpr int G = SLC / (WT * EPL);
   typedef typename Io<DT>::Raw Raw;
   __shared__ SliceTabs Tb;
-  __shared__ uint32_t lh[NBW];  // masses at 2^19: a slice's 4096 columns cannot overflow a bin
+  __shared__ u64 lh[NBW];
   __shared__ FS S;
   const int tid = threadIdx.x;
   const int V = a.V;
@@ -243,7 +242,7 @@ __global__ __launch_bounds__(WT, 8) void wide_bins_kernel(const SampleArgs a) {
     __syncthreads();
     if (W.mode == WIDE_TOP_P) {
       u64* gh = reinterpret_cast<u64*>(W.ws + WS_HIST);
-      for (int b = tid; b < NBW; b += WT) { const uint32_t v = lh[b]; if (v) atomicAdd(&gh[b], (u64)v); }
+      for (int b = tid; b < NBW; b += WT) { const u64 v = lh[b]; if (v) atomicAdd(&gh[b], v); }
       const u64 t = blk_sum_u64<WNW>(S, mtop);
       if (tid == 0 && t) atomicAdd(reinterpret_cast<u64*>(W.ws + WS_SCAL), t);
     } else if (W.mode == WIDE_MIN_P) {
@@ -261,7 +260,7 @@ __global__ __launch_bounds__(WT, 8) void wide_bins_kernel(const SampleArgs a) {
       if (cur >= 0) flush();
       W = load_row(a, (unsigned)slot);
       cur = slot;
-      for (int b = tid; b < NBW; b += WT) lh[b] = 0u;
+      for (int b = tid; b < NBW; b += WT) lh[b] = 0ull;
     }
     if (W.mode == WIDE_ALL) continue;  // every column survives: nothing to find in a first pass
     const DT* rowp = reinterpret_cast<const DT*>(a.logits) + (size_t)W.row * (size_t)a.stride;
@@ -281,8 +280,8 @@ __global__ __launch_bounds__(WT, 8) void wide_bins_kernel(const SampleArgs a) {
       if (W.mode == WIDE_MIN_P) { ymax = fmaxf(ymax, tempered(z, W.C)); return; }
       int b;
       const float w = mass_term(z, W.C, b);
-      if (z < W.C.g) atomicAdd(&lh[b], (uint32_t)(w * BSCALE + 0.5f));
-      else mtop += (u64)(w * BSCALE + 0.5f);
+      if (z < W.C.g) atomicAdd(&lh[b], mass_fix_below(w));
+      else mtop += mass_fix(fminf(w, W_LIMIT));
     };
     if (W.h_active) for_history_columns<DT>(Tb, W, rowp, c0, V, one);
     if (W.mode == WIDE_MIN_P) {  // the row maximum is all a value cut needs
@@ -322,13 +321,13 @@ __global__ __launch_bounds__(WT, 8) void wide_bins_kernel(const SampleArgs a) {
           int b;
           const float w = mass_term(z[e], W.C, b);
           const bool below = z[e] < W.C.g;
-          atomicAdd(&lh[b], below ? (uint32_t)(w * BSCALE + 0.5f) : 0u);
+          atomicAdd(&lh[b], below ? mass_fix_below(w) : 0ull);
           any_top = any_top || !below;
         }
         if (__ballot(any_top)) {  // few columns: the 64-bit conversion stays out of the main line
 #pragma unroll
           for (int e = 0; e < EPL; ++e)
-            if (!(z[e] < W.C.g)) { int b; mtop += (u64)(mass_term(z[e], W.C, b) * BSCALE + 0.5f); }
+            if (!(z[e] < W.C.g)) { int b; mtop += mass_fix(fminf(mass_term(z[e], W.C, b), W_LIMIT)); }
         }
       } else {
         for (int idx = idx0; idx < V; ++idx)
@@ -344,7 +343,7 @@ __global__ __launch_bounds__(WT, 8) void wide_bins_kernel(const SampleArgs a) {
 
 // ---------------------------------------------------------------- classify --------------------
 template <typename DT>
-__global__ __launch_bounds__(WT, 6) void wide_classify_kernel(const SampleArgs a) {
+__global__ __launch_bounds__(WT, 5) void wide_classify_kernel(const SampleArgs a) {
   constexpr int EPL = Io<DT>::EPL;
   constexpr int G = SLC / (WT * EPL);  // 16-byte groups per thread and slice; a slice is one tile of the draw's walk
   constexpr unsigned EMASK = (1u << EPL) - 1u;
