@@ -34,13 +34,15 @@ namespace simple {
 namespace fast {
 
 #ifdef SIMPLE_PHASE_TIMES  // profiling builds only: per-workgroup timestamps of the first kernel (100 MHz wall clock)
-__device__ unsigned long long g_wide_phase_times[2 * 8192 * 8];
+__device__ unsigned long long g_wide_phase_times[3 * 8192 * 8];
+#define CPHASE(i) do { if (threadIdx.x == 0 && blockIdx.x < 8192) g_wide_phase_times[(16384 + blockIdx.x) * 8 + (i)] = wall_clock64(); } while (0)
 #define XPHASE(i) do { if (threadIdx.x == 0 && blockIdx.x < 8192) g_wide_phase_times[(8192 + blockIdx.x) * 8 + (i)] = wall_clock64(); } while (0)
 #define XWHY(code, v) do { if (threadIdx.x == 0 && blockIdx.x < 8192) { g_wide_phase_times[(8192 + blockIdx.x) * 8 + 6] = (code); g_wide_phase_times[(8192 + blockIdx.x) * 8 + 7] = (v); } } while (0)
 #define WPHASE(i) do { if (threadIdx.x == 0 && blockIdx.x < 8192) g_wide_phase_times[blockIdx.x * 8 + (i)] = wall_clock64(); } while (0)
 #else
 #define WPHASE(i) do { } while (0)
 #define XPHASE(i) do { } while (0)
+#define CPHASE(i) do { } while (0)
 #define XWHY(code, v) do { } while (0)
 #endif
 
@@ -64,17 +66,27 @@ struct WideRow {
   unsigned char* ws;
 };
 
+// The record is the same in every lane; saying so keeps the row's constants in scalar registers.
+__device__ __forceinline__ uint32_t uni(uint32_t v) { return (uint32_t)__builtin_amdgcn_readfirstlane((int)v); }
+__device__ __forceinline__ int uni(int v) { return __builtin_amdgcn_readfirstlane(v); }
+__device__ __forceinline__ float uni(float v) { return __uint_as_float(uni(__float_as_uint(v))); }
+__device__ __forceinline__ double uni(double v) {
+  const unsigned long long b = (unsigned long long)__double_as_longlong(v);
+  return __longlong_as_double((long long)(((unsigned long long)uni((uint32_t)(b >> 32)) << 32) | (unsigned long long)uni((uint32_t)b)));
+}
+
 __device__ __forceinline__ WideRow load_row(const SampleArgs& a, unsigned slot) {
   WideRow W;
+  slot = uni(slot);
   const WideRec rec = reinterpret_cast<const WideRec*>(a.wq + WQ_HEAD)[slot];
-  W.row = (int)rec.row; W.mode = rec.mode; W.flags = rec.flags;
-  W.tau = rec.tau; W.top_p = rec.top_p; W.min_p = rec.min_p;
-  W.C.g = rec.g; W.C.y_g = rec.g / rec.tau; W.C.inv_tau = 1.0 / (double)rec.tau; W.C.need_sum = true;
+  W.row = uni((int)rec.row); W.mode = uni(rec.mode); W.flags = uni(rec.flags);
+  W.tau = uni(rec.tau); W.top_p = uni(rec.top_p); W.min_p = uni(rec.min_p);
+  W.C.g = uni(rec.g); W.C.y_g = uni(rec.g / rec.tau); W.C.inv_tau = uni(1.0 / (double)rec.tau); W.C.need_sum = true;
   W.C.l2e_tau = 0.0f;
-  W.rep = rec.rep; W.freq = rec.freq; W.pres = rec.pres;
-  W.inv_rep = 1.0 / (double)rec.rep;
-  W.h_active = rec.h_active != 0;
-  W.distinct = rec.distinct;
+  W.rep = uni(rec.rep); W.freq = uni(rec.freq); W.pres = uni(rec.pres);
+  W.inv_rep = uni(1.0 / (double)rec.rep);
+  W.h_active = uni(rec.h_active) != 0;
+  W.distinct = uni(rec.distinct);
   W.ws = a.wws + (size_t)slot * a.ws_stride;
   return W;
 }
@@ -342,7 +354,7 @@ __global__ __launch_bounds__(WT, 8) void wide_bins_kernel(const SampleArgs a) {
 }
 
 // ---------------------------------------------------------------- classify --------------------
-template <typename DT>
+template <typename DT, bool use_hot>  // use_hot: a hot set is installed (section 5.3): masses are split by class
 __global__ __launch_bounds__(WT, 5) void wide_classify_kernel(const SampleArgs a) {
   constexpr int EPL = Io<DT>::EPL;
   constexpr int G = SLC / (WT * EPL);  // 16-byte groups per thread and slice; a slice is one tile of the draw's walk
@@ -358,7 +370,7 @@ __global__ __launch_bounds__(WT, 5) void wide_classify_kernel(const SampleArgs a
   const Items I = my_items(a);
   if (I.i0 >= I.i1) return;
   const uint32_t* hot_bits = a.hot_bits;
-  const bool use_hot = hot_bits != nullptr;
+  CPHASE(0);
   int cur = -1;
   WideRow W;
   int bstar = -1;
@@ -371,6 +383,7 @@ __global__ __launch_bounds__(WT, 5) void wide_classify_kernel(const SampleArgs a
       cur = slot;
       const RowCut rc = row_cut(S, W);
       bstar = rc.bstar; thr_y = rc.thr_y; valid = rc.valid;
+      CPHASE(1);
     }
     if (!valid) continue;  // the finishing kernel hands the row on
     const int c0 = sl * SLC;
@@ -391,6 +404,7 @@ __global__ __launch_bounds__(WT, 5) void wide_classify_kernel(const SampleArgs a
     __syncthreads();
     if (W.h_active) slice_counts(Tb, W.ws, a);
     __syncthreads();
+    CPHASE(2);
     unsigned n_sure = 0u;
     u64 acc_all = 0ull;  // exact mass of every column of the slice
     float ymax = -INFINITY;  // largest tempered value
@@ -415,6 +429,7 @@ __global__ __launch_bounds__(WT, 5) void wide_classify_kernel(const SampleArgs a
       }
     };
     if (W.h_active) for_history_columns<DT>(Tb, W, rowp, c0, V, one);
+    CPHASE(3);
     u64 acc0 = 0ull, acc1 = 0ull;
 #pragma unroll
     for (int j = 0; j < G; ++j) {
@@ -436,7 +451,7 @@ __global__ __launch_bounds__(WT, 5) void wide_classify_kernel(const SampleArgs a
           ymax = fmaxf(ymax, y);
           const uint32_t m = below ? (uint32_t)mass_fix_below(w) : 0u;
           const uint32_t ms = sure ? m : 0u;
-          const bool hot = ((hq[j] >> e) & 1u) != 0u;
+          const bool hot = use_hot && ((hq[j] >> e) & 1u) != 0u;
           gall += m;
           g0 += hot ? 0u : ms;
           g1 += hot ? ms : 0u;
@@ -454,7 +469,7 @@ __global__ __launch_bounds__(WT, 5) void wide_classify_kernel(const SampleArgs a
               if (!(w <= W_LIMIT)) { bad = true; continue; }
               const u64 m = mass_fix(w);
               acc_all += m;
-              if (y >= thr_y) { if ((hq[j] >> e) & 1u) acc1 += m; else acc0 += m; }
+              if (y >= thr_y) { if (use_hot && ((hq[j] >> e) & 1u)) acc1 += m; else acc0 += m; }
             }
           }
         }
@@ -474,6 +489,7 @@ __global__ __launch_bounds__(WT, 5) void wide_classify_kernel(const SampleArgs a
           if (!(W.h_active && slice_bit(idx - c0, Tb))) one(Io<DT>::one(rowp + idx), idx);
       }
     }
+    CPHASE(4);
     {
       const u64 s0 = wave_sum(acc0);
       if (lane == 0 && s0) atomicAdd(&ltile[0], s0);
@@ -502,6 +518,7 @@ __global__ __launch_bounds__(WT, 5) void wide_classify_kernel(const SampleArgs a
     for (unsigned t = tid; t < min(nb, (unsigned)ICAP); t += WT)
       if (base + t < (unsigned)RCAP) reinterpret_cast<u64*>(W.ws + WS_RL)[base + t] = lrl[t];
     __syncthreads();
+    CPHASE(5);
   }
 }
 
@@ -736,7 +753,7 @@ __global__ __launch_bounds__(WT) void wide_finish_kernel(const SampleArgs a) {
 
 #ifdef SIMPLE_PHASE_TIMES
 extern "C" int simple_debug_wide_phase_times(unsigned long long* dst_host, int n) {
-  return (int)hipMemcpyFromSymbol(dst_host, HIP_SYMBOL(simple::fast::g_wide_phase_times), sizeof(unsigned long long) * 8 * (size_t)n);  // n <= 2 * 8192
+  return (int)hipMemcpyFromSymbol(dst_host, HIP_SYMBOL(simple::fast::g_wide_phase_times), sizeof(unsigned long long) * 8 * (size_t)n);  // n <= 3 * 8192
 }
 #endif
 
@@ -744,11 +761,13 @@ hipError_t launch_wide(const SampleArgs& a, int dtype, hipStream_t st) {
   const dim3 grid(4096), fin(1024), blk(fast::WT);
   if (dtype == SIMPLE_F32) {
     hipLaunchKernelGGL((fast::wide_bins_kernel<float>), grid, blk, 0, st, a);
-    hipLaunchKernelGGL((fast::wide_classify_kernel<float>), grid, blk, 0, st, a);
+    if (a.hot_bits) hipLaunchKernelGGL((fast::wide_classify_kernel<float, true>), grid, blk, 0, st, a);
+    else hipLaunchKernelGGL((fast::wide_classify_kernel<float, false>), grid, blk, 0, st, a);
     hipLaunchKernelGGL((fast::wide_finish_kernel<float>), fin, blk, 0, st, a);
   } else {
     hipLaunchKernelGGL((fast::wide_bins_kernel<uint16_t>), grid, blk, 0, st, a);
-    hipLaunchKernelGGL((fast::wide_classify_kernel<uint16_t>), grid, blk, 0, st, a);
+    if (a.hot_bits) hipLaunchKernelGGL((fast::wide_classify_kernel<uint16_t, true>), grid, blk, 0, st, a);
+    else hipLaunchKernelGGL((fast::wide_classify_kernel<uint16_t, false>), grid, blk, 0, st, a);
     hipLaunchKernelGGL((fast::wide_finish_kernel<uint16_t>), fin, blk, 0, st, a);
   }
   return hipGetLastError();
