@@ -18,6 +18,7 @@ struct simple_ctx {
   int64_t hot_V;        // V the installed hot set was built for, 0 if none
   int32_t hot_H;
   int lds_limit;
+  int n_cu;
   uint32_t* pend;       // device: queue of rows the single-pass kernel leaves to the general kernel
   uint32_t* wq;         // device: queue of rows for the whole-vocabulary-nucleus kernels
   unsigned char* wws;   // device: their workspace, WIDE_SLOTS slots
@@ -114,13 +115,15 @@ int simple_create(simple_ctx** out, int device, int64_t max_V, int64_t max_nnz_p
   if (!guard.ok) return SIMPLE_EDEVICE;
   int lds = 0;
   if (hipDeviceGetAttribute(&lds, hipDeviceAttributeMaxSharedMemoryPerBlock, device) != hipSuccess) return SIMPLE_EDEVICE;
+  int n_cu = 0;
+  if (hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, device) != hipSuccess || n_cu <= 0) return SIMPLE_EDEVICE;
   const simple::LdsLayout L = simple::make_layout(max_V, max_nnz_per_row, max_nnz_per_row > 0);
   if ((int64_t)L.total + 1024 > (int64_t)lds) return SIMPLE_ECAPACITY;
   if (simple::set_max_lds((unsigned)lds - 1024u) != hipSuccess) return SIMPLE_EDEVICE;
   if (simple::set_max_lds_fast((unsigned)lds - 1024u) != hipSuccess) return SIMPLE_EDEVICE;
   simple_ctx* c = new (std::nothrow) simple_ctx();
   if (!c) return SIMPLE_ENOMEM;
-  c->device = device; c->max_V = max_V; c->max_nnz = max_nnz_per_row; c->lds_limit = lds;
+  c->device = device; c->max_V = max_V; c->max_nnz = max_nnz_per_row; c->lds_limit = lds; c->n_cu = n_cu;
   c->hot_V = 0; c->hot_H = 0; c->hot_bits = nullptr; c->hot_flags = nullptr; c->pend = nullptr; c->wq = nullptr; c->wws = nullptr; c->ws_stride = 0; c->parity = 0;
   c->prof_ev = nullptr; c->prof_n = 0;
   const size_t words = (size_t)((max_V + 31) / 32) + 1;
@@ -259,6 +262,7 @@ int simple_sample(simple_ctx* ctx, const void* logits_dev, int64_t B, int64_t V,
   a.seed = seed; a.step = step;
   a.max_nnz = (int)ctx->max_nnz;
   a.pend = ctx->pend;
+  a.n_cu = ctx->n_cu;
   a.wq = ctx->wq; a.wws = ctx->wws; a.wide_slots = simple::WIDE_SLOTS; a.ws_stride = ctx->ws_stride;
   a.L = simple::make_layout(V, ctx->max_nnz, hist_ptr_dev != nullptr);
   a.F = simple::make_fast_layout(V, dtype, hist_ptr_dev ? ctx->max_nnz : 0, hist_ptr_dev != nullptr, vec, ctx->lds_limit);

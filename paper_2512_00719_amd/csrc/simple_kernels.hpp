@@ -62,6 +62,7 @@ struct SampleArgs {
   int wide_slots;
   uint32_t ws_stride;  // bytes per slot: fixed part, then the row's history tables
   int parity;
+  int n_cu;        // compute units of the device (sizes the grids of the sliced kernels)
   LdsLayout L;
   FastLayout F;
 };

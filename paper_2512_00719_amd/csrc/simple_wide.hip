@@ -231,7 +231,7 @@ __device__ __forceinline__ Items my_items(const SampleArgs& a) {
 
 // ---------------------------------------------------------------- bins ------------------------
 template <typename DT>
-__global__ __launch_bounds__(WT, 8) void wide_bins_kernel(const SampleArgs a) {
+__global__ __launch_bounds__(WT, 6) void wide_bins_kernel(const SampleArgs a) {
   constexpr int EPL = Io<DT>::EPL;
   constexpr int G = SLC / (WT * EPL);
   typedef typename Io<DT>::Raw Raw;
@@ -758,16 +758,18 @@ extern "C" int simple_debug_wide_phase_times(unsigned long long* dst_host, int n
 #endif
 
 hipError_t launch_wide(const SampleArgs& a, int dtype, hipStream_t st) {
-  const dim3 grid(4096), fin(1024), blk(fast::WT);
+  // One resident round of workgroups each: six (bins) and five (classify) per compute unit fit by
+  // registers and LDS; a workgroup then takes a contiguous run of slices, mostly of one row.
+  const dim3 bins((unsigned)a.n_cu * 6u), cls((unsigned)a.n_cu * 5u), fin(1024), blk(fast::WT);
   if (dtype == SIMPLE_F32) {
-    hipLaunchKernelGGL((fast::wide_bins_kernel<float>), grid, blk, 0, st, a);
-    if (a.hot_bits) hipLaunchKernelGGL((fast::wide_classify_kernel<float, true>), grid, blk, 0, st, a);
-    else hipLaunchKernelGGL((fast::wide_classify_kernel<float, false>), grid, blk, 0, st, a);
+    hipLaunchKernelGGL((fast::wide_bins_kernel<float>), bins, blk, 0, st, a);
+    if (a.hot_bits) hipLaunchKernelGGL((fast::wide_classify_kernel<float, true>), cls, blk, 0, st, a);
+    else hipLaunchKernelGGL((fast::wide_classify_kernel<float, false>), cls, blk, 0, st, a);
     hipLaunchKernelGGL((fast::wide_finish_kernel<float>), fin, blk, 0, st, a);
   } else {
-    hipLaunchKernelGGL((fast::wide_bins_kernel<uint16_t>), grid, blk, 0, st, a);
-    if (a.hot_bits) hipLaunchKernelGGL((fast::wide_classify_kernel<uint16_t, true>), grid, blk, 0, st, a);
-    else hipLaunchKernelGGL((fast::wide_classify_kernel<uint16_t, false>), grid, blk, 0, st, a);
+    hipLaunchKernelGGL((fast::wide_bins_kernel<uint16_t>), bins, blk, 0, st, a);
+    if (a.hot_bits) hipLaunchKernelGGL((fast::wide_classify_kernel<uint16_t, true>), cls, blk, 0, st, a);
+    else hipLaunchKernelGGL((fast::wide_classify_kernel<uint16_t, false>), cls, blk, 0, st, a);
     hipLaunchKernelGGL((fast::wide_finish_kernel<uint16_t>), fin, blk, 0, st, a);
   }
   return hipGetLastError();
