@@ -65,9 +65,8 @@ FastLayout make_fast_layout(int64_t V, int dtype, int64_t max_nnz, bool with_his
   const uint32_t tables = 256u * 12u + 256u * 16u;           // bucket tables of the long-list epilogue
   uint32_t body = off < 28672u ? 28672u : off;               // >= 14 KB of sorted-epilogue arrays, >= 3072-entry list
   F.long_cap = (body - tables) / 8u;
-  F.hist = body;
-  F.samp = body + 8192u;
-  const uint32_t total = body + 8192u + 1024u;
+  F.samp = body;
+  const uint32_t total = body + 1024u;
   F.threads = ((int64_t)total + 1024 <= (int64_t)lds_limit / 4) ? 256 : 512;
   const uint32_t reg_cap = (uint32_t)(CAPF_PER_THREAD * F.threads);  // the epilogue moves the list to registers
   F.list_cap = body / 8u < reg_cap ? body / 8u : reg_cap;

@@ -27,7 +27,6 @@ struct FastLayout {
   uint32_t cnt;       // 16-bit generated-token counts, indexed by the rank of the id among the set bits
   uint32_t list_cap;  // entries of the candidate list (value word + id word each) the region holds
   uint32_t long_cap;  // entries of a long certified list that fit beside its bucket tables
-  uint32_t hist;      // 8 KB behind the region: mass histogram of the stream, later per-tile masses
   uint32_t samp;      // threshold sample merge area
   uint32_t total;     // 0: the call cannot use the kernel
   int threads;        // workgroup size the layout was made for (256 or 512)

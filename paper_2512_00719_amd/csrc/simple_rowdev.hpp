@@ -81,7 +81,6 @@ struct FS {
   unsigned wcnt[16];
   unsigned r32a[16], r32b[16];
   u64 r64a[16], r64b[16];
-  double rd[16];
 };
 
 // Per-row constants, identical in every thread.
@@ -111,17 +110,6 @@ __device__ inline u64 blk_sum_u64(FS& S, u64 v) {
   unsigned a = 0, b = 0; u64 c = 0;
   blk_reduce<NWV>(S, a, b, c, v);
   return v;
-}
-template <int NWV>
-__device__ inline double blk_sum_f64(FS& S, double v) {  // fixed tree: bit-reproducible
-  v = wave_sum(v);
-  __syncthreads();
-  if (lane_id() == 0) S.rd[wave_id()] = v;
-  __syncthreads();
-  double t = 0.0;
-#pragma unroll
-  for (int w = 0; w < NWV; ++w) t += S.rd[w];
-  return t;
 }
 // Exclusive scans of one (count, mass) pair per thread, with totals.
 template <int NWV>
@@ -248,7 +236,6 @@ __device__ __forceinline__ u64 mass_fix_below(float w) { return (u64)(uint32_t)(
 __device__ __forceinline__ uint32_t below_term(float z, const StreamCtx& C) {
   return (uint32_t)__builtin_amdgcn_exp2f(fmaf(z - C.g, C.l2e_tau, 28.0f));
 }
-__device__ __forceinline__ u64 hist_entry(float w) { return (1ull << 46) | mass_fix_below(w); }
 
 }  // namespace fast
 }  // namespace simple
