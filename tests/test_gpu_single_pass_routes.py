@@ -230,3 +230,36 @@ def test_nucleus_rows_whose_candidates_overflow_the_list():
         assert ((f & WIDE) > 0).all()
         # tie groups wider than the boundary table may still need the general kernel
         assert ((f & GENERAL) > 0).sum() <= B
+
+
+def test_rows_the_sliced_kernels_hand_on():
+    """Cases the sliced kernels detect and leave to the general kernel: a cut inside a plateau of
+    equal values wider than the boundary table (spread out, and packed into one slice), a mass the
+    fixed point cannot carry on a row without truncation, and data errors on such rows."""
+    rng = np.random.default_rng(31)
+    B, V = 8, 50_000
+    z = (rng.standard_normal((B, V)) * 0.5 - 12.0).astype(np.float32)
+    head = rng.choice(V, 300, replace=False)
+    z[:, head] = (rng.standard_normal((B, 300)) * 0.3 + 1.0).astype(np.float32)   # about half of the mass
+    spread = rng.choice(np.setdiff1d(np.arange(V), head), 9000, replace=False)
+    z[0, spread] = -2.5    # 9000 equal columns carrying the other half: the 0.8 cut falls among them
+    z[1, spread] = -2.5
+    packed = np.setdiff1d(np.arange(3000, 9000), head)
+    z[2, packed] = -2.0    # the same, packed into two slices
+    z[3] = (rng.standard_normal(V) * 1.0).astype(np.float32)
+    z[3, 777] = 120.0      # no truncation and one dominant logit: exp overflows the fixed point
+    z[4] = z[3]
+    z[4, 778] = np.nan     # data errors on rows without truncation
+    z[5] = z[3]
+    z[5, 779] = np.inf
+    z[6] = -np.inf         # nothing to draw from
+    params = synth.make_params(B, temperature=[1.0, 0.9, 1.0, 1.0, 1.0, 1.0, 1.0, 0.8],
+                               top_p=[0.8, 0.8, 0.8, 1.0, 1.0, 1.0, 1.0, 0.9])
+    w = synth.Workload("hand-on", B, V, "f32", z, params, np.zeros(B + 1, np.int64), np.zeros(0, np.int32))
+    for step in (0, 1, 2):
+        ids, dg = P.run_gpu(w, step)
+        P.compare(ids, dg, P.run_oracle(w, step), range(B))
+        f = dg["flags"]
+        assert ((f & GENERAL) > 0)[[0, 1, 2, 3, 4, 5, 6]].all(), f
+        assert ids[3] == 777 and list(ids[[4, 5, 6]]) == [-1, -1, -1] and (f[[4, 5, 6]] & 1).all()
+        assert not (f[7] & GENERAL)
