@@ -43,6 +43,10 @@
  *
  * Determinism: ids depend only on (logits, params, history, hot set, seed, step, global row
  * index), never on launch geometry or on how a batch is split into calls.
+ *
+ * Concurrency: a context owns device-side queues and workspace that every simple_sample call on
+ * it uses, so the calls on one context must be ordered: issue them on one stream (or order the
+ * streams with events), from one host thread at a time.  Different contexts are independent.
  */
 #ifndef SIMPLE_SAMPLE_H
 #define SIMPLE_SAMPLE_H
@@ -53,7 +57,7 @@
 extern "C" {
 #endif
 
-typedef struct simple_ctx simple_ctx; /* opaque; owns the hot-set bitmap */
+typedef struct simple_ctx simple_ctx; /* opaque; owns the hot-set bitmap, the row queues and their workspace */
 
 enum { SIMPLE_F32 = 0, SIMPLE_BF16 = 1 };
 
@@ -106,8 +110,10 @@ enum {
 
 /*
  * Create a context on HIP device `device` for calls with at most max_V vocabulary entries and at
- * most max_nnz_per_row history ids per row (0 if no history will ever be passed).  Allocates the
- * hot-set membership bitmap (max_V bits) in device memory.  Returns SIMPLE_ECAPACITY if one row's
+ * most max_nnz_per_row history ids per row (0 if no history will ever be passed).  Allocates, in
+ * device memory, the hot-set membership bitmap (max_V bits), the row queues and the workspace of
+ * the rows whose survivors do not fit the on-chip candidate list (1024 slots of about 52 KB plus
+ * the size of one row's history tables).  Returns SIMPLE_ECAPACITY if one row's
  * on-chip state (history bitmap, counts, candidate list) cannot fit the LDS of one compute unit.
  * Host pointers: out.
  */
