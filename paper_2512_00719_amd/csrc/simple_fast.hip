@@ -331,7 +331,7 @@ __device__ __forceinline__ int finalize_small(FS& S, const RowCfg& R, unsigned n
         m_cert = key_thr > key_g;
       }
       const bool known = R.k_on || p_found || m_cert;
-      if (!known) rc = ((R.need_sum && !R.minp_on) || (!R.k_on && !R.p_on && R.minp_on)) ? FIN_WIDE : FIN_PENDING;
+      if (!known) rc = (R.need_sum || (!R.k_on && !R.p_on && R.minp_on)) ? FIN_WIDE : FIN_PENDING;
       // every cut is a prefix of the sorted order; the first entry always survives
       const bool use_hot = hot_bits != nullptr;
       unsigned okm = 0u, hotm = 0u;
@@ -511,7 +511,7 @@ __device__ __forceinline__ int finalize_long(FS& S, const RowCfg& R, unsigned n,
     if (key_thr > key_g) { cut_m = (u64)key_thr << 32; m_cert = true; }
   }
   const bool known = R.k_on || p_found || m_cert;
-  if (!known) return ((R.need_sum && !R.minp_on) || (!R.k_on && !R.p_on && R.minp_on)) ? FIN_WIDE : FIN_PENDING;
+  if (!known) return (R.need_sum || (!R.k_on && !R.p_on && R.minp_on)) ? FIN_WIDE : FIN_PENDING;
   if (R.k_on && R.p_on && !p_found) { FWHY(203); return FIN_PENDING; }  // cannot happen: the top-k prefix holds its own mass
   u64 cut = cut_k;
   if (p_found && cut_p > cut) cut = cut_p;

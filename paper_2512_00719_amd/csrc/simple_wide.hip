@@ -204,13 +204,11 @@ __device__ inline RowCut row_cut(FS& S, const WideRow& W) {  // every thread cal
   RowCut c;
   c.thr_y = -INFINITY; c.valid = true;
   if (W.mode == WIDE_TOP_P) { c.bstar = find_cut(S, W); c.valid = c.bstar >= 0; }
-  else {
-    c.bstar = NBW;  // no bin holds a cut
-    if (W.mode == WIDE_MIN_P) {
-      const uint32_t kmax = as_global(reinterpret_cast<const uint32_t*>(W.ws + WS_SCAL))[6];
-      c.valid = kmax > KEY_NEG_INF;
-      c.thr_y = keyf(kmax) + (float)log((double)W.min_p);  // fl(y_max + fl(ln min_p)), as in the list's epilogue
-    }
+  else c.bstar = NBW;  // no bin holds a cut
+  if (W.mode != WIDE_ALL && W.min_p > 0.0f) {  // min-p, alone or on top of top-p: the shorter prefix wins
+    const uint32_t kmax = as_global(reinterpret_cast<const uint32_t*>(W.ws + WS_SCAL))[6];
+    c.valid = c.valid && kmax > KEY_NEG_INF;
+    c.thr_y = keyf(kmax) + (float)log((double)W.min_p);  // fl(y_max + fl(ln min_p)), as in the list's epilogue
   }
   return c;
 }
@@ -249,7 +247,7 @@ __global__ __launch_bounds__(WT, 6) void wide_bins_kernel(const SampleArgs a) {
   int cur = -1;
   WideRow W;
   u64 mtop = 0ull;
-  float ymax = -INFINITY;  // min-p rows: largest tempered value seen by this thread
+  float ymax = -INFINITY;  // rows with a min-p cut: largest tempered value seen by this thread
   auto flush = [&]() {
     __syncthreads();
     if (W.mode == WIDE_TOP_P) {
@@ -257,7 +255,8 @@ __global__ __launch_bounds__(WT, 6) void wide_bins_kernel(const SampleArgs a) {
       for (int b = tid; b < NBW; b += WT) { const u64 v = lh[b]; if (v) atomicAdd(&gh[b], v); }
       const u64 t = blk_sum_u64<WNW>(S, mtop);
       if (tid == 0 && t) atomicAdd(reinterpret_cast<u64*>(W.ws + WS_SCAL), t);
-    } else if (W.mode == WIDE_MIN_P) {
+    }
+    if (W.min_p > 0.0f) {
       const float m = wave_max(ymax);
       if ((tid & 63) == 0 && m > -INFINITY) atomicMax(reinterpret_cast<uint32_t*>(W.ws + WS_SCAL) + 6, fkey(m));
     }
@@ -290,8 +289,9 @@ __global__ __launch_bounds__(WT, 6) void wide_bins_kernel(const SampleArgs a) {
     WPHASE(2);
     auto one = [&](float z, int) {
       if (W.mode == WIDE_MIN_P) { ymax = fmaxf(ymax, tempered(z, W.C)); return; }
-      int b;
-      const float w = mass_term(z, W.C, b);
+      int b; float y;
+      const float w = mass_term(z, W.C, b, y);
+      ymax = fmaxf(ymax, y);
       if (z < W.C.g) atomicAdd(&lh[b], mass_fix_below(w));
       else mtop += mass_fix(fminf(w, W_LIMIT));
     };
@@ -328,6 +328,7 @@ __global__ __launch_bounds__(WT, 6) void wide_bins_kernel(const SampleArgs a) {
 #pragma unroll
           for (int e = 0; e < EPL; ++e) z[e] = ((nib >> e) & 1u) ? -INFINITY : z[e];
         }
+        float zm = -INFINITY;
 #pragma unroll
         for (int e = 0; e < EPL; ++e) {  // straight-line: a column at or above g adds zero to its bin
           int b;
@@ -335,7 +336,9 @@ __global__ __launch_bounds__(WT, 6) void wide_bins_kernel(const SampleArgs a) {
           const bool below = z[e] < W.C.g;
           atomicAdd(&lh[b], below ? mass_fix_below(w) : 0ull);
           any_top = any_top || !below;
+          zm = fmaxf(zm, z[e]);
         }
+        if (W.min_p > 0.0f) ymax = fmaxf(ymax, tempered(zm, W.C));  // the tempered value is monotone in z
         if (__ballot(any_top)) {  // few columns: the 64-bit conversion stays out of the main line
 #pragma unroll
           for (int e = 0; e < EPL; ++e)
@@ -457,7 +460,7 @@ __global__ __launch_bounds__(WT, 5) void wide_classify_kernel(const SampleArgs a
           g1 += hot ? ms : 0u;
           n_sure += sure ? 1u : 0u;
           any_top = any_top || !below;
-          any_edge = any_edge || (((live >> e) & 1u) && below && b == bstar);
+          any_edge = any_edge || (((live >> e) & 1u) && below && b == bstar && y >= thr_y);
         }
         acc0 += (u64)g0; acc1 += (u64)g1; acc_all += (u64)gall;
         if (__ballot(any_top)) {
@@ -476,9 +479,9 @@ __global__ __launch_bounds__(WT, 5) void wide_classify_kernel(const SampleArgs a
         if (__ballot(any_edge)) {
 #pragma unroll
           for (int e = 0; e < EPL; ++e) {
-            int b;
-            (void)mass_term(z[e], W.C, b);
-            if (((live >> e) & 1u) && z[e] < W.C.g && b == bstar) {
+            int b; float y;
+            (void)mass_term(z[e], W.C, b, y);
+            if (((live >> e) & 1u) && z[e] < W.C.g && b == bstar && y >= thr_y) {
               const unsigned s = atomicAdd(&l_n, 1u);
               if (s < (unsigned)ICAP) lrl[s] = ((u64)__float_as_uint(z[e]) << 32) | (u64)(uint32_t)(idx0 + e);
             }
@@ -557,14 +560,17 @@ __device__ inline bool finish_row(const SampleArgs& a, const WideRow& W, FS& S, 
   XPHASE(1);
   if (!rcut.valid) { XWHY(1, 0); return false; }
   const bool top_p_route = W.mode == WIDE_TOP_P;
-  // a count past the limit is also how the classifying pass reports a row it could not handle
-  if (n_r > (unsigned)RCAP || (n_r == 0u) == top_p_route) { XWHY(2, n_r); return false; }
+  // a count past the limit is also how the classifying pass reports a row it could not handle; no
+  // collected column on the top-p route means that a min-p cut ended the survivors above the bin
+  const bool minp_too = top_p_route && W.min_p > 0.0f;
+  if (n_r > (unsigned)RCAP || (!top_p_route && n_r != 0u) || (top_p_route && n_r == 0u && !minp_too)) { XWHY(2, n_r); return false; }
   if (tid == 0) { S.bd = -1; S.cut_k = 0ull; S.cut_p = ~0ull; S.out_id = -1; S.out_w = 0ull; }
   tiles[tid] = tv[0]; tiles[WT + tid] = tv[1];
   const u64 msure = tv[0] + tv[1];
   u64 cut_found = 0ull;  // every collected column at or after it in the order survives; 0: no collected columns
   unsigned r_in = 0;
-  if (top_p_route) {
+  if (top_p_route && n_r == 0u) cut_found = ~0ull;  // nothing of the bin survives
+  if (top_p_route && n_r != 0u) {
   // exact masses from here: the columns surely inside must stay below the target, the collected bin must reach it
   const u64 m_above = blk_sum_u64<WNW>(S, msure);  // barriers inside
   const u64 target = (u64)__double2ull_ru((double)W.top_p * (double)S_tot);
@@ -632,8 +638,10 @@ __device__ inline bool finish_row(const SampleArgs& a, const WideRow& W, FS& S, 
       __syncthreads();
     }
     if (differ == 0ull && m_above + (u64)rl[0] < target) ok = false;  // a single column, and it does not reach the target
-    if (!ok) { XWHY(4, 0); return false; }
-    cut_found = prefix;
+    // the collected columns do not reach the target: with a min-p cut those below it were never
+    // collected, and the min-p prefix is the shorter one (all collected columns survive)
+    if (!ok && !minp_too) { XWHY(4, 0); return false; }
+    cut_found = ok ? prefix : 1ull;
   }
   XPHASE(2);
   if (cut_found == 0ull) { XWHY(6, 0); return false; }

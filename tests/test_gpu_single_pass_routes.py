@@ -263,3 +263,29 @@ def test_rows_the_sliced_kernels_hand_on():
         assert ((f & GENERAL) > 0)[[0, 1, 2, 3, 4, 5, 6]].all(), f
         assert ids[3] == 777 and list(ids[[4, 5, 6]]) == [-1, -1, -1] and (f[[4, 5, 6]] & 1).all()
         assert not (f[7] & GENERAL)
+
+
+def test_top_p_and_min_p_together_beyond_the_list():
+    """Both cuts on a flat row: the shorter prefix wins, whichever it is (min-p above the nucleus'
+    boundary bin, inside it, or below it), with history, bf16 ties and SHVS."""
+    rng = np.random.default_rng(32)
+    B, V = 12, 44_000
+    z = _flat_logits(rng, B, V, sigma=1.3)
+    lens = rng.integers(0, 1000, B)
+    hist_ptr, hist_ids = _head_history(z, lens, rng, head=900)
+    params = synth.make_params(B, temperature=[1.0, 1.2, 0.9] * 4,
+                               top_p=[0.9, 0.9, 0.9, 0.97, 0.97, 0.97, 0.6, 0.6, 0.6, 0.999, 0.999, 0.999],
+                               min_p=[1e-2, 1e-3, 1e-4, 3e-3, 3e-4, 1e-5, 2e-2, 2e-3, 1e-6, 1e-3, 1e-4, 1e-5],
+                               rep_penalty=1.15, freq_penalty=0.2, pres_penalty=0.1)
+    w = synth.Workload("p+minp", B, V, "f32", z, params, hist_ptr, hist_ids)
+    n_seen = set()
+    for ids, dg in _run(w, steps=(0, 1, 2)):
+        f = dg["flags"]
+        assert ((f & WIDE) > 0).sum() >= 8 and not ((f & GENERAL) > 0).any()
+        n_seen.update(int(x) for x in dg["n_survivors"])
+    assert len(n_seen) >= 8  # the cuts differ from row to row
+    bits = synth.f32_to_bf16_bits(z)
+    hot = np.sort(np.argsort(-z.mean(axis=0))[:1500]).astype(np.int32)
+    wb = synth.Workload("p+minp-bf16", B, V, "bf16", bits, params, hist_ptr, hist_ids, hot_ids=hot)
+    for ids, dg in _run(wb, steps=(0, 1)):
+        assert not ((dg["flags"] & GENERAL) > 0).any()
