@@ -99,8 +99,8 @@ def main() -> int:
                          "HBM traffic, to scale rocprofv3 FETCH_SIZE / WRITE_SIZE readings)")
     args = ap.parse_args()
     if args.gpus != 1:
-        print("bench.py: this build runs on ONE GPU; --gpus N with N > 1 is not supported "
-              "(rows shard trivially across GPUs, see DESIGN.md)", file=sys.stderr)
+        print("bench.py: the library runs on ONE GPU; --gpus N with N > 1 is not supported "
+              "(rows are independent: N GPUs would each take B / N rows and call it unchanged)", file=sys.stderr)
         return 2
 
     import torch
