@@ -72,7 +72,7 @@ __device__ __forceinline__ uint32_t wave_threshold(const uint32_t (&k)[N], unsig
 __device__ __forceinline__ u64 wfix(uint32_t key, float y_max) {
   const float d = keyf(key) - y_max;
   const float t = fmaf(d, L2E_HI, d * L2E_LO);
-  return (u64)__double2ull_rn((double)__builtin_amdgcn_exp2f(t) * WSCALE);
+  return float_to_u64(__builtin_amdgcn_exp2f(t) * 0x1p44f);  // the scaling is exact
 }
 
 // ---------------------------------------------------------------- history ---------------------
@@ -897,7 +897,7 @@ __global__ __launch_bounds__(NTHR, 4) void fast_rows_kernel(const SampleArgs a) 
         const float z = ez[j];
         if (z != z || z == INFINITY) err = true;
         else if (!(z < C.g)) {
-          const float y = R.greedy ? z : z / R.tau;
+          const float y = R.greedy ? z : tempered(z, C);  // the IEEE quotient z / tau
           if (y == INFINITY) err = true;
           else {
             key[j] = fkey(y);

@@ -225,7 +225,14 @@ __device__ __forceinline__ float mass_term(float z, const StreamCtx& C, int& bin
 }
 __device__ __forceinline__ float mass_term(float z, const StreamCtx& C, int& bin) { float y; return mass_term(z, C, bin, y); }
 constexpr float W_LIMIT = 2097152.0f;  // 2^21: largest mass relative to the one at g that the 2^28 fixed point carries
-__device__ __forceinline__ u64 mass_fix(float w) { return (u64)(w * MSCALE + 0.5f); }
+// Nearest integer of a float in [0, 2^52) as 64 bits, in two 32-bit conversions (the split is exact:
+// a float has 24 significant bits).
+__device__ __forceinline__ u64 float_to_u64(float v) {
+  const float hi = floorf(v * 0x1p-24f);
+  const float lo = v - hi * 0x1p24f;
+  return ((u64)(uint32_t)hi << 24) + (u64)(uint32_t)(lo + 0.5f);
+}
+__device__ __forceinline__ u64 mass_fix(float w) { return float_to_u64(w * MSCALE); }
 // same integer for w <= 1 (every column below g), one conversion instruction
 __device__ __forceinline__ u64 mass_fix_below(float w) { return (u64)(uint32_t)(w * MSCALE + 0.5f); }
 // Mass of a column below g for the single-pass kernel's running total: exp((z - g) / tau) * 2^28
