@@ -161,6 +161,8 @@ def main() -> int:
     n_rec, total_ms = binding.simple_profile_read(s.ctx)
     assert n_rec == timed, (n_rec, timed)
     kern_ms = total_ms / n_rec  # average launch duration of the dominant kernel
+    per_launch = binding.simple_profile_read_launches(s.ctx)
+    p10, p50, p90 = (float(x) for x in np.percentile(per_launch, [10, 50, 90]))
     binding.simple_profile_enable(s.ctx, False)
     ms_per_step = wall * 1e3 / args.steps
     rows_per_s = w.B * args.steps / wall
@@ -179,6 +181,30 @@ def main() -> int:
         stats["H"] = int(w.hot_ids.size)
     achieved = alg_bytes / (kern_ms * 1e-3) / 1e9
     s.close()
+
+    # What a one-pass row kernel can reach here: the library's read-only row-maximum reduction over
+    # the same logits copies, timed with events on the stream it is launched on.
+    row_max = torch.empty(w.B, dtype=torch.float32, device=dev)
+    stream = torch.cuda.current_stream()
+    dt_code = binding.SIMPLE_F32 if w.dtype == "f32" else binding.SIMPLE_BF16
+
+    def probe(i: int):
+        lg = logits[i % n_copies]
+        rc = binding.simple_stream_probe(lg.data_ptr(), w.B, w.V, dt_code, lg.stride(0), row_max.data_ptr(),
+                                         stream.cuda_stream)
+        assert rc == 0, rc
+
+    n_probe = 50
+    for i in range(5):
+        probe(i)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record(stream)
+    for i in range(n_probe):
+        probe(5 + i)
+    e1.record(stream)
+    e1.synchronize()
+    probe_ms = e0.elapsed_time(e1) / n_probe
+    ceiling = (w.B * w.V * esize + w.B * 4) / (probe_ms * 1e-3) / 1e9
     if args.copy_probe_mib > 0:
         src = torch.ones(args.copy_probe_mib << 18, dtype=torch.float32, device=dev)
         dst = torch.empty_like(src)
@@ -197,7 +223,11 @@ def main() -> int:
                    "input_copies_rotated": n_copies, **stats},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": PEAK_HBM_GBS, "unit": "GB/s",
                      "frac": achieved / PEAK_HBM_GBS, "traffic": recorded_traffic(args.config),
-                     "kernel": "simple::fast::fast_rows_kernel", "kernel_ms": kern_ms, "algorithmic_bytes": alg_bytes,
+                     "kernel": "simple::fast::fast_rows_kernel", "kernel_ms": kern_ms,
+                     "kernel_ms_p10_p50_p90": [p10, p50, p90], "algorithmic_bytes": alg_bytes,
+                     "stream_ceiling": {"what": "read-only row-maximum reduction over the same logits",
+                                        "ms": probe_ms, "achieved": ceiling, "frac_of_peak": ceiling / PEAK_HBM_GBS},
+                     "frac_of_stream_ceiling": achieved / ceiling,
                      "step_ms": ms_per_step, "step_frac": alg_bytes / (ms_per_step * 1e-3) / 1e9 / PEAK_HBM_GBS},
     }
     if not args.no_cpu_baseline:

@@ -166,10 +166,26 @@ int simple_sample(simple_ctx* ctx, const void* logits_dev, int64_t B, int64_t V,
  * not recorded) and resets the record; simple_profile_enable(ctx, 0) destroys them.
  * simple_profile_read synchronises with the recorded events and returns the number of recorded
  * launches; *total_ms_host (host pointer) receives the sum of their durations in milliseconds.
- * Returns a negative error code on failure.
+ * simple_profile_read_launches does the same and also writes the duration of each of the first
+ * min(cap, recorded) launches, in launch order, to ms_host[] (host pointer, cap floats; may be
+ * NULL with cap = 0).  Both return a negative error code on failure.
  */
 int simple_profile_enable(simple_ctx* ctx, int on);
 int simple_profile_read(simple_ctx* ctx, double* total_ms_host);
+int simple_profile_read_launches(simple_ctx* ctx, float* ms_host, int cap, double* total_ms_host);
+
+/*
+ * Bandwidth yardstick for benchmarks (not part of the method): a read-only streaming reduction
+ * over the same kind of buffer simple_sample reads.  row_max_dev[b] (device, B floats, written)
+ * receives the maximum of the first V columns of row b, NaNs ignored, -inf for none; one
+ * workgroup per row with the sampling kernel's load pattern and none of its arithmetic, so its
+ * rate is the ceiling a one-pass row kernel can reach on the device.  Enqueued on hip_stream on
+ * the current device; no context is needed and nothing is allocated.  logits_dev and every row
+ * must be 16-byte aligned (SIMPLE_EINVAL otherwise, as for NULL pointers, B < 0, V <= 0,
+ * row_stride_elems < V or an unknown dtype); B = 0 is a no-op.
+ */
+int simple_stream_probe(const void* logits_dev, int64_t B, int64_t V, int dtype, int64_t row_stride_elems,
+                        float* row_max_dev, void* hip_stream);
 
 /* Bytes of LDS one row's workgroup uses for the given context (for occupancy reasoning). */
 int64_t simple_lds_bytes(const simple_ctx* ctx);

@@ -30,7 +30,8 @@ ROW_DIAG_DTYPE = np.dtype([("alpha", "<f8"), ("s_k", "<f8"), ("p_chosen", "<f4")
 assert ROW_DIAG_DTYPE.itemsize == 32
 
 EXPORTS = ("simple_create", "simple_destroy", "simple_set_hot_set", "simple_sample",
-           "simple_profile_enable", "simple_profile_read",
+           "simple_profile_enable", "simple_profile_read", "simple_profile_read_launches",
+           "simple_stream_probe",
            "simple_lds_bytes", "simple_strerror", "simple_version")
 
 
@@ -52,6 +53,11 @@ def _load() -> ctypes.CDLL:
     lib.simple_profile_enable.restype = ctypes.c_int
     lib.simple_profile_read.argtypes = [vp, ctypes.POINTER(ctypes.c_double)]
     lib.simple_profile_read.restype = ctypes.c_int
+    lib.simple_profile_read_launches.argtypes = [vp, ctypes.POINTER(ctypes.c_float), ctypes.c_int,
+                                                 ctypes.POINTER(ctypes.c_double)]
+    lib.simple_profile_read_launches.restype = ctypes.c_int
+    lib.simple_stream_probe.argtypes = [vp, i64, i64, ctypes.c_int, i64, vp, vp]
+    lib.simple_stream_probe.restype = ctypes.c_int
     lib.simple_lds_bytes.argtypes = [vp]
     lib.simple_lds_bytes.restype = i64
     lib.simple_strerror.argtypes = [ctypes.c_int]
@@ -106,6 +112,24 @@ def simple_profile_read(ctx: int) -> tuple[int, float]:
     if n < 0:
         raise SimpleError(n, "simple_profile_read")
     return n, float(total.value)
+
+
+def simple_profile_read_launches(ctx: int, cap: int = 1024) -> np.ndarray:
+    """Durations in ms of the recorded launches of the dominant kernel, in launch order."""
+    buf = (ctypes.c_float * max(cap, 1))()
+    total = ctypes.c_double(0.0)
+    n = int(_lib.simple_profile_read_launches(ctypes.c_void_p(ctx), buf, int(cap), ctypes.byref(total)))
+    if n < 0:
+        raise SimpleError(n, "simple_profile_read_launches")
+    return np.frombuffer(buf, dtype=np.float32, count=min(n, cap)).copy()
+
+
+def simple_stream_probe(logits_ptr: int, B: int, V: int, dtype: int, row_stride: int, row_max_ptr: int,
+                        stream: int = 0) -> int:
+    """Raw call: row maxima by a read-only streaming reduction.  Returns the C status code."""
+    vp = ctypes.c_void_p
+    return int(_lib.simple_stream_probe(vp(logits_ptr), int(B), int(V), int(dtype), int(row_stride),
+                                        vp(row_max_ptr), vp(stream)))
 
 
 def simple_set_hot_set(ctx: int, hot_ids_ptr: int, H: int, V: int, stream: int = 0) -> int:

@@ -189,8 +189,8 @@ int simple_profile_enable(simple_ctx* ctx, int on) {
   return SIMPLE_OK;
 }
 
-int simple_profile_read(simple_ctx* ctx, double* total_ms_host) {
-  if (!ctx || !total_ms_host) return SIMPLE_EINVAL;
+int simple_profile_read_launches(simple_ctx* ctx, float* ms_host, int cap, double* total_ms_host) {
+  if (!ctx || !total_ms_host || cap < 0 || (cap > 0 && !ms_host)) return SIMPLE_EINVAL;
   *total_ms_host = 0.0;
   if (!ctx->prof_ev) return 0;
   simple::DeviceGuard guard(ctx->device);
@@ -200,10 +200,15 @@ int simple_profile_read(simple_ctx* ctx, double* total_ms_host) {
     if (hipEventSynchronize(ctx->prof_ev[2 * i + 1]) != hipSuccess) return SIMPLE_EDEVICE;
     float ms = 0.0f;
     if (hipEventElapsedTime(&ms, ctx->prof_ev[2 * i], ctx->prof_ev[2 * i + 1]) != hipSuccess) return SIMPLE_EDEVICE;
+    if (i < cap) ms_host[i] = ms;
     total += (double)ms;
   }
   *total_ms_host = total;
   return ctx->prof_n;
+}
+
+int simple_profile_read(simple_ctx* ctx, double* total_ms_host) {
+  return simple_profile_read_launches(ctx, nullptr, 0, total_ms_host);
 }
 
 int64_t simple_lds_bytes(const simple_ctx* ctx) {
