@@ -48,6 +48,9 @@ template <> struct Io<float> {
   __device__ static __forceinline__ Raw load(const float* p) { return __builtin_nontemporal_load(as_global(reinterpret_cast<const f32x4*>(p))); }
   __device__ static __forceinline__ void unpack(const Raw& r, float (&z)[4]) { z[0] = r.x; z[1] = r.y; z[2] = r.z; z[3] = r.w; }
   __device__ static __forceinline__ float one(const float* p) { return *as_global(p); }
+  typedef float Elem;  // one element as loaded, converted where it is used (the load stays in flight until then)
+  __device__ static __forceinline__ Elem raw(const float* p) { return *as_global(p); }
+  __device__ static __forceinline__ float cvt(Elem v) { return v; }
 };
 template <> struct Io<uint16_t> {  // bfloat16 bit patterns; the upcast to float32 is exact
   static constexpr int EPL = 8;
@@ -59,6 +62,9 @@ template <> struct Io<uint16_t> {  // bfloat16 bit patterns; the upcast to float
     for (int i = 0; i < 4; ++i) { z[2 * i] = __uint_as_float(w[i] << 16); z[2 * i + 1] = __uint_as_float(w[i] & 0xFFFF0000u); }
   }
   __device__ static __forceinline__ float one(const uint16_t* p) { return __uint_as_float((uint32_t)(*as_global(p)) << 16); }
+  typedef uint32_t Elem;
+  __device__ static __forceinline__ Elem raw(const uint16_t* p) { return (uint32_t)(*as_global(p)); }
+  __device__ static __forceinline__ float cvt(Elem v) { return __uint_as_float(v << 16); }
 };
 
 __device__ __forceinline__ u64 composite(uint32_t key, uint32_t id) { return ((u64)key << 32) | (u64)(0xFFFFFFFFu - id); }
@@ -216,25 +222,36 @@ constexpr uint32_t WS_HT = 53312u;      // the row's history tables as the singl
 // bin of y (linear in y, so columns of equal y share a bin).  y is formed as fl32(double(z) * fl64(1 /
 // tau)): the IEEE float32 quotient (see apply_penalties).  float32 exponential, split log2(e).
 __device__ __forceinline__ float tempered(float z, const StreamCtx& C) { return (float)((double)z * C.inv_tau); }
+// UNIT_TAU: the caller knows that tau == 1, where y is z itself (the same float as the product).
+template <bool UNIT_TAU = false>
 __device__ __forceinline__ float mass_term(float z, const StreamCtx& C, int& bin, float& y) {
-  y = (float)((double)z * C.inv_tau);
+  y = UNIT_TAU ? z : (float)((double)z * C.inv_tau);
   const float d = y - C.y_g;
   const float t = fmaf(d, L2E_HI, d * L2E_LO);
   bin = (int)fminf(fmaxf(-t * BINS_PER_LOG2, 0.0f), (float)(NBW - 1));
   return __builtin_amdgcn_exp2f(t);
 }
-__device__ __forceinline__ float mass_term(float z, const StreamCtx& C, int& bin) { float y; return mass_term(z, C, bin, y); }
+template <bool UNIT_TAU = false>
+__device__ __forceinline__ float mass_term(float z, const StreamCtx& C, int& bin) { float y; return mass_term<UNIT_TAU>(z, C, bin, y); }
 constexpr float W_LIMIT = 2097152.0f;  // 2^21: largest mass relative to the one at g that the 2^28 fixed point carries
 // Nearest integer of a float in [0, 2^52) as 64 bits, in two 32-bit conversions (the split is exact:
-// a float has 24 significant bits).
+// a float has 24 significant bits): hi counts units of 2^24.  The two parts of several values can
+// be summed separately in 32 bits and combined once.
+__device__ __forceinline__ void float_to_parts(float v, uint32_t& hi, uint32_t& lo) {
+  const float h = floorf(v * 0x1p-24f);
+  hi = (uint32_t)h;
+  lo = (uint32_t)(fmaf(-h, 0x1p24f, v) + 0.5f);  // v - h * 2^24 is exact either way
+}
+__device__ __forceinline__ u64 parts_to_u64(uint32_t hi, uint32_t lo) { return ((u64)hi << 24) + (u64)lo; }
 __device__ __forceinline__ u64 float_to_u64(float v) {
-  const float hi = floorf(v * 0x1p-24f);
-  const float lo = v - hi * 0x1p24f;
-  return ((u64)(uint32_t)hi << 24) + (u64)(uint32_t)(lo + 0.5f);
+  uint32_t hi, lo;
+  float_to_parts(v, hi, lo);
+  return parts_to_u64(hi, lo);
 }
 __device__ __forceinline__ u64 mass_fix(float w) { return float_to_u64(w * MSCALE); }
-// same integer for w <= 1 (every column below g), one conversion instruction
-__device__ __forceinline__ u64 mass_fix_below(float w) { return (u64)(uint32_t)(w * MSCALE + 0.5f); }
+// same integer for w <= 1 (every column below g), one conversion instruction (the product with the
+// scale is exact, so the fused form rounds once, as the sum does)
+__device__ __forceinline__ u64 mass_fix_below(float w) { return (u64)(uint32_t)fmaf(w, MSCALE, 0.5f); }
 // Mass of a column below g for the single-pass kernel's running total: exp((z - g) / tau) * 2^28
 // without the exactly rounded tempered value; the scale rides in the exponent and the conversion
 // truncates.  Relative error of the total below 1e-6 (rounding of the exponent at magnitude 28,

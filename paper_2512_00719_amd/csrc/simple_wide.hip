@@ -8,17 +8,27 @@
 //
 //   bins      per slice, the penalised, tempered logits below g are binned (bins linear in the
 //             tempered logit, 1/64 of a factor two in probability wide) with their masses relative
-//             to the mass at g (integers, LDS atomics); the mass at or above g is summed beside
-//             them.  This pass points at the bin that holds the cut.
-//   classify  that bin follows from the cumulated masses; per tile, the exact (integer) masses of
-//             the columns surely inside are summed by class (tail / hot), the columns of the
-//             cut's bin are collected, and the exact mass of the whole row is summed.
+//             to the mass at g (integers, LDS atomics); the mass at or above g goes to one more
+//             slot.  The bins are exact sums, so they also give the mass of the whole row, and they
+//             point at the bin that holds the cut.
+//   classify  that bin follows from the cumulated masses.  Tempered value, bin and the comparison
+//             with g are monotone in the logit, so the class of a column (surely inside, in the
+//             cut's bin, outside) is decided by two thresholds on the logit itself, found once per
+//             row by a search over floats.  Per tile, the exact (integer) masses of the columns
+//             surely inside are summed by class (tail / hot) and the columns of the cut's bin are
+//             collected.
 //   finish    one workgroup per row checks that the cut does lie in the collected bin (else the
 //             general kernel takes the row), finds it exactly among those columns by a radix
 //             descent over (value, id) weighted by mass, however many of them tie (total order:
 //             value descending, id ascending), applies the SHVS acceptance test (section 5.3), walks
 //             the per-tile masses of the drawn class in ascending id and reads one tile a last time
 //             to locate the drawn id (inverse CDF, step (3) of section 2.1).
+//
+// The first two kernels are software pipelines over a workgroup's slices: the loads of the next
+// slice (logits, hot-set bits, history mask) are requested before the current one is processed, and
+// a slice's own dependent loads (history counts, logits of its history columns) are requested
+// before its main line runs, so that no trip through memory is waited for in full.  Loads return in
+// order: what is needed first is requested first.
 //
 // Rows without truncation skip the first kernel and have no cut; rows with a min-p cut use the first
 // kernel for the row maximum only (the cut is a value).
@@ -28,6 +38,8 @@
 // loads its part of them into LDS.  All masses are
 // integers, so no result depends on the order of the additions.  A row for which a table overflows
 // or the passes disagree is handed to the general kernel.
+#include <type_traits>
+
 #include "simple_rowdev.hpp"
 
 namespace simple {
@@ -39,7 +51,14 @@ __device__ unsigned long long g_wide_phase_times[3 * 8192 * 8];
 #define XPHASE(i) do { if (threadIdx.x == 0 && blockIdx.x < 8192) g_wide_phase_times[(8192 + blockIdx.x) * 8 + (i)] = wall_clock64(); } while (0)
 #define XWHY(code, v) do { if (threadIdx.x == 0 && blockIdx.x < 8192) { g_wide_phase_times[(8192 + blockIdx.x) * 8 + 6] = (code); g_wide_phase_times[(8192 + blockIdx.x) * 8 + 7] = (v); } } while (0)
 #define WPHASE(i) do { if (threadIdx.x == 0 && blockIdx.x < 8192) g_wide_phase_times[blockIdx.x * 8 + (i)] = wall_clock64(); } while (0)
+// classify: time per phase summed over a workgroup's items (wave 0's clock)
+#define CACC_INIT() unsigned long long pacc_[8] = {0, 0, 0, 0, 0, 0, 0, 0}; unsigned long long plast_ = wall_clock64()
+#define CACC(i) do { const unsigned long long t_ = wall_clock64(); pacc_[i] += t_ - plast_; plast_ = t_; } while (0)
+#define CACC_DUMP() do { if (threadIdx.x == 0 && blockIdx.x < 8192) for (int q_ = 0; q_ < 8; ++q_) g_wide_phase_times[(16384 + blockIdx.x) * 8 + q_] = pacc_[q_]; } while (0)
 #else
+#define CACC_INIT() do { } while (0)
+#define CACC(i) do { } while (0)
+#define CACC_DUMP() do { } while (0)
 #define WPHASE(i) do { } while (0)
 #define XPHASE(i) do { } while (0)
 #define CPHASE(i) do { } while (0)
@@ -49,7 +68,8 @@ __device__ unsigned long long g_wide_phase_times[3 * 8192 * 8];
 constexpr int WT = 256;      // threads per workgroup
 constexpr int WNW = WT / 64;
 constexpr int SLC = 4096;    // columns per slice
-constexpr int ICAP = 1024;   // columns of the boundary bin one slice can stage
+constexpr int ICAP = 1024;   // columns of the boundary bin one slice can always stage
+constexpr int LCAP = 2048;   // size of the stage: written out once fewer than ICAP places are free
 static_assert(WS_HT == WIDE_SLOT_FIXED, "workspace slot size");
 static_assert(sizeof(WideRec) == 64, "queue record size");
 
@@ -94,10 +114,13 @@ __device__ __forceinline__ WideRow load_row(const SampleArgs& a, unsigned slot) 
 // A slice's part of the row's history tables, in LDS: the mask words of its columns, the
 // rank at the start of each of its word pairs (and of the next slice), and the counts of its
 // columns, indexed by rank minus the slice's first rank.
+constexpr int HCAP = 512;  // history columns of a slice that are spread over all threads; more stay with their mask word's thread
 struct SliceTabs {
   uint32_t bm[SLC / 32];
   uint32_t dir[SLC / 64 + 2];
   uint16_t cnt[SLC];
+  float hz[HCAP];       // logit of the history column of rank j in the slice, as read
+  uint16_t hcol[HCAP];  // its column, counted from the slice's first
 };
 static_assert(WT == 256, "the finishing kernel maps one tile of each class to a thread");
 static_assert(SLC / 32 + SLC / 64 + 1 <= WT, "one mask word or directory entry per thread");
@@ -151,21 +174,85 @@ __device__ __forceinline__ float slice_value(float z, int o, const SliceTabs& T,
   return apply_penalties(z, (uint32_t)T.cnt[min(r, (unsigned)SLC - 1u)], W.rep, W.inv_rep, W.freq, W.pres);
 }
 __device__ __forceinline__ bool slice_bit(int o, const SliceTabs& T) { return (T.bm[o >> 5] >> (o & 31)) & 1u; }
-// The history columns of a slice, one mask word per thread: f(z', idx) for each, with its penalised
-// value.  The streaming loops skip these columns, so their main line carries no table lookups.
-template <typename DT, typename F>
-__device__ __forceinline__ void for_history_columns(const SliceTabs& T, const WideRow& W, const DT* rowp, int c0, int V, F&& f) {
+// The history columns of a slice, one mask word per thread.  Their logits and the slice's counts are
+// requested first (hist_fetch, right after the mask and directory reached LDS) and used later
+// (hist_columns), so that their way through memory overlaps with the slice's main line, which skips
+// these columns and carries no table lookups.
+constexpr int HPRE = 4;  // history columns per mask word whose logits are requested ahead; more are read in place
+template <typename DT>
+struct HistPre { typename Io<DT>::Elem z[HPRE]; uint32_t cnt; };
+template <typename DT>
+__device__ __forceinline__ void hist_fetch(HistPre<DT>& P, const SliceTabs& T, const unsigned char* ws, const SampleArgs& a,
+                                           const DT* rowp, int c0, int V) {
   const int tid = threadIdx.x;
+  const uint16_t* gcnt = reinterpret_cast<const uint16_t*>(ws + WS_HT + a.F.cnt);
+  const unsigned r0 = T.dir[0];
+  const unsigned nc = min(T.dir[SLC / 64] - r0, (unsigned)SLC);
+  P.cnt = 0u;
+  if ((unsigned)tid < nc) P.cnt = (uint32_t)as_global(gcnt)[r0 + tid];
+#pragma unroll
+  for (int k = 0; k < HPRE; ++k) P.z[k] = typename Io<DT>::Elem();
   if (tid < SLC / 32) {
+    uint32_t word = T.bm[tid];
+#pragma unroll
+    for (int k = 0; k < HPRE; ++k) {
+      if (word) {
+        const int idx = c0 + 32 * tid + (__ffs((int)word) - 1);
+        word &= word - 1u;
+        if (idx < V) P.z[k] = Io<DT>::raw(rowp + idx);
+      }
+    }
+  }
+}
+// The counts go to LDS (first WT of them from the registers, the rest from memory), and so do the
+// logits and columns of the first HCAP history columns, by rank; a barrier must follow.
+template <typename DT>
+__device__ __forceinline__ void hist_stage(SliceTabs& T, const HistPre<DT>& P, const unsigned char* ws, const SampleArgs& a,
+                                           const DT* rowp, int c0, int V) {
+  int tid = threadIdx.x;
+  // the addresses below are formed here, not kept in registers across the caller's loop (a register
+  // spilled there would be reloaded through memory, behind every load in flight)
+  asm volatile("" : "+v"(tid));
+  const uint16_t* gcnt = reinterpret_cast<const uint16_t*>(ws + WS_HT + a.F.cnt);
+  const unsigned r0 = T.dir[0];
+  const unsigned nc = min(T.dir[SLC / 64] - r0, (unsigned)SLC);
+  if ((unsigned)tid < nc) T.cnt[tid] = (uint16_t)P.cnt;
+  for (unsigned t = tid + WT; t < nc; t += WT) T.cnt[t] = as_global(gcnt)[r0 + t];
+  if (tid < SLC / 32) {
+    uint32_t word = T.bm[tid];
+    unsigned r = T.dir[tid >> 1] - r0 + ((tid & 1) ? (unsigned)__popc(T.bm[tid - 1]) : 0u);
+    auto put = [&](float z_raw) {
+      T.hz[r] = z_raw;
+      T.hcol[r] = (uint16_t)(32 * tid + (__ffs((int)word) - 1));
+      word &= word - 1u;
+      ++r;
+    };
+#pragma unroll
+    for (int k = 0; k < HPRE; ++k) if (word && r < (unsigned)HCAP) put(Io<DT>::cvt(P.z[k]));
+    while (word && r < (unsigned)HCAP) {
+      const int idx = c0 + 32 * tid + (__ffs((int)word) - 1);
+      put(idx < V ? Io<DT>::one(rowp + idx) : 0.0f);
+    }
+  }
+}
+// f(z', idx) for each history column of the slice, with its penalised value: the staged ones one per
+// thread, the rest (a slice with more than HCAP of them) by their mask word's thread.
+template <typename DT, typename F>
+__device__ __forceinline__ void hist_columns(const SliceTabs& T, const WideRow& W, const DT* rowp, int c0, int V, F&& f) {
+  const int tid = threadIdx.x;
+  const unsigned nc = min(T.dir[SLC / 64] - T.dir[0], (unsigned)SLC);
+  for (unsigned j = tid; j < min(nc, (unsigned)HCAP); j += WT) {
+    const int idx = c0 + (int)T.hcol[j];
+    if (idx < V) f(apply_penalties(T.hz[j], (uint32_t)T.cnt[j], W.rep, W.inv_rep, W.freq, W.pres), idx);
+  }
+  if (nc > (unsigned)HCAP && tid < SLC / 32) {
     uint32_t word = T.bm[tid];
     unsigned r = T.dir[tid >> 1] - T.dir[0] + ((tid & 1) ? (unsigned)__popc(T.bm[tid - 1]) : 0u);
     while (word) {
       const int idx = c0 + 32 * tid + (__ffs((int)word) - 1);
       word &= word - 1u;
-      if (idx < V) {
-        const float z = apply_penalties(Io<DT>::one(rowp + idx), (uint32_t)T.cnt[min(r, (unsigned)SLC - 1u)], W.rep, W.inv_rep, W.freq, W.pres);
-        f(z, idx);
-      }
+      if (r >= (unsigned)HCAP && idx < V)
+        f(apply_penalties(Io<DT>::one(rowp + idx), (uint32_t)T.cnt[min(r, (unsigned)SLC - 1u)], W.rep, W.inv_rep, W.freq, W.pres), idx);
       ++r;
     }
   }
@@ -173,7 +260,7 @@ __device__ __forceinline__ void for_history_columns(const SliceTabs& T, const Wi
 
 // The bin that holds the cut, from the masses of the first pass: cumulative mass from the top
 // reaches top_p * total.  bstar < 0 if none.  Ends with a barrier.
-__device__ inline int find_cut(FS& S, const WideRow& W) {
+__device__ inline int find_cut(FS& S, const WideRow& W, u64& s_tot) {
   const int tid = threadIdx.x;
   constexpr int BPT = NBW / WT;
   const u64* gh = reinterpret_cast<const u64*>(W.ws + WS_HIST);
@@ -184,7 +271,8 @@ __device__ inline int find_cut(FS& S, const WideRow& W) {
   if (tid == 0) S.bk = -1;
   unsigned ce, ct; u64 me, mt;
   blk_excl_scan2<WNW>(S, 0u, loc, ce, me, ct, mt);
-  const u64 target = (u64)__double2ull_ru((double)W.top_p * (double)(m_top + mt));
+  s_tot = m_top + mt;  // the bins are exact sums: this is the mass of the whole row
+  const u64 target = (u64)__double2ull_ru((double)W.top_p * (double)s_tot);
   u64 run = m_top + me;
 #pragma unroll
   for (int j = 0; j < BPT; ++j) {
@@ -199,17 +287,73 @@ __device__ inline int find_cut(FS& S, const WideRow& W) {
 
 // How a column is classified, per route: it surely survives iff its tempered value reaches thr_y and it
 // lies at or above g or in a bin before bstar; columns of bin bstar are resolved one by one.
-struct RowCut { int bstar; float thr_y; bool valid; };
+struct RowCut { int bstar; float thr_y; bool valid; u64 s_tot; /* top-p route: exact mass of the row */ };
 __device__ inline RowCut row_cut(FS& S, const WideRow& W) {  // every thread calls; barriers inside on one route
   RowCut c;
-  c.thr_y = -INFINITY; c.valid = true;
-  if (W.mode == WIDE_TOP_P) { c.bstar = find_cut(S, W); c.valid = c.bstar >= 0; }
+  c.thr_y = -INFINITY; c.valid = true; c.s_tot = 0ull;
+  if (W.mode == WIDE_TOP_P) { c.bstar = find_cut(S, W, c.s_tot); c.valid = c.bstar >= 0; }
   else c.bstar = NBW;  // no bin holds a cut
   if (W.mode != WIDE_ALL && W.min_p > 0.0f) {  // min-p, alone or on top of top-p: the shorter prefix wins
     const uint32_t kmax = as_global(reinterpret_cast<const uint32_t*>(W.ws + WS_SCAL))[6];
     c.valid = c.valid && kmax > KEY_NEG_INF;
     c.thr_y = keyf(kmax) + (float)log((double)W.min_p);  // fl(y_max + fl(ln min_p)), as in the list's epilogue
   }
+  return c;
+}
+
+// Smallest float, in the order of the keys, at which a predicate that is monotone in its argument
+// (false, then true) holds; +inf if it holds nowhere.  One wave, 64 candidates per round, no LDS
+// and no barrier; the result is the same in every lane.
+template <typename P>
+__device__ __forceinline__ float wave_lower_bound(P&& pred) {
+  const unsigned lane = threadIdx.x & 63u;
+  uint32_t lo = KEY_NEG_INF, hi = KEY_POS_INF;
+  if (__ballot(pred(keyf(hi))) == 0ull) return INFINITY;
+  while (lo < hi) {  // the answer lies in [lo, hi] and the predicate holds at hi
+    const u64 step = ((u64)hi - (u64)lo + 63ull) / 64ull;
+    const u64 c = (u64)lo + step * (u64)lane;
+    const uint32_t cand = (c < (u64)hi) ? (uint32_t)c : hi;
+    const u64 m = __ballot(pred(keyf(cand)));
+    if (m == 0ull) { lo = (uint32_t)((u64)lo + 63ull * step) + 1u; continue; }  // lane 63 stood below hi
+    const unsigned f = (unsigned)__ffsll((long long)m) - 1u;
+    const u64 cf = (u64)lo + step * (u64)f;
+    const uint32_t top = (cf < (u64)hi) ? (uint32_t)cf : hi;
+    lo = f ? (uint32_t)((u64)lo + step * (u64)(f - 1u)) + 1u : top;
+    hi = top;
+  }
+  return keyf(uni(lo));
+}
+// The same, trying first the 64 floats around a guess: one round when the answer lies among them.
+template <typename P>
+__device__ __forceinline__ float wave_lower_bound_near(float guess, P&& pred) {
+  const unsigned lane = threadIdx.x & 63u;
+  const uint32_t kg = fkey(uni(guess));
+  if (guess == guess && kg >= KEY_NEG_INF + 32u && kg <= KEY_POS_INF - 32u) {
+    const u64 m = __ballot(pred(keyf(kg - 32u + lane)));
+    if (!(m & 1ull) && (m >> 63)) return keyf(uni(kg - 32u + (uint32_t)__ffsll((long long)m) - 1u));
+  }
+  return wave_lower_bound(pred);
+}
+// The classification of a column by its logit alone.  Tempered value, bin and the comparison with
+// g are all monotone in z, so each test holds from one float upwards, and so do their
+// combinations: a column surely survives iff z >= z_sure, and is a boundary column iff
+// z_edge <= z < z_sure.  Every wave computes the same two numbers.
+struct ZCut { float z_sure, z_edge; };
+__device__ __forceinline__ ZCut z_cut(const WideRow& W, int bstar, float thr_y) {
+  // smallest z whose tempered value reaches the min-p threshold
+  float z_thr = -INFINITY;
+  if (thr_y > -INFINITY) z_thr = wave_lower_bound_near(thr_y * W.tau, [&](float z) { return tempered(z, W.C) >= thr_y; });
+  // smallest z whose bin lies before `limit` (bins count downwards from y_g, 1 / BINS_PER_LOG2 of a log2 each)
+  auto before_bin = [&](int limit) -> float {
+    if (limit >= NBW) return -INFINITY;
+    if (limit <= 0) return INFINITY;
+    const float y_guess = W.C.y_g - (float)limit * (0.6931471805599453f / BINS_PER_LOG2);
+    return wave_lower_bound_near(y_guess * W.tau, [&](float z) { int b; (void)mass_term(z, W.C, b); return b < limit; });
+  };
+  const float z_a = before_bin(bstar), z_b = before_bin(bstar + 1);
+  ZCut c;  // sure: y >= thr and (z >= g or bin < bstar); sure or boundary: the same with bin <= bstar
+  c.z_sure = fmaxf(z_thr, fminf(W.C.g, z_a));
+  c.z_edge = fmaxf(z_thr, fminf(W.C.g, z_b));
   return c;
 }
 
@@ -227,25 +371,79 @@ __device__ __forceinline__ Items my_items(const SampleArgs& a) {
   return I;
 }
 
+// What an item needs from memory before its columns can be processed; requested one item ahead.
+// The row and history flag of a queue slot come from the slot's record: a workgroup's items are
+// contiguous, so it keeps them for its current slot and the next.
+template <typename DT>
+struct ItemLoads {
+  static constexpr int G = SLC / (WT * Io<DT>::EPL);  // 16-byte groups per thread and slice
+  typename Io<DT>::Raw A[G];
+  uint32_t hq[G];  // hot-set bits of each group's columns
+  uint32_t pre;    // this thread's mask word or directory entry
+};
+struct SlotIds {
+  uint32_t row_c, act_c, row_n, act_n;  // current slot, next slot
+  __device__ __forceinline__ void request(const SampleArgs& a, unsigned slot, unsigned n_wide, uint32_t& row, uint32_t& act) {
+    row = 0u; act = 0u;
+    if (slot < n_wide) {
+      const uint32_t* rec = reinterpret_cast<const uint32_t*>(reinterpret_cast<const WideRec*>(a.wq + WQ_HEAD) + slot);
+      row = as_global(rec)[0]; act = as_global(rec)[11];
+    }
+  }
+  // The record is the same in every lane: scalars from here on.  Called where the workgroup waits
+  // for its loads anyway (a row's record), so that no later use has to wait for loads in flight.
+  __device__ __forceinline__ void settle() { row_c = uni(row_c); act_c = uni(act_c); row_n = uni(row_n); act_n = uni(act_n); }
+};
+static_assert(offsetof(WideRec, row) == 0 && offsetof(WideRec, h_active) == 44, "record words read by SlotIds");
+template <typename DT, bool use_hot>
+__device__ __forceinline__ void item_fetch(ItemLoads<DT>& L, const SampleArgs& a, unsigned item, unsigned n_sl, int cur_slot, const SlotIds& ids) {
+  constexpr int EPL = Io<DT>::EPL;
+  const int tid = threadIdx.x;
+  const int slot = (int)(item / n_sl), c0 = (int)(item % n_sl) * SLC;
+  const uint32_t row = slot == cur_slot ? ids.row_c : ids.row_n;  // scalars (SlotIds::settle)
+  const bool act = (slot == cur_slot ? ids.act_c : ids.act_n) != 0u;
+  const DT* rowp = reinterpret_cast<const DT*>(a.logits) + (size_t)row * (size_t)a.stride;
+  L.pre = act ? slice_fetch(a.wws + (size_t)slot * a.ws_stride, a, c0) : 0u;
+#pragma unroll
+  for (int j = 0; j < ItemLoads<DT>::G; ++j) {
+    const int idx0 = c0 + (j * WT + tid) * EPL;
+    L.hq[j] = 0u;
+    L.A[j] = typename Io<DT>::Raw();
+    if (idx0 + EPL <= a.V) L.A[j] = Io<DT>::load(rowp + idx0);
+    if (use_hot && idx0 < a.V) L.hq[j] = (as_global(a.hot_bits)[idx0 >> 5] >> ((unsigned)idx0 & 31u)) & ((1u << EPL) - 1u);
+  }
+}
+
 // ---------------------------------------------------------------- bins ------------------------
 template <typename DT>
-__global__ __launch_bounds__(WT, 6) void wide_bins_kernel(const SampleArgs a) {
+__global__ __launch_bounds__(WT, 5) void wide_bins_kernel(const SampleArgs a) {
   constexpr int EPL = Io<DT>::EPL;
-  constexpr int G = SLC / (WT * EPL);
-  typedef typename Io<DT>::Raw Raw;
+  constexpr int G = ItemLoads<DT>::G;
   __shared__ SliceTabs Tb;
-  __shared__ u64 lh[NBW];
+  __shared__ u64 lh[NBW + 1];  // the bins, and the mass at or above g
   __shared__ FS S;
   const int tid = threadIdx.x;
   const int V = a.V;
+  // mask word and bit of this thread's first column in each of its groups (a group step is whole words)
+  const int wbase = (tid * EPL) >> 5;
+  const unsigned wsh = (unsigned)(tid * EPL) & 31u;
+  static_assert((WT * EPL) % 32 == 0, "group stride in mask words");
   const Items I = my_items(a);
   if (I.i0 >= I.i1) return;
   WPHASE(0);
 #ifdef SIMPLE_PHASE_TIMES
   if (threadIdx.x == 0 && blockIdx.x < 8192) { g_wide_phase_times[blockIdx.x * 8 + 5] = __builtin_amdgcn_s_getreg(63492); g_wide_phase_times[blockIdx.x * 8 + 6] = __builtin_amdgcn_s_getreg(63508); }
 #endif
-  int cur = -1;
-  WideRow W;
+  const unsigned n_wide = min(as_global(a.wq)[a.parity], (unsigned)a.wide_slots);
+  int cur = (int)(I.i0 / I.n_sl);
+  SlotIds ids;
+  ids.request(a, (unsigned)cur, n_wide, ids.row_c, ids.act_c);
+  ids.request(a, (unsigned)cur + 1u, n_wide, ids.row_n, ids.act_n);
+  WideRow W = load_row(a, (unsigned)cur);
+  ids.settle();
+  ItemLoads<DT> N;  // the next item's loads
+  item_fetch<DT, false>(N, a, I.i0, I.n_sl, cur, ids);
+  for (int b = tid; b <= NBW; b += WT) lh[b] = 0ull;
   u64 mtop = 0ull;
   float ymax = -INFINITY;  // rows with a min-p cut: largest tempered value seen by this thread
   auto flush = [&]() {
@@ -253,7 +451,7 @@ __global__ __launch_bounds__(WT, 6) void wide_bins_kernel(const SampleArgs a) {
     if (W.mode == WIDE_TOP_P) {
       u64* gh = reinterpret_cast<u64*>(W.ws + WS_HIST);
       for (int b = tid; b < NBW; b += WT) { const u64 v = lh[b]; if (v) atomicAdd(&gh[b], v); }
-      const u64 t = blk_sum_u64<WNW>(S, mtop);
+      const u64 t = blk_sum_u64<WNW>(S, mtop) + lh[NBW];
       if (tid == 0 && t) atomicAdd(reinterpret_cast<u64*>(W.ws + WS_SCAL), t);
     }
     if (W.min_p > 0.0f) {
@@ -265,27 +463,30 @@ __global__ __launch_bounds__(WT, 6) void wide_bins_kernel(const SampleArgs a) {
   for (unsigned it = I.i0; it < I.i1; ++it) {
     const int slot = (int)(it / I.n_sl), sl = (int)(it % I.n_sl);
     const int c0 = sl * SLC;
-    const unsigned char* ws = a.wws + (size_t)slot * a.ws_stride;
-    const uint32_t pre = slice_fetch(ws, a, c0);  // in flight while the record arrives
+    const ItemLoads<DT> L = N;
+    const bool more = it + 1u < I.i1;
     if (slot != cur) {
-      if (cur >= 0) flush();
-      W = load_row(a, (unsigned)slot);
+      flush();
       cur = slot;
-      for (int b = tid; b < NBW; b += WT) lh[b] = 0ull;
+      ids.row_c = ids.row_n; ids.act_c = ids.act_n;
+      ids.request(a, (unsigned)slot + 1u, n_wide, ids.row_n, ids.act_n);
+      W = load_row(a, (unsigned)slot);
+      ids.settle();
+      for (int b = tid; b <= NBW; b += WT) lh[b] = 0ull;
     }
-    if (W.mode == WIDE_ALL) continue;  // every column survives: nothing to find in a first pass
+    if (W.mode == WIDE_ALL) {  // every column survives: nothing to find in a first pass
+      if (more) item_fetch<DT, false>(N, a, it + 1u, I.n_sl, cur, ids);
+      continue;
+    }
     const DT* rowp = reinterpret_cast<const DT*>(a.logits) + (size_t)W.row * (size_t)a.stride;
-    Raw A[G];
-#pragma unroll
-    for (int j = 0; j < G; ++j) {
-      const int idx0 = c0 + (j * WT + tid) * EPL;
-      if (idx0 + EPL <= V) A[j] = Io<DT>::load(rowp + idx0);
-    }
     WPHASE(1);
-    slice_store(Tb, pre, a, c0, W.distinct);
-    __syncthreads();
-    if (W.h_active) slice_counts(Tb, ws, a);
-    __syncthreads();
+    HistPre<DT> HP;
+    if (W.h_active) {
+      slice_store(Tb, L.pre, a, c0, W.distinct);
+      __syncthreads();
+      hist_fetch<DT>(HP, Tb, W.ws, a, rowp, c0, V);  // this item's own loads go first: loads return in order
+    } else __syncthreads();  // the zeroed bins are visible
+    if (more) item_fetch<DT, false>(N, a, it + 1u, I.n_sl, cur, ids);
     WPHASE(2);
     auto one = [&](float z, int) {
       if (W.mode == WIDE_MIN_P) { ymax = fmaxf(ymax, tempered(z, W.C)); return; }
@@ -295,15 +496,14 @@ __global__ __launch_bounds__(WT, 6) void wide_bins_kernel(const SampleArgs a) {
       if (z < W.C.g) atomicAdd(&lh[b], mass_fix_below(w));
       else mtop += mass_fix(fminf(w, W_LIMIT));
     };
-    if (W.h_active) for_history_columns<DT>(Tb, W, rowp, c0, V, one);
     if (W.mode == WIDE_MIN_P) {  // the row maximum is all a value cut needs
 #pragma unroll
       for (int j = 0; j < G; ++j) {
         const int idx0 = c0 + (j * WT + tid) * EPL;
         if (idx0 + EPL <= V) {
           float z[EPL];
-          Io<DT>::unpack(A[j], z);
-          const uint32_t nib = W.h_active ? (Tb.bm[(idx0 - c0) >> 5] >> ((unsigned)(idx0 - c0) & 31u)) & ((1u << EPL) - 1u) : 0u;
+          Io<DT>::unpack(L.A[j], z);
+          const uint32_t nib = W.h_active ? (Tb.bm[wbase + j * (WT * EPL / 32)] >> wsh) & ((1u << EPL) - 1u) : 0u;
           float zm = -INFINITY;  // the tempered value is monotone in z: one division per group
 #pragma unroll
           for (int e = 0; e < EPL; ++e) zm = ((nib >> e) & 1u) ? zm : fmaxf(zm, z[e]);
@@ -313,43 +513,49 @@ __global__ __launch_bounds__(WT, 6) void wide_bins_kernel(const SampleArgs a) {
             if (!(W.h_active && slice_bit(idx - c0, Tb))) one(Io<DT>::one(rowp + idx), idx);
         }
       }
+    } else {
+      auto sweep = [&](auto unit_tau_c) {
+        constexpr bool UT = decltype(unit_tau_c)::value;
+#pragma unroll
+        for (int j = 0; j < G; ++j) {
+          const int idx0 = c0 + (j * WT + tid) * EPL;
+          if (idx0 + EPL <= V) {
+            float z[EPL];
+            Io<DT>::unpack(L.A[j], z);
+            if (W.h_active) {  // history columns are handled below: here they count as -inf (no mass)
+              const uint32_t nib = (Tb.bm[wbase + j * (WT * EPL / 32)] >> wsh) & ((1u << EPL) - 1u);
+#pragma unroll
+              for (int e = 0; e < EPL; ++e) z[e] = ((nib >> e) & 1u) ? -INFINITY : z[e];
+            }
+#pragma unroll
+            for (int e = 0; e < EPL; ++e) {  // straight-line: the columns at or above g share one more slot
+              int b;
+              const float w = mass_term<UT>(z[e], W.C, b);
+              uint32_t hi, lo;
+              float_to_parts(fminf(w, W_LIMIT) * MSCALE, hi, lo);
+              atomicAdd(&lh[(z[e] < W.C.g) ? b : NBW], parts_to_u64(hi, lo));
+            }
+            if (W.min_p > 0.0f) {  // the tempered value is monotone in z: one division per group
+              float zm = z[0];
+#pragma unroll
+              for (int e = 1; e < EPL; ++e) zm = fmaxf(zm, z[e]);
+              ymax = fmaxf(ymax, tempered(zm, W.C));
+            }
+          } else {
+            for (int idx = idx0; idx < V; ++idx)
+              if (!(W.h_active && slice_bit(idx - c0, Tb))) one(Io<DT>::one(rowp + idx), idx);
+          }
+          __builtin_amdgcn_sched_barrier(0);  // one group at a time: interleaving them costs registers
+        }
+      };
+      if (W.tau == 1.0f) sweep(std::true_type{}); else sweep(std::false_type{});
+    }
+    if (W.h_active) {  // the history columns, whose logits and counts were requested before the main line
+      hist_stage<DT>(Tb, HP, W.ws, a, rowp, c0, V);
       __syncthreads();
-      continue;
+      hist_columns<DT>(Tb, W, rowp, c0, V, one);
+      __syncthreads();  // the tables are rewritten by the next item
     }
-#pragma unroll
-    for (int j = 0; j < G; ++j) {
-      const int idx0 = c0 + (j * WT + tid) * EPL;
-      if (idx0 + EPL <= V) {
-        float z[EPL];
-        Io<DT>::unpack(A[j], z);
-        bool any_top = false;
-        if (W.h_active) {  // history columns were handled above: here they count as -inf (no mass)
-          const uint32_t nib = (Tb.bm[(idx0 - c0) >> 5] >> ((unsigned)(idx0 - c0) & 31u)) & ((1u << EPL) - 1u);
-#pragma unroll
-          for (int e = 0; e < EPL; ++e) z[e] = ((nib >> e) & 1u) ? -INFINITY : z[e];
-        }
-        float zm = -INFINITY;
-#pragma unroll
-        for (int e = 0; e < EPL; ++e) {  // straight-line: a column at or above g adds zero to its bin
-          int b;
-          const float w = mass_term(z[e], W.C, b);
-          const bool below = z[e] < W.C.g;
-          atomicAdd(&lh[b], below ? mass_fix_below(w) : 0ull);
-          any_top = any_top || !below;
-          zm = fmaxf(zm, z[e]);
-        }
-        if (W.min_p > 0.0f) ymax = fmaxf(ymax, tempered(zm, W.C));  // the tempered value is monotone in z
-        if (__ballot(any_top)) {  // few columns: the 64-bit conversion stays out of the main line
-#pragma unroll
-          for (int e = 0; e < EPL; ++e)
-            if (!(z[e] < W.C.g)) { int b; mtop += mass_fix(fminf(mass_term(z[e], W.C, b), W_LIMIT)); }
-        }
-      } else {
-        for (int idx = idx0; idx < V; ++idx)
-          if (!(W.h_active && slice_bit(idx - c0, Tb))) one(Io<DT>::one(rowp + idx), idx);
-      }
-    }
-    __syncthreads();  // the tables are reloaded by the next item
     WPHASE(3);
   }
   flush();
@@ -358,60 +564,113 @@ __global__ __launch_bounds__(WT, 6) void wide_bins_kernel(const SampleArgs a) {
 
 // ---------------------------------------------------------------- classify --------------------
 template <typename DT, bool use_hot>  // use_hot: a hot set is installed (section 5.3): masses are split by class
-__global__ __launch_bounds__(WT, 5) void wide_classify_kernel(const SampleArgs a) {
+__global__ __launch_bounds__(WT, 4) void wide_classify_kernel(const SampleArgs a) {
   constexpr int EPL = Io<DT>::EPL;
-  constexpr int G = SLC / (WT * EPL);  // 16-byte groups per thread and slice; a slice is one tile of the draw's walk
+  constexpr int G = ItemLoads<DT>::G;  // a slice is one tile of the draw's walk
   constexpr unsigned EMASK = (1u << EPL) - 1u;
-  typedef typename Io<DT>::Raw Raw;
   __shared__ SliceTabs Tb;
-  __shared__ u64 lrl[ICAP];
+  __shared__ u64 lrl[LCAP];  // boundary columns of the current row found by this workgroup, not yet written out
   __shared__ u64 ltile[2];
   __shared__ unsigned l_n, l_base;
   __shared__ FS S;
   const int tid = threadIdx.x, lane = tid & 63;
   const int V = a.V;
+  // mask word and bit of this thread's first column in each of its groups (a group step is whole words)
+  const int wbase = (tid * EPL) >> 5;
+  const unsigned wsh = (unsigned)(tid * EPL) & 31u;
+  static_assert((WT * EPL) % 32 == 0, "group stride in mask words");
   const Items I = my_items(a);
   if (I.i0 >= I.i1) return;
   const uint32_t* hot_bits = a.hot_bits;
-  CPHASE(0);
-  int cur = -1;
+  CACC_INIT();
+  const unsigned n_wide = min(as_global(a.wq)[a.parity], (unsigned)a.wide_slots);
+  int cur = (int)(I.i0 / I.n_sl);
+  SlotIds ids;
+  ids.request(a, (unsigned)cur, n_wide, ids.row_c, ids.act_c);
+  ids.request(a, (unsigned)cur + 1u, n_wide, ids.row_n, ids.act_n);
+  ids.settle();
+  ItemLoads<DT> N;  // the next item's loads
+  item_fetch<DT, use_hot>(N, a, I.i0, I.n_sl, cur, ids);
   WideRow W;
   int bstar = -1;
   float thr_y = -INFINITY;
   bool valid = false;
+  ZCut zc = {INFINITY, INFINITY};
+  auto enter_row = [&](int slot) {  // barriers inside
+    W = load_row(a, (unsigned)slot);
+    ids.settle();
+    const RowCut rc = row_cut(S, W);
+    bstar = rc.bstar; thr_y = rc.thr_y; valid = rc.valid;
+    if (valid) zc = z_cut(W, bstar, thr_y);
+  };
+  // What a thread gathers over this workgroup's slices of one row, reduced when the row ends:
+  unsigned n_sure = 0u;    // sure columns
+  u64 acc_all = 0ull;      // exact mass of every column (routes without bins)
+  float ymax = -INFINITY;  // largest tempered value
+  bool bad = false;        // a mass the fixed point cannot carry, or a NaN
+  // Writes the staged boundary columns to the row's list.  All threads call, after a barrier that
+  // follows the last append; ends with a barrier.
+  auto list_out = [&]() {
+    const unsigned nb = l_n;
+    if (nb == 0u) return;
+    uint32_t* sc = reinterpret_cast<uint32_t*>(W.ws + WS_SCAL);
+    // more columns than the stage holds: the count is pushed past the limit, so that the finishing
+    // kernel hands the row on
+    if (tid == 0) l_base = atomicAdd(&sc[3], nb > (unsigned)LCAP ? (unsigned)RCAP + 1u : nb);
+    __syncthreads();
+    const unsigned base = l_base;
+    if (nb <= (unsigned)LCAP)
+      for (unsigned t = tid; t < nb; t += WT)
+        if (base + t < (unsigned)RCAP) reinterpret_cast<u64*>(W.ws + WS_RL)[base + t] = lrl[t];
+    if (tid == 0) l_n = 0u;
+    __syncthreads();
+  };
+  auto leave_row = [&]() {  // barriers inside
+    if (!valid) return;
+    __syncthreads();
+    list_out();
+    uint32_t* sc = reinterpret_cast<uint32_t*>(W.ws + WS_SCAL);
+    const float m = wave_max(ymax);
+    if (lane == 0 && m > -INFINITY) atomicMax(&sc[6], fkey(m));
+    if (__ballot(bad) && lane == 0) atomicAdd(&sc[3], (unsigned)RCAP + 1u);  // the finishing kernel hands the row on
+    unsigned ns = n_sure, dz = 0u; u64 mx = 0ull, dsum = acc_all;
+    blk_reduce<WNW>(S, ns, dz, mx, dsum);
+    if (tid == 0) {
+      if (ns) atomicAdd(&sc[2], ns);
+      if (dsum) atomicAdd(reinterpret_cast<u64*>(W.ws + WS_SCAL + 16), dsum);
+    }
+    n_sure = 0u; acc_all = 0ull; ymax = -INFINITY; bad = false;
+  };
+  if (tid == 0) l_n = 0u;
+  enter_row(cur);
+  CACC(7);
   for (unsigned it = I.i0; it < I.i1; ++it) {
     const int slot = (int)(it / I.n_sl), sl = (int)(it % I.n_sl);
+    const ItemLoads<DT> L = N;
+    const bool more = it + 1u < I.i1;
     if (slot != cur) {
-      W = load_row(a, (unsigned)slot);
+      leave_row();
       cur = slot;
-      const RowCut rc = row_cut(S, W);
-      bstar = rc.bstar; thr_y = rc.thr_y; valid = rc.valid;
-      CPHASE(1);
+      ids.row_c = ids.row_n; ids.act_c = ids.act_n;
+      ids.request(a, (unsigned)slot + 1u, n_wide, ids.row_n, ids.act_n);
+      enter_row(slot);
+      CACC(7);
     }
-    if (!valid) continue;  // the finishing kernel hands the row on
+    if (!valid) {  // the finishing kernel hands the row on
+      if (more) item_fetch<DT, use_hot>(N, a, it + 1u, I.n_sl, cur, ids);
+      continue;
+    }
     const int c0 = sl * SLC;
-    const uint32_t pre = slice_fetch(W.ws, a, c0);
     const DT* rowp = reinterpret_cast<const DT*>(a.logits) + (size_t)W.row * (size_t)a.stride;
-    Raw A[G];
-    uint32_t hq[G];
-#pragma unroll
-    for (int j = 0; j < G; ++j) {
-      const int idx0 = c0 + (j * WT + tid) * EPL;
-      hq[j] = 0u;
-      if (idx0 + EPL <= V) A[j] = Io<DT>::load(rowp + idx0);
-      if (use_hot && idx0 < V) hq[j] = (as_global(hot_bits)[idx0 >> 5] >> ((unsigned)idx0 & 31u)) & EMASK;
-    }
+    CACC(0);
     if (tid < 2) ltile[tid] = 0ull;
-    if (tid == 0) l_n = 0u;
-    slice_store(Tb, pre, a, c0, W.distinct);
+    if (W.h_active) slice_store(Tb, L.pre, a, c0, W.distinct);
     __syncthreads();
-    if (W.h_active) slice_counts(Tb, W.ws, a);
-    __syncthreads();
-    CPHASE(2);
-    unsigned n_sure = 0u;
-    u64 acc_all = 0ull;  // exact mass of every column of the slice
-    float ymax = -INFINITY;  // largest tempered value
-    bool bad = false;        // a mass the fixed point cannot carry, or a NaN
+    CACC(1);
+    HistPre<DT> HP;
+    if (W.h_active) hist_fetch<DT>(HP, Tb, W.ws, a, rowp, c0, V);  // this item's own loads go first: loads return in order
+    if (more) item_fetch<DT, use_hot>(N, a, it + 1u, I.n_sl, cur, ids);
+    CACC(2);
     // one column the slow way: history columns and the ragged end of the row
     auto one = [&](float z, int idx) {
       int b; float y;
@@ -428,101 +687,100 @@ __global__ __launch_bounds__(WT, 5) void wide_classify_kernel(const SampleArgs a
         ++n_sure;
       } else if (b == bstar) {
         const unsigned s = atomicAdd(&l_n, 1u);
-        if (s < (unsigned)ICAP) lrl[s] = ((u64)__float_as_uint(z) << 32) | (u64)(uint32_t)idx;
+        if (s < (unsigned)LCAP) lrl[s] = ((u64)__float_as_uint(z) << 32) | (u64)(uint32_t)idx;
       }
     };
-    if (W.h_active) for_history_columns<DT>(Tb, W, rowp, c0, V, one);
-    CPHASE(3);
-    u64 acc0 = 0ull, acc1 = 0ull;
+    // The main line: masses of the columns below g and their class by the logit alone; the rare
+    // cases (a column at or above g, a boundary column) follow under wave-wide tests.
+    u64 acc_s = 0ull, acc1 = 0ull;  // mass of the sure columns, and of the hot ones among them
+    auto sweep = [&](auto unit_tau_c, auto want_all_c) {
+      constexpr bool UT = decltype(unit_tau_c)::value, WANT_ALL = decltype(want_all_c)::value;
 #pragma unroll
-    for (int j = 0; j < G; ++j) {
-      const int idx0 = c0 + (j * WT + tid) * EPL;
-      if (idx0 + EPL <= V) {
-        float z[EPL];
-        Io<DT>::unpack(A[j], z);
-        bool any_top = false, any_edge = false;
-        // history columns were handled above: here they are skipped
-        const uint32_t live = W.h_active ? ~((Tb.bm[(idx0 - c0) >> 5] >> ((unsigned)(idx0 - c0) & 31u)) & EMASK) : ~0u;
-        uint32_t g0 = 0u, g1 = 0u, gall = 0u;  // group sums: <= 8 masses of <= 2^28
+      for (int j = 0; j < G; ++j) {
+        const int idx0 = c0 + (j * WT + tid) * EPL;
+        if (idx0 + EPL <= V) {
+          float z[EPL];
+          Io<DT>::unpack(L.A[j], z);
+          bool any_edge = false;
+          uint32_t live = ~0u;
+          if (W.h_active) {  // history columns are handled below: here they carry no mass
+            live = ~((Tb.bm[wbase + j * (WT * EPL / 32)] >> wsh) & EMASK);
 #pragma unroll
-        for (int e = 0; e < EPL; ++e) {  // straight-line; the rare cases follow under wave-wide tests
-          if (!((live >> e) & 1u)) z[e] = -INFINITY;  // no mass, no bin of interest ...
-          int b; float y;
-          const float w = mass_term(z[e], W.C, b, y);
-          const bool below = z[e] < W.C.g;
-          const bool sure = ((live >> e) & 1u) && y >= thr_y && (!below || b < bstar);
-          ymax = fmaxf(ymax, y);
-          const uint32_t m = below ? (uint32_t)mass_fix_below(w) : 0u;
-          const uint32_t ms = sure ? m : 0u;
-          const bool hot = use_hot && ((hq[j] >> e) & 1u) != 0u;
-          gall += m;
-          g0 += hot ? 0u : ms;
-          g1 += hot ? ms : 0u;
-          n_sure += sure ? 1u : 0u;
-          any_top = any_top || !below;
-          any_edge = any_edge || (((live >> e) & 1u) && below && b == bstar && y >= thr_y);
-        }
-        acc0 += (u64)g0; acc1 += (u64)g1; acc_all += (u64)gall;
-        if (__ballot(any_top)) {
-#pragma unroll
-          for (int e = 0; e < EPL; ++e) {
-            if (!(z[e] < W.C.g)) {  // not below the list's threshold: inside any top-p nucleus that got here
-              int b; float y;
-              const float w = mass_term(z[e], W.C, b, y);
-              if (!(w <= W_LIMIT)) { bad = true; continue; }
-              const u64 m = mass_fix(w);
-              acc_all += m;
-              if (y >= thr_y) { if (use_hot && ((hq[j] >> e) & 1u)) acc1 += m; else acc0 += m; }
-            }
+            for (int e = 0; e < EPL; ++e) z[e] = ((live >> e) & 1u) ? z[e] : -INFINITY;
+            // ... but -inf counts as sure when every value does
+            if (zc.z_sure == -INFINITY) n_sure -= (unsigned)__popc(~live & EMASK);
           }
-        }
-        if (__ballot(any_edge)) {
+          // group sums of the masses' two parts (units of 2^24, and the rest): <= 8 terms of <= 2^25
+          uint32_t sh = 0u, sl_ = 0u, hh = 0u, hl = 0u, ah = 0u, al = 0u;
 #pragma unroll
           for (int e = 0; e < EPL; ++e) {
             int b; float y;
-            (void)mass_term(z[e], W.C, b, y);
-            if (((live >> e) & 1u) && z[e] < W.C.g && b == bstar && y >= thr_y) {
-              const unsigned s = atomicAdd(&l_n, 1u);
-              if (s < (unsigned)ICAP) lrl[s] = ((u64)__float_as_uint(z[e]) << 32) | (u64)(uint32_t)(idx0 + e);
+            const float w = mass_term<UT>(z[e], W.C, b, y);
+            bad = bad || !(w <= W_LIMIT);  // a mass the fixed point cannot carry, or a NaN
+            uint32_t hi, lo;
+            float_to_parts(w * MSCALE, hi, lo);
+            const bool sure = z[e] >= zc.z_sure;
+            ymax = fmaxf(ymax, y);
+            const uint32_t his = sure ? hi : 0u, los = sure ? lo : 0u;
+            sh += his; sl_ += los;
+            if (use_hot) { const uint32_t hm = (uint32_t)(-(int32_t)((L.hq[j] >> e) & 1u)); hh += his & hm; hl += los & hm; }
+            if (WANT_ALL) { ah += hi; al += lo; }
+            n_sure += sure ? 1u : 0u;
+            any_edge = any_edge || (z[e] >= zc.z_edge && !sure);
+          }
+          acc_s += parts_to_u64(sh, sl_);
+          if (use_hot) acc1 += parts_to_u64(hh, hl);
+          if (WANT_ALL) acc_all += parts_to_u64(ah, al);
+          if (__ballot(any_edge)) {  // boundary columns of the whole group: one reservation per wave
+            u64 em[EPL];
+            unsigned pre[EPL], tot = 0u;
+#pragma unroll
+            for (int e = 0; e < EPL; ++e) {
+              em[e] = __ballot(((live >> e) & 1u) && z[e] >= zc.z_edge && !(z[e] >= zc.z_sure));
+              pre[e] = tot; tot += (unsigned)__popcll(em[e]);
+            }
+            unsigned base = 0u;  // the first active lane reserves (the ragged end of a row leaves lanes out)
+            if (lane == __ffsll((long long)__ballot(true)) - 1 && tot) base = atomicAdd(&l_n, tot);
+            base = uni(base);
+#pragma unroll
+            for (int e = 0; e < EPL; ++e) {
+              if ((em[e] >> lane) & 1ull) {
+                const unsigned s = base + pre[e] + lanes_before(em[e]);
+                if (s < (unsigned)LCAP) lrl[s] = ((u64)__float_as_uint(z[e]) << 32) | (u64)(uint32_t)(idx0 + e);
+              }
             }
           }
+        } else {
+          for (int idx = idx0; idx < V; ++idx)
+            if (!(W.h_active && slice_bit(idx - c0, Tb))) one(Io<DT>::one(rowp + idx), idx);
         }
-      } else {
-        for (int idx = idx0; idx < V; ++idx)
-          if (!(W.h_active && slice_bit(idx - c0, Tb))) one(Io<DT>::one(rowp + idx), idx);
+        __builtin_amdgcn_sched_barrier(0);  // one group at a time: interleaving them costs registers
       }
+    };
+    // the top-p route has the row's mass from its bins; the other routes sum it here
+    if (W.tau == 1.0f) { if (W.mode == WIDE_TOP_P) sweep(std::true_type{}, std::false_type{}); else sweep(std::true_type{}, std::true_type{}); }
+    else { if (W.mode == WIDE_TOP_P) sweep(std::false_type{}, std::false_type{}); else sweep(std::false_type{}, std::true_type{}); }
+    CACC(3);
+    if (W.h_active) {  // the history columns, whose logits and counts were requested before the main line
+      hist_stage<DT>(Tb, HP, W.ws, a, rowp, c0, V);
+      __syncthreads();
+      hist_columns<DT>(Tb, W, rowp, c0, V, one);
     }
-    CPHASE(4);
+    CACC(4);
     {
-      const u64 s0 = wave_sum(acc0);
+      const u64 s0 = wave_sum(acc_s - acc1);
       if (lane == 0 && s0) atomicAdd(&ltile[0], s0);
       if (use_hot) { const u64 s1 = wave_sum(acc1); if (lane == 0 && s1) atomicAdd(&ltile[1], s1); }
     }
-    unsigned ns = n_sure, dz = 0u; u64 mx = 0ull, dsum = acc_all;
-    blk_reduce<WNW>(S, ns, dz, mx, dsum);  // barriers inside: tile sums and the boundary list are complete
-    u64* gt = reinterpret_cast<u64*>(W.ws + WS_TILES);
-    uint32_t* sc = reinterpret_cast<uint32_t*>(W.ws + WS_SCAL);
-    if (tid < 2 && sl < 256) gt[tid * 256 + sl] = ltile[tid];
-    {
-      const float m = wave_max(ymax);
-      if (lane == 0 && m > -INFINITY) atomicMax(&sc[6], fkey(m));
-      if (__ballot(bad) && lane == 0) atomicAdd(&sc[3], (unsigned)RCAP + 1u);  // the finishing kernel hands the row on
-    }
-    const unsigned nb = l_n;
-    if (tid == 0) {
-      if (ns) atomicAdd(&sc[2], ns);
-      if (dsum) atomicAdd(reinterpret_cast<u64*>(W.ws + WS_SCAL + 16), dsum);
-      // more columns of the bin in one slice than the staging list holds: the count is pushed past
-      // the limit, so that the finishing kernel hands the row on
-      l_base = nb ? atomicAdd(&sc[3], nb > (unsigned)ICAP ? (unsigned)RCAP + 1u : nb) : 0u;
-    }
-    __syncthreads();
-    const unsigned base = l_base;
-    for (unsigned t = tid; t < min(nb, (unsigned)ICAP); t += WT)
-      if (base + t < (unsigned)RCAP) reinterpret_cast<u64*>(W.ws + WS_RL)[base + t] = lrl[t];
-    __syncthreads();
-    CPHASE(5);
+    __syncthreads();  // the tile sums and this slice's appends are complete
+    CACC(5);
+    if (tid < 2 && sl < 256) reinterpret_cast<u64*>(W.ws + WS_TILES)[tid * 256 + sl] = ltile[tid];
+    // every slice may add ICAP boundary columns before the stage has to be written out
+    if (l_n > (unsigned)(LCAP - ICAP)) list_out();
+    CACC(6);
   }
+  leave_row();
+  CACC_DUMP();
 }
 
 // ---------------------------------------------------------------- finish ----------------------
@@ -548,7 +806,7 @@ __device__ inline bool finish_row(const SampleArgs& a, const WideRow& W, FS& S, 
   // every value of the slot this workgroup needs is requested before the first barrier
   const uint32_t* sc = reinterpret_cast<const uint32_t*>(W.ws + WS_SCAL);
   const unsigned n_sure = as_global(sc)[2], n_r = as_global(sc)[3];
-  const u64 S_tot = as_global(reinterpret_cast<const u64*>(W.ws + WS_SCAL))[2];  // exact mass of the row
+  const u64 S_sum = as_global(reinterpret_cast<const u64*>(W.ws + WS_SCAL))[2];  // mass of the row, summed by the classifying pass
   u64 tv[2];
 #pragma unroll
   for (int k = 0; k < 2; ++k) tv[k] = as_global(reinterpret_cast<const u64*>(W.ws + WS_TILES))[k * WT + tid];
@@ -560,6 +818,7 @@ __device__ inline bool finish_row(const SampleArgs& a, const WideRow& W, FS& S, 
   XPHASE(1);
   if (!rcut.valid) { XWHY(1, 0); return false; }
   const bool top_p_route = W.mode == WIDE_TOP_P;
+  const u64 S_tot = top_p_route ? rcut.s_tot : S_sum;  // exact mass of the row (from the bins where there are bins)
   // a count past the limit is also how the classifying pass reports a row it could not handle; no
   // collected column on the top-p route means that a min-p cut ended the survivors above the bin
   const bool minp_too = top_p_route && W.min_p > 0.0f;
@@ -768,7 +1027,7 @@ extern "C" int simple_debug_wide_phase_times(unsigned long long* dst_host, int n
 hipError_t launch_wide(const SampleArgs& a, int dtype, hipStream_t st) {
   // One resident round of workgroups each: six (bins) and five (classify) per compute unit fit by
   // registers and LDS; a workgroup then takes a contiguous run of slices, mostly of one row.
-  const dim3 bins((unsigned)a.n_cu * 6u), cls((unsigned)a.n_cu * 5u), fin(1024), blk(fast::WT);
+  const dim3 bins((unsigned)a.n_cu * 5u), cls((unsigned)a.n_cu * 4u), fin(1024), blk(fast::WT);
   if (dtype == SIMPLE_F32) {
     hipLaunchKernelGGL((fast::wide_bins_kernel<float>), bins, blk, 0, st, a);
     if (a.hot_bits) hipLaunchKernelGGL((fast::wide_classify_kernel<float, true>), cls, blk, 0, st, a);

@@ -289,3 +289,47 @@ def test_top_p_and_min_p_together_beyond_the_list():
     wb = synth.Workload("p+minp-bf16", B, V, "bf16", bits, params, hist_ptr, hist_ids, hot_ids=hot)
     for ids, dg in _run(wb, steps=(0, 1)):
         assert not ((dg["flags"] & GENERAL) > 0).any()
+
+
+def test_plateau_at_the_cut_staged_over_several_slices_of_one_workgroup():
+    """A cut inside a plateau of 3000 equal values below the list's threshold, with enough rows that a
+    workgroup of the classifying pass meets several slices of one row in a row: its stage of boundary
+    columns is written out in the middle of a row, and the tie is resolved by token id."""
+    from paper_2512_00719_amd import binding
+    rng = np.random.default_rng(33)
+    B, V = 640, 5 * 4096
+    z = (rng.standard_normal((B, V)) * 0.5 - 12.0).astype(np.float32)
+    cols = rng.permutation(V)
+    head, plateau = cols[:2000], cols[2000:5000]
+    z[:, head] = (rng.standard_normal((B, 2000)) * 0.3 + 1.0).astype(np.float32)  # about three quarters of the mass
+    z[:, plateau] = -0.5                                                        # the rest: the 0.8 cut falls here
+    params = synth.make_params(B, temperature=1.0, top_p=0.8)
+    w = synth.Workload("plateau-staged", B, V, "f32", z, params, np.zeros(B + 1, np.int64), np.zeros(0, np.int32))
+    s = binding.Sampler(V, 0)
+    dev = P.to_device(w)
+    rows = sorted(set(rng.choice(B, 40, replace=False).tolist()) | {0, B - 1})
+    for step in (0, 1):
+        ids, dg = P.run_gpu(w, step, sampler=s, dev=dev)
+        P.compare(ids, dg, P.run_oracle(w, step, rows=rows), rows)
+        f = dg["flags"]
+        assert ((f & WIDE) > 0).all() and not ((f & GENERAL) > 0).any()
+        assert (dg["n_survivors"] > 2000).all() and (dg["n_survivors"] < 5000).all()
+    s.close()
+
+
+def test_history_denser_than_the_per_slice_stage():
+    """More than 512 distinct history columns inside one slice of 4096: the ones beyond the stage that
+    spreads them over all threads stay with their mask word's thread."""
+    rng = np.random.default_rng(34)
+    B, V = 6, 3 * 4096 + 40
+    z = _flat_logits(rng, B, V)
+    lens = np.array([3000, 2500, 0, 4000, 600, 3500])
+    pool = rng.choice(4096, 2200, replace=False) + 4096  # all inside the second slice
+    hist_ptr = np.concatenate([[0], np.cumsum(lens)]).astype(np.int64)
+    hist_ids = np.concatenate([rng.choice(pool, int(n)) for n in lens]).astype(np.int32)
+    params = synth.make_params(B, temperature=[1.0, 0.8, 1.2] * 2, top_p=[0.9, 1.0, 0.95, 0.97, 1.0, 0.9],
+                               rep_penalty=1.15, freq_penalty=0.25, pres_penalty=0.1, n_prompt=[0, 500, 0, 100, 0, 3500])
+    w = synth.Workload("dense-hist", B, V, "f32", z, params, hist_ptr, hist_ids)
+    for ids, dg in _run(w, steps=(0, 1, 2)):
+        f = dg["flags"]
+        assert ((f & WIDE) > 0).all() and not ((f & GENERAL) > 0).any()
