@@ -49,8 +49,11 @@ LdsLayout make_layout(int64_t V, int64_t max_nnz, bool with_history) {
 
 // The single-pass kernel needs 16-byte aligned rows, a vocabulary whose columns fit 18 bits, 16-bit
 // token counts and at least two tiles per wave.  Its row state is sized so that four workgroups of
-// 256 threads share a compute unit when the history tables allow it, else 512 threads are used.
-FastLayout make_fast_layout(int64_t V, int dtype, int64_t max_nnz, bool with_history, bool vec, int lds_limit) {
+// 256 threads share a compute unit when the history tables allow it, else 512 threads are used.  A
+// batch with fewer rows than that many workgroups gets more threads per row (up to 1024: sixteen
+// waves, what a compute unit holds of this kernel), so that the compute units it reaches are full.
+FastLayout make_fast_layout(int64_t V, int dtype, int64_t max_nnz, bool with_history, bool vec, int lds_limit,
+                            int64_t B, int n_cu) {
   FastLayout F{};
   if (!vec || V >= ((int64_t)1 << 18) || max_nnz > 65535) return F;
   const int64_t tile = 64 * 4 * ((dtype == SIMPLE_F32) ? 4 : 8);
@@ -66,8 +69,12 @@ FastLayout make_fast_layout(int64_t V, int dtype, int64_t max_nnz, bool with_his
   uint32_t body = off < 28672u ? 28672u : off;               // >= 14 KB of sorted-epilogue arrays, >= 3072-entry list
   F.long_cap = (body - tables) / 8u;
   F.samp = body;
-  const uint32_t total = body + 1024u;
-  F.threads = ((int64_t)total + 1024 <= (int64_t)lds_limit / 4) ? 256 : 512;
+  // the sample merge area holds SPW keys per wave
+  F.threads = ((int64_t)body + 2048 <= (int64_t)lds_limit / 4) ? 256 : 512;  // four workgroups per compute unit, static LDS included
+  if (B <= (int64_t)n_cu) F.threads = 1024;
+  else if (B <= 2 * (int64_t)n_cu) F.threads = 512;
+  while (F.threads > 256 && V / tile < 2 * (F.threads / 64)) F.threads /= 2;  // two tiles per wave
+  const uint32_t total = body + align16((uint32_t)(F.threads / 64) * (uint32_t)SAMPLE_PER_WAVE * 4u);
   const uint32_t reg_cap = (uint32_t)(CAPF_PER_THREAD * F.threads);  // the epilogue moves the list to registers
   F.list_cap = body / 8u < reg_cap ? body / 8u : reg_cap;
   if ((int64_t)total + 1024 > (int64_t)lds_limit) return F;  // total stays 0
@@ -136,7 +143,7 @@ int simple_create(simple_ctx** out, int device, int64_t max_V, int64_t max_nnz_p
   const size_t wq_bytes = 64 + 64 * (size_t)simple::WIDE_SLOTS;  // head, then one 64-byte record per slot
   {  // a slot holds the fixed part and the largest history tables the single-pass kernel can have
     const simple::FastLayout Fm = simple::make_fast_layout(max_V < ((int64_t)1 << 18) ? max_V : ((int64_t)1 << 18) - 1, SIMPLE_F32,
-                                                           max_nnz_per_row, max_nnz_per_row > 0, true, lds);
+                                                           max_nnz_per_row, max_nnz_per_row > 0, true, lds, (int64_t)1 << 30, c->n_cu);
     const uint32_t tables = (max_nnz_per_row > 0 && Fm.total) ? Fm.cnt + (uint32_t)((max_nnz_per_row + 3) / 2) * 4u + 16u : 0u;
     c->ws_stride = (simple::WIDE_SLOT_FIXED + tables + 63u) & ~63u;
   }
@@ -269,7 +276,8 @@ int simple_sample(simple_ctx* ctx, const void* logits_dev, int64_t B, int64_t V,
   a.n_cu = ctx->n_cu;
   a.wq = ctx->wq; a.wws = ctx->wws; a.wide_slots = simple::WIDE_SLOTS; a.ws_stride = ctx->ws_stride;
   a.L = simple::make_layout(V, ctx->max_nnz, hist_ptr_dev != nullptr);
-  a.F = simple::make_fast_layout(V, dtype, hist_ptr_dev ? ctx->max_nnz : 0, hist_ptr_dev != nullptr, vec, ctx->lds_limit);
+  a.F = simple::make_fast_layout(V, dtype, hist_ptr_dev ? ctx->max_nnz : 0, hist_ptr_dev != nullptr, vec, ctx->lds_limit,
+                                 B < simple::PEND_ROWS ? B : simple::PEND_ROWS, ctx->n_cu);
   a.gated = (a.F.total != 0u) ? 1 : 0;
   // rows go out in launches of at most PEND_ROWS (the capacity of the pending-row queue)
   for (int64_t b0 = 0; b0 < B; b0 += simple::PEND_ROWS) {

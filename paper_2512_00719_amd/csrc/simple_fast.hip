@@ -1019,18 +1019,22 @@ hipError_t launch_fast(const SampleArgs& a, int dtype, hipStream_t st) {
   if (a.F.threads == 256) {
     if (dtype == SIMPLE_F32) hipLaunchKernelGGL((fast::fast_rows_kernel<float, 256>), grid, dim3(256), a.F.total, st, a);
     else hipLaunchKernelGGL((fast::fast_rows_kernel<uint16_t, 256>), grid, dim3(256), a.F.total, st, a);
-  } else {
+  } else if (a.F.threads == 512) {
     if (dtype == SIMPLE_F32) hipLaunchKernelGGL((fast::fast_rows_kernel<float, 512>), grid, dim3(512), a.F.total, st, a);
     else hipLaunchKernelGGL((fast::fast_rows_kernel<uint16_t, 512>), grid, dim3(512), a.F.total, st, a);
+  } else {
+    if (dtype == SIMPLE_F32) hipLaunchKernelGGL((fast::fast_rows_kernel<float, 1024>), grid, dim3(1024), a.F.total, st, a);
+    else hipLaunchKernelGGL((fast::fast_rows_kernel<uint16_t, 1024>), grid, dim3(1024), a.F.total, st, a);
   }
   return hipGetLastError();
 }
 
 hipError_t set_max_lds_fast(unsigned bytes) {
-  const void* fns[4] = {
+  const void* fns[6] = {
     reinterpret_cast<const void*>(fast::fast_rows_kernel<float, 256>), reinterpret_cast<const void*>(fast::fast_rows_kernel<uint16_t, 256>),
-    reinterpret_cast<const void*>(fast::fast_rows_kernel<float, 512>), reinterpret_cast<const void*>(fast::fast_rows_kernel<uint16_t, 512>)};
-  for (int i = 0; i < 4; ++i) {
+    reinterpret_cast<const void*>(fast::fast_rows_kernel<float, 512>), reinterpret_cast<const void*>(fast::fast_rows_kernel<uint16_t, 512>),
+    reinterpret_cast<const void*>(fast::fast_rows_kernel<float, 1024>), reinterpret_cast<const void*>(fast::fast_rows_kernel<uint16_t, 1024>)};
+  for (int i = 0; i < 6; ++i) {
     const hipError_t e = hipFuncSetAttribute(fns[i], hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
     if (e != hipSuccess) return e;
   }

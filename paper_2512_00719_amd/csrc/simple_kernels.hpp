@@ -29,9 +29,10 @@ struct FastLayout {
   uint32_t long_cap;  // entries of a long certified list that fit beside its bucket tables
   uint32_t samp;      // threshold sample merge area
   uint32_t total;     // 0: the call cannot use the kernel
-  int threads;        // workgroup size the layout was made for (256 or 512)
+  int threads;        // workgroup size the layout was made for (256, 512 or 1024)
 };
 
+constexpr int SAMPLE_PER_WAVE = 48;   // keys of the threshold sample a wave hands to the merge (sizes the merge area)
 constexpr int CAPF_PER_THREAD = 12;  // candidate-list entries per thread the single-pass kernel's epilogue holds in registers
 constexpr int KMAXF = 1024;   // largest top-k its list certifies
 constexpr int32_t PENDING = -2;  // id left by the single-pass kernel on rows the general kernel completes
@@ -68,7 +69,8 @@ struct SampleArgs {
 
 LdsLayout make_layout(int64_t V, int64_t max_nnz, bool with_history);
 // Layout of the single-pass kernel; total = 0 when the call cannot use it.
-FastLayout make_fast_layout(int64_t V, int dtype, int64_t max_nnz, bool with_history, bool vec, int lds_limit);
+FastLayout make_fast_layout(int64_t V, int dtype, int64_t max_nnz, bool with_history, bool vec, int lds_limit,
+                            int64_t B, int n_cu);
 hipError_t launch_sample(const SampleArgs& a, int dtype, bool vec, hipStream_t st, hipEvent_t ev0, hipEvent_t ev1);
 hipError_t launch_fast(const SampleArgs& a, int dtype, hipStream_t st);
 hipError_t launch_wide(const SampleArgs& a, int dtype, hipStream_t st);  // after launch_fast, before the general kernel

@@ -18,7 +18,7 @@ typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef unsigned long long u64;
 
 constexpr int UNR = 4;       // 16-byte loads per lane and tile
-constexpr int SPW = 48;      // sample entries a wave hands to the merge
+constexpr int SPW = SAMPLE_PER_WAVE;  // sample entries a wave hands to the merge
 constexpr int NBF = 256;     // buckets of the long-list tables
 constexpr int MEMB = 512;    // entries the sorted epilogue handles
 constexpr int MEMB2 = 256;   // members of one bucket the long-list path resolves exactly
