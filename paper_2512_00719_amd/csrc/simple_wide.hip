@@ -47,7 +47,6 @@ namespace fast {
 
 #ifdef SIMPLE_PHASE_TIMES  // profiling builds only: per-workgroup timestamps of the first kernel (100 MHz wall clock)
 __device__ unsigned long long g_wide_phase_times[3 * 8192 * 8];
-#define CPHASE(i) do { if (threadIdx.x == 0 && blockIdx.x < 8192) g_wide_phase_times[(16384 + blockIdx.x) * 8 + (i)] = wall_clock64(); } while (0)
 #define XPHASE(i) do { if (threadIdx.x == 0 && blockIdx.x < 8192) g_wide_phase_times[(8192 + blockIdx.x) * 8 + (i)] = wall_clock64(); } while (0)
 #define XWHY(code, v) do { if (threadIdx.x == 0 && blockIdx.x < 8192) { g_wide_phase_times[(8192 + blockIdx.x) * 8 + 6] = (code); g_wide_phase_times[(8192 + blockIdx.x) * 8 + 7] = (v); } } while (0)
 #define WPHASE(i) do { if (threadIdx.x == 0 && blockIdx.x < 8192) g_wide_phase_times[blockIdx.x * 8 + (i)] = wall_clock64(); } while (0)
@@ -61,7 +60,6 @@ __device__ unsigned long long g_wide_phase_times[3 * 8192 * 8];
 #define CACC_DUMP() do { } while (0)
 #define WPHASE(i) do { } while (0)
 #define XPHASE(i) do { } while (0)
-#define CPHASE(i) do { } while (0)
 #define XWHY(code, v) do { } while (0)
 #endif
 
@@ -382,26 +380,30 @@ struct ItemLoads {
   uint32_t pre;    // this thread's mask word or directory entry
 };
 struct SlotIds {
-  uint32_t row_c, act_c, row_n, act_n;  // current slot, next slot
+  uint32_t row_c, act_c, row_n, act_n;  // current slot, next slot; act: bit 0 history in force, bit 1 no truncation
   __device__ __forceinline__ void request(const SampleArgs& a, unsigned slot, unsigned n_wide, uint32_t& row, uint32_t& act) {
     row = 0u; act = 0u;
     if (slot < n_wide) {
       const uint32_t* rec = reinterpret_cast<const uint32_t*>(reinterpret_cast<const WideRec*>(a.wq + WQ_HEAD) + slot);
-      row = as_global(rec)[0]; act = as_global(rec)[11];
+      row = as_global(rec)[0];
+      act = (as_global(rec)[11] != 0u ? 1u : 0u) | (as_global(rec)[2] == (uint32_t)WIDE_ALL ? 2u : 0u);
     }
   }
   // The record is the same in every lane: scalars from here on.  Called where the workgroup waits
   // for its loads anyway (a row's record), so that no later use has to wait for loads in flight.
   __device__ __forceinline__ void settle() { row_c = uni(row_c); act_c = uni(act_c); row_n = uni(row_n); act_n = uni(act_n); }
 };
-static_assert(offsetof(WideRec, row) == 0 && offsetof(WideRec, h_active) == 44, "record words read by SlotIds");
-template <typename DT, bool use_hot>
+static_assert(offsetof(WideRec, row) == 0 && offsetof(WideRec, mode) == 8 && offsetof(WideRec, h_active) == 44, "record words read by SlotIds");
+// skip_all: rows without truncation need nothing from this pass (the bins kernel)
+template <typename DT, bool use_hot, bool skip_all = false>
 __device__ __forceinline__ void item_fetch(ItemLoads<DT>& L, const SampleArgs& a, unsigned item, unsigned n_sl, int cur_slot, const SlotIds& ids) {
   constexpr int EPL = Io<DT>::EPL;
   const int tid = threadIdx.x;
   const int slot = (int)(item / n_sl), c0 = (int)(item % n_sl) * SLC;
   const uint32_t row = slot == cur_slot ? ids.row_c : ids.row_n;  // scalars (SlotIds::settle)
-  const bool act = (slot == cur_slot ? ids.act_c : ids.act_n) != 0u;
+  const uint32_t actw = slot == cur_slot ? ids.act_c : ids.act_n;
+  const bool act = (actw & 1u) != 0u;
+  if (skip_all && (actw & 2u)) return;
   const DT* rowp = reinterpret_cast<const DT*>(a.logits) + (size_t)row * (size_t)a.stride;
   L.pre = act ? slice_fetch(a.wws + (size_t)slot * a.ws_stride, a, c0) : 0u;
 #pragma unroll
@@ -441,8 +443,12 @@ __global__ __launch_bounds__(WT, 5) void wide_bins_kernel(const SampleArgs a) {
   ids.request(a, (unsigned)cur + 1u, n_wide, ids.row_n, ids.act_n);
   WideRow W = load_row(a, (unsigned)cur);
   ids.settle();
+  {  // nothing to do for rows without truncation (a workgroup's items lie in at most two slots)
+    const int last = (int)((I.i1 - 1u) / I.n_sl);
+    if ((ids.act_c & 2u) && (last == cur || (last == cur + 1 && (ids.act_n & 2u)))) return;
+  }
   ItemLoads<DT> N;  // the next item's loads
-  item_fetch<DT, false>(N, a, I.i0, I.n_sl, cur, ids);
+  item_fetch<DT, false, true>(N, a, I.i0, I.n_sl, cur, ids);
   for (int b = tid; b <= NBW; b += WT) lh[b] = 0ull;
   u64 mtop = 0ull;
   float ymax = -INFINITY;  // rows with a min-p cut: largest tempered value seen by this thread
@@ -475,7 +481,7 @@ __global__ __launch_bounds__(WT, 5) void wide_bins_kernel(const SampleArgs a) {
       for (int b = tid; b <= NBW; b += WT) lh[b] = 0ull;
     }
     if (W.mode == WIDE_ALL) {  // every column survives: nothing to find in a first pass
-      if (more) item_fetch<DT, false>(N, a, it + 1u, I.n_sl, cur, ids);
+      if (more) item_fetch<DT, false, true>(N, a, it + 1u, I.n_sl, cur, ids);
       continue;
     }
     const DT* rowp = reinterpret_cast<const DT*>(a.logits) + (size_t)W.row * (size_t)a.stride;
@@ -486,7 +492,7 @@ __global__ __launch_bounds__(WT, 5) void wide_bins_kernel(const SampleArgs a) {
       __syncthreads();
       hist_fetch<DT>(HP, Tb, W.ws, a, rowp, c0, V);  // this item's own loads go first: loads return in order
     } else __syncthreads();  // the zeroed bins are visible
-    if (more) item_fetch<DT, false>(N, a, it + 1u, I.n_sl, cur, ids);
+    if (more) item_fetch<DT, false, true>(N, a, it + 1u, I.n_sl, cur, ids);
     WPHASE(2);
     auto one = [&](float z, int) {
       if (W.mode == WIDE_MIN_P) { ymax = fmaxf(ymax, tempered(z, W.C)); return; }
@@ -671,6 +677,7 @@ __global__ __launch_bounds__(WT, 4) void wide_classify_kernel(const SampleArgs a
     if (W.h_active) hist_fetch<DT>(HP, Tb, W.ws, a, rowp, c0, V);  // this item's own loads go first: loads return in order
     if (more) item_fetch<DT, use_hot>(N, a, it + 1u, I.n_sl, cur, ids);
     CACC(2);
+    u64 acc_s = 0ull, acc1 = 0ull;  // this slice: mass of the sure columns, and of the hot ones among them
     // one column the slow way: history columns and the ragged end of the row
     auto one = [&](float z, int idx) {
       int b; float y;
@@ -682,17 +689,16 @@ __global__ __launch_bounds__(WT, 4) void wide_classify_kernel(const SampleArgs a
       ymax = fmaxf(ymax, y);
       if (!(y >= thr_y)) return;
       if (!below || b < bstar) {
-        const unsigned hot = use_hot ? hot_bit(hot_bits, (uint32_t)idx) : 0u;
-        atomicAdd(&ltile[hot], m);
+        acc_s += m;
+        if (use_hot && hot_bit(hot_bits, (uint32_t)idx)) acc1 += m;
         ++n_sure;
       } else if (b == bstar) {
         const unsigned s = atomicAdd(&l_n, 1u);
         if (s < (unsigned)LCAP) lrl[s] = ((u64)__float_as_uint(z) << 32) | (u64)(uint32_t)idx;
       }
     };
-    // The main line: masses of the columns below g and their class by the logit alone; the rare
-    // cases (a column at or above g, a boundary column) follow under wave-wide tests.
-    u64 acc_s = 0ull, acc1 = 0ull;  // mass of the sure columns, and of the hot ones among them
+    // The main line: every column's mass, and its class by the logit alone; boundary columns follow
+    // under a wave-wide test.
     auto sweep = [&](auto unit_tau_c, auto want_all_c) {
       constexpr bool UT = decltype(unit_tau_c)::value, WANT_ALL = decltype(want_all_c)::value;
 #pragma unroll
