@@ -699,8 +699,9 @@ __global__ __launch_bounds__(WT, 4) void wide_classify_kernel(const SampleArgs a
     };
     // The main line: every column's mass, and its class by the logit alone; boundary columns follow
     // under a wave-wide test.
-    auto sweep = [&](auto unit_tau_c, auto want_all_c) {
-      constexpr bool UT = decltype(unit_tau_c)::value, WANT_ALL = decltype(want_all_c)::value;
+    auto sweep = [&](auto unit_tau_c, auto want_all_c, auto all_sure_c) {
+      // UT: tau == 1; WANT_ALL: the row's mass is summed here (no bins); ALL_SURE: no truncation, every column survives
+      constexpr bool UT = decltype(unit_tau_c)::value, WANT_ALL = decltype(want_all_c)::value, ALL_SURE = decltype(all_sure_c)::value;
 #pragma unroll
       for (int j = 0; j < G; ++j) {
         const int idx0 = c0 + (j * WT + tid) * EPL;
@@ -714,7 +715,7 @@ __global__ __launch_bounds__(WT, 4) void wide_classify_kernel(const SampleArgs a
 #pragma unroll
             for (int e = 0; e < EPL; ++e) z[e] = ((live >> e) & 1u) ? z[e] : -INFINITY;
             // ... but -inf counts as sure when every value does
-            if (zc.z_sure == -INFINITY) n_sure -= (unsigned)__popc(~live & EMASK);
+            if (ALL_SURE || zc.z_sure == -INFINITY) n_sure -= (unsigned)__popc(~live & EMASK);
           }
           // group sums of the masses' two parts (units of 2^24, and the rest): <= 8 terms of <= 2^25
           uint32_t sh = 0u, sl_ = 0u, hh = 0u, hl = 0u, ah = 0u, al = 0u;
@@ -725,18 +726,24 @@ __global__ __launch_bounds__(WT, 4) void wide_classify_kernel(const SampleArgs a
             bad = bad || !(w <= W_LIMIT);  // a mass the fixed point cannot carry, or a NaN
             uint32_t hi, lo;
             float_to_parts(w * MSCALE, hi, lo);
-            const bool sure = z[e] >= zc.z_sure;
             ymax = fmaxf(ymax, y);
-            const uint32_t his = sure ? hi : 0u, los = sure ? lo : 0u;
-            sh += his; sl_ += los;
-            if (use_hot) { const uint32_t hm = (uint32_t)(-(int32_t)((L.hq[j] >> e) & 1u)); hh += his & hm; hl += los & hm; }
-            if (WANT_ALL) { ah += hi; al += lo; }
-            n_sure += sure ? 1u : 0u;
-            any_edge = any_edge || (z[e] >= zc.z_edge && !sure);
+            if (ALL_SURE) {
+              sh += hi; sl_ += lo;
+              if (use_hot) { const uint32_t hm = (uint32_t)(-(int32_t)((L.hq[j] >> e) & 1u)); hh += hi & hm; hl += lo & hm; }
+            } else {
+              const bool sure = z[e] >= zc.z_sure;
+              const uint32_t his = sure ? hi : 0u, los = sure ? lo : 0u;
+              sh += his; sl_ += los;
+              if (use_hot) { const uint32_t hm = (uint32_t)(-(int32_t)((L.hq[j] >> e) & 1u)); hh += his & hm; hl += los & hm; }
+              if (WANT_ALL) { ah += hi; al += lo; }
+              n_sure += sure ? 1u : 0u;
+              any_edge = any_edge || (z[e] >= zc.z_edge && !sure);
+            }
           }
           acc_s += parts_to_u64(sh, sl_);
           if (use_hot) acc1 += parts_to_u64(hh, hl);
-          if (WANT_ALL) acc_all += parts_to_u64(ah, al);
+          if (ALL_SURE) { acc_all += parts_to_u64(sh, sl_); n_sure += (unsigned)EPL; }
+          else if (WANT_ALL) acc_all += parts_to_u64(ah, al);
           if (__ballot(any_edge)) {  // boundary columns of the whole group: one reservation per wave
             u64 em[EPL];
             unsigned pre[EPL], tot = 0u;
@@ -764,8 +771,13 @@ __global__ __launch_bounds__(WT, 4) void wide_classify_kernel(const SampleArgs a
       }
     };
     // the top-p route has the row's mass from its bins; the other routes sum it here
-    if (W.tau == 1.0f) { if (W.mode == WIDE_TOP_P) sweep(std::true_type{}, std::false_type{}); else sweep(std::true_type{}, std::true_type{}); }
-    else { if (W.mode == WIDE_TOP_P) sweep(std::false_type{}, std::false_type{}); else sweep(std::false_type{}, std::true_type{}); }
+    const std::true_type yes{};
+    const std::false_type no{};
+    if (W.tau == 1.0f) {
+      if (W.mode == WIDE_TOP_P) sweep(yes, no, no); else if (W.mode == WIDE_ALL) sweep(yes, yes, yes); else sweep(yes, yes, no);
+    } else {
+      if (W.mode == WIDE_TOP_P) sweep(no, no, no); else if (W.mode == WIDE_ALL) sweep(no, yes, yes); else sweep(no, yes, no);
+    }
     CACC(3);
     if (W.h_active) {  // the history columns, whose logits and counts were requested before the main line
       hist_stage<DT>(Tb, HP, W.ws, a, rowp, c0, V);
