@@ -112,8 +112,9 @@ enum {
  * Create a context on HIP device `device` for calls with at most max_V vocabulary entries and at
  * most max_nnz_per_row history ids per row (0 if no history will ever be passed).  Allocates, in
  * device memory, the hot-set membership bitmap (max_V bits), the row queues and the workspace of
- * the rows whose survivors do not fit the on-chip candidate list (1024 slots of about 52 KB plus
- * the size of one row's history tables).  Returns SIMPLE_ECAPACITY if one row's
+ * the rows whose survivors do not fit the on-chip candidate list (4096 slots of about 52 KB plus
+ * the size of one row's history tables: 0.2 to 0.5 GB; a call with more rows than slots goes out in
+ * several launches, so no row ever lacks a slot).  Returns SIMPLE_ECAPACITY if one row's
  * on-chip state (history bitmap, counts, candidate list) cannot fit the LDS of one compute unit.
  * Host pointers: out.
  */

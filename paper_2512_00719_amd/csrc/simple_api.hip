@@ -276,12 +276,13 @@ int simple_sample(simple_ctx* ctx, const void* logits_dev, int64_t B, int64_t V,
   a.n_cu = ctx->n_cu;
   a.wq = ctx->wq; a.wws = ctx->wws; a.wide_slots = simple::WIDE_SLOTS; a.ws_stride = ctx->ws_stride;
   a.L = simple::make_layout(V, ctx->max_nnz, hist_ptr_dev != nullptr);
+  // rows go out in launches that neither queue can overflow
+  const int64_t per_launch = simple::PEND_ROWS < simple::WIDE_SLOTS ? simple::PEND_ROWS : simple::WIDE_SLOTS;
   a.F = simple::make_fast_layout(V, dtype, hist_ptr_dev ? ctx->max_nnz : 0, hist_ptr_dev != nullptr, vec, ctx->lds_limit,
-                                 B < simple::PEND_ROWS ? B : simple::PEND_ROWS, ctx->n_cu);
+                                 B < per_launch ? B : per_launch, ctx->n_cu);
   a.gated = (a.F.total != 0u) ? 1 : 0;
-  // rows go out in launches of at most PEND_ROWS (the capacity of the pending-row queue)
-  for (int64_t b0 = 0; b0 < B; b0 += simple::PEND_ROWS) {
-    const int64_t nb = (B - b0 < simple::PEND_ROWS) ? (B - b0) : simple::PEND_ROWS;
+  for (int64_t b0 = 0; b0 < B; b0 += per_launch) {
+    const int64_t nb = (B - b0 < per_launch) ? (B - b0) : per_launch;
     a.B = (int)nb;
     a.logits = static_cast<const char*>(logits_dev) + (size_t)b0 * (size_t)row_stride_elems * esz;
     a.params = params_dev + b0;

@@ -37,7 +37,8 @@ constexpr int CAPF_PER_THREAD = 12;  // candidate-list entries per thread the si
 constexpr int KMAXF = 1024;   // largest top-k its list certifies
 constexpr int32_t PENDING = -2;  // id left by the single-pass kernel on rows the general kernel completes
 constexpr int PEND_ROWS = 65536; // rows per launch (capacity of the pending-row queue)
-constexpr int WIDE_SLOTS = 1024; // rows per launch the whole-vocabulary-nucleus kernels can take
+constexpr int WIDE_SLOTS = 4096; // workspace slots of the whole-vocabulary-nucleus kernels; a launch takes no more rows than this,
+                                 // so every row of it can be queued for them
 constexpr uint32_t WIDE_SLOT_FIXED = 53312;  // workspace per such row, before its history tables
 
 struct SampleArgs {
