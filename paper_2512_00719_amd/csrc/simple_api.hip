@@ -64,6 +64,7 @@ FastLayout make_fast_layout(int64_t V, int dtype, int64_t max_nnz, bool with_his
     off = align16(n_pairs * 8u);
     F.dir = off; off = align16(off + n_pairs * 2u);
     F.cnt = off; off = align16(off + (uint32_t)((max_nnz + 3) / 2) * 4u);
+    F.claim = off; off = align16(off + (uint32_t)((max_nnz + 31) / 32) * 4u);
   }
   const uint32_t tables = 256u * 12u + 256u * 16u;           // bucket tables of the long-list epilogue
   uint32_t body = off < 28672u ? 28672u : off;               // >= 14 KB of sorted-epilogue arrays, >= 3072-entry list

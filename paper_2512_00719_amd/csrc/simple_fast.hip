@@ -641,12 +641,14 @@ __global__ __launch_bounds__(NTHR, 4) void fast_rows_kernel(const SampleArgs a) 
   const bool lowering = par.rep_penalty >= 1.0f && par.freq_penalty >= 0.0f && par.pres_penalty >= 0.0f;
   const bool h_active = (nnz > 0) && pen_on;
   const bool no_trunc = !R.greedy && !R.k_on && !R.p_on && !R.minp_on;
-  // the mass correction below needs every history id in the owners' registers
-  const bool sum_ok = !R.need_sum || !h_active || nnz <= IDR * NTHR;
-  // rows without any truncation keep no candidate list: they only pass through here on their way
-  // to the kernels of the whole-vocabulary routes
-  const bool eligible = no_trunc ? (!bad_par && !too_long)
-                                 : (!bad_par && !too_long && (!h_active || lowering) && sum_ok &&
+  // Rows that keep no candidate list and only pass through here on their way to the kernels of the
+  // whole-vocabulary routes, which apply any penalties column by column: rows without any
+  // truncation, and rows without top-k whose penalties raise logits (the list's threshold test on
+  // raw logits would miss columns).
+  const bool straight = no_trunc || (!R.greedy && !R.k_on && !R.p_le0 && h_active && !lowering);
+  const uint32_t straight_mode = no_trunc ? (uint32_t)WIDE_ALL : (R.p_on ? (uint32_t)WIDE_TOP_P : (uint32_t)WIDE_MIN_P);
+  const bool eligible = straight ? (!bad_par && !too_long)
+                                 : (!bad_par && !too_long && (!h_active || lowering) &&
                                     (R.greedy || !R.k_on || par.top_k <= KMAXF));
   if (!eligible) {  // the general kernel takes the row (it also reports parameter errors)
     FWHY(1);
@@ -681,7 +683,7 @@ __global__ __launch_bounds__(NTHR, 4) void fast_rows_kernel(const SampleArgs a) 
     __syncthreads();
     // ---- presence mask of the history (in the shared region); all tables for a row that leaves early ----
     if (H.active) {
-      if (no_trunc) { unsigned own; build_history<NTHR>(S, H, ids, hist, nnz, par.n_prompt, V, own); }
+      if (straight) { unsigned own; build_history<NTHR>(S, H, ids, hist, nnz, par.n_prompt, V, own); }
       else build_bitmap<NTHR>(S, H, ids, hist, nnz, V);
     }
   }
@@ -790,8 +792,8 @@ __global__ __launch_bounds__(NTHR, 4) void fast_rows_kernel(const SampleArgs a) 
     }
     return true;
   };
-  if (no_trunc) {  // every column survives: nothing to select here
-    if (!queue_wide(WIDE_ALL, true) && tid == 0) queue_pending(a, row);
+  if (straight) {  // nothing to select here (without truncation every column survives)
+    if (!queue_wide(straight_mode, true) && tid == 0) queue_pending(a, row);
     return;
   }
   const bool minp_only = !R.greedy && !R.k_on && !R.p_on && R.minp_on;
@@ -867,17 +869,47 @@ __global__ __launch_bounds__(NTHR, 4) void fast_rows_kernel(const SampleArgs a) 
       FPHASE(16);
       if (R.need_sum) {
         // exact correction of the mass below g for the history columns (the stream summed their raw
-        // values); each distinct column is handled by the thread that first marked it
+        // values), once per distinct column: by the thread that first marked it when all ids sit in
+        // registers, else by the thread that first claims the column's rank
+        const bool by_claim = nnz > IDR * NTHR;
+        uint32_t* claim = reinterpret_cast<uint32_t*>(lds + a.F.claim);
+        if (by_claim) {
+          zero16(claim, ((nnz + 31) / 32) * 4, tid, NTHR);
+          __syncthreads();
+        }
+        auto claims = [&](int id) -> bool {  // true for exactly one of the entries that name this column
+          if ((unsigned)id >= (unsigned)V) return false;
+          const unsigned r = H.rank(id, H.bm[id >> 5]);
+          const uint32_t bit = 1u << (r & 31u);
+          return !(atomicOr(&claim[r >> 5], bit) & bit);
+        };
+        auto correct = [&](float z_raw, int id) {  // columns at or above g are in the list: their terms are settled there
+          if (z_raw < C.g) {
+            below_mass -= (u64)below_term(z_raw, C);
+            below_mass += (u64)below_term(H.penalised_at(z_raw, id), C);
+          }
+        };
+        if (by_claim) {
+          own = 0u;
+#pragma unroll
+          for (int j = 0; j < IDR; ++j) if (tid + j * NTHR < nnz && claims(ids[j])) own |= 1u << j;
+        }
         float zr[IDR];
 #pragma unroll
         for (int j = 0; j < IDR; ++j) zr[j] = ((own >> j) & 1u) ? Io<DT>::one(rowp + ids[j]) : 0.0f;
 #pragma unroll
-        for (int j = 0; j < IDR; ++j) {
-          // columns at or above g are in the list: their terms are settled there
-          if (((own >> j) & 1u) && zr[j] < C.g) {
-            below_mass -= (u64)below_term(zr[j], C);
-            below_mass += (u64)below_term(H.penalised_at(zr[j], ids[j]), C);
-          }
+        for (int j = 0; j < IDR; ++j) if ((own >> j) & 1u) correct(zr[j], ids[j]);
+        // entries beyond the registers, four at a time (their trips to memory overlap)
+        for (int i0 = tid + IDR * NTHR; i0 < nnz; i0 += 4 * NTHR) {
+          int id4[4]; bool mine[4]; float z4[4];
+#pragma unroll
+          for (int k = 0; k < 4; ++k) id4[k] = (i0 + k * NTHR < nnz) ? hist[i0 + k * NTHR] : -1;
+#pragma unroll
+          for (int k = 0; k < 4; ++k) mine[k] = claims(id4[k]);
+#pragma unroll
+          for (int k = 0; k < 4; ++k) z4[k] = mine[k] ? Io<DT>::one(rowp + id4[k]) : 0.0f;
+#pragma unroll
+          for (int k = 0; k < 4; ++k) if (mine[k]) correct(z4[k], id4[k]);
         }
       }
       __syncthreads();

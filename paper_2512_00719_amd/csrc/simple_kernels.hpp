@@ -25,6 +25,7 @@ struct FastLayout {
   uint32_t bitmap;    // history presence mask, one bit per column (region offset 0)
   uint32_t dir;       // 16-bit count of set bits before each pair of mask words
   uint32_t cnt;       // 16-bit generated-token counts, indexed by the rank of the id among the set bits
+  uint32_t claim;     // one bit per rank: set by the thread that corrects that column's mass (long histories)
   uint32_t list_cap;  // entries of the candidate list (value word + id word each) the region holds
   uint32_t long_cap;  // entries of a long certified list that fit beside its bucket tables
   uint32_t samp;      // threshold sample merge area

@@ -133,11 +133,36 @@ def test_rows_the_single_pass_kernel_must_leave_to_the_general_kernel():
     w = synth.Workload("leave", B, V, "f32", z, params, hist_ptr, hist_ids)
     for ids, dg in _run(w, steps=(0, 1)):
         general = (dg["flags"] & GENERAL) > 0
-        # 0: nucleus over all of V with more history ids than the mass correction holds in registers;
-        # 3, 6: penalties that raise logits; 4: top-k above the list's limit
-        assert general[[0, 3, 4, 6]].all()
-        # 2, 5: no truncation at all: straight to the whole-vocabulary kernels
-        assert not general[[1, 2, 5, 7]].any() and ((dg["flags"] & WIDE) > 0)[[2, 5]].all()
+        wide = (dg["flags"] & WIDE) > 0
+        # 3: top-k with penalties that raise logits; 4: top-k above the list's limit
+        assert general[[3, 4]].all()
+        # 0: a long history is corrected by claims, not left; 2, 5: no truncation at all and 6: no top-k
+        # with penalties that raise logits: straight to the whole-vocabulary kernels
+        assert not general[[0, 1, 2, 5, 7]].any() and wide[[2, 5]].all()
+        assert wide[6] or general[6]
+
+
+def test_nucleus_rows_with_more_history_ids_than_registers_hold():
+    """top-p without top-k keeps the mass below the threshold exact by correcting every distinct
+    history column once; with more ids than 16 per thread the columns are claimed by rank."""
+    rng = np.random.default_rng(35)
+    B, V = 600, 20_480  # more rows than two per compute unit: 256 threads per row, 4096 ids in registers
+    z = _flat_logits(rng, B, V, sigma=3.5)
+    lens = rng.integers(0, 3000, B)
+    lens[:24] = rng.integers(4097, 12_000, 24)
+    hist_ptr, hist_ids = _head_history(z, lens, rng, head=6000)
+    params = synth.make_params(B, temperature=[0.9, 1.0, 1.1] * 200, top_p=[0.9, 0.8, 0.95, 0.7] * 150,
+                               rep_penalty=1.2, freq_penalty=0.15, pres_penalty=0.1, n_prompt=[0, 2000, 50] * 200)
+    w = synth.Workload("long-hist", B, V, "f32", z, params, hist_ptr, hist_ids)
+    rows = sorted(set(range(24)) | set(rng.choice(B, 24, replace=False).tolist()))
+    for step in (0, 1):
+        ids, dg = P.run_gpu(w, step)
+        P.compare(ids, dg, P.run_oracle(w, step, rows=rows), rows)
+        f = dg["flags"]
+        # most of them are settled by the list (a history that covers the whole head of the row can
+        # still push the cut above the threshold, which the general kernel resolves)
+        assert ((f & GENERAL) > 0)[:24].sum() <= 4
+        assert (((f & WIDE) == 0) & ((f & GENERAL) == 0))[:24].sum() >= 12
 
 
 def test_one_context_alternating_routes_call_after_call():
