@@ -645,8 +645,11 @@ __global__ __launch_bounds__(NTHR, 4) void fast_rows_kernel(const SampleArgs a) 
   // whole-vocabulary routes, which apply any penalties column by column: rows without any
   // truncation, and rows without top-k whose penalties raise logits (the list's threshold test on
   // raw logits would miss columns).
-  const bool straight = no_trunc || (!R.greedy && !R.k_on && !R.p_le0 && h_active && !lowering);
-  const uint32_t straight_mode = no_trunc ? (uint32_t)WIDE_ALL : (R.p_on ? (uint32_t)WIDE_TOP_P : (uint32_t)WIDE_MIN_P);
+  // ... and rows with top-k alone beyond the list's reach (any penalties).
+  const bool big_k = !R.greedy && R.k_on && par.top_k > KMAXF && !R.p_on && !R.minp_on;
+  const bool straight = no_trunc || big_k || (!R.greedy && !R.k_on && !R.p_le0 && h_active && !lowering);
+  const uint32_t straight_mode = no_trunc ? (uint32_t)WIDE_ALL : big_k ? (uint32_t)WIDE_TOP_K
+                                          : (R.p_on ? (uint32_t)WIDE_TOP_P : (uint32_t)WIDE_MIN_P);
   const bool eligible = straight ? (!bad_par && !too_long)
                                  : (!bad_par && !too_long && (!h_active || lowering) &&
                                     (R.greedy || !R.k_on || par.top_k <= KMAXF));
@@ -655,7 +658,9 @@ __global__ __launch_bounds__(NTHR, 4) void fast_rows_kernel(const SampleArgs a) 
     if (tid == 0) queue_pending(a, row);
     return;
   }
-  const int k_sel = R.greedy ? 1 : (R.k_on ? par.top_k : (R.p_le0 ? 1 : KMAXF));
+  // (top-k beyond the list: the threshold is only the reference of the masses and must leave fewer
+  // than top_k columns above it, so it aims at a quarter of them)
+  const int k_sel = R.greedy ? 1 : (R.k_on ? (big_k ? par.top_k / 4 : par.top_k) : (R.p_le0 ? 1 : KMAXF));
   if (tid == 0) {
     S.cand_count = 0u; S.flags = 0u; S.kmax = 0u; S.memb = 0u; S.bk = -1; S.bp = -1; S.bd = -1;
     S.need_k = 0u; S.cut_k = 0ull; S.cut_p = 0ull; S.n_p = 0u; S.out_id = -1; S.out_w = 0ull;
@@ -786,7 +791,7 @@ __global__ __launch_bounds__(NTHR, 4) void fast_rows_kernel(const SampleArgs a) 
       rec.row = (uint32_t)row; rec.g = C.g; rec.mode = mode; rec.flags = S.flags & 0x3FFFFFFFu;
       rec.tau = R.tau; rec.top_p = R.top_p; rec.rep = par.rep_penalty; rec.freq = par.freq_penalty;
       rec.pres = par.pres_penalty; rec.nnz = nnz; rec.n_prompt = min(max(par.n_prompt, 0), nnz); rec.h_active = h_active ? 1 : 0;
-      rec.min_p = R.min_p; rec.reserved0 = 0u; rec.distinct = H.active ? S.distinct : 0u; rec.reserved1 = 0u;
+      rec.min_p = R.min_p; rec.top_k = par.top_k; rec.distinct = H.active ? S.distinct : 0u; rec.reserved1 = 0u;
       reinterpret_cast<WideRec*>(a.wq + WQ_HEAD)[slot] = rec;
       a.out[row] = PENDING;
     }

@@ -203,17 +203,19 @@ struct WideRec {  // 64 bytes: everything the later kernels need to know about t
   uint32_t row; float g; uint32_t mode, flags;
   float tau, top_p, rep, freq;
   float pres; int nnz, n_prompt, h_active;
-  float min_p; uint32_t reserved0; uint32_t distinct, reserved1;
+  float min_p; int32_t top_k; uint32_t distinct, reserved1;
 };
 // What delimits the survivors of a queued row (each is a prefix of the total order, section 5.2):
 enum { WIDE_TOP_P = 0,   // the shortest prefix whose mass reaches top_p of the row's mass
        WIDE_ALL = 1,     // no truncation: every column
-       WIDE_MIN_P = 2 }; // tempered value >= fl(y_max + fl(ln min_p))
+       WIDE_MIN_P = 2,   // tempered value >= fl(y_max + fl(ln min_p))
+       WIDE_TOP_K = 3 }; // the first top_k columns of the order (top-k alone, beyond the candidate list's reach)
+constexpr int CNT_SHIFT = 46;  // top-k route: a bin's column count rides above its mass (< 2^18 columns of <= 2^28 each)
 constexpr int WQ_HEAD = 16;             // words before the records
 constexpr uint32_t WS_HIST = 0u;        // u64[NBW]: mass of the columns below g, by bin
 constexpr uint32_t WS_TILES = 16384u;   // u64[2][256]: survivors' mass per tile, tail class then hot class
 constexpr uint32_t WS_SCAL = 20480u;    // u64 mass at or above g; u32 sure survivors; u32 boundary columns; u64 exact mass
-                                        // of the row; u32 largest key of a tempered value
+                                        // of the row; u32 largest key of a tempered value; u32 columns at or above g
 constexpr uint32_t WS_RL = 20544u;      // u64[RCAP]: columns of the boundary bin (value bits << 32 | id)
 constexpr uint32_t WS_HT = 53312u;      // the row's history tables as the single-pass kernel laid them out in LDS
 // [0, WS_RL) must be zero when a row is queued

@@ -1,6 +1,7 @@
 // Rows whose survivors are not a short prefix that the single-pass kernel's candidate list can hold:
 // a nucleus over the whole vocabulary that is wider than the list (top-p over all of V, section 2.1
-// Eq. (2)), no truncation at all (every column survives), or a min-p cut below the list's reach.
+// Eq. (2)), no truncation at all (every column survives), a min-p cut below the list's reach, or
+// top-k alone with k above what the list certifies.
 //
 // The single-pass kernel queues such rows with their threshold g.  Their remaining work is two more
 // reads of the row, which one workgroup per row would do at the latency of a single compute unit;
@@ -31,7 +32,9 @@
 // order: what is needed first is requested first.
 //
 // Rows without truncation skip the first kernel and have no cut; rows with a min-p cut use the first
-// kernel for the row maximum only (the cut is a value).
+// kernel for the row maximum only (the cut is a value).  Rows with top-k alone run the same three
+// kernels by count instead of mass: a bin also counts its columns, the cut's bin is the one in which
+// the count from the top reaches k, and the descent inside it weighs every column as one.
 //
 // Penalties (section 2.2) are applied on the fly: the single-pass kernel leaves the row's history
 // tables (presence mask, rank directory, counts by rank) in the row's workspace slot, and a slice
@@ -81,6 +84,7 @@ struct WideRow {
   float rep, freq, pres;
   double inv_rep;
   uint32_t distinct;
+  int top_k;
   unsigned char* ws;
 };
 
@@ -105,6 +109,7 @@ __device__ __forceinline__ WideRow load_row(const SampleArgs& a, unsigned slot) 
   W.inv_rep = uni(1.0 / (double)rec.rep);
   W.h_active = uni(rec.h_active) != 0;
   W.distinct = uni(rec.distinct);
+  W.top_k = uni(rec.top_k);
   W.ws = a.wws + (size_t)slot * a.ws_stride;
   return W;
 }
@@ -258,6 +263,7 @@ __device__ __forceinline__ void hist_columns(const SliceTabs& T, const WideRow& 
 
 // The bin that holds the cut, from the masses of the first pass: cumulative mass from the top
 // reaches top_p * total.  bstar < 0 if none.  Ends with a barrier.
+constexpr u64 MASS_BITS = (1ull << CNT_SHIFT) - 1ull;
 __device__ inline int find_cut(FS& S, const WideRow& W, u64& s_tot) {
   const int tid = threadIdx.x;
   constexpr int BPT = NBW / WT;
@@ -265,7 +271,7 @@ __device__ inline int find_cut(FS& S, const WideRow& W, u64& s_tot) {
   const u64 m_top = as_global(reinterpret_cast<const u64*>(W.ws + WS_SCAL))[0];
   u64 hm[BPT]; u64 loc = 0ull;
 #pragma unroll
-  for (int j = 0; j < BPT; ++j) { hm[j] = as_global(gh)[tid * BPT + j]; loc += hm[j]; }
+  for (int j = 0; j < BPT; ++j) { hm[j] = as_global(gh)[tid * BPT + j] & MASS_BITS; loc += hm[j]; }
   if (tid == 0) S.bk = -1;
   unsigned ce, ct; u64 me, mt;
   blk_excl_scan2<WNW>(S, 0u, loc, ce, me, ct, mt);
@@ -282,6 +288,31 @@ __device__ inline int find_cut(FS& S, const WideRow& W, u64& s_tot) {
   __syncthreads();
   return bstar;
 }
+// The same by count, for top-k alone: the bin in which the number of columns from the top reaches
+// top_k.  bstar < 0 if none (already top_k columns at or above g, or fewer than top_k in all).
+__device__ inline int find_cut_k(FS& S, const WideRow& W) {
+  const int tid = threadIdx.x;
+  constexpr int BPT = NBW / WT;
+  const u64* gh = reinterpret_cast<const u64*>(W.ws + WS_HIST);
+  const unsigned n_top = as_global(reinterpret_cast<const uint32_t*>(W.ws + WS_SCAL))[7];
+  unsigned hc[BPT], loc = 0u;
+#pragma unroll
+  for (int j = 0; j < BPT; ++j) { hc[j] = (unsigned)(as_global(gh)[tid * BPT + j] >> CNT_SHIFT); loc += hc[j]; }
+  if (tid == 0) S.bk = -1;
+  unsigned ce, ct; u64 me, mt;
+  blk_excl_scan2<WNW>(S, loc, 0ull, ce, me, ct, mt);
+  const unsigned target = (unsigned)W.top_k;
+  unsigned run = n_top + ce;
+#pragma unroll
+  for (int j = 0; j < BPT; ++j) {
+    if (run < target && run + hc[j] >= target) S.bk = tid * BPT + j;
+    run += hc[j];
+  }
+  __syncthreads();
+  const int bstar = S.bk;
+  __syncthreads();
+  return bstar;
+}
 
 // How a column is classified, per route: it surely survives iff its tempered value reaches thr_y and it
 // lies at or above g or in a bin before bstar; columns of bin bstar are resolved one by one.
@@ -290,6 +321,7 @@ __device__ inline RowCut row_cut(FS& S, const WideRow& W) {  // every thread cal
   RowCut c;
   c.thr_y = -INFINITY; c.valid = true; c.s_tot = 0ull;
   if (W.mode == WIDE_TOP_P) { c.bstar = find_cut(S, W, c.s_tot); c.valid = c.bstar >= 0; }
+  else if (W.mode == WIDE_TOP_K) { c.bstar = find_cut_k(S, W); c.valid = c.bstar >= 0; }
   else c.bstar = NBW;  // no bin holds a cut
   if (W.mode != WIDE_ALL && W.min_p > 0.0f) {  // min-p, alone or on top of top-p: the shorter prefix wins
     const uint32_t kmax = as_global(reinterpret_cast<const uint32_t*>(W.ws + WS_SCAL))[6];
@@ -451,20 +483,25 @@ __global__ __launch_bounds__(WT, 5) void wide_bins_kernel(const SampleArgs a) {
   item_fetch<DT, false, true>(N, a, I.i0, I.n_sl, cur, ids);
   for (int b = tid; b <= NBW; b += WT) lh[b] = 0ull;
   u64 mtop = 0ull;
+  unsigned ntop = 0u;      // top-k route: columns at or above g seen by this thread
   float ymax = -INFINITY;  // rows with a min-p cut: largest tempered value seen by this thread
   auto flush = [&]() {
     __syncthreads();
-    if (W.mode == WIDE_TOP_P) {
+    if (W.mode == WIDE_TOP_P || W.mode == WIDE_TOP_K) {
       u64* gh = reinterpret_cast<u64*>(W.ws + WS_HIST);
       for (int b = tid; b < NBW; b += WT) { const u64 v = lh[b]; if (v) atomicAdd(&gh[b], v); }
       const u64 t = blk_sum_u64<WNW>(S, mtop) + lh[NBW];
       if (tid == 0 && t) atomicAdd(reinterpret_cast<u64*>(W.ws + WS_SCAL), t);
+      if (W.mode == WIDE_TOP_K) {
+        const unsigned nt = wave_sum(ntop);
+        if ((tid & 63) == 0 && nt) atomicAdd(reinterpret_cast<uint32_t*>(W.ws + WS_SCAL) + 7, nt);
+      }
     }
     if (W.min_p > 0.0f) {
       const float m = wave_max(ymax);
       if ((tid & 63) == 0 && m > -INFINITY) atomicMax(reinterpret_cast<uint32_t*>(W.ws + WS_SCAL) + 6, fkey(m));
     }
-    mtop = 0ull; ymax = -INFINITY;
+    mtop = 0ull; ntop = 0u; ymax = -INFINITY;
   };
   for (unsigned it = I.i0; it < I.i1; ++it) {
     const int slot = (int)(it / I.n_sl), sl = (int)(it % I.n_sl);
@@ -499,8 +536,9 @@ __global__ __launch_bounds__(WT, 5) void wide_bins_kernel(const SampleArgs a) {
       int b; float y;
       const float w = mass_term(z, W.C, b, y);
       ymax = fmaxf(ymax, y);
-      if (z < W.C.g) atomicAdd(&lh[b], mass_fix_below(w));
-      else mtop += mass_fix(fminf(w, W_LIMIT));
+      // top-k route: a bin also counts its columns, above its mass
+      if (z < W.C.g) atomicAdd(&lh[b], mass_fix_below(w) | (W.mode == WIDE_TOP_K ? 1ull << CNT_SHIFT : 0ull));
+      else { mtop += mass_fix(fminf(w, W_LIMIT)); ++ntop; }
     };
     if (W.mode == WIDE_MIN_P) {  // the row maximum is all a value cut needs
 #pragma unroll
@@ -520,16 +558,17 @@ __global__ __launch_bounds__(WT, 5) void wide_bins_kernel(const SampleArgs a) {
         }
       }
     } else {
-      auto sweep = [&](auto unit_tau_c) {
-        constexpr bool UT = decltype(unit_tau_c)::value;
+      auto sweep = [&](auto unit_tau_c, auto top_k_c) {
+        constexpr bool UT = decltype(unit_tau_c)::value, TOPK = decltype(top_k_c)::value;
 #pragma unroll
         for (int j = 0; j < G; ++j) {
           const int idx0 = c0 + (j * WT + tid) * EPL;
           if (idx0 + EPL <= V) {
             float z[EPL];
             Io<DT>::unpack(L.A[j], z);
+            uint32_t nib = 0u;
             if (W.h_active) {  // history columns are handled below: here they count as -inf (no mass)
-              const uint32_t nib = (Tb.bm[wbase + j * (WT * EPL / 32)] >> wsh) & ((1u << EPL) - 1u);
+              nib = (Tb.bm[wbase + j * (WT * EPL / 32)] >> wsh) & ((1u << EPL) - 1u);
 #pragma unroll
               for (int e = 0; e < EPL; ++e) z[e] = ((nib >> e) & 1u) ? -INFINITY : z[e];
             }
@@ -539,7 +578,13 @@ __global__ __launch_bounds__(WT, 5) void wide_bins_kernel(const SampleArgs a) {
               const float w = mass_term<UT>(z[e], W.C, b);
               uint32_t hi, lo;
               float_to_parts(fminf(w, W_LIMIT) * MSCALE, hi, lo);
-              atomicAdd(&lh[(z[e] < W.C.g) ? b : NBW], parts_to_u64(hi, lo));
+              const bool below = z[e] < W.C.g;
+              u64 v = parts_to_u64(hi, lo);
+              if (TOPK) {  // the bin counts the column too (not the history columns, handled below)
+                v |= (below && !((nib >> e) & 1u)) ? 1ull << CNT_SHIFT : 0ull;
+                ntop += below ? 0u : 1u;
+              }
+              atomicAdd(&lh[below ? b : NBW], v);
             }
             if (W.min_p > 0.0f) {  // the tempered value is monotone in z: one division per group
               float zm = z[0];
@@ -554,7 +599,10 @@ __global__ __launch_bounds__(WT, 5) void wide_bins_kernel(const SampleArgs a) {
           __builtin_amdgcn_sched_barrier(0);  // one group at a time: interleaving them costs registers
         }
       };
-      if (W.tau == 1.0f) sweep(std::true_type{}); else sweep(std::false_type{});
+      const std::true_type yes{};
+      const std::false_type no{};
+      if (W.mode == WIDE_TOP_K) { if (W.tau == 1.0f) sweep(yes, yes); else sweep(no, yes); }
+      else { if (W.tau == 1.0f) sweep(yes, no); else sweep(no, no); }
     }
     if (W.h_active) {  // the history columns, whose logits and counts were requested before the main line
       hist_stage<DT>(Tb, HP, W.ws, a, rowp, c0, V);
@@ -774,9 +822,9 @@ __global__ __launch_bounds__(WT, 4) void wide_classify_kernel(const SampleArgs a
     const std::true_type yes{};
     const std::false_type no{};
     if (W.tau == 1.0f) {
-      if (W.mode == WIDE_TOP_P) sweep(yes, no, no); else if (W.mode == WIDE_ALL) sweep(yes, yes, yes); else sweep(yes, yes, no);
+      if (W.mode == WIDE_TOP_P || W.mode == WIDE_TOP_K) sweep(yes, no, no); else if (W.mode == WIDE_ALL) sweep(yes, yes, yes); else sweep(yes, yes, no);
     } else {
-      if (W.mode == WIDE_TOP_P) sweep(no, no, no); else if (W.mode == WIDE_ALL) sweep(no, yes, yes); else sweep(no, yes, no);
+      if (W.mode == WIDE_TOP_P || W.mode == WIDE_TOP_K) sweep(no, no, no); else if (W.mode == WIDE_ALL) sweep(no, yes, yes); else sweep(no, yes, no);
     }
     CACC(3);
     if (W.h_active) {  // the history columns, whose logits and counts were requested before the main line
@@ -835,22 +883,25 @@ __device__ inline bool finish_row(const SampleArgs& a, const WideRow& W, FS& S, 
   const float thr_y = rcut.thr_y;
   XPHASE(1);
   if (!rcut.valid) { XWHY(1, 0); return false; }
-  const bool top_p_route = W.mode == WIDE_TOP_P;
+  const bool top_p_route = W.mode == WIDE_TOP_P, top_k_route = W.mode == WIDE_TOP_K;
+  const bool cut_route = top_p_route || top_k_route;  // a cut inside a bin: by mass, or by count
   const u64 S_tot = top_p_route ? rcut.s_tot : S_sum;  // exact mass of the row (from the bins where there are bins)
   // a count past the limit is also how the classifying pass reports a row it could not handle; no
   // collected column on the top-p route means that a min-p cut ended the survivors above the bin
   const bool minp_too = top_p_route && W.min_p > 0.0f;
-  if (n_r > (unsigned)RCAP || (!top_p_route && n_r != 0u) || (top_p_route && n_r == 0u && !minp_too)) { XWHY(2, n_r); return false; }
+  if (n_r > (unsigned)RCAP || (!cut_route && n_r != 0u) || (cut_route && n_r == 0u && !minp_too)) { XWHY(2, n_r); return false; }
   if (tid == 0) { S.bd = -1; S.cut_k = 0ull; S.cut_p = ~0ull; S.out_id = -1; S.out_w = 0ull; }
   tiles[tid] = tv[0]; tiles[WT + tid] = tv[1];
   const u64 msure = tv[0] + tv[1];
   u64 cut_found = 0ull;  // every collected column at or after it in the order survives; 0: no collected columns
   unsigned r_in = 0;
-  if (top_p_route && n_r == 0u) cut_found = ~0ull;  // nothing of the bin survives
-  if (top_p_route && n_r != 0u) {
-  // exact masses from here: the columns surely inside must stay below the target, the collected bin must reach it
-  const u64 m_above = blk_sum_u64<WNW>(S, msure);  // barriers inside
-  const u64 target = (u64)__double2ull_ru((double)W.top_p * (double)S_tot);
+  if (cut_route && n_r == 0u) cut_found = ~0ull;  // nothing of the bin survives
+  if (cut_route && n_r != 0u) {
+  // exact masses (top-k: counts) from here: the columns surely inside must stay below the target, the
+  // collected bin must reach it
+  const u64 m_sure = blk_sum_u64<WNW>(S, msure);  // barriers inside
+  const u64 m_above = top_k_route ? (u64)n_sure : m_sure;
+  const u64 target = top_k_route ? (u64)W.top_k : (u64)__double2ull_ru((double)W.top_p * (double)S_tot);
   if (m_above >= target) { XWHY(3, 0); return false; }
   // -- the boundary bin, exactly: shortest prefix in the total order whose mass reaches the target --
   {
@@ -898,7 +949,7 @@ __device__ inline bool finish_row(const SampleArgs& a, const WideRow& W, FS& S, 
       __syncthreads();
       for (unsigned t = tid; t < n_r; t += WT) {
         const u64 c = rcmp[t];
-        if ((c & mask) == prefix) atomicAdd(&dmass[(unsigned)(c >> shift) & 0xFFu], (u64)rl[t]);
+        if ((c & mask) == prefix) atomicAdd(&dmass[(unsigned)(c >> shift) & 0xFFu], top_k_route ? 1ull : (u64)rl[t]);
       }
       __syncthreads();
       {  // thread i looks at digit 255 - i: the exclusive scan sums the digits above it
@@ -914,7 +965,7 @@ __device__ inline bool finish_row(const SampleArgs& a, const WideRow& W, FS& S, 
       prefix |= (u64)(unsigned)d << shift; mask |= 0xFFull << shift;
       __syncthreads();
     }
-    if (differ == 0ull && m_above + (u64)rl[0] < target) ok = false;  // a single column, and it does not reach the target
+    if (differ == 0ull && m_above + (top_k_route ? 1ull : (u64)rl[0]) < target) ok = false;  // a single column, and it does not reach the target
     // the collected columns do not reach the target: with a min-p cut those below it were never
     // collected, and the min-p prefix is the shorter one (all collected columns survive)
     if (!ok && !minp_too) { XWHY(4, 0); return false; }
@@ -930,10 +981,11 @@ __device__ inline bool finish_row(const SampleArgs& a, const WideRow& W, FS& S, 
       ++r_in;
     }
   }
-  }  // top-p route
+  }  // a cut inside a bin
   const u64 cut_c = cut_found;
   unsigned ns = r_in + (tid == 0 ? n_sure : 0u), dz = 0; u64 mx = 0ull, dsum = 0ull;
   blk_reduce<WNW>(S, ns, dz, mx, dsum);  // barriers inside: the tile masses are complete after it
+  if (top_k_route && ns != (unsigned)W.top_k) { XWHY(5, ns); return false; }  // the passes disagree
   // -- masses of the classes, acceptance (section 5.3), the tile that holds the draw --
   u64 p0 = 0ull, p1 = 0ull;
   for (int i = tid; i < 256; i += WT) { p0 += tiles[i]; p1 += tiles[256 + i]; }
@@ -950,7 +1002,7 @@ __device__ inline bool finish_row(const SampleArgs& a, const WideRow& W, FS& S, 
   const u64 S_cls = use_hot ? (pick_hot ? S1 : S0) : S_K;
   const double u = use_hot ? (pick_hot ? u3[0] : u3[2]) : u3[0];
   dg.n_survivors = (int)ns;
-  dg.s_k = (double)S_tot / (double)MSCALE * exp((double)C.y_g - (double)keyf(kmax));
+  dg.s_k = (double)(top_k_route ? S_K : S_tot) / (double)MSCALE * exp((double)C.y_g - (double)keyf(kmax));
   if (S_cls == 0ull) { XWHY(7, 0); return false; }
   u64 tfix = (u64)__double2ull_rd(u * (double)S_cls);
   if (tfix >= S_cls) tfix = S_cls - 1ull;

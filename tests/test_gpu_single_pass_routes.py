@@ -134,12 +134,13 @@ def test_rows_the_single_pass_kernel_must_leave_to_the_general_kernel():
     for ids, dg in _run(w, steps=(0, 1)):
         general = (dg["flags"] & GENERAL) > 0
         wide = (dg["flags"] & WIDE) > 0
-        # 3: top-k with penalties that raise logits; 4: top-k above the list's limit
-        assert general[[3, 4]].all()
-        # 0: a long history is corrected by claims, not left; 2, 5: no truncation at all and 6: no top-k
-        # with penalties that raise logits: straight to the whole-vocabulary kernels
+        # 3: top-k with penalties that raise logits
+        assert general[3]
+        # 0: a long history is corrected by claims, not left; 2, 5: no truncation at all, 4: top-k alone
+        # above the list's limit and 6: no top-k with penalties that raise logits: straight to the
+        # whole-vocabulary kernels
         assert not general[[0, 1, 2, 5, 7]].any() and wide[[2, 5]].all()
-        assert wide[6] or general[6]
+        assert (wide[[4, 6]] | general[[4, 6]]).all()
 
 
 def test_nucleus_rows_with_more_history_ids_than_registers_hold():
@@ -174,7 +175,7 @@ def test_one_context_alternating_routes_call_after_call():
     empty = (np.zeros(B + 1, np.int64), np.zeros(0, np.int32))
     wide = synth.Workload("a", B, V, "f32", z, synth.make_params(B, temperature=1.0, top_p=0.9), *empty)
     topk = synth.Workload("b", B, V, "f32", z, synth.make_params(B, temperature=0.8, top_k=20, top_p=0.9), *empty)
-    plain = synth.Workload("c", B, V, "f32", z, synth.make_params(B, temperature=1.0, top_k=2000), *empty)  # general kernel
+    plain = synth.Workload("c", B, V, "f32", z, synth.make_params(B, temperature=1.0, top_k=2000, top_p=0.95), *empty)  # general kernel
     s = binding.Sampler(V, 0)
     want = {}
     for step, w in enumerate([wide, topk, plain, wide, wide, plain, topk, topk, wide, plain, plain, wide]):
@@ -359,3 +360,27 @@ def test_history_denser_than_the_per_slice_stage():
     for ids, dg in _run(w, steps=(0, 1, 2)):
         f = dg["flags"]
         assert ((f & WIDE) > 0).all() and not ((f & GENERAL) > 0).any()
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_top_k_alone_beyond_the_list(dtype):
+    """top-k above 1024 without top-p or min-p: the sliced kernels find the k-th column by count (bins
+    that count their columns, then a radix descent by count inside the cut's bin; bf16 ties in
+    hundreds), with any penalties and history."""
+    rng = np.random.default_rng(36)
+    B, V = 12, 50_000 + 8
+    z = _flat_logits(rng, B, V, sigma=2.0)
+    lens = rng.integers(0, 2500, B)
+    hist_ptr, hist_ids = _head_history(z, lens, rng, head=4000)
+    ks = [1025, 1500, 2000, 3000, 5000, 8000, 1025, 2048, 4097, 12_000, 30_000, V - 1]
+    params = synth.make_params(B, temperature=[1.0, 0.7, 1.3] * 4, top_k=ks,
+                               rep_penalty=[1.0, 1.2, 0.9, 1.1] * 3, freq_penalty=[0.0, 0.2, -0.1] * 4,
+                               pres_penalty=[0.0, 0.1] * 6, n_prompt=[0, 300, 10_000] * 4)
+    logits = synth.f32_to_bf16_bits(z) if dtype == "bf16" else z
+    w = synth.Workload("big-k", B, V, dtype, logits, params, hist_ptr, hist_ids)
+    for ids, dg in _run(w, steps=(0, 1, 2)):
+        f = dg["flags"]
+        wide, general = (f & WIDE) > 0, (f & GENERAL) > 0
+        assert (wide | general).all()
+        assert wide[:9].all() and not general[:9].any()  # k up to 5000: always within the bins' reach
+        assert np.array_equal(dg["n_survivors"][wide], np.array(ks)[wide])
