@@ -114,6 +114,15 @@ __device__ __forceinline__ WideRow load_row(const SampleArgs& a, unsigned slot) 
   return W;
 }
 
+// threadIdx.x as a value the compiler cannot trace: what is derived from it below (table indices, LDS
+// addresses) is then formed where it is used instead of being kept across the kernels' item loops,
+// where a register too many is spilled and its reload waits behind every load in flight.
+__device__ __forceinline__ int fresh_tid() {
+  int t = threadIdx.x;
+  asm volatile("" : "+v"(t));
+  return t;
+}
+
 // A slice's part of the row's history tables, in LDS: the mask words of its columns, the
 // rank at the start of each of its word pairs (and of the next slice), and the counts of its
 // columns, indexed by rank minus the slice's first rank.
@@ -131,7 +140,7 @@ static_assert(SLC / 32 + SLC / 64 + 1 <= WT, "one mask word or directory entry p
 // with the other loads of an item.  First this thread's mask word or directory entry (the addresses
 // follow from the slot alone):
 __device__ __forceinline__ uint32_t slice_fetch(const unsigned char* ws, const SampleArgs& a, int c0) {
-  const int tid = threadIdx.x;
+  const int tid = fresh_tid();
   const unsigned char* ht = ws + WS_HT;
   const int n_pairs = (((a.V + 31) >> 5) + 1) >> 1;  // the mask is stored in whole pairs of words
   const int w0 = c0 >> 5, p0 = c0 >> 6;
@@ -145,7 +154,7 @@ __device__ __forceinline__ uint32_t slice_fetch(const unsigned char* ws, const S
 }
 // ... stored to LDS (past the directory's end stands the number of distinct columns); a barrier must follow.
 __device__ __forceinline__ void slice_store(SliceTabs& T, uint32_t v, const SampleArgs& a, int c0, uint32_t distinct) {
-  const int tid = threadIdx.x;
+  const int tid = fresh_tid();
   const int n_pairs = (((a.V + 31) >> 5) + 1) >> 1;
   if (tid < SLC / 32) T.bm[tid] = v;
   else if (tid < SLC / 32 + SLC / 64 + 1) {
@@ -187,7 +196,7 @@ struct HistPre { typename Io<DT>::Elem z[HPRE]; uint32_t cnt; };
 template <typename DT>
 __device__ __forceinline__ void hist_fetch(HistPre<DT>& P, const SliceTabs& T, const unsigned char* ws, const SampleArgs& a,
                                            const DT* rowp, int c0, int V) {
-  const int tid = threadIdx.x;
+  const int tid = fresh_tid();
   const uint16_t* gcnt = reinterpret_cast<const uint16_t*>(ws + WS_HT + a.F.cnt);
   const unsigned r0 = T.dir[0];
   const unsigned nc = min(T.dir[SLC / 64] - r0, (unsigned)SLC);
@@ -212,10 +221,7 @@ __device__ __forceinline__ void hist_fetch(HistPre<DT>& P, const SliceTabs& T, c
 template <typename DT>
 __device__ __forceinline__ void hist_stage(SliceTabs& T, const HistPre<DT>& P, const unsigned char* ws, const SampleArgs& a,
                                            const DT* rowp, int c0, int V) {
-  int tid = threadIdx.x;
-  // the addresses below are formed here, not kept in registers across the caller's loop (a register
-  // spilled there would be reloaded through memory, behind every load in flight)
-  asm volatile("" : "+v"(tid));
+  const int tid = fresh_tid();
   const uint16_t* gcnt = reinterpret_cast<const uint16_t*>(ws + WS_HT + a.F.cnt);
   const unsigned r0 = T.dir[0];
   const unsigned nc = min(T.dir[SLC / 64] - r0, (unsigned)SLC);
@@ -242,7 +248,7 @@ __device__ __forceinline__ void hist_stage(SliceTabs& T, const HistPre<DT>& P, c
 // thread, the rest (a slice with more than HCAP of them) by their mask word's thread.
 template <typename DT, typename F>
 __device__ __forceinline__ void hist_columns(const SliceTabs& T, const WideRow& W, const DT* rowp, int c0, int V, F&& f) {
-  const int tid = threadIdx.x;
+  const int tid = fresh_tid();
   const unsigned nc = min(T.dir[SLC / 64] - T.dir[0], (unsigned)SLC);
   for (unsigned j = tid; j < min(nc, (unsigned)HCAP); j += WT) {
     const int idx = c0 + (int)T.hcol[j];
@@ -792,21 +798,11 @@ __global__ __launch_bounds__(WT, 4) void wide_classify_kernel(const SampleArgs a
           if (use_hot) acc1 += parts_to_u64(hh, hl);
           if (ALL_SURE) { acc_all += parts_to_u64(sh, sl_); n_sure += (unsigned)EPL; }
           else if (WANT_ALL) acc_all += parts_to_u64(ah, al);
-          if (__ballot(any_edge)) {  // boundary columns of the whole group: one reservation per wave
-            u64 em[EPL];
-            unsigned pre[EPL], tot = 0u;
+          if (__ballot(any_edge)) {  // boundary columns: few per wave, element by element
 #pragma unroll
             for (int e = 0; e < EPL; ++e) {
-              em[e] = __ballot(((live >> e) & 1u) && z[e] >= zc.z_edge && !(z[e] >= zc.z_sure));
-              pre[e] = tot; tot += (unsigned)__popcll(em[e]);
-            }
-            unsigned base = 0u;  // the first active lane reserves (the ragged end of a row leaves lanes out)
-            if (lane == __ffsll((long long)__ballot(true)) - 1 && tot) base = atomicAdd(&l_n, tot);
-            base = uni(base);
-#pragma unroll
-            for (int e = 0; e < EPL; ++e) {
-              if ((em[e] >> lane) & 1ull) {
-                const unsigned s = base + pre[e] + lanes_before(em[e]);
+              if (((live >> e) & 1u) && z[e] >= zc.z_edge && !(z[e] >= zc.z_sure)) {
+                const unsigned s = atomicAdd(&l_n, 1u);
                 if (s < (unsigned)LCAP) lrl[s] = ((u64)__float_as_uint(z[e]) << 32) | (u64)(uint32_t)(idx0 + e);
               }
             }
