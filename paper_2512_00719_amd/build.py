@@ -22,6 +22,11 @@ HIPCC_FLAGS = [
 ]
 
 
+# The single-pass kernel reserves list slots with one LDS atomic issued by one lane of a wave; the
+# compiler's wave-level aggregation of atomics would wrap that single lane in a second reduction.
+PER_SOURCE_FLAGS = {"simple_fast.hip": ["-mllvm", "-amdgpu-atomic-optimizer-strategy=None"]}
+
+
 def build(verbose: bool = False, extra_flags: tuple = (), lib: str = LIB) -> str:
     hipcc = shutil.which("hipcc") or "/opt/rocm/bin/hipcc"
     os.makedirs(OBJ_DIR, exist_ok=True)
@@ -29,7 +34,7 @@ def build(verbose: bool = False, extra_flags: tuple = (), lib: str = LIB) -> str
 
     def compile_one(src: str) -> str:
         obj = os.path.join(OBJ_DIR, os.path.basename(src) + ".o")
-        cmd = [hipcc, *HIPCC_FLAGS, *extra_flags, *inc, "-c", src, "-o", obj]
+        cmd = [hipcc, *HIPCC_FLAGS, *PER_SOURCE_FLAGS.get(os.path.basename(src), []), *extra_flags, *inc, "-c", src, "-o", obj]
         if verbose:
             print(" ".join(cmd), flush=True)
         subprocess.run(cmd, check=True)

@@ -212,19 +212,20 @@ __device__ __forceinline__ void sample_group(const typename Io<DT>::Raw& A, int 
 }
 
 // Appends the flagged elements of one 16-byte group per lane with a single list reservation.
+// m[e]: the wave's ballot of "element e is at or above g".
 template <int EPL>
-__device__ __forceinline__ void append_group(FS& S, uint32_t* lz, uint32_t* li, unsigned cap, const float (&z)[EPL], float g, int idx0) {
+__device__ __forceinline__ void append_group(FS& S, uint32_t* lz, uint32_t* li, unsigned cap, const float (&z)[EPL], float g,
+                                             const u64 (&m)[EPL], int idx0) {
   const int lane = lane_id();
-  u64 m[EPL];
   unsigned pre[EPL], tot = 0;
 #pragma unroll
-  for (int e = 0; e < EPL; ++e) { m[e] = __ballot(!(z[e] < g)); pre[e] = tot; tot += (unsigned)__popcll(m[e]); }
+  for (int e = 0; e < EPL; ++e) { pre[e] = tot; tot += (unsigned)__popcll(m[e]); }
   unsigned base = 0;
   if (lane == 0) base = atomicAdd(&S.cand_count, tot);
   base = __builtin_amdgcn_readfirstlane(base);
 #pragma unroll
   for (int e = 0; e < EPL; ++e) {
-    if ((m[e] >> lane) & 1ull) {
+    if (!(z[e] < g)) {  // the lanes of m[e]
       const unsigned slot = base + pre[e] + lanes_before(m[e]);
       if (slot < cap) { lz[slot] = __float_as_uint(z[e]); li[slot] = (uint32_t)(idx0 + e); }
     }
@@ -248,10 +249,10 @@ __device__ __forceinline__ void stream_tile(const typename Io<DT>::Raw (&A)[UNR]
       for (int e = 0; e < EPL; ++e) grp += (z[e] < C.g) ? below_term(z[e], C) : 0u;
       below_mass += (u64)grp;
     }
-    bool any = false;
+    u64 m[EPL], any = 0ull;  // one compare per element, straight into the wave's mask; the rest is scalar
 #pragma unroll
-    for (int e = 0; e < EPL; ++e) any = any || !(z[e] < C.g);
-    if (__ballot(any)) append_group<EPL>(S, lz, li, cap, z, C.g, idx0);
+    for (int e = 0; e < EPL; ++e) { m[e] = __ballot(!(z[e] < C.g)); any |= m[e]; }
+    if (any) append_group<EPL>(S, lz, li, cap, z, C.g, m, idx0);
   }
 }
 
@@ -811,15 +812,34 @@ __global__ __launch_bounds__(NTHR, 4) void fast_rows_kernel(const SampleArgs a) 
 
   FPHASE(2);
   // ---- the stream (raw logits) ----
-  stream_tile<DT>(A, t0 * T, C, S, lz, li, cap, below_mass);
-  for (int cur = t0 + 1; cur < t1; ++cur) {
+  if constexpr (sizeof(DT) == 2) {
+    // two buffers in turn: A holds tile cur and Bf tile cur + 1; each is refilled (two tiles ahead) as
+    // soon as it has been consumed, so no registers are copied (bf16: 7 % faster on C5 than the
+    // rotation below, which in turn is 1.5 % faster for float32 on C3)
+    for (int cur = t0; cur < t1; cur += 2) {
+      stream_tile<DT>(A, cur * T, C, S, lz, li, cap, below_mass);
+      if (cur + 2 < t1) {
 #pragma unroll
-    for (int u = 0; u < UNR; ++u) A[u] = Bf[u];
-    if (cur + 1 < t1) {
+        for (int u = 0; u < UNR; ++u) A[u] = Io<DT>::load(rowp + (size_t)(cur + 2) * T + u * 64 * EPL + lane * EPL);
+      }
+      if (cur + 1 >= t1) break;
+      stream_tile<DT>(Bf, (cur + 1) * T, C, S, lz, li, cap, below_mass);
+      if (cur + 3 < t1) {
 #pragma unroll
-      for (int u = 0; u < UNR; ++u) Bf[u] = Io<DT>::load(rowp + (size_t)(cur + 1) * T + u * 64 * EPL + lane * EPL);
+        for (int u = 0; u < UNR; ++u) Bf[u] = Io<DT>::load(rowp + (size_t)(cur + 3) * T + u * 64 * EPL + lane * EPL);
+      }
     }
-    stream_tile<DT>(A, cur * T, C, S, lz, li, cap, below_mass);
+  } else {
+    stream_tile<DT>(A, t0 * T, C, S, lz, li, cap, below_mass);
+    for (int cur = t0 + 1; cur < t1; ++cur) {
+#pragma unroll
+      for (int u = 0; u < UNR; ++u) A[u] = Bf[u];
+      if (cur + 1 < t1) {
+#pragma unroll
+        for (int u = 0; u < UNR; ++u) Bf[u] = Io<DT>::load(rowp + (size_t)(cur + 1) * T + u * 64 * EPL + lane * EPL);
+      }
+      stream_tile<DT>(A, cur * T, C, S, lz, li, cap, below_mass);
+    }
   }
   FPHASE(3);
   // the epilogue rebuilds the history tables: fetch the ids while the other waves finish
