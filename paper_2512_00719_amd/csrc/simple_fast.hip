@@ -244,9 +244,9 @@ __device__ __forceinline__ void stream_tile(const typename Io<DT>::Raw (&A)[UNR]
     Io<DT>::unpack(A[u], z);
     const int idx0 = tb + u * 64 * EPL + lane * EPL;
     if (C.need_sum) {
-      uint32_t grp = 0u;  // straight-line: a column at or above g adds zero; <= 8 terms of <= 2^28
+      uint32_t grp = 0u;  // straight-line: a column at or above g adds 2^28 (taken off after the stream); <= 8 terms
 #pragma unroll
-      for (int e = 0; e < EPL; ++e) grp += (z[e] < C.g) ? below_term(z[e], C) : 0u;
+      for (int e = 0; e < EPL; ++e) grp += below_term_clamped(z[e], C);
       below_mass += (u64)grp;
     }
     u64 m[EPL], any = 0ull;  // one compare per element, straight into the wave's mask; the rest is scalar
@@ -849,7 +849,7 @@ __global__ __launch_bounds__(NTHR, 4) void fast_rows_kernel(const SampleArgs a) 
   // ragged tail, element by element
   for (int idx = nfull * T + tid; idx < V; idx += NTHR) {
     const float zz = Io<DT>::one(rowp + idx);
-    if (C.need_sum && zz < C.g) below_mass += (u64)below_term(zz, C);
+    if (C.need_sum) below_mass += (u64)below_term_clamped(zz, C);
     if (!(zz < C.g)) {
       const unsigned slot = atomicAdd(&S.cand_count, 1u);
       if (slot < cap) { lz[slot] = __float_as_uint(zz); li[slot] = (uint32_t)idx; }
@@ -865,6 +865,8 @@ __global__ __launch_bounds__(NTHR, 4) void fast_rows_kernel(const SampleArgs a) 
   if (a.hot_bits && a.hot_flags && *a.hot_flags) dg.flags |= SIMPLE_DIAG_BAD_HOT_SET;
   int rc = FIN_PENDING;
   const unsigned n = S.cand_count;
+  // the stream added 2^28 for every column at or above g: all of them were counted for the list
+  if (C.need_sum && tid == 0) below_mass -= (u64)n << 28;
   FWHY(2);
   if (n > cap && (R.need_sum || minp_only)) {
     // more columns at or above g than the list holds, and a cut that the whole-vocabulary routes

@@ -262,6 +262,11 @@ __device__ __forceinline__ u64 mass_fix_below(float w) { return (u64)(uint32_t)f
 __device__ __forceinline__ uint32_t below_term(float z, const StreamCtx& C) {
   return (uint32_t)__builtin_amdgcn_exp2f(fmaf(z - C.g, C.l2e_tau, 28.0f));
 }
+// The same for any column, without a test: a column at or above g (or a NaN) yields exactly 2^28, so
+// a sum over all columns exceeds the mass below g by 2^28 times the number of columns at or above g.
+__device__ __forceinline__ uint32_t below_term_clamped(float z, const StreamCtx& C) {
+  return (uint32_t)__builtin_amdgcn_exp2f(fminf(fmaf(z - C.g, C.l2e_tau, 28.0f), 28.0f));
+}
 
 }  // namespace fast
 }  // namespace simple
