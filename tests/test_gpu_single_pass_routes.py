@@ -384,3 +384,45 @@ def test_top_k_alone_beyond_the_list(dtype):
         assert (wide | general).all()
         assert wide[:9].all() and not general[:9].any()  # k up to 5000: always within the bins' reach
         assert np.array_equal(dg["n_survivors"][wide], np.array(ks)[wide])
+
+
+def test_whole_vocabulary_routes_at_extreme_temperatures_and_thresholds_near_zero():
+    """The classifying pass turns the cut into thresholds on the logit by a search over floats that
+    starts from a closed-form guess; small and large temperatures and a threshold near zero (where the
+    guess loses its digits) must give the same ids as the oracle."""
+    rng = np.random.default_rng(37)
+    V = 40_000 + 24
+    taus = [0.05, 0.2, 1.0, 5.0, 30.0, 0.05, 0.2, 1.0, 5.0, 30.0]
+    B = len(taus)
+    z = np.empty((B, V), np.float32)
+    for b, tau in enumerate(taus):
+        sigma = 1.3 * min(tau, 3.0)            # tempered spread about 1.3 (less for the largest tau): wide nuclei
+        shift = -2.9 * sigma if b >= 5 else 4.0 * sigma  # second half: the list's threshold lands near zero
+        z[b] = (rng.standard_normal(V) * sigma + shift).astype(np.float32)
+    lens = rng.integers(100, 900, B)
+    hist_ptr, hist_ids = _head_history(z, lens, rng, head=1500)
+    params = synth.make_params(B, temperature=taus, top_p=[0.9, 0.95, 0.8, 0.9, 0.99] * 2,
+                               min_p=[0, 0, 1e-4, 0, 0, 1e-5, 0, 0, 0, 1e-6],
+                               rep_penalty=1.1, freq_penalty=0.1)
+    w = synth.Workload("taus", B, V, "f32", z, params, hist_ptr, hist_ids)
+    for ids, dg in _run(w, steps=(0, 1, 2)):
+        f = dg["flags"]
+        assert ((f & WIDE) > 0).sum() >= 7 and not ((f & GENERAL) > 0).any()
+    # min-p alone (the cut is a tempered value) at the same temperatures
+    params2 = synth.make_params(B, temperature=taus, min_p=[1e-3, 1e-4, 1e-5, 1e-3, 1e-4] * 2, rep_penalty=1.1)
+    w2 = synth.Workload("taus-minp", B, V, "f32", z, params2, hist_ptr, hist_ids)
+    for ids, dg in _run(w2, steps=(0, 1)):
+        assert not ((dg["flags"] & GENERAL) > 0).any()
+
+
+def test_top_k_alone_beyond_the_list_with_a_hot_set():
+    rng = np.random.default_rng(38)
+    B, V = 8, 30_000
+    z = _flat_logits(rng, B, V, sigma=1.5)
+    hot = np.sort(rng.choice(V, 3000, replace=False)).astype(np.int32)
+    params = synth.make_params(B, temperature=[1.0, 0.8] * 4, top_k=[1500, 2500, 4000, 1025, 6000, 2000, 1200, 9000])
+    w = synth.Workload("big-k-hot", B, V, "f32", z, params, np.zeros(B + 1, np.int64), np.zeros(0, np.int32), hot_ids=hot)
+    for ids, dg in _run(w, steps=(0, 1, 2, 3)):
+        f = dg["flags"]
+        assert ((f & WIDE) > 0).all() and ((f & SHVS) > 0).all() and not ((f & GENERAL) > 0).any()
+        assert np.array_equal(dg["n_survivors"], params["top_k"])
