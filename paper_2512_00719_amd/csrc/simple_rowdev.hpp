@@ -82,6 +82,7 @@ struct FS {
   unsigned n2, nunc;           // certified / uncertified entries of the list
   unsigned e_n; int e_rc, e_acc;
   unsigned distinct;           // distinct history columns of the row
+  unsigned tile_ctr;           // next tile of the stream that no wave has taken yet
   u64 e_SK, e_SH, e_tfix, e_skfix;
   float wmax[16];
   unsigned wcnt[16];
