@@ -882,7 +882,9 @@ __device__ __noinline__ void wide_route(const RowReader<DT>& R, Shared& S, uint3
   const unsigned n = max(1u, min(n_k, min(n_m, n_p)));
   Cut cut;
   if (n == 1u && !(have_p && n_p == 1u) && !(S.k_on && n_k == 1u)) {
-    cut = Cut{maxkey, 0u, 0ull, 1u, 1u, 1ull << QBITS};  // the single best token: lowest id at the maximum
+    // the single best token: lowest id at the maximum; how many columns tie there is not known, so the
+    // count is set past any r and the walk below looks for the first of them
+    cut = Cut{maxkey, 0u, 0ull, 0xFFFFFFFFu, 1u, 1ull << QBITS};
   } else if (have_p && n == n_p) {
     cut = cp_;
   } else if (S.k_on && n == n_k) {

@@ -321,3 +321,19 @@ def test_boundary_argument_errors_and_empty_batch():
     with pytest.raises(binding.SimpleError) as e:
         binding.Sampler(4_000_000, 60_000)  # one row's state would not fit the LDS of a compute unit
     assert e.value.code == binding.SIMPLE_ECAPACITY
+
+
+def test_single_best_token_among_thousands_of_ties_in_the_general_kernel():
+    """top_p <= 0 keeps one token, the lowest id at the maximum.  With top-k above the candidate list's
+    reach the row takes the general kernel's multi-pass route, which must stop at the first of the
+    columns that tie at the maximum (it used to admit them all and then find no id)."""
+    rng = np.random.default_rng(41)
+    B, V = 4, 50_008
+    z = (rng.integers(-6, 3, (B, V)) * 0.75).astype(np.float32)   # nine distinct values, thousands of ties
+    params = synth.make_params(B, temperature=[1.0, 4.0, 0.5, 1.0], top_k=[1025, 3000, V - 1, 1025],
+                               top_p=[0.0, 0.0, -1.0, 0.0], min_p=[0.0, 0.01, 0.0, 0.0])
+    for dtype in ("f32", "bf16"):
+        logits = synth.f32_to_bf16_bits(z) if dtype == "bf16" else z
+        w = synth.Workload("one-of-many", B, V, dtype, logits, params, np.zeros(B + 1, np.int64), np.zeros(0, np.int32))
+        for ids, dg, _ in _check(w, steps=(0, 1)):
+            assert np.array_equal(ids, np.argmax(z, axis=1)) and (dg["n_survivors"] == 1).all()
