@@ -11,11 +11,15 @@ from paper_2512_00719_amd import synth
 pytestmark = pytest.mark.gpu
 
 
-def _random_workload(seed):
-    rng = np.random.default_rng(1000 + seed)
+def _random_workload(seed, large_batch=False):
+    rng = np.random.default_rng(1000 + seed + (5000 if large_batch else 0))
     dtype = "f32" if rng.random() < 0.5 else "bf16"
-    V = int(rng.choice([97, 1000, 4096, 8191, 20_000, 33_333, 50_008, 70_016]))
-    B = int(rng.integers(1, 40))
+    if large_batch:  # more rows than two per compute unit: the 256-thread form of the single-pass kernel
+        V = int(rng.choice([8191, 20_000, 33_336]))
+        B = int(rng.integers(300, 700))  # 257..512 rows: 512 threads per row; more: 256
+    else:
+        V = int(rng.choice([97, 1000, 4096, 8191, 20_000, 33_333, 50_008, 70_016]))
+        B = int(rng.integers(1, 40))
     kind = rng.integers(0, 4)
     if kind == 0:    # flat
         z = rng.standard_normal((B, V)) * rng.uniform(0.2, 2.0)
@@ -33,7 +37,7 @@ def _random_workload(seed):
     z = z.astype(np.float32)
     if rng.random() < 0.3:
         z[rng.integers(0, B), rng.choice(V, min(V, 50), replace=False)] = -np.inf  # masked tokens
-    lens = np.where(rng.random(B) < 0.25, 0, rng.integers(0, 3000, B))
+    lens = np.where(rng.random(B) < 0.25, 0, rng.integers(0, 800 if large_batch else 3000, B))
     if rng.random() < 0.5:
         lens[:] = 0
     head = np.argsort(-z, axis=1)[:, : max(1, min(V, 2000))]
@@ -67,3 +71,11 @@ def test_random_mix(seed):
     for step in (0, 1):
         ids, dg = P.run_gpu(w, step)
         P.compare(ids, dg, P.run_oracle(w, step), range(w.B))
+
+
+@pytest.mark.parametrize("seed", range(24))
+def test_random_mix_large_batch(seed):
+    w = _random_workload(seed, large_batch=True)
+    print(f"seed {seed}: B={w.B} V={w.V} {w.dtype} nnz={w.hist_ids.size} hot={None if w.hot_ids is None else w.hot_ids.size}", flush=True)
+    ids, dg = P.run_gpu(w, 0)
+    P.compare(ids, dg, P.run_oracle(w, 0), range(w.B))
