@@ -11,7 +11,7 @@ from paper_2512_00719_amd import synth
 pytestmark = pytest.mark.gpu
 
 
-def _random_workload(seed, large_batch=False):
+def _random_workload(seed, large_batch=False, with_errors=False):
     rng = np.random.default_rng(1000 + seed + (5000 if large_batch else 0))
     dtype = "f32" if rng.random() < 0.5 else "bf16"
     if large_batch:  # more rows than two per compute unit: the 256-thread form of the single-pass kernel
@@ -57,6 +57,19 @@ def _random_workload(seed, large_batch=False):
         freq_penalty=pick([0.0, 0.0, 0.2, 1.0, -0.3]),
         pres_penalty=pick([0.0, 0.0, 0.1, 0.8, -0.2]),
         n_prompt=pick([0, 0, 10, 500, 100_000]).astype(np.int32))
+    if with_errors:  # data and parameter errors: the row's id is -1, its neighbours are untouched
+        for b in rng.choice(B, max(1, B // 4), replace=False):
+            what = rng.integers(0, 5)
+            if what == 0:
+                z[b, rng.integers(0, V)] = np.nan
+            elif what == 1:
+                z[b, rng.integers(0, V)] = np.inf
+            elif what == 2:
+                z[b] = -np.inf
+            elif what == 3:
+                params["temperature"][b] = -0.5
+            else:
+                params["rep_penalty"][b] = rng.choice([0.0, -1.0])
     hot = None
     if rng.random() < 0.4:
         hot = np.sort(rng.choice(V, int(rng.integers(1, max(2, V // 3))), replace=False)).astype(np.int32)
@@ -79,3 +92,16 @@ def test_random_mix_large_batch(seed):
     print(f"seed {seed}: B={w.B} V={w.V} {w.dtype} nnz={w.hist_ids.size} hot={None if w.hot_ids is None else w.hot_ids.size}", flush=True)
     ids, dg = P.run_gpu(w, 0)
     P.compare(ids, dg, P.run_oracle(w, 0), range(w.B))
+
+
+@pytest.mark.parametrize("seed", range(40))
+def test_random_mix_with_error_rows(seed):
+    """NaN / +inf logits, all -inf rows, negative temperatures and non-positive repetition penalties in
+    a quarter of the rows: those rows return -1 with the error flag, the others their oracle ids."""
+    w = _random_workload(3000 + seed, with_errors=True)
+    print(f"seed {seed}: B={w.B} V={w.V} {w.dtype} nnz={w.hist_ids.size} hot={None if w.hot_ids is None else w.hot_ids.size}", flush=True)
+    ids, dg = P.run_gpu(w, 0)
+    want = P.run_oracle(w, 0)
+    P.compare(ids, dg, want, range(w.B))
+    err = np.array([o.id < 0 for o in want])
+    assert err.any() and np.array_equal((dg["flags"] & 1) > 0, err)
