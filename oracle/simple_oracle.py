@@ -353,6 +353,7 @@ class RowResult:
     accepted: Optional[bool]
     S_k: float
     dist: Optional[RowDist] = None
+    alt_p: tuple = ()  # p-tilde of ``id`` under the neighbouring nucleus lengths, when the boundary is ambiguous
 
 
 def _neighbours(d: RowDist, tok: int, hot_mask, accepted) -> set:
@@ -393,15 +394,19 @@ def sample_row(z_row: np.ndarray, par, hist_row, hot_mask: Optional[np.ndarray],
     if float(margin) < AMBIGUITY_WINDOW:
         ambiguous = True
         alt |= _neighbours(d, tok, hot_mask, accepted)
+    alt_p = []
     for d2 in d.alt:  # nucleus boundary within the window: the neighbouring prefix lengths
         ambiguous = True
         t2, _, a2 = draw(d2, u_draw, u_acc, u_tail, hot_mask)
         alt.add(int(t2))
         alt |= _neighbours(d2, int(t2), hot_mask, None if a2 is None else bool(a2))
+        j2 = int(np.searchsorted(d2.ids, tok))
+        if j2 < d2.ids.size and int(d2.ids[j2]) == tok:  # the same id, normalised over the other prefix
+            alt_p.append(float(d2.w[j2] / d2.S_K))
     alt.discard(tok)
     p_chosen = float(d.w[np.searchsorted(d.ids, tok)] / d.S_K)
     return RowResult(tok, alt, ambiguous, d.n, p_chosen, alpha, accepted, d.S_k,
-                     d if keep_dist else None)
+                     d if keep_dist else None, tuple(alt_p))
 
 
 def hot_mask_from_ids(hot_ids: Optional[Sequence[int]], V: int) -> Optional[np.ndarray]:
