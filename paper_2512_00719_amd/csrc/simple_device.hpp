@@ -149,7 +149,7 @@ struct History {
   __device__ __forceinline__ uint32_t count_at(int r) const { return (cnt[r >> 1] >> ((r & 1) * 16)) & 0xFFFFu; }
   // Z' for a column that is in the history: repetition (sign-aware), frequency, presence; each
   // operation rounded to float32 on its own (the file is built with FP contraction off).
-  __device__ __noinline__ float penalise(float z, int id) const {
+  __device__ __forceinline__ float penalise_inline(float z, int id) const {
     const uint32_t c = count_at(rank(id));
     z = (z > 0.0f) ? z / rep : z * rep;
     if (c > 0u) {
@@ -159,6 +159,8 @@ struct History {
     }
     return z;
   }
+  // The same as a call: for loops that keep no loads in flight across it.
+  __device__ __noinline__ float penalise(float z, int id) const { return penalise_inline(z, id); }
 };
 
 // Builds the history state of one row.  hist points at the row's ids (nnz of them, the first

@@ -23,8 +23,8 @@
 namespace simple {
 
 #ifdef SIMPLE_PHASE_TIMES  // profiling builds only: per-row phase timestamps (100 MHz wall clock)
-__device__ unsigned long long g_phase_times[8192 * 8];
-#define PHASE_MARK(i) do { if (threadIdx.x == 0 && blockIdx.x < 8192) g_phase_times[blockIdx.x * 8 + (i)] = wall_clock64(); } while (0)
+__device__ unsigned long long g_phase_times[8192 * 16];
+#define PHASE_MARK(i) do { if (threadIdx.x == 0 && blockIdx.x < 8192) g_phase_times[blockIdx.x * 16 + (i)] = wall_clock64(); } while (0)
 #else
 #define PHASE_MARK(i) do { } while (0)
 #endif
@@ -705,24 +705,125 @@ __device__ inline int sampled_route(const DT* __restrict__ rowp, int V, const Hi
 template <typename DT>
 struct RowReader {
   const DT* p; int V; float tau; bool greedy; const History* H;
-  __device__ __forceinline__ uint32_t ykey(int idx) const {  // 0 for a NaN / +inf element
-    float z = Elem<DT>::one(p + idx);
-    if (H->active && H->test(idx)) z = H->penalise(z, idx);
+  // Through a global-typed pointer: a generic load would also count as an LDS access, and every
+  // wait for an LDS result (the history mask) would then wait for the row loads in flight.
+  __device__ __forceinline__ float load(int idx) const {
+    typedef __attribute__((address_space(1))) const DT GlobDT;
+    const DT raw = *((GlobDT*)p + idx);
+    return Elem<DT>::one(&raw);
+  }
+  // Key of the tempered value z / tau; 0 for NaN / +inf.
+  __device__ __forceinline__ uint32_t key_plain(float z) const {
     if (z != z || z == INFINITY) return 0u;
     const float y = greedy ? z : z / tau;
     return (y == INFINITY) ? 0u : fkey(y);
   }
-};
-template <typename DT, class F>
-__device__ __forceinline__ void scan_row(const RowReader<DT>& R, F f) {
-  const int lane = lane_id();
-  for (int base = wave_id() * 512; base < R.V; base += NW * 512) {
+  // The same for column idx whose raw logit is z, after the penalties of a history column.  The
+  // penalty is inlined: a call would wait for every load the caller has in flight.
+  __device__ __forceinline__ uint32_t key_of(float z, int idx) const {
+    if (H->active && H->test(idx)) z = H->penalise_inline(z, idx);
+    return key_plain(z);
+  }
+  // Bit j set: column base + 64 j + lane is a history column (or lies beyond the row).
+  template <int N>
+  __device__ __forceinline__ uint32_t history_mask(int base, int lane) const {
+    uint32_t m = 0u;
+    if (H->active) {
 #pragma unroll
-    for (int j = 0; j < 8; ++j) {
-      const int idx = base + j * 64 + lane;
-      if (idx < R.V) f(R.ykey(idx), idx);
+      for (int j = 0; j < N; ++j) {
+        const int c = min(base + j * 64 + lane, V - 1);
+        m |= ((H->bits[c >> 5] >> (c & 31)) & 1u) << j;
+      }
+    }
+    return m;
+  }
+  // f(key, idx) for the history columns, one column per thread at a time.  A penalised column costs
+  // a rank (up to eight mask words), a count and a division; met inside the stream, one such column
+  // holds up the 64 lanes of its wave, and with a few thousand distinct ids most groups of 64
+  // columns hold one.
+  template <class F>
+  __device__ __forceinline__ void history_columns(F f) const {
+    if (!H->active) return;
+    for (int w = threadIdx.x; w < H->n_words; w += NT) {
+      uint32_t b = H->bits[w];
+      while (b) {
+        const int idx = (w << 5) + __builtin_ctz(b);
+        b &= b - 1u;
+        if (idx < V) f(key_plain(H->penalise_inline(load(idx), idx)), idx);
+      }
     }
   }
+  __device__ __forceinline__ uint32_t ykey(int idx) const { return key_of(load(idx), idx); }
+};
+// The reader reaches these functions by reference, that is through memory; every element would pay
+// for a chain of dependent loads (reader -> history -> mask word).  The routes below therefore work
+// on a copy whose fields are wave-uniform values held in scalar registers (every thread of the
+// workgroup serves the same row).
+template <class T> __device__ __forceinline__ T* uni_ptr(T* q) {
+  const unsigned long long v = (unsigned long long)q;
+  const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)v);
+  const uint32_t hi = __builtin_amdgcn_readfirstlane((uint32_t)(v >> 32));
+  return reinterpret_cast<T*>(((unsigned long long)hi << 32) | lo);
+}
+// For a pointer into the workgroup's LDS: the same, with the address space stated, so that accesses
+// through it are LDS instructions and wait on no global load in flight.
+template <class T> __device__ __forceinline__ T* uni_lds_ptr(T* q) {
+  T* const u = uni_ptr(q);
+#if defined(__HIP_DEVICE_COMPILE__)  // the builtin exists in the device pass only
+  __builtin_assume(__builtin_amdgcn_is_shared(u));
+#endif
+  return u;
+}
+__device__ __forceinline__ int uni(int x) { return __builtin_amdgcn_readfirstlane(x); }
+__device__ __forceinline__ float uni(float x) { return __int_as_float(__builtin_amdgcn_readfirstlane(__float_as_int(x))); }
+__device__ __forceinline__ History uniform_copy(const History& h) {
+  History o;
+  o.bits = uni_lds_ptr(h.bits); o.grp = uni_lds_ptr(h.grp); o.cnt = uni_lds_ptr(h.cnt);
+  o.n_words = uni(h.n_words); o.distinct = uni(h.distinct);
+  o.rep = uni(h.rep); o.freq = uni(h.freq); o.pres = uni(h.pres);
+  o.active = uni((int)h.active) != 0;
+  return o;
+}
+template <typename DT>
+__device__ __forceinline__ RowReader<DT> uniform_copy(const RowReader<DT>& r, const History* h) {
+  return RowReader<DT>{uni_ptr(r.p), uni(r.V), uni(r.tau), uni((int)r.greedy) != 0, h};
+}
+
+// f(key, idx) for every column of the row, in no particular order: the columns outside the history
+// from the stream, then the history columns.  Each lane keeps two groups of SCAN_U loads going: the
+// next group is requested before the current one is worked on.
+constexpr int SCAN_U = 8;
+template <typename DT, class F>
+__device__ __forceinline__ void scan_row(const RowReader<DT>& R, F f) {
+  const int lane = lane_id(), V = R.V;
+  constexpr int STEP = NW * 64 * SCAN_U;
+  float cur[SCAN_U], nxt[SCAN_U];
+  int base = wave_id() * 64 * SCAN_U;
+  if (base < V) {
+#pragma unroll
+    for (int j = 0; j < SCAN_U; ++j) {
+      const int idx = base + j * 64 + lane;
+      cur[j] = (idx < V) ? R.load(idx) : 0.0f;
+    }
+  }
+  for (; base < V; base += STEP) {
+    if (base + STEP < V) {
+#pragma unroll
+      for (int j = 0; j < SCAN_U; ++j) {
+        const int idx = base + STEP + j * 64 + lane;
+        nxt[j] = (idx < V) ? R.load(idx) : 0.0f;
+      }
+    }
+    const uint32_t hm = R.template history_mask<SCAN_U>(base, lane);
+#pragma unroll
+    for (int j = 0; j < SCAN_U; ++j) {
+      const int idx = base + j * 64 + lane;
+      if (idx < V && !((hm >> j) & 1u)) f(R.key_plain(cur[j]), idx);
+    }
+#pragma unroll
+    for (int j = 0; j < SCAN_U; ++j) cur[j] = nxt[j];
+  }
+  R.history_columns(f);
 }
 
 struct Cut {  // the prefix {key > t} plus the first r (by id) of {key == t}
@@ -739,10 +840,18 @@ __device__ __forceinline__ unsigned long long qmass(uint32_t key, float ymax) {
 // largest element.  by_mass = true: finds the key at which the running mass (largest first)
 // reaches T.  `lim` (optional) restricts the descent to the prefix described by another cut.
 template <typename DT>
-__device__ __noinline__ Cut descend(const RowReader<DT>& R, Shared& S, uint32_t* hcnt,
-                              unsigned long long* hmass, float ymax, bool by_mass,
-                              uint32_t need_cnt, double T, const Cut* lim) {
+__device__ __noinline__ Cut descend(const RowReader<DT>& R_in, Shared& S, uint32_t* hcnt_in,
+                              unsigned long long* hmass_in, float ymax_in, bool by_mass,
+                              uint32_t need_cnt, double T, const Cut* lim_in) {
   const int tid = threadIdx.x;
+  const History Hs = uniform_copy(*R_in.H);
+  const RowReader<DT> R = uniform_copy(R_in, &Hs);
+  uint32_t* const hcnt = uni_lds_ptr(hcnt_in);
+  unsigned long long* const hmass = uni_lds_ptr(hmass_in);
+  const float ymax = uni(ymax_in);
+  Cut lim_copy = {0u, 0u, 0ull, 0u, 0u, 0ull};
+  if (lim_in) lim_copy = *lim_in;
+  const Cut* const lim = lim_in ? &lim_copy : nullptr;
   uint32_t prefix = 0u, base_c = 0u;
   unsigned long long base_m = 0ull;
   uint32_t need = need_cnt;
@@ -809,10 +918,20 @@ __device__ __noinline__ Cut descend(const RowReader<DT>& R, Shared& S, uint32_t*
 
 // Exact route for any row: survivor set as a cut (t, r), then the inverse-CDF walk in ascending
 // id through per-chunk masses.  `lds` is the candidate-list region (32 KB), free on this route.
+// Bit idx of the hot-set mask (device memory), read through a global-typed pointer.
+__device__ __forceinline__ int hot_bit(const uint32_t* hot_bits, int idx) {
+  typedef __attribute__((address_space(1))) const uint32_t GlobU32;
+  return (int)((*((GlobU32*)hot_bits + (idx >> 5)) >> (idx & 31)) & 1u);
+}
+
 template <typename DT>
-__device__ __noinline__ void wide_route(const RowReader<DT>& R, Shared& S, uint32_t* hist, unsigned char* lds,
-                                  const Draws& U, const uint32_t* __restrict__ hot_bits,
+__device__ __noinline__ void wide_route(const RowReader<DT>& R_in, Shared& S, uint32_t* hist, unsigned char* lds_in,
+                                  const Draws& U, const uint32_t* __restrict__ hot_bits_in,
                                   simple_row_diag& dg) {
+  const History Hs = uniform_copy(*R_in.H);
+  const RowReader<DT> R = uniform_copy(R_in, &Hs);
+  unsigned char* const lds = uni_lds_ptr(lds_in);
+  const uint32_t* const hot_bits = uni_ptr(hot_bits_in);
   const int tid = threadIdx.x, lane = lane_id(), V = R.V;
   unsigned long long* hmass = reinterpret_cast<unsigned long long*>(lds);  // 16 KB
   // pass A: row maximum and validity
@@ -827,6 +946,7 @@ __device__ __noinline__ void wide_route(const RowReader<DT>& R, Shared& S, uint3
     __syncthreads();
   }
   const uint32_t maxkey = S.found_hi;
+  PHASE_MARK(8);
   if (S.flag_ws || maxkey <= KEY_NEG_INF) { if (tid == 0) S.flags |= SIMPLE_DIAG_ERROR | SIMPLE_DIAG_BAD_LOGIT; return; }
   const float ymax = keyf(maxkey);
   if (S.greedy) {  // lowest id attaining the maximum
@@ -849,11 +969,12 @@ __device__ __noinline__ void wide_route(const RowReader<DT>& R, Shared& S, uint3
   const unsigned n_m = block_sum(c_ge, S.scan_u32);
   const unsigned long long mass_m = block_sum(m_ge, S.scan_u64);
   const unsigned long long mass_all = block_sum(m_all, S.scan_u64);
+  PHASE_MARK(9);
   // top-k prefix
   Cut ck_;
   unsigned long long S_k;
   if (S.k_on) {
-    ck_ = descend(R, S, hist, hmass, ymax, false, (uint32_t)S.top_k, 0.0, nullptr);
+    ck_ = descend(R_in, S, hist, hmass, ymax, false, (uint32_t)S.top_k, 0.0, nullptr);
     if (S.flags & SIMPLE_DIAG_ERROR) return;
     ck_.r = (uint32_t)S.top_k - ck_.cnt_gt;
     S_k = ck_.mass_gt + (unsigned long long)ck_.r * ck_.q_t;
@@ -861,12 +982,13 @@ __device__ __noinline__ void wide_route(const RowReader<DT>& R, Shared& S, uint3
     S_k = mass_all;
   }
   const unsigned n_k = S.k_on ? (unsigned)S.top_k : (unsigned)V;
+  PHASE_MARK(10);
   // nucleus inside the top-k prefix
   Cut cp_; unsigned n_p = n_k;
   bool have_p = false;
   if (S.top_p < 1.0f && S.top_p > 0.0f) {
     const double T = (double)S.top_p * (double)S_k;
-    cp_ = descend(R, S, hist, hmass, ymax, true, 0u, T, S.k_on ? &ck_ : nullptr);
+    cp_ = descend(R_in, S, hist, hmass, ymax, true, 0u, T, S.k_on ? &ck_ : nullptr);
     if (S.flags & SIMPLE_DIAG_ERROR) return;
     // smallest r >= 1 with mass_gt + r * q_t >= T
     double rr = ceil((T - (double)cp_.mass_gt) / (double)cp_.q_t);
@@ -895,6 +1017,7 @@ __device__ __noinline__ void wide_route(const RowReader<DT>& R, Shared& S, uint3
   dg.n_survivors = (int)n;
   dg.s_k = (double)S_k * (1.0 / (double)(1ull << QBITS));
   __syncthreads();
+  PHASE_MARK(11);
   // pass F1: per-chunk survivor mass (class 0 = tail / everything, class 1 = hot) and tie counts
   const bool use_hot = hot_bits != nullptr;
   int J = 8;
@@ -904,13 +1027,23 @@ __device__ __noinline__ void wide_route(const RowReader<DT>& R, Shared& S, uint3
   unsigned* ct = reinterpret_cast<unsigned*>(lds + (size_t)16 * NC);   // [2][NC]
   for (int c = wave_id(); c < NC; c += NW) {
     unsigned long long m[2] = {0ull, 0ull}; unsigned t[2] = {0u, 0u};
-    for (int j = 0; j < J; ++j) {
-      const int idx = c * CH + j * 64 + lane;
-      if (idx < V) {
-        const uint32_t key = R.ykey(idx);
-        if (key >= cut.t && key) {
-          const int cls = use_hot ? ((hot_bits[idx >> 5] >> (idx & 31)) & 1u) : 0;
-          if (key > cut.t) m[cls] += qmass(key, ymax); else t[cls] += 1u;
+    for (int j0 = 0; j0 < J; j0 += 8) {  // J is a multiple of 8; the eight loads go out together
+      float z[8];
+#pragma unroll
+      for (int j = 0; j < 8; ++j) {
+        const int idx = c * CH + (j0 + j) * 64 + lane;
+        z[j] = (idx < V) ? R.load(idx) : 0.0f;
+      }
+      const uint32_t hm = R.template history_mask<8>(c * CH + j0 * 64, lane);
+#pragma unroll
+      for (int j = 0; j < 8; ++j) {
+        const int idx = c * CH + (j0 + j) * 64 + lane;
+        if (idx < V && !((hm >> j) & 1u)) {
+          const uint32_t key = R.key_plain(z[j]);
+          if (key >= cut.t && key) {
+            const int cls = use_hot ? hot_bit(hot_bits, idx) : 0;
+            if (key > cut.t) m[cls] += qmass(key, ymax); else t[cls] += 1u;
+          }
         }
       }
     }
@@ -919,6 +1052,14 @@ __device__ __noinline__ void wide_route(const RowReader<DT>& R, Shared& S, uint3
     if (lane == 0) { cm[c] = m[0]; cm[NC + c] = m[1]; ct[c] = t[0]; ct[NC + c] = t[1]; }
   }
   __syncthreads();
+  R.history_columns([&](uint32_t key, int idx) {  // the history columns join their chunks
+    if (key >= cut.t && key) {
+      const int cls = use_hot ? hot_bit(hot_bits, idx) : 0, c = idx / CH;
+      if (key > cut.t) atomicAdd(&cm[cls * NC + c], qmass(key, ymax)); else atomicAdd(&ct[cls * NC + c], 1u);
+    }
+  });
+  __syncthreads();
+  PHASE_MARK(12);
   // which chunk holds the r-th tie (ties are admitted in ascending id)
   if (tid == 0) {
     int tc = NC;  // all ties admitted
@@ -944,7 +1085,7 @@ __device__ __noinline__ void wide_route(const RowReader<DT>& R, Shared& S, uint3
       const unsigned long long mask = __ballot(tie);
       const unsigned rank = __popcll(mask & ((1ull << lane) - 1ull));
       if (tie && rank < left) {
-        const int cls = use_hot ? ((hot_bits[idx >> 5] >> (idx & 31)) & 1u) : 0;
+        const int cls = use_hot ? hot_bit(hot_bits, idx) : 0;
         a[cls] += 1u;
       }
       const unsigned here = __popcll(mask);
@@ -1007,7 +1148,7 @@ __device__ __noinline__ void wide_route(const RowReader<DT>& R, Shared& S, uint3
       const unsigned trank = ties_before + __popcll(tmask & ((1ull << lane) - 1ull));
       unsigned long long q = 0ull;
       if (key) {
-        const int c = use_hot ? ((hot_bits[idx >> 5] >> (idx & 31)) & 1u) : 0;
+        const int c = use_hot ? hot_bit(hot_bits, idx) : 0;
         if (c == cls) {
           if (key > cut.t) q = qmass(key, ymax);
           else if (tie && trank < cut.r) q = cut.q_t;
@@ -1222,7 +1363,7 @@ __global__ void hot_scatter_kernel(const int32_t* __restrict__ ids, int H, int V
 
 #ifdef SIMPLE_PHASE_TIMES
 extern "C" int simple_debug_phase_times(unsigned long long* dst_host, int n_rows) {
-  return (int)hipMemcpyFromSymbol(dst_host, HIP_SYMBOL(simple::g_phase_times), sizeof(unsigned long long) * 8 * (size_t)n_rows);
+  return (int)hipMemcpyFromSymbol(dst_host, HIP_SYMBOL(simple::g_phase_times), sizeof(unsigned long long) * 16 * (size_t)n_rows);
 }
 #endif
 
