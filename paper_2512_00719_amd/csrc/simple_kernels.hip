@@ -88,6 +88,7 @@ struct Shared {
   int walk_chunk, tie_chunk;
   unsigned long long walk_base;
   unsigned walk_ties_before, adm_split[2];
+  unsigned list_n;  // keys the descent has set aside for its last level
   int out_id;
   float out_p;
 };
@@ -737,21 +738,38 @@ struct RowReader {
     }
     return m;
   }
-  // f(key, idx) for the history columns, one column per thread at a time.  A penalised column costs
-  // a rank (up to eight mask words), a count and a division; met inside the stream, one such column
-  // holds up the 64 lanes of its wave, and with a few thousand distinct ids most groups of 64
-  // columns hold one.
-  template <class F>
-  __device__ __forceinline__ void history_columns(F f) const {
+  // g(z', idx) for the history columns, z' the penalised logit, one column per thread at a time.  A
+  // penalised column costs a rank (up to eight mask words), a count and a division; met inside the
+  // stream, one such column holds up the 64 lanes of its wave, and with a few thousand distinct ids
+  // most groups of 64 columns hold one.
+  template <class G>
+  __device__ __forceinline__ void history_columns_raw(G g) const {
     if (!H->active) return;
     for (int w = threadIdx.x; w < H->n_words; w += NT) {
       uint32_t b = H->bits[w];
       while (b) {
         const int idx = (w << 5) + __builtin_ctz(b);
         b &= b - 1u;
-        if (idx < V) f(key_plain(H->penalise_inline(load(idx), idx)), idx);
+        if (idx < V) g(H->penalise_inline(load(idx), idx), idx);
       }
     }
+  }
+  template <class F>
+  __device__ __forceinline__ void history_columns(F f) const {
+    history_columns_raw([&](float z, int idx) { f(key_plain(z), idx); });
+  }
+  // The smallest logit after penalties (as a key) whose tempered key is >= K, KEY_POS_INF if no finite
+  // one is: tempering is monotone, so {key >= K} is {z' >= keyf(result)} and a pass can sort columns
+  // by a float compare, dividing by tau only for those it keeps.  (A quotient that overflows counts
+  // as above K; rows that hold one never get this far.)
+  __device__ __noinline__ uint32_t z_lower_bound(uint32_t K) const {
+    uint32_t lo = KEY_NEG_INF, hi = KEY_POS_INF;
+    while (lo < hi) {
+      const uint32_t mid = lo + ((hi - lo) >> 1);
+      const uint32_t k = key_plain(keyf(mid));
+      if (k == 0u || k >= K) hi = mid; else lo = mid + 1u;
+    }
+    return lo;
   }
   __device__ __forceinline__ uint32_t ykey(int idx) const { return key_of(load(idx), idx); }
 };
@@ -775,6 +793,7 @@ template <class T> __device__ __forceinline__ T* uni_lds_ptr(T* q) {
   return u;
 }
 __device__ __forceinline__ int uni(int x) { return __builtin_amdgcn_readfirstlane(x); }
+__device__ __forceinline__ uint32_t uni(uint32_t x) { return (uint32_t)__builtin_amdgcn_readfirstlane((int)x); }
 __device__ __forceinline__ float uni(float x) { return __int_as_float(__builtin_amdgcn_readfirstlane(__float_as_int(x))); }
 __device__ __forceinline__ History uniform_copy(const History& h) {
   History o;
@@ -789,41 +808,53 @@ __device__ __forceinline__ RowReader<DT> uniform_copy(const RowReader<DT>& r, co
   return RowReader<DT>{uni_ptr(r.p), uni(r.V), uni(r.tau), uni((int)r.greedy) != 0, h};
 }
 
-// f(key, idx) for every column of the row, in no particular order: the columns outside the history
-// from the stream, then the history columns.  Each lane keeps two groups of SCAN_U loads going: the
-// next group is requested before the current one is worked on.
+// g(z', idx) for every column of the row, z' the logit after the penalties, in no particular order:
+// the columns outside the history from the stream, then the history columns.  Each lane keeps two
+// groups of SCAN_U loads going: the next group is requested before the current one is worked on.
+// A group that lies inside the row (all but the last) runs without per-column bounds checks.
 constexpr int SCAN_U = 8;
-template <typename DT, class F>
-__device__ __forceinline__ void scan_row(const RowReader<DT>& R, F f) {
+template <typename DT, class G>
+__device__ __forceinline__ void scan_row_raw(const RowReader<DT>& R, G g) {
   const int lane = lane_id(), V = R.V;
-  constexpr int STEP = NW * 64 * SCAN_U;
+  constexpr int GROUP = 64 * SCAN_U, STEP = NW * GROUP;
   float cur[SCAN_U], nxt[SCAN_U];
-  int base = wave_id() * 64 * SCAN_U;
-  if (base < V) {
+  auto fetch = [&](float (&z)[SCAN_U], int b) {
+    if (b + GROUP <= V) {
 #pragma unroll
-    for (int j = 0; j < SCAN_U; ++j) {
-      const int idx = base + j * 64 + lane;
-      cur[j] = (idx < V) ? R.load(idx) : 0.0f;
-    }
-  }
-  for (; base < V; base += STEP) {
-    if (base + STEP < V) {
+      for (int j = 0; j < SCAN_U; ++j) z[j] = R.load(b + j * 64 + lane);
+    } else {
 #pragma unroll
       for (int j = 0; j < SCAN_U; ++j) {
-        const int idx = base + STEP + j * 64 + lane;
-        nxt[j] = (idx < V) ? R.load(idx) : 0.0f;
+        const int idx = b + j * 64 + lane;
+        z[j] = (idx < V) ? R.load(idx) : 0.0f;
       }
     }
+  };
+  int base = uni(wave_id() * GROUP);
+  if (base < V) fetch(cur, base);
+  for (; base < V; base += STEP) {
+    if (base + STEP < V) fetch(nxt, base + STEP);
     const uint32_t hm = R.template history_mask<SCAN_U>(base, lane);
+    if (base + GROUP <= V) {
 #pragma unroll
-    for (int j = 0; j < SCAN_U; ++j) {
-      const int idx = base + j * 64 + lane;
-      if (idx < V && !((hm >> j) & 1u)) f(R.key_plain(cur[j]), idx);
+      for (int j = 0; j < SCAN_U; ++j)
+        if (!((hm >> j) & 1u)) g(cur[j], base + j * 64 + lane);
+    } else {
+#pragma unroll
+      for (int j = 0; j < SCAN_U; ++j) {
+        const int idx = base + j * 64 + lane;
+        if (idx < V && !((hm >> j) & 1u)) g(cur[j], idx);
+      }
     }
 #pragma unroll
     for (int j = 0; j < SCAN_U; ++j) cur[j] = nxt[j];
   }
-  R.history_columns(f);
+  R.history_columns_raw(g);
+}
+// f(key, idx) for every column, key that of the tempered value (0 for NaN / +inf).
+template <typename DT, class F>
+__device__ __forceinline__ void scan_row(const RowReader<DT>& R, F f) {
+  scan_row_raw(R, [&](float z, int idx) { f(R.key_plain(z), idx); });
 }
 
 struct Cut {  // the prefix {key > t} plus the first r (by id) of {key == t}
@@ -836,13 +867,20 @@ __device__ __forceinline__ unsigned long long qmass(uint32_t key, float ymax) {
 }
 
 // Radix descent over the 32-bit key of y (three levels: 11, 11, 10 bits) with exact integer
-// count and fixed-point mass histograms.  by_mass = false: finds the key of the need_cnt-th
-// largest element.  by_mass = true: finds the key at which the running mass (largest first)
-// reaches T.  `lim` (optional) restricts the descent to the prefix described by another cut.
-template <typename DT>
+// histograms.  BY_MASS = false: counts only; finds the key of the need_cnt-th largest element (the
+// cut's masses stay 0).  BY_MASS = true: fixed-point masses too; finds the key at which the running
+// mass (largest first) reaches top_p times the mass of everything the descent covers, and stores
+// that mass in *covered.  `lim` (optional) restricts the descent to the prefix described by
+// another cut.  When the bin chosen at the first level holds no more than LIST_CAP keys, the second
+// level's pass sets them aside in LDS (the 16 KB after the mass histogram) and the third level reads
+// them there instead of the row.
+constexpr unsigned LIST_CAP = 4096u;
+template <typename DT, bool BY_MASS>
 __device__ __noinline__ Cut descend(const RowReader<DT>& R_in, Shared& S, uint32_t* hcnt_in,
-                              unsigned long long* hmass_in, float ymax_in, bool by_mass,
-                              uint32_t need_cnt, double T, const Cut* lim_in) {
+                              unsigned long long* hmass_in, float ymax_in,
+                              uint32_t need_cnt, float top_p, unsigned long long* covered, const Cut* lim_in) {
+  constexpr bool by_mass = BY_MASS;
+  double T = 0.0;
   const int tid = threadIdx.x;
   const History Hs = uniform_copy(*R_in.H);
   const RowReader<DT> R = uniform_copy(R_in, &Hs);
@@ -850,41 +888,82 @@ __device__ __noinline__ Cut descend(const RowReader<DT>& R_in, Shared& S, uint32
   unsigned long long* const hmass = uni_lds_ptr(hmass_in);
   const float ymax = uni(ymax_in);
   Cut lim_copy = {0u, 0u, 0ull, 0u, 0u, 0ull};
-  if (lim_in) lim_copy = *lim_in;
+  if (lim_in) { lim_copy = *lim_in; lim_copy.t = uni(lim_copy.t); }
   const Cut* const lim = lim_in ? &lim_copy : nullptr;
+  uint32_t* const list = reinterpret_cast<uint32_t*>(hmass + NBINS);
+  typedef __attribute__((address_space(3))) unsigned LdsU32;
+  LdsU32* const list_n = (LdsU32*)&S.list_n;  // LDS-typed: the add must not count as a global access
   uint32_t prefix = 0u, base_c = 0u;
   unsigned long long base_m = 0ull;
   uint32_t need = need_cnt;
   const int widths[3] = {11, 11, 10};
   int shift = 32;
+  unsigned in_bin = 0xFFFFFFFFu;  // keys in the bin the level before chose
+  bool listed = false;
   for (int lvl = 0; lvl < 3; ++lvl) {
     const int w = widths[lvl];
     shift -= w;
-    for (int i = tid; i < NBINS; i += NT) { hcnt[i] = 0u; hmass[i] = 0ull; }
-    if (tid == 0) S.sel_found = 0u;
+    for (int i = tid; i < NBINS; i += NT) { hcnt[i] = 0u; if (by_mass) hmass[i] = 0ull; }
+    if (tid == 0) { S.sel_found = 0u; if (lvl == 1) S.list_n = 0u; }
     __syncthreads();
-    scan_row(R, [&](uint32_t key, int) {
-      if (!key) return;
-      if (lim && key < lim->t) return;
-      if (lvl > 0 && (key >> (shift + w)) != prefix) return;
+    auto tally = [&](uint32_t key) {
       const unsigned d = (key >> shift) & ((1u << w) - 1u);
       atomicAdd(&hcnt[d], 1u);
-      atomicAdd(&hmass[d], qmass(key, ymax));
-    });
+      if (by_mass) atomicAdd(&hmass[d], qmass(key, ymax));
+    };
+    if (listed) {  // third level, from the keys the second set aside (all of them inside the limit)
+      const unsigned n_list = S.list_n;
+      for (unsigned i = tid; i < n_list; i += NT) {
+        const uint32_t key = list[i];
+        if ((key >> (shift + w)) == prefix) tally(key);
+      }
+    } else {
+      const bool collect = (lvl == 1) && (in_bin <= LIST_CAP);
+      // the keys this level looks at, [prefix << (shift + w), (prefix + 1) << (shift + w)) and not
+      // below the limit, as a range of z'
+      float z_from = -INFINITY, z_below = INFINITY;
+      if (lvl > 0) {
+        const unsigned long long k_end = (unsigned long long)(prefix + 1u) << (shift + w);
+        z_from = uni(keyf(R.z_lower_bound(prefix << (shift + w))));
+        if (k_end <= 0xFFFFFFFFull) z_below = uni(keyf(R.z_lower_bound((uint32_t)k_end)));
+      }
+      if (lim) z_from = fmaxf(z_from, uni(keyf(R.z_lower_bound(lim->t))));
+      scan_row_raw(R, [&](float z, int) {
+        if (!(z >= z_from && z < z_below)) return;
+        const uint32_t key = R.key_plain(z);
+        if (!key) return;
+        tally(key);
+        if (collect) {  // (ties the limit leaves out are met here too, so the count can pass in_bin)
+          const unsigned slot = __hip_atomic_fetch_add(list_n, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+          if (slot < LIST_CAP) list[slot] = key;
+        }
+      });
+      __syncthreads();
+      listed = collect && (S.list_n <= LIST_CAP);
+    }
     __syncthreads();
+    if (lvl == 0) PHASE_MARK(13);
+    if (lvl == 1) PHASE_MARK(14);
     if (lim && tid == 0 && (lvl == 0 || (lim->t >> (shift + w)) == prefix)) {
       const unsigned d = (lim->t >> shift) & ((1u << w) - 1u);  // ties beyond the limit's r do not count
       hcnt[d] -= (lim->cnt_eq - lim->r);
-      hmass[d] -= (unsigned long long)(lim->cnt_eq - lim->r) * lim->q_t;
+      if (by_mass) hmass[d] -= (unsigned long long)(lim->cnt_eq - lim->r) * lim->q_t;
     }
     __syncthreads();
     unsigned lc[4], tc = 0;
     unsigned long long lm[4], tm = 0;
 #pragma unroll
-    for (int j = 0; j < 4; ++j) { lc[j] = hcnt[4 * tid + j]; lm[j] = hmass[4 * tid + j]; tc += lc[j]; tm += lm[j]; }
-    unsigned totc; unsigned long long totm;
+    for (int j = 0; j < 4; ++j) {
+      lc[j] = hcnt[4 * tid + j]; lm[j] = by_mass ? hmass[4 * tid + j] : 0ull;
+      tc += lc[j]; tm += lm[j];
+    }
+    unsigned totc; unsigned long long totm = 0ull;
     const unsigned ic = block_incl_scan(tc, S.scan_u32, totc);
-    const unsigned long long im = block_incl_scan(tm, S.scan_u64, totm);
+    const unsigned long long im = by_mass ? block_incl_scan(tm, S.scan_u64, totm) : 0ull;
+    if (by_mass && lvl == 0) {  // the first level's histogram holds everything the descent covers
+      T = (double)top_p * (double)totm;
+      if (covered) *covered = totm;
+    }
     unsigned above_c = totc - ic;
     unsigned long long above_m = totm - im;
 #pragma unroll
@@ -904,7 +983,8 @@ __device__ __noinline__ Cut descend(const RowReader<DT>& R_in, Shared& S, uint32
       Cut bad = {KEY_POS_INF, 0u, 0ull, 0u, 0u, 0ull};
       return bad;
     }
-    prefix = (prefix << w) | S.sel_digit;
+    prefix = (prefix << w) | uni((uint32_t)S.sel_digit);
+    in_bin = uni((uint32_t)S.sel_cnt);
     base_c += S.sel_above_cnt;
     base_m += S.sel_above_mass;
     if (!by_mass) need -= S.sel_above_cnt;
@@ -927,7 +1007,7 @@ __device__ __forceinline__ int hot_bit(const uint32_t* hot_bits, int idx) {
 template <typename DT>
 __device__ __noinline__ void wide_route(const RowReader<DT>& R_in, Shared& S, uint32_t* hist, unsigned char* lds_in,
                                   const Draws& U, const uint32_t* __restrict__ hot_bits_in,
-                                  simple_row_diag& dg) {
+                                  simple_row_diag& dg, const bool want_s_k) {
   const History Hs = uniform_copy(*R_in.H);
   const RowReader<DT> R = uniform_copy(R_in, &Hs);
   unsigned char* const lds = uni_lds_ptr(lds_in);
@@ -935,8 +1015,11 @@ __device__ __noinline__ void wide_route(const RowReader<DT>& R_in, Shared& S, ui
   const int tid = threadIdx.x, lane = lane_id(), V = R.V;
   unsigned long long* hmass = reinterpret_cast<unsigned long long*>(lds);  // 16 KB
   // pass A: row maximum and validity
-  uint32_t mk = 0u; unsigned bad = 0u;
-  scan_row(R, [&](uint32_t key, int) { if (!key) bad = 1u; mk = max(mk, key); });
+  // (tempering is monotone and rounds correctly, so the largest key is the key of the largest z')
+  float mz = -INFINITY; unsigned bad = 0u;
+  scan_row_raw(R, [&](float z, int) { if (z != z || z == INFINITY) bad = 1u; mz = fmaxf(mz, z); });
+  const uint32_t mk = R.key_plain(mz);
+  if (!mk) bad = 1u;  // z' / tau overflows
   {
     __syncthreads();
     if (tid == 0) { S.found_hi = 0u; S.flag_ws = 0u; }
@@ -945,10 +1028,10 @@ __device__ __noinline__ void wide_route(const RowReader<DT>& R_in, Shared& S, ui
     if (bad) atomicOr(&S.flag_ws, 1u);
     __syncthreads();
   }
-  const uint32_t maxkey = S.found_hi;
+  const uint32_t maxkey = uni((uint32_t)S.found_hi);
   PHASE_MARK(8);
   if (S.flag_ws || maxkey <= KEY_NEG_INF) { if (tid == 0) S.flags |= SIMPLE_DIAG_ERROR | SIMPLE_DIAG_BAD_LOGIT; return; }
-  const float ymax = keyf(maxkey);
+  const float ymax = uni(keyf(maxkey));
   if (S.greedy) {  // lowest id attaining the maximum
     if (tid == 0) S.found_lo = 0xFFFFFFFFu;
     __syncthreads();
@@ -958,38 +1041,33 @@ __device__ __noinline__ void wide_route(const RowReader<DT>& R_in, Shared& S, ui
     dg.n_survivors = 1;
     return;
   }
-  // pass D: total mass, and count / mass of the min-p prefix
-  const uint32_t thr_key = (S.min_p > 0.0f) ? fkey(ymax + (float)log((double)S.min_p)) : KEY_NEG_INF;
-  unsigned c_ge = 0; unsigned long long m_ge = 0ull, m_all = 0ull;
-  scan_row(R, [&](uint32_t key, int) {
-    const unsigned long long q = qmass(key, ymax);
-    m_all += q;
-    if (key >= thr_key) { ++c_ge; m_ge += q; }
-  });
-  const unsigned n_m = block_sum(c_ge, S.scan_u32);
-  const unsigned long long mass_m = block_sum(m_ge, S.scan_u64);
-  const unsigned long long mass_all = block_sum(m_all, S.scan_u64);
+  // pass D: size of the min-p prefix (every column is a valid key here, so without min-p it is V)
+  const uint32_t thr_key = uni((S.min_p > 0.0f) ? fkey(ymax + (float)log((double)S.min_p)) : KEY_NEG_INF);
+  unsigned n_m = (unsigned)V;
+  if (S.min_p > 0.0f) {
+    const float z_thr = uni(keyf(R.z_lower_bound(thr_key)));
+    unsigned c_ge = 0;
+    scan_row_raw(R, [&](float z, int) { if (z >= z_thr) ++c_ge; });
+    n_m = block_sum(c_ge, S.scan_u32);
+  }
   PHASE_MARK(9);
   // top-k prefix
   Cut ck_;
-  unsigned long long S_k;
   if (S.k_on) {
-    ck_ = descend(R_in, S, hist, hmass, ymax, false, (uint32_t)S.top_k, 0.0, nullptr);
+    ck_ = descend<DT, false>(R_in, S, hist, hmass, ymax, (uint32_t)S.top_k, 0.0f, nullptr, nullptr);
     if (S.flags & SIMPLE_DIAG_ERROR) return;
     ck_.r = (uint32_t)S.top_k - ck_.cnt_gt;
-    S_k = ck_.mass_gt + (unsigned long long)ck_.r * ck_.q_t;
-  } else {
-    S_k = mass_all;
   }
   const unsigned n_k = S.k_on ? (unsigned)S.top_k : (unsigned)V;
   PHASE_MARK(10);
-  // nucleus inside the top-k prefix
+  // nucleus inside the top-k prefix; the descent also measures S_k, the mass of that prefix
   Cut cp_; unsigned n_p = n_k;
   bool have_p = false;
+  unsigned long long S_k = 0ull;
   if (S.top_p < 1.0f && S.top_p > 0.0f) {
-    const double T = (double)S.top_p * (double)S_k;
-    cp_ = descend(R_in, S, hist, hmass, ymax, true, 0u, T, S.k_on ? &ck_ : nullptr);
+    cp_ = descend<DT, true>(R_in, S, hist, hmass, ymax, 0u, S.top_p, &S_k, S.k_on ? &ck_ : nullptr);
     if (S.flags & SIMPLE_DIAG_ERROR) return;
+    const double T = (double)S.top_p * (double)S_k;
     // smallest r >= 1 with mass_gt + r * q_t >= T
     double rr = ceil((T - (double)cp_.mass_gt) / (double)cp_.q_t);
     unsigned r = (rr < 1.0) ? 1u : (rr > (double)cp_.cnt_eq ? cp_.cnt_eq : (unsigned)rr);
@@ -998,8 +1076,19 @@ __device__ __noinline__ void wide_route(const RowReader<DT>& R_in, Shared& S, ui
     cp_.r = r;
     n_p = cp_.cnt_gt + r;
     have_p = true;
-  } else if (S.top_p <= 0.0f) {
-    n_p = 1u;
+  } else {
+    if (S.top_p <= 0.0f) n_p = 1u;
+    if (want_s_k) {  // reported only: the mass above the top-k cut plus its admitted ties, or of the whole row
+      const float z_k = uni(S.k_on ? keyf(R.z_lower_bound(ck_.t)) : -INFINITY);
+      const uint32_t t_k = uni(S.k_on ? ck_.t : 0u);
+      unsigned long long m_gt = 0ull;
+      scan_row_raw(R, [&](float z, int) {
+        if (!(z >= z_k)) return;
+        const uint32_t key = R.key_plain(z);
+        if (key > t_k) m_gt += qmass(key, ymax);
+      });
+      S_k = block_sum(m_gt, S.scan_u64) + (S.k_on ? (unsigned long long)ck_.r * ck_.q_t : 0ull);
+    }
   }
   const unsigned n = max(1u, min(n_k, min(n_m, n_p)));
   Cut cut;
@@ -1012,8 +1101,9 @@ __device__ __noinline__ void wide_route(const RowReader<DT>& R_in, Shared& S, ui
   } else if (S.k_on && n == n_k) {
     cut = ck_;
   } else {  // the min-p prefix {key >= thr_key}, or everything
-    cut = Cut{thr_key - 1u, n_m, mass_m, 0u, 0u, 0ull};
+    cut = Cut{thr_key - 1u, n_m, 0ull, 0u, 0u, 0ull};
   }
+  cut.t = uni(cut.t); cut.r = uni(cut.r); cut.cnt_eq = uni(cut.cnt_eq);
   dg.n_survivors = (int)n;
   dg.s_k = (double)S_k * (1.0 / (double)(1ull << QBITS));
   __syncthreads();
@@ -1025,6 +1115,7 @@ __device__ __noinline__ void wide_route(const RowReader<DT>& R_in, Shared& S, ui
   const int CH = 64 * J, NC = (V + CH - 1) / CH;
   unsigned long long* cm = reinterpret_cast<unsigned long long*>(lds);  // [2][NC]
   unsigned* ct = reinterpret_cast<unsigned*>(lds + (size_t)16 * NC);   // [2][NC]
+  const float z_cut = uni(keyf(R.z_lower_bound(cut.t)));  // {key >= cut.t} as a compare of z'
   for (int c = wave_id(); c < NC; c += NW) {
     unsigned long long m[2] = {0ull, 0ull}; unsigned t[2] = {0u, 0u};
     for (int j0 = 0; j0 < J; j0 += 8) {  // J is a multiple of 8; the eight loads go out together
@@ -1038,7 +1129,7 @@ __device__ __noinline__ void wide_route(const RowReader<DT>& R_in, Shared& S, ui
 #pragma unroll
       for (int j = 0; j < 8; ++j) {
         const int idx = c * CH + (j0 + j) * 64 + lane;
-        if (idx < V && !((hm >> j) & 1u)) {
+        if (idx < V && !((hm >> j) & 1u) && z[j] >= z_cut) {
           const uint32_t key = R.key_plain(z[j]);
           if (key >= cut.t && key) {
             const int cls = use_hot ? hot_bit(hot_bits, idx) : 0;
@@ -1307,7 +1398,7 @@ __device__ inline void sample_row_body(const SampleArgs& a, const int row, unsig
   if (!done) {
     dg.flags |= SIMPLE_DIAG_WIDE;
     RowReader<DT> R{rowp, V, S.tau, greedy, &H};
-    wide_route<DT>(R, S, hist, lds + a.L.cand, U, hot_bits, dg);
+    wide_route<DT>(R, S, hist, lds + a.L.cand, U, hot_bits, dg, a.diag != nullptr);
     __syncthreads();
   }
   if (tid == 0) {
@@ -1380,7 +1471,11 @@ static hipError_t launch_one(const SampleArgs& a, hipStream_t st) {
 template <typename DT, bool VEC>
 static hipError_t launch_pending(const SampleArgs& a, hipStream_t st) {
   auto k = pending_rows_kernel<DT, VEC>;
-  const unsigned grid = (unsigned)(a.B < 256 ? a.B : 256);
+  // As many workgroups as the device holds at once: two per compute unit by registers (128 each for
+  // 512 threads), one where the row state takes more than half of the 160 KB of LDS.
+  const unsigned per_cu = (2u * (a.L.total + 1024u) <= 160u * 1024u) ? 2u : 1u;
+  const unsigned resident = per_cu * (unsigned)(a.n_cu > 0 ? a.n_cu : 256);
+  const unsigned grid = (unsigned)a.B < resident ? (unsigned)a.B : resident;
   hipLaunchKernelGGL(k, dim3(grid), dim3(NT), a.L.total, st, a);
   return hipGetLastError();
 }
