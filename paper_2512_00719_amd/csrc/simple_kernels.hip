@@ -713,6 +713,22 @@ struct RowReader {
     const DT raw = *((GlobDT*)p + idx);
     return Elem<DT>::one(&raw);
   }
+  // Sixteen bytes from column idx on (a multiple of Elem<DT>::EPL, the row 16-byte aligned).
+  __device__ __forceinline__ u32x4 load16(int idx) const {
+    typedef __attribute__((address_space(1))) const DT GlobDT;
+    typedef __attribute__((address_space(1))) const u32x4 GlobVec;
+    return *(GlobVec*)((GlobDT*)p + idx);
+  }
+  static __device__ __forceinline__ void unpack(const u32x4& q, float (&z)[Elem<DT>::EPL]) {
+    const uint32_t w[4] = {q.x, q.y, q.z, q.w};
+    if constexpr (sizeof(DT) == 4) {
+#pragma unroll
+      for (int i = 0; i < 4; ++i) z[i] = __uint_as_float(w[i]);
+    } else {
+#pragma unroll
+      for (int i = 0; i < 4; ++i) { z[2 * i] = __uint_as_float(w[i] << 16); z[2 * i + 1] = __uint_as_float(w[i] & 0xFFFF0000u); }
+    }
+  }
   // Key of the tempered value z / tau; 0 for NaN / +inf.
   __device__ __forceinline__ uint32_t key_plain(float z) const {
     if (z != z || z == INFINITY) return 0u;
@@ -808,14 +824,73 @@ __device__ __forceinline__ RowReader<DT> uniform_copy(const RowReader<DT>& r, co
   return RowReader<DT>{uni_ptr(r.p), uni(r.V), uni(r.tau), uni((int)r.greedy) != 0, h};
 }
 
+// Stream of a 16-byte aligned row in groups of VGROUP columns, wave w taking groups w, w + NW, ...:
+// g(z, idx) for every column of the full groups that is outside the history, then after_group(grp)
+// with all lanes active.  A lane reads 16 bytes at a time and two groups are in flight per wave, in
+// two register sets that take turns (no copy between them, so nothing waits for the group just
+// requested).  The columns past the last full group are the caller's.
+constexpr int VGROUP = 1024;
+template <typename DT, class G, class AG>
+__device__ __forceinline__ void scan_groups_vec(const RowReader<DT>& R, G g, AG after_group) {
+  constexpr int EPL = Elem<DT>::EPL, NV = VGROUP / (64 * EPL);
+  const int lane = lane_id();
+  const int n_full = R.V / VGROUP;
+  const History& H = *R.H;
+  u32x4 qa[NV], qb[NV];
+  auto fetch = [&](u32x4 (&q)[NV], int grp) {
+#pragma unroll
+    for (int j = 0; j < NV; ++j) q[j] = R.load16(grp * VGROUP + (j * 64 + lane) * EPL);
+  };
+  auto work = [&](const u32x4 (&q)[NV], int grp) {
+    uint32_t hm[NV];  // history bits of the lane's columns (EPL consecutive columns share a mask word)
+#pragma unroll
+    for (int j = 0; j < NV; ++j) {
+      const int idx0 = grp * VGROUP + (j * 64 + lane) * EPL;
+      hm[j] = H.active ? (H.bits[idx0 >> 5] >> (idx0 & 31)) : 0u;
+    }
+#pragma unroll
+    for (int j = 0; j < NV; ++j) {
+      const int idx0 = grp * VGROUP + (j * 64 + lane) * EPL;
+      float z[EPL];
+      RowReader<DT>::unpack(q[j], z);
+#pragma unroll
+      for (int e = 0; e < EPL; ++e)
+        if (!((hm[j] >> e) & 1u)) g(z[e], idx0 + e);
+    }
+    after_group(grp);
+  };
+  int grp = uni(wave_id());
+  if (grp >= n_full) return;
+  fetch(qa, grp);
+  for (;;) {
+    const bool more_b = grp + NW < n_full;
+    if (more_b) fetch(qb, grp + NW);
+    work(qa, grp);
+    if (!more_b) break;
+    grp += NW;
+    const bool more_a = grp + NW < n_full;
+    if (more_a) fetch(qa, grp + NW);
+    work(qb, grp);
+    if (!more_a) break;
+    grp += NW;
+  }
+}
+
 // g(z', idx) for every column of the row, z' the logit after the penalties, in no particular order:
 // the columns outside the history from the stream, then the history columns.  Each lane keeps two
 // groups of SCAN_U loads going: the next group is requested before the current one is worked on.
 // A group that lies inside the row (all but the last) runs without per-column bounds checks.
 constexpr int SCAN_U = 8;
-template <typename DT, class G>
+template <typename DT, bool VEC, class G>
 __device__ __forceinline__ void scan_row_raw(const RowReader<DT>& R, G g) {
   const int lane = lane_id(), V = R.V;
+  if constexpr (VEC) {  // aligned rows: 16-byte loads; the columns past the last full group one per thread
+    scan_groups_vec(R, g, [](int) {});
+    for (int idx = (V / VGROUP) * VGROUP + (int)threadIdx.x; idx < V; idx += NT)
+      if (!(R.H->active && R.H->test(idx))) g(R.load(idx), idx);
+    R.history_columns_raw(g);
+    return;
+  }
   constexpr int GROUP = 64 * SCAN_U, STEP = NW * GROUP;
   float cur[SCAN_U], nxt[SCAN_U];
   auto fetch = [&](float (&z)[SCAN_U], int b) {
@@ -852,18 +927,39 @@ __device__ __forceinline__ void scan_row_raw(const RowReader<DT>& R, G g) {
   R.history_columns_raw(g);
 }
 // f(key, idx) for every column, key that of the tempered value (0 for NaN / +inf).
-template <typename DT, class F>
+template <typename DT, bool VEC, class F>
 __device__ __forceinline__ void scan_row(const RowReader<DT>& R, F f) {
-  scan_row_raw(R, [&](float z, int idx) { f(R.key_plain(z), idx); });
+  scan_row_raw<DT, VEC>(R, [&](float z, int idx) { f(R.key_plain(z), idx); });
 }
 
 struct Cut {  // the prefix {key > t} plus the first r (by id) of {key == t}
   uint32_t t; uint32_t cnt_gt; unsigned long long mass_gt; uint32_t cnt_eq; uint32_t r; unsigned long long q_t;
 };
 
+// Fixed-point mass of a column, the nearest integer to exp(y - ymax) * 2^QBITS, as a function of the
+// key alone (every pass must give a column the same mass).  The exponential is 2^n * 2^f with
+// n = rint(x log2 e) and a degree-10 polynomial for 2^f on [-1/2, 1/2]: relative error below 1e-12,
+// five orders under the tolerance on probabilities, at a quarter of the library routine's
+// double-precision instructions.  Below x = -44 the mass rounds to zero.
 __device__ __forceinline__ unsigned long long qmass(uint32_t key, float ymax) {
-  const double w = exp((double)keyf(key) - (double)ymax);
-  return (unsigned long long)__double2ull_rn(w * (double)(1ull << QBITS));
+  const double x = (double)keyf(key) - (double)ymax;
+  if (!(x >= -44.0)) return 0ull;
+  const double t = x * 1.4426950408889634;
+  const double n = rint(t), f = t - n;
+  double p = 7.054911620801121e-09;
+  p = fma(p, f, 1.0178086009239696e-07);
+  p = fma(p, f, 1.3215486790144305e-06);
+  p = fma(p, f, 1.5252733804059838e-05);
+  p = fma(p, f, 0.00015403530393381606);
+  p = fma(p, f, 0.0013333558146428441);
+  p = fma(p, f, 0.009618129107628477);
+  p = fma(p, f, 0.055504108664821576);
+  p = fma(p, f, 0.2402265069591007);
+  p = fma(p, f, 0.6931471805599453);
+  p = fma(p, f, 1.0);
+  const double v = rint(ldexp(p, (int)n + QBITS));  // an integer below 2^(QBITS + 1) for x <= 0
+  const double h = floor(v * 0x1p-32);
+  return ((unsigned long long)(uint32_t)h << 32) | (unsigned long long)(uint32_t)(v - h * 0x1p32);
 }
 
 // Radix descent over the 32-bit key of y (three levels: 11, 11, 10 bits) with exact integer
@@ -875,7 +971,7 @@ __device__ __forceinline__ unsigned long long qmass(uint32_t key, float ymax) {
 // level's pass sets them aside in LDS (the 16 KB after the mass histogram) and the third level reads
 // them there instead of the row.
 constexpr unsigned LIST_CAP = 4096u;
-template <typename DT, bool BY_MASS>
+template <typename DT, bool VEC, bool BY_MASS>
 __device__ __noinline__ Cut descend(const RowReader<DT>& R_in, Shared& S, uint32_t* hcnt_in,
                               unsigned long long* hmass_in, float ymax_in,
                               uint32_t need_cnt, float top_p, unsigned long long* covered, const Cut* lim_in) {
@@ -928,7 +1024,7 @@ __device__ __noinline__ Cut descend(const RowReader<DT>& R_in, Shared& S, uint32
         if (k_end <= 0xFFFFFFFFull) z_below = uni(keyf(R.z_lower_bound((uint32_t)k_end)));
       }
       if (lim) z_from = fmaxf(z_from, uni(keyf(R.z_lower_bound(lim->t))));
-      scan_row_raw(R, [&](float z, int) {
+      scan_row_raw<DT, VEC>(R, [&](float z, int) {
         if (!(z >= z_from && z < z_below)) return;
         const uint32_t key = R.key_plain(z);
         if (!key) return;
@@ -1004,7 +1100,7 @@ __device__ __forceinline__ int hot_bit(const uint32_t* hot_bits, int idx) {
   return (int)((*((GlobU32*)hot_bits + (idx >> 5)) >> (idx & 31)) & 1u);
 }
 
-template <typename DT>
+template <typename DT, bool VEC>
 __device__ __noinline__ void wide_route(const RowReader<DT>& R_in, Shared& S, uint32_t* hist, unsigned char* lds_in,
                                   const Draws& U, const uint32_t* __restrict__ hot_bits_in,
                                   simple_row_diag& dg, const bool want_s_k) {
@@ -1017,7 +1113,7 @@ __device__ __noinline__ void wide_route(const RowReader<DT>& R_in, Shared& S, ui
   // pass A: row maximum and validity
   // (tempering is monotone and rounds correctly, so the largest key is the key of the largest z')
   float mz = -INFINITY; unsigned bad = 0u;
-  scan_row_raw(R, [&](float z, int) { if (z != z || z == INFINITY) bad = 1u; mz = fmaxf(mz, z); });
+  scan_row_raw<DT, VEC>(R, [&](float z, int) { if (z != z || z == INFINITY) bad = 1u; mz = fmaxf(mz, z); });
   const uint32_t mk = R.key_plain(mz);
   if (!mk) bad = 1u;  // z' / tau overflows
   {
@@ -1035,7 +1131,7 @@ __device__ __noinline__ void wide_route(const RowReader<DT>& R_in, Shared& S, ui
   if (S.greedy) {  // lowest id attaining the maximum
     if (tid == 0) S.found_lo = 0xFFFFFFFFu;
     __syncthreads();
-    scan_row(R, [&](uint32_t key, int idx) { if (key == maxkey) atomicMin(&S.found_lo, (unsigned)idx); });
+    scan_row<DT, VEC>(R, [&](uint32_t key, int idx) { if (key == maxkey) atomicMin(&S.found_lo, (unsigned)idx); });
     __syncthreads();
     if (tid == 0) { S.out_id = (int)S.found_lo; S.out_p = 1.0f; }
     dg.n_survivors = 1;
@@ -1047,14 +1143,14 @@ __device__ __noinline__ void wide_route(const RowReader<DT>& R_in, Shared& S, ui
   if (S.min_p > 0.0f) {
     const float z_thr = uni(keyf(R.z_lower_bound(thr_key)));
     unsigned c_ge = 0;
-    scan_row_raw(R, [&](float z, int) { if (z >= z_thr) ++c_ge; });
+    scan_row_raw<DT, VEC>(R, [&](float z, int) { if (z >= z_thr) ++c_ge; });
     n_m = block_sum(c_ge, S.scan_u32);
   }
   PHASE_MARK(9);
   // top-k prefix
   Cut ck_;
   if (S.k_on) {
-    ck_ = descend<DT, false>(R_in, S, hist, hmass, ymax, (uint32_t)S.top_k, 0.0f, nullptr, nullptr);
+    ck_ = descend<DT, VEC, false>(R_in, S, hist, hmass, ymax, (uint32_t)S.top_k, 0.0f, nullptr, nullptr);
     if (S.flags & SIMPLE_DIAG_ERROR) return;
     ck_.r = (uint32_t)S.top_k - ck_.cnt_gt;
   }
@@ -1065,7 +1161,7 @@ __device__ __noinline__ void wide_route(const RowReader<DT>& R_in, Shared& S, ui
   bool have_p = false;
   unsigned long long S_k = 0ull;
   if (S.top_p < 1.0f && S.top_p > 0.0f) {
-    cp_ = descend<DT, true>(R_in, S, hist, hmass, ymax, 0u, S.top_p, &S_k, S.k_on ? &ck_ : nullptr);
+    cp_ = descend<DT, VEC, true>(R_in, S, hist, hmass, ymax, 0u, S.top_p, &S_k, S.k_on ? &ck_ : nullptr);
     if (S.flags & SIMPLE_DIAG_ERROR) return;
     const double T = (double)S.top_p * (double)S_k;
     // smallest r >= 1 with mass_gt + r * q_t >= T
@@ -1082,7 +1178,7 @@ __device__ __noinline__ void wide_route(const RowReader<DT>& R_in, Shared& S, ui
       const float z_k = uni(S.k_on ? keyf(R.z_lower_bound(ck_.t)) : -INFINITY);
       const uint32_t t_k = uni(S.k_on ? ck_.t : 0u);
       unsigned long long m_gt = 0ull;
-      scan_row_raw(R, [&](float z, int) {
+      scan_row_raw<DT, VEC>(R, [&](float z, int) {
         if (!(z >= z_k)) return;
         const uint32_t key = R.key_plain(z);
         if (key > t_k) m_gt += qmass(key, ymax);
@@ -1110,12 +1206,37 @@ __device__ __noinline__ void wide_route(const RowReader<DT>& R_in, Shared& S, ui
   PHASE_MARK(11);
   // pass F1: per-chunk survivor mass (class 0 = tail / everything, class 1 = hot) and tie counts
   const bool use_hot = hot_bits != nullptr;
-  int J = 8;
+  // (an aligned row of up to 2^20 columns: a chunk is one group of the vector stream)
+  const bool by_groups = VEC && V <= VGROUP * 1024;
+  int J = by_groups ? VGROUP / 64 : 8;
   while ((long long)64 * J * 1024 < (long long)V) J <<= 1;
   const int CH = 64 * J, NC = (V + CH - 1) / CH;
   unsigned long long* cm = reinterpret_cast<unsigned long long*>(lds);  // [2][NC]
   unsigned* ct = reinterpret_cast<unsigned*>(lds + (size_t)16 * NC);   // [2][NC]
   const float z_cut = uni(keyf(R.z_lower_bound(cut.t)));  // {key >= cut.t} as a compare of z'
+  if (by_groups) {
+    unsigned long long m[2] = {0ull, 0ull}; unsigned t[2] = {0u, 0u};
+    auto column = [&](float z, int idx) {
+      if (!(z >= z_cut)) return;
+      const uint32_t key = R.key_plain(z);
+      if (key >= cut.t && key) {
+        const int cls = use_hot ? hot_bit(hot_bits, idx) : 0;
+        if (key > cut.t) m[cls] += qmass(key, ymax); else t[cls] += 1u;
+      }
+    };
+    auto chunk_done = [&](int c) {
+#pragma unroll
+      for (int x = 0; x < 2; ++x) { m[x] = wave_sum(m[x]); t[x] = wave_sum(t[x]); }
+      if (lane == 0) { cm[c] = m[0]; cm[NC + c] = m[1]; ct[c] = t[0]; ct[NC + c] = t[1]; }
+      m[0] = m[1] = 0ull; t[0] = t[1] = 0u;
+    };
+    scan_groups_vec(R, column, chunk_done);
+    if (V % VGROUP != 0 && wave_id() == 0) {  // the columns past the last full group: the last chunk
+      for (int idx = (V / VGROUP) * VGROUP + lane; idx < V; idx += 64)
+        if (!(R.H->active && R.H->test(idx))) column(R.load(idx), idx);
+      chunk_done(NC - 1);
+    }
+  } else
   for (int c = wave_id(); c < NC; c += NW) {
     unsigned long long m[2] = {0ull, 0ull}; unsigned t[2] = {0u, 0u};
     for (int j0 = 0; j0 < J; j0 += 8) {  // J is a multiple of 8; the eight loads go out together
@@ -1398,7 +1519,7 @@ __device__ inline void sample_row_body(const SampleArgs& a, const int row, unsig
   if (!done) {
     dg.flags |= SIMPLE_DIAG_WIDE;
     RowReader<DT> R{rowp, V, S.tau, greedy, &H};
-    wide_route<DT>(R, S, hist, lds + a.L.cand, U, hot_bits, dg, a.diag != nullptr);
+    wide_route<DT, VEC>(R, S, hist, lds + a.L.cand, U, hot_bits, dg, a.diag != nullptr);
     __syncthreads();
   }
   if (tid == 0) {
