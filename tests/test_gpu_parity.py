@@ -337,3 +337,33 @@ def test_single_best_token_among_thousands_of_ties_in_the_general_kernel():
         w = synth.Workload("one-of-many", B, V, dtype, logits, params, np.zeros(B + 1, np.int64), np.zeros(0, np.int32))
         for ids, dg, _ in _check(w, steps=(0, 1)):
             assert np.array_equal(ids, np.argmax(z, axis=1)) and (dg["n_survivors"] == 1).all()
+
+
+@pytest.mark.parametrize("V,dtype", [(1 << 18, "f32"), ((1 << 18) + 1000, "bf16"), (300_001, "f32"), ((1 << 18) + 8, "bf16")])
+def test_vocabularies_of_two_to_the_eighteen_columns_and_more(V, dtype):
+    """From 2^18 columns on the general kernel serves the whole batch (the single-pass kernel's fixed
+    point is sized for fewer); whole-vocabulary nuclei, large top-k and min-p rows take its multi-pass
+    route: aligned rows in 16-byte loads (a row length that is and is not a multiple of the stream's
+    group of 1024 columns), the odd float32 length element by element."""
+    rng = np.random.default_rng(V % 1000 + 11)
+    B = 12
+    z = synth.zipf_profile_logits(B, V, 1.1, 1.5, rng, "f32", rng.permutation(V))
+    z[3, rng.choice(V, 5000, replace=False)] = z[3].max()          # a plateau at the maximum
+    z[5] = np.round(z[5] * 2) / 2                                   # few distinct values: ties at every cut
+    lens = np.array([0, 700, 3000, 50, 0, 1500, 200, 0, 4000, 10, 900, 0])
+    head = np.argsort(-z, axis=1)[:, :3000]
+    hist_ptr = np.concatenate([[0], np.cumsum(lens)]).astype(np.int64)
+    hist_ids = np.concatenate([rng.choice(head[b], int(lens[b])) for b in range(B)]).astype(np.int32)
+    params = synth.make_params(
+        B, temperature=[1.0, 0.8, 1.2, 1.0, 0.0, 0.7, 1.0, 1.5, 0.9, 1.0, 0.6, 1.0],
+        top_k=[0, 3000, 0, 0, 0, 20_000, V - 1, 0, 1500, 0, 50, 0],
+        top_p=[0.9, 0.95, 0.999, 0.5, 1.0, 0.9, 0.8, 1.0, 1.0, 0.97, 0.9, 0.3],
+        min_p=[0, 0, 1e-5, 0, 0, 0, 0, 1e-4, 0, 1e-3, 0, 0],
+        rep_penalty=1.1, freq_penalty=0.2, pres_penalty=0.1)
+    hot = np.sort(rng.choice(V, 40_000, replace=False)).astype(np.int32) if dtype == "bf16" else None
+    logits = synth.f32_to_bf16_bits(z) if dtype == "bf16" else z
+    w = synth.Workload(f"large-V-{V}", B, V, dtype, logits, params, hist_ptr, hist_ids, hot_ids=hot)
+    res = _check(w, steps=(0, 1))
+    flags = res[0][1]["flags"]
+    assert not (flags & 128).any()       # no row came through the single-pass kernel's queue
+    assert (flags & 4).sum() >= 6        # the whole-vocabulary and large-k rows: multi-pass route
