@@ -33,28 +33,34 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
 // ------------------------------------------------------------------ element access -------------
+// The pointers are into the logits, device memory, and the loads say so (global-typed pointers): a
+// generic load also counts as an LDS access, and every wait for an LDS result would wait for it.
 template <typename DT> struct Elem;
 template <> struct Elem<float> {
   static constexpr int EPL = 4;
-  __device__ static __forceinline__ float one(const float* p) { return *p; }
+  typedef __attribute__((address_space(1))) const float Glob;
+  typedef __attribute__((address_space(1))) const f32x4 GlobVec;
+  __device__ static __forceinline__ float one(const float* p) { return *(Glob*)p; }
   template <bool VEC>
   __device__ static __forceinline__ void vec(const float* p, float (&z)[4]) {
     if (VEC) {  // streamed once: non-temporal so the row does not displace what the L2 should keep
-      const f32x4 v = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(p));
+      const f32x4 v = __builtin_nontemporal_load((GlobVec*)p);
       z[0] = v.x; z[1] = v.y; z[2] = v.z; z[3] = v.w;
     } else {
 #pragma unroll
-      for (int e = 0; e < 4; ++e) z[e] = p[e];
+      for (int e = 0; e < 4; ++e) z[e] = ((Glob*)p)[e];
     }
   }
 };
 template <> struct Elem<uint16_t> {  // bfloat16 bit patterns; the upcast to float32 is exact
   static constexpr int EPL = 8;
-  __device__ static __forceinline__ float one(const uint16_t* p) { return __uint_as_float((uint32_t)(*p) << 16); }
+  typedef __attribute__((address_space(1))) const uint16_t Glob;
+  typedef __attribute__((address_space(1))) const u32x4 GlobVec;
+  __device__ static __forceinline__ float one(const uint16_t* p) { return __uint_as_float((uint32_t)(*(Glob*)p) << 16); }
   template <bool VEC>
   __device__ static __forceinline__ void vec(const uint16_t* p, float (&z)[8]) {
     if (VEC) {
-      const u32x4 v = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(p));
+      const u32x4 v = __builtin_nontemporal_load((GlobVec*)p);
       const uint32_t w[4] = {v.x, v.y, v.z, v.w};
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
@@ -706,13 +712,7 @@ __device__ inline int sampled_route(const DT* __restrict__ rowp, int V, const Hi
 template <typename DT>
 struct RowReader {
   const DT* p; int V; float tau; bool greedy; const History* H;
-  // Through a global-typed pointer: a generic load would also count as an LDS access, and every
-  // wait for an LDS result (the history mask) would then wait for the row loads in flight.
-  __device__ __forceinline__ float load(int idx) const {
-    typedef __attribute__((address_space(1))) const DT GlobDT;
-    const DT raw = *((GlobDT*)p + idx);
-    return Elem<DT>::one(&raw);
-  }
+  __device__ __forceinline__ float load(int idx) const { return Elem<DT>::one(p + idx); }
   // Sixteen bytes from column idx on (a multiple of Elem<DT>::EPL, the row 16-byte aligned).
   __device__ __forceinline__ u32x4 load16(int idx) const {
     typedef __attribute__((address_space(1))) const DT GlobDT;
