@@ -957,9 +957,10 @@ __device__ __forceinline__ unsigned long long qmass(uint32_t key, float ymax) {
   p = fma(p, f, 0.2402265069591007);
   p = fma(p, f, 0.6931471805599453);
   p = fma(p, f, 1.0);
-  const double v = rint(ldexp(p, (int)n + QBITS));  // an integer below 2^(QBITS + 1) for x <= 0
-  const double h = floor(v * 0x1p-32);
-  return ((unsigned long long)(uint32_t)h << 32) | (unsigned long long)(uint32_t)(v - h * 0x1p32);
+  // below 2^(QBITS + 1) for x <= 0; adding 2^52 rounds it to the nearest integer (ties to even) and
+  // leaves that integer in the low 52 bits of the sum
+  const double v = ldexp(p, (int)n + QBITS) + 0x1p52;
+  return (unsigned long long)__double_as_longlong(v) & 0x000FFFFFFFFFFFFFull;
 }
 
 // Radix descent over the 32-bit key of y (three levels: 11, 11, 10 bits) with exact integer
