@@ -367,3 +367,34 @@ def test_vocabularies_of_two_to_the_eighteen_columns_and_more(V, dtype):
     flags = res[0][1]["flags"]
     assert not (flags & 128).any()       # no row came through the single-pass kernel's queue
     assert (flags & 4).sum() >= 6        # the whole-vocabulary and large-k rows: multi-pass route
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_multi_pass_route_cuts_inside_and_above_a_plateau(dtype):
+    """Top-k cuts that fall inside a plateau of 12,000 equal logits (the first r ties by id survive),
+    with a nucleus inside that prefix: the nucleus descent meets every tie of the plateau, also the
+    ones the top-k cut left out, so the keys it sets aside for its last level overflow and that
+    level reads the row instead; with the cut above the plateau the keys fit.  Rows 6 and 7 carry
+    histories that move some of the ties."""
+    rng = np.random.default_rng(5)
+    B, V = 8, 40_000
+    z = (rng.standard_normal((B, V)) * 0.5 - 6.0).astype(np.float32)
+    for b in range(B):
+        perm = rng.permutation(V)
+        z[b, perm[:1500]] = rng.uniform(1.0, 6.0, 1500).astype(np.float32)   # the head
+        z[b, perm[1500:13_500]] = 0.5                                          # the plateau
+    lens = np.array([0, 0, 0, 0, 0, 0, 2500, 600])
+    hist_ptr = np.concatenate([[0], np.cumsum(lens)]).astype(np.int64)
+    order = np.argsort(-z, axis=1, kind="stable")
+    hist_ids = np.concatenate([rng.choice(order[b, :9000], int(lens[b])) for b in range(B)]).astype(np.int32)
+    params = synth.make_params(
+        B, temperature=[1.0, 1.0, 0.7, 1.3, 1.0, 1.0, 1.0, 0.9],
+        top_k=[3000, 3000, 9000, 13_499, 1400, 0, 3000, 5000],
+        top_p=[0.99, 0.5, 0.999, 0.97, 0.9, 0.98, 0.95, 0.999],
+        min_p=[0, 0, 0, 0, 0, 1e-3, 0, 0],
+        rep_penalty=1.2, freq_penalty=0.1, pres_penalty=0.05)
+    hot = np.sort(rng.choice(V, 6000, replace=False)).astype(np.int32) if dtype == "bf16" else None
+    logits = synth.f32_to_bf16_bits(z) if dtype == "bf16" else z
+    w = synth.Workload(f"plateau-cuts-{dtype}", B, V, dtype, logits, params, hist_ptr, hist_ids, hot_ids=hot)
+    res = _check(w, steps=(0, 1, 2))
+    assert (res[0][1]["flags"] & 4).sum() >= 5  # the multi-pass route of the general kernel
