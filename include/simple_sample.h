@@ -25,7 +25,8 @@
  *     y >= fl32(y_max + fl32(ln min_p)), top-p keeps the shortest prefix of the top-k prefix whose
  *     mass reaches top_p times the top-k prefix mass; the shortest of the three wins, never empty;
  *   - one Philox4x32-10 block per (row, step): key = (seed lo, seed hi), counter =
- *     (row_offset + row, step lo, step hi, 0); word w -> (x >> 8) * 2^-24; word 0 drives the draw,
+ *     (r lo, step lo, step hi, r hi) with r = row_offset + row the 64-bit global row index;
+ *     word w -> (x >> 8) * 2^-24; word 0 drives the draw,
  *     word 1 the SHVS acceptance test (accept iff u * S_K <= S_H), word 2 the SHVS tail draw;
  *   - every CDF walk (full, hot, tail) runs in ascending token id and returns the first id whose
  *     running mass exceeds u * total.
@@ -85,7 +86,9 @@ typedef struct {
 /* Optional per-row diagnostics (32 bytes, device memory, array of B). */
 typedef struct {
   double alpha;        /* SHVS hot mass alpha_b = S_H / S_K (Eq. (7)); NaN without a hot set */
-  double s_k;          /* mass of the top-k prefix relative to the row maximum */
+  double s_k;          /* mass of the top-k prefix relative to the row maximum; formed (and reported)
+                          on rows with 0 < top_p < 1, whose nucleus target it scales; unspecified
+                          on other rows, which never need it */
   float p_chosen;      /* p~ of the returned id */
   int32_t n_survivors; /* |K_b| */
   uint32_t flags;      /* SIMPLE_DIAG_* */

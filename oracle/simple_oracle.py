@@ -75,7 +75,8 @@ def row_uniforms(seed: int, rows: np.ndarray, step) -> tuple[np.ndarray, np.ndar
     """The three uniforms of a (row, step) pair: ``(u_draw, u_acc, u_tail)`` in [0, 1).
 
     Convention (the paper names no generator): one Philox block per (row, step) with
-    key = (seed low 32 bits, seed high 32 bits) and counter = (row, step low, step high, 0);
+    key = (seed low 32 bits, seed high 32 bits) and counter = (row low, step low, step high,
+    row high), so that global row indices that differ by 2^32 do not share their uniforms;
     word i is turned into ``(x >> 8) * 2^-24``, which is exact in float32 and float64.
     Word 0 drives the categorical draw, word 1 the SHVS acceptance test, word 2 the SHVS tail
     draw (three independent variates, as the exactness identity of section 5.3 assumes).
@@ -85,7 +86,7 @@ def row_uniforms(seed: int, rows: np.ndarray, step) -> tuple[np.ndarray, np.ndar
     step = np.asarray(step, dtype=np.uint64)
     rows, step = np.broadcast_arrays(rows, step)
     ctr = np.stack(
-        [rows & _MASK32, step & _MASK32, step >> np.uint64(32), np.zeros_like(rows)], axis=-1
+        [rows & _MASK32, step & _MASK32, step >> np.uint64(32), rows >> np.uint64(32)], axis=-1
     ).astype(np.uint32)
     key = np.array([seed & 0xFFFFFFFF, (seed >> 32) & 0xFFFFFFFF], dtype=np.uint32)
     x = philox4x32_10(ctr, key)
@@ -354,6 +355,7 @@ class RowResult:
     S_k: float
     dist: Optional[RowDist] = None
     alt_p: tuple = ()  # p-tilde of ``id`` under the neighbouring nucleus lengths, when the boundary is ambiguous
+    S_k_used: bool = False  # the row's controls make S_k part of the method (0 < top_p < 1: it scales the nucleus target)
 
 
 def _neighbours(d: RowDist, tok: int, hot_mask, accepted) -> set:
@@ -406,7 +408,7 @@ def sample_row(z_row: np.ndarray, par, hist_row, hot_mask: Optional[np.ndarray],
     alt.discard(tok)
     p_chosen = float(d.w[np.searchsorted(d.ids, tok)] / d.S_K)
     return RowResult(tok, alt, ambiguous, d.n, p_chosen, alpha, accepted, d.S_k,
-                     d if keep_dist else None, tuple(alt_p))
+                     d if keep_dist else None, tuple(alt_p), bool(0.0 < float(par["top_p"]) < 1.0))
 
 
 def hot_mask_from_ids(hot_ids: Optional[Sequence[int]], V: int) -> Optional[np.ndarray]:

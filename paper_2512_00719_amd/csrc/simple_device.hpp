@@ -117,7 +117,7 @@ __device__ inline void philox4x32_10(uint32_t c0, uint32_t c1, uint32_t c2, uint
 }
 __device__ inline void row_uniforms(uint64_t seed, uint64_t row, uint64_t step, double (&u)[3]) {
   uint32_t x[4];
-  philox4x32_10((uint32_t)row, (uint32_t)step, (uint32_t)(step >> 32), 0u, (uint32_t)seed,
+  philox4x32_10((uint32_t)row, (uint32_t)step, (uint32_t)(step >> 32), (uint32_t)(row >> 32), (uint32_t)seed,
                 (uint32_t)(seed >> 32), x);
 #pragma unroll
   for (int i = 0; i < 3; ++i) u[i] = (double)(x[i] >> 8) * 0x1p-24;

@@ -257,16 +257,19 @@ __device__ __forceinline__ u64 mass_fix(float w) { return float_to_u64(w * MSCAL
 __device__ __forceinline__ u64 mass_fix_below(float w) { return (u64)(uint32_t)fmaf(w, MSCALE, 0.5f); }
 // Mass of a column below g for the single-pass kernel's running total: exp((z - g) / tau) * 2^28
 // without the exactly rounded tempered value; the scale rides in the exponent and the conversion
-// truncates.  Relative error of the total below 1e-6 (rounding of the exponent at magnitude 28,
-// independent from column to column), inside the 1e-5 tolerance on probabilities; the total only
-// decides whether the nucleus fits the list, and the list's target.
+// rounds to nearest (truncating would lose half a unit per column, all in one direction: with V
+// columns below a g that a min-p bound holds close to the row maximum that is V * 2^-29 of the mass
+// at g, up to 4e-5 of the row's mass).  Relative error of the total below 1e-6 (rounding of the
+// exponent at magnitude 28 and of the integer, independent from column to column), inside the 1e-5
+// tolerance on probabilities; the total only decides whether the nucleus fits the list, and the
+// list's target.
 __device__ __forceinline__ uint32_t below_term(float z, const StreamCtx& C) {
-  return (uint32_t)__builtin_amdgcn_exp2f(fmaf(z - C.g, C.l2e_tau, 28.0f));
+  return (uint32_t)(__builtin_amdgcn_exp2f(fmaf(z - C.g, C.l2e_tau, 28.0f)) + 0.5f);
 }
 // The same for any column, without a test: a column at or above g (or a NaN) yields exactly 2^28, so
 // a sum over all columns exceeds the mass below g by 2^28 times the number of columns at or above g.
 __device__ __forceinline__ uint32_t below_term_clamped(float z, const StreamCtx& C) {
-  return (uint32_t)__builtin_amdgcn_exp2f(fminf(fmaf(z - C.g, C.l2e_tau, 28.0f), 28.0f));
+  return (uint32_t)(__builtin_amdgcn_exp2f(fminf(fmaf(z - C.g, C.l2e_tau, 28.0f), 28.0f)) + 0.5f);  // 2^28 + 0.5 is 2^28 in float32
 }
 
 }  // namespace fast

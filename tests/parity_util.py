@@ -37,9 +37,21 @@ def run_gpu(w: synth.Workload, step: int, sampler=None, dev=None, row_offset: in
     torch.cuda.synchronize()
     ids = out.cpu().numpy()
     dg = diag.cpu().numpy().view(binding.ROW_DIAG_DTYPE)
+    # the same call without a diagnostics buffer (what a serving loop and the benchmark issue)
+    ids_nd = run_gpu_no_diag(w, step, sampler, dev, row_offset)
+    assert np.array_equal(ids, ids_nd), ("ids differ without a diagnostics buffer", np.flatnonzero(ids != ids_nd)[:10])
     if own:
         sampler.close()
     return ids, dg
+
+
+def run_gpu_no_diag(w: synth.Workload, step: int, sampler, dev, row_offset: int = 0):
+    """The same call without a diagnostics buffer; returns ids[B]."""
+    import torch
+    out = sampler.sample(dev["logits"], dev["params"], dev["hist_ptr"], dev["hist_ids"], dev["hot_ids"],
+                         seed=w.seed, step=step, row_offset=row_offset, diag=None, V=w.V)
+    torch.cuda.synchronize()
+    return out.cpu().numpy()
 
 
 def run_oracle(w: synth.Workload, step: int, rows=None, row_offset: int = 0, keep_dist=False):
@@ -49,26 +61,72 @@ def run_oracle(w: synth.Workload, step: int, rows=None, row_offset: int = 0, kee
                     row_offset=row_offset, keep_dist=keep_dist)
 
 
+def oracle_rows_parallel(w: synth.Workload, step: int, rows, workers: int = 16):
+    """run_oracle over `rows` in forked worker processes.  Must be called before this process
+    initialises the GPU (a forked child must not inherit a live HIP runtime)."""
+    import multiprocessing as mp
+    import os
+    global _FORK_W
+    _FORK_W = (w, step)
+    rows = list(rows)
+    n = max(1, min(workers, len(os.sched_getaffinity(0)), len(rows)))
+    chunks = [rows[i::n * 8] for i in range(n * 8) if rows[i::n * 8]]
+    with mp.get_context("fork").Pool(n) as pool:
+        parts = pool.map(_fork_rows, chunks, chunksize=1)
+    by_row = {r: o for ch, part in zip(chunks, parts) for r, o in zip(ch, part)}
+    return [by_row[r] for r in rows]
+
+
+_FORK_W = None
+
+
+def _fork_rows(rows):
+    w, step = _FORK_W
+    has_hist = w.hist_ids.size > 0
+    hot_mask = O.hot_mask_from_ids(w.hot_ids, w.V)
+    out = []
+    for b in rows:
+        zr = w.logits[b] if w.dtype == "f32" else synth.bf16_bits_to_f32(w.logits[b])
+        hr = w.hist_ids[int(w.hist_ptr[b]):int(w.hist_ptr[b + 1])] if has_hist else None
+        out.append(O.sample_row(zr, w.params[b], hr, hot_mask, w.seed, b, step))
+    return out
+
+
 def compare(ids, dg, oracle_rows, rows, max_mismatch_frac=1e-4, check_p=True):
     """Exact id parity outside the ambiguity window; returns a summary dict.
 
     A row whose uniform (or nucleus / acceptance decision) lies within 1e-6 of a boundary may
     return one of the oracle's alternative ids; such rows count against the mismatch budget.  When
     the nucleus boundary itself is within the window the survivor set may differ by its last
-    element, so p~ of the (same) id may be normalised over either prefix."""
-    hard, soft, ambiguous = [], [], 0
+    element, so p~ of the (same) id may be normalised over either prefix.  Outside ambiguous rows
+    the diagnostics record must agree with the oracle too: |K_b| exactly, alpha within 1e-6, the
+    mass of the top-k prefix within 1e-5 relative (on rows whose nucleus target it scales, 0 < top_p
+    < 1; other rows never form it), and the SHVS acceptance decision."""
+    hard, soft, ambiguous, diag_bad = [], [], 0, []
     for r, o in zip(rows, oracle_rows):
         ambiguous += bool(o.ambiguous)
         if int(ids[r]) == o.id:
-            if check_p and o.id >= 0 and not (dg["flags"][r] & 2):
+            greedy = bool(dg["flags"][r] & 2)
+            if check_p and o.id >= 0 and not greedy:
                 got = float(dg["p_chosen"][r])
                 assert any(abs(got - p) <= 1e-5 * p + 1e-30 for p in (o.p_chosen, *o.alt_p)), (r, dg[r], o.p_chosen, o.alt_p)
+            if check_p and o.id >= 0 and not o.ambiguous:
+                if int(dg["n_survivors"][r]) != o.n:
+                    diag_bad.append((r, "n", int(dg["n_survivors"][r]), o.n))
+                if not greedy and o.S_k_used and not abs(float(dg["s_k"][r]) - o.S_k) <= 1e-5 * o.S_k:
+                    diag_bad.append((r, "s_k", float(dg["s_k"][r]), o.S_k))
+                if o.accepted is not None:
+                    if not abs(float(dg["alpha"][r]) - o.alpha) <= 1e-6:
+                        diag_bad.append((r, "alpha", float(dg["alpha"][r]), o.alpha))
+                    if bool(dg["flags"][r] & 16) != bool(o.accepted):
+                        diag_bad.append((r, "accepted", bool(dg["flags"][r] & 16), o.accepted))
             continue
         if o.ambiguous and int(ids[r]) in o.alt_ids:
             soft.append(r)
         else:
             hard.append((r, int(ids[r]), o.id, sorted(o.alt_ids), o.n, int(dg["n_survivors"][r]), hex(int(dg["flags"][r]))))
     assert not hard, f"id mismatch outside the ambiguity window (row, gpu, oracle, alt, n_oracle, n_gpu, flags): {hard[:10]}"
+    assert not diag_bad, f"diagnostics disagree with the oracle (row, field, gpu, oracle): {diag_bad[:10]}"
     budget = max(1, int(np.ceil(max_mismatch_frac * len(rows))))
     assert len(soft) <= budget, f"{len(soft)} ambiguous-window mismatches over {len(rows)} rows"
     return {"rows": len(rows), "ambiguous": ambiguous, "soft_mismatch": len(soft)}

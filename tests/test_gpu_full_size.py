@@ -1,8 +1,10 @@
-"""GPU parity at the full sizes of the five benchmark configurations, in the launch configuration
-the benchmark times.  One oracle row costs about ten milliseconds, so the first call is compared
-with the oracle on every row of C2, C3 and C4 and on a seeded sample of C5's 4096 rows, the second
-call on a smaller sample; all rows of every call are checked for properties that hold at any size:
-ids inside [0, V), no error flags, greedy rows flagged greedy, determinism."""
+"""GPU parity at the full sizes of the benchmark configurations, in the launch configuration the
+benchmark times.  Every row of the first call of C2, C3, C4 (at each hot-set size of its sweep) and
+C5 is compared with the oracle; the oracle rows are computed in forked worker processes before the
+test process first touches the GPU.  A second call is compared on a sample of rows, and one more
+call without a diagnostics buffer (what the benchmark times) must return the same ids.  All rows of
+every call are checked for properties that hold at any size: ids inside [0, V), no error flags,
+greedy rows flagged greedy, determinism."""
 import numpy as np
 import pytest
 
@@ -23,18 +25,40 @@ def _sample_rows(w, n, seed):
     return sorted(rows)
 
 
-@pytest.mark.parametrize("idx,n_first,n_rows", [(2, 256, 40), (3, 1024, 72), (4, 512, 24), (5, 256, 40)])
-def test_full_size_config(idx, n_first, n_rows):
+# The oracle legs fork worker processes, so they run before any test of the session touches the
+# GPU: tests/conftest.py calls prepare() when collection has finished and this module is selected.
+_CASES = [(2, None), (3, None), (4, 4096), (4, 8192), (4, 16384), (4, 32768), (5, None)]
+_ORACLE = {}
+_WORKLOADS = {}
+
+
+def prepare():
+    import torch
+    if _ORACLE:
+        return
+    assert not torch.cuda.is_initialized(), "the oracle legs fork and must run before the GPU is touched"
+    for idx, H in _CASES:
+        if idx not in _WORKLOADS:
+            print(f"config {idx}: generating", flush=True)
+            _WORKLOADS[idx] = synth.make_config(idx)
+        w = _WORKLOADS[idx] if H is None else _WORKLOADS[idx].with_hot(H)
+        rows1 = _sample_rows(w, 40 if idx != 4 else 24, 100 + idx)
+        print(f"config {idx} H={H}: oracle on all {w.B} rows of step 0 and {len(rows1)} rows of step 1", flush=True)
+        _ORACLE[(idx, H)] = {0: (list(range(w.B)), P.oracle_rows_parallel(w, 0, range(w.B))),
+                             1: (rows1, P.oracle_rows_parallel(w, 1, rows1))}
+
+
+@pytest.mark.parametrize("idx,H", _CASES)
+def test_full_size_config(idx, H):
+    prepare()
     from paper_2512_00719_amd import binding
-    print(f"config {idx}: generating", flush=True)
-    w = synth.make_config(idx)
-    rows_by_step = {0: _sample_rows(w, n_first, 200 + idx), 1: _sample_rows(w, n_rows, 100 + idx)}
+    w = _WORKLOADS[idx] if H is None else _WORKLOADS[idx].with_hot(H)
     nnz_max = int(np.diff(w.hist_ptr).max()) if w.hist_ids.size else 0
     s = binding.Sampler(w.V, nnz_max)
     dev = P.to_device(w)
     for step in (0, 1):
-        rows = rows_by_step[step]
-        print(f"config {idx}: step {step} on {w.B} x {w.V} {w.dtype}, {len(rows)} rows against the oracle", flush=True)
+        rows, oracle_rows = _ORACLE[(idx, H)][step]
+        print(f"config {idx} H={H}: step {step} on {w.B} x {w.V} {w.dtype}, {len(rows)} rows against the oracle", flush=True)
         ids, dg = P.run_gpu(w, step, sampler=s, dev=dev)
         assert ids.min() >= 0 and ids.max() < w.V
         assert not (dg["flags"] & binding.DIAG_ERROR).any()
@@ -47,7 +71,9 @@ def test_full_size_config(idx, n_first, n_rows):
             assert np.all((a >= 0) & (a <= 1))
         ids2, _ = P.run_gpu(w, step, sampler=s, dev=dev)
         assert np.array_equal(ids, ids2)  # same call twice: same ids
-        summary = P.compare(ids, dg, P.run_oracle(w, step, rows=rows), rows)
-        print(f"config {idx}: step {step} parity {summary}; wide rows {int(((dg['flags'] & 4) > 0).sum())}, "
-              f"careful rows {int(((dg['flags'] & 32) > 0).sum())}", flush=True)
+        ids3 = P.run_gpu_no_diag(w, step, sampler=s, dev=dev)
+        assert np.array_equal(ids, ids3)  # the call the benchmark times (no diagnostics buffer)
+        summary = P.compare(ids, dg, oracle_rows, rows)
+        print(f"config {idx} H={H}: step {step} parity {summary}; wide rows {int(((dg['flags'] & 4) > 0).sum())}, "
+              f"general-kernel rows {int(((dg['flags'] & 128) > 0).sum())}", flush=True)
     s.close()

@@ -69,6 +69,13 @@ def test_philox_vectorised_matches_scalar_and_is_uniform():
     assert O.row_uniforms(1, np.array(3), 5)[0] != O.row_uniforms(1, np.array(3), 5 + (1 << 32))[0]
     # the seed's high word is part of the key
     assert O.row_uniforms(1, np.array(3), 5)[0] != O.row_uniforms(1 + (1 << 32), np.array(3), 5)[0]
+    # a global row index above 2^32 reaches the fourth counter word: word placement checked against
+    # the block function itself
+    big = (7 << 32) + 3
+    assert O.row_uniforms(1, np.array(3), 5)[0] != O.row_uniforms(1, np.array(big, dtype=np.uint64), 5)[0]
+    x = O.philox4x32_10(np.array([3, 5, 9, 7], np.uint32), np.array([1, 0], np.uint32))
+    u = O.row_uniforms(1, np.array(big, dtype=np.uint64), 5 + (9 << 32))
+    assert [float(v) for v in u] == [float(int(w) >> 8) * 2.0 ** -24 for w in x[:3]]
 
 
 # ------------------------------------------------------------------ penalties -------------------
@@ -234,12 +241,36 @@ def test_truncated_softmax_equals_masked_softmax():
 
 
 def test_filter_composition_is_shortest_prefix():
+    """K_b against a prefix formed independently: sort once (value descending, id ascending), then
+    three explicit scans for the lengths the filters allow, in exact rational-free arithmetic
+    (math.fsum), and the shortest wins.  Pins the composition rule and each n_* of the oracle."""
     rng = np.random.default_rng(6)
-    z = (rng.standard_normal(4000) * 2).astype(np.float32)
-    for k, p, m in ((50, 0.9, 0.0), (50, 0.3, 0.0), (0, 0.9, 0.05), (1000, 0.99, 0.2), (5, 1.0, 0.5)):
-        d = O.row_distribution(z, _par(top_k=k, top_p=p, min_p=m, temperature=0.8))
-        assert d.n == max(1, min(d.n_k, d.n_m, d.n_p))
-        assert d.n_k == (k if k else 4000)
+    V = 4000
+    z = (rng.standard_normal(V) * 2).astype(np.float32)
+    z[[5, 17, 900]] = z[3]  # ties, also where a cut may fall
+    for k, p, m, tau in ((50, 0.9, 0.0, 0.8), (50, 0.3, 0.0, 0.8), (0, 0.9, 0.05, 0.8), (1000, 0.99, 0.2, 1.3),
+                         (5, 1.0, 0.5, 0.7), (0, 0.97, 0.0, 1.1), (3, 0.999, 1e-4, 1.0)):
+        par = _par(top_k=k, top_p=p, min_p=m, temperature=tau)
+        d = O.row_distribution(z, par)
+        y = [float(np.float32(v) / np.float32(tau)) for v in z]            # IEEE float32 quotient
+        order = sorted(range(V), key=lambda i: (-y[i], i))
+        w = [math.exp(y[i] - y[order[0]]) for i in order]
+        n_k = k if 1 <= k < V else V
+        n_m = V
+        if m > 0:
+            thr = float(np.float32(np.float32(y[order[0]]) + np.float32(math.log(float(np.float32(m))))))
+            n_m = 0
+            while n_m < V and y[order[n_m]] >= thr:
+                n_m += 1
+        n_p = n_k
+        if p < 1:
+            target = float(np.float32(p)) * math.fsum(w[:n_k])
+            n_p = 1
+            while math.fsum(w[:n_p]) < target:
+                n_p += 1
+        n = max(1, min(n_k, n_m, n_p))
+        assert (d.n_k, d.n_m, d.n_p, d.n) == (n_k, n_m, n_p, n), (k, p, m, tau)
+        assert sorted(order[:n]) == d.ids.tolist()
 
 
 def test_degenerate_rows():
@@ -452,3 +483,138 @@ def test_ambiguity_protocol_reports_neighbours():
     d = O.row_distribution(z, _par())
     ids, margin, _ = O.draw(d, np.array([0.25 - 1e-9, 0.25 + 1e-9, 0.1]))
     assert list(ids) == [0, 1, 0] and margin[0] < 1e-6 and margin[1] < 1e-6 and margin[2] > 0.09
+
+
+def test_neighbours_are_the_adjacent_ids_of_the_walk():
+    """`_neighbours`: the ids next to a token in the CDF walk that produced it (all of K_b without a
+    hot set; the hot or the tail members of K_b with one), hand-listed."""
+    d = O.RowDist(V=32, ids=np.array([3, 7, 8, 20]), w=np.ones(4), n=4)
+    assert O._neighbours(d, 7, None, None) == {3, 8}
+    assert O._neighbours(d, 3, None, None) == {7}
+    assert O._neighbours(d, 20, None, None) == {8}
+    hot = np.zeros(32, bool)
+    hot[[7, 20, 31]] = True
+    assert O._neighbours(d, 7, hot, True) == {20}     # hot walk: 7, 20
+    assert O._neighbours(d, 20, hot, True) == {7}
+    assert O._neighbours(d, 8, hot, False) == {3}     # tail walk: 3, 8
+    assert O._neighbours(d, 3, hot, False) == {8}
+
+
+def _nucleus_row():
+    """Five exactly representable logits at temperature 1: w = e^0 .. e^-4, hand-summed."""
+    z = np.array([-1.0, 2.0, 0.0, -2.0, 1.0], np.float32)    # order by value: ids 1, 4, 2, 0, 3
+    w = [math.exp(-i) for i in range(5)]
+    S = math.fsum(w)
+    return z, w, S
+
+
+def _f32_below(x):
+    t = np.float32(x)
+    return t if float(t) < x else np.nextafter(t, np.float32(-np.inf))
+
+
+def test_nucleus_ambiguity_alternatives_hand_built():
+    """The branch that builds RowDist.alt / RowResult.alt_p.  top_p is placed one float32 step
+    below and above the mass of the two-token prefix (the boundary is then within 1e-7 of the
+    target: exactly one alternative, the prefix one longer / one shorter, with hand-computed p~),
+    and 1e-3 below it (no alternative, not ambiguous)."""
+    z, w, S = _nucleus_row()
+    r2 = (w[0] + w[1]) / S
+    p_lo = _f32_below(r2)
+    p_hi = np.nextafter(p_lo, np.float32(np.inf))
+    if float(p_hi) <= r2:
+        p_hi = np.nextafter(p_hi, np.float32(np.inf))
+    assert float(p_lo) < r2 < float(p_hi) and float(p_hi) - float(p_lo) < 2e-7
+    d = O.row_distribution(z, _par(top_p=p_lo))
+    assert d.n == 2 and d.ids.tolist() == [1, 4] and d.nucleus_margin < 1e-6
+    assert [(a.n, a.ids.tolist()) for a in d.alt] == [(3, [1, 2, 4])]
+    d = O.row_distribution(z, _par(top_p=p_hi))
+    assert d.n == 3 and d.ids.tolist() == [1, 2, 4] and d.nucleus_margin < 1e-6
+    assert [(a.n, a.ids.tolist()) for a in d.alt] == [(2, [1, 4])]
+    d = O.row_distribution(z, _par(top_p=np.float32(r2 - 1e-3)))
+    assert d.n == 2 and d.alt == [] and 0.9e-3 < d.nucleus_margin < 1.1e-3
+    # a top-k cut at the same place removes the longer alternative (the nucleus never exceeds n_k)
+    d = O.row_distribution(z, _par(top_p=np.float32(0.999999), top_k=2))
+    assert d.n == 2 and d.alt == []
+
+
+def test_sample_row_alternatives_and_alt_p(monkeypatch):
+    """sample_row's ambiguity protocol end to end, with the uniforms planted: ids and p~ of the
+    neighbouring prefix, the neighbours of a draw on a CDF step, and none of it away from boundaries."""
+    z, w, S = _nucleus_row()
+    r2 = (w[0] + w[1]) / S
+
+    def plant(u_draw, u_acc=0.5, u_tail=0.5):
+        monkeypatch.setattr(O, "row_uniforms", lambda seed, rows, step: (np.float64(u_draw), np.float64(u_acc), np.float64(u_tail)))
+
+    # walk in ascending id over K = {1, 4}: id 1 holds [0, w0 / (w0 + w1)), id 4 the rest
+    s2, s3 = w[0] + w[1], w[0] + w[1] + w[2]
+    plant(0.9)
+    r = O.sample_row(z, _par(top_p=_f32_below(r2)), None, None, 1, 0, 0)
+    assert r.id == 4 and r.ambiguous and r.n == 2
+    assert abs(r.p_chosen - w[1] / s2) < 1e-15 and len(r.alt_p) == 1 and abs(r.alt_p[0] - w[1] / s3) < 1e-15
+    # under the alternative K = {1, 2, 4} (masses w0, w2, w1 in id order) u = 0.9 falls on id 4 too
+    # (0.9 * s3 > w0 + w2); what is forgiven is that draw and its neighbour in the alternative's walk
+    assert 0.9 * s3 > w[0] + w[2] and r.alt_ids == {2}
+    plant(0.74)  # K = {1, 4}: 0.74 * s2 > w0 -> id 4; K = {1, 2, 4}: 0.74 * s3 in [w0, w0 + w2) -> id 2
+    assert 0.74 * s2 > w[0] and w[0] <= 0.74 * s3 < w[0] + w[2]
+    r = O.sample_row(z, _par(top_p=_f32_below(r2)), None, None, 1, 0, 0)
+    assert r.id == 4 and r.ambiguous and 2 in r.alt_ids and len(r.alt_p) == 1
+    # away from the nucleus boundary and from every CDF step: nothing is forgiven
+    r = O.sample_row(z, _par(top_p=np.float32(r2 - 1e-3)), None, None, 1, 0, 0)
+    assert r.id == 4 and not r.ambiguous and r.alt_ids == set() and r.alt_p == ()
+    # a uniform 1e-9 (relative) past the CDF step between ids 1 and 4: flagged, the other side allowed
+    plant(w[0] / s2 + 1e-9)
+    r = O.sample_row(z, _par(top_p=np.float32(r2 - 1e-3)), None, None, 1, 0, 0)
+    assert r.id == 4 and r.ambiguous and r.alt_ids == {1} and r.alt_p == ()
+    # SHVS: an acceptance test within the window allows the other proposal's draw
+    hot = np.zeros(5, bool)
+    hot[1] = True
+    alpha = w[0] / s2
+    plant(0.3, u_acc=alpha + 1e-9, u_tail=0.4)
+    r = O.sample_row(z, _par(top_p=np.float32(r2 - 1e-3)), None, hot, 1, 0, 0)
+    assert r.accepted is False and r.id == 4 and r.ambiguous and r.alt_ids == {1}
+    plant(0.3, u_acc=alpha - 1e-3, u_tail=0.4)
+    r = O.sample_row(z, _par(top_p=np.float32(r2 - 1e-3)), None, hot, 1, 0, 0)
+    assert r.accepted is True and r.id == 1 and not r.ambiguous and r.alt_ids == set()
+
+
+def test_ambiguity_flags_on_headline_shaped_rows():
+    """On rows shaped like the headline configuration (V = 128,256, mixed controls, history): a row
+    is flagged for its nucleus exactly when a neighbouring prefix mass, re-summed here in extended
+    precision, lies within 1e-6 of the target (a wide nucleus ends among columns of probability
+    1e-7 and less, so a few percent of such rows are, by the window's definition); draws flagged
+    for a CDF step are rarer than 1e-3; and what a flagged row forgives is a handful of ids, never
+    a class of rows wholesale."""
+    w = synth.make_config(3, B=192)
+    n_nucleus = n_step = total = 0
+    for step in range(3):
+        res = O.sample(w.logits, w.params, w.hist_ptr, w.hist_ids, None, w.seed, step, keep_dist=True)
+        for b, r in enumerate(res):
+            d, par = r.dist, w.params[b]
+            total += 1
+            assert len(r.alt_ids) <= 6
+            if d.greedy:
+                assert not r.ambiguous and not r.alt_ids
+                continue
+            if step == 0 and par["top_p"] < 1:
+                c_o, mask = O.history_histograms(w.hist_ids[w.hist_ptr[b]:w.hist_ptr[b + 1]], 0, w.V)
+                zp = O.apply_penalties(w.logits[b], c_o, mask, par["rep_penalty"], par["freq_penalty"], par["pres_penalty"])
+                y = np.sort((zp / np.float32(par["temperature"])).astype(np.float32))[::-1]
+                mass = np.exp(y[:d.n_k].astype(np.longdouble) - np.longdouble(y[0]))
+                cum = np.cumsum(mass)
+                target = np.longdouble(np.float32(par["top_p"])) * cum[-1]
+                n_p = int(np.argmax(cum >= target)) + 1
+                want = set()
+                if n_p < d.n_k and (cum[n_p - 1] - target) / cum[-1] < 1e-6:
+                    want.add(n_p + 1)
+                if n_p >= 2 and (target - cum[n_p - 2]) / cum[-1] < 1e-6:
+                    want.add(n_p - 1)
+                want = {max(1, min(d.n_k, d.n_m, q)) for q in want} - {d.n}
+                assert d.n_p == n_p and {a.n for a in d.alt} == want, (b, n_p, want, [a.n for a in d.alt])
+            if d.alt:
+                n_nucleus += 1
+                assert r.ambiguous
+            elif r.ambiguous:
+                n_step += 1
+    assert total == 576 and n_step <= 1 and n_nucleus <= 0.08 * total, (n_step, n_nucleus, total)
