@@ -112,16 +112,16 @@ enum {
 };
 
 /*
- * Create a context on HIP device `device` for calls with at most max_V vocabulary entries and at
- * most max_nnz_per_row history ids per row (0 if no history will ever be passed).  Allocates, in
- * device memory, the hot-set membership bitmap (max_V bits), the row queues and the workspace of
- * the rows whose survivors do not fit the on-chip candidate list (4096 slots of about 52 KB plus
- * the size of one row's history tables: 0.2 to 0.5 GB; a call with more rows than slots goes out in
- * several launches, so no row ever lacks a slot).  Returns SIMPLE_ECAPACITY if one row's
- * on-chip state (history bitmap, counts, candidate list) cannot fit the LDS of one compute unit.
- * Host pointers: out.
+ * Create a context on HIP device `device` for calls with up to max_B rows, at most max_V vocabulary
+ * entries and at most max_nnz_per_row history ids per row (0 if no history will ever be passed).
+ * Allocates, in one block of device memory, the hot-set membership bitmap (max_V bits), the row
+ * queues and one workspace slot per row of a launch, for the rows whose survivors do not fit the
+ * on-chip candidate list (min(max_B, 4096) slots of about 52 KB plus the size of one row's history
+ * tables; a call with more rows than slots is still served, in several launches, so no row ever
+ * lacks a slot).  Returns SIMPLE_ECAPACITY if one row's on-chip state (history bitmap, counts,
+ * candidate list) cannot fit the LDS of one compute unit.  Host pointers: out.
  */
-int simple_create(simple_ctx** out, int device, int64_t max_V, int64_t max_nnz_per_row);
+int simple_create(simple_ctx** out, int device, int64_t max_B, int64_t max_V, int64_t max_nnz_per_row);
 
 /* Free the context (synchronises the device it lives on).  NULL is accepted. */
 void simple_destroy(simple_ctx* ctx);

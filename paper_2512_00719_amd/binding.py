@@ -40,7 +40,7 @@ def _load() -> ctypes.CDLL:
         raise ImportError(f"{LIB_PATH} is missing: build it with `python -m paper_2512_00719_amd.build`")
     lib = ctypes.CDLL(LIB_PATH)
     vp, i32, i64, u64 = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64, ctypes.c_uint64
-    lib.simple_create.argtypes = [ctypes.POINTER(vp), ctypes.c_int, i64, i64]
+    lib.simple_create.argtypes = [ctypes.POINTER(vp), ctypes.c_int, i64, i64, i64]
     lib.simple_create.restype = ctypes.c_int
     lib.simple_destroy.argtypes = [vp]
     lib.simple_destroy.restype = None
@@ -49,6 +49,10 @@ def _load() -> ctypes.CDLL:
     lib.simple_sample.argtypes = [vp, vp, i64, i64, ctypes.c_int, i64, vp, vp, vp, vp, i32, u64, u64, u64,
                                   vp, vp, vp]
     lib.simple_sample.restype = ctypes.c_int
+    lib.simple_sample_static.argtypes = [vp, i64, i64, ctypes.c_int, i64, vp, vp, vp, vp, i32, u64, u64, u64, vp, vp, vp]
+    lib.simple_sample_static.restype = ctypes.c_int
+    lib.simple_static_limit.argtypes = [ctypes.c_int]
+    lib.simple_static_limit.restype = i64
     lib.simple_profile_enable.argtypes = [vp, ctypes.c_int]
     lib.simple_profile_enable.restype = ctypes.c_int
     lib.simple_profile_read.argtypes = [vp, ctypes.POINTER(ctypes.c_double)]
@@ -84,10 +88,10 @@ def simple_strerror(code: int) -> str:
     return _lib.simple_strerror(int(code)).decode()
 
 
-def simple_create(device: int, max_V: int, max_nnz_per_row: int) -> int:
+def simple_create(device: int, max_B: int, max_V: int, max_nnz_per_row: int) -> int:
     """Returns the context handle (an integer address); raises SimpleError on failure."""
     h = ctypes.c_void_p()
-    rc = _lib.simple_create(ctypes.byref(h), int(device), int(max_V), int(max_nnz_per_row))
+    rc = _lib.simple_create(ctypes.byref(h), int(device), int(max_B), int(max_V), int(max_nnz_per_row))
     if rc != SIMPLE_OK:
         raise SimpleError(rc, "simple_create")
     return h.value
@@ -149,11 +153,27 @@ def simple_sample(ctx: int, logits_ptr: int, B: int, V: int, dtype: int, row_str
                                   vp(stream)))
 
 
+def simple_sample_static(logits_ptr: int, B: int, V: int, dtype: int, row_stride: int, params_ptr: int,
+                         hist_ptr_ptr: int, hist_ids_ptr: int, hot_ids_ptr: int, H: int, seed: int, step: int,
+                         row_offset: int, out_ids_ptr: int, diag_ptr: int, stream: int = 0) -> int:
+    """Raw call of the entry point that allocates nothing (no context).  Returns the C status code."""
+    vp = ctypes.c_void_p
+    return int(_lib.simple_sample_static(vp(logits_ptr), int(B), int(V), int(dtype), int(row_stride),
+                                         vp(params_ptr), vp(hist_ptr_ptr), vp(hist_ids_ptr), vp(hot_ids_ptr), int(H),
+                                         ctypes.c_uint64(seed & (2 ** 64 - 1)), ctypes.c_uint64(step & (2 ** 64 - 1)),
+                                         ctypes.c_uint64(row_offset & (2 ** 64 - 1)), vp(out_ids_ptr), vp(diag_ptr),
+                                         vp(stream)))
+
+
+def simple_static_limit(what: int) -> int:
+    return int(_lib.simple_static_limit(int(what)))
+
+
 class Sampler:
     """Convenience wrapper over torch device tensors (marshalling only)."""
 
-    def __init__(self, max_V: int, max_nnz_per_row: int, device: int = 0):
-        self.ctx = simple_create(device, max_V, max_nnz_per_row)
+    def __init__(self, max_V: int, max_nnz_per_row: int, device: int = 0, max_B: int = 4096):
+        self.ctx = simple_create(device, max_B, max_V, max_nnz_per_row)
         self.device = device
 
     def close(self) -> None:

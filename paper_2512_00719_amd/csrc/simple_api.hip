@@ -21,15 +21,22 @@ struct simple_ctx {
   int n_cu;
   uint32_t* pend;       // device: queue of rows the single-pass kernel leaves to the general kernel
   uint32_t* wq;         // device: queue of rows for the whole-vocabulary-nucleus kernels
-  unsigned char* wws;   // device: their workspace, WIDE_SLOTS slots
+  unsigned char* wws;   // device: their workspace, `slots` slots
   uint32_t ws_stride;   // bytes per slot
+  int slots;            // rows per launch: every row of a launch can be queued, with a slot
   int parity;           // which queue counters the next launch uses
   hipEvent_t* prof_ev;  // 2 * PROF_MAX events while profiling is enabled, else null
   int prof_n;           // launches recorded so far
+  void* base;           // device allocation that holds all of the above (null: not owned)
 };
 constexpr int PROF_MAX = 1024;
 
 namespace simple {
+
+// Device memory of a context, carved from one block: hot-set bitmap (max_V bits), one flag word, the
+// pending-row queue (two counters, then one entry per row of a launch), the wide-row queue (a head,
+// then one 64-byte record per slot) and the slots.  Every part starts on a 256-byte boundary.
+struct CtxLayout { size_t hot_bits, hot_flags, pend, wq, wws, total; uint32_t ws_stride; };
 
 static uint32_t align16(uint32_t x) { return (x + 15u) & ~15u; }
 
@@ -84,6 +91,25 @@ FastLayout make_fast_layout(int64_t V, int dtype, int64_t max_nnz, bool with_his
   return F;
 }
 
+static size_t align256(size_t x) { return (x + 255u) & ~(size_t)255u; }
+
+CtxLayout ctx_layout(int64_t max_V, int64_t max_nnz, int slots, int lds_limit, int n_cu) {
+  CtxLayout L{};
+  size_t off = 0;
+  L.hot_bits = off;  off = align256(off + ((size_t)((max_V + 31) / 32) + 1) * 4u);
+  L.hot_flags = off; off = align256(off + 4u);
+  L.pend = off;      off = align256(off + (2u + (size_t)slots) * 4u);
+  L.wq = off;        off = align256(off + 64u + 64u * (size_t)slots);  // head, then one 64-byte record per slot
+  // a slot holds the fixed part and the largest history tables the single-pass kernel can have
+  const FastLayout Fm = make_fast_layout(max_V < ((int64_t)1 << 18) ? max_V : ((int64_t)1 << 18) - 1, SIMPLE_F32,
+                                         max_nnz, max_nnz > 0, true, lds_limit, (int64_t)1 << 30, n_cu);
+  const uint32_t tables = (max_nnz > 0 && Fm.total) ? Fm.cnt + (uint32_t)((max_nnz + 3) / 2) * 4u + 16u : 0u;
+  L.ws_stride = (WIDE_SLOT_FIXED + tables + 255u) & ~255u;
+  L.wws = off;       off = align256(off + (size_t)L.ws_stride * (size_t)slots);
+  L.total = off;
+  return L;
+}
+
 struct DeviceGuard {
   int prev = -1; bool ok = false;
   explicit DeviceGuard(int dev) {
@@ -111,10 +137,10 @@ const char* simple_strerror(int code) {
   }
 }
 
-int simple_create(simple_ctx** out, int device, int64_t max_V, int64_t max_nnz_per_row) {
+int simple_create(simple_ctx** out, int device, int64_t max_B, int64_t max_V, int64_t max_nnz_per_row) {
   if (!out) return SIMPLE_EINVAL;
   *out = nullptr;
-  if (max_V <= 0 || max_V >= (int64_t)1 << 30 || max_nnz_per_row < 0 || device < 0) return SIMPLE_EINVAL;
+  if (max_B <= 0 || max_V <= 0 || max_V >= (int64_t)1 << 30 || max_nnz_per_row < 0 || device < 0) return SIMPLE_EINVAL;
   if (max_nnz_per_row > 65535) return SIMPLE_ECAPACITY;  // 16-bit per-token counts
   int n_dev = 0;
   if (hipGetDeviceCount(&n_dev) != hipSuccess || device >= n_dev) return SIMPLE_EDEVICE;
@@ -132,31 +158,23 @@ int simple_create(simple_ctx** out, int device, int64_t max_V, int64_t max_nnz_p
   if (!c) return SIMPLE_ENOMEM;
   c->device = device; c->max_V = max_V; c->max_nnz = max_nnz_per_row; c->lds_limit = lds; c->n_cu = n_cu;
   c->hot_V = 0; c->hot_H = 0; c->hot_bits = nullptr; c->hot_flags = nullptr; c->pend = nullptr; c->wq = nullptr; c->wws = nullptr; c->ws_stride = 0; c->parity = 0;
-  c->prof_ev = nullptr; c->prof_n = 0;
-  const size_t words = (size_t)((max_V + 31) / 32) + 1;
-  const size_t total_words = words + 1 + 2 + (size_t)simple::PEND_ROWS;
-  if (hipMalloc(reinterpret_cast<void**>(&c->hot_bits), total_words * sizeof(uint32_t)) != hipSuccess) {
+  c->prof_ev = nullptr; c->prof_n = 0; c->base = nullptr; c->slots = 0;
+  c->slots = (int)(max_B < (int64_t)simple::WIDE_SLOTS ? max_B : (int64_t)simple::WIDE_SLOTS);
+  const simple::CtxLayout CL = simple::ctx_layout(max_V, max_nnz_per_row, c->slots, lds, n_cu);
+  unsigned char* base = nullptr;
+  if (hipMalloc(reinterpret_cast<void**>(&base), CL.total) != hipSuccess) {
     delete c;
     return SIMPLE_ENOMEM;
   }
-  c->hot_flags = c->hot_bits + words;
-  c->pend = c->hot_flags + 1;
-  const size_t wq_bytes = 64 + 64 * (size_t)simple::WIDE_SLOTS;  // head, then one 64-byte record per slot
-  {  // a slot holds the fixed part and the largest history tables the single-pass kernel can have
-    const simple::FastLayout Fm = simple::make_fast_layout(max_V < ((int64_t)1 << 18) ? max_V : ((int64_t)1 << 18) - 1, SIMPLE_F32,
-                                                           max_nnz_per_row, max_nnz_per_row > 0, true, lds, (int64_t)1 << 30, c->n_cu);
-    const uint32_t tables = (max_nnz_per_row > 0 && Fm.total) ? Fm.cnt + (uint32_t)((max_nnz_per_row + 3) / 2) * 4u + 16u : 0u;
-    c->ws_stride = (simple::WIDE_SLOT_FIXED + tables + 63u) & ~63u;
-  }
-  if (hipMalloc(reinterpret_cast<void**>(&c->wq), wq_bytes + (size_t)c->ws_stride * (size_t)simple::WIDE_SLOTS) != hipSuccess) {
-    (void)hipFree(c->hot_bits);
-    delete c;
-    return SIMPLE_ENOMEM;
-  }
-  c->wws = reinterpret_cast<unsigned char*>(c->wq) + wq_bytes;
-  if (hipMemset(c->hot_bits, 0, total_words * sizeof(uint32_t)) != hipSuccess || hipMemset(c->wq, 0, wq_bytes) != hipSuccess) {
-    (void)hipFree(c->hot_bits);
-    (void)hipFree(c->wq);
+  c->base = base;
+  c->hot_bits = reinterpret_cast<uint32_t*>(base + CL.hot_bits);
+  c->hot_flags = reinterpret_cast<uint32_t*>(base + CL.hot_flags);
+  c->pend = reinterpret_cast<uint32_t*>(base + CL.pend);
+  c->wq = reinterpret_cast<uint32_t*>(base + CL.wq);
+  c->wws = base + CL.wws;
+  c->ws_stride = CL.ws_stride;
+  if (hipMemset(base, 0, CL.wws) != hipSuccess) {  // everything before the slots (a slot is cleared when a row takes it)
+    (void)hipFree(base);
     delete c;
     return SIMPLE_EDEVICE;
   }
@@ -171,8 +189,7 @@ void simple_destroy(simple_ctx* ctx) {
     if (guard.ok) {
       (void)hipDeviceSynchronize();
       if (ctx->prof_ev) (void)simple_profile_enable(ctx, 0);
-      if (ctx->hot_bits) (void)hipFree(ctx->hot_bits);
-      if (ctx->wq) (void)hipFree(ctx->wq);
+      if (ctx->base) (void)hipFree(ctx->base);
     }
   }
   delete ctx;
@@ -275,10 +292,10 @@ int simple_sample(simple_ctx* ctx, const void* logits_dev, int64_t B, int64_t V,
   a.max_nnz = (int)ctx->max_nnz;
   a.pend = ctx->pend;
   a.n_cu = ctx->n_cu;
-  a.wq = ctx->wq; a.wws = ctx->wws; a.wide_slots = simple::WIDE_SLOTS; a.ws_stride = ctx->ws_stride;
+  a.wq = ctx->wq; a.wws = ctx->wws; a.wide_slots = ctx->slots; a.ws_stride = ctx->ws_stride;
   a.L = simple::make_layout(V, ctx->max_nnz, hist_ptr_dev != nullptr);
   // rows go out in launches that neither queue can overflow
-  const int64_t per_launch = simple::PEND_ROWS < simple::WIDE_SLOTS ? simple::PEND_ROWS : simple::WIDE_SLOTS;
+  const int64_t per_launch = ctx->slots;
   a.F = simple::make_fast_layout(V, dtype, hist_ptr_dev ? ctx->max_nnz : 0, hist_ptr_dev != nullptr, vec, ctx->lds_limit,
                                  B < per_launch ? B : per_launch, ctx->n_cu);
   a.gated = (a.F.total != 0u) ? 1 : 0;

@@ -45,13 +45,16 @@ def test_null_context_and_bad_arguments_are_rejected_on_the_host():
     assert binding.simple_lds_bytes(0) == binding.SIMPLE_EINVAL
     binding.simple_destroy(None)  # accepted
     with pytest.raises(binding.SimpleError) as e:
-        binding.simple_create(0, 0, 0)  # max_V <= 0
+        binding.simple_create(0, 16, 0, 0)  # max_V <= 0
     assert e.value.code == binding.SIMPLE_EINVAL
     with pytest.raises(binding.SimpleError) as e:
-        binding.simple_create(0, 1024, 70000)  # counts are 16-bit
+        binding.simple_create(0, 0, 1024, 0)  # max_B <= 0
+    assert e.value.code == binding.SIMPLE_EINVAL
+    with pytest.raises(binding.SimpleError) as e:
+        binding.simple_create(0, 16, 1024, 70000)  # counts are 16-bit
     assert e.value.code == binding.SIMPLE_ECAPACITY
     with pytest.raises(binding.SimpleError):
-        binding.simple_create(-1, 1024, 0)
+        binding.simple_create(-1, 16, 1024, 0)
 
 
 def test_synthetic_configs_have_the_stated_shapes():
