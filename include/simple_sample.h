@@ -163,6 +163,31 @@ int simple_sample(simple_ctx* ctx, const void* logits_dev, int64_t B, int64_t V,
                   void* hip_stream);
 
 /*
+ * simple_sample for callers that cannot allocate device memory or create a context: code under HIP
+ * graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments and results as
+ * simple_sample, on the current HIP device, without a context: the row queues, the workspace slots
+ * and the hot-set bitmap live in a static device array of simple_static_limit(3) bytes (8 MiB) that
+ * each GPU the library runs on holds until the process ends.  Limits: V <= simple_static_limit(0)
+ * (2^18 - 1), at most simple_static_limit(1) (8192) history ids per row (a longer row gets id -1 and
+ * SIMPLE_DIAG_HISTORY_TOO_LONG), simple_static_limit(2) (64) rows per launch (a larger batch is
+ * served in several launches).  A hot set is passed with the call (hot_ids_dev, H > 0; H = -1 is
+ * SIMPLE_EINVAL) and its bitmap is rebuilt on the stream every time.  Returns SIMPLE_ECAPACITY for a
+ * larger V, else what simple_sample returns.  Calls no hipMalloc / hipFree or other allocating
+ * routine; the first call on a device looks up the array's address and the device's attributes.
+ * All calls on one GPU share the array: calls that overlap on one GPU (two streams, two host
+ * threads) race; issue them on one stream or order them with events.
+ */
+int simple_sample_static(const void* logits_dev, int64_t B, int64_t V, int dtype,
+                         int64_t row_stride_elems, const simple_row_params* params_dev,
+                         const int64_t* hist_ptr_dev, const int32_t* hist_ids_dev,
+                         const int32_t* hot_ids_dev, int32_t H, uint64_t seed, uint64_t step,
+                         uint64_t row_offset, int32_t* out_ids_dev, simple_row_diag* diag_dev,
+                         void* hip_stream);
+/* Limits of simple_sample_static: what = 0 max V, 1 max history ids per row, 2 rows per launch,
+ * 3 bytes of the static array; SIMPLE_EINVAL otherwise. */
+int64_t simple_static_limit(int what);
+
+/*
  * Timing aid for benchmarks (not part of the method): while enabled, every simple_sample call
  * brackets the launch of its dominant kernel (the single-pass row kernel when the call can use
  * it, else the general row kernel) with two HIP events on the call's stream.

@@ -30,6 +30,7 @@ ROW_DIAG_DTYPE = np.dtype([("alpha", "<f8"), ("s_k", "<f8"), ("p_chosen", "<f4")
 assert ROW_DIAG_DTYPE.itemsize == 32
 
 EXPORTS = ("simple_create", "simple_destroy", "simple_set_hot_set", "simple_sample",
+           "simple_sample_static", "simple_static_limit",
            "simple_profile_enable", "simple_profile_read", "simple_profile_read_launches",
            "simple_stream_probe",
            "simple_lds_bytes", "simple_strerror", "simple_version")

@@ -37,6 +37,11 @@ namespace simple {
 // pending-row queue (two counters, then one entry per row of a launch), the wide-row queue (a head,
 // then one 64-byte record per slot) and the slots.  Every part starts on a 256-byte boundary.
 struct CtxLayout { size_t hot_bits, hot_flags, pend, wq, wws, total; uint32_t ws_stride; };
+// Maxima of simple_sample_static, whose context lives in a static device array.
+constexpr int64_t STATIC_MAX_V = ((int64_t)1 << 18) - 1;
+constexpr int64_t STATIC_MAX_NNZ = 8192;
+constexpr int STATIC_SLOTS = 64;
+constexpr size_t STATIC_BYTES = (size_t)8 << 20;
 
 static uint32_t align16(uint32_t x) { return (x + 15u) & ~15u; }
 
@@ -315,6 +320,78 @@ int simple_sample(simple_ctx* ctx, const void* logits_dev, int64_t B, int64_t V,
     if (simple::launch_sample(a, dtype, vec, st, ev0, ev1) != hipSuccess) return SIMPLE_EDEVICE;
   }
   return SIMPLE_OK;
+}
+
+// ---- the entry point that allocates nothing -----------------------------------------------------
+// Its context memory is a static device array.  `scratch` is a host-side stand-in for the symbol: the
+// device address is taken once per device with hipGetSymbolAddress and used from then on.
+}  // extern "C"
+
+static __device__ __align__(256) unsigned char scratch[simple::STATIC_BYTES];
+
+namespace simple {
+constexpr int STATIC_MAX_DEVICES = 64;
+static simple_ctx g_static_ctx[STATIC_MAX_DEVICES];
+static bool g_static_ready[STATIC_MAX_DEVICES];
+
+// The static context of the current device, set up at the first call on it; null with *err set on failure.
+static simple_ctx* static_ctx(int* err) {
+  int device = -1;
+  if (hipGetDevice(&device) != hipSuccess || device < 0) { *err = SIMPLE_EDEVICE; return nullptr; }
+  if (device >= STATIC_MAX_DEVICES) { *err = SIMPLE_ECAPACITY; return nullptr; }
+  simple_ctx* c = &g_static_ctx[device];
+  if (g_static_ready[device]) return c;
+  int lds = 0, n_cu = 0;
+  if (hipDeviceGetAttribute(&lds, hipDeviceAttributeMaxSharedMemoryPerBlock, device) != hipSuccess ||
+      hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, device) != hipSuccess || n_cu <= 0) { *err = SIMPLE_EDEVICE; return nullptr; }
+  if (set_max_lds((unsigned)lds - 1024u) != hipSuccess || set_max_lds_fast((unsigned)lds - 1024u) != hipSuccess) { *err = SIMPLE_EDEVICE; return nullptr; }
+  const CtxLayout L = ctx_layout(STATIC_MAX_V, STATIC_MAX_NNZ, STATIC_SLOTS, lds, n_cu);
+  if (L.total > STATIC_BYTES) { *err = SIMPLE_ECAPACITY; return nullptr; }
+  unsigned char* ptr = nullptr;  // this device's copy of the array
+  if (hipGetSymbolAddress(reinterpret_cast<void**>(&ptr), HIP_SYMBOL(scratch)) != hipSuccess || !ptr) { *err = SIMPLE_EDEVICE; return nullptr; }
+  *c = simple_ctx();
+  c->device = device; c->max_V = STATIC_MAX_V; c->max_nnz = STATIC_MAX_NNZ; c->lds_limit = lds; c->n_cu = n_cu;
+  c->hot_bits = reinterpret_cast<uint32_t*>(ptr + L.hot_bits);
+  c->hot_flags = reinterpret_cast<uint32_t*>(ptr + L.hot_flags);
+  c->pend = reinterpret_cast<uint32_t*>(ptr + L.pend);
+  c->wq = reinterpret_cast<uint32_t*>(ptr + L.wq);
+  c->wws = ptr + L.wws;
+  c->ws_stride = L.ws_stride;
+  c->slots = STATIC_SLOTS;
+  // The array is zero when the code object is loaded, which is what the queue counters need at the
+  // first launch; afterwards every launch clears the pair of counters the previous one used, the
+  // hot-set bitmap is rebuilt by the call that passes a hot set, and a slot is cleared by the row
+  // that takes it.
+  g_static_ready[device] = true;
+  return c;
+}
+}  // namespace simple
+
+extern "C" {
+
+int simple_sample_static(const void* logits_dev, int64_t B, int64_t V, int dtype,
+                         int64_t row_stride_elems, const simple_row_params* params_dev,
+                         const int64_t* hist_ptr_dev, const int32_t* hist_ids_dev,
+                         const int32_t* hot_ids_dev, int32_t H, uint64_t seed, uint64_t step,
+                         uint64_t row_offset, int32_t* out_ids_dev, simple_row_diag* diag_dev,
+                         void* hip_stream) {
+  if (H == -1) return SIMPLE_EINVAL;  // no installed hot set here: pass the ids with the call
+  if (V > simple::STATIC_MAX_V) return SIMPLE_ECAPACITY;
+  int err = SIMPLE_OK;
+  simple_ctx* c = simple::static_ctx(&err);
+  if (!c) return err;
+  return simple_sample(c, logits_dev, B, V, dtype, row_stride_elems, params_dev, hist_ptr_dev, hist_ids_dev,
+                       hot_ids_dev, H, seed, step, row_offset, out_ids_dev, diag_dev, hip_stream);
+}
+
+int64_t simple_static_limit(int what) {
+  switch (what) {
+    case 0: return simple::STATIC_MAX_V;
+    case 1: return simple::STATIC_MAX_NNZ;
+    case 2: return (int64_t)simple::STATIC_SLOTS;
+    case 3: return (int64_t)simple::STATIC_BYTES;
+    default: return SIMPLE_EINVAL;
+  }
 }
 
 }  // extern "C"

@@ -55,6 +55,12 @@ def test_null_context_and_bad_arguments_are_rejected_on_the_host():
     assert e.value.code == binding.SIMPLE_ECAPACITY
     with pytest.raises(binding.SimpleError):
         binding.simple_create(-1, 16, 1024, 0)
+    # the entry point without a context: sizes beyond its static workspace, and a hot set by reference
+    assert binding.simple_static_limit(0) == 2 ** 18 - 1 and binding.simple_static_limit(3) == 8 << 20
+    assert binding.simple_static_limit(9) == binding.SIMPLE_EINVAL
+    V = binding.simple_static_limit(0) + 1
+    assert binding.simple_sample_static(0, 1, V, 0, V, 0, 0, 0, 0, 0, 1, 0, 0, 0, 0) == binding.SIMPLE_ECAPACITY
+    assert binding.simple_sample_static(0, 1, 8, 0, 8, 0, 0, 0, 0, -1, 1, 0, 0, 0, 0) == binding.SIMPLE_EINVAL
 
 
 def test_synthetic_configs_have_the_stated_shapes():
