@@ -37,16 +37,6 @@
 namespace simple {
 namespace fast {
 
-#ifdef SIMPLE_PHASE_TIMES  // profiling builds only: per-row phase timestamps (100 MHz wall clock)
-__device__ unsigned long long g_fast_phase_times[8192 * 32];
-#define FPHASE(i) do { if (threadIdx.x == 0 && blockIdx.x < 8192) g_fast_phase_times[blockIdx.x * 32 + (i)] = wall_clock64(); } while (0)
-#define FPHASE_HW() do { if (threadIdx.x == 0 && blockIdx.x < 8192) { g_fast_phase_times[blockIdx.x * 32 + 15] = __builtin_amdgcn_s_getreg(63492); g_fast_phase_times[blockIdx.x * 32 + 14] = __builtin_amdgcn_s_getreg(63508); } } while (0)
-#define FWHY(code) do { if (threadIdx.x == 0 && blockIdx.x < 8192) g_fast_phase_times[blockIdx.x * 32 + 13] = (code); } while (0)
-#else
-#define FPHASE_HW() do { } while (0)
-#define FPHASE(i) do { } while (0)
-#define FWHY(code) do { } while (0)
-#endif
 
 
 // A key t with need <= #{keys >= t} among the 64 x N keys held by a wave (N per lane), found by
@@ -157,7 +147,6 @@ __device__ inline void build_history(FS& S, const Hist& H, const int (&ids)[IDR]
   }
   if (bad) atomicOr(&S.flags, SIMPLE_DIAG_BAD_HISTORY_ID);
   __syncthreads();
-  FPHASE(7);
   // directory: exclusive scan of the word pairs' popcounts, NTHR * 8 pairs per round
   unsigned carry = 0;
   for (int p0 = 0; p0 < n_pairs; p0 += NTHR * 8) {
@@ -182,7 +171,6 @@ __device__ inline void build_history(FS& S, const Hist& H, const int (&ids)[IDR]
   }
   if (tid == 0) S.distinct = carry;
   __syncthreads();
-  FPHASE(8);
   n_prompt = min(max(n_prompt, 0), nnz);
   auto count_one = [&](int id) {
     if ((unsigned)id < (unsigned)V) {
@@ -289,9 +277,7 @@ __device__ __forceinline__ int finalize_small(FS& S, const RowCfg& R, unsigned n
     sc[r] = c;
     sw[r] = R.greedy ? 0ull : wfix((uint32_t)(c >> 32), y_max);
   }
-  FPHASE(21);
   __syncthreads();
-  FPHASE(22);
   if (wave == 0) {
     int rc = FIN_DONE;
     if (R.greedy) {
@@ -370,9 +356,7 @@ __device__ __forceinline__ int finalize_small(FS& S, const RowCfg& R, unsigned n
     }
     if (lane == 0) S.e_rc = rc;
   }
-  FPHASE(23);
   __syncthreads();
-  FPHASE(24);
   if (S.e_rc != FIN_DONE) return S.e_rc;
   dg.n_survivors = (int)S.e_n;
   if (R.greedy) { dg.p_chosen = 1.0f; return FIN_DONE; }
@@ -448,7 +432,7 @@ __device__ __forceinline__ int finalize_long(FS& S, const RowCfg& R, unsigned n,
     }
     __syncthreads();
     const unsigned nm = S.memb;
-    if (nm > (unsigned)MEMB2) { FWHY(201); return FIN_PENDING; }  // ties wider than the member table
+    if (nm > (unsigned)MEMB2) return FIN_PENDING;  // ties wider than the member table
     const unsigned need = S.need_k;
     for (unsigned mi = tid; mi < nm; mi += NTHR) {
       const u64 cm = mc[mi];
@@ -488,7 +472,7 @@ __device__ __forceinline__ int finalize_long(FS& S, const RowCfg& R, unsigned n,
       }
       __syncthreads();
       const unsigned nm = S.memb;
-      if (nm > (unsigned)MEMB2) { FWHY(202); return FIN_PENDING; }
+      if (nm > (unsigned)MEMB2) return FIN_PENDING;
       const u64 mab = S.mab_p;
       for (unsigned mi = tid; mi < nm; mi += NTHR) {
         const u64 cm = mc[mi], wm = mw[mi];
@@ -513,7 +497,7 @@ __device__ __forceinline__ int finalize_long(FS& S, const RowCfg& R, unsigned n,
   }
   const bool known = R.k_on || p_found || m_cert;
   if (!known) return (R.need_sum || (!R.k_on && !R.p_on && R.minp_on)) ? FIN_WIDE : FIN_PENDING;
-  if (R.k_on && R.p_on && !p_found) { FWHY(203); return FIN_PENDING; }  // cannot happen: the top-k prefix holds its own mass
+  if (R.k_on && R.p_on && !p_found) { return FIN_PENDING; }  // cannot happen: the top-k prefix holds its own mass
   u64 cut = cut_k;
   if (p_found && cut_p > cut) cut = cut_p;
   if (m_cert && cut_m > cut) cut = cut_m;
@@ -543,7 +527,7 @@ __device__ __forceinline__ int finalize_long(FS& S, const RowCfg& R, unsigned n,
   const double u = use_hot ? (pick_hot ? R.u_draw : R.u_tail) : R.u_draw;
   dg.n_survivors = (int)ns;
   dg.s_k = (double)S_k_fix / WSCALE;
-  if (S_cls == 0ull) { FWHY(204); return FIN_PENDING; }  // the chosen class holds no mass here: general kernel
+  if (S_cls == 0ull) { return FIN_PENDING; }  // the chosen class holds no mass here: general kernel
   // ---- inverse CDF in ascending token id: first id whose running mass exceeds u * S ----
   u64 tfix = (u64)__double2ull_rd(u * (double)S_cls);
   if (tfix >= S_cls) tfix = S_cls - 1ull;
@@ -565,7 +549,7 @@ __device__ __forceinline__ int finalize_long(FS& S, const RowCfg& R, unsigned n,
   }
   __syncthreads();
   const int bd = S.bd;
-  if (bd < 0) { FWHY(205); return FIN_PENDING; }  // cannot happen: tfix < S_cls
+  if (bd < 0) { return FIN_PENDING; }  // cannot happen: tfix < S_cls
   for (unsigned i = tid; i < n; i += NTHR) {
     if (in_class(lk[i], li[i]) && (int)(li[i] >> ishift) == bd) {
       const unsigned slot = atomicAdd(&S.memb, 1u);
@@ -575,7 +559,7 @@ __device__ __forceinline__ int finalize_long(FS& S, const RowCfg& R, unsigned n,
   __syncthreads();
   {
     const unsigned nm = S.memb;
-    if (nm > (unsigned)MEMB2) { FWHY(206); return FIN_PENDING; }
+    if (nm > (unsigned)MEMB2) return FIN_PENDING;
     const u64 mab = S.mab_d;
     for (unsigned mi = tid; mi < nm; mi += NTHR) {
       const u64 im = mc[mi], wm = mw[mi];
@@ -597,7 +581,7 @@ __device__ inline void queue_pending(const SampleArgs& a, int row) {
 
 // ---------------------------------------------------------------- the kernel ------------------
 template <typename DT, int NTHR>
-__global__ __launch_bounds__(NTHR, 4) void fast_rows_kernel(const SampleArgs a) {
+__global__ __launch_bounds__(NTHR, NTHR == 256 ? 4 : (NTHR == 512 ? 2 : 1)) void fast_rows_kernel(const SampleArgs a) {
   constexpr int NWV = NTHR / 64;
   constexpr int EPL = Io<DT>::EPL;
   constexpr int T = 64 * EPL * UNR;
@@ -619,8 +603,6 @@ __global__ __launch_bounds__(NTHR, 4) void fast_rows_kernel(const SampleArgs a) 
   for (int u = 0; u < UNR; ++u) Bf[u] = Io<DT>::load(rowp + (size_t)(t0 + 1) * T + u * 64 * EPL + lane * EPL);
   const simple_row_params par = a.params[row];
   if (row == 0 && tid == 0) { a.pend[a.parity ^ 1] = 0u; a.wq[a.parity ^ 1] = 0u; }  // the previous launch's counts
-  FPHASE(0);
-  FPHASE_HW();
   uint32_t* samp = reinterpret_cast<uint32_t*>(lds + a.F.samp);
 
   // ---- row configuration (identical in every thread) ----
@@ -655,7 +637,6 @@ __global__ __launch_bounds__(NTHR, 4) void fast_rows_kernel(const SampleArgs a) 
                                  : (!bad_par && !too_long && (!h_active || lowering) &&
                                     (R.greedy || !R.k_on || par.top_k <= KMAXF));
   if (!eligible) {  // the general kernel takes the row (it also reports parameter errors)
-    FWHY(1);
     if (tid == 0) queue_pending(a, row);
     return;
   }
@@ -694,7 +675,6 @@ __global__ __launch_bounds__(NTHR, 4) void fast_rows_kernel(const SampleArgs a) 
     }
   }
   const uint32_t* hot_bits = R.greedy ? nullptr : a.hot_bits;
-  FPHASE(1);
 
   // ---- threshold from the sample: three largest penalised values per lane, wave select, merge ----
   float a1 = -INFINITY, a2 = -INFINITY, a3 = -INFINITY;  // branch-free insertion; a NaN is ignored here
@@ -711,7 +691,6 @@ __global__ __launch_bounds__(NTHR, 4) void fast_rows_kernel(const SampleArgs a) 
     for (int e = 0; e < EPL; ++e) SIMPLE_TAKE3(z[e]);
   }
 #undef SIMPLE_TAKE3
-  FPHASE(9);
   // rank in the sample whose value leaves, with high probability, >= k_sel columns above it in the row
   const float m_exp = (float)k_sel * (float)(NWV * 2 * T) / (float)V;
   const unsigned r_samp = (unsigned)ceilf(1.15f * m_exp + 3.2f * sqrtf(m_exp) + 3.5f);
@@ -733,9 +712,7 @@ __global__ __launch_bounds__(NTHR, 4) void fast_rows_kernel(const SampleArgs a) 
     const float wp = wave_max(a1);
     if (lane == 0) { S.wmax[wave] = wp; S.wcnt[wave] = have; }
   }
-  FPHASE(10);
   __syncthreads();
-  FPHASE(11);
   StreamCtx C;
   {
     constexpr int NS = (NWV * SPW) / 64;
@@ -809,8 +786,6 @@ __global__ __launch_bounds__(NTHR, 4) void fast_rows_kernel(const SampleArgs a) 
   const unsigned cap = (unsigned)a.F.list_cap;
   uint32_t* li = lz + cap;
   u64 below_mass = 0ull;  // this thread's share of the mass below g (integer: the total is order-free)
-
-  FPHASE(2);
   // ---- the stream (raw logits) ----
   // Every wave starts with its two sample tiles (in registers).  With four waves per row each then
   // takes the rest of its contiguous share of the row; with more, the other tiles are handed out one
@@ -868,7 +843,6 @@ __global__ __launch_bounds__(NTHR, 4) void fast_rows_kernel(const SampleArgs a) 
       }
     }
   }
-  FPHASE(3);
   // the epilogue rebuilds the history tables: fetch the ids while the other waves finish
   int ids[IDR];
 #pragma unroll
@@ -883,7 +857,6 @@ __global__ __launch_bounds__(NTHR, 4) void fast_rows_kernel(const SampleArgs a) 
     }
   }
   __syncthreads();
-  FPHASE(4);
 
   // ---- epilogue ----
   simple_row_diag dg;
@@ -894,14 +867,12 @@ __global__ __launch_bounds__(NTHR, 4) void fast_rows_kernel(const SampleArgs a) 
   const unsigned n = S.cand_count;
   // the stream added 2^28 for every column at or above g: all of them were counted for the list
   if (C.need_sum && tid == 0) below_mass -= (u64)n << 28;
-  FWHY(2);
   if (n > cap && (R.need_sum || minp_only)) {
     // more columns at or above g than the list holds, and a cut that the whole-vocabulary routes
     // find without the list
     if (queue_wide(R.need_sum ? WIDE_TOP_P : WIDE_MIN_P, false)) return;
   }
   if (n <= cap) {
-    FWHY(0);
     // the list moves to registers; the region takes the history tables again
     float ez[PER]; uint32_t eid[PER];
 #pragma unroll
@@ -911,7 +882,6 @@ __global__ __launch_bounds__(NTHR, 4) void fast_rows_kernel(const SampleArgs a) 
       eid[j] = (i < n) ? li[i] : 0u;
     }
     __syncthreads();
-    FPHASE(12);
     if (H.active) {
       unsigned own = 0u;
       build_history<NTHR>(S, H, ids, hist, nnz, par.n_prompt, V, own);
@@ -920,7 +890,6 @@ __global__ __launch_bounds__(NTHR, 4) void fast_rows_kernel(const SampleArgs a) 
         const unsigned i = (unsigned)tid + (unsigned)j * NTHR;
         if (i < n) ez[j] = H.penalised_at(ez[j], (int)eid[j]);
       }
-      FPHASE(16);
       if (R.need_sum) {
         // exact correction of the mass below g for the history columns (the stream summed their raw
         // values), once per distinct column: by the thread that first marked it when all ids sit in
@@ -968,7 +937,6 @@ __global__ __launch_bounds__(NTHR, 4) void fast_rows_kernel(const SampleArgs a) 
       }
       __syncthreads();
     }
-    FPHASE(17);
     // keys of the tempered values; listed columns that fell below g return to the mass below g
     uint32_t key[PER];
     bool err = false, peaked = false;
@@ -1003,7 +971,6 @@ __global__ __launch_bounds__(NTHR, 4) void fast_rows_kernel(const SampleArgs a) 
     if (err) atomicOr(&S.flags, SIMPLE_DIAG_ERROR | SIMPLE_DIAG_BAD_LOGIT);
     if (peaked) atomicOr(&S.flags, 1u << 30);
     __syncthreads();
-    FPHASE(18);
     // mass below g (integer, exact) and the decision between the list and the kernels that follow
     u64 S_below_int = 0ull, M_list = 0ull, M_cert = 0ull;
     bool wide = false;
@@ -1016,14 +983,12 @@ __global__ __launch_bounds__(NTHR, 4) void fast_rows_kernel(const SampleArgs a) 
     }
     const double S_below = (double)S_below_int / (double)MSCALE;
     const uint32_t kmax = S.kmax;
-    FPHASE(19);
     bool tables_live = false;  // the region still holds the history tables
     if (S.flags & SIMPLE_DIAG_ERROR) rc = FIN_DONE;
-    else if (kmax <= key_g || kmax <= KEY_NEG_INF) { rc = FIN_PENDING; FWHY(3); }
+    else if (kmax <= key_g || kmax <= KEY_NEG_INF) rc = FIN_PENDING;
     else if (wide) {
       rc = ((S.flags >> 30) & 1u) ? FIN_PENDING : FIN_WIDE;
       tables_live = true;
-      if (rc == FIN_PENDING) FWHY(4);
     } else {
       // certified entries (tempered value strictly above fl(g / tau)) as composites
       u64* mc = reinterpret_cast<u64*>(lds);                       // MEMB * 8
@@ -1042,11 +1007,9 @@ __global__ __launch_bounds__(NTHR, 4) void fast_rows_kernel(const SampleArgs a) 
       if (nul) atomicAdd(&S.nunc, nul);
       __syncthreads();
       const unsigned n_cert = S.n2, n_unc = S.nunc;
-      FPHASE(20);
-      if (R.k_on && !R.greedy && n_cert < (unsigned)R.top_k) { rc = FIN_PENDING; FWHY(5); }  // the sampled threshold admitted too few
+      if (R.k_on && !R.greedy && n_cert < (unsigned)R.top_k) rc = FIN_PENDING;  // the sampled threshold admitted too few
       else if (n_cert <= (unsigned)MEMB) {
         rc = finalize_small<NTHR>(S, R, n_cert, n_unc, kmax, key_g, C.g, S_below, mc, sc, sw, sid, hot_bits, dg);
-        if (rc != FIN_DONE) FWHY(7);
       } else if (n_cert <= (unsigned)a.F.long_cap) {
         // long list: keys and ids go back to the region, the bucket tables behind them
         const unsigned lcap = (unsigned)a.F.long_cap;
@@ -1062,7 +1025,6 @@ __global__ __launch_bounds__(NTHR, 4) void fast_rows_kernel(const SampleArgs a) 
         __syncthreads();
         rc = finalize_long<NTHR>(S, R, n_cert, n_unc, kmax, key_g, C.g, S_below, lk, lid, lds + (size_t)lcap * 8u, hot_bits, dg);
       }
-      else FWHY(6);
       if (rc == FIN_WIDE && ((S.flags >> 30) & 1u)) rc = FIN_PENDING;
     }
 
@@ -1072,8 +1034,6 @@ __global__ __launch_bounds__(NTHR, 4) void fast_rows_kernel(const SampleArgs a) 
       rc = FIN_PENDING;  // no free slot: the general kernel takes the row
     }
   }
-  FPHASE(5);
-  FPHASE(6);
   if (tid == 0) {
     if (rc != FIN_DONE) {
       queue_pending(a, row);
@@ -1093,11 +1053,6 @@ __global__ __launch_bounds__(NTHR, 4) void fast_rows_kernel(const SampleArgs a) 
 }  // namespace fast
 
 }  // namespace simple
-#ifdef SIMPLE_PHASE_TIMES
-extern "C" int simple_debug_fast_phase_times(unsigned long long* dst_host, int n_rows) {
-  return (int)hipMemcpyFromSymbol(dst_host, HIP_SYMBOL(simple::fast::g_fast_phase_times), sizeof(unsigned long long) * 32 * (size_t)n_rows);
-}
-#endif
 namespace simple {
 
 hipError_t launch_fast(const SampleArgs& a, int dtype, hipStream_t st) {

@@ -22,12 +22,6 @@
 
 namespace simple {
 
-#ifdef SIMPLE_PHASE_TIMES  // profiling builds only: per-row phase timestamps (100 MHz wall clock)
-__device__ unsigned long long g_phase_times[8192 * 16];
-#define PHASE_MARK(i) do { if (threadIdx.x == 0 && blockIdx.x < 8192) g_phase_times[blockIdx.x * 16 + (i)] = wall_clock64(); } while (0)
-#else
-#define PHASE_MARK(i) do { } while (0)
-#endif
 
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
@@ -675,7 +669,6 @@ __device__ inline int sampled_route(const DT* __restrict__ rowp, int V, const Hi
   }
   if (tid == 0) { S.cand_count = kept; S.n_conv = kept; }
   __syncthreads();
-  PHASE_MARK(2);
   g = S.g_pass;
   if (!sampled_all) {
     for (int ti = wave; ti < ntiles; ti += NW) {
@@ -683,10 +676,8 @@ __device__ inline int sampled_route(const DT* __restrict__ rowp, int V, const Hi
       process_tile<DT, VEC, FULL, false>(rowp, ti * T, V, g, H, need_sum, E, S, ck, ci);
     }
   }
-  PHASE_MARK(3);
   if (FULL && H.active) history_columns<DT>(rowp, H, g, need_sum, E, S, ck, ci);
   __syncthreads();
-  PHASE_MARK(4);
   const unsigned total = S.cand_count;
   if (total > (unsigned)CAP) return ROUTE_RETRY;
   convert_entries(S, ck, ci, kept, total, H, !FULL);
@@ -704,7 +695,6 @@ __device__ inline int sampled_route(const DT* __restrict__ rowp, int V, const Hi
   const double S_total = need_sum ? combine_exp_sums(S, E) : 0.0;
   __syncthreads();
   const bool complete = exact_k || (sampled_all && L <= (unsigned)KMAX);
-  PHASE_MARK(5);
   return finalize_small(S, ck, ci, complete, S_total, U, hot_bits, dg) ? ROUTE_DONE : ROUTE_UNCERTIFIED;
 }
 
@@ -1039,8 +1029,6 @@ __device__ __noinline__ Cut descend(const RowReader<DT>& R_in, Shared& S, uint32
       listed = collect && (S.list_n <= LIST_CAP);
     }
     __syncthreads();
-    if (lvl == 0) PHASE_MARK(13);
-    if (lvl == 1) PHASE_MARK(14);
     if (lim && tid == 0 && (lvl == 0 || (lim->t >> (shift + w)) == prefix)) {
       const unsigned d = (lim->t >> shift) & ((1u << w) - 1u);  // ties beyond the limit's r do not count
       hcnt[d] -= (lim->cnt_eq - lim->r);
@@ -1126,7 +1114,6 @@ __device__ __noinline__ void wide_route(const RowReader<DT>& R_in, Shared& S, ui
     __syncthreads();
   }
   const uint32_t maxkey = uni((uint32_t)S.found_hi);
-  PHASE_MARK(8);
   if (S.flag_ws || maxkey <= KEY_NEG_INF) { if (tid == 0) S.flags |= SIMPLE_DIAG_ERROR | SIMPLE_DIAG_BAD_LOGIT; return; }
   const float ymax = uni(keyf(maxkey));
   if (S.greedy) {  // lowest id attaining the maximum
@@ -1147,7 +1134,6 @@ __device__ __noinline__ void wide_route(const RowReader<DT>& R_in, Shared& S, ui
     scan_row_raw<DT, VEC>(R, [&](float z, int) { if (z >= z_thr) ++c_ge; });
     n_m = block_sum(c_ge, S.scan_u32);
   }
-  PHASE_MARK(9);
   // top-k prefix
   Cut ck_;
   if (S.k_on) {
@@ -1156,7 +1142,6 @@ __device__ __noinline__ void wide_route(const RowReader<DT>& R_in, Shared& S, ui
     ck_.r = (uint32_t)S.top_k - ck_.cnt_gt;
   }
   const unsigned n_k = S.k_on ? (unsigned)S.top_k : (unsigned)V;
-  PHASE_MARK(10);
   // nucleus inside the top-k prefix; the descent also measures S_k, the mass of that prefix
   Cut cp_; unsigned n_p = n_k;
   bool have_p = false;
@@ -1204,7 +1189,6 @@ __device__ __noinline__ void wide_route(const RowReader<DT>& R_in, Shared& S, ui
   dg.n_survivors = (int)n;
   dg.s_k = (double)S_k * (1.0 / (double)(1ull << QBITS));
   __syncthreads();
-  PHASE_MARK(11);
   // pass F1: per-chunk survivor mass (class 0 = tail / everything, class 1 = hot) and tie counts
   const bool use_hot = hot_bits != nullptr;
   // (an aligned row of up to 2^20 columns: a chunk is one group of the vector stream)
@@ -1272,7 +1256,6 @@ __device__ __noinline__ void wide_route(const RowReader<DT>& R_in, Shared& S, ui
     }
   });
   __syncthreads();
-  PHASE_MARK(12);
   // which chunk holds the r-th tie (ties are admitted in ascending id)
   if (tid == 0) {
     int tc = NC;  // all ties admitted
@@ -1407,7 +1390,6 @@ __device__ inline void sample_row_body(const SampleArgs& a, const int row, unsig
   simple_row_diag dg;
   dg.alpha = __longlong_as_double(0x7FF8000000000000ll);
   dg.s_k = 0.0; dg.p_chosen = 0.0f; dg.n_survivors = 0; dg.flags = a.gated ? SIMPLE_DIAG_GENERAL : 0u; dg.reserved = 0u;
-  PHASE_MARK(0);
 
   // ---- row configuration (identical in every thread) ----
   const bool bad_par = !(par.temperature >= 0.0f) || !(par.rep_penalty > 0.0f);
@@ -1451,7 +1433,6 @@ __device__ inline void sample_row_body(const SampleArgs& a, const int row, unsig
   }
   if (a.hot_bits && a.hot_flags && *a.hot_flags) dg.flags |= SIMPLE_DIAG_BAD_HOT_SET;
   const uint32_t* hot_bits = greedy ? nullptr : a.hot_bits;
-  PHASE_MARK(1);
 
   Draws U;
   { double u[3]; row_uniforms(a.seed, a.row_offset + (uint64_t)row, a.step, u); U.u_draw = u[0]; U.u_acc = u[1]; U.u_tail = u[2]; }
@@ -1516,7 +1497,6 @@ __device__ inline void sample_row_body(const SampleArgs& a, const int row, unsig
     }
     __syncthreads();
   }
-  PHASE_MARK(6);
   if (!done) {
     dg.flags |= SIMPLE_DIAG_WIDE;
     RowReader<DT> R{rowp, V, S.tau, greedy, &H};
@@ -1533,7 +1513,6 @@ __device__ inline void sample_row_body(const SampleArgs& a, const int row, unsig
       a.diag[row] = dg;
     }
   }
-  PHASE_MARK(7);
 }
 
 template <typename DT, bool VEC>
@@ -1544,17 +1523,27 @@ __global__ __launch_bounds__(NT, 4) void sample_rows_kernel(const SampleArgs a) 
 }
 
 // Completes the rows the single-pass kernel queued: workgroup i takes queue entries i, i + grid, ...
-// The next launch's single-pass kernel clears the count.
+// The next launch's single-pass kernel clears the count.  The queue is empty in the common case, so
+// the count is looked at first.  The row body takes the arguments by reference; handing it the
+// by-value parameter would make every lane of every launch copy the whole record to scratch memory
+// at the kernel's entry (220 bytes a lane, 28 MB a launch), so it gets the record where the launch
+// placed it, in the kernel-argument segment (the record is the kernel's only parameter).
 template <typename DT, bool VEC>
-__global__ __launch_bounds__(NT, 4) void pending_rows_kernel(const SampleArgs a) {
-  extern __shared__ __align__(16) unsigned char lds[];
-  __shared__ Shared S;
-  const unsigned n = min(__hip_atomic_load(&a.pend[a.parity], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT), (unsigned)a.B);
+__device__ __noinline__ void pending_rows_body(const SampleArgs& a, unsigned n, unsigned char* lds, Shared& S) {
   for (unsigned i = blockIdx.x; i < n; i += gridDim.x) {
     const int row = (int)a.pend[2 + i];
     if (row >= 0 && row < a.B) sample_row_body<DT, VEC>(a, row, lds, S);
     __syncthreads();
   }
+}
+template <typename DT, bool VEC>
+__global__ __launch_bounds__(NT, 4) void pending_rows_kernel(const SampleArgs a) {
+  extern __shared__ __align__(16) unsigned char lds[];
+  __shared__ Shared S;
+  const unsigned n = min(__hip_atomic_load(&a.pend[a.parity], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT), (unsigned)a.B);
+  if (blockIdx.x >= n) return;
+  const SampleArgs* in_place = (const SampleArgs*)__builtin_amdgcn_kernarg_segment_ptr();
+  pending_rows_body<DT, VEC>(*in_place, n, lds, S);
 }
 
 // Hot-set membership bitmap (section 5.3): V bits, built from the id list.
@@ -1574,11 +1563,6 @@ __global__ void hot_scatter_kernel(const int32_t* __restrict__ ids, int H, int V
 
 }  // namespace simple
 
-#ifdef SIMPLE_PHASE_TIMES
-extern "C" int simple_debug_phase_times(unsigned long long* dst_host, int n_rows) {
-  return (int)hipMemcpyFromSymbol(dst_host, HIP_SYMBOL(simple::g_phase_times), sizeof(unsigned long long) * 16 * (size_t)n_rows);
-}
-#endif
 
 // ------------------------------------------------------------------ launchers ------------------
 namespace simple {

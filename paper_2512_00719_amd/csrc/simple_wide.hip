@@ -48,23 +48,6 @@
 namespace simple {
 namespace fast {
 
-#ifdef SIMPLE_PHASE_TIMES  // profiling builds only: per-workgroup timestamps of the first kernel (100 MHz wall clock)
-__device__ unsigned long long g_wide_phase_times[3 * 8192 * 8];
-#define XPHASE(i) do { if (threadIdx.x == 0 && blockIdx.x < 8192) g_wide_phase_times[(8192 + blockIdx.x) * 8 + (i)] = wall_clock64(); } while (0)
-#define XWHY(code, v) do { if (threadIdx.x == 0 && blockIdx.x < 8192) { g_wide_phase_times[(8192 + blockIdx.x) * 8 + 6] = (code); g_wide_phase_times[(8192 + blockIdx.x) * 8 + 7] = (v); } } while (0)
-#define WPHASE(i) do { if (threadIdx.x == 0 && blockIdx.x < 8192) g_wide_phase_times[blockIdx.x * 8 + (i)] = wall_clock64(); } while (0)
-// classify: time per phase summed over a workgroup's items (wave 0's clock)
-#define CACC_INIT() unsigned long long pacc_[8] = {0, 0, 0, 0, 0, 0, 0, 0}; unsigned long long plast_ = wall_clock64()
-#define CACC(i) do { const unsigned long long t_ = wall_clock64(); pacc_[i] += t_ - plast_; plast_ = t_; } while (0)
-#define CACC_DUMP() do { if (threadIdx.x == 0 && blockIdx.x < 8192) for (int q_ = 0; q_ < 8; ++q_) g_wide_phase_times[(16384 + blockIdx.x) * 8 + q_] = pacc_[q_]; } while (0)
-#else
-#define CACC_INIT() do { } while (0)
-#define CACC(i) do { } while (0)
-#define CACC_DUMP() do { } while (0)
-#define WPHASE(i) do { } while (0)
-#define XPHASE(i) do { } while (0)
-#define XWHY(code, v) do { } while (0)
-#endif
 
 constexpr int WT = 256;      // threads per workgroup
 constexpr int WNW = WT / 64;
@@ -470,10 +453,6 @@ __global__ __launch_bounds__(WT, 5) void wide_bins_kernel(const SampleArgs a) {
   static_assert((WT * EPL) % 32 == 0, "group stride in mask words");
   const Items I = my_items(a);
   if (I.i0 >= I.i1) return;
-  WPHASE(0);
-#ifdef SIMPLE_PHASE_TIMES
-  if (threadIdx.x == 0 && blockIdx.x < 8192) { g_wide_phase_times[blockIdx.x * 8 + 5] = __builtin_amdgcn_s_getreg(63492); g_wide_phase_times[blockIdx.x * 8 + 6] = __builtin_amdgcn_s_getreg(63508); }
-#endif
   const unsigned n_wide = min(as_global(a.wq)[a.parity], (unsigned)a.wide_slots);
   int cur = (int)(I.i0 / I.n_sl);
   SlotIds ids;
@@ -528,7 +507,6 @@ __global__ __launch_bounds__(WT, 5) void wide_bins_kernel(const SampleArgs a) {
       continue;
     }
     const DT* rowp = reinterpret_cast<const DT*>(a.logits) + (size_t)W.row * (size_t)a.stride;
-    WPHASE(1);
     HistPre<DT> HP;
     if (W.h_active) {
       slice_store(Tb, L.pre, a, c0, W.distinct);
@@ -536,7 +514,6 @@ __global__ __launch_bounds__(WT, 5) void wide_bins_kernel(const SampleArgs a) {
       hist_fetch<DT>(HP, Tb, W.ws, a, rowp, c0, V);  // this item's own loads go first: loads return in order
     } else __syncthreads();  // the zeroed bins are visible
     if (more) item_fetch<DT, false, true>(N, a, it + 1u, I.n_sl, cur, ids);
-    WPHASE(2);
     auto one = [&](float z, int) {
       if (W.mode == WIDE_MIN_P) { ymax = fmaxf(ymax, tempered(z, W.C)); return; }
       int b; float y;
@@ -616,10 +593,8 @@ __global__ __launch_bounds__(WT, 5) void wide_bins_kernel(const SampleArgs a) {
       hist_columns<DT>(Tb, W, rowp, c0, V, one);
       __syncthreads();  // the tables are rewritten by the next item
     }
-    WPHASE(3);
   }
   flush();
-  WPHASE(4);
 }
 
 // ---------------------------------------------------------------- classify --------------------
@@ -642,7 +617,6 @@ __global__ __launch_bounds__(WT, 4) void wide_classify_kernel(const SampleArgs a
   const Items I = my_items(a);
   if (I.i0 >= I.i1) return;
   const uint32_t* hot_bits = a.hot_bits;
-  CACC_INIT();
   const unsigned n_wide = min(as_global(a.wq)[a.parity], (unsigned)a.wide_slots);
   int cur = (int)(I.i0 / I.n_sl);
   SlotIds ids;
@@ -703,7 +677,6 @@ __global__ __launch_bounds__(WT, 4) void wide_classify_kernel(const SampleArgs a
   };
   if (tid == 0) l_n = 0u;
   enter_row(cur);
-  CACC(7);
   for (unsigned it = I.i0; it < I.i1; ++it) {
     const int slot = (int)(it / I.n_sl), sl = (int)(it % I.n_sl);
     const ItemLoads<DT> L = N;
@@ -714,7 +687,6 @@ __global__ __launch_bounds__(WT, 4) void wide_classify_kernel(const SampleArgs a
       ids.row_c = ids.row_n; ids.act_c = ids.act_n;
       ids.request(a, (unsigned)slot + 1u, n_wide, ids.row_n, ids.act_n);
       enter_row(slot);
-      CACC(7);
     }
     if (!valid) {  // the finishing kernel hands the row on
       if (more) item_fetch<DT, use_hot>(N, a, it + 1u, I.n_sl, cur, ids);
@@ -722,15 +694,12 @@ __global__ __launch_bounds__(WT, 4) void wide_classify_kernel(const SampleArgs a
     }
     const int c0 = sl * SLC;
     const DT* rowp = reinterpret_cast<const DT*>(a.logits) + (size_t)W.row * (size_t)a.stride;
-    CACC(0);
     if (tid < 2) ltile[tid] = 0ull;
     if (W.h_active) slice_store(Tb, L.pre, a, c0, W.distinct);
     __syncthreads();
-    CACC(1);
     HistPre<DT> HP;
     if (W.h_active) hist_fetch<DT>(HP, Tb, W.ws, a, rowp, c0, V);  // this item's own loads go first: loads return in order
     if (more) item_fetch<DT, use_hot>(N, a, it + 1u, I.n_sl, cur, ids);
-    CACC(2);
     u64 acc_s = 0ull, acc1 = 0ull;  // this slice: mass of the sure columns, and of the hot ones among them
     // one column the slow way: history columns and the ragged end of the row
     auto one = [&](float z, int idx) {
@@ -822,27 +791,22 @@ __global__ __launch_bounds__(WT, 4) void wide_classify_kernel(const SampleArgs a
     } else {
       if (W.mode == WIDE_TOP_P || W.mode == WIDE_TOP_K) sweep(no, no, no); else if (W.mode == WIDE_ALL) sweep(no, yes, yes); else sweep(no, yes, no);
     }
-    CACC(3);
     if (W.h_active) {  // the history columns, whose logits and counts were requested before the main line
       hist_stage<DT>(Tb, HP, W.ws, a, rowp, c0, V);
       __syncthreads();
       hist_columns<DT>(Tb, W, rowp, c0, V, one);
     }
-    CACC(4);
     {
       const u64 s0 = wave_sum(acc_s - acc1);
       if (lane == 0 && s0) atomicAdd(&ltile[0], s0);
       if (use_hot) { const u64 s1 = wave_sum(acc1); if (lane == 0 && s1) atomicAdd(&ltile[1], s1); }
     }
     __syncthreads();  // the tile sums and this slice's appends are complete
-    CACC(5);
     if (tid < 2 && sl < 256) reinterpret_cast<u64*>(W.ws + WS_TILES)[tid * 256 + sl] = ltile[tid];
     // every slice may add ICAP boundary columns before the stage has to be written out
     if (l_n > (unsigned)(LCAP - ICAP)) list_out();
-    CACC(6);
   }
   leave_row();
-  CACC_DUMP();
 }
 
 // ---------------------------------------------------------------- finish ----------------------
@@ -873,19 +837,17 @@ __device__ inline bool finish_row(const SampleArgs& a, const WideRow& W, FS& S, 
 #pragma unroll
   for (int k = 0; k < 2; ++k) tv[k] = as_global(reinterpret_cast<const u64*>(W.ws + WS_TILES))[k * WT + tid];
   const uint32_t kmax = as_global(sc)[6];
-  XPHASE(0);
   const RowCut rcut = row_cut(S, W);
   const int bstar = rcut.bstar;
   const float thr_y = rcut.thr_y;
-  XPHASE(1);
-  if (!rcut.valid) { XWHY(1, 0); return false; }
+  if (!rcut.valid) { return false; }
   const bool top_p_route = W.mode == WIDE_TOP_P, top_k_route = W.mode == WIDE_TOP_K;
   const bool cut_route = top_p_route || top_k_route;  // a cut inside a bin: by mass, or by count
   const u64 S_tot = top_p_route ? rcut.s_tot : S_sum;  // exact mass of the row (from the bins where there are bins)
   // a count past the limit is also how the classifying pass reports a row it could not handle; no
   // collected column on the top-p route means that a min-p cut ended the survivors above the bin
   const bool minp_too = top_p_route && W.min_p > 0.0f;
-  if (n_r > (unsigned)RCAP || (!cut_route && n_r != 0u) || (cut_route && n_r == 0u && !minp_too)) { XWHY(2, n_r); return false; }
+  if (n_r > (unsigned)RCAP || (!cut_route && n_r != 0u) || (cut_route && n_r == 0u && !minp_too)) { return false; }
   if (tid == 0) { S.bd = -1; S.cut_k = 0ull; S.cut_p = ~0ull; S.out_id = -1; S.out_w = 0ull; }
   tiles[tid] = tv[0]; tiles[WT + tid] = tv[1];
   const u64 msure = tv[0] + tv[1];
@@ -898,7 +860,7 @@ __device__ inline bool finish_row(const SampleArgs& a, const WideRow& W, FS& S, 
   const u64 m_sure = blk_sum_u64<WNW>(S, msure);  // barriers inside
   const u64 m_above = top_k_route ? (u64)n_sure : m_sure;
   const u64 target = top_k_route ? (u64)W.top_k : (u64)__double2ull_ru((double)W.top_p * (double)S_tot);
-  if (m_above >= target) { XWHY(3, 0); return false; }
+  if (m_above >= target) { return false; }
   // -- the boundary bin, exactly: shortest prefix in the total order whose mass reaches the target --
   {
     u64 cmax_t = 0ull, cmin_t = ~0ull;
@@ -964,11 +926,10 @@ __device__ inline bool finish_row(const SampleArgs& a, const WideRow& W, FS& S, 
     if (differ == 0ull && m_above + (top_k_route ? 1ull : (u64)rl[0]) < target) ok = false;  // a single column, and it does not reach the target
     // the collected columns do not reach the target: with a min-p cut those below it were never
     // collected, and the min-p prefix is the shorter one (all collected columns survive)
-    if (!ok && !minp_too) { XWHY(4, 0); return false; }
+    if (!ok && !minp_too) { return false; }
     cut_found = ok ? prefix : 1ull;
   }
-  XPHASE(2);
-  if (cut_found == 0ull) { XWHY(6, 0); return false; }
+  if (cut_found == 0ull) { return false; }
   for (unsigned t = tid; t < n_r; t += WT) {
     if (rcmp[t] >= cut_found) {
       const uint32_t id = 0xFFFFFFFFu - (uint32_t)rcmp[t];
@@ -981,7 +942,7 @@ __device__ inline bool finish_row(const SampleArgs& a, const WideRow& W, FS& S, 
   const u64 cut_c = cut_found;
   unsigned ns = r_in + (tid == 0 ? n_sure : 0u), dz = 0; u64 mx = 0ull, dsum = 0ull;
   blk_reduce<WNW>(S, ns, dz, mx, dsum);  // barriers inside: the tile masses are complete after it
-  if (top_k_route && ns != (unsigned)W.top_k) { XWHY(5, ns); return false; }  // the passes disagree
+  if (top_k_route && ns != (unsigned)W.top_k) { return false; }  // the passes disagree
   // -- masses of the classes, acceptance (section 5.3), the tile that holds the draw --
   u64 p0 = 0ull, p1 = 0ull;
   for (int i = tid; i < 256; i += WT) { p0 += tiles[i]; p1 += tiles[256 + i]; }
@@ -999,7 +960,7 @@ __device__ inline bool finish_row(const SampleArgs& a, const WideRow& W, FS& S, 
   const double u = use_hot ? (pick_hot ? u3[0] : u3[2]) : u3[0];
   dg.n_survivors = (int)ns;
   dg.s_k = (double)(top_k_route ? S_K : S_tot) / (double)MSCALE * exp((double)C.y_g - (double)keyf(kmax));
-  if (S_cls == 0ull) { XWHY(7, 0); return false; }
+  if (S_cls == 0ull) { return false; }
   u64 tfix = (u64)__double2ull_rd(u * (double)S_cls);
   if (tfix >= S_cls) tfix = S_cls - 1ull;
   {
@@ -1010,15 +971,13 @@ __device__ inline bool finish_row(const SampleArgs& a, const WideRow& W, FS& S, 
   }
   __syncthreads();
   const int tstar = S.bd;
-  XPHASE(3);
-  if (tstar < 0) { XWHY(8, 0); return false; }
+  if (tstar < 0) { return false; }
   // -- the drawn id inside one tile --
   const int c0 = tstar * T;
   float zv[EPT];  // requested before the tables' barriers
 #pragma unroll
   for (int e = 0; e < EPT; ++e) { const int idx = c0 + tid * EPT + e; zv[e] = (idx < V) ? Io<DT>::one(rowp + idx) : 0.0f; }
   if (W.h_active) load_slice(Tb, W, a, c0);
-  XPHASE(4);
   u64 mloc[EPT]; u64 lsum = 0ull;
 #pragma unroll
   for (int e = 0; e < EPT; ++e) {
@@ -1049,7 +1008,6 @@ __device__ inline bool finish_row(const SampleArgs& a, const WideRow& W, FS& S, 
   }
   __syncthreads();
   dg.p_chosen = (float)((double)S.out_w / (double)S_K);
-  XPHASE(5);
   return S.out_id >= 0;
 }
 
@@ -1084,11 +1042,6 @@ __global__ __launch_bounds__(WT) void wide_finish_kernel(const SampleArgs a) {
 
 }  // namespace fast
 
-#ifdef SIMPLE_PHASE_TIMES
-extern "C" int simple_debug_wide_phase_times(unsigned long long* dst_host, int n) {
-  return (int)hipMemcpyFromSymbol(dst_host, HIP_SYMBOL(simple::fast::g_wide_phase_times), sizeof(unsigned long long) * 8 * (size_t)n);  // n <= 3 * 8192
-}
-#endif
 
 hipError_t launch_wide(const SampleArgs& a, int dtype, hipStream_t st) {
   // One resident round of workgroups each: six (bins) and five (classify) per compute unit fit by
