@@ -7,6 +7,10 @@ Default workload: B=1024, V=128,256, fp32, heterogeneous per-row controls, 4096 
 row (the configuration the headline metric is quoted on).  Prints ONE JSON line on stdout.
 
   python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 2|3|4|5] [--H N] [--no-cpu-baseline]
+                  [--all-configs]
+
+--all-configs also runs C2, C4 (at each hot-set size of its sweep) and C5 for a few steps and prints
+one JSON line per run on stderr; stdout stays the one line of the headline configuration.
 """
 from __future__ import annotations
 
@@ -112,6 +116,14 @@ def cpu_baseline(w, budget_s: float = 10.0) -> dict:
     return out
 
 
+METRIC = {
+    2: "sampled rows/sec + achieved HBM GB/s (fraction of peak), B=256 V=151,936 bf16",
+    3: "sampled rows/sec + achieved HBM GB/s (fraction of peak), B=1024 V=128,256 fp32",
+    4: "sampled rows/sec + achieved HBM GB/s (fraction of peak), B=512 V=201,088 bf16, SHVS",
+    5: "sampled rows/sec + achieved HBM GB/s (fraction of peak), B=4096 V=256,000 bf16, SHVS H=16,384",
+}
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -121,6 +133,7 @@ def main() -> int:
     ap.add_argument("--H", type=int, default=None, help="hot-set size for configs 4 and 5")
     ap.add_argument("--copies", type=int, default=0, help="distinct input copies to rotate over (0 = auto: >= 1 GiB)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--all-configs", action="store_true", help="also run C2, C4 (H sweep) and C5 briefly; their lines go to stderr")
     ap.add_argument("--copy-probe-mib", type=int, default=0,
                     help="after the timed region, run one plain device copy of this many MiB (a kernel of known "
                          "HBM traffic, to scale rocprofv3 FETCH_SIZE / WRITE_SIZE readings)")
@@ -130,11 +143,23 @@ def main() -> int:
               "(rows are independent: N GPUs would each take B / N rows and call it unchanged)", file=sys.stderr)
         return 2
 
+    result = run_config(args, args.config, args.H, args.steps, args.warmup, not args.no_cpu_baseline)
+    if args.all_configs:
+        for cfg, H in ((2, None), (4, 4096), (4, 8192), (4, 16384), (4, 32768), (5, None)):
+            if cfg == args.config and H == args.H:
+                continue
+            r = run_config(args, cfg, H, min(args.steps, 50), min(args.warmup, 10), False)
+            print(json.dumps(r), file=sys.stderr, flush=True)
+    print(json.dumps(result), flush=True)
+    return 0
+
+
+def run_config(args, config: int, H_arg, steps: int, warmup: int, cpu_leg: bool) -> dict:
     import torch
     from paper_2512_00719_amd import binding, synth
 
     t_gen = time.perf_counter()
-    w = synth.make_config(args.config, H=args.H)
+    w = synth.make_config(config, H=H_arg)
     esize = 4 if w.dtype == "f32" else 2
     nnz_total = int(w.hist_ids.size)
     nnz_max = int(np.diff(w.hist_ptr).max()) if nnz_total else 0
@@ -144,7 +169,7 @@ def main() -> int:
           file=sys.stderr, flush=True)
 
     # the CPU leg forks workers: it runs before this process initialises the GPU
-    cpu = None if args.no_cpu_baseline else cpu_baseline(w)
+    cpu = cpu_baseline(w) if cpu_leg else None
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     dev = "cuda:0"
     # Rotate over distinct copies of the inputs so that the 256 MB memory-side cache cannot serve
@@ -162,7 +187,8 @@ def main() -> int:
     out = torch.empty(w.B, dtype=torch.int32, device=dev)
     diag = torch.zeros(w.B * 32, dtype=torch.uint8, device=dev)
 
-    s = binding.Sampler(w.V, nnz_max)
+    s = binding.Sampler(w.V, nnz_max, max_B=w.B)
+    stats_dev = torch.zeros(64, dtype=torch.uint8, device=dev)
     H = 0
     if hot_ids is not None:  # the bitmap is built once, outside the timed region
         s.set_hot_set(hot_ids, w.V)
@@ -173,18 +199,18 @@ def main() -> int:
         s.sample(logits[c], params, hist_ptr, hist_ids[c], None, H, seed=w.seed, step=i, out=out,
                  diag=diag if with_diag else None, V=w.V)
 
-    for i in range(args.warmup):
+    for i in range(warmup):
         step(i)
     torch.cuda.synchronize()
     # The library brackets its dominant kernel (the single-pass row kernel) with HIP events on the
     # stream it launches on; the whole step (both kernels of a call) is timed by the wall clock
     # between two device synchronisations.
-    timed = min(args.steps, 1024)
+    timed = min(steps, 1024)
     assert binding.simple_profile_enable(s.ctx, True) == 0
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    for i in range(args.steps):
-        step(args.warmup + i)
+    for i in range(steps):
+        step(warmup + i)
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
     n_rec, total_ms = binding.simple_profile_read(s.ctx)
@@ -193,20 +219,21 @@ def main() -> int:
     per_launch = binding.simple_profile_read_launches(s.ctx)
     p10, p50, p90 = (float(x) for x in np.percentile(per_launch, [10, 50, 90]))
     binding.simple_profile_enable(s.ctx, False)
-    ms_per_step = wall * 1e3 / args.steps
-    rows_per_s = w.B * args.steps / wall
+    ms_per_step = wall * 1e3 / steps
+    rows_per_s = w.B * steps / wall
 
-    step(args.warmup + args.steps, with_diag=True)
+    # one more call, outside the timed region, with the library's device-side aggregate installed
+    assert binding.simple_set_stats(s.ctx, stats_dev.data_ptr()) == 0
+    step(warmup + steps)
     torch.cuda.synchronize()
-    dg = diag.cpu().numpy().view(binding.ROW_DIAG_DTYPE)
-    flags = dg["flags"]
-    stats = {"second_pass_rows": int(((flags & binding.DIAG_WIDE) > 0).sum()),
-             "general_kernel_rows": int(((flags & binding.DIAG_GENERAL) > 0).sum()),
-             "error_rows": int(((flags & binding.DIAG_ERROR) > 0).sum())}
+    assert binding.simple_set_stats(s.ctx, 0) == 0
+    agg = stats_dev.cpu().numpy().view(binding.STATS_DTYPE)[0]
+    stats = {"second_pass_rows": int(agg["second_pass_rows"]), "general_kernel_rows": int(agg["general_rows"]),
+             "error_flags": int(agg["error_flags"])}
     if hot_ids is not None:
-        shvs = (flags & binding.DIAG_SHVS) > 0
-        stats["shvs_acceptance_rate"] = float(((flags & binding.DIAG_ACCEPTED) > 0)[shvs].mean())
-        stats["shvs_mean_alpha"] = float(dg["alpha"][shvs].mean())
+        n_shvs = int(agg["shvs_accepted"] + agg["shvs_rejected"])
+        stats["shvs_acceptance_rate"] = float(agg["shvs_accepted"]) / max(n_shvs, 1)
+        stats["shvs_mean_alpha"] = float(agg["sum_alpha_q32"]) / 2.0 ** 32 / max(n_shvs, 1)
         stats["H"] = int(w.hot_ids.size)
     achieved = alg_bytes / (kern_ms * 1e-3) / 1e9
     s.close()
@@ -241,28 +268,35 @@ def main() -> int:
         dst.copy_(src)
         torch.cuda.synchronize()
 
+    kernel_name = "simple::fast::fast_rows_kernel"
+    call_gbs = alg_bytes / (ms_per_step * 1e-3) / 1e9
+    traffic = recorded_traffic(config)
     result = {
-        "metric": "sampled rows/sec + achieved HBM GB/s (fraction of peak), B=1024 V=128,256 fp32",
-        "value": rows_per_s, "unit": "rows/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "metric": METRIC[config],
+        "value": rows_per_s, "unit": "rows/s", "n_gpus": 1, "steps": steps, "warmup": warmup,
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "f32", "data": "synthetic",
+        "dtype": w.dtype, "data": "synthetic",
         "config": {"workload": f"{w.name}: B={w.B} V={w.V} {w.dtype} logits (Zipf profile + noise), "
                                f"{nnz_max} history ids/row, heterogeneous per-row controls"
-                               if args.config in (3, 5) else f"{w.name}: B={w.B} V={w.V} {w.dtype}, {nnz_max} history ids/row",
+                               if config in (3, 5) else f"{w.name}: B={w.B} V={w.V} {w.dtype}, {nnz_max} history ids/row",
                    "input_copies_rotated": n_copies, **stats},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": PEAK_HBM_GBS, "unit": "GB/s",
-                     "frac": achieved / PEAK_HBM_GBS, "traffic": recorded_traffic(args.config),
-                     "kernel": "simple::fast::fast_rows_kernel", "kernel_ms": kern_ms,
+                     "frac": achieved / PEAK_HBM_GBS, "traffic": traffic,
+                     "traffic_source": None if traffic is None else "recorded: rocprofv3 counter runs summarised under profiles/, "
+                                                                    "valid while the kernel's sources are unchanged",
+                     "kernel": kernel_name, "kernel_ms": kern_ms,
                      "kernel_ms_p10_p50_p90": [p10, p50, p90], "algorithmic_bytes": alg_bytes,
                      "stream_ceiling": {"what": "read-only row-maximum reduction over the same logits",
                                         "ms": probe_ms, "achieved": ceiling, "frac_of_peak": ceiling / PEAK_HBM_GBS},
                      "frac_of_stream_ceiling": achieved / ceiling,
-                     "step_ms": ms_per_step, "step_frac": alg_bytes / (ms_per_step * 1e-3) / 1e9 / PEAK_HBM_GBS},
+                     # every kernel of the call (the dominant one, the kernels behind it, the gaps between them)
+                     "whole_call": {"ms": ms_per_step, "achieved": call_gbs, "frac": call_gbs / PEAK_HBM_GBS}},
     }
     if cpu is not None:
         result["cpu_baseline"] = cpu
-    print(json.dumps(result), flush=True)
-    return 0
+    del logits, hist_ids
+    torch.cuda.empty_cache()
+    return result
 
 
 if __name__ == "__main__":

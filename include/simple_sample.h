@@ -111,6 +111,24 @@ enum {
   SIMPLE_DIAG_BAD_HOT_SET = 1u << 12   /* hot id outside [0, V) or duplicated (ignored) */
 };
 
+/* Optional aggregate over the rows of the calls made while it is installed (64 bytes, device
+ * memory; the "basic observability" of the paper's implementation section: acceptance rate and
+ * sampler counts without reading one record per row).  The kernels add to it with atomics; the
+ * caller zeroes it and reads it (stream-ordered copies).  Mean alpha = sum_alpha_q32 / 2^32 /
+ * (shvs_accepted + shvs_rejected), a fixed-point sum, so its value does not depend on the order of
+ * the additions. */
+typedef struct {
+  uint64_t rows;             /* rows completed */
+  uint64_t greedy_rows;
+  uint64_t shvs_accepted;    /* rows that used a hot set and accepted the hot draw */
+  uint64_t shvs_rejected;    /* rows that used a hot set and drew from the tail */
+  uint64_t second_pass_rows; /* rows whose survivors did not fit the on-chip candidate list (SIMPLE_DIAG_WIDE) */
+  uint64_t general_rows;     /* rows completed by the general kernel (SIMPLE_DIAG_GENERAL) */
+  uint64_t sum_alpha_q32;    /* sum over SHVS rows of alpha_b * 2^32, rounded to nearest */
+  uint32_t error_flags;      /* OR of the SIMPLE_DIAG_* error bits of all rows */
+  uint32_t reserved;
+} simple_stats;
+
 /*
  * Create a context on HIP device `device` for calls with up to max_B rows, at most max_V vocabulary
  * entries and at most max_nnz_per_row history ids per row (0 if no history will ever be passed).
@@ -132,6 +150,14 @@ void simple_destroy(simple_ctx* ctx);
  * duplicate ids are ignored and reported through SIMPLE_DIAG_BAD_HOT_SET on later rows.
  */
 int simple_set_hot_set(simple_ctx* ctx, const int32_t* hot_ids_dev, int32_t H, int64_t V, void* hip_stream);
+
+/*
+ * Install (or, with NULL, remove) the aggregate that later simple_sample calls on this context add
+ * to.  stats_dev: device memory, 8-byte aligned, owned and zeroed by the caller, alive until it is
+ * removed or the context destroyed.  Host-side only: nothing is enqueued.  Returns SIMPLE_EINVAL
+ * for a NULL context or a misaligned pointer.
+ */
+int simple_set_stats(simple_ctx* ctx, simple_stats* stats_dev);
 
 /*
  * The sampling call (section 2.1 steps (1)-(3); section 5.3 when a hot set is in force).

@@ -29,7 +29,12 @@ ROW_DIAG_DTYPE = np.dtype([("alpha", "<f8"), ("s_k", "<f8"), ("p_chosen", "<f4")
                            ("n_survivors", "<i4"), ("flags", "<u4"), ("reserved", "<u4")])
 assert ROW_DIAG_DTYPE.itemsize == 32
 
-EXPORTS = ("simple_create", "simple_destroy", "simple_set_hot_set", "simple_sample",
+STATS_DTYPE = np.dtype([("rows", "<u8"), ("greedy_rows", "<u8"), ("shvs_accepted", "<u8"), ("shvs_rejected", "<u8"),
+                        ("second_pass_rows", "<u8"), ("general_rows", "<u8"), ("sum_alpha_q32", "<u8"),
+                        ("error_flags", "<u4"), ("reserved", "<u4")])
+assert STATS_DTYPE.itemsize == 64
+
+EXPORTS = ("simple_create", "simple_destroy", "simple_set_hot_set", "simple_set_stats", "simple_sample",
            "simple_sample_static", "simple_static_limit",
            "simple_profile_enable", "simple_profile_read", "simple_profile_read_launches",
            "simple_stream_probe",
@@ -47,6 +52,8 @@ def _load() -> ctypes.CDLL:
     lib.simple_destroy.restype = None
     lib.simple_set_hot_set.argtypes = [vp, vp, i32, i64, vp]
     lib.simple_set_hot_set.restype = ctypes.c_int
+    lib.simple_set_stats.argtypes = [vp, vp]
+    lib.simple_set_stats.restype = ctypes.c_int
     lib.simple_sample.argtypes = [vp, vp, i64, i64, ctypes.c_int, i64, vp, vp, vp, vp, i32, u64, u64, u64,
                                   vp, vp, vp]
     lib.simple_sample.restype = ctypes.c_int
@@ -140,6 +147,10 @@ def simple_stream_probe(logits_ptr: int, B: int, V: int, dtype: int, row_stride:
 def simple_set_hot_set(ctx: int, hot_ids_ptr: int, H: int, V: int, stream: int = 0) -> int:
     return int(_lib.simple_set_hot_set(ctypes.c_void_p(ctx), ctypes.c_void_p(hot_ids_ptr), int(H), int(V),
                                        ctypes.c_void_p(stream)))
+
+
+def simple_set_stats(ctx: int, stats_ptr: int) -> int:
+    return int(_lib.simple_set_stats(ctypes.c_void_p(ctx), ctypes.c_void_p(stats_ptr)))
 
 
 def simple_sample(ctx: int, logits_ptr: int, B: int, V: int, dtype: int, row_stride: int, params_ptr: int,

@@ -28,6 +28,7 @@ struct simple_ctx {
   hipEvent_t* prof_ev;  // 2 * PROF_MAX events while profiling is enabled, else null
   int prof_n;           // launches recorded so far
   void* base;           // device allocation that holds all of the above (null: not owned)
+  simple_stats* stats;  // caller's aggregate (device), or null
 };
 constexpr int PROF_MAX = 1024;
 
@@ -163,7 +164,7 @@ int simple_create(simple_ctx** out, int device, int64_t max_B, int64_t max_V, in
   if (!c) return SIMPLE_ENOMEM;
   c->device = device; c->max_V = max_V; c->max_nnz = max_nnz_per_row; c->lds_limit = lds; c->n_cu = n_cu;
   c->hot_V = 0; c->hot_H = 0; c->hot_bits = nullptr; c->hot_flags = nullptr; c->pend = nullptr; c->wq = nullptr; c->wws = nullptr; c->ws_stride = 0; c->parity = 0;
-  c->prof_ev = nullptr; c->prof_n = 0; c->base = nullptr; c->slots = 0;
+  c->prof_ev = nullptr; c->prof_n = 0; c->base = nullptr; c->slots = 0; c->stats = nullptr;
   c->slots = (int)(max_B < (int64_t)simple::WIDE_SLOTS ? max_B : (int64_t)simple::WIDE_SLOTS);
   const simple::CtxLayout CL = simple::ctx_layout(max_V, max_nnz_per_row, c->slots, lds, n_cu);
   unsigned char* base = nullptr;
@@ -198,6 +199,12 @@ void simple_destroy(simple_ctx* ctx) {
     }
   }
   delete ctx;
+}
+
+int simple_set_stats(simple_ctx* ctx, simple_stats* stats_dev) {
+  if (!ctx || (reinterpret_cast<uintptr_t>(stats_dev) & 7u) != 0) return SIMPLE_EINVAL;
+  ctx->stats = stats_dev;
+  return SIMPLE_OK;
 }
 
 int simple_profile_enable(simple_ctx* ctx, int on) {
@@ -294,6 +301,7 @@ int simple_sample(simple_ctx* ctx, const void* logits_dev, int64_t B, int64_t V,
   a.hot_bits = use_hot ? ctx->hot_bits : nullptr;
   a.hot_flags = use_hot ? ctx->hot_flags : nullptr;
   a.seed = seed; a.step = step;
+  a.stats = ctx->stats;
   a.max_nnz = (int)ctx->max_nnz;
   a.pend = ctx->pend;
   a.n_cu = ctx->n_cu;

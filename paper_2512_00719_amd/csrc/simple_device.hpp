@@ -123,6 +123,24 @@ __device__ inline void row_uniforms(uint64_t seed, uint64_t row, uint64_t step, 
   for (int i = 0; i < 3; ++i) u[i] = (double)(x[i] >> 8) * 0x1p-24;
 }
 
+// ---------------------------------------------------------------- aggregate over rows ---------
+// One completed row's share of the optional aggregate (called by one thread per row).  Integer
+// atomics only: the sums do not depend on the order in which rows finish.
+constexpr uint32_t DIAG_ERROR_BITS = SIMPLE_DIAG_ERROR | SIMPLE_DIAG_BAD_PARAM | SIMPLE_DIAG_BAD_LOGIT | SIMPLE_DIAG_BAD_HISTORY_ID |
+                                     SIMPLE_DIAG_HISTORY_TOO_LONG | SIMPLE_DIAG_BAD_HOT_SET;
+__device__ __forceinline__ void stats_add(simple_stats* st, uint32_t flags, double alpha) {
+  typedef unsigned long long ull;
+  atomicAdd(reinterpret_cast<ull*>(&st->rows), 1ull);
+  if (flags & SIMPLE_DIAG_GREEDY) atomicAdd(reinterpret_cast<ull*>(&st->greedy_rows), 1ull);
+  if ((flags & SIMPLE_DIAG_SHVS) && !(flags & SIMPLE_DIAG_ERROR)) {
+    atomicAdd(reinterpret_cast<ull*>((flags & SIMPLE_DIAG_ACCEPTED) ? &st->shvs_accepted : &st->shvs_rejected), 1ull);
+    atomicAdd(reinterpret_cast<ull*>(&st->sum_alpha_q32), (ull)__double2ull_rn(alpha * 4294967296.0));
+  }
+  if (flags & SIMPLE_DIAG_WIDE) atomicAdd(reinterpret_cast<ull*>(&st->second_pass_rows), 1ull);
+  if (flags & SIMPLE_DIAG_GENERAL) atomicAdd(reinterpret_cast<ull*>(&st->general_rows), 1ull);
+  if (flags & DIAG_ERROR_BITS) atomicOr(&st->error_flags, flags & DIAG_ERROR_BITS);
+}
+
 // ---------------------------------------------------------------- per-row history state -------
 // The histograms of section 2.2 are never materialised over V.  A row keeps, in LDS:
 //   bits  : V-bit presence mask  M_p or M_o            (which columns are penalised at all)

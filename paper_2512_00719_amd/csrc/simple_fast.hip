@@ -1041,11 +1041,10 @@ __global__ __launch_bounds__(NTHR, NTHR == 256 ? 4 : (NTHR == 512 ? 2 : 1)) void
       const unsigned f = S.flags & 0x3FFFFFFFu;
       const bool err = (f & SIMPLE_DIAG_ERROR) != 0u;
       a.out[row] = err ? -1 : S.out_id;
-      if (a.diag) {
-        dg.flags |= f | (R.greedy ? SIMPLE_DIAG_GREEDY : 0u);
-        if (err) dg.p_chosen = 0.0f;
-        a.diag[row] = dg;
-      }
+      dg.flags |= f | (R.greedy ? SIMPLE_DIAG_GREEDY : 0u);
+      if (err) dg.p_chosen = 0.0f;
+      if (a.diag) a.diag[row] = dg;
+      if (a.stats) stats_add(a.stats, dg.flags, dg.alpha);
     }
   }
 }

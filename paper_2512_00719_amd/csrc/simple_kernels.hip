@@ -1415,7 +1415,9 @@ __device__ inline void sample_row_body(const SampleArgs& a, const int row, unsig
   if (bad_par || too_long) {
     if (tid == 0) {
       a.out[row] = -1;
-      if (a.diag) { dg.flags = SIMPLE_DIAG_ERROR | (bad_par ? SIMPLE_DIAG_BAD_PARAM : 0u) | (too_long ? SIMPLE_DIAG_HISTORY_TOO_LONG : 0u); a.diag[row] = dg; }
+      dg.flags |= SIMPLE_DIAG_ERROR | (bad_par ? SIMPLE_DIAG_BAD_PARAM : 0u) | (too_long ? SIMPLE_DIAG_HISTORY_TOO_LONG : 0u);
+      if (a.diag) a.diag[row] = dg;
+      if (a.stats) stats_add(a.stats, dg.flags, dg.alpha);
     }
     return;
   }
@@ -1507,11 +1509,10 @@ __device__ inline void sample_row_body(const SampleArgs& a, const int row, unsig
     const unsigned f = S.flags;
     const bool err = (f & SIMPLE_DIAG_ERROR) != 0u;
     a.out[row] = err ? -1 : S.out_id;
-    if (a.diag) {
-      dg.flags |= f | (greedy ? SIMPLE_DIAG_GREEDY : 0u);
-      dg.p_chosen = err ? 0.0f : S.out_p;
-      a.diag[row] = dg;
-    }
+    dg.flags |= f | (greedy ? SIMPLE_DIAG_GREEDY : 0u);
+    dg.p_chosen = err ? 0.0f : S.out_p;
+    if (a.diag) a.diag[row] = dg;
+    if (a.stats) stats_add(a.stats, dg.flags, dg.alpha);
   }
 }
 

@@ -54,6 +54,7 @@ struct SampleArgs {
   uint64_t seed, step, row_offset;
   int32_t* out;
   simple_row_diag* diag;
+  simple_stats* stats;  // aggregate over rows, or nullptr
   int max_nnz;
   int gated;       // 1: the single-pass kernel runs first and queues the rows it leaves
   // Queues filled by the single-pass kernel.  Word [parity] counts the entries of this launch; the

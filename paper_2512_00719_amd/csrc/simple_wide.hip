@@ -1035,6 +1035,7 @@ __global__ __launch_bounds__(WT) void wide_finish_kernel(const SampleArgs a) {
       else {
         a.out[W.row] = S.out_id;
         if (a.diag) a.diag[W.row] = dg;
+        if (a.stats) stats_add(a.stats, dg.flags, dg.alpha);
       }
     }
   }

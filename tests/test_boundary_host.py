@@ -42,6 +42,7 @@ def test_null_context_and_bad_arguments_are_rejected_on_the_host():
     # NULL context: rejected before any device work
     assert binding.simple_sample(0, 0, 1, 8, 0, 8, 0, 0, 0, 0, 0, 1, 0, 0, 0, 0) == binding.SIMPLE_EINVAL
     assert binding.simple_set_hot_set(0, 0, 4, 8) == binding.SIMPLE_EINVAL
+    assert binding.simple_set_stats(0, 0) == binding.SIMPLE_EINVAL
     assert binding.simple_lds_bytes(0) == binding.SIMPLE_EINVAL
     binding.simple_destroy(None)  # accepted
     with pytest.raises(binding.SimpleError) as e:

@@ -398,3 +398,51 @@ def test_multi_pass_route_cuts_inside_and_above_a_plateau(dtype):
     w = synth.Workload(f"plateau-cuts-{dtype}", B, V, dtype, logits, params, hist_ptr, hist_ids, hot_ids=hot)
     res = _check(w, steps=(0, 1, 2))
     assert (res[0][1]["flags"] & 4).sum() >= 5  # the multi-pass route of the general kernel
+
+
+def test_aggregate_stats_equal_the_sum_over_the_row_records():
+    """simple_set_stats: the device-side aggregate of two calls equals what the per-row diagnostics
+    records of the same calls add up to (rows, greedy, SHVS accepted / rejected, second-pass and
+    general-kernel rows, the fixed-point sum of alpha, the error bits), and nothing is added once it
+    is removed."""
+    import torch
+    from paper_2512_00719_amd import binding
+    w = synth.make_config(3, B=96, V=33_000, nnz=700).with_hot(2500)
+    w.params["temperature"][5] = -1.0                 # a parameter error (general kernel)
+    w.params["top_k"][7:11] = 0                       # nuclei over the whole vocabulary
+    w.params["min_p"][7:11] = 0.0
+    w.params["temperature"][7:11] = 1.3
+    w.logits[12, 100] = np.nan                        # a data error
+    dev = P.to_device(w)
+    s = binding.Sampler(w.V, 700, max_B=w.B)
+    stats = torch.zeros(64, dtype=torch.uint8, device="cuda:0")
+    assert binding.simple_set_stats(s.ctx, stats.data_ptr() + 4) == binding.SIMPLE_EINVAL
+    assert binding.simple_set_stats(s.ctx, stats.data_ptr()) == binding.SIMPLE_OK
+    want = np.zeros(1, binding.STATS_DTYPE)[0]
+    for step in (0, 1):
+        diag = torch.zeros(w.B * 32, dtype=torch.uint8, device="cuda:0")
+        s.sample(dev["logits"], dev["params"], dev["hist_ptr"], dev["hist_ids"], dev["hot_ids"], seed=w.seed, step=step, diag=diag, V=w.V)
+        torch.cuda.synchronize()
+        dg = diag.cpu().numpy().view(binding.ROW_DIAG_DTYPE)
+        f = dg["flags"]
+        ok_shvs = ((f & binding.DIAG_SHVS) > 0) & ((f & binding.DIAG_ERROR) == 0)
+        want["rows"] += w.B
+        want["greedy_rows"] += int(((f & binding.DIAG_GREEDY) > 0).sum())
+        want["shvs_accepted"] += int((ok_shvs & ((f & binding.DIAG_ACCEPTED) > 0)).sum())
+        want["shvs_rejected"] += int((ok_shvs & ((f & binding.DIAG_ACCEPTED) == 0)).sum())
+        want["second_pass_rows"] += int(((f & binding.DIAG_WIDE) > 0).sum())
+        want["general_rows"] += int(((f & binding.DIAG_GENERAL) > 0).sum())
+        want["sum_alpha_q32"] += int(sum(int(np.rint(a * 2.0 ** 32)) for a in dg["alpha"][ok_shvs]))
+        err_bits = binding.DIAG_ERROR | binding.DIAG_BAD_PARAM | binding.DIAG_BAD_LOGIT | binding.DIAG_BAD_HISTORY_ID | \
+            binding.DIAG_HISTORY_TOO_LONG | binding.DIAG_BAD_HOT_SET
+        want["error_flags"] |= int(np.bitwise_or.reduce(f) & err_bits)
+    got = stats.cpu().numpy().view(binding.STATS_DTYPE)[0]
+    for name in binding.STATS_DTYPE.names:
+        assert got[name] == want[name], (name, got, want)
+    assert got["shvs_accepted"] > 0 and got["shvs_rejected"] > 0 and got["second_pass_rows"] > 0 and got["general_rows"] > 0
+    assert got["error_flags"] & binding.DIAG_BAD_PARAM and got["error_flags"] & binding.DIAG_BAD_LOGIT
+    assert binding.simple_set_stats(s.ctx, 0) == binding.SIMPLE_OK
+    s.sample(dev["logits"], dev["params"], dev["hist_ptr"], dev["hist_ids"], dev["hot_ids"], seed=w.seed, step=2, V=w.V)
+    torch.cuda.synchronize()
+    assert stats.cpu().numpy().view(binding.STATS_DTYPE)[0] == got
+    s.close()
