@@ -113,6 +113,53 @@ def history_histograms(hist_row: np.ndarray, n_prompt: int, V: int) -> tuple[np.
     return c_o, (c_p > 0) | (c_o > 0)
 
 
+class IncrementalHistory:
+    """The incremental penalty state of section 5.2 for a batch of B sequences.
+
+    A row-append token buffer ``Y`` of shape ``[L_max, B]`` (the tokens generated at step s form
+    row s) and the histograms carried from step to step instead of being rebuilt:
+    ``C_o^{s+1} = C_o^s + Hist(Y_s)`` and ``M_o^{s+1} = (C_o^{s+1} > 0)``; the prompt histogram
+    ``C_p`` (hence ``M_p``) is invariant over the steps of a sequence.  Dense ``[B, V]`` arrays, as
+    the paper writes them.  A sequence may be restarted (its slot evicted and given a new prompt)
+    at any step; its generated tokens then start again at row 0 of its column.
+    """
+
+    def __init__(self, B: int, V: int, L_max: int):
+        self.B, self.V, self.L_max = B, V, L_max
+        self.Y = np.full((L_max, B), -1, dtype=np.int64)
+        self.n_out = np.zeros(B, dtype=np.int64)          # generated tokens per sequence
+        self.C_o = np.zeros((B, V), dtype=np.int64)
+        self.M_p = np.zeros((B, V), dtype=bool)
+
+    def restart(self, b: int, prompt_ids) -> None:
+        prompt_ids = np.asarray(prompt_ids, dtype=np.int64)
+        if prompt_ids.size and (prompt_ids.min() < 0 or prompt_ids.max() >= self.V):
+            raise ValueError("prompt id outside [0, V)")
+        self.Y[:, b] = -1
+        self.n_out[b] = 0
+        self.C_o[b] = 0
+        self.M_p[b] = np.bincount(prompt_ids, minlength=self.V) > 0
+
+    def append(self, ids) -> None:
+        """One step: ``ids[b]`` is the token generated for sequence b (negative: none this step)."""
+        ids = np.asarray(ids, dtype=np.int64)
+        for b in range(self.B):
+            t = int(ids[b])
+            if t < 0:
+                continue
+            if t >= self.V:
+                raise ValueError("token id outside [0, V)")
+            if self.n_out[b] >= self.L_max:
+                raise ValueError("token buffer full")
+            self.Y[self.n_out[b], b] = t
+            self.n_out[b] += 1
+            self.C_o[b, t] += 1                            # C_o += Hist(Y_s): a one-hot row per sequence
+
+    def histograms(self, b: int) -> tuple[np.ndarray, np.ndarray]:
+        """``(C_o, M_p or M_o)`` of sequence b, what ``history_histograms`` rebuilds from the token list."""
+        return self.C_o[b], self.M_p[b] | (self.C_o[b] > 0)
+
+
 def apply_penalties(z: np.ndarray, c_o: np.ndarray, mask: np.ndarray, rep: float, freq: float,
                     pres: float, literal_division: bool = False) -> np.ndarray:
     """``Z' = ApplyPenalty(Z, Y_<s)`` (Eq. (1)), float32, one rounding per operation.
@@ -180,7 +227,7 @@ def _survivors(order: np.ndarray, w_sorted: np.ndarray, n: int, V: int) -> tuple
 
 
 def row_distribution(z_row: np.ndarray, par, hist_row: Optional[np.ndarray] = None,
-                     literal_division: bool = False) -> RowDist:
+                     literal_division: bool = False, histograms: Optional[tuple] = None) -> RowDist:
     """Steps (1) and (2) of section 2.1 for one row; returns K_b and the weights on it.
 
     Conventions where the paper is silent:
@@ -201,7 +248,10 @@ def row_distribution(z_row: np.ndarray, par, hist_row: Optional[np.ndarray] = No
     rep = np.float32(par["rep_penalty"])
     if not (temperature >= 0) or not (rep > 0):
         return RowDist(V=V, error=True)
-    if hist_row is not None and len(hist_row):
+    if histograms is not None:  # carried from step to step (section 5.2) instead of rebuilt from the token list
+        c_o, mask = histograms
+        z = apply_penalties(z, c_o, mask, rep, par["freq_penalty"], par["pres_penalty"], literal_division)
+    elif hist_row is not None and len(hist_row):
         c_o, mask = history_histograms(hist_row, int(par["n_prompt"]), V)
         z = apply_penalties(z, c_o, mask, rep, par["freq_penalty"], par["pres_penalty"],
                             literal_division)
@@ -369,10 +419,10 @@ def _neighbours(d: RowDist, tok: int, hot_mask, accepted) -> set:
 
 
 def sample_row(z_row: np.ndarray, par, hist_row, hot_mask: Optional[np.ndarray], seed: int,
-               row: int, step: int, keep_dist: bool = False) -> RowResult:
+               row: int, step: int, keep_dist: bool = False, histograms: Optional[tuple] = None) -> RowResult:
     """One row of the sampling call: distribution, uniforms, draw, and the alternative ids that
     count as correct when a decision is within ``AMBIGUITY_WINDOW`` of a boundary."""
-    d = row_distribution(z_row, par, hist_row)
+    d = row_distribution(z_row, par, hist_row, histograms=histograms)
     u_draw, u_acc, u_tail = (float(x) for x in row_uniforms(seed, np.array(row), step))
     tok, margin, acc = draw(d, u_draw, u_acc, u_tail, hot_mask)
     tok = int(tok)
@@ -409,6 +459,15 @@ def sample_row(z_row: np.ndarray, par, hist_row, hot_mask: Optional[np.ndarray],
     p_chosen = float(d.w[np.searchsorted(d.ids, tok)] / d.S_K)
     return RowResult(tok, alt, ambiguous, d.n, p_chosen, alpha, accepted, d.S_k,
                      d if keep_dist else None, tuple(alt_p), bool(0.0 < float(par["top_p"]) < 1.0))
+
+
+def sample_with_state(logits_f32: np.ndarray, params, state: IncrementalHistory, hot_ids, seed: int, step: int,
+                      row_offset: int = 0) -> list[RowResult]:
+    """The whole call with the penalties taken from the incremental state (row b is sequence b)."""
+    B, V = logits_f32.shape
+    hot_mask = hot_mask_from_ids(hot_ids, V)
+    return [sample_row(logits_f32[b], params[b], None, hot_mask, seed, row_offset + b, step,
+                       histograms=state.histograms(b)) for b in range(B)]
 
 
 def hot_mask_from_ids(hot_ids: Optional[Sequence[int]], V: int) -> Optional[np.ndarray]:

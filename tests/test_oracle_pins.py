@@ -618,3 +618,46 @@ def test_ambiguity_flags_on_headline_shaped_rows():
             elif r.ambiguous:
                 n_step += 1
     assert total == 576 and n_step <= 1 and n_nucleus <= 0.08 * total, (n_step, n_nucleus, total)
+
+
+def test_incremental_history_equals_the_rebuild_at_every_step():
+    """Section 5.2: the histograms carried by C_o += Hist(Y_s) equal the ones rebuilt from the whole
+    token list (prompt first) at every step, through restarts of single sequences and steps on which
+    a sequence generates nothing; the token buffer holds the generated tokens row by row."""
+    rng = np.random.default_rng(12)
+    B, V, L = 5, 50, 40
+    st = O.IncrementalHistory(B, V, L)
+    prompts = [rng.integers(0, V, int(rng.integers(0, 12))) for _ in range(B)]
+    gen = [[] for _ in range(B)]
+    for b in range(B):
+        st.restart(b, prompts[b])
+    for step in range(30):
+        if step in (7, 19):  # one sequence ends and its slot is given to a new one
+            b = int(rng.integers(0, B))
+            prompts[b] = rng.integers(0, V, int(rng.integers(0, 12)))
+            gen[b] = []
+            st.restart(b, prompts[b])
+        ids = rng.integers(0, V, B)
+        ids[rng.random(B) < 0.2] = -1
+        st.append(ids)
+        for b in range(B):
+            if ids[b] >= 0:
+                gen[b].append(int(ids[b]))
+            full = np.concatenate([prompts[b], np.array(gen[b], dtype=np.int64)]).astype(np.int64)
+            c_ref, m_ref = O.history_histograms(full, len(prompts[b]), V)
+            c_inc, m_inc = st.histograms(b)
+            assert np.array_equal(c_ref, c_inc) and np.array_equal(m_ref, m_inc)
+            assert st.Y[:len(gen[b]), b].tolist() == gen[b] and np.all(st.Y[len(gen[b]):, b] == -1)
+    # hand-computed: prompt (3, 3, 9), generated 9, 4, 9 -> C_o = {9: 2, 4: 1}, mask = {3, 4, 9}
+    st = O.IncrementalHistory(1, 12, 8)
+    st.restart(0, [3, 3, 9])
+    for t in (9, 4, 9):
+        st.append([t])
+    c, m = st.histograms(0)
+    assert {i: int(v) for i, v in enumerate(c) if v} == {9: 2, 4: 1} and np.flatnonzero(m).tolist() == [3, 4, 9]
+    # the sampling call on the carried state equals the call on the rebuilt token list
+    z = (rng.standard_normal((1, 12)) * 2).astype(np.float32)
+    par = synth.make_params(1, rep_penalty=1.3, freq_penalty=0.4, pres_penalty=0.2, top_k=5, temperature=0.8, n_prompt=3)
+    a = O.sample_with_state(z, par, st, None, 5, 2)[0]
+    b = O.sample(z, par, np.array([0, 6]), np.array([3, 3, 9, 9, 4, 9], np.int32), None, 5, 2)[0]
+    assert (a.id, a.n, a.p_chosen) == (b.id, b.n, b.p_chosen)
