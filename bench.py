@@ -133,6 +133,8 @@ def main() -> int:
     ap.add_argument("--H", type=int, default=None, help="hot-set size for configs 4 and 5")
     ap.add_argument("--copies", type=int, default=0, help="distinct input copies to rotate over (0 = auto: >= 1 GiB)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--stateful", action="store_true",
+                    help="take the rows' histories from an incremental penalty state (simple_sample_state) instead of the CSR arrays")
     ap.add_argument("--all-configs", action="store_true", help="also run C2, C4 (H sweep) and C5 briefly; their lines go to stderr")
     ap.add_argument("--copy-probe-mib", type=int, default=0,
                     help="after the timed region, run one plain device copy of this many MiB (a kernel of known "
@@ -194,10 +196,32 @@ def run_config(args, config: int, H_arg, steps: int, warmup: int, cpu_leg: bool)
         s.set_hot_set(hot_ids, w.V)
         H = -1
 
+    state = None
+    if args.stateful and nnz_total:
+        # every sequence's tokens so far are loaded as generated tokens (n_prompt = 0, as in the CSR form of the workload)
+        state = binding.simple_state_create(0, w.B, w.V, nnz_max)
+        zeros = torch.zeros(w.B, dtype=torch.int32, device=dev)
+        rc = binding.simple_state_restart(state, 0, w.B, hist_ptr.data_ptr(), hist_ids[0].data_ptr(), zeros.data_ptr(),
+                                          torch.cuda.current_stream().cuda_stream)
+        assert rc == 0, rc
+        ref = s.sample(logits[0], params, hist_ptr, hist_ids[0], None, H, seed=w.seed, step=0, V=w.V).clone()
+
     def step(i: int, with_diag: bool = False):
         c = i % n_copies
+        if state is not None:
+            rc = binding.simple_sample_state(s.ctx, state, 0, logits[c].data_ptr(), w.B, w.V, dt_code, logits[c].stride(0),
+                                             params.data_ptr(), 0, H, w.seed, i, 0, out.data_ptr(),
+                                             diag.data_ptr() if with_diag else 0, torch.cuda.current_stream().cuda_stream)
+            assert rc == 0, rc
+            return
         s.sample(logits[c], params, hist_ptr, hist_ids[c], None, H, seed=w.seed, step=i, out=out,
                  diag=diag if with_diag else None, V=w.V)
+
+    dt_code = binding.SIMPLE_F32 if w.dtype == "f32" else binding.SIMPLE_BF16
+    if state is not None:
+        step(0)
+        torch.cuda.synchronize()
+        assert torch.equal(out, ref), "stateful and stateless calls disagree"
 
     for i in range(warmup):
         step(i)
@@ -237,13 +261,13 @@ def run_config(args, config: int, H_arg, steps: int, warmup: int, cpu_leg: bool)
         stats["H"] = int(w.hot_ids.size)
     achieved = alg_bytes / (kern_ms * 1e-3) / 1e9
     s.close()
+    if state is not None:
+        binding.simple_state_destroy(state)
 
     # What a one-pass row kernel can reach here: the library's read-only row-maximum reduction over
     # the same logits copies, timed with events on the stream it is launched on.
     row_max = torch.empty(w.B, dtype=torch.float32, device=dev)
     stream = torch.cuda.current_stream()
-    dt_code = binding.SIMPLE_F32 if w.dtype == "f32" else binding.SIMPLE_BF16
-
     def probe(i: int):
         lg = logits[i % n_copies]
         rc = binding.simple_stream_probe(lg.data_ptr(), w.B, w.V, dt_code, lg.stride(0), row_max.data_ptr(),
@@ -279,7 +303,7 @@ def run_config(args, config: int, H_arg, steps: int, warmup: int, cpu_leg: bool)
         "config": {"workload": f"{w.name}: B={w.B} V={w.V} {w.dtype} logits (Zipf profile + noise), "
                                f"{nnz_max} history ids/row, heterogeneous per-row controls"
                                if config in (3, 5) else f"{w.name}: B={w.B} V={w.V} {w.dtype}, {nnz_max} history ids/row",
-                   "input_copies_rotated": n_copies, **stats},
+                   "input_copies_rotated": n_copies, "history": "incremental state" if state is not None else "CSR arrays", **stats},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": PEAK_HBM_GBS, "unit": "GB/s",
                      "frac": achieved / PEAK_HBM_GBS, "traffic": traffic,
                      "traffic_source": None if traffic is None else "recorded: rocprofv3 counter runs summarised under profiles/, "

@@ -189,6 +189,50 @@ int simple_sample(simple_ctx* ctx, const void* logits_dev, int64_t B, int64_t V,
                   void* hip_stream);
 
 /*
+ * Incremental penalty state (paper section 5.2: row-append token buffer; the histograms are carried
+ * from step to step, C_o^{s+1} = C_o^s + Hist(Y_s), M_o = (C_o > 0), C_p and M_p fixed per sequence,
+ * instead of being rebuilt from the token list on every call).
+ *
+ * A state has max_seqs sequence slots for vocabulary size V; a slot holds up to L_max tokens (prompt
+ * plus generated) in device memory, together with the presence mask, rank directory and generated-
+ * token counts that the sampling kernel otherwise builds on chip from the CSR history.
+ *   simple_state_restart   evicts what n slots held and installs their prompts: slot slots_dev[i]
+ *                          (or i, with slots_dev NULL) gets prompt_ids_dev[prompt_ptr_dev[i] ..
+ *                          prompt_ptr_dev[i + 1]) (prompt_ptr_dev NULL: empty prompts).  Prompt
+ *                          tokens count towards the repetition penalty only.  With n_prompt_dev
+ *                          (n values, else NULL) only the first n_prompt_dev[i] ids of list i are
+ *                          the prompt and the rest are tokens the sequence has already generated
+ *                          (a sequence that moves in from another sampler, or a bulk load).
+ *   simple_state_append    one step: new_ids_dev[b] (device, B ids; negative = none) is appended to
+ *                          slot slots_dev[b] (or b) as a generated token.  Cost per sequence: one
+ *                          counter, or for an id not seen before O(V / 64 + distinct ids).
+ *   simple_sample_state    simple_sample with the rows' histories taken from the state: row b uses
+ *                          slot slots_dev[b] (or b); params[b].n_prompt is ignored (the state knows
+ *                          each sequence's prompt length).  Ids equal those of simple_sample called
+ *                          with the same token lists as CSR history.
+ * All three enqueue on hip_stream and return without synchronising; calls that touch the same state
+ * must be ordered by the caller (one stream, or events).  No two rows of one call may name the same
+ * slot.  A slot index outside [0, max_seqs) is skipped by restart / append and makes the row's id -1
+ * (SIMPLE_DIAG_HISTORY_TOO_LONG) in simple_sample_state, as does a sequence longer than L_max or
+ * than the context's max_nnz_per_row.  A token id outside [0, V) is kept in the list, ignored by the
+ * penalties and reported as SIMPLE_DIAG_BAD_HISTORY_ID on the sequence's later rows.
+ * Errors: SIMPLE_EINVAL for NULL / negative / inconsistent arguments (a state of another V or
+ * device than the call's, B > max_seqs without slots_dev), SIMPLE_ECAPACITY for L_max > 65535, a
+ * slot whose tables exceed the LDS of a compute unit, or L_max above the context's
+ * max_nnz_per_row; SIMPLE_ENOMEM / SIMPLE_EDEVICE as for simple_create.
+ */
+typedef struct simple_state simple_state;
+int simple_state_create(simple_state** out, int device, int64_t max_seqs, int64_t V, int64_t L_max);
+void simple_state_destroy(simple_state* state);
+int simple_state_restart(simple_state* state, const int32_t* slots_dev, int64_t n, const int64_t* prompt_ptr_dev,
+                         const int32_t* prompt_ids_dev, const int32_t* n_prompt_dev, void* hip_stream);
+int simple_state_append(simple_state* state, const int32_t* slots_dev, const int32_t* new_ids_dev, int64_t B, void* hip_stream);
+int simple_sample_state(simple_ctx* ctx, const simple_state* state, const int32_t* slots_dev, const void* logits_dev, int64_t B, int64_t V,
+                        int dtype, int64_t row_stride_elems, const simple_row_params* params_dev,
+                        const int32_t* hot_ids_dev, int32_t H, uint64_t seed, uint64_t step, uint64_t row_offset,
+                        int32_t* out_ids_dev, simple_row_diag* diag_dev, void* hip_stream);
+
+/*
  * simple_sample for callers that cannot allocate device memory or create a context: code under HIP
  * graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments and results as
  * simple_sample, on the current HIP device, without a context: the row queues, the workspace slots

@@ -36,6 +36,7 @@ assert STATS_DTYPE.itemsize == 64
 
 EXPORTS = ("simple_create", "simple_destroy", "simple_set_hot_set", "simple_set_stats", "simple_sample",
            "simple_sample_static", "simple_static_limit",
+           "simple_state_create", "simple_state_destroy", "simple_state_restart", "simple_state_append", "simple_sample_state",
            "simple_profile_enable", "simple_profile_read", "simple_profile_read_launches",
            "simple_stream_probe",
            "simple_lds_bytes", "simple_strerror", "simple_version")
@@ -61,6 +62,16 @@ def _load() -> ctypes.CDLL:
     lib.simple_sample_static.restype = ctypes.c_int
     lib.simple_static_limit.argtypes = [ctypes.c_int]
     lib.simple_static_limit.restype = i64
+    lib.simple_state_create.argtypes = [ctypes.POINTER(vp), ctypes.c_int, i64, i64, i64]
+    lib.simple_state_create.restype = ctypes.c_int
+    lib.simple_state_destroy.argtypes = [vp]
+    lib.simple_state_destroy.restype = None
+    lib.simple_state_restart.argtypes = [vp, vp, i64, vp, vp, vp, vp]
+    lib.simple_state_restart.restype = ctypes.c_int
+    lib.simple_state_append.argtypes = [vp, vp, vp, i64, vp]
+    lib.simple_state_append.restype = ctypes.c_int
+    lib.simple_sample_state.argtypes = [vp, vp, vp, vp, i64, i64, ctypes.c_int, i64, vp, vp, i32, u64, u64, u64, vp, vp, vp]
+    lib.simple_sample_state.restype = ctypes.c_int
     lib.simple_profile_enable.argtypes = [vp, ctypes.c_int]
     lib.simple_profile_enable.restype = ctypes.c_int
     lib.simple_profile_read.argtypes = [vp, ctypes.POINTER(ctypes.c_double)]
@@ -179,6 +190,42 @@ def simple_sample_static(logits_ptr: int, B: int, V: int, dtype: int, row_stride
 
 def simple_static_limit(what: int) -> int:
     return int(_lib.simple_static_limit(int(what)))
+
+
+def simple_state_create(device: int, max_seqs: int, V: int, L_max: int) -> int:
+    """Returns the state handle (an integer address); raises SimpleError on failure."""
+    h = ctypes.c_void_p()
+    rc = _lib.simple_state_create(ctypes.byref(h), int(device), int(max_seqs), int(V), int(L_max))
+    if rc != SIMPLE_OK:
+        raise SimpleError(rc, "simple_state_create")
+    return h.value
+
+
+def simple_state_destroy(state: Optional[int]) -> None:
+    _lib.simple_state_destroy(ctypes.c_void_p(state))
+
+
+def simple_state_restart(state: int, slots_ptr: int, n: int, prompt_ptr_ptr: int, prompt_ids_ptr: int, n_prompt_ptr: int = 0,
+                         stream: int = 0) -> int:
+    vp = ctypes.c_void_p
+    return int(_lib.simple_state_restart(vp(state), vp(slots_ptr), int(n), vp(prompt_ptr_ptr), vp(prompt_ids_ptr), vp(n_prompt_ptr),
+                                         vp(stream)))
+
+
+def simple_state_append(state: int, slots_ptr: int, new_ids_ptr: int, B: int, stream: int = 0) -> int:
+    vp = ctypes.c_void_p
+    return int(_lib.simple_state_append(vp(state), vp(slots_ptr), vp(new_ids_ptr), int(B), vp(stream)))
+
+
+def simple_sample_state(ctx: int, state: int, slots_ptr: int, logits_ptr: int, B: int, V: int, dtype: int, row_stride: int,
+                        params_ptr: int, hot_ids_ptr: int, H: int, seed: int, step: int, row_offset: int,
+                        out_ids_ptr: int, diag_ptr: int, stream: int = 0) -> int:
+    """Raw call: the sampling call with the rows' histories taken from a state.  Returns the C status code."""
+    vp = ctypes.c_void_p
+    return int(_lib.simple_sample_state(vp(ctx), vp(state), vp(slots_ptr), vp(logits_ptr), int(B), int(V), int(dtype),
+                                        int(row_stride), vp(params_ptr), vp(hot_ids_ptr), int(H),
+                                        ctypes.c_uint64(seed & (2 ** 64 - 1)), ctypes.c_uint64(step & (2 ** 64 - 1)),
+                                        ctypes.c_uint64(row_offset & (2 ** 64 - 1)), vp(out_ids_ptr), vp(diag_ptr), vp(stream)))
 
 
 class Sampler:

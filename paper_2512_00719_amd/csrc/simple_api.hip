@@ -32,6 +32,16 @@ struct simple_ctx {
 };
 constexpr int PROF_MAX = 1024;
 
+struct simple_state {
+  int device;
+  int64_t n_slots, V, lmax;
+  uint32_t stride, off_dir, off_cnt;  // bytes of tables per slot; offsets of the rank directory and the counts in them
+  simple::StateRec* rec;
+  int32_t* tokens;
+  unsigned char* tables;
+  void* base;
+};
+
 namespace simple {
 
 // Device memory of a context, carved from one block: hot-set bitmap (max_V bits), one flag word, the
@@ -44,7 +54,7 @@ constexpr int64_t STATIC_MAX_NNZ = 8192;
 constexpr int STATIC_SLOTS = 64;
 constexpr size_t STATIC_BYTES = (size_t)8 << 20;
 
-static uint32_t align16(uint32_t x) { return (x + 15u) & ~15u; }
+uint32_t align16(uint32_t x) { return (x + 15u) & ~15u; }
 
 LdsLayout make_layout(int64_t V, int64_t max_nnz, bool with_history) {
   LdsLayout L{};
@@ -97,7 +107,7 @@ FastLayout make_fast_layout(int64_t V, int dtype, int64_t max_nnz, bool with_his
   return F;
 }
 
-static size_t align256(size_t x) { return (x + 255u) & ~(size_t)255u; }
+size_t align256(size_t x) { return (x + 255u) & ~(size_t)255u; }
 
 CtxLayout ctx_layout(int64_t max_V, int64_t max_nnz, int slots, int lds_limit, int n_cu) {
   CtxLayout L{};
@@ -265,13 +275,18 @@ int simple_set_hot_set(simple_ctx* ctx, const int32_t* hot_ids_dev, int32_t H, i
   return SIMPLE_OK;
 }
 
-int simple_sample(simple_ctx* ctx, const void* logits_dev, int64_t B, int64_t V, int dtype,
-                  int64_t row_stride_elems, const simple_row_params* params_dev,
-                  const int64_t* hist_ptr_dev, const int32_t* hist_ids_dev,
-                  const int32_t* hot_ids_dev, int32_t H, uint64_t seed, uint64_t step,
-                  uint64_t row_offset, int32_t* out_ids_dev, simple_row_diag* diag_dev,
-                  void* hip_stream) {
+}  // extern "C"
+
+// The sampling call; the rows' histories come from the CSR arrays or, with `state`, from its slots.
+static int sample_impl(simple_ctx* ctx, const simple_state* state, const int32_t* slots_dev, const void* logits_dev, int64_t B, int64_t V,
+                       int dtype, int64_t row_stride_elems, const simple_row_params* params_dev,
+                       const int64_t* hist_ptr_dev, const int32_t* hist_ids_dev,
+                       const int32_t* hot_ids_dev, int32_t H, uint64_t seed, uint64_t step,
+                       uint64_t row_offset, int32_t* out_ids_dev, simple_row_diag* diag_dev,
+                       void* hip_stream) {
   if (!ctx || B < 0 || V <= 0) return SIMPLE_EINVAL;
+  if (state && (state->V != V || state->device != ctx->device || hist_ptr_dev || hist_ids_dev)) return SIMPLE_EINVAL;
+  if (state && (state->lmax > ctx->max_nnz || (!slots_dev && B > state->n_slots))) return SIMPLE_ECAPACITY;
   if (dtype != SIMPLE_F32 && dtype != SIMPLE_BF16) return SIMPLE_EINVAL;
   if (row_stride_elems < V) return SIMPLE_EINVAL;
   if (H < -1 || (int64_t)H > V) return SIMPLE_EINVAL;
@@ -298,6 +313,11 @@ int simple_sample(simple_ctx* ctx, const void* logits_dev, int64_t B, int64_t V,
   simple::SampleArgs a{};
   a.logits = logits_dev; a.stride = row_stride_elems; a.V = (int)V;
   a.params = params_dev; a.hist_ptr = hist_ptr_dev; a.hist_ids = hist_ids_dev;
+  const bool with_hist = hist_ptr_dev != nullptr || state != nullptr;
+  if (state) {
+    a.st_rec = state->rec; a.st_tokens = state->tokens; a.st_tables = state->tables;
+    a.st_lmax = (int)state->lmax; a.st_nslots = (int)state->n_slots; a.st_stride = state->stride;
+  }
   a.hot_bits = use_hot ? ctx->hot_bits : nullptr;
   a.hot_flags = use_hot ? ctx->hot_flags : nullptr;
   a.seed = seed; a.step = step;
@@ -306,10 +326,10 @@ int simple_sample(simple_ctx* ctx, const void* logits_dev, int64_t B, int64_t V,
   a.pend = ctx->pend;
   a.n_cu = ctx->n_cu;
   a.wq = ctx->wq; a.wws = ctx->wws; a.wide_slots = ctx->slots; a.ws_stride = ctx->ws_stride;
-  a.L = simple::make_layout(V, ctx->max_nnz, hist_ptr_dev != nullptr);
+  a.L = simple::make_layout(V, ctx->max_nnz, with_hist);
   // rows go out in launches that neither queue can overflow
   const int64_t per_launch = ctx->slots;
-  a.F = simple::make_fast_layout(V, dtype, hist_ptr_dev ? ctx->max_nnz : 0, hist_ptr_dev != nullptr, vec, ctx->lds_limit,
+  a.F = simple::make_fast_layout(V, dtype, with_hist ? ctx->max_nnz : 0, with_hist, vec, ctx->lds_limit,
                                  B < per_launch ? B : per_launch, ctx->n_cu);
   a.gated = (a.F.total != 0u) ? 1 : 0;
   for (int64_t b0 = 0; b0 < B; b0 += per_launch) {
@@ -318,6 +338,8 @@ int simple_sample(simple_ctx* ctx, const void* logits_dev, int64_t B, int64_t V,
     a.logits = static_cast<const char*>(logits_dev) + (size_t)b0 * (size_t)row_stride_elems * esz;
     a.params = params_dev + b0;
     a.hist_ptr = hist_ptr_dev ? hist_ptr_dev + b0 : nullptr;
+    a.st_slots = slots_dev ? slots_dev + b0 : nullptr;
+    a.st_slot0 = (int)b0;
     a.row_offset = row_offset + (uint64_t)b0;
     a.out = out_ids_dev + b0;
     a.diag = diag_dev ? diag_dev + b0 : nullptr;
@@ -328,6 +350,100 @@ int simple_sample(simple_ctx* ctx, const void* logits_dev, int64_t B, int64_t V,
     if (simple::launch_sample(a, dtype, vec, st, ev0, ev1) != hipSuccess) return SIMPLE_EDEVICE;
   }
   return SIMPLE_OK;
+}
+
+extern "C" {
+
+int simple_sample(simple_ctx* ctx, const void* logits_dev, int64_t B, int64_t V, int dtype,
+                  int64_t row_stride_elems, const simple_row_params* params_dev,
+                  const int64_t* hist_ptr_dev, const int32_t* hist_ids_dev,
+                  const int32_t* hot_ids_dev, int32_t H, uint64_t seed, uint64_t step,
+                  uint64_t row_offset, int32_t* out_ids_dev, simple_row_diag* diag_dev,
+                  void* hip_stream) {
+  return sample_impl(ctx, nullptr, nullptr, logits_dev, B, V, dtype, row_stride_elems, params_dev, hist_ptr_dev, hist_ids_dev,
+                     hot_ids_dev, H, seed, step, row_offset, out_ids_dev, diag_dev, hip_stream);
+}
+
+// ---- incremental penalty state (section 5.2) ------------------------------------------------------
+int simple_state_create(simple_state** out, int device, int64_t max_seqs, int64_t V, int64_t L_max) {
+  if (!out) return SIMPLE_EINVAL;
+  *out = nullptr;
+  if (device < 0 || max_seqs <= 0 || max_seqs > (int64_t)0x7FFFFFFF || V <= 0 || V >= (int64_t)1 << 30 || L_max <= 0) return SIMPLE_EINVAL;
+  if (L_max > 65535) return SIMPLE_ECAPACITY;  // 16-bit per-token counts
+  int n_dev = 0;
+  if (hipGetDeviceCount(&n_dev) != hipSuccess || device >= n_dev) return SIMPLE_EDEVICE;
+  simple::DeviceGuard guard(device);
+  if (!guard.ok) return SIMPLE_EDEVICE;
+  int lds = 0;
+  if (hipDeviceGetAttribute(&lds, hipDeviceAttributeMaxSharedMemoryPerBlock, device) != hipSuccess) return SIMPLE_EDEVICE;
+  simple_state* s = new (std::nothrow) simple_state();
+  if (!s) return SIMPLE_ENOMEM;
+  s->device = device; s->n_slots = max_seqs; s->V = V; s->lmax = L_max;
+  // the tables of a slot lie as the single-pass kernel lays them out in LDS (make_fast_layout)
+  const uint32_t n_words = (uint32_t)((V + 31) / 32), n_pairs = (n_words + 1u) / 2u;
+  s->off_dir = simple::align16(n_pairs * 8u);
+  s->off_cnt = simple::align16(s->off_dir + n_pairs * 2u);
+  s->stride = (s->off_cnt + (uint32_t)((L_max + 3) / 2) * 4u + 16u + 255u) & ~255u;
+  if ((int64_t)s->stride + 2048 > (int64_t)lds) { delete s; return SIMPLE_ECAPACITY; }  // the restart kernel builds a slot's tables in LDS
+  if (simple::set_max_lds_state((unsigned)lds - 1024u) != hipSuccess) { delete s; return SIMPLE_EDEVICE; }
+  const size_t rec_b = simple::align256(sizeof(simple::StateRec) * (size_t)max_seqs);
+  const size_t tok_b = simple::align256(4u * (size_t)L_max * (size_t)max_seqs);
+  const size_t tab_b = (size_t)s->stride * (size_t)max_seqs;
+  unsigned char* base = nullptr;
+  if (hipMalloc(reinterpret_cast<void**>(&base), rec_b + tok_b + tab_b) != hipSuccess) { delete s; return SIMPLE_ENOMEM; }
+  if (hipMemset(base, 0, rec_b + tok_b + tab_b) != hipSuccess) { (void)hipFree(base); delete s; return SIMPLE_EDEVICE; }  // every slot: an empty sequence
+  s->base = base;
+  s->rec = reinterpret_cast<simple::StateRec*>(base);
+  s->tokens = reinterpret_cast<int32_t*>(base + rec_b);
+  s->tables = base + rec_b + tok_b;
+  *out = s;
+  return SIMPLE_OK;
+}
+
+void simple_state_destroy(simple_state* state) {
+  if (!state) return;
+  {
+    simple::DeviceGuard guard(state->device);
+    if (guard.ok) {
+      (void)hipDeviceSynchronize();
+      if (state->base) (void)hipFree(state->base);
+    }
+  }
+  delete state;
+}
+
+int simple_state_restart(simple_state* state, const int32_t* slots_dev, int64_t n, const int64_t* prompt_ptr_dev,
+                         const int32_t* prompt_ids_dev, const int32_t* n_prompt_dev, void* hip_stream) {
+  if (!state || n < 0 || n > state->n_slots || (prompt_ptr_dev && !prompt_ids_dev)) return SIMPLE_EINVAL;
+  if (n == 0) return SIMPLE_OK;
+  simple::DeviceGuard guard(state->device);
+  if (!guard.ok) return SIMPLE_EDEVICE;
+  if (simple::launch_state_reset(state->rec, state->tokens, state->tables, (int)state->n_slots, (int)state->lmax, (int)state->V, state->stride,
+                                 state->off_dir, state->off_cnt, slots_dev, (int)n, prompt_ptr_dev, prompt_ids_dev, n_prompt_dev,
+                                 static_cast<hipStream_t>(hip_stream)) != hipSuccess)
+    return SIMPLE_EDEVICE;
+  return SIMPLE_OK;
+}
+
+int simple_state_append(simple_state* state, const int32_t* slots_dev, const int32_t* new_ids_dev, int64_t B, void* hip_stream) {
+  if (!state || B < 0 || (B > 0 && !new_ids_dev) || (!slots_dev && B > state->n_slots) || B > (int64_t)0x7FFFFFFF) return SIMPLE_EINVAL;
+  if (B == 0) return SIMPLE_OK;
+  simple::DeviceGuard guard(state->device);
+  if (!guard.ok) return SIMPLE_EDEVICE;
+  if (simple::launch_state_append(state->rec, state->tokens, state->tables, (int)state->n_slots, (int)state->lmax, (int)state->V, state->stride,
+                                  state->off_dir, state->off_cnt, slots_dev, new_ids_dev, (int)B,
+                                  static_cast<hipStream_t>(hip_stream)) != hipSuccess)
+    return SIMPLE_EDEVICE;
+  return SIMPLE_OK;
+}
+
+int simple_sample_state(simple_ctx* ctx, const simple_state* state, const int32_t* slots_dev, const void* logits_dev, int64_t B, int64_t V,
+                        int dtype, int64_t row_stride_elems, const simple_row_params* params_dev,
+                        const int32_t* hot_ids_dev, int32_t H, uint64_t seed, uint64_t step, uint64_t row_offset,
+                        int32_t* out_ids_dev, simple_row_diag* diag_dev, void* hip_stream) {
+  if (!state) return SIMPLE_EINVAL;
+  return sample_impl(ctx, state, slots_dev, logits_dev, B, V, dtype, row_stride_elems, params_dev, nullptr, nullptr,
+                     hot_ids_dev, H, seed, step, row_offset, out_ids_dev, diag_dev, hip_stream);
 }
 
 // ---- the entry point that allocates nothing -----------------------------------------------------

@@ -65,126 +65,6 @@ __device__ __forceinline__ u64 wfix(uint32_t key, float y_max) {
   return float_to_u64(__builtin_amdgcn_exp2f(t) * 0x1p44f);  // the scaling is exact
 }
 
-// ---------------------------------------------------------------- history ---------------------
-struct Hist {
-  uint32_t* bm;     // V bits
-  uint16_t* dir;    // set bits before each pair of mask words
-  uint32_t* cnt32;  // 16-bit counts by rank, two per word
-  int n_words;
-  float rep, freq, pres;
-  double inv_rep;
-  bool active;
-  __device__ __forceinline__ const uint16_t* cnt() const { return reinterpret_cast<const uint16_t*>(cnt32); }
-  // Rank of column idx among the set bits (`word` is its mask word).
-  __device__ __forceinline__ unsigned rank(int idx, uint32_t word) const {
-    const int w = idx >> 5;
-    unsigned r = (unsigned)dir[w >> 1];
-    if (w & 1) r += (unsigned)__popc(bm[w - 1]);
-    return r + (unsigned)__popc(word & ((1u << (idx & 31)) - 1u));
-  }
-  __device__ __forceinline__ float apply(float z, uint32_t c) const { return apply_penalties(z, c, rep, inv_rep, freq, pres); }
-  __device__ __forceinline__ float penalised_at(float z, int idx) const {
-    const uint32_t word = bm[idx >> 5];
-    if ((word >> (idx & 31)) & 1u) z = apply(z, (uint32_t)cnt()[rank(idx, word)]);
-    return z;
-  }
-};
-
-// Clears `bytes` (rounded up to 16; the regions are 16-byte aligned and padded) with 16-byte stores.
-__device__ __forceinline__ void zero16(void* p, int bytes, int tid, int nthr) {
-  u32x4* q = reinterpret_cast<u32x4*>(p);
-  const u32x4 z = {0u, 0u, 0u, 0u};
-  for (int i = tid; i < (bytes + 15) / 16; i += nthr) q[i] = z;
-}
-
-// The presence mask alone (enough for the threshold sample): ids[j] is history entry tid + j * NTHR.
-template <int NTHR>
-__device__ inline void build_bitmap(FS& S, const Hist& H, const int (&ids)[IDR], const int32_t* __restrict__ hist, int nnz, int V) {
-  const int tid = threadIdx.x;
-  const int n_pairs = (H.n_words + 1) >> 1;
-  zero16(H.bm, n_pairs * 8, tid, NTHR);
-  __syncthreads();
-#pragma unroll
-  for (int j = 0; j < IDR; ++j) {
-    const int i = tid + j * NTHR;
-    if (i < nnz && (unsigned)ids[j] < (unsigned)V) atomicOr(&H.bm[ids[j] >> 5], 1u << (ids[j] & 31));
-  }
-  for (int i = tid + IDR * NTHR; i < nnz; i += NTHR) {
-    const int id = hist[i];
-    if ((unsigned)id < (unsigned)V) atomicOr(&H.bm[id >> 5], 1u << (id & 31));
-  }
-  __syncthreads();
-}
-
-// Builds bitmap, rank directory and counts of one row from the ids a thread holds in registers
-// (ids[j] is history entry tid + j * NTHR) and, beyond those, from global memory.  own gets bit j
-// set when this thread was the first to mark ids[j] (one owner per distinct id).  Out-of-range ids
-// are ignored and flagged.
-template <int NTHR>
-__device__ inline void build_history(FS& S, const Hist& H, const int (&ids)[IDR], const int32_t* __restrict__ hist,
-                                     int nnz, int n_prompt, int V, unsigned& own) {
-  constexpr int NWV = NTHR / 64;
-  const int tid = threadIdx.x;
-  const int n_pairs = (H.n_words + 1) >> 1;
-  zero16(H.bm, n_pairs * 8, tid, NTHR);
-  zero16(H.cnt32, ((nnz + 2) / 2) * 4, tid, NTHR);
-  __syncthreads();
-  bool bad = false;
-  own = 0u;
-#pragma unroll
-  for (int j = 0; j < IDR; ++j) {
-    const int i = tid + j * NTHR;
-    if (i < nnz) {
-      if ((unsigned)ids[j] < (unsigned)V) {
-        const uint32_t bit = 1u << (ids[j] & 31);
-        if (!(atomicOr(&H.bm[ids[j] >> 5], bit) & bit)) own |= 1u << j;
-      } else bad = true;
-    }
-  }
-  for (int i = tid + IDR * NTHR; i < nnz; i += NTHR) {
-    const int id = hist[i];
-    if ((unsigned)id < (unsigned)V) atomicOr(&H.bm[id >> 5], 1u << (id & 31)); else bad = true;
-  }
-  if (bad) atomicOr(&S.flags, SIMPLE_DIAG_BAD_HISTORY_ID);
-  __syncthreads();
-  // directory: exclusive scan of the word pairs' popcounts, NTHR * 8 pairs per round
-  unsigned carry = 0;
-  for (int p0 = 0; p0 < n_pairs; p0 += NTHR * 8) {
-    const int pb = p0 + tid * 8;
-    unsigned pc[8], tot = 0;
-#pragma unroll
-    for (int j = 0; j < 8; ++j) {
-      pc[j] = (pb + j < n_pairs) ? (unsigned)(__popc(H.bm[2 * (pb + j)]) + __popc(H.bm[2 * (pb + j) + 1])) : 0u;
-      tot += pc[j];
-    }
-    const unsigned incl = wave_incl_scan(tot);
-    __syncthreads();
-    if (lane_id() == 63) S.r32a[wave_id()] = incl;
-    __syncthreads();
-    unsigned base = 0, all = 0;
-#pragma unroll
-    for (int w = 0; w < NWV; ++w) { const unsigned x = S.r32a[w]; if (w < wave_id()) base += x; all += x; }
-    unsigned run = carry + base + incl - tot;
-#pragma unroll
-    for (int j = 0; j < 8; ++j) { if (pb + j < n_pairs) H.dir[pb + j] = (uint16_t)run; run += pc[j]; }
-    carry += all;
-  }
-  if (tid == 0) S.distinct = carry;
-  __syncthreads();
-  n_prompt = min(max(n_prompt, 0), nnz);
-  auto count_one = [&](int id) {
-    if ((unsigned)id < (unsigned)V) {
-      const unsigned r = H.rank(id, H.bm[id >> 5]);
-      atomicAdd(&H.cnt32[r >> 1], 1u << ((r & 1u) * 16u));
-    }
-  };
-#pragma unroll
-  for (int j = 0; j < IDR; ++j) { const int i = tid + j * NTHR; if (i >= n_prompt && i < nnz) count_one(ids[j]); }
-  for (int i = tid + IDR * NTHR; i < nnz; i += NTHR) if (i >= n_prompt) count_one(hist[i]);
-  __syncthreads();
-}
-
-
 // Unpacks one 16-byte group of a sample tile; columns that are in the history are masked out, so
 // the threshold comes from unpenalised columns only (history columns can only add to the prefix).
 template <typename DT>
@@ -580,8 +460,11 @@ __device__ inline void queue_pending(const SampleArgs& a, int row) {
 }
 
 // ---------------------------------------------------------------- the kernel ------------------
+// (The second launch bound is HIP's: waves per SIMD, not workgroups per compute unit.  Four waves per
+// SIMD, 128 registers each, are sixteen waves per compute unit at every workgroup size: four
+// workgroups of 256 threads, two of 512, one of 1024.)
 template <typename DT, int NTHR>
-__global__ __launch_bounds__(NTHR, NTHR == 256 ? 4 : (NTHR == 512 ? 2 : 1)) void fast_rows_kernel(const SampleArgs a) {
+__global__ __launch_bounds__(NTHR, 4) void fast_rows_kernel(const SampleArgs a) {
   constexpr int NWV = NTHR / 64;
   constexpr int EPL = Io<DT>::EPL;
   constexpr int T = 64 * EPL * UNR;
@@ -617,8 +500,9 @@ __global__ __launch_bounds__(NTHR, NTHR == 256 ? 4 : (NTHR == 512 ? 2 : 1)) void
   R.p_le0 = par.top_p <= 0.0f;
   R.minp_on = par.min_p > 0.0f;
   R.need_sum = !R.greedy && !R.k_on && R.p_on && !R.p_le0;
-  long long h0 = 0; int nnz = 0;
-  if (a.hist_ptr) { h0 = a.hist_ptr[row]; const long long h1 = a.hist_ptr[row + 1]; nnz = (int)min(max(h1 - h0, 0ll), (long long)a.max_nnz + 1); }
+  const RowHist rh = row_history(a, row, par.n_prompt);  // the call's CSR arrays, or the row's slot of an incremental state
+  const int nnz = rh.nnz;
+  const bool stateful = a.st_rec != nullptr;
   const bool too_long = nnz > a.max_nnz;
   const bool pen_on = par.rep_penalty != 1.0f || par.freq_penalty != 0.0f || par.pres_penalty != 0.0f;
   const bool lowering = par.rep_penalty >= 1.0f && par.freq_penalty >= 0.0f && par.pres_penalty >= 0.0f;
@@ -649,7 +533,18 @@ __global__ __launch_bounds__(NTHR, NTHR == 256 ? 4 : (NTHR == 512 ? 2 : 1)) void
     S.n2 = 0u; S.nunc = 0u; S.e_rc = FIN_PENDING; S.e_n = 0u; S.tile_ctr = 0u;
   }
   // ---- loads first: history ids, then this wave's two sample tiles ----
-  const int32_t* hist = a.hist_ids + h0;
+  const int32_t* hist = rh.ids;
+  // With a state the tables come ready-made from the row's slot (section 5.2: carried from step to
+  // step, not rebuilt): `whole` = mask, rank directory and counts, else the mask alone.  Ends with a barrier.
+  auto load_tables = [&](bool whole) {
+    const unsigned n_pairs = (unsigned)((((V + 31) >> 5) + 1) >> 1);
+    const unsigned units = whole ? (a.F.cnt + (unsigned)((nnz + 3) / 2) * 4u + 15u) / 16u : (n_pairs * 8u + 15u) / 16u;
+    const u32x4* src = reinterpret_cast<const u32x4*>(a.st_tables + (size_t)rh.slot * a.st_stride);
+    u32x4* dst = reinterpret_cast<u32x4*>(lds);
+    for (unsigned i = tid; i < units; i += NTHR) dst[i] = as_global(src)[i];
+    if (tid == 0) { S.distinct = (unsigned)a.st_rec[rh.slot].distinct; if (rh.flags) atomicOr(&S.flags, rh.flags); }
+    __syncthreads();
+  };
   Hist H;
   H.bm = reinterpret_cast<uint32_t*>(lds + a.F.bitmap);
   H.dir = reinterpret_cast<uint16_t*>(lds + a.F.dir);
@@ -661,7 +556,7 @@ __global__ __launch_bounds__(NTHR, NTHR == 256 ? 4 : (NTHR == 512 ? 2 : 1)) void
   {
     int ids[IDR];
 #pragma unroll
-    for (int j = 0; j < IDR; ++j) { const int i = tid + j * NTHR; ids[j] = (h_active && i < nnz) ? hist[i] : -1; }
+    for (int j = 0; j < IDR; ++j) { const int i = tid + j * NTHR; ids[j] = (h_active && !stateful && i < nnz) ? hist[i] : -1; }
     {
       double u[3];
       row_uniforms(a.seed, a.row_offset + (uint64_t)row, a.step, u);
@@ -670,7 +565,8 @@ __global__ __launch_bounds__(NTHR, NTHR == 256 ? 4 : (NTHR == 512 ? 2 : 1)) void
     __syncthreads();
     // ---- presence mask of the history (in the shared region); all tables for a row that leaves early ----
     if (H.active) {
-      if (straight) { unsigned own; build_history<NTHR>(S, H, ids, hist, nnz, par.n_prompt, V, own); }
+      if (stateful) load_tables(straight);
+      else if (straight) { unsigned own; build_history<NTHR>(S, H, ids, hist, nnz, rh.n_prompt, V, own); }
       else build_bitmap<NTHR>(S, H, ids, hist, nnz, V);
     }
   }
@@ -746,11 +642,14 @@ __global__ __launch_bounds__(NTHR, NTHR == 256 ? 4 : (NTHR == 512 ? 2 : 1)) void
   auto queue_wide = [&](uint32_t mode, bool tables_live) -> bool {
     __syncthreads();
     if (H.active && !tables_live) {
-      int ids2[IDR];
+      if (stateful) load_tables(true);
+      else {
+        int ids2[IDR];
 #pragma unroll
-      for (int j = 0; j < IDR; ++j) { const int i = tid + j * NTHR; ids2[j] = (i < nnz) ? hist[i] : -1; }
-      unsigned own;
-      build_history<NTHR>(S, H, ids2, hist, nnz, par.n_prompt, V, own);
+        for (int j = 0; j < IDR; ++j) { const int i = tid + j * NTHR; ids2[j] = (i < nnz) ? hist[i] : -1; }
+        unsigned own;
+        build_history<NTHR>(S, H, ids2, hist, nnz, rh.n_prompt, V, own);
+      }
     }
     if (tid == 0) S.e_n = atomicAdd(&a.wq[a.parity], 1u);
     __syncthreads();
@@ -768,7 +667,7 @@ __global__ __launch_bounds__(NTHR, NTHR == 256 ? 4 : (NTHR == 512 ? 2 : 1)) void
       WideRec rec;
       rec.row = (uint32_t)row; rec.g = C.g; rec.mode = mode; rec.flags = S.flags & 0x3FFFFFFFu;
       rec.tau = R.tau; rec.top_p = R.top_p; rec.rep = par.rep_penalty; rec.freq = par.freq_penalty;
-      rec.pres = par.pres_penalty; rec.nnz = nnz; rec.n_prompt = min(max(par.n_prompt, 0), nnz); rec.h_active = h_active ? 1 : 0;
+      rec.pres = par.pres_penalty; rec.nnz = nnz; rec.n_prompt = min(max(rh.n_prompt, 0), nnz); rec.h_active = h_active ? 1 : 0;
       rec.min_p = R.min_p; rec.top_k = par.top_k; rec.distinct = H.active ? S.distinct : 0u; rec.reserved1 = 0u;
       reinterpret_cast<WideRec*>(a.wq + WQ_HEAD)[slot] = rec;
       a.out[row] = PENDING;
@@ -846,7 +745,7 @@ __global__ __launch_bounds__(NTHR, NTHR == 256 ? 4 : (NTHR == 512 ? 2 : 1)) void
   // the epilogue rebuilds the history tables: fetch the ids while the other waves finish
   int ids[IDR];
 #pragma unroll
-  for (int j = 0; j < IDR; ++j) { const int i = tid + j * NTHR; ids[j] = (h_active && i < nnz) ? hist[i] : -1; }
+  for (int j = 0; j < IDR; ++j) { const int i = tid + j * NTHR; ids[j] = (h_active && (!stateful || R.need_sum) && i < nnz) ? hist[i] : -1; }
   // ragged tail, element by element
   for (int idx = nfull * T + tid; idx < V; idx += NTHR) {
     const float zz = Io<DT>::one(rowp + idx);
@@ -884,7 +783,8 @@ __global__ __launch_bounds__(NTHR, NTHR == 256 ? 4 : (NTHR == 512 ? 2 : 1)) void
     __syncthreads();
     if (H.active) {
       unsigned own = 0u;
-      build_history<NTHR>(S, H, ids, hist, nnz, par.n_prompt, V, own);
+      if (stateful) load_tables(true);
+      else build_history<NTHR>(S, H, ids, hist, nnz, rh.n_prompt, V, own);
 #pragma unroll
       for (int j = 0; j < PER; ++j) {
         const unsigned i = (unsigned)tid + (unsigned)j * NTHR;
@@ -894,7 +794,7 @@ __global__ __launch_bounds__(NTHR, NTHR == 256 ? 4 : (NTHR == 512 ? 2 : 1)) void
         // exact correction of the mass below g for the history columns (the stream summed their raw
         // values), once per distinct column: by the thread that first marked it when all ids sit in
         // registers, else by the thread that first claims the column's rank
-        const bool by_claim = nnz > IDR * NTHR;
+        const bool by_claim = stateful || nnz > IDR * NTHR;  // (ready-made tables come without first-marker flags)
         uint32_t* claim = reinterpret_cast<uint32_t*>(lds + a.F.claim);
         if (by_claim) {
           zero16(claim, ((nnz + 31) / 32) * 4, tid, NTHR);

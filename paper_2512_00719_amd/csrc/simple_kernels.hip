@@ -1395,8 +1395,8 @@ __device__ inline void sample_row_body(const SampleArgs& a, const int row, unsig
   const bool bad_par = !(par.temperature >= 0.0f) || !(par.rep_penalty > 0.0f);
   const bool greedy = par.temperature == 0.0f;
   const bool k_on = par.top_k >= 1 && par.top_k < V;
-  long long h0 = 0; int nnz = 0;
-  if (a.hist_ptr) { h0 = a.hist_ptr[row]; const long long h1 = a.hist_ptr[row + 1]; nnz = (int)min(max(h1 - h0, 0ll), (long long)a.max_nnz + 1); }
+  const RowHist rh = row_history(a, row, par.n_prompt);  // the call's CSR arrays, or the row's slot of an incremental state
+  const int nnz = rh.nnz;
   const bool too_long = nnz > a.max_nnz;
   const bool pen_on = par.rep_penalty != 1.0f || par.freq_penalty != 0.0f || par.pres_penalty != 0.0f;
   const bool lowering = par.rep_penalty >= 1.0f && par.freq_penalty >= 0.0f && par.pres_penalty >= 0.0f;
@@ -1431,7 +1431,7 @@ __device__ inline void sample_row_body(const SampleArgs& a, const int row, unsig
   H.rep = par.rep_penalty; H.freq = par.freq_penalty; H.pres = par.pres_penalty;
   H.active = (nnz > 0) && pen_on;
   if (H.active) {
-    if (!build_history(H, a.hist_ids + h0, nnz, par.n_prompt, V, S.scan_u32, &S.flag_ws)) dg.flags |= SIMPLE_DIAG_BAD_HISTORY_ID;
+    if (!build_history(H, rh.ids, nnz, rh.n_prompt, V, S.scan_u32, &S.flag_ws)) dg.flags |= SIMPLE_DIAG_BAD_HISTORY_ID;
   }
   if (a.hot_bits && a.hot_flags && *a.hot_flags) dg.flags |= SIMPLE_DIAG_BAD_HOT_SET;
   const uint32_t* hot_bits = greedy ? nullptr : a.hot_bits;

@@ -42,6 +42,14 @@ constexpr int WIDE_SLOTS = 4096; // workspace slots of the whole-vocabulary-nucl
                                  // so every row of it can be queued for them
 constexpr uint32_t WIDE_SLOT_FIXED = 53312;  // workspace per such row, before its history tables
 
+// Incremental penalty state (paper section 5.2), one record per sequence slot.
+struct StateRec {
+  int32_t len;       // tokens of the sequence so far (prompt, then generated); above the capacity: too long
+  int32_t n_prompt;  // the first n_prompt of them are the prompt
+  int32_t distinct;  // distinct ids among them (set bits of the presence mask)
+  uint32_t flags;    // SIMPLE_DIAG_BAD_HISTORY_ID if an id outside [0, V) was met (it is ignored)
+};
+
 struct SampleArgs {
   const void* logits;
   int64_t stride;  // elements between rows
@@ -55,6 +63,15 @@ struct SampleArgs {
   int32_t* out;
   simple_row_diag* diag;
   simple_stats* stats;  // aggregate over rows, or nullptr
+  // With an incremental penalty state (st_rec != nullptr) a row's history is its sequence slot's:
+  // the token list in st_tokens and, ready-made, the tables the single-pass kernel otherwise builds
+  // in LDS from that list (presence mask, rank directory, counts by rank, at the same offsets).
+  const StateRec* st_rec;
+  const int32_t* st_tokens;         // st_lmax ids per slot
+  const unsigned char* st_tables;   // st_stride bytes per slot
+  const int32_t* st_slots;          // slot of each row of the launch, or nullptr: row b uses slot st_slot0 + b
+  int st_lmax, st_nslots, st_slot0;
+  uint32_t st_stride;
   int max_nnz;
   int gated;       // 1: the single-pass kernel runs first and queues the rows it leaves
   // Queues filled by the single-pass kernel.  Word [parity] counts the entries of this launch; the
@@ -70,6 +87,31 @@ struct SampleArgs {
   FastLayout F;
 };
 
+// Where a row's token history comes from: the CSR arrays of the call, or its slot of the state.
+struct RowHist { const int32_t* ids; int nnz, n_prompt, slot; uint32_t flags; };
+__device__ __forceinline__ RowHist row_history(const SampleArgs& a, int row, int par_n_prompt) {
+  RowHist h;
+  h.ids = nullptr; h.nnz = 0; h.n_prompt = par_n_prompt; h.slot = -1; h.flags = 0u;
+  if (a.st_rec) {
+    const int slot = a.st_slots ? a.st_slots[row] : a.st_slot0 + row;
+    if ((unsigned)slot >= (unsigned)a.st_nslots) { h.nnz = a.max_nnz + 1; return h; }  // reported as a history that is too long
+    const StateRec rec = a.st_rec[slot];
+    h.slot = slot;
+    h.ids = a.st_tokens + (size_t)slot * (size_t)a.st_lmax;
+    h.nnz = (rec.len > a.st_lmax || rec.len > a.max_nnz) ? a.max_nnz + 1 : max(rec.len, 0);
+    h.n_prompt = rec.n_prompt;
+    h.flags = rec.flags;
+  } else if (a.hist_ptr) {
+    const long long h0 = a.hist_ptr[row], h1 = a.hist_ptr[row + 1];
+    long long n = h1 - h0;
+    if (n < 0) n = 0;
+    if (n > (long long)a.max_nnz + 1) n = (long long)a.max_nnz + 1;
+    h.nnz = (int)n;
+    h.ids = a.hist_ids + h0;
+  }
+  return h;
+}
+
 LdsLayout make_layout(int64_t V, int64_t max_nnz, bool with_history);
 // Layout of the single-pass kernel; total = 0 when the call cannot use it.
 FastLayout make_fast_layout(int64_t V, int dtype, int64_t max_nnz, bool with_history, bool vec, int lds_limit,
@@ -79,6 +121,12 @@ hipError_t launch_fast(const SampleArgs& a, int dtype, hipStream_t st);
 hipError_t launch_wide(const SampleArgs& a, int dtype, hipStream_t st);  // after launch_fast, before the general kernel
 hipError_t set_max_lds(unsigned bytes);
 hipError_t set_max_lds_fast(unsigned bytes);
+hipError_t launch_state_reset(StateRec* rec, int32_t* tokens, unsigned char* tables, int n_slots, int lmax, int V, uint32_t stride,
+                              uint32_t off_dir, uint32_t off_cnt, const int32_t* slots, int n, const int64_t* prompt_ptr,
+                              const int32_t* prompt_ids, const int32_t* n_prompt, hipStream_t st);
+hipError_t launch_state_append(StateRec* rec, int32_t* tokens, unsigned char* tables, int n_slots, int lmax, int V, uint32_t stride,
+                               uint32_t off_dir, uint32_t off_cnt, const int32_t* slots, const int32_t* new_ids, int B, hipStream_t st);
+hipError_t set_max_lds_state(unsigned bytes);
 hipError_t launch_hot_build(const int32_t* ids, int H, int V, uint32_t* bits, uint32_t* flags, hipStream_t st);
 
 }  // namespace simple

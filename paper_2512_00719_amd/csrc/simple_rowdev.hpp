@@ -189,6 +189,126 @@ __device__ __forceinline__ float apply_penalties(float z, uint32_t count, float 
   return z;
 }
 
+// ---------------------------------------------------------------- history ---------------------
+struct Hist {
+  uint32_t* bm;     // V bits
+  uint16_t* dir;    // set bits before each pair of mask words
+  uint32_t* cnt32;  // 16-bit counts by rank, two per word
+  int n_words;
+  float rep, freq, pres;
+  double inv_rep;
+  bool active;
+  __device__ __forceinline__ const uint16_t* cnt() const { return reinterpret_cast<const uint16_t*>(cnt32); }
+  // Rank of column idx among the set bits (`word` is its mask word).
+  __device__ __forceinline__ unsigned rank(int idx, uint32_t word) const {
+    const int w = idx >> 5;
+    unsigned r = (unsigned)dir[w >> 1];
+    if (w & 1) r += (unsigned)__popc(bm[w - 1]);
+    return r + (unsigned)__popc(word & ((1u << (idx & 31)) - 1u));
+  }
+  __device__ __forceinline__ float apply(float z, uint32_t c) const { return apply_penalties(z, c, rep, inv_rep, freq, pres); }
+  __device__ __forceinline__ float penalised_at(float z, int idx) const {
+    const uint32_t word = bm[idx >> 5];
+    if ((word >> (idx & 31)) & 1u) z = apply(z, (uint32_t)cnt()[rank(idx, word)]);
+    return z;
+  }
+};
+
+// Clears `bytes` (rounded up to 16; the regions are 16-byte aligned and padded) with 16-byte stores.
+__device__ __forceinline__ void zero16(void* p, int bytes, int tid, int nthr) {
+  u32x4* q = reinterpret_cast<u32x4*>(p);
+  const u32x4 z = {0u, 0u, 0u, 0u};
+  for (int i = tid; i < (bytes + 15) / 16; i += nthr) q[i] = z;
+}
+
+// The presence mask alone (enough for the threshold sample): ids[j] is history entry tid + j * NTHR.
+template <int NTHR>
+__device__ inline void build_bitmap(FS& S, const Hist& H, const int (&ids)[IDR], const int32_t* __restrict__ hist, int nnz, int V) {
+  const int tid = threadIdx.x;
+  const int n_pairs = (H.n_words + 1) >> 1;
+  zero16(H.bm, n_pairs * 8, tid, NTHR);
+  __syncthreads();
+#pragma unroll
+  for (int j = 0; j < IDR; ++j) {
+    const int i = tid + j * NTHR;
+    if (i < nnz && (unsigned)ids[j] < (unsigned)V) atomicOr(&H.bm[ids[j] >> 5], 1u << (ids[j] & 31));
+  }
+  for (int i = tid + IDR * NTHR; i < nnz; i += NTHR) {
+    const int id = hist[i];
+    if ((unsigned)id < (unsigned)V) atomicOr(&H.bm[id >> 5], 1u << (id & 31));
+  }
+  __syncthreads();
+}
+
+// Builds bitmap, rank directory and counts of one row from the ids a thread holds in registers
+// (ids[j] is history entry tid + j * NTHR) and, beyond those, from global memory.  own gets bit j
+// set when this thread was the first to mark ids[j] (one owner per distinct id).  Out-of-range ids
+// are ignored and flagged.
+template <int NTHR>
+__device__ inline void build_history(FS& S, const Hist& H, const int (&ids)[IDR], const int32_t* __restrict__ hist,
+                                     int nnz, int n_prompt, int V, unsigned& own) {
+  constexpr int NWV = NTHR / 64;
+  const int tid = threadIdx.x;
+  const int n_pairs = (H.n_words + 1) >> 1;
+  zero16(H.bm, n_pairs * 8, tid, NTHR);
+  zero16(H.cnt32, ((nnz + 2) / 2) * 4, tid, NTHR);
+  __syncthreads();
+  bool bad = false;
+  own = 0u;
+#pragma unroll
+  for (int j = 0; j < IDR; ++j) {
+    const int i = tid + j * NTHR;
+    if (i < nnz) {
+      if ((unsigned)ids[j] < (unsigned)V) {
+        const uint32_t bit = 1u << (ids[j] & 31);
+        if (!(atomicOr(&H.bm[ids[j] >> 5], bit) & bit)) own |= 1u << j;
+      } else bad = true;
+    }
+  }
+  for (int i = tid + IDR * NTHR; i < nnz; i += NTHR) {
+    const int id = hist[i];
+    if ((unsigned)id < (unsigned)V) atomicOr(&H.bm[id >> 5], 1u << (id & 31)); else bad = true;
+  }
+  if (bad) atomicOr(&S.flags, SIMPLE_DIAG_BAD_HISTORY_ID);
+  __syncthreads();
+  // directory: exclusive scan of the word pairs' popcounts, NTHR * 8 pairs per round
+  unsigned carry = 0;
+  for (int p0 = 0; p0 < n_pairs; p0 += NTHR * 8) {
+    const int pb = p0 + tid * 8;
+    unsigned pc[8], tot = 0;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      pc[j] = (pb + j < n_pairs) ? (unsigned)(__popc(H.bm[2 * (pb + j)]) + __popc(H.bm[2 * (pb + j) + 1])) : 0u;
+      tot += pc[j];
+    }
+    const unsigned incl = wave_incl_scan(tot);
+    __syncthreads();
+    if (lane_id() == 63) S.r32a[wave_id()] = incl;
+    __syncthreads();
+    unsigned base = 0, all = 0;
+#pragma unroll
+    for (int w = 0; w < NWV; ++w) { const unsigned x = S.r32a[w]; if (w < wave_id()) base += x; all += x; }
+    unsigned run = carry + base + incl - tot;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) { if (pb + j < n_pairs) H.dir[pb + j] = (uint16_t)run; run += pc[j]; }
+    carry += all;
+  }
+  if (tid == 0) S.distinct = carry;
+  __syncthreads();
+  n_prompt = min(max(n_prompt, 0), nnz);
+  auto count_one = [&](int id) {
+    if ((unsigned)id < (unsigned)V) {
+      const unsigned r = H.rank(id, H.bm[id >> 5]);
+      atomicAdd(&H.cnt32[r >> 1], 1u << ((r & 1u) * 16u));
+    }
+  };
+#pragma unroll
+  for (int j = 0; j < IDR; ++j) { const int i = tid + j * NTHR; if (i >= n_prompt && i < nnz) count_one(ids[j]); }
+  for (int i = tid + IDR * NTHR; i < nnz; i += NTHR) if (i >= n_prompt) count_one(hist[i]);
+  __syncthreads();
+}
+
+
 // ---------------------------------------------------------------- stream ----------------------
 struct StreamCtx {
   float g, y_g;    // candidate threshold on the logit, and its tempered value fl32(g / tau)

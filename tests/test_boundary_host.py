@@ -43,6 +43,17 @@ def test_null_context_and_bad_arguments_are_rejected_on_the_host():
     assert binding.simple_sample(0, 0, 1, 8, 0, 8, 0, 0, 0, 0, 0, 1, 0, 0, 0, 0) == binding.SIMPLE_EINVAL
     assert binding.simple_set_hot_set(0, 0, 4, 8) == binding.SIMPLE_EINVAL
     assert binding.simple_set_stats(0, 0) == binding.SIMPLE_EINVAL
+    # incremental penalty state: NULL handles and sizes are rejected on the host
+    assert binding.simple_state_restart(0, 0, 1, 0, 0, 0) == binding.SIMPLE_EINVAL
+    assert binding.simple_state_append(0, 0, 0, 1) == binding.SIMPLE_EINVAL
+    assert binding.simple_sample_state(0, 0, 0, 0, 1, 8, 0, 8, 0, 0, 0, 1, 0, 0, 0, 0) == binding.SIMPLE_EINVAL
+    binding.simple_state_destroy(None)  # accepted
+    with pytest.raises(binding.SimpleError) as e:
+        binding.simple_state_create(0, 4, 1024, 70000)  # counts are 16-bit
+    assert e.value.code == binding.SIMPLE_ECAPACITY
+    with pytest.raises(binding.SimpleError) as e:
+        binding.simple_state_create(0, 0, 1024, 16)
+    assert e.value.code == binding.SIMPLE_EINVAL
     assert binding.simple_lds_bytes(0) == binding.SIMPLE_EINVAL
     binding.simple_destroy(None)  # accepted
     with pytest.raises(binding.SimpleError) as e:
