@@ -160,6 +160,19 @@ int simple_set_hot_set(simple_ctx* ctx, const int32_t* hot_ids_dev, int32_t H, i
 int simple_set_stats(simple_ctx* ctx, simple_stats* stats_dev);
 
 /*
+ * The rest of the decisions record the paper's samplers return beside the token ids (section 4.2,
+ * step 6: "next-token ids, EOS flags, optional log-probs").  Install (or, with NULLs, remove)
+ * per-row outputs that later sampling calls on this context fill, row b of a call at index b:
+ *   logprobs_dev   [max rows of a call] float: natural log of p~ of the returned id (0 for a greedy
+ *                  row, -inf for a row whose id is -1)
+ *   eos_dev        [max rows of a call] uint8: 1 if the returned id is one of the end-of-sequence ids
+ * eos_ids_host: n_eos (0..8) token ids, host memory, copied.  Either output pointer may be NULL.
+ * Host-side only: nothing is enqueued.  SIMPLE_EINVAL for a NULL context, n_eos outside [0, 8] or
+ * n_eos > 0 without eos_ids_host.
+ */
+int simple_set_decision_outputs(simple_ctx* ctx, float* logprobs_dev, uint8_t* eos_dev, const int32_t* eos_ids_host, int n_eos);
+
+/*
  * The sampling call (section 2.1 steps (1)-(3); section 5.3 when a hot set is in force).
  *
  *  logits_dev        [B, row_stride_elems] row-major, dtype SIMPLE_F32 (float) or SIMPLE_BF16

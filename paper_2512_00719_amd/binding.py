@@ -34,7 +34,7 @@ STATS_DTYPE = np.dtype([("rows", "<u8"), ("greedy_rows", "<u8"), ("shvs_accepted
                         ("error_flags", "<u4"), ("reserved", "<u4")])
 assert STATS_DTYPE.itemsize == 64
 
-EXPORTS = ("simple_create", "simple_destroy", "simple_set_hot_set", "simple_set_stats", "simple_sample",
+EXPORTS = ("simple_create", "simple_destroy", "simple_set_hot_set", "simple_set_stats", "simple_set_decision_outputs", "simple_sample",
            "simple_sample_static", "simple_static_limit",
            "simple_state_create", "simple_state_destroy", "simple_state_restart", "simple_state_append", "simple_sample_state",
            "simple_profile_enable", "simple_profile_read", "simple_profile_read_launches",
@@ -53,6 +53,8 @@ def _load() -> ctypes.CDLL:
     lib.simple_destroy.restype = None
     lib.simple_set_hot_set.argtypes = [vp, vp, i32, i64, vp]
     lib.simple_set_hot_set.restype = ctypes.c_int
+    lib.simple_set_decision_outputs.argtypes = [vp, vp, vp, ctypes.POINTER(ctypes.c_int32), ctypes.c_int]
+    lib.simple_set_decision_outputs.restype = ctypes.c_int
     lib.simple_set_stats.argtypes = [vp, vp]
     lib.simple_set_stats.restype = ctypes.c_int
     lib.simple_sample.argtypes = [vp, vp, i64, i64, ctypes.c_int, i64, vp, vp, vp, vp, i32, u64, u64, u64,
@@ -158,6 +160,13 @@ def simple_stream_probe(logits_ptr: int, B: int, V: int, dtype: int, row_stride:
 def simple_set_hot_set(ctx: int, hot_ids_ptr: int, H: int, V: int, stream: int = 0) -> int:
     return int(_lib.simple_set_hot_set(ctypes.c_void_p(ctx), ctypes.c_void_p(hot_ids_ptr), int(H), int(V),
                                        ctypes.c_void_p(stream)))
+
+
+def simple_set_decision_outputs(ctx: int, logprobs_ptr: int, eos_ptr: int, eos_ids=()) -> int:
+    """Install per-row log-probability (float32) and EOS-flag (uint8) outputs; eos_ids: up to 8 token ids."""
+    ids = (ctypes.c_int32 * max(len(eos_ids), 1))(*[int(x) for x in eos_ids])
+    return int(_lib.simple_set_decision_outputs(ctypes.c_void_p(ctx), ctypes.c_void_p(logprobs_ptr), ctypes.c_void_p(eos_ptr), ids,
+                                                len(eos_ids)))
 
 
 def simple_set_stats(ctx: int, stats_ptr: int) -> int:

@@ -29,6 +29,10 @@ struct simple_ctx {
   int prof_n;           // launches recorded so far
   void* base;           // device allocation that holds all of the above (null: not owned)
   simple_stats* stats;  // caller's aggregate (device), or null
+  float* logprobs;      // caller's per-row outputs (device), or null
+  uint8_t* eos_out;
+  int32_t eos_ids[8];
+  int n_eos;
 };
 constexpr int PROF_MAX = 1024;
 
@@ -175,6 +179,7 @@ int simple_create(simple_ctx** out, int device, int64_t max_B, int64_t max_V, in
   c->device = device; c->max_V = max_V; c->max_nnz = max_nnz_per_row; c->lds_limit = lds; c->n_cu = n_cu;
   c->hot_V = 0; c->hot_H = 0; c->hot_bits = nullptr; c->hot_flags = nullptr; c->pend = nullptr; c->wq = nullptr; c->wws = nullptr; c->ws_stride = 0; c->parity = 0;
   c->prof_ev = nullptr; c->prof_n = 0; c->base = nullptr; c->slots = 0; c->stats = nullptr;
+  c->logprobs = nullptr; c->eos_out = nullptr; c->n_eos = 0;
   c->slots = (int)(max_B < (int64_t)simple::WIDE_SLOTS ? max_B : (int64_t)simple::WIDE_SLOTS);
   const simple::CtxLayout CL = simple::ctx_layout(max_V, max_nnz_per_row, c->slots, lds, n_cu);
   unsigned char* base = nullptr;
@@ -214,6 +219,13 @@ void simple_destroy(simple_ctx* ctx) {
 int simple_set_stats(simple_ctx* ctx, simple_stats* stats_dev) {
   if (!ctx || (reinterpret_cast<uintptr_t>(stats_dev) & 7u) != 0) return SIMPLE_EINVAL;
   ctx->stats = stats_dev;
+  return SIMPLE_OK;
+}
+
+int simple_set_decision_outputs(simple_ctx* ctx, float* logprobs_dev, uint8_t* eos_dev, const int32_t* eos_ids_host, int n_eos) {
+  if (!ctx || n_eos < 0 || n_eos > 8 || (n_eos > 0 && !eos_ids_host)) return SIMPLE_EINVAL;
+  ctx->logprobs = logprobs_dev; ctx->eos_out = eos_dev; ctx->n_eos = n_eos;
+  for (int i = 0; i < 8; ++i) ctx->eos_ids[i] = i < n_eos ? eos_ids_host[i] : -1;
   return SIMPLE_OK;
 }
 
@@ -322,6 +334,8 @@ static int sample_impl(simple_ctx* ctx, const simple_state* state, const int32_t
   a.hot_flags = use_hot ? ctx->hot_flags : nullptr;
   a.seed = seed; a.step = step;
   a.stats = ctx->stats;
+  a.n_eos = ctx->n_eos;
+  for (int i = 0; i < 8; ++i) a.eos_ids[i] = ctx->eos_ids[i];
   a.max_nnz = (int)ctx->max_nnz;
   a.pend = ctx->pend;
   a.n_cu = ctx->n_cu;
@@ -343,6 +357,8 @@ static int sample_impl(simple_ctx* ctx, const simple_state* state, const int32_t
     a.row_offset = row_offset + (uint64_t)b0;
     a.out = out_ids_dev + b0;
     a.diag = diag_dev ? diag_dev + b0 : nullptr;
+    a.logprobs = ctx->logprobs ? ctx->logprobs + b0 : nullptr;
+    a.eos_out = ctx->eos_out ? ctx->eos_out + b0 : nullptr;
     a.parity = ctx->parity;
     if (a.gated) ctx->parity ^= 1;
     hipEvent_t ev0 = nullptr, ev1 = nullptr;

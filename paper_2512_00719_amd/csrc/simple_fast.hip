@@ -945,6 +945,7 @@ __global__ __launch_bounds__(NTHR, 4) void fast_rows_kernel(const SampleArgs a) 
       if (err) dg.p_chosen = 0.0f;
       if (a.diag) a.diag[row] = dg;
       if (a.stats) stats_add(a.stats, dg.flags, dg.alpha);
+      write_decision(a, row, err ? -1 : S.out_id, dg.p_chosen, R.greedy);
     }
   }
 }

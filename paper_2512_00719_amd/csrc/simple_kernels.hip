@@ -1418,6 +1418,7 @@ __device__ inline void sample_row_body(const SampleArgs& a, const int row, unsig
       dg.flags |= SIMPLE_DIAG_ERROR | (bad_par ? SIMPLE_DIAG_BAD_PARAM : 0u) | (too_long ? SIMPLE_DIAG_HISTORY_TOO_LONG : 0u);
       if (a.diag) a.diag[row] = dg;
       if (a.stats) stats_add(a.stats, dg.flags, dg.alpha);
+      write_decision(a, row, -1, 0.0f, false);
     }
     return;
   }
@@ -1513,6 +1514,7 @@ __device__ inline void sample_row_body(const SampleArgs& a, const int row, unsig
     dg.p_chosen = err ? 0.0f : S.out_p;
     if (a.diag) a.diag[row] = dg;
     if (a.stats) stats_add(a.stats, dg.flags, dg.alpha);
+    write_decision(a, row, err ? -1 : S.out_id, dg.p_chosen, greedy);
   }
 }
 

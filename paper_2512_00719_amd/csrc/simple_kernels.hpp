@@ -63,6 +63,10 @@ struct SampleArgs {
   int32_t* out;
   simple_row_diag* diag;
   simple_stats* stats;  // aggregate over rows, or nullptr
+  float* logprobs;      // ln p~ of the returned id per row, or nullptr
+  uint8_t* eos_out;     // 1 where the returned id is an end-of-sequence id, or nullptr
+  int32_t eos_ids[8];
+  int n_eos;
   // With an incremental penalty state (st_rec != nullptr) a row's history is its sequence slot's:
   // the token list in st_tokens and, ready-made, the tables the single-pass kernel otherwise builds
   // in LDS from that list (presence mask, rank directory, counts by rank, at the same offsets).
@@ -86,6 +90,16 @@ struct SampleArgs {
   LdsLayout L;
   FastLayout F;
 };
+
+// The decision outputs of one completed row (called by one thread): log-probability and EOS flag.
+__device__ __forceinline__ void write_decision(const SampleArgs& a, int row, int id, float p, bool greedy) {
+  if (a.logprobs) a.logprobs[row] = id < 0 ? -INFINITY : (greedy ? 0.0f : logf(p));
+  if (a.eos_out) {
+    bool e = false;
+    for (int i = 0; i < a.n_eos; ++i) e = e || (id == a.eos_ids[i]);
+    a.eos_out[row] = (id >= 0 && e) ? 1 : 0;
+  }
+}
 
 // Where a row's token history comes from: the CSR arrays of the call, or its slot of the state.
 struct RowHist { const int32_t* ids; int nnz, n_prompt, slot; uint32_t flags; };

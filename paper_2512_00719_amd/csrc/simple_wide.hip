@@ -1036,6 +1036,7 @@ __global__ __launch_bounds__(WT) void wide_finish_kernel(const SampleArgs a) {
         a.out[W.row] = S.out_id;
         if (a.diag) a.diag[W.row] = dg;
         if (a.stats) stats_add(a.stats, dg.flags, dg.alpha);
+        write_decision(a, W.row, S.out_id, dg.p_chosen, false);
       }
     }
   }

@@ -446,3 +446,72 @@ def test_aggregate_stats_equal_the_sum_over_the_row_records():
     torch.cuda.synchronize()
     assert stats.cpu().numpy().view(binding.STATS_DTYPE)[0] == got
     s.close()
+
+
+def test_decision_outputs_log_probability_and_eos_flag():
+    """simple_set_decision_outputs: ln p~ of the returned id against the oracle (1e-5: the tolerance on
+    p~ itself), 0 for greedy rows, -inf and no flag for an error row; the EOS flag marks exactly the
+    rows whose id is one of the installed ids; rows of every route (list, whole-vocabulary kernels,
+    general kernel)."""
+    import torch
+    from paper_2512_00719_amd import binding
+    w = synth.make_config(3, B=64, V=33_000, nnz=300)
+    w.params["top_k"][3:7] = 0
+    w.params["min_p"][3:7] = 0.0
+    w.params["temperature"][3:7] = 1.3
+    w.params["rep_penalty"][9] = 0.7
+    w.logits[11, 5] = np.nan
+    ids, dg = P.run_gpu(w, 1)
+    want = P.run_oracle(w, 1)
+    eos = sorted({int(ids[0]), int(ids[20]), int(ids[33])})
+    dev = P.to_device(w)
+    s = binding.Sampler(w.V, 300, max_B=w.B)
+    lp = torch.full((w.B,), 7.0, dtype=torch.float32, device="cuda:0")
+    fl = torch.full((w.B,), 9, dtype=torch.uint8, device="cuda:0")
+    assert binding.simple_set_decision_outputs(s.ctx, lp.data_ptr(), fl.data_ptr(), eos) == binding.SIMPLE_OK
+    assert binding.simple_set_decision_outputs(s.ctx, 0, 0, list(range(9))) == binding.SIMPLE_EINVAL
+    out = s.sample(dev["logits"], dev["params"], dev["hist_ptr"], dev["hist_ids"], seed=w.seed, step=1, V=w.V)
+    torch.cuda.synchronize()
+    assert np.array_equal(out.cpu().numpy(), ids)
+    lp, fl = lp.cpu().numpy(), fl.cpu().numpy()
+    routes = set()
+    for b, o in enumerate(want):
+        if o.id < 0:
+            assert ids[b] == -1 and lp[b] == -np.inf and fl[b] == 0
+            continue
+        greedy = w.params["temperature"][b] == 0
+        if int(ids[b]) == o.id:
+            assert any(abs(lp[b] - np.log(p)) <= 1e-5 for p in ((1.0,) if greedy else (o.p_chosen, *o.alt_p))), (b, lp[b], o.p_chosen)
+        assert lp[b] <= 0 and fl[b] == (1 if int(ids[b]) in eos else 0)
+        routes.add(int(dg["flags"][b]) & (binding.DIAG_WIDE | binding.DIAG_GENERAL))
+    assert fl.sum() >= 3 and len(routes) == 3 and (w.params["temperature"] == 0).any()
+    assert binding.simple_set_decision_outputs(s.ctx, 0, 0, []) == binding.SIMPLE_OK
+    s.close()
+
+
+def test_tvd_instrument_shvs_against_the_baseline_sampler():
+    """The paper's exactness experiment (section 7: cumulative mean TVD between the SHVS sampler's and
+    the baseline sampler's token distributions, below 1 %), on one row replicated over the batch:
+    the TVD between the two samplers stays at what sampling noise alone gives, for two hot-set
+    sizes, and so does the TVD of either against the oracle's exact p~."""
+    from paper_2512_00719_amd import tvd
+    rng = np.random.default_rng(21)
+    B, V, steps = 4096, 6000, 30
+    perm = rng.permutation(V)
+    row = np.empty(V, np.float32)
+    row[perm] = (-1.2 * np.log(np.arange(1, V + 1)) + rng.standard_normal(V)).astype(np.float32)
+    par = synth.make_params(B, temperature=1.0, top_p=0.95)
+    d = O.row_distribution(row, par[0])
+    p = d.probs()
+    noise = tvd.expected_tvd_of_sampling(p, B * steps)
+    for H in (64, 1024):
+        hot = perm[:H].astype(np.int32)
+        base = synth.Workload("tvd", B, V, "f32", np.tile(row, (B, 1)), par, np.zeros(B + 1, np.int64), np.zeros(0, np.int32))
+        shvs = synth.Workload("tvd", B, V, "f32", base.logits, par, base.hist_ptr, base.hist_ids, hot_ids=hot, seed=base.seed + 1)
+        acc = tvd.CumulativeTvd(V)
+        for step in range(steps):
+            acc.add(P.run_gpu(shvs, step)[0], P.run_gpu(base, step)[0])
+        two_sample = np.sqrt(2.0) * noise   # both sides are empirical
+        print(f"H={H}: final TVD {acc.history[-1]:.4f}, cumulative mean {acc.mean:.4f}, sampling noise alone {two_sample:.4f}", flush=True)
+        assert acc.history[-1] < 1.25 * two_sample and acc.history[-1] < 0.05
+        assert tvd.tvd(acc.a, p) < 1.25 * noise and tvd.tvd(acc.b, p) < 1.25 * noise
