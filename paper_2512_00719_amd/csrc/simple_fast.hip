@@ -463,7 +463,9 @@ __device__ inline void queue_pending(const SampleArgs& a, int row) {
 // (The second launch bound is HIP's: waves per SIMD, not workgroups per compute unit.  Four waves per
 // SIMD, 128 registers each, are sixteen waves per compute unit at every workgroup size: four
 // workgroups of 256 threads, two of 512, one of 1024.)
-template <typename DT, int NTHR>
+// STATEFUL: the rows' histories come from an incremental penalty state (its own instantiation, so
+// that the stateless kernel carries none of that code).
+template <typename DT, int NTHR, bool STATEFUL>
 __global__ __launch_bounds__(NTHR, 4) void fast_rows_kernel(const SampleArgs a) {
   constexpr int NWV = NTHR / 64;
   constexpr int EPL = Io<DT>::EPL;
@@ -500,9 +502,10 @@ __global__ __launch_bounds__(NTHR, 4) void fast_rows_kernel(const SampleArgs a) 
   R.p_le0 = par.top_p <= 0.0f;
   R.minp_on = par.min_p > 0.0f;
   R.need_sum = !R.greedy && !R.k_on && R.p_on && !R.p_le0;
-  const RowHist rh = row_history(a, row, par.n_prompt);  // the call's CSR arrays, or the row's slot of an incremental state
+  // the call's CSR arrays, or the row's slot of an incremental state
+  const RowHist rh = STATEFUL ? row_history_state(a, row, par.n_prompt) : row_history_csr(a, row, par.n_prompt);
   const int nnz = rh.nnz;
-  const bool stateful = a.st_rec != nullptr;
+  constexpr bool stateful = STATEFUL;
   const bool too_long = nnz > a.max_nnz;
   const bool pen_on = par.rep_penalty != 1.0f || par.freq_penalty != 0.0f || par.pres_penalty != 0.0f;
   const bool lowering = par.rep_penalty >= 1.0f && par.freq_penalty >= 0.0f && par.pres_penalty >= 0.0f;
@@ -955,27 +958,34 @@ __global__ __launch_bounds__(NTHR, 4) void fast_rows_kernel(const SampleArgs a) 
 }  // namespace simple
 namespace simple {
 
-hipError_t launch_fast(const SampleArgs& a, int dtype, hipStream_t st) {
+template <bool STATEFUL>
+static hipError_t launch_fast_instance(const SampleArgs& a, int dtype, hipStream_t st) {
   const dim3 grid((unsigned)a.B);
   if (a.F.threads == 256) {
-    if (dtype == SIMPLE_F32) hipLaunchKernelGGL((fast::fast_rows_kernel<float, 256>), grid, dim3(256), a.F.total, st, a);
-    else hipLaunchKernelGGL((fast::fast_rows_kernel<uint16_t, 256>), grid, dim3(256), a.F.total, st, a);
+    if (dtype == SIMPLE_F32) hipLaunchKernelGGL((fast::fast_rows_kernel<float, 256, STATEFUL>), grid, dim3(256), a.F.total, st, a);
+    else hipLaunchKernelGGL((fast::fast_rows_kernel<uint16_t, 256, STATEFUL>), grid, dim3(256), a.F.total, st, a);
   } else if (a.F.threads == 512) {
-    if (dtype == SIMPLE_F32) hipLaunchKernelGGL((fast::fast_rows_kernel<float, 512>), grid, dim3(512), a.F.total, st, a);
-    else hipLaunchKernelGGL((fast::fast_rows_kernel<uint16_t, 512>), grid, dim3(512), a.F.total, st, a);
+    if (dtype == SIMPLE_F32) hipLaunchKernelGGL((fast::fast_rows_kernel<float, 512, STATEFUL>), grid, dim3(512), a.F.total, st, a);
+    else hipLaunchKernelGGL((fast::fast_rows_kernel<uint16_t, 512, STATEFUL>), grid, dim3(512), a.F.total, st, a);
   } else {
-    if (dtype == SIMPLE_F32) hipLaunchKernelGGL((fast::fast_rows_kernel<float, 1024>), grid, dim3(1024), a.F.total, st, a);
-    else hipLaunchKernelGGL((fast::fast_rows_kernel<uint16_t, 1024>), grid, dim3(1024), a.F.total, st, a);
+    if (dtype == SIMPLE_F32) hipLaunchKernelGGL((fast::fast_rows_kernel<float, 1024, STATEFUL>), grid, dim3(1024), a.F.total, st, a);
+    else hipLaunchKernelGGL((fast::fast_rows_kernel<uint16_t, 1024, STATEFUL>), grid, dim3(1024), a.F.total, st, a);
   }
   return hipGetLastError();
 }
+hipError_t launch_fast(const SampleArgs& a, int dtype, hipStream_t st) {
+  return a.st_rec ? launch_fast_instance<true>(a, dtype, st) : launch_fast_instance<false>(a, dtype, st);
+}
 
 hipError_t set_max_lds_fast(unsigned bytes) {
-  const void* fns[6] = {
-    reinterpret_cast<const void*>(fast::fast_rows_kernel<float, 256>), reinterpret_cast<const void*>(fast::fast_rows_kernel<uint16_t, 256>),
-    reinterpret_cast<const void*>(fast::fast_rows_kernel<float, 512>), reinterpret_cast<const void*>(fast::fast_rows_kernel<uint16_t, 512>),
-    reinterpret_cast<const void*>(fast::fast_rows_kernel<float, 1024>), reinterpret_cast<const void*>(fast::fast_rows_kernel<uint16_t, 1024>)};
-  for (int i = 0; i < 6; ++i) {
+  const void* fns[12] = {
+    reinterpret_cast<const void*>(fast::fast_rows_kernel<float, 256, false>), reinterpret_cast<const void*>(fast::fast_rows_kernel<uint16_t, 256, false>),
+    reinterpret_cast<const void*>(fast::fast_rows_kernel<float, 512, false>), reinterpret_cast<const void*>(fast::fast_rows_kernel<uint16_t, 512, false>),
+    reinterpret_cast<const void*>(fast::fast_rows_kernel<float, 1024, false>), reinterpret_cast<const void*>(fast::fast_rows_kernel<uint16_t, 1024, false>),
+    reinterpret_cast<const void*>(fast::fast_rows_kernel<float, 256, true>), reinterpret_cast<const void*>(fast::fast_rows_kernel<uint16_t, 256, true>),
+    reinterpret_cast<const void*>(fast::fast_rows_kernel<float, 512, true>), reinterpret_cast<const void*>(fast::fast_rows_kernel<uint16_t, 512, true>),
+    reinterpret_cast<const void*>(fast::fast_rows_kernel<float, 1024, true>), reinterpret_cast<const void*>(fast::fast_rows_kernel<uint16_t, 1024, true>)};
+  for (int i = 0; i < 12; ++i) {
     const hipError_t e = hipFuncSetAttribute(fns[i], hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
     if (e != hipSuccess) return e;
   }

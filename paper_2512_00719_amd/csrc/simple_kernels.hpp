@@ -103,19 +103,10 @@ __device__ __forceinline__ void write_decision(const SampleArgs& a, int row, int
 
 // Where a row's token history comes from: the CSR arrays of the call, or its slot of the state.
 struct RowHist { const int32_t* ids; int nnz, n_prompt, slot; uint32_t flags; };
-__device__ __forceinline__ RowHist row_history(const SampleArgs& a, int row, int par_n_prompt) {
+__device__ __forceinline__ RowHist row_history_csr(const SampleArgs& a, int row, int par_n_prompt) {
   RowHist h;
   h.ids = nullptr; h.nnz = 0; h.n_prompt = par_n_prompt; h.slot = -1; h.flags = 0u;
-  if (a.st_rec) {
-    const int slot = a.st_slots ? a.st_slots[row] : a.st_slot0 + row;
-    if ((unsigned)slot >= (unsigned)a.st_nslots) { h.nnz = a.max_nnz + 1; return h; }  // reported as a history that is too long
-    const StateRec rec = a.st_rec[slot];
-    h.slot = slot;
-    h.ids = a.st_tokens + (size_t)slot * (size_t)a.st_lmax;
-    h.nnz = (rec.len > a.st_lmax || rec.len > a.max_nnz) ? a.max_nnz + 1 : max(rec.len, 0);
-    h.n_prompt = rec.n_prompt;
-    h.flags = rec.flags;
-  } else if (a.hist_ptr) {
+  if (a.hist_ptr) {
     const long long h0 = a.hist_ptr[row], h1 = a.hist_ptr[row + 1];
     long long n = h1 - h0;
     if (n < 0) n = 0;
@@ -124,6 +115,22 @@ __device__ __forceinline__ RowHist row_history(const SampleArgs& a, int row, int
     h.ids = a.hist_ids + h0;
   }
   return h;
+}
+__device__ __forceinline__ RowHist row_history_state(const SampleArgs& a, int row, int par_n_prompt) {
+  RowHist h;
+  h.ids = nullptr; h.nnz = 0; h.n_prompt = par_n_prompt; h.slot = -1; h.flags = 0u;
+  const int slot = a.st_slots ? a.st_slots[row] : a.st_slot0 + row;
+  if ((unsigned)slot >= (unsigned)a.st_nslots) { h.nnz = a.max_nnz + 1; return h; }  // reported as a history that is too long
+  const StateRec rec = a.st_rec[slot];
+  h.slot = slot;
+  h.ids = a.st_tokens + (size_t)slot * (size_t)a.st_lmax;
+  h.nnz = (rec.len > a.st_lmax || rec.len > a.max_nnz) ? a.max_nnz + 1 : max(rec.len, 0);
+  h.n_prompt = rec.n_prompt;
+  h.flags = rec.flags;
+  return h;
+}
+__device__ __forceinline__ RowHist row_history(const SampleArgs& a, int row, int par_n_prompt) {
+  return a.st_rec ? row_history_state(a, row, par_n_prompt) : row_history_csr(a, row, par_n_prompt);
 }
 
 LdsLayout make_layout(int64_t V, int64_t max_nnz, bool with_history);
