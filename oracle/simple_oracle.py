@@ -185,6 +185,36 @@ def apply_penalties(z: np.ndarray, c_o: np.ndarray, mask: np.ndarray, rep: float
     return np.where(c_o > 0, zf, zr).astype(np.float32)
 
 
+def apply_constraints(z_row: np.ndarray, bias_ids=None, bias_vals=None, allow_ids=None) -> np.ndarray:
+    """Logit bias and allow-list of one row, before the penalties (section 5.2 lists allow-lists among
+    the constraints that compose on the survivor set, section 6 of the paper "optional biases").
+
+    Convention (the paper gives none): an allow-list, if the row has one, masks every other column
+    to -inf; a bias entry adds ``fl32(z + bias)`` to its column (entries naming the same column
+    add up in list order); a bias on a column the allow-list masks leaves it masked.  Both are
+    independent of the order of the survivors (a column's value changes, the filters of Eq. (2)
+    then see the changed row), and both come before ``ApplyPenalty``, as a logits processor that
+    runs ahead of the sampler would.  Returns float32.
+    """
+    z = np.array(z_row, dtype=np.float32, copy=True)
+    V = z.size
+    if allow_ids is not None:
+        allow_ids = np.asarray(allow_ids, dtype=np.int64)
+        if allow_ids.size and (allow_ids.min() < 0 or allow_ids.max() >= V):
+            raise ValueError("allowed id outside [0, V)")
+        keep = np.zeros(V, dtype=bool)
+        keep[allow_ids] = True
+        z[~keep] = -np.inf
+    if bias_ids is not None:
+        bias_ids = np.asarray(bias_ids, dtype=np.int64)
+        bias_vals = np.asarray(bias_vals, dtype=np.float32)
+        if bias_ids.size and (bias_ids.min() < 0 or bias_ids.max() >= V):
+            raise ValueError("biased id outside [0, V)")
+        for i, v in zip(bias_ids, bias_vals):
+            z[i] = np.float32(z[i] + v)
+    return z
+
+
 # ----------------------------------------------------------------------------------------------
 # Step 2: temperature, filter, stable softmax (Eq. (2); truncation-first filtering, section 5.2)
 # ----------------------------------------------------------------------------------------------

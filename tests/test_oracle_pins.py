@@ -661,3 +661,25 @@ def test_incremental_history_equals_the_rebuild_at_every_step():
     a = O.sample_with_state(z, par, st, None, 5, 2)[0]
     b = O.sample(z, par, np.array([0, 6]), np.array([3, 3, 9, 9, 4, 9], np.int32), None, 5, 2)[0]
     assert (a.id, a.n, a.p_chosen) == (b.id, b.n, b.p_chosen)
+
+
+def test_constraints_hand_computed_and_their_effect_on_the_draw():
+    """apply_constraints: a hand-computed row (allow-list masks the rest, biases add in float32 and
+    accumulate, a bias on a masked column leaves it masked); an allowed-only support of every draw;
+    a large bias makes top-k = 1 pick the biased token; an empty allow-list is an error row."""
+    z = np.array([1.5, -2.0, 0.25, 3.0, -0.5], np.float32)
+    out = O.apply_constraints(z, [2, 0, 2, 3], [0.5, -1.0, 0.25, 2.0], [0, 2, 4])
+    assert out.tolist() == [0.5, -np.inf, 1.0, -np.inf, -0.5] and out.dtype == np.float32
+    assert O.apply_constraints(z).tolist() == z.tolist()
+    assert O.apply_constraints(z, [1], [np.float32(0.1)])[1] == np.float32(np.float32(-2.0) + np.float32(0.1))
+    rng = np.random.default_rng(31)
+    zz = (rng.standard_normal(200) * 2).astype(np.float32)
+    allow = rng.choice(200, 17, replace=False)
+    d = O.row_distribution(O.apply_constraints(zz, allow_ids=allow), _par(temperature=1.3))
+    assert set(d.ids[d.w > 0].tolist()) == set(allow.tolist())   # masked columns keep weight zero
+    ids, _, _ = O.draw(d, np.linspace(0, 1, 4001)[:-1])
+    assert set(ids.tolist()) <= set(allow.tolist())
+    j = int(np.argmin(zz))
+    d = O.row_distribution(O.apply_constraints(zz, [j], [100.0]), _par(top_k=1))
+    assert d.ids.tolist() == [j]
+    assert O.row_distribution(O.apply_constraints(zz, allow_ids=[]), _par()).error
