@@ -202,6 +202,29 @@ int simple_sample(simple_ctx* ctx, const void* logits_dev, int64_t B, int64_t V,
                   void* hip_stream);
 
 /*
+ * Logit bias and allow-lists (section 5.2 names allow-lists among the constraints that compose on the
+ * survivor set; the implementation section mentions optional biases), as a pass ahead of the
+ * sampling call: out[b, v] = fl32(z[b, v] + bias(b, v)) for the columns row b allows, -inf for the
+ * others, written as float32 to out_dev ([B, out_stride_elems], device, owned by the caller), which
+ * the caller then hands to simple_sample with dtype SIMPLE_F32.  Constraints come before the
+ * penalties and are independent of the order of the survivors.
+ *   bias_ptr_dev / bias_ids_dev / bias_vals_dev   CSR over rows ([B + 1] offsets, ids, float32
+ *       values), or all NULL.  Entries of a row that name the same column add up in list order.
+ *   allow_ptr_dev / allow_ids_dev                 CSR over rows, or both NULL.  A row with entries keeps
+ *       only the listed columns (a bias on a column it masks leaves it masked); a row with none
+ *       has no allow-list.
+ * Ids outside [0, V) are ignored.  out_dev may be logits_dev itself when dtype is SIMPLE_F32 and the
+ * strides are equal.  A call without constraints never needs this pass; one with them pays one more
+ * read and one write of its logits.  No context, nothing allocated; enqueued on hip_stream.
+ * SIMPLE_EINVAL for NULL / negative / inconsistent arguments (offsets without their arrays, strides
+ * below V, unknown dtype), SIMPLE_ECAPACITY if an allow-list's V-bit mask exceeds 96 KB of LDS.
+ */
+int simple_apply_logit_constraints(const void* logits_dev, int64_t B, int64_t V, int dtype, int64_t row_stride_elems,
+                                   const int64_t* bias_ptr_dev, const int32_t* bias_ids_dev, const float* bias_vals_dev,
+                                   const int64_t* allow_ptr_dev, const int32_t* allow_ids_dev,
+                                   float* out_dev, int64_t out_stride_elems, void* hip_stream);
+
+/*
  * Incremental penalty state (paper section 5.2: row-append token buffer; the histograms are carried
  * from step to step, C_o^{s+1} = C_o^s + Hist(Y_s), M_o = (C_o > 0), C_p and M_p fixed per sequence,
  * instead of being rebuilt from the token list on every call).

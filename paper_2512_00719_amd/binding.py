@@ -36,6 +36,7 @@ assert STATS_DTYPE.itemsize == 64
 
 EXPORTS = ("simple_create", "simple_destroy", "simple_set_hot_set", "simple_set_stats", "simple_set_decision_outputs", "simple_sample",
            "simple_sample_static", "simple_static_limit",
+           "simple_apply_logit_constraints",
            "simple_state_create", "simple_state_destroy", "simple_state_restart", "simple_state_append", "simple_sample_state",
            "simple_profile_enable", "simple_profile_read", "simple_profile_read_launches",
            "simple_stream_probe",
@@ -64,6 +65,8 @@ def _load() -> ctypes.CDLL:
     lib.simple_sample_static.restype = ctypes.c_int
     lib.simple_static_limit.argtypes = [ctypes.c_int]
     lib.simple_static_limit.restype = i64
+    lib.simple_apply_logit_constraints.argtypes = [vp, i64, i64, ctypes.c_int, i64, vp, vp, vp, vp, vp, vp, i64, vp]
+    lib.simple_apply_logit_constraints.restype = ctypes.c_int
     lib.simple_state_create.argtypes = [ctypes.POINTER(vp), ctypes.c_int, i64, i64, i64]
     lib.simple_state_create.restype = ctypes.c_int
     lib.simple_state_destroy.argtypes = [vp]
@@ -199,6 +202,16 @@ def simple_sample_static(logits_ptr: int, B: int, V: int, dtype: int, row_stride
 
 def simple_static_limit(what: int) -> int:
     return int(_lib.simple_static_limit(int(what)))
+
+
+def simple_apply_logit_constraints(logits_ptr: int, B: int, V: int, dtype: int, row_stride: int, bias_ptr_ptr: int, bias_ids_ptr: int,
+                                   bias_vals_ptr: int, allow_ptr_ptr: int, allow_ids_ptr: int, out_ptr: int, out_stride: int,
+                                   stream: int = 0) -> int:
+    """Raw call: logit bias and allow-lists written out as a float32 matrix.  Returns the C status code."""
+    vp = ctypes.c_void_p
+    return int(_lib.simple_apply_logit_constraints(vp(logits_ptr), int(B), int(V), int(dtype), int(row_stride), vp(bias_ptr_ptr),
+                                                   vp(bias_ids_ptr), vp(bias_vals_ptr), vp(allow_ptr_ptr), vp(allow_ids_ptr),
+                                                   vp(out_ptr), int(out_stride), vp(stream)))
 
 
 def simple_state_create(device: int, max_seqs: int, V: int, L_max: int) -> int:

@@ -43,6 +43,12 @@ def test_null_context_and_bad_arguments_are_rejected_on_the_host():
     assert binding.simple_sample(0, 0, 1, 8, 0, 8, 0, 0, 0, 0, 0, 1, 0, 0, 0, 0) == binding.SIMPLE_EINVAL
     assert binding.simple_set_hot_set(0, 0, 4, 8) == binding.SIMPLE_EINVAL
     assert binding.simple_set_stats(0, 0) == binding.SIMPLE_EINVAL
+    # logit constraints: sizes and pointer pairs are checked before anything is enqueued
+    assert binding.simple_apply_logit_constraints(0, 1, 0, 0, 8, 0, 0, 0, 0, 0, 0, 8) == binding.SIMPLE_EINVAL
+    assert binding.simple_apply_logit_constraints(0, 1, 8, 0, 8, 1, 0, 0, 0, 0, 0, 8) == binding.SIMPLE_EINVAL   # offsets without ids
+    assert binding.simple_apply_logit_constraints(0, 1, 8, 0, 8, 0, 0, 0, 0, 0, 0, 4) == binding.SIMPLE_EINVAL   # output stride below V
+    assert binding.simple_apply_logit_constraints(0, 0, 8, 0, 8, 0, 0, 0, 0, 0, 0, 8) == binding.SIMPLE_OK       # empty batch
+    assert binding.simple_apply_logit_constraints(0, 1, 1 << 22, 0, 1 << 22, 0, 0, 0, 1, 1, 0, 1 << 22) == binding.SIMPLE_EINVAL  # NULL logits
     # incremental penalty state: NULL handles and sizes are rejected on the host
     assert binding.simple_state_restart(0, 0, 1, 0, 0, 0) == binding.SIMPLE_EINVAL
     assert binding.simple_state_append(0, 0, 0, 1) == binding.SIMPLE_EINVAL
