@@ -147,11 +147,21 @@ def main() -> int:
 
     result = run_config(args, args.config, args.H, args.steps, args.warmup, not args.no_cpu_baseline)
     if args.all_configs:
+        sweep = []
         for cfg, H in ((2, None), (4, 4096), (4, 8192), (4, 16384), (4, 32768), (5, None)):
             if cfg == args.config and H == args.H:
                 continue
             r = run_config(args, cfg, H, min(args.steps, 50), min(args.warmup, 10), False)
             print(json.dumps(r), file=sys.stderr, flush=True)
+            if cfg == 4:
+                sweep.append((H, r["ms_per_step"] * 1e-3 / 512, r["config"]["shvs_mean_alpha"]))
+        if len(sweep) >= 2:
+            # the paper's sizing model (section 5.4) on the measured sweep: cost per row against H, hit ratio, F(H);
+            # reference constants: the affine CPU fit the paper reports for its own samplers
+            from paper_2512_00719_amd import sizing
+            print(json.dumps({"sizing_C4": sizing.summarize_sweep([h for h, _, _ in sweep], [t for _, t, _ in sweep],
+                                                                  [a for _, _, a in sweep], 201_088, reference=(1.06e-8, 8.55e-6))}),
+                  file=sys.stderr, flush=True)
     print(json.dumps(result), flush=True)
     return 0
 
