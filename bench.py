@@ -135,6 +135,9 @@ def main() -> int:
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--stateful", action="store_true",
                     help="take the rows' histories from an incremental penalty state (simple_sample_state) instead of the CSR arrays")
+    ap.add_argument("--hot-first-sweep", action="store_true",
+                    help="instead of the headline run: SHVS on a hot-first vocabulary with caller-supplied tail statistics "
+                         "(simple_sample_hot_first), swept over the hot-set size, with the paper's sizing model on the result")
     ap.add_argument("--all-configs", action="store_true", help="also run C2, C4 (H sweep) and C5 briefly; their lines go to stderr")
     ap.add_argument("--copy-probe-mib", type=int, default=0,
                     help="after the timed region, run one plain device copy of this many MiB (a kernel of known "
@@ -145,6 +148,8 @@ def main() -> int:
               "(rows are independent: N GPUs would each take B / N rows and call it unchanged)", file=sys.stderr)
         return 2
 
+    if args.hot_first_sweep:
+        return hot_first_sweep(args)
     result = run_config(args, args.config, args.H, args.steps, args.warmup, not args.no_cpu_baseline)
     if args.all_configs:
         sweep = []
@@ -163,6 +168,79 @@ def main() -> int:
                                                                   [a for _, _, a in sweep], 201_088, reference=(1.06e-8, 8.55e-6))}),
                   file=sys.stderr, flush=True)
     print(json.dumps(result), flush=True)
+    return 0
+
+
+def hot_first_sweep(args) -> int:
+    """The GPU analogue of the paper's sizing experiment (section 7, sizing model validation): rows that
+    sample with temperature alone on a hot-first vocabulary of C4's shape, a batch large enough that
+    the time per call reflects the average cost of a row (accepted rows read H columns, rejected ones
+    their tail as well).  Per H: the measured cost per row, the hot path's own cost (every draw forced
+    to accept by statistics that declare an empty tail), acceptance and mean alpha; then the affine fit
+    T(H) = c H + c0 of the hot path, F(H) of Eq. (cpu-time) and its minimiser against the measured one."""
+    import torch
+    from paper_2512_00719_amd import binding, sizing, synth
+    B, V = 4096, 201_088
+    rng = np.random.default_rng(synth.DATA_SEED_BASE + 6)
+    logits_np = synth.zipf_profile_logits(B, V, 1.2, 1.0, rng, "bf16", np.arange(V, dtype=np.int64))
+    dev = "cuda:0"
+    lg = torch.from_numpy(logits_np.view(np.int16)).to(dev).view(torch.bfloat16)
+    par = synth.make_params(B, temperature=1.0)
+    params = torch.from_numpy(par.view(np.uint8).reshape(B, 32)).to(dev)
+    out = torch.empty(B, dtype=torch.int32, device=dev)
+    s = binding.Sampler(V, 0, max_B=B)
+    stats_dev = torch.zeros(64, dtype=torch.uint8, device=dev)
+    stream = torch.cuda.current_stream().cuda_stream
+    rows = []
+    for H in (2048, 4096, 8192, 16384, 32768, 65536):
+        # what the producer of the logits would supply (temperature 1): maximum and exponential sum of each row's tail
+        tail = lg[:, H:].float()
+        tmax = tail.max(dim=1).values
+        tsum = torch.exp((tail - tmax[:, None]).double()).sum(dim=1)
+        ts = np.zeros(B, binding.TAIL_STATS_DTYPE)
+        ts["tail_max"] = tmax.cpu().numpy(); ts["tail_sum"] = tsum.cpu().numpy()
+        del tail
+        real = torch.from_numpy(ts.view(np.uint8).reshape(B, 16)).to(dev)
+        ts_none = ts.copy(); ts_none["tail_sum"] = 0.0    # an empty tail: every draw is accepted (timing of the hot path alone)
+        forced = torch.from_numpy(ts_none.view(np.uint8).reshape(B, 16)).to(dev)
+
+        def run(tsd, n):
+            for i in range(n):
+                rc = binding.simple_sample_hot_first(s.ctx, lg.data_ptr(), B, V, binding.SIMPLE_BF16, lg.stride(0), params.data_ptr(), H,
+                                                     tsd.data_ptr(), synth.SAMPLER_SEED, i, 0, out.data_ptr(), 0, stream)
+                assert rc == 0, rc
+        times = {}
+        for name, tsd in (("measured", real), ("hot_path", forced)):
+            run(tsd, 5)
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            run(tsd, args.steps if args.steps < 200 else 50)
+            torch.cuda.synchronize()
+            times[name] = (time.perf_counter() - t0) / (args.steps if args.steps < 200 else 50)
+        stats_dev.zero_()
+        assert binding.simple_set_stats(s.ctx, stats_dev.data_ptr()) == 0
+        run(real, 1)
+        torch.cuda.synchronize()
+        assert binding.simple_set_stats(s.ctx, 0) == 0
+        agg = stats_dev.cpu().numpy().view(binding.STATS_DTYPE)[0]
+        n = int(agg["shvs_accepted"] + agg["shvs_rejected"])
+        row = {"H": H, "ms_per_call": times["measured"] * 1e3, "ms_per_call_hot_path_only": times["hot_path"] * 1e3,
+               "rows_per_s": B / times["measured"], "acceptance_rate": float(agg["shvs_accepted"]) / n,
+               "mean_alpha": float(agg["sum_alpha_q32"]) / 2.0 ** 32 / n,
+               "bytes_read_per_row_model": (float(agg["shvs_accepted"]) * H + float(agg["shvs_rejected"]) * V) * 2 / n}
+        rows.append(row)
+        print(json.dumps({"hot_first": row}), file=sys.stderr, flush=True)
+    Hs = [r["H"] for r in rows]
+    c, c0 = sizing.fit_affine_cost(Hs, [r["ms_per_call_hot_path_only"] * 1e-3 / B for r in rows])
+    alpha = [r["mean_alpha"] for r in rows]
+    F = sizing.expected_cost(Hs, alpha, c, c0, V)
+    measured = [r["ms_per_call"] * 1e-3 / B for r in rows]
+    summary = {"workload": f"hot-first sweep: B={B} V={V} bf16, Zipf(1.2) profile + N(0,1) noise in rank order, temperature 1, no truncation",
+               "hot_path_fit": {"c_seconds_per_column": c, "c0_seconds": c0},
+               "F_model_seconds_per_row": [float(x) for x in F], "measured_seconds_per_row": measured,
+               "best_H_model": Hs[int(np.argmin(F))], "best_H_measured": Hs[int(np.argmin(measured))], "sweep": rows}
+    print(json.dumps(summary), flush=True)
+    s.close()
     return 0
 
 

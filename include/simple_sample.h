@@ -202,6 +202,36 @@ int simple_sample(simple_ctx* ctx, const void* logits_dev, int64_t B, int64_t V,
                   void* hip_stream);
 
 /*
+ * Speculative hot-vocab sampling that reads only the hot columns when the hot draw is accepted
+ * (section 5.3; the cost model of section 5.4: H columns on acceptance, the other V - H on
+ * rejection).  The vocabulary must be laid out hot-first: the hot set is the columns [0, H) (an
+ * LM head whose rows are permuted offline).  alpha_b needs the mass of the tail, so each row
+ * comes with two numbers from the kernel that wrote the logits (section 5.3: the weights "can be
+ * pre-computed on GPUs when writing logits"):
+ *   tail_max   max over v >= H of logits[b, v]                          (-inf if H == V)
+ *   tail_sum   sum over v >= H of exp((logits[b, v] - tail_max) / temperature_b)   (0 if H == V)
+ * Rows served from the hot columns: temperature > 0, no top-k / top-p / min-p, no penalties (their
+ * survivor set is all of V, so Eq. (7) needs nothing of the tail but its mass); a rejected row
+ * streams its tail for the tail proposal.  Every other row (truncated, greedy, invalid) is served
+ * by the general kernel with [0, H) as the hot set, so all rows get the ids of SHVS as defined for
+ * simple_sample with hot_ids = 0 .. H-1 (same uniforms, same walk order).  No history arguments:
+ * penalised rows belong to simple_sample.  H must be a positive multiple of 1024 (float32) or
+ * 2048 (bfloat16) columns, at most V; rows and logits_dev 16-byte aligned; V - H and H at most
+ * 2^20 (float32) or 2^21 (bfloat16).  Otherwise as simple_sample (stream semantics, errors, diag,
+ * statistics and decision outputs).  A NaN or +inf tail_max, or a negative / NaN tail_sum, is a
+ * data error of the row (id -1).
+ */
+typedef struct {
+  double tail_sum;
+  float tail_max;
+  float reserved;
+} simple_tail_stats;
+int simple_sample_hot_first(simple_ctx* ctx, const void* logits_dev, int64_t B, int64_t V, int dtype, int64_t row_stride_elems,
+                            const simple_row_params* params_dev, int32_t H, const simple_tail_stats* tail_stats_dev,
+                            uint64_t seed, uint64_t step, uint64_t row_offset, int32_t* out_ids_dev,
+                            simple_row_diag* diag_dev, void* hip_stream);
+
+/*
  * Logit bias and allow-lists (section 5.2 names allow-lists among the constraints that compose on the
  * survivor set; the implementation section mentions optional biases), as a pass ahead of the
  * sampling call: out[b, v] = fl32(z[b, v] + bias(b, v)) for the columns row b allows, -inf for the

@@ -36,7 +36,7 @@ assert STATS_DTYPE.itemsize == 64
 
 EXPORTS = ("simple_create", "simple_destroy", "simple_set_hot_set", "simple_set_stats", "simple_set_decision_outputs", "simple_sample",
            "simple_sample_static", "simple_static_limit",
-           "simple_apply_logit_constraints",
+           "simple_apply_logit_constraints", "simple_sample_hot_first",
            "simple_state_create", "simple_state_destroy", "simple_state_restart", "simple_state_append", "simple_sample_state",
            "simple_profile_enable", "simple_profile_read", "simple_profile_read_launches",
            "simple_stream_probe",
@@ -65,6 +65,8 @@ def _load() -> ctypes.CDLL:
     lib.simple_sample_static.restype = ctypes.c_int
     lib.simple_static_limit.argtypes = [ctypes.c_int]
     lib.simple_static_limit.restype = i64
+    lib.simple_sample_hot_first.argtypes = [vp, vp, i64, i64, ctypes.c_int, i64, vp, i32, vp, u64, u64, u64, vp, vp, vp]
+    lib.simple_sample_hot_first.restype = ctypes.c_int
     lib.simple_apply_logit_constraints.argtypes = [vp, i64, i64, ctypes.c_int, i64, vp, vp, vp, vp, vp, vp, i64, vp]
     lib.simple_apply_logit_constraints.restype = ctypes.c_int
     lib.simple_state_create.argtypes = [ctypes.POINTER(vp), ctypes.c_int, i64, i64, i64]
@@ -202,6 +204,21 @@ def simple_sample_static(logits_ptr: int, B: int, V: int, dtype: int, row_stride
 
 def simple_static_limit(what: int) -> int:
     return int(_lib.simple_static_limit(int(what)))
+
+
+TAIL_STATS_DTYPE = np.dtype([("tail_sum", "<f8"), ("tail_max", "<f4"), ("reserved", "<f4")])
+assert TAIL_STATS_DTYPE.itemsize == 16
+
+
+def simple_sample_hot_first(ctx: int, logits_ptr: int, B: int, V: int, dtype: int, row_stride: int, params_ptr: int, H: int,
+                            tail_stats_ptr: int, seed: int, step: int, row_offset: int, out_ids_ptr: int, diag_ptr: int,
+                            stream: int = 0) -> int:
+    """Raw call: SHVS on a hot-first vocabulary with per-row tail statistics.  Returns the C status code."""
+    vp = ctypes.c_void_p
+    return int(_lib.simple_sample_hot_first(vp(ctx), vp(logits_ptr), int(B), int(V), int(dtype), int(row_stride), vp(params_ptr), int(H),
+                                            vp(tail_stats_ptr), ctypes.c_uint64(seed & (2 ** 64 - 1)),
+                                            ctypes.c_uint64(step & (2 ** 64 - 1)), ctypes.c_uint64(row_offset & (2 ** 64 - 1)),
+                                            vp(out_ids_ptr), vp(diag_ptr), vp(stream)))
 
 
 def simple_apply_logit_constraints(logits_ptr: int, B: int, V: int, dtype: int, row_stride: int, bias_ptr_ptr: int, bias_ids_ptr: int,

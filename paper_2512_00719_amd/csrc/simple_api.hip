@@ -17,6 +17,7 @@ struct simple_ctx {
   uint32_t* hot_flags;  // device, one word
   int64_t hot_V;        // V the installed hot set was built for, 0 if none
   int32_t hot_H;
+  bool hot_is_range;    // the installed hot set is the column range [0, hot_H) (built for the hot-first call)
   int lds_limit;
   int n_cu;
   uint32_t* pend;       // device: queue of rows the single-pass kernel leaves to the general kernel
@@ -177,7 +178,7 @@ int simple_create(simple_ctx** out, int device, int64_t max_B, int64_t max_V, in
   simple_ctx* c = new (std::nothrow) simple_ctx();
   if (!c) return SIMPLE_ENOMEM;
   c->device = device; c->max_V = max_V; c->max_nnz = max_nnz_per_row; c->lds_limit = lds; c->n_cu = n_cu;
-  c->hot_V = 0; c->hot_H = 0; c->hot_bits = nullptr; c->hot_flags = nullptr; c->pend = nullptr; c->wq = nullptr; c->wws = nullptr; c->ws_stride = 0; c->parity = 0;
+  c->hot_V = 0; c->hot_H = 0; c->hot_is_range = false; c->hot_bits = nullptr; c->hot_flags = nullptr; c->pend = nullptr; c->wq = nullptr; c->wws = nullptr; c->ws_stride = 0; c->parity = 0;
   c->prof_ev = nullptr; c->prof_n = 0; c->base = nullptr; c->slots = 0; c->stats = nullptr;
   c->logprobs = nullptr; c->eos_out = nullptr; c->n_eos = 0;
   c->slots = (int)(max_B < (int64_t)simple::WIDE_SLOTS ? max_B : (int64_t)simple::WIDE_SLOTS);
@@ -283,14 +284,15 @@ int simple_set_hot_set(simple_ctx* ctx, const int32_t* hot_ids_dev, int32_t H, i
   if (simple::launch_hot_build(hot_ids_dev, H, (int)V, ctx->hot_bits, ctx->hot_flags,
                                static_cast<hipStream_t>(hip_stream)) != hipSuccess)
     return SIMPLE_EDEVICE;
-  ctx->hot_V = V; ctx->hot_H = H;
+  ctx->hot_V = V; ctx->hot_H = H; ctx->hot_is_range = false;
   return SIMPLE_OK;
 }
 
 }  // extern "C"
 
 // The sampling call; the rows' histories come from the CSR arrays or, with `state`, from its slots.
-static int sample_impl(simple_ctx* ctx, const simple_state* state, const int32_t* slots_dev, const void* logits_dev, int64_t B, int64_t V,
+static int sample_impl(simple_ctx* ctx, const simple_state* state, const int32_t* slots_dev, const simple_tail_stats* tail,
+                       const void* logits_dev, int64_t B, int64_t V,
                        int dtype, int64_t row_stride_elems, const simple_row_params* params_dev,
                        const int64_t* hist_ptr_dev, const int32_t* hist_ids_dev,
                        const int32_t* hot_ids_dev, int32_t H, uint64_t seed, uint64_t step,
@@ -303,7 +305,7 @@ static int sample_impl(simple_ctx* ctx, const simple_state* state, const int32_t
   if (row_stride_elems < V) return SIMPLE_EINVAL;
   if (H < -1 || (int64_t)H > V) return SIMPLE_EINVAL;
   if (hot_ids_dev && H <= 0) return SIMPLE_EINVAL;
-  if (!hot_ids_dev && H > 0) return SIMPLE_EINVAL;
+  if (!hot_ids_dev && H > 0 && !tail) return SIMPLE_EINVAL;
   if (H == -1 && ctx->hot_V != V) return SIMPLE_EINVAL;
   if (hist_ptr_dev && !hist_ids_dev) return SIMPLE_EINVAL;
   if (B == 0) return SIMPLE_OK;
@@ -315,10 +317,21 @@ static int sample_impl(simple_ctx* ctx, const simple_state* state, const int32_t
   if (!guard.ok) return SIMPLE_EDEVICE;
   hipStream_t st = static_cast<hipStream_t>(hip_stream);
   const bool use_hot = (H != 0);
+  const size_t esz0 = (dtype == SIMPLE_F32) ? 4 : 2;
+  if (tail) {  // the hot-first call: the hot set is the column range [0, H)
+    const int tile = simple::hot_first_tile(dtype);
+    const bool aligned = ((reinterpret_cast<uintptr_t>(logits_dev) & 15u) == 0) && (((size_t)row_stride_elems * esz0) % 16 == 0);
+    if (H <= 0 || H % tile != 0 || !aligned || hot_ids_dev || state || hist_ptr_dev) return SIMPLE_EINVAL;
+    if ((int64_t)H / tile > simple::hot_first_max_tiles() || (V - H + tile - 1) / tile > simple::hot_first_max_tiles()) return SIMPLE_ECAPACITY;
+    if (ctx->hot_V != V || ctx->hot_H != H || !ctx->hot_is_range) {
+      if (simple::launch_hot_range(ctx->hot_bits, ctx->hot_flags, (int)V, (int)H, st) != hipSuccess) return SIMPLE_EDEVICE;
+      ctx->hot_V = V; ctx->hot_H = H; ctx->hot_is_range = true;
+    }
+  }
   if (hot_ids_dev) {
     if (simple::launch_hot_build(hot_ids_dev, H, (int)V, ctx->hot_bits, ctx->hot_flags, st) != hipSuccess)
       return SIMPLE_EDEVICE;
-    ctx->hot_V = V; ctx->hot_H = H;
+    ctx->hot_V = V; ctx->hot_H = H; ctx->hot_is_range = false;
   }
   const size_t esz = (dtype == SIMPLE_F32) ? 4 : 2;
   const bool vec = ((reinterpret_cast<uintptr_t>(logits_dev) & 15u) == 0) && (((size_t)row_stride_elems * esz) % 16 == 0);
@@ -345,7 +358,7 @@ static int sample_impl(simple_ctx* ctx, const simple_state* state, const int32_t
   const int64_t per_launch = ctx->slots;
   a.F = simple::make_fast_layout(V, dtype, with_hist ? ctx->max_nnz : 0, with_hist, vec, ctx->lds_limit,
                                  B < per_launch ? B : per_launch, ctx->n_cu);
-  a.gated = (a.F.total != 0u) ? 1 : 0;
+  a.gated = (a.F.total != 0u || tail) ? 1 : 0;
   for (int64_t b0 = 0; b0 < B; b0 += per_launch) {
     const int64_t nb = (B - b0 < per_launch) ? (B - b0) : per_launch;
     a.B = (int)nb;
@@ -363,6 +376,13 @@ static int sample_impl(simple_ctx* ctx, const simple_state* state, const int32_t
     if (a.gated) ctx->parity ^= 1;
     hipEvent_t ev0 = nullptr, ev1 = nullptr;
     if (ctx->prof_ev && ctx->prof_n < PROF_MAX) { ev0 = ctx->prof_ev[2 * ctx->prof_n]; ev1 = ctx->prof_ev[2 * ctx->prof_n + 1]; ++ctx->prof_n; }
+    if (tail) {  // the hot-first kernel, then the general kernel on the rows it left
+      if (ev0 && hipEventRecord(ev0, st) != hipSuccess) return SIMPLE_EDEVICE;
+      if (simple::launch_hot_first(a, dtype, (int)H, tail + b0, st) != hipSuccess) return SIMPLE_EDEVICE;
+      if (ev1 && hipEventRecord(ev1, st) != hipSuccess) return SIMPLE_EDEVICE;
+      if (simple::launch_pending_rows(a, dtype, vec, st) != hipSuccess) return SIMPLE_EDEVICE;
+      continue;
+    }
     if (simple::launch_sample(a, dtype, vec, st, ev0, ev1) != hipSuccess) return SIMPLE_EDEVICE;
   }
   return SIMPLE_OK;
@@ -376,7 +396,7 @@ int simple_sample(simple_ctx* ctx, const void* logits_dev, int64_t B, int64_t V,
                   const int32_t* hot_ids_dev, int32_t H, uint64_t seed, uint64_t step,
                   uint64_t row_offset, int32_t* out_ids_dev, simple_row_diag* diag_dev,
                   void* hip_stream) {
-  return sample_impl(ctx, nullptr, nullptr, logits_dev, B, V, dtype, row_stride_elems, params_dev, hist_ptr_dev, hist_ids_dev,
+  return sample_impl(ctx, nullptr, nullptr, nullptr, logits_dev, B, V, dtype, row_stride_elems, params_dev, hist_ptr_dev, hist_ids_dev,
                      hot_ids_dev, H, seed, step, row_offset, out_ids_dev, diag_dev, hip_stream);
 }
 
@@ -453,12 +473,21 @@ int simple_state_append(simple_state* state, const int32_t* slots_dev, const int
   return SIMPLE_OK;
 }
 
+int simple_sample_hot_first(simple_ctx* ctx, const void* logits_dev, int64_t B, int64_t V, int dtype, int64_t row_stride_elems,
+                            const simple_row_params* params_dev, int32_t H, const simple_tail_stats* tail_stats_dev,
+                            uint64_t seed, uint64_t step, uint64_t row_offset, int32_t* out_ids_dev,
+                            simple_row_diag* diag_dev, void* hip_stream) {
+  if (!tail_stats_dev || H <= 0) return SIMPLE_EINVAL;
+  return sample_impl(ctx, nullptr, nullptr, tail_stats_dev, logits_dev, B, V, dtype, row_stride_elems, params_dev, nullptr, nullptr,
+                     nullptr, H, seed, step, row_offset, out_ids_dev, diag_dev, hip_stream);
+}
+
 int simple_sample_state(simple_ctx* ctx, const simple_state* state, const int32_t* slots_dev, const void* logits_dev, int64_t B, int64_t V,
                         int dtype, int64_t row_stride_elems, const simple_row_params* params_dev,
                         const int32_t* hot_ids_dev, int32_t H, uint64_t seed, uint64_t step, uint64_t row_offset,
                         int32_t* out_ids_dev, simple_row_diag* diag_dev, void* hip_stream) {
   if (!state) return SIMPLE_EINVAL;
-  return sample_impl(ctx, state, slots_dev, logits_dev, B, V, dtype, row_stride_elems, params_dev, nullptr, nullptr,
+  return sample_impl(ctx, state, slots_dev, nullptr, logits_dev, B, V, dtype, row_stride_elems, params_dev, nullptr, nullptr,
                      hot_ids_dev, H, seed, step, row_offset, out_ids_dev, diag_dev, hip_stream);
 }
 

@@ -1589,6 +1589,11 @@ static hipError_t launch_pending(const SampleArgs& a, hipStream_t st) {
   return hipGetLastError();
 }
 
+hipError_t launch_pending_rows(const SampleArgs& a, int dtype, bool vec, hipStream_t st) {
+  if (dtype == SIMPLE_F32) return vec ? launch_pending<float, true>(a, st) : launch_pending<float, false>(a, st);
+  return vec ? launch_pending<uint16_t, true>(a, st) : launch_pending<uint16_t, false>(a, st);
+}
+
 // ev0 / ev1 (may be null): recorded right before and after the dominant kernel of the call.
 hipError_t launch_sample(const SampleArgs& a, int dtype, bool vec, hipStream_t st, hipEvent_t ev0, hipEvent_t ev1) {
   if (ev0 && hipEventRecord(ev0, st) != hipSuccess) return hipErrorUnknown;

@@ -148,6 +148,11 @@ hipError_t launch_state_reset(StateRec* rec, int32_t* tokens, unsigned char* tab
 hipError_t launch_state_append(StateRec* rec, int32_t* tokens, unsigned char* tables, int n_slots, int lmax, int V, uint32_t stride,
                                uint32_t off_dir, uint32_t off_cnt, const int32_t* slots, const int32_t* new_ids, int B, hipStream_t st);
 hipError_t set_max_lds_state(unsigned bytes);
+hipError_t launch_pending_rows(const SampleArgs& a, int dtype, bool vec, hipStream_t st);  // the general kernel on the queued rows
+hipError_t launch_hot_range(uint32_t* bits, uint32_t* flags, int V, int H, hipStream_t st);  // hot set [0, H) as a mask
+hipError_t launch_hot_first(const SampleArgs& a, int dtype, int H, const simple_tail_stats* tail, hipStream_t st);
+int hot_first_tile(int dtype);   // columns per tile of the hot-first kernel: H must be a multiple
+int hot_first_max_tiles();       // tiles of hot set or tail it can index
 hipError_t launch_hot_build(const int32_t* ids, int H, int V, uint32_t* bits, uint32_t* flags, hipStream_t st);
 
 }  // namespace simple

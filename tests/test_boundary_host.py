@@ -43,6 +43,8 @@ def test_null_context_and_bad_arguments_are_rejected_on_the_host():
     assert binding.simple_sample(0, 0, 1, 8, 0, 8, 0, 0, 0, 0, 0, 1, 0, 0, 0, 0) == binding.SIMPLE_EINVAL
     assert binding.simple_set_hot_set(0, 0, 4, 8) == binding.SIMPLE_EINVAL
     assert binding.simple_set_stats(0, 0) == binding.SIMPLE_EINVAL
+    assert binding.simple_sample_hot_first(0, 0, 1, 4096, 0, 4096, 0, 1024, 0, 1, 0, 0, 0, 0) == binding.SIMPLE_EINVAL   # no tail statistics
+    assert binding.simple_sample_hot_first(0, 0, 1, 4096, 0, 4096, 0, 0, 1, 1, 0, 0, 0, 0) == binding.SIMPLE_EINVAL      # H <= 0
     # logit constraints: sizes and pointer pairs are checked before anything is enqueued
     assert binding.simple_apply_logit_constraints(0, 1, 0, 0, 8, 0, 0, 0, 0, 0, 0, 8) == binding.SIMPLE_EINVAL
     assert binding.simple_apply_logit_constraints(0, 1, 8, 0, 8, 1, 0, 0, 0, 0, 0, 8) == binding.SIMPLE_EINVAL   # offsets without ids
