@@ -192,7 +192,7 @@ def hot_first_sweep(args) -> int:
     stats_dev = torch.zeros(64, dtype=torch.uint8, device=dev)
     stream = torch.cuda.current_stream().cuda_stream
     rows = []
-    for H in (2048, 4096, 8192, 16384, 32768, 65536):
+    for H in ((args.H,) if args.H else (2048, 4096, 8192, 16384, 32768, 65536)):
         # what the producer of the logits would supply (temperature 1): maximum and exponential sum of each row's tail
         tail = lg[:, H:].float()
         tmax = tail.max(dim=1).values
@@ -231,6 +231,10 @@ def hot_first_sweep(args) -> int:
         rows.append(row)
         print(json.dumps({"hot_first": row}), file=sys.stderr, flush=True)
     Hs = [r["H"] for r in rows]
+    if len(rows) < 2:  # a single hot-set size (--H): no fit
+        print(json.dumps({"sweep": rows}), flush=True)
+        s.close()
+        return 0
     c, c0 = sizing.fit_affine_cost(Hs, [r["ms_per_call_hot_path_only"] * 1e-3 / B for r in rows])
     alpha = [r["mean_alpha"] for r in rows]
     F = sizing.expected_cost(Hs, alpha, c, c0, V)
