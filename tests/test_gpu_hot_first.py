@@ -131,3 +131,40 @@ def test_hot_first_whole_vocabulary_hot_and_argument_errors():
     ids = out.cpu().numpy()
     assert ids[10] == -1 and ids[11] == -1 and (ids[[0, 7, 8, 9]] >= 0).all()
     s.close()
+
+
+def test_hot_first_at_the_size_of_the_shvs_configuration():
+    """B = 512, V = 201,088 bf16 (the shape of the SHVS sweep), H = 16384, in the launch configuration the
+    benchmark's hot-first sweep times: every row for range, flags and determinism, a seeded sample of
+    rows (accepted and rejected ones) against the oracle."""
+    import torch
+    B, V, H = 512, 201_088, 16_384
+    w = _workload("bf16", B, V, 91)
+    w.params["top_k"][:] = 0; w.params["top_p"][:] = 1.0; w.params["min_p"][:] = 0.0
+    w.params["temperature"][:] = 1.0; w.params["rep_penalty"][:] = 1.0
+    ts = tail_stats(w.logits_f32(), w.params, H)
+    wh = synth.Workload(w.name, B, V, "bf16", w.logits, w.params, w.hist_ptr, w.hist_ids, hot_ids=np.arange(H, dtype=np.int32), seed=w.seed)
+    dev = P.to_device(wh)
+    s = binding.Sampler(V, 0, max_B=B)
+    ts_dev = _dev(ts.view(np.uint8).reshape(B, 16))
+    lg = dev["logits"]
+    res = []
+    for rep in range(2):
+        out = torch.full((B,), -9, dtype=torch.int32, device="cuda:0")
+        diag = torch.zeros(B * 32, dtype=torch.uint8, device="cuda:0")
+        rc = binding.simple_sample_hot_first(s.ctx, lg.data_ptr(), B, V, binding.SIMPLE_BF16, lg.stride(0), dev["params"].data_ptr(), H,
+                                             ts_dev.data_ptr(), w.seed, 4, 0, out.data_ptr(), diag.data_ptr() if rep == 0 else 0,
+                                             torch.cuda.current_stream().cuda_stream)
+        assert rc == 0
+        torch.cuda.synchronize()
+        res.append((out.cpu().numpy(), diag.cpu().numpy().view(binding.ROW_DIAG_DTYPE)))
+    ids, dg = res[0]
+    assert np.array_equal(ids, res[1][0])                     # the same call without a diagnostics buffer
+    assert ids.min() >= 0 and ids.max() < V and not (dg["flags"] & (binding.DIAG_ERROR | binding.DIAG_GENERAL)).any()
+    acc = (dg["flags"] & binding.DIAG_ACCEPTED) > 0
+    assert np.all(ids[acc] < H) and np.all(ids[~acc] >= H) and 0 < (~acc).sum() < B // 4
+    rng = np.random.default_rng(3)
+    rows = sorted(set(rng.choice(B, 40, replace=False).tolist()) | set(np.flatnonzero(~acc)[:12].tolist()))
+    summary = P.compare(ids, dg, P.run_oracle(wh, 4, rows=rows), rows)
+    print(f"full size: {summary}; accepted {int(acc.sum())} of {B}", flush=True)
+    s.close()
