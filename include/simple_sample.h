@@ -108,7 +108,8 @@ enum {
   SIMPLE_DIAG_BAD_LOGIT = 1u << 9,     /* NaN or +inf logit, or every logit -inf */
   SIMPLE_DIAG_BAD_HISTORY_ID = 1u << 10, /* ignored */
   SIMPLE_DIAG_HISTORY_TOO_LONG = 1u << 11,
-  SIMPLE_DIAG_BAD_HOT_SET = 1u << 12   /* hot id outside [0, V) or duplicated (ignored) */
+  SIMPLE_DIAG_BAD_HOT_SET = 1u << 12,  /* hot id outside [0, V) or duplicated (ignored) */
+  SIMPLE_DIAG_PATTERN = 1u << 13       /* bfloat16 row without top-k and penalties, completed from counts per bit pattern */
 };
 
 /* Optional aggregate over the rows of the calls made while it is installed (64 bytes, device

@@ -22,8 +22,8 @@ SIMPLE_OK, SIMPLE_EINVAL, SIMPLE_ENOMEM, SIMPLE_EDEVICE, SIMPLE_ECAPACITY = 0, -
 
 DIAG_ERROR, DIAG_GREEDY, DIAG_WIDE, DIAG_SHVS, DIAG_ACCEPTED, DIAG_CAREFUL, DIAG_REPLAY, DIAG_GENERAL = (
     1 << i for i in range(8))
-DIAG_BAD_PARAM, DIAG_BAD_LOGIT, DIAG_BAD_HISTORY_ID, DIAG_HISTORY_TOO_LONG, DIAG_BAD_HOT_SET = (
-    1 << i for i in range(8, 13))
+DIAG_BAD_PARAM, DIAG_BAD_LOGIT, DIAG_BAD_HISTORY_ID, DIAG_HISTORY_TOO_LONG, DIAG_BAD_HOT_SET, DIAG_PATTERN = (
+    1 << i for i in range(8, 14))
 
 ROW_DIAG_DTYPE = np.dtype([("alpha", "<f8"), ("s_k", "<f8"), ("p_chosen", "<f4"),
                            ("n_survivors", "<i4"), ("flags", "<u4"), ("reserved", "<u4")])

@@ -9,7 +9,7 @@ from concurrent.futures import ThreadPoolExecutor
 PKG = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(PKG)
 LIB = os.path.join(PKG, "libsimple_sample.so")
-SOURCES = [os.path.join(PKG, "csrc", f) for f in ("simple_kernels.hip", "simple_fast.hip", "simple_wide.hip", "simple_state.hip", "simple_constraints.hip", "simple_hotfirst.hip", "simple_probe.hip", "simple_api.hip")]
+SOURCES = [os.path.join(PKG, "csrc", f) for f in ("simple_kernels.hip", "simple_fast.hip", "simple_wide.hip", "simple_pattern.hip", "simple_state.hip", "simple_constraints.hip", "simple_hotfirst.hip", "simple_probe.hip", "simple_api.hip")]
 OBJ_DIR = os.path.join(PKG, "_build")
 
 HIPCC_FLAGS = [

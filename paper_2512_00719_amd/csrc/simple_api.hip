@@ -359,6 +359,7 @@ static int sample_impl(simple_ctx* ctx, const simple_state* state, const int32_t
   a.F = simple::make_fast_layout(V, dtype, with_hist ? ctx->max_nnz : 0, with_hist, vec, ctx->lds_limit,
                                  B < per_launch ? B : per_launch, ctx->n_cu);
   a.gated = (a.F.total != 0u || tail) ? 1 : 0;
+  a.pattern_on = (a.F.total != 0u && !tail && dtype == SIMPLE_BF16 && V < ((int64_t)1 << 18)) ? 1 : 0;
   for (int64_t b0 = 0; b0 < B; b0 += per_launch) {
     const int64_t nb = (B - b0 < per_launch) ? (B - b0) : per_launch;
     a.B = (int)nb;

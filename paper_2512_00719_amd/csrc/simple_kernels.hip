@@ -1598,7 +1598,9 @@ hipError_t launch_pending_rows(const SampleArgs& a, int dtype, bool vec, hipStre
 hipError_t launch_sample(const SampleArgs& a, int dtype, bool vec, hipStream_t st, hipEvent_t ev0, hipEvent_t ev1) {
   if (ev0 && hipEventRecord(ev0, st) != hipSuccess) return hipErrorUnknown;
   if (a.gated) {  // single-pass kernel first; the general kernel then completes the rows it queued
-    hipError_t e = launch_fast(a, dtype, st);
+    hipError_t e = a.pattern_on ? launch_pattern(a, st) : hipSuccess;
+    if (e != hipSuccess) return e;
+    e = launch_fast(a, dtype, st);
     if (e != hipSuccess) return e;
     if (ev1 && hipEventRecord(ev1, st) != hipSuccess) return hipErrorUnknown;
     e = launch_wide(a, dtype, st);  // rows whose nucleus spans more of the vocabulary than the list holds

@@ -37,6 +37,7 @@ constexpr int SAMPLE_PER_WAVE = 48;   // keys of the threshold sample a wave han
 constexpr int CAPF_PER_THREAD = 12;  // candidate-list entries per thread the single-pass kernel's epilogue holds in registers
 constexpr int KMAXF = 1024;   // largest top-k its list certifies
 constexpr int32_t PENDING = -2;  // id left by the single-pass kernel on rows the general kernel completes
+constexpr int32_t NOT_TAKEN = -3;  // id left by the pattern-count kernel on a row of its route that it hands back to the single-pass kernel
 constexpr int PEND_ROWS = 65536; // rows per launch (capacity of the pending-row queue)
 constexpr int WIDE_SLOTS = 4096; // workspace slots of the whole-vocabulary-nucleus kernels; a launch takes no more rows than this,
                                  // so every row of it can be queued for them
@@ -78,6 +79,7 @@ struct SampleArgs {
   uint32_t st_stride;
   int max_nnz;
   int gated;       // 1: the single-pass kernel runs first and queues the rows it leaves
+  int pattern_on;  // 1: the pattern-count kernel (bfloat16 rows without top-k and penalties) ran before the single-pass kernel
   // Queues filled by the single-pass kernel.  Word [parity] counts the entries of this launch; the
   // single-pass kernel clears word [parity ^ 1], which the previous launch on the stream used.
   uint32_t* pend;  // rows left to the general kernel: [0], [1] counts, [2 ..] row indices
@@ -133,12 +135,22 @@ __device__ __forceinline__ RowHist row_history(const SampleArgs& a, int row, int
   return a.st_rec ? row_history_state(a, row, par_n_prompt) : row_history_csr(a, row, par_n_prompt);
 }
 
+// Rows of the pattern-count route (bfloat16 calls only): survivors are a prefix of the whole vocabulary
+// (no top-k; top-p, min-p or no truncation), no penalty is in force, and the parameters are valid.
+__device__ __forceinline__ bool pattern_route(const simple_row_params& par, int V, int nnz, int max_nnz) {
+  const bool pen_on = par.rep_penalty != 1.0f || par.freq_penalty != 0.0f || par.pres_penalty != 0.0f;
+  const bool k_on = par.top_k >= 1 && par.top_k < V;
+  return par.temperature > 0.0f && par.temperature < INFINITY && par.rep_penalty > 0.0f && !k_on && par.top_p > 0.0f &&
+         !(nnz > 0 && pen_on) && nnz <= max_nnz;
+}
+
 LdsLayout make_layout(int64_t V, int64_t max_nnz, bool with_history);
 // Layout of the single-pass kernel; total = 0 when the call cannot use it.
 FastLayout make_fast_layout(int64_t V, int dtype, int64_t max_nnz, bool with_history, bool vec, int lds_limit,
                             int64_t B, int n_cu);
 hipError_t launch_sample(const SampleArgs& a, int dtype, bool vec, hipStream_t st, hipEvent_t ev0, hipEvent_t ev1);
 hipError_t launch_fast(const SampleArgs& a, int dtype, hipStream_t st);
+hipError_t launch_pattern(const SampleArgs& a, hipStream_t st);  // before launch_fast, when a.pattern_on
 hipError_t launch_wide(const SampleArgs& a, int dtype, hipStream_t st);  // after launch_fast, before the general kernel
 hipError_t set_max_lds(unsigned bytes);
 hipError_t set_max_lds_fast(unsigned bytes);

@@ -1,0 +1,166 @@
+"""GPU parity on the pattern-count route: bfloat16 rows without top-k and without penalties in
+force are completed from counts per bit pattern (one LDS atomic per column), the cut and the class
+masses from the counts, the drawn id from a second read.  Every case is compared with the CPU
+oracle row by row, to the bar of test_gpu_parity.py, and the diagnostic flag of the route says which
+rows took it.  Cases: nuclei of every width, min-p, no truncation, temperatures, with and without a
+hot set, a ragged row end behind a padded stride, rows made of a handful of distinct values (the
+cut falls inside a pattern with thousands of tied columns), rows the route must hand back (an
+infinity, a magnitude outside its bins, a row maximum near zero), rows that must not take it
+(top-k, penalties in force, float32)."""
+import numpy as np
+import pytest
+
+import parity_util as P
+from paper_2512_00719_amd import binding, synth
+
+pytestmark = pytest.mark.gpu
+
+PATTERN, WIDE, SHVS, GENERAL = binding.DIAG_PATTERN, binding.DIAG_WIDE, binding.DIAG_SHVS, binding.DIAG_GENERAL
+
+
+def _bf16(z32):
+    bits = synth.f32_to_bf16_bits(np.asarray(z32, np.float32))
+    return bits, synth.bf16_bits_to_f32(bits)
+
+
+def _run(w, steps=(0, 1), dev=None):
+    out = []
+    for step in steps:
+        ids, dg = P.run_gpu(w, step, dev=dev)
+        s = P.compare(ids, dg, P.run_oracle(w, step), range(w.B))
+        out.append((ids, dg, s))
+    return out
+
+
+def _zipf_rows(rng, B, V, s=1.0, sigma=1.0):
+    base = -s * np.log(np.arange(1, V + 1, dtype=np.float64))
+    z = np.empty((B, V), np.float32)
+    for b in range(B):
+        z[b, rng.permutation(V)] = base + sigma * rng.standard_normal(V)
+    return z + 12.0
+
+
+@pytest.mark.parametrize("hot", [False, True])
+def test_nuclei_min_p_and_no_truncation(hot):
+    rng = np.random.default_rng(31 + hot)
+    B, V = 24, 50_000 + 16
+    bits, zf = _bf16(_zipf_rows(rng, B, V, s=1.1, sigma=1.2))
+    top_p = np.array([0.3, 0.9, 0.95, 0.999, 1.0, 1.0, 0.5, 0.99] * 3, np.float32)
+    min_p = np.array([0.0, 0.0, 0.0, 0.0, 0.0, 1e-4, 1e-3, 0.02] * 3, np.float32)
+    temp = np.array([1.0] * 8 + [0.6] * 8 + [1.7] * 8, np.float32)
+    params = synth.make_params(B, temperature=temp, top_p=top_p, min_p=min_p)
+    hot_ids = np.sort(np.argsort(-zf.mean(axis=0))[:4000]).astype(np.int32) if hot else None
+    w = synth.Workload("pattern", B, V, "bf16", bits, params, np.zeros(B + 1, np.int64), np.zeros(0, np.int32), hot_ids=hot_ids)
+    for ids, dg, s in _run(w, steps=(0, 1, 2)):
+        f = dg["flags"]
+        assert ((f & PATTERN) > 0).all() and ((f & WIDE) > 0).all() and not (f & GENERAL).any(), [hex(int(x)) for x in f]
+        assert (((f & SHVS) > 0) == hot).all()
+        print("pattern route:", s, "accepted", int(((f & binding.DIAG_ACCEPTED) > 0).sum()), flush=True)
+
+
+def test_few_distinct_values_cut_inside_a_pattern():
+    """Logits on a grid of a few dozen values: every pattern holds thousands of tied columns, so the
+    nucleus ends inside one and takes its first j columns in ascending id."""
+    rng = np.random.default_rng(33)
+    B, V = 16, 30_000 + 8
+    z = np.round(rng.standard_normal((B, V)) * 2.0) * 0.5 + 3.0
+    z[:, ::1000] += 0.25  # a few columns of their own value
+    bits, zf = _bf16(z)
+    params = synth.make_params(B, temperature=[1.0, 0.8, 1.3, 1.0] * 4, top_p=[0.5, 0.9, 0.97, 0.2] * 4,
+                               min_p=[0.0, 0.0, 0.05, 0.0] * 4)
+    hot_ids = np.sort(rng.choice(V, 6000, replace=False)).astype(np.int32)
+    w = synth.Workload("pattern-ties", B, V, "bf16", bits, params, np.zeros(B + 1, np.int64), np.zeros(0, np.int32), hot_ids=hot_ids)
+    for ids, dg, s in _run(w, steps=(0, 1, 2, 3)):
+        assert ((dg["flags"] & PATTERN) > 0).all()
+    w.hot_ids = None
+    for ids, dg, s in _run(w, steps=(4, 5)):
+        assert ((dg["flags"] & PATTERN) > 0).all()
+
+
+def test_ragged_row_end_behind_a_padded_stride():
+    import torch
+    rng = np.random.default_rng(34)
+    B, V, stride = 12, 33_003, 33_008  # V is no multiple of the vector width: the last columns are read one by one
+    z = rng.standard_normal((B, V)) * 1.5
+    z[:, V - 2] = 9.0  # a likely draw in the ragged end
+    z[3, V - 1] = 11.0
+    bits, zf = _bf16(z)
+    params = synth.make_params(B, temperature=[1.0, 0.7, 1.2] * 4, top_p=[0.9, 1.0, 0.99, 0.6] * 3)
+    hot_ids = np.sort(np.concatenate([rng.choice(V - 8, 3000, replace=False), [V - 2]])).astype(np.int32)
+    w = synth.Workload("pattern-ragged", B, V, "bf16", bits, params, np.zeros(B + 1, np.int64), np.zeros(0, np.int32), hot_ids=hot_ids)
+    padded = np.full((B, stride), 0x7F80, np.uint16)  # +inf in the padding: it must never be read as a logit
+    padded[:, :V] = bits
+    dev = P.to_device(w)
+    dev["logits"] = torch.from_numpy(padded.view(np.int16)).cuda().view(torch.bfloat16)
+    got_end = 0
+    for ids, dg, s in _run(w, steps=tuple(range(6)), dev=dev):
+        assert ((dg["flags"] & PATTERN) > 0).all()
+        got_end += int((ids >= V - 3).sum())
+    assert got_end > 0  # the draw did land behind the last whole group
+
+
+def test_rows_handed_back_and_rows_that_never_take_the_route():
+    rng = np.random.default_rng(35)
+    B, V = 16, 20_000
+    z = _zipf_rows(rng, B, V, s=1.0, sigma=1.0)
+    z[0, 5:400] = -np.inf           # masked columns
+    z[1, 77] = 300.0                # a magnitude outside the bins
+    z[2] = rng.standard_normal(V) * 1e-6   # row maximum near zero
+    z[3] = 0.0                      # all columns equal
+    z[4, 9] = np.inf                # an error row
+    z[5, 11] = np.nan
+    z[6] = np.where(rng.random(V) < 0.002, 0.0, z[6])  # some exact zeros among ordinary values
+    bits, zf = _bf16(z)
+    params = synth.make_params(B, temperature=1.0, top_p=0.9)
+    params["top_k"][8] = 50                 # top-k: the single-pass kernel's list
+    params["rep_penalty"][9] = 1.2          # penalties in force (history below)
+    params["temperature"][10] = 0.0         # greedy
+    params["top_p"][11] = 0.0               # keeps one token
+    params["top_p"][12] = 1.0               # no truncation at all
+    params["min_p"][13] = 0.1
+    lens = np.zeros(B, np.int64); lens[9] = 40; lens[14] = 25   # row 14: a history, but no penalty in force
+    hist_ptr = np.concatenate([[0], np.cumsum(lens)]).astype(np.int64)
+    hist_ids = rng.integers(0, V, int(hist_ptr[-1])).astype(np.int32)
+    w = synth.Workload("pattern-edges", B, V, "bf16", bits, params, hist_ptr, hist_ids)
+    for ids, dg, s in _run(w, steps=(0, 1)):
+        f = dg["flags"]
+        took = (f & PATTERN) > 0
+        assert not took[[0, 1, 2, 3, 4, 5, 8, 9, 10, 11]].any(), took
+        assert took[[6, 7, 12, 13, 14, 15]].all(), took
+        assert ids[4] == -1 and ids[5] == -1 and (ids[[0, 1, 2, 3]] >= 0).all()
+    # float32 calls never take it
+    w32 = synth.Workload("pattern-f32", B, V, "f32", zf.copy(), params, hist_ptr, hist_ids)
+    w32.logits[4, 9] = 1.0; w32.logits[5, 11] = 1.0
+    ids, dg = P.run_gpu(w32, 0)
+    assert not (dg["flags"] & PATTERN).any()
+
+
+def test_decision_outputs_and_aggregate_on_the_route():
+    """Log-probabilities, EOS flags and the aggregate of a call come out of this route as of the others."""
+    import torch
+    rng = np.random.default_rng(36)
+    B, V = 64, 16_384
+    bits, zf = _bf16(_zipf_rows(rng, B, V))
+    params = synth.make_params(B, temperature=1.0, top_p=0.9)
+    w = synth.Workload("pattern-out", B, V, "bf16", bits, params, np.zeros(B + 1, np.int64), np.zeros(0, np.int32))
+    dev = P.to_device(w)
+    ctx = binding.Sampler(V, 0, max_B=B)
+    lp = torch.full((B,), 7.0, dtype=torch.float32, device="cuda:0")
+    eos = torch.full((B,), 9, dtype=torch.uint8, device="cuda:0")
+    stats = torch.zeros(binding.STATS_DTYPE.itemsize, dtype=torch.uint8, device="cuda:0")
+    want = P.run_oracle(w, 0)
+    eos_id = int(want[0].id)
+    assert binding.simple_set_decision_outputs(ctx.ctx, lp.data_ptr(), eos.data_ptr(), [eos_id]) == 0
+    assert binding.simple_set_stats(ctx.ctx, stats.data_ptr()) == 0
+    diag = torch.zeros(B * 32, dtype=torch.uint8, device="cuda:0")
+    out = ctx.sample(dev["logits"], dev["params"], None, None, None, seed=w.seed, step=0, diag=diag, V=V)
+    torch.cuda.synchronize()
+    ids = out.cpu().numpy()
+    dg = diag.cpu().numpy().view(binding.ROW_DIAG_DTYPE)
+    P.compare(ids, dg, want, range(B))
+    assert ((dg["flags"] & PATTERN) > 0).all()
+    assert np.allclose(lp.cpu().numpy(), np.log(dg["p_chosen"]), rtol=0, atol=1e-6)
+    assert np.array_equal(eos.cpu().numpy() == 1, ids == eos_id)
+    st = stats.cpu().numpy().view(binding.STATS_DTYPE)[0]
+    assert int(st["rows"]) == B and int(st["second_pass_rows"]) == B and int(st["general_rows"]) == 0
+    ctx.close()
