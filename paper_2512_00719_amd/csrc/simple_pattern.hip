@@ -53,6 +53,7 @@ constexpr int TILE = 64 * 8 * TG;  // columns per tile of the second pass, one w
 constexpr int NTILE = (1 << 18) / TILE;  // V < 2^18
 static_assert(NTILE <= PT, "one tile per thread in the scans over tiles");
 constexpr int UN = 4;          // 16-byte loads in flight per lane, twice (two register sets take turns)
+constexpr uint32_t FILL = 0xC381C381u;  // two patterns (-258.0) whose bin, taken without the upper clamp, is the spare entry NB of the table
 constexpr int CBIT = 58;       // a table entry counts a column of the cut pattern from this bit up
 constexpr u64 MASS_PART = (1ull << CBIT) - 1ull;
 static_assert(TILE / 64 < (1 << (64 - CBIT)), "a lane's columns of one tile fit the count");
@@ -68,8 +69,8 @@ __device__ __forceinline__ int bin_of(uint32_t raw) {
   return (NMAG - 1) - (q ^ s);
 }
 // The same for the two patterns of a 32-bit word at once (packed 16-bit arithmetic), as byte offsets
-// into a table of 8-byte entries, low pattern in the low half; pmax gathers the largest magnitudes.
-template <bool CLAMP_HIGH>
+// into a table of (1 << SHIFT)-byte entries, low pattern in the low half; pmax gathers the largest magnitudes.
+template <bool CLAMP_HIGH, int SHIFT>
 __device__ __forceinline__ uint32_t bin_offsets2(uint32_t x, s16x2& pmax) {
   const s16x2 xs = __builtin_bit_cast(s16x2, x);
   const s16x2 s = xs >> (short)15;
@@ -78,7 +79,7 @@ __device__ __forceinline__ uint32_t bin_offsets2(uint32_t x, s16x2& pmax) {
   s16x2 q = __builtin_elementwise_max((s16x2)(p - (short)(PLO - 1)), (s16x2)((short)0));
   if (CLAMP_HIGH) q = __builtin_elementwise_min(q, (s16x2)((short)QMAX));
   const s16x2 d = (short)(NMAG - 1) - (q ^ s);
-  return __builtin_bit_cast(uint32_t, (u16x2)(__builtin_bit_cast(u16x2, d) << (unsigned short)3));
+  return __builtin_bit_cast(uint32_t, (u16x2)(__builtin_bit_cast(u16x2, d) << (unsigned short)SHIFT));
 }
 // bit pattern of a bin (zero for the merged bins)
 __device__ __forceinline__ uint32_t raw_of(int d) {
@@ -143,7 +144,7 @@ __device__ __forceinline__ void tile_load(TileRegs& R, const uint16_t* rowp, con
 #pragma unroll
   for (int h = 0; h < TG; ++h) {
     const int g = tile * (TILE / 8) + h * 64 + lane;
-    R.r[h] = u32x4{0u, 0u, 0u, 0u};
+    R.r[h] = u32x4{FILL, FILL, FILL, FILL};
     R.hq[h] = 0u;
     if (g < n_groups) {
       R.r[h] = *as_global(reinterpret_cast<const u32x4*>(rowp) + g);
@@ -158,7 +159,7 @@ __device__ __forceinline__ uint32_t raw_at(const u32x4& r, int e) {
 
 template <bool USE_HOT>
 __global__ __launch_bounds__(PT, 4) void pattern_rows_kernel(const SampleArgs a) {
-  __shared__ __align__(16) u64 tab[NB];   // counts in the first pass, then per bin the mass of a surviving column
+  __shared__ __align__(16) u64 tab[NB + 2];   // 32-bit counts (in its first half) in the first pass, then per bin the mass of a surviving column
   __shared__ u64 tall[NTILE], thot[NTILE];  // per tile: mass of the sure survivors, and of the hot ones among them
   __shared__ uint32_t tcc[NTILE];           // per tile: columns of the cut pattern, the hot ones among them from bit 16
   __shared__ PS P;
@@ -191,7 +192,8 @@ __global__ __launch_bounds__(PT, 4) void pattern_rows_kernel(const SampleArgs a)
     }
   };
   fetch(A, 0);
-  for (int i = tid; i < NB; i += PT) tab[i] = 0ull;
+  for (int i = tid; i < NB / 2; i += PT) tab[i] = 0ull;
+  if (tid < 2) tab[NB + tid] = 0ull;  // stays zero: what a group behind the row's end looks up
   if (tid == 0) {
     P.dtop = NB; P.dcut = -1; P.bad = 0; P.tdraw = -1; P.id_cut = -1; P.partial = 0;
     P.pm = 0u; P.pos_m = 0u; P.pos_p = 0u; P.jcut = 0u; P.ccut = 0u; P.tcut = 0u; P.rcut = 0u; P.hot_before = 0u; P.hot_in = 0u; P.merged_n = 0u;
@@ -200,7 +202,7 @@ __global__ __launch_bounds__(PT, 4) void pattern_rows_kernel(const SampleArgs a)
   __syncthreads();
   s16x2 pmax = {0, 0};  // largest magnitude patterns seen by this thread
   auto count2 = [&](uint32_t x) {
-    const uint32_t off = bin_offsets2<true>(x, pmax);
+    const uint32_t off = bin_offsets2<true, 2>(x, pmax);
     __hip_atomic_fetch_add(reinterpret_cast<uint32_t*>(tabb + (off & 0xFFFFu)), 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
     __hip_atomic_fetch_add(reinterpret_cast<uint32_t*>(tabb + (off >> 16)), 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
   };
@@ -218,7 +220,7 @@ __global__ __launch_bounds__(PT, 4) void pattern_rows_kernel(const SampleArgs a)
   uint32_t pm = (uint32_t)max((int)pmax.x, (int)pmax.y);
   if (tid < V - n_groups * 8) {  // the ragged end of the row
     const uint32_t raw = (uint32_t)*as_global(rowp + n_groups * 8 + tid);
-    __hip_atomic_fetch_add(reinterpret_cast<uint32_t*>(tabb + 8 * bin_of(raw)), 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+    __hip_atomic_fetch_add(reinterpret_cast<uint32_t*>(tabb + 4 * bin_of(raw)), 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
     pm = max(pm, raw & 0x7FFFu);
   }
   pm = wave_max_u32(pm);
@@ -233,7 +235,7 @@ __global__ __launch_bounds__(PT, 4) void pattern_rows_kernel(const SampleArgs a)
     int dfirst = NB;
 #pragma unroll
     for (int j = 0; j < BPT; ++j) {
-      ca[j] = (uint32_t)tab[d_first + j];
+      ca[j] = reinterpret_cast<const uint32_t*>(tab)[d_first + j];
       csum += ca[j];
       if (ca[j] && dfirst == NB) dfirst = d_first + j;
     }
@@ -324,16 +326,14 @@ __global__ __launch_bounds__(PT, 4) void pattern_rows_kernel(const SampleArgs a)
       if (t + PNW < n_tiles) tile_load<USE_HOT>(N, rowp, hot_bits, t + PNW, lane, n_groups);
       u64 acc = 0ull, acc_h = 0ull;
 #pragma unroll
-      for (int h = 0; h < TG; ++h) {
-        const bool in = t * (TILE / 8) + h * 64 + lane < n_groups;
+      for (int h = 0; h < TG; ++h) {  // (groups behind the row's end hold FILL, whose table entry is zero)
         const uint32_t w4[4] = {R.r[h].x, R.r[h].y, R.r[h].z, R.r[h].w};
 #pragma unroll
         for (int k = 0; k < 4; ++k) {
           s16x2 unused = {0, 0};
-          const uint32_t off = bin_offsets2<false>(w4[k], unused);
-          u64 m0 = *reinterpret_cast<const u64*>(tabb + (off & 0xFFFFu));
-          u64 m1 = *reinterpret_cast<const u64*>(tabb + (off >> 16));
-          m0 = in ? m0 : 0ull; m1 = in ? m1 : 0ull;
+          const uint32_t off = bin_offsets2<false, 3>(w4[k], unused);
+          const u64 m0 = *reinterpret_cast<const u64*>(tabb + (off & 0xFFFFu));
+          const u64 m1 = *reinterpret_cast<const u64*>(tabb + (off >> 16));
           acc += m0 + m1;
           if (USE_HOT) {
             const u64 h0 = 0ull - (u64)((R.hq[h] >> (2 * k)) & 1u), h1 = 0ull - (u64)((R.hq[h] >> (2 * k + 1)) & 1u);
@@ -380,36 +380,47 @@ __global__ __launch_bounds__(PT, 4) void pattern_rows_kernel(const SampleArgs a)
       const unsigned r = P.rcut;
       TileRegs R;
       tile_load<USE_HOT>(R, rowp, hot_bits, t, lane, n_groups);
-      unsigned before = 0u, hot_in = 0u;
-      int id = -1;
+      // matches per 16-byte group of each lane; the group row (64 groups) that holds the r-th match
+      uint32_t mm[TG];
+      unsigned tot[TG];
 #pragma unroll
       for (int h = 0; h < TG; ++h) {
         const bool in = t * (TILE / 8) + h * 64 + lane < n_groups;
-        uint32_t mm = 0u;
+        mm[h] = 0u;
 #pragma unroll
-        for (int e = 0; e < 8; ++e) mm |= (in && raw_at(R.r[h], e) == cut_raw) ? (1u << e) : 0u;
-        const unsigned c = (unsigned)__popc(mm);
-        const unsigned inc = wave_incl_scan(c);
-        const unsigned tot = (unsigned)__shfl((int)inc, 63, 64);
-        const unsigned lo = before + inc - c;  // matches before this lane's
-        uint32_t keep = 0u;                     // this lane's matches that are among the first r
-        if (lo + c <= r) keep = mm;
+        for (int e = 0; e < 8; ++e) mm[h] |= (in && raw_at(R.r[h], e) == cut_raw) ? (1u << e) : 0u;
+        tot[h] = wave_total((uint32_t)__popc(mm[h]));
+      }
+      unsigned before = 0u, hot_in = 0u;
+      int id = -1;
+      bool found = false;
+#pragma unroll
+      for (int h = 0; h < TG; ++h) {
+        if (found) continue;
+        if (before + tot[h] < r) {  // all of this group row's matches come before the r-th
+          hot_in += (unsigned)__popc(mm[h] & R.hq[h]);
+          before += tot[h];
+          continue;
+        }
+        found = true;
+        const unsigned c = (unsigned)__popc(mm[h]);
+        const unsigned lo = before + wave_incl_scan(c) - c;  // matches before this lane's
+        uint32_t keep = 0u;                                   // this lane's matches that are among the first r
+        if (lo + c <= r) keep = mm[h];
         else if (lo < r) {
-          uint32_t m = mm;
+          uint32_t m = mm[h];
           for (unsigned k = lo; k < r; ++k) { keep |= m & (0u - m); m &= m - 1u; }
         }
         hot_in += (unsigned)__popc(keep & R.hq[h]);
-        const bool mine = c > 0u && lo < r && r <= lo + c;
-        const u64 bal = __ballot(mine);
+        const u64 bal = __ballot(c > 0u && lo < r && r <= lo + c);
         if (bal) {
           const int src = (int)__ffsll((long long)bal) - 1;
           const int e_last = 31 - __clz((int)(keep | 1u));  // only meaningful in the lane `src`
-          const int cand = (t * (TILE / 8) + h * 64 + lane) * 8 + e_last;
-          id = __shfl(cand, src, 64);
+          id = __shfl((t * (TILE / 8) + h * 64 + lane) * 8 + e_last, src, 64);
         }
-        before += tot;
+        before += tot[h];
       }
-      hot_in = wave_sum(hot_in);
+      hot_in = wave_total(hot_in);
       if (lane == 0) {
         if (id < 0 && t == n_tiles - 1) {  // among the columns behind the last whole group
           unsigned k = before;
@@ -477,21 +488,34 @@ __global__ __launch_bounds__(PT, 4) void pattern_rows_kernel(const SampleArgs a)
     tile_load<USE_HOT>(R, rowp, hot_bits, t, lane, n_groups);
     u64 base = P.mab;
     int id = -1; u64 w_id = 0ull; uint32_t raw_id = 0u;
+    u64 ls[TG], tot[TG];  // mass of each lane's 16-byte groups, and of each group row (64 groups)
 #pragma unroll
     for (int h = 0; h < TG; ++h) {
       const int idx0 = (t * (TILE / 8) + h * 64 + lane) * 8;
-      const bool in = idx0 < n_groups * 8;
-      u64 m[8]; u64 ls = 0ull;
+      ls[h] = 0ull;
+      if (idx0 < n_groups * 8) {
 #pragma unroll
-      for (int e = 0; e < 8; ++e) { m[e] = in ? col_mass(raw_at(R.r[h], e), (R.hq[h] >> e) & 1u, idx0 + e) : 0ull; ls += m[e]; }
-      const u64 inc = wave_incl_scan(ls);
-      u64 run = base + inc - ls;
-#pragma unroll
-      for (int e = 0; e < 8; ++e) {
-        if (m[e] > 0ull && run <= tfix && tfix < run + m[e]) { id = idx0 + e; w_id = m[e]; raw_id = raw_at(R.r[h], e); }
-        run += m[e];
+        for (int e = 0; e < 8; ++e) ls[h] += col_mass(raw_at(R.r[h], e), (R.hq[h] >> e) & 1u, idx0 + e);
       }
-      base += __shfl(inc, 63, 64);
+      tot[h] = wave_total(ls[h]);
+    }
+    bool found = false;
+#pragma unroll
+    for (int h = 0; h < TG; ++h) {
+      if (found) continue;
+      if (base + tot[h] <= tfix) { base += tot[h]; continue; }
+      found = true;  // the draw lies in this group row
+      const int idx0 = (t * (TILE / 8) + h * 64 + lane) * 8;
+      u64 run = base + wave_incl_scan(ls[h]) - ls[h];
+      if (ls[h] > 0ull && run <= tfix && tfix < run + ls[h]) {
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+          const u64 m = col_mass(raw_at(R.r[h], e), (R.hq[h] >> e) & 1u, idx0 + e);
+          if (m > 0ull && run <= tfix && tfix < run + m) { id = idx0 + e; w_id = m; raw_id = raw_at(R.r[h], e); }
+          run += m;
+        }
+      }
+      base += tot[h];
     }
     const u64 bal = __ballot(id >= 0);
     if (bal) {
