@@ -488,6 +488,8 @@ __global__ __launch_bounds__(NTHR, 4) void fast_rows_kernel(const SampleArgs a) 
   for (int u = 0; u < UNR; ++u) Bf[u] = Io<DT>::load(rowp + (size_t)(t0 + 1) * T + u * 64 * EPL + lane * EPL);
   const simple_row_params par = a.params[row];
   if (row == 0 && tid == 0) { a.pend[a.parity ^ 1] = 0u; a.wq[a.parity ^ 1] = 0u; }  // the previous launch's counts
+  // the pattern-count kernel, when it ran before this one, has left NOT_TAKEN on every row that is still to do
+  if (a.pattern_on && a.out[row] != NOT_TAKEN) return;
   uint32_t* samp = reinterpret_cast<uint32_t*>(lds + a.F.samp);
 
   // ---- row configuration (identical in every thread) ----
@@ -510,8 +512,6 @@ __global__ __launch_bounds__(NTHR, 4) void fast_rows_kernel(const SampleArgs a) 
   const bool pen_on = par.rep_penalty != 1.0f || par.freq_penalty != 0.0f || par.pres_penalty != 0.0f;
   const bool lowering = par.rep_penalty >= 1.0f && par.freq_penalty >= 0.0f && par.pres_penalty >= 0.0f;
   const bool h_active = (nnz > 0) && pen_on;
-  // a row of the pattern-count route that the kernel before this one has completed
-  if (a.pattern_on && pattern_route(par, V, nnz, a.max_nnz) && a.out[row] != NOT_TAKEN) return;
   const bool no_trunc = !R.greedy && !R.k_on && !R.p_on && !R.minp_on;
   // Rows that keep no candidate list and only pass through here on their way to the kernels of the
   // whole-vocabulary routes, which apply any penalties column by column: rows without any

@@ -37,7 +37,7 @@ constexpr int SAMPLE_PER_WAVE = 48;   // keys of the threshold sample a wave han
 constexpr int CAPF_PER_THREAD = 12;  // candidate-list entries per thread the single-pass kernel's epilogue holds in registers
 constexpr int KMAXF = 1024;   // largest top-k its list certifies
 constexpr int32_t PENDING = -2;  // id left by the single-pass kernel on rows the general kernel completes
-constexpr int32_t NOT_TAKEN = -3;  // id left by the pattern-count kernel on a row of its route that it hands back to the single-pass kernel
+constexpr int32_t NOT_TAKEN = -3;  // id left by the pattern-count kernel on every row that the single-pass kernel still has to do
 constexpr int PEND_ROWS = 65536; // rows per launch (capacity of the pending-row queue)
 constexpr int WIDE_SLOTS = 4096; // workspace slots of the whole-vocabulary-nucleus kernels; a launch takes no more rows than this,
                                  // so every row of it can be queued for them

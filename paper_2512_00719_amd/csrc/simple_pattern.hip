@@ -27,8 +27,8 @@
 // bin per sign, valued zero: the kernel checks that what this costs in mass stays five orders below
 // the decision tolerance and that no cut falls into such a bin.  A row with a larger magnitude, an
 // infinity or a NaN, or one that fails one of these checks, is left to the single-pass kernel, which
-// runs after this one: the row's id is set to NOT_TAKEN, and the single-pass kernel skips exactly
-// the rows of this route whose id is something else.
+// runs after this one: this kernel leaves NOT_TAKEN as the id of every row it does not complete (the
+// rows that are not of its route among them), and the single-pass kernel skips the others.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
@@ -170,7 +170,10 @@ __global__ __launch_bounds__(PT, 4) void pattern_rows_kernel(const SampleArgs a)
   const simple_row_params par = a.params[row];
   {
     const RowHist rh = row_history(a, row, par.n_prompt);
-    if (!pattern_route(par, V, rh.nnz, a.max_nnz)) return;  // the single-pass kernel takes the row
+    if (!pattern_route(par, V, rh.nnz, a.max_nnz)) {  // the single-pass kernel takes the row
+      if (threadIdx.x == 0) a.out[row] = NOT_TAKEN;
+      return;
+    }
   }
   const uint16_t* rowp = reinterpret_cast<const uint16_t*>(a.logits) + (size_t)row * (size_t)a.stride;
   const uint32_t* hot_bits = a.hot_bits;
