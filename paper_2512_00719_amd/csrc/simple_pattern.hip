@@ -25,8 +25,9 @@
 //
 // Patterns are kept for magnitudes from 2^-14 to 2^8 (2814 per sign).  Smaller magnitudes share one
 // bin per sign, valued zero: the kernel checks that what this costs in mass stays five orders below
-// the decision tolerance and that no cut falls into such a bin.  A row with a larger magnitude, an
-// infinity or a NaN, or one that fails one of these checks, is left to the single-pass kernel, which
+// the decision tolerance and that no cut falls into such a bin.  The last bin holds -inf (masked
+// columns) and anything else at or below -256: columns without mass.  A row with a value of 256 or
+// more, +inf or a NaN, or one that fails one of these checks, is left to the single-pass kernel, which
 // runs after this one: this kernel leaves NOT_TAKEN as the id of every row it does not complete (the
 // rows that are not of its route among them), and the single-pass kernel skips the others.
 #include <hip/hip_runtime.h>
@@ -53,7 +54,7 @@ constexpr int TILE = 64 * 8 * TG;  // columns per tile of the second pass, one w
 constexpr int NTILE = (1 << 18) / TILE;  // V < 2^18
 static_assert(NTILE <= PT, "one tile per thread in the scans over tiles");
 constexpr int UN = 4;          // 16-byte loads in flight per lane, twice (two register sets take turns)
-constexpr uint32_t FILL = 0xC381C381u;  // two patterns (-258.0) whose bin, taken without the upper clamp, is the spare entry NB of the table
+constexpr uint32_t FILL = 0xFF80FF80u;  // two patterns (-inf) of the last bin, whose columns have no mass
 constexpr int CBIT = 58;       // a table entry counts a column of the cut pattern from this bit up
 constexpr u64 MASS_PART = (1ull << CBIT) - 1ull;
 static_assert(TILE / 64 < (1 << (64 - CBIT)), "a lane's columns of one tile fit the count");
@@ -69,15 +70,20 @@ __device__ __forceinline__ int bin_of(uint32_t raw) {
   return (NMAG - 1) - (q ^ s);
 }
 // The same for the two patterns of a 32-bit word at once (packed 16-bit arithmetic), as byte offsets
-// into a table of (1 << SHIFT)-byte entries, low pattern in the low half; pmax gathers the largest magnitudes.
-template <bool CLAMP_HIGH, int SHIFT>
-__device__ __forceinline__ uint32_t bin_offsets2(uint32_t x, s16x2& pmax) {
+// into a table of (1 << SHIFT)-byte entries, low pattern in the low half.  TRACK: smax gathers the
+// largest patterns read as signed numbers (the largest positive value), umax read as unsigned
+// numbers (the negative value of the largest magnitude, if there is a negative one).
+template <bool TRACK, int SHIFT>
+__device__ __forceinline__ uint32_t bin_offsets2(uint32_t x, s16x2& smax, u16x2& umax) {
   const s16x2 xs = __builtin_bit_cast(s16x2, x);
+  if (TRACK) {
+    smax = __builtin_elementwise_max(smax, xs);
+    umax = __builtin_elementwise_max(umax, __builtin_bit_cast(u16x2, x));
+  }
   const s16x2 s = xs >> (short)15;
   const s16x2 p = xs & (short)0x7FFF;
-  if (CLAMP_HIGH) pmax = __builtin_elementwise_max(pmax, p);
   s16x2 q = __builtin_elementwise_max((s16x2)(p - (short)(PLO - 1)), (s16x2)((short)0));
-  if (CLAMP_HIGH) q = __builtin_elementwise_min(q, (s16x2)((short)QMAX));
+  q = __builtin_elementwise_min(q, (s16x2)((short)QMAX));
   const s16x2 d = (short)(NMAG - 1) - (q ^ s);
   return __builtin_bit_cast(uint32_t, (u16x2)(__builtin_bit_cast(u16x2, d) << (unsigned short)SHIFT));
 }
@@ -132,8 +138,8 @@ __device__ __forceinline__ u64 wave_total(u64 v) {
 }
 
 struct PS {  // row-wide state
-  int dtop, dcut, bad, tdraw, id_cut, partial;
-  unsigned pm, pos_m, pos_p, jcut, ccut, tcut, rcut, hot_before, hot_in, merged_n;
+  int dtop, dcut, bad, tdraw, id_cut, partial, pos_max;
+  unsigned neg_max, pos_m, pos_p, jcut, ccut, tcut, rcut, hot_before, hot_in, merged_n;
   u64 mcut, sure_all, mab, m_merged;
 };
 
@@ -159,7 +165,7 @@ __device__ __forceinline__ uint32_t raw_at(const u32x4& r, int e) {
 
 template <bool USE_HOT>
 __global__ __launch_bounds__(PT, 4) void pattern_rows_kernel(const SampleArgs a) {
-  __shared__ __align__(16) u64 tab[NB + 2];   // 32-bit counts (in its first half) in the first pass, then per bin the mass of a surviving column
+  __shared__ __align__(16) u64 tab[NB];   // 32-bit counts (in its first half) in the first pass, then per bin the mass of a surviving column
   __shared__ u64 tall[NTILE], thot[NTILE];  // per tile: mass of the sure survivors, and of the hot ones among them
   __shared__ uint32_t tcc[NTILE];           // per tile: columns of the cut pattern, the hot ones among them from bit 16
   __shared__ PS P;
@@ -196,16 +202,16 @@ __global__ __launch_bounds__(PT, 4) void pattern_rows_kernel(const SampleArgs a)
   };
   fetch(A, 0);
   for (int i = tid; i < NB / 2; i += PT) tab[i] = 0ull;
-  if (tid < 2) tab[NB + tid] = 0ull;  // stays zero: what a group behind the row's end looks up
   if (tid == 0) {
     P.dtop = NB; P.dcut = -1; P.bad = 0; P.tdraw = -1; P.id_cut = -1; P.partial = 0;
-    P.pm = 0u; P.pos_m = 0u; P.pos_p = 0u; P.jcut = 0u; P.ccut = 0u; P.tcut = 0u; P.rcut = 0u; P.hot_before = 0u; P.hot_in = 0u; P.merged_n = 0u;
+    P.pos_max = 0; P.neg_max = 0u; P.pos_m = 0u; P.pos_p = 0u; P.jcut = 0u; P.ccut = 0u; P.tcut = 0u; P.rcut = 0u; P.hot_before = 0u; P.hot_in = 0u; P.merged_n = 0u;
     P.mcut = 0ull; P.sure_all = 0ull; P.mab = 0ull; P.m_merged = 0ull;
   }
   __syncthreads();
-  s16x2 pmax = {0, 0};  // largest magnitude patterns seen by this thread
+  s16x2 smax = {0, 0};  // largest positive patterns seen by this thread
+  u16x2 umax = {0, 0};  // negative patterns of the largest magnitude (any negative one is above every positive one)
   auto count2 = [&](uint32_t x) {
-    const uint32_t off = bin_offsets2<true, 2>(x, pmax);
+    const uint32_t off = bin_offsets2<true, 2>(x, smax, umax);
     __hip_atomic_fetch_add(reinterpret_cast<uint32_t*>(tabb + (off & 0xFFFFu)), 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
     __hip_atomic_fetch_add(reinterpret_cast<uint32_t*>(tabb + (off >> 16)), 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
   };
@@ -220,14 +226,17 @@ __global__ __launch_bounds__(PT, 4) void pattern_rows_kernel(const SampleArgs a)
     fetch(A, g0 + 2 * UN * PT);
     consume(Bq, g0 + UN * PT);
   }
-  uint32_t pm = (uint32_t)max((int)pmax.x, (int)pmax.y);
+  int pos_max = max((int)smax.x, (int)smax.y);
+  uint32_t neg_max = max((uint32_t)umax.x, (uint32_t)umax.y);
   if (tid < V - n_groups * 8) {  // the ragged end of the row
     const uint32_t raw = (uint32_t)*as_global(rowp + n_groups * 8 + tid);
     __hip_atomic_fetch_add(reinterpret_cast<uint32_t*>(tabb + 4 * bin_of(raw)), 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
-    pm = max(pm, raw & 0x7FFFu);
+    pos_max = max(pos_max, (int)(short)raw);
+    neg_max = max(neg_max, raw);
   }
-  pm = wave_max_u32(pm);
-  if (lane == 0) atomicMax(&P.pm, pm);
+  pos_max = (int)wave_max_u32((uint32_t)max(pos_max, 0));
+  neg_max = wave_max_u32(neg_max);
+  if (lane == 0) { atomicMax(&P.pos_max, pos_max); atomicMax(&P.neg_max, neg_max); }
   __syncthreads();
 
   // ---- the cut, from the counts ----
@@ -246,11 +255,17 @@ __global__ __launch_bounds__(PT, 4) void pattern_rows_kernel(const SampleArgs a)
   }
   __syncthreads();
   const int dtop = P.dtop;
-  // a magnitude outside the bins (also: infinities, NaN), or a row maximum inside a merged bin
-  if (P.pm >= (uint32_t)PHI || dtop >= NB || merged_bin(dtop)) { hand_back(); return; }
+  // a positive magnitude outside the bins (also: +inf, NaN), a negative NaN, or a row maximum inside a
+  // merged bin or in the last bin (every column at or below -256)
+  if (P.pos_max >= PHI || P.neg_max > 0xFF80u || dtop >= NB - 1 || merged_bin(dtop)) { hand_back(); return; }
   const float y_max = value_of(raw_of(dtop)) / tau;
   if (!(fabsf(y_max) < INFINITY)) { hand_back(); return; }  // the division overflowed: an error row, reported by the other kernels
   const bool p_on = par.top_p < 1.0f, minp_on = par.min_p > 0.0f;
+  // The last bin holds -inf (masked columns) and whatever else lies at or below -256: its columns
+  // count as survivors where nothing is truncated, with no mass.  That is exact for -inf; for a
+  // finite value it requires that the value's mass rounds to nothing (31 below the maximum in the
+  // exponent) and, with min-p, that no threshold reaches that far down (ln of the smallest float32 is -103.3).
+  if (P.neg_max >= (0x8000u | (uint32_t)PHI) && !((value_of(raw_of(dtop)) + 256.0f) / tau >= (minp_on ? 104.0f : 32.0f))) { hand_back(); return; }
   const float thr_y = minp_on ? y_max + (float)log((double)par.min_p) : -INFINITY;
   u64 mb[BPT];
   u64 msum = 0ull;
@@ -258,7 +273,7 @@ __global__ __launch_bounds__(PT, 4) void pattern_rows_kernel(const SampleArgs a)
 #pragma unroll
   for (int j = 0; j < BPT; ++j) {
     mb[j] = 0ull;
-    if (ca[j]) {
+    if (ca[j] && d_first + j < NB - 1) {
       const float y = value_of(raw_of(d_first + j)) / tau;
       mb[j] = mass_fix44(y, y_max);
       ge_thr |= (y >= thr_y) ? (1u << j) : 0u;
@@ -306,7 +321,7 @@ __global__ __launch_bounds__(PT, 4) void pattern_rows_kernel(const SampleArgs a)
   __syncthreads();
   const int dcut = P.dcut;
   const bool partial = P.partial != 0;
-  if (dcut < 0 || (partial && merged_bin(dcut))) { hand_back(); return; }
+  if (dcut < 0 || (partial && (merged_bin(dcut) || dcut == NB - 1))) { hand_back(); return; }
   const u64 mcut = P.mcut;
   const uint32_t cut_raw = raw_of(dcut);
   // from here on the table holds, per bin, the mass of a surviving column; a cut pattern of which
@@ -329,12 +344,13 @@ __global__ __launch_bounds__(PT, 4) void pattern_rows_kernel(const SampleArgs a)
       if (t + PNW < n_tiles) tile_load<USE_HOT>(N, rowp, hot_bits, t + PNW, lane, n_groups);
       u64 acc = 0ull, acc_h = 0ull;
 #pragma unroll
-      for (int h = 0; h < TG; ++h) {  // (groups behind the row's end hold FILL, whose table entry is zero)
+      for (int h = 0; h < TG; ++h) {  // (groups behind the row's end hold FILL: -inf, no mass)
         const uint32_t w4[4] = {R.r[h].x, R.r[h].y, R.r[h].z, R.r[h].w};
 #pragma unroll
         for (int k = 0; k < 4; ++k) {
-          s16x2 unused = {0, 0};
-          const uint32_t off = bin_offsets2<false, 3>(w4[k], unused);
+          s16x2 unused_s = {0, 0};
+          u16x2 unused_u = {0, 0};
+          const uint32_t off = bin_offsets2<false, 3>(w4[k], unused_s, unused_u);
           const u64 m0 = *reinterpret_cast<const u64*>(tabb + (off & 0xFFFFu));
           const u64 m1 = *reinterpret_cast<const u64*>(tabb + (off >> 16));
           acc += m0 + m1;

@@ -4,8 +4,8 @@ masses from the counts, the drawn id from a second read.  Every case is compared
 oracle row by row, to the bar of test_gpu_parity.py, and the diagnostic flag of the route says which
 rows took it.  Cases: nuclei of every width, min-p, no truncation, temperatures, with and without a
 hot set, a ragged row end behind a padded stride, rows made of a handful of distinct values (the
-cut falls inside a pattern with thousands of tied columns), rows the route must hand back (an
-infinity, a magnitude outside its bins, a row maximum near zero), rows that must not take it
+cut falls inside a pattern with thousands of tied columns), masked (-inf) columns, rows the route must hand back (+inf, NaN, a value
+outside its bins, a row maximum near zero), rows that must not take it
 (top-k, penalties in force, float32)."""
 import numpy as np
 import pytest
@@ -103,8 +103,9 @@ def test_rows_handed_back_and_rows_that_never_take_the_route():
     rng = np.random.default_rng(35)
     B, V = 16, 20_000
     z = _zipf_rows(rng, B, V, s=1.0, sigma=1.0)
-    z[0, 5:400] = -np.inf           # masked columns
-    z[1, 77] = 300.0                # a magnitude outside the bins
+    z[0, 5:400] = -np.inf           # masked columns: taken, they have no mass
+    z[0, 1000:1100] = -300.0        # ... as have values this far down
+    z[1, 77] = 300.0                # a value outside the bins
     z[2] = rng.standard_normal(V) * 1e-6   # row maximum near zero
     z[3] = 0.0                      # all columns equal
     z[4, 9] = np.inf                # an error row
@@ -125,8 +126,8 @@ def test_rows_handed_back_and_rows_that_never_take_the_route():
     for ids, dg, s in _run(w, steps=(0, 1)):
         f = dg["flags"]
         took = (f & PATTERN) > 0
-        assert not took[[0, 1, 2, 3, 4, 5, 8, 9, 10, 11]].any(), took
-        assert took[[6, 7, 12, 13, 14, 15]].all(), took
+        assert not took[[1, 2, 3, 4, 5, 8, 9, 10, 11]].any(), took
+        assert took[[0, 6, 7, 12, 13, 14, 15]].all(), took
         assert ids[4] == -1 and ids[5] == -1 and (ids[[0, 1, 2, 3]] >= 0).all()
     # float32 calls never take it
     w32 = synth.Workload("pattern-f32", B, V, "f32", zf.copy(), params, hist_ptr, hist_ids)
@@ -163,4 +164,81 @@ def test_decision_outputs_and_aggregate_on_the_route():
     assert np.array_equal(eos.cpu().numpy() == 1, ids == eos_id)
     st = stats.cpu().numpy().view(binding.STATS_DTYPE)[0]
     assert int(st["rows"]) == B and int(st["second_pass_rows"]) == B and int(st["general_rows"]) == 0
+    ctx.close()
+
+
+def test_masked_columns_have_no_mass_but_count_where_nothing_is_truncated():
+    """Rows in which a third of the columns is -inf (an allow-list, a padded vocabulary): the route
+    takes them; without truncation |K_b| still counts every column, as the oracle does."""
+    rng = np.random.default_rng(37)
+    B, V = 8, 24_000 + 8
+    z = _zipf_rows(rng, B, V, s=1.0, sigma=1.5)
+    z[:, rng.random(V) < 0.33] = -np.inf
+    z[:, V - 40:] = -np.inf                    # a padded end
+    bits, zf = _bf16(z)
+    bits[7, 123] = 0xFFC0                      # a NaN with the sign bit set: an error row
+    params = synth.make_params(B, temperature=[1.0, 0.7, 1.4, 1.0] * 2, top_p=[0.9, 1.0, 1.0, 0.99] * 2,
+                               min_p=[0.0, 0.0, 0.05, 1e-30] * 2)
+    hot_ids = np.sort(rng.choice(V, 3000, replace=False)).astype(np.int32)
+    w = synth.Workload("pattern-masked", B, V, "bf16", bits, params, np.zeros(B + 1, np.int64), np.zeros(0, np.int32), hot_ids=hot_ids)
+    for ids, dg, s in _run(w, steps=(0, 1, 2)):
+        took = (dg["flags"] & PATTERN) > 0
+        assert took[:7].all() and not took[7], took
+        assert ids[7] == -1 and (dg["flags"][7] & binding.DIAG_BAD_LOGIT)
+        assert dg["n_survivors"][1] == V and dg["n_survivors"][5] == V
+
+
+def test_more_rows_than_one_launch_and_a_row_offset():
+    """4200 rows go out in two launches; the Philox counter of a row is its index plus row_offset."""
+    rng = np.random.default_rng(38)
+    B, V = 4200, 16_384 + 8
+    bits, zf = _bf16(rng.standard_normal((B, V)).astype(np.float32) * 2.0 + 3.0)
+    params = synth.make_params(B, temperature=1.0, top_p=0.9)
+    params["top_p"][::3] = 1.0
+    params["min_p"][1::5] = 0.01
+    w = synth.Workload("pattern-many", B, V, "bf16", bits, params, np.zeros(B + 1, np.int64), np.zeros(0, np.int32))
+    ids, dg = P.run_gpu(w, 2, row_offset=(1 << 32) - 100)
+    rows = list(range(0, B, 7)) + list(range(4090, 4110))
+    P.compare(ids, dg, P.run_oracle(w, 2, rows=rows, row_offset=(1 << 32) - 100), rows)
+    assert ((dg["flags"] & PATTERN) > 0).all() and ids.min() >= 0
+
+
+def test_state_and_static_entry_points_take_the_route():
+    """A row whose sequence has tokens but no penalty in force is a row of the route, also through
+    simple_sample_state; simple_sample_static returns the ids of simple_sample."""
+    import torch
+    rng = np.random.default_rng(39)
+    B, V, L = 12, 20_000, 64
+    bits, zf = _bf16(_zipf_rows(rng, B, V))
+    params = synth.make_params(B, temperature=[1.0, 0.8, 1.3] * 4, top_p=[0.9, 0.95, 1.0, 0.7] * 3)
+    w = synth.Workload("pattern-state", B, V, "bf16", bits, params, np.zeros(B + 1, np.int64), np.zeros(0, np.int32))
+    dev = P.to_device(w)
+    want = P.run_oracle(w, 5)
+    ctx = binding.Sampler(V, L, max_B=B)
+    st = binding.simple_state_create(0, B, V, L)
+    stream = torch.cuda.current_stream().cuda_stream
+    lens = rng.integers(1, 40, B)
+    ptr = np.concatenate([[0], np.cumsum(lens)]).astype(np.int64)
+    toks = rng.integers(0, V, int(ptr[-1])).astype(np.int32)
+    p_d, t_d = torch.from_numpy(ptr).cuda(), torch.from_numpy(toks).cuda()
+    assert binding.simple_state_restart(st, 0, B, p_d.data_ptr(), t_d.data_ptr(), 0, stream) == 0
+    out = torch.full((B,), -9, dtype=torch.int32, device="cuda:0")
+    diag = torch.zeros(B * 32, dtype=torch.uint8, device="cuda:0")
+    lg = dev["logits"]
+    rc = binding.simple_sample_state(ctx.ctx, st, 0, lg.data_ptr(), B, V, binding.SIMPLE_BF16, lg.stride(0), dev["params"].data_ptr(),
+                                     0, 0, w.seed, 5, 0, out.data_ptr(), diag.data_ptr(), stream)
+    assert rc == 0, binding.simple_strerror(rc)
+    torch.cuda.synchronize()
+    ids, dg = out.cpu().numpy(), diag.cpu().numpy().view(binding.ROW_DIAG_DTYPE)
+    P.compare(ids, dg, want, range(B))
+    assert ((dg["flags"] & PATTERN) > 0).all()
+    out2 = torch.full((B,), -9, dtype=torch.int32, device="cuda:0")
+    diag2 = torch.zeros(B * 32, dtype=torch.uint8, device="cuda:0")
+    rc = binding.simple_sample_static(lg.data_ptr(), B, V, binding.SIMPLE_BF16, lg.stride(0), dev["params"].data_ptr(), 0, 0, 0, 0,
+                                      w.seed, 5, 0, out2.data_ptr(), diag2.data_ptr(), stream)
+    assert rc == 0, binding.simple_strerror(rc)
+    torch.cuda.synchronize()
+    assert np.array_equal(out2.cpu().numpy(), ids)
+    assert ((diag2.cpu().numpy().view(binding.ROW_DIAG_DTYPE)["flags"] & PATTERN) > 0).all()
+    binding.simple_state_destroy(st)
     ctx.close()
