@@ -478,6 +478,11 @@ __global__ __launch_bounds__(NTHR, 4) void fast_rows_kernel(const SampleArgs a) 
   const int row = blockIdx.x;
   const int V = a.V;
   const DT* rowp = reinterpret_cast<const DT*>(a.logits) + (size_t)row * (size_t)a.stride;
+  // the pattern-count kernel, when it ran before this one, has left NOT_TAKEN on every row that is still to do
+  if (a.pattern_on && a.out[row] != NOT_TAKEN) {
+    if (row == 0 && tid == 0) { a.pend[a.parity ^ 1] = 0u; a.wq[a.parity ^ 1] = 0u; }  // the previous launch's counts
+    return;
+  }
   // this wave's first two tiles (its threshold sample): issued before anything else
   const int nfull = V / T;  // the host guarantees nfull >= 2 * NWV
   const int t0 = (int)(((long long)wave * nfull) / NWV);
@@ -488,8 +493,6 @@ __global__ __launch_bounds__(NTHR, 4) void fast_rows_kernel(const SampleArgs a) 
   for (int u = 0; u < UNR; ++u) Bf[u] = Io<DT>::load(rowp + (size_t)(t0 + 1) * T + u * 64 * EPL + lane * EPL);
   const simple_row_params par = a.params[row];
   if (row == 0 && tid == 0) { a.pend[a.parity ^ 1] = 0u; a.wq[a.parity ^ 1] = 0u; }  // the previous launch's counts
-  // the pattern-count kernel, when it ran before this one, has left NOT_TAKEN on every row that is still to do
-  if (a.pattern_on && a.out[row] != NOT_TAKEN) return;
   uint32_t* samp = reinterpret_cast<uint32_t*>(lds + a.F.samp);
 
   // ---- row configuration (identical in every thread) ----

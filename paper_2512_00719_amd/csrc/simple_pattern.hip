@@ -5,8 +5,8 @@
 // A bfloat16 logit has 16 bits, and under one temperature everything the filter and the softmax
 // need of a column (its tempered value, its place in the order "value descending", its mass) is a
 // function of that bit pattern.  One read of the row therefore only counts columns per pattern (an
-// LDS integer atomic each); the order statistics then
-// come from the counts, in the order the oracle-style definition walks them:
+// LDS integer atomic each); every order statistic then comes from the counts, exactly as it would
+// from the sorted row:
 //
 //   counts    one pass over the row: hist[pattern] += 1;
 //   cut       per occupied pattern one exponential gives the exact (2^44 fixed-point) mass of one of
@@ -197,7 +197,7 @@ __global__ __launch_bounds__(PT, 4) void pattern_rows_kernel(const SampleArgs a)
     for (int u = 0; u < UN; ++u) {
       const int g = g0 + u * PT + tid;
       R[u] = u32x4{0u, 0u, 0u, 0u};
-      if (g < n_groups) R[u] = __builtin_nontemporal_load(as_global(rp + g));
+      if (g < n_groups) R[u] = *as_global(rp + g);
     }
   };
   fetch(A, 0);
