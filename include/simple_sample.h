@@ -190,6 +190,11 @@ int simple_set_decision_outputs(simple_ctx* ctx, float* logprobs_dev, uint8_t* e
  *  diag_dev          [B] simple_row_diag, or NULL
  *  hip_stream        hipStream_t (NULL = the default stream)
  *
+ * Which kernel completes a row depends on its controls and on the call (dtype, alignment, V); the
+ * id does not, beyond the rounding of masses near a decision boundary, and is the same for the
+ * same call repeated.  Rows of a bfloat16 call without top-k and without a penalty in force are
+ * sampled from counts per bit pattern (SIMPLE_DIAG_PATTERN in the row's record).
+ *
  * B = 0 is a no-op that returns SIMPLE_OK.  Returns SIMPLE_EINVAL for NULL required pointers,
  * B < 0, V <= 0, row_stride_elems < V, an unknown dtype, H < -1, H > V, H = -1 without an
  * installed set of that V, or hist_ptr_dev given without hist_ids_dev; SIMPLE_ECAPACITY for
