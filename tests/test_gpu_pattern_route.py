@@ -242,3 +242,52 @@ def test_state_and_static_entry_points_take_the_route():
     assert ((diag2.cpu().numpy().view(binding.ROW_DIAG_DTYPE)["flags"] & PATTERN) > 0).all()
     binding.simple_state_destroy(st)
     ctx.close()
+
+
+def test_seeded_random_rows():
+    """Sixty seeded random cases: batch, vocabulary size (ragged ends behind padded strides), value
+    distribution (normal, Zipf profile, coarse grids with thousands of ties, sparse spikes, tiny and
+    large ranges), masked columns, out-of-range values, temperatures, top-p, min-p, a stray top-k
+    row, hot sets of any size; every row against the oracle."""
+    import torch
+    tot = {"rows": 0, "ambiguous": 0, "soft": 0, "pattern": 0}
+    for case in range(60):
+        rng = np.random.default_rng(7000 + case)
+        B = int(rng.integers(1, 16))
+        V = int(rng.integers(2100, 12000)) * 8 + (int(rng.integers(1, 8)) if rng.random() < 0.3 else 0)
+        stride = (V + 7) // 8 * 8 + 8 * int(rng.integers(0, 3))
+        kind = int(rng.integers(0, 5))
+        if kind == 0:
+            z = rng.standard_normal((B, V)) * rng.uniform(0.5, 4.0)
+        elif kind == 1:
+            z = _zipf_rows(rng, B, V, s=rng.uniform(0.7, 1.5), sigma=rng.uniform(0.3, 2.0)) - 12.0 + rng.uniform(0, 25)
+        elif kind == 2:
+            z = np.round(rng.standard_normal((B, V)) * rng.uniform(1, 3)) * rng.choice([0.25, 0.5, 1.0]) + rng.uniform(-3, 8)
+        elif kind == 3:
+            z = rng.standard_normal((B, V)) * 2 + np.where(rng.random((B, V)) < 0.001, rng.uniform(5, 20), 0)
+        else:
+            z = rng.uniform(-1, 1, (B, V)) * rng.choice([1e-3, 0.1, 10, 100])
+        if rng.random() < 0.3:
+            z[:, rng.random(V) < rng.uniform(0.01, 0.9)] = -np.inf
+        if rng.random() < 0.1:
+            z[rng.integers(0, B), rng.integers(0, V)] = rng.choice([300.0, -300.0, 255.0])
+        bits, _ = _bf16(z)
+        params = synth.make_params(B, temperature=rng.uniform(0.3, 2.0, B).astype(np.float32),
+                                   top_p=np.where(rng.random(B) < 0.25, 1.0, rng.uniform(0.05, 1.0, B)).astype(np.float32),
+                                   min_p=np.where(rng.random(B) < 0.6, 0.0, 10 ** rng.uniform(-6, -0.5, B)).astype(np.float32))
+        if rng.random() < 0.2:
+            params["top_k"][rng.integers(0, B)] = int(rng.integers(1, 200))
+        hot = np.sort(rng.choice(V, int(rng.integers(1, V // 2)), replace=False)).astype(np.int32) if rng.random() < 0.6 else None
+        w = synth.Workload(f"random{case}", B, V, "bf16", bits, params, np.zeros(B + 1, np.int64), np.zeros(0, np.int32),
+                           hot_ids=hot, seed=int(rng.integers(1, 1 << 40)))
+        padded = np.full((B, stride), 0x7FC0, np.uint16)  # NaN in the padding: it must never be read as a logit
+        padded[:, :V] = bits
+        dev = P.to_device(w)
+        dev["logits"] = torch.from_numpy(padded.view(np.int16)).cuda().view(torch.bfloat16)
+        step = int(rng.integers(0, 1 << 20))
+        ids, dg = P.run_gpu(w, step, dev=dev)
+        s = P.compare(ids, dg, P.run_oracle(w, step), range(B), max_mismatch_frac=0.2)
+        tot["rows"] += s["rows"]; tot["ambiguous"] += s["ambiguous"]; tot["soft"] += s["soft_mismatch"]
+        tot["pattern"] += int(((dg["flags"] & PATTERN) > 0).sum())
+    print("random rows:", tot, flush=True)
+    assert tot["pattern"] > 0.8 * tot["rows"] and tot["soft"] <= 2
