@@ -37,26 +37,62 @@ constexpr uint32_t KEY_NEG_INF = 0x007FFFFFu;
 constexpr uint32_t KEY_POS_INF = 0xFF800000u;
 
 // ---------------------------------------------------------------- wave / block collectives ----
-template <typename T>
-__device__ __forceinline__ T wave_incl_scan(T v) {
-  const int l = lane_id();
-#pragma unroll
-  for (int o = 1; o < 64; o <<= 1) {
-    T t = __shfl_up(v, o, 64);
-    if (l >= o) v += t;
+// Built on the data-parallel primitives (a lane reads another lane's register inside the vector
+// unit: no trip through the LDS pipe, which a shuffle would take and wait for).  All 64 lanes of the
+// wave must be active.
+// A value moved between lanes: CTRL selects the pattern; lanes of rows outside ROW_MASK, and lanes
+// whose source lies outside the row, keep `old`.
+template <int CTRL, int ROW_MASK, typename T>
+__device__ __forceinline__ T dpp_move(T old, T v) {
+  static_assert(sizeof(T) == 4 || sizeof(T) == 8, "32- or 64-bit values");
+  if constexpr (sizeof(T) == 4) {
+    const int r = __builtin_amdgcn_update_dpp(__builtin_bit_cast(int, old), __builtin_bit_cast(int, v), CTRL, ROW_MASK, 0xF, false);
+    return __builtin_bit_cast(T, r);
+  } else {
+    const unsigned long long o = __builtin_bit_cast(unsigned long long, old), x = __builtin_bit_cast(unsigned long long, v);
+    const unsigned lo = (unsigned)__builtin_amdgcn_update_dpp((int)(unsigned)o, (int)(unsigned)x, CTRL, ROW_MASK, 0xF, false);
+    const unsigned hi = (unsigned)__builtin_amdgcn_update_dpp((int)(unsigned)(o >> 32), (int)(unsigned)(x >> 32), CTRL, ROW_MASK, 0xF, false);
+    return __builtin_bit_cast(T, ((unsigned long long)hi << 32) | (unsigned long long)lo);
   }
+}
+template <typename T>
+__device__ __forceinline__ T read_lane(T v, int lane) {  // `lane` must be the same in every lane
+  if constexpr (sizeof(T) == 4) return __builtin_bit_cast(T, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), lane));
+  else {
+    const unsigned long long x = __builtin_bit_cast(unsigned long long, v);
+    const unsigned lo = (unsigned)__builtin_amdgcn_readlane((int)(unsigned)x, lane), hi = (unsigned)__builtin_amdgcn_readlane((int)(unsigned)(x >> 32), lane);
+    return __builtin_bit_cast(T, ((unsigned long long)hi << 32) | (unsigned long long)lo);
+  }
+}
+constexpr int DPP_XOR1 = 0xB1, DPP_XOR2 = 0x4E, DPP_HALF_MIRROR = 0x141, DPP_MIRROR = 0x140;  // partners inside a row of 16 lanes
+constexpr int DPP_BCAST15 = 0x142, DPP_BCAST31 = 0x143;  // last lane of a row (of the first two rows) to the next row (the last two)
+template <int N> constexpr int dpp_row_shr() { return 0x110 + N; }
+// f over all 64 lanes, the same in every lane: a butterfly inside each row of 16, then the four rows.
+template <typename T, typename F>
+__device__ __forceinline__ T wave_all(T v, F&& f) {
+  v = f(v, dpp_move<DPP_XOR1, 0xF>(v, v));
+  v = f(v, dpp_move<DPP_XOR2, 0xF>(v, v));
+  v = f(v, dpp_move<DPP_HALF_MIRROR, 0xF>(v, v));
+  v = f(v, dpp_move<DPP_MIRROR, 0xF>(v, v));
+  return f(f(read_lane(v, 0), read_lane(v, 16)), f(read_lane(v, 32), read_lane(v, 48)));
+}
+template <typename T>
+__device__ __forceinline__ T wave_incl_scan(T v) {  // sums of lanes 0 .. l
+  const T zero = T(0);
+  v += dpp_move<dpp_row_shr<1>(), 0xF>(zero, v);
+  v += dpp_move<dpp_row_shr<2>(), 0xF>(zero, v);
+  v += dpp_move<dpp_row_shr<4>(), 0xF>(zero, v);
+  v += dpp_move<dpp_row_shr<8>(), 0xF>(zero, v);
+  v += dpp_move<DPP_BCAST15, 0xA>(zero, v);
+  v += dpp_move<DPP_BCAST31, 0xC>(zero, v);
   return v;
 }
 template <typename T>
 __device__ __forceinline__ T wave_sum(T v) {
-#pragma unroll
-  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
-  return v;
+  return wave_all(v, [](T a, T b) { return a + b; });
 }
 __device__ __forceinline__ float wave_max(float v) {
-#pragma unroll
-  for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
-  return v;
+  return wave_all(v, [](float a, float b) { return fmaxf(a, b); });
 }
 
 // Block-wide inclusive scan; `ws` is LDS scratch of NW+1 elements.  All threads must call.

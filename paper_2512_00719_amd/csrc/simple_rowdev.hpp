@@ -102,8 +102,7 @@ struct RowCfg {
 template <int NWV>
 __device__ inline void blk_reduce(FS& S, unsigned& a, unsigned& b, u64& cmax, u64& d) {
   a = wave_sum(a); b = wave_sum(b); d = wave_sum(d);
-#pragma unroll
-  for (int o = 32; o > 0; o >>= 1) { const u64 t = __shfl_xor(cmax, o, 64); cmax = (t > cmax) ? t : cmax; }
+  cmax = wave_all(cmax, [](u64 x, u64 y) { return x > y ? x : y; });
   __syncthreads();
   if (lane_id() == 0) { const int w = wave_id(); S.r32a[w] = a; S.r32b[w] = b; S.r64a[w] = cmax; S.r64b[w] = d; }
   __syncthreads();
@@ -136,16 +135,8 @@ __device__ inline void blk_excl_scan2(FS& S, unsigned c, u64 m, unsigned& ce, u6
   ce = cb + ci - c; me = mb + mi - m; ct = ctt; mt = mtt;
 }
 
-__device__ __forceinline__ uint32_t wave_max_u32(uint32_t v) {
-#pragma unroll
-  for (int o = 32; o > 0; o >>= 1) v = max(v, (uint32_t)__shfl_xor((int)v, o, 64));
-  return v;
-}
-__device__ __forceinline__ uint32_t wave_min_u32(uint32_t v) {
-#pragma unroll
-  for (int o = 32; o > 0; o >>= 1) v = min(v, (uint32_t)__shfl_xor((int)v, o, 64));
-  return v;
-}
+__device__ __forceinline__ uint32_t wave_max_u32(uint32_t v) { return wave_all(v, [](uint32_t x, uint32_t y) { return max(x, y); }); }
+__device__ __forceinline__ uint32_t wave_min_u32(uint32_t v) { return wave_all(v, [](uint32_t x, uint32_t y) { return min(x, y); }); }
 
 // All-pairs helpers over small LDS tables: eight entries are loaded before they are used, so the
 // reads overlap instead of each waiting out the LDS latency.
