@@ -175,7 +175,7 @@ __device__ __forceinline__ int finalize_small(FS& S, const RowCfg& R, unsigned n
         loc += wl[j];
       }
       const u64 incl = wave_incl_scan(loc);
-      const u64 total_m = __shfl(incl, 63, 64);
+      const u64 total_m = read_lane(incl, 63);
       u64 run = incl - loc;
 #pragma unroll
       for (int j = 0; j < 8; ++j) { run += wl[j]; cum[j] = run; }

@@ -117,25 +117,9 @@ __device__ __forceinline__ u64 mass_fix44(float y, float y_max) {
   return (u64)__double2ull_rn(ldexp(p, (int)n + 44));
 }
 
-// Sums over the 16 lanes of a row of the wave (data-parallel primitives: no LDS, no waiting), then
-// over its four rows; the result is the same in every lane.
-template <int CTRL>
-__device__ __forceinline__ uint32_t dpp(uint32_t v) { return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, CTRL, 0xF, 0xF, true); }
-template <int CTRL>
-__device__ __forceinline__ u64 dpp64(u64 v) { return ((u64)dpp<CTRL>((uint32_t)(v >> 32)) << 32) | (u64)dpp<CTRL>((uint32_t)v); }
-__device__ __forceinline__ uint32_t wave_total(uint32_t v) {
-  v += dpp<0xB1>(v); v += dpp<0x4E>(v); v += dpp<0x141>(v); v += dpp<0x140>(v);  // lanes ^1, ^2, mirrored in 8, mirrored in 16
-  return (uint32_t)(__builtin_amdgcn_readlane((int)v, 0) + __builtin_amdgcn_readlane((int)v, 16) + __builtin_amdgcn_readlane((int)v, 32) +
-                    __builtin_amdgcn_readlane((int)v, 48));
-}
-__device__ __forceinline__ u64 wave_total(u64 v) {
-  v += dpp64<0xB1>(v); v += dpp64<0x4E>(v); v += dpp64<0x141>(v); v += dpp64<0x140>(v);
-  u64 t = 0ull;
-#pragma unroll
-  for (int r = 0; r < 64; r += 16)
-    t += ((u64)(uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)(v >> 32), r) << 32) | (u64)(uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)v, r);
-  return t;
-}
+// Sum over the wave, the same in every lane (data-parallel primitives: no LDS, no waiting).
+template <typename T>
+__device__ __forceinline__ T wave_total(T v) { return wave_sum(v); }
 
 struct PS {  // row-wide state
   int dtop, dcut, bad, tdraw, id_cut, partial, pos_max;

@@ -882,11 +882,8 @@ __device__ inline bool finish_row(const SampleArgs& a, const WideRow& W, FS& S, 
         cmax_t = (c > cmax_t) ? c : cmax_t; cmin_t = (c < cmin_t) ? c : cmin_t;
       }
     }
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) {
-      const u64 hi = __shfl_xor(cmax_t, o, 64), lo = __shfl_xor(cmin_t, o, 64);
-      cmax_t = (hi > cmax_t) ? hi : cmax_t; cmin_t = (lo < cmin_t) ? lo : cmin_t;
-    }
+    cmax_t = wave_all(cmax_t, [](u64 x, u64 y) { return x > y ? x : y; });
+    cmin_t = wave_all(cmin_t, [](u64 x, u64 y) { return x < y ? x : y; });
     if ((tid & 63) == 0) { atomicMax(&S.cut_k, cmax_t); atomicMin(&S.cut_p, cmin_t); }
   }
   __syncthreads();
