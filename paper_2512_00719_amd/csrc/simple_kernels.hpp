@@ -135,12 +135,13 @@ __device__ __forceinline__ RowHist row_history(const SampleArgs& a, int row, int
   return a.st_rec ? row_history_state(a, row, par_n_prompt) : row_history_csr(a, row, par_n_prompt);
 }
 
-// Rows of the pattern-count route (bfloat16 calls only): survivors are a prefix of the whole vocabulary
-// (no top-k; top-p, min-p or no truncation), no penalty is in force, and the parameters are valid.
+// Rows of the pattern-count route (bfloat16 calls only): survivors are a long prefix of the vocabulary
+// (top-p, min-p or no truncation without top-k, or a top-k above what the single-pass kernel's list
+// certifies), no penalty is in force, and the parameters are valid.
 __device__ __forceinline__ bool pattern_route(const simple_row_params& par, int V, int nnz, int max_nnz) {
   const bool pen_on = par.rep_penalty != 1.0f || par.freq_penalty != 0.0f || par.pres_penalty != 0.0f;
-  const bool k_on = par.top_k >= 1 && par.top_k < V;
-  return par.temperature > 0.0f && par.temperature < INFINITY && par.rep_penalty > 0.0f && !k_on && par.top_p > 0.0f &&
+  const bool small_k = par.top_k >= 1 && par.top_k < V && par.top_k <= KMAXF;
+  return par.temperature > 0.0f && par.temperature < INFINITY && par.rep_penalty > 0.0f && !small_k && par.top_p > 0.0f &&
          !(nnz > 0 && pen_on) && nnz <= max_nnz;
 }
 

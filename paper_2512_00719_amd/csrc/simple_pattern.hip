@@ -1,6 +1,6 @@
-// bfloat16 rows whose survivors are a prefix of the whole vocabulary (top-p and / or min-p without
-// top-k, or no truncation: section 2.1 Eq. (2)) and that carry no penalties: the row is reduced to a
-// count per distinct value.
+// bfloat16 rows whose survivors are a long prefix of the vocabulary (top-p and / or min-p without
+// top-k, no truncation, or a top-k beyond what the single-pass kernel's candidate list certifies:
+// section 2.1 Eq. (2)) and that carry no penalties: the row is reduced to a count per distinct value.
 //
 // A bfloat16 logit has 16 bits, and under one temperature everything the filter and the softmax
 // need of a column (its tempered value, its place in the order "value descending", its mass) is a
@@ -124,7 +124,7 @@ __device__ __forceinline__ T wave_total(T v) { return wave_sum(v); }
 struct PS {  // row-wide state
   int dtop, dcut, bad, tdraw, id_cut, partial, pos_max;
   unsigned neg_max, pos_m, pos_p, jcut, ccut, tcut, rcut, hot_before, hot_in, merged_n;
-  u64 mcut, sure_all, mab, m_merged;
+  u64 mcut, sure_all, mab, m_merged, s_k;
 };
 
 // The 16-byte groups of a tile that a lane holds (group g < n_groups), and the hot bits of their columns.
@@ -189,7 +189,7 @@ __global__ __launch_bounds__(PT, 4) void pattern_rows_kernel(const SampleArgs a)
   if (tid == 0) {
     P.dtop = NB; P.dcut = -1; P.bad = 0; P.tdraw = -1; P.id_cut = -1; P.partial = 0;
     P.pos_max = 0; P.neg_max = 0u; P.pos_m = 0u; P.pos_p = 0u; P.jcut = 0u; P.ccut = 0u; P.tcut = 0u; P.rcut = 0u; P.hot_before = 0u; P.hot_in = 0u; P.merged_n = 0u;
-    P.mcut = 0ull; P.sure_all = 0ull; P.mab = 0ull; P.m_merged = 0ull;
+    P.mcut = 0ull; P.sure_all = 0ull; P.mab = 0ull; P.m_merged = 0ull; P.s_k = 0ull;
   }
   __syncthreads();
   s16x2 smax = {0, 0};  // largest positive patterns seen by this thread
@@ -267,7 +267,20 @@ __global__ __launch_bounds__(PT, 4) void pattern_rows_kernel(const SampleArgs a)
   }
   unsigned ce, ct; u64 me, s_tot;
   blk_excl_scan2<PNW>(S, csum, msum, ce, me, ct, s_tot);  // barriers inside
-  const u64 target = p_on ? (u64)__double2ull_ru((double)par.top_p * (double)s_tot) : 0ull;
+  // top-k (only above what the single-pass kernel's list certifies): exactly k columns, and S_k, the mass of that prefix
+  const bool k_on = par.top_k >= 1 && par.top_k < V;
+  u64 s_k = s_tot;
+  if (k_on) {
+    unsigned cb = ce; u64 mbef = me;
+#pragma unroll
+    for (int j = 0; j < BPT; ++j) {
+      if (ca[j] && cb < (unsigned)par.top_k && (unsigned)par.top_k <= cb + ca[j]) P.s_k = mbef + (u64)((unsigned)par.top_k - cb) * mb[j];
+      cb += ca[j]; mbef += (u64)ca[j] * mb[j];
+    }
+    __syncthreads();
+    s_k = P.s_k;
+  }
+  const u64 target = p_on ? (u64)__double2ull_ru((double)par.top_p * (double)s_k) : 0ull;
   {
     unsigned cb = ce; u64 mbef = me;
     unsigned pos_m = 0u;
@@ -285,11 +298,11 @@ __global__ __launch_bounds__(PT, 4) void pattern_rows_kernel(const SampleArgs a)
   if (P.merged_n) {
     const double err = (double)P.merged_n * (double)P.m_merged * (6.2e-5 / (double)tau);
     const bool near_thr = minp_on && fabsf(thr_y) * tau <= 1.3e-4f;
-    if (err > (double)s_tot * 0x1p-24 || near_thr) { hand_back(); return; }
+    if (err > (double)s_k * 0x1p-24 || near_thr) { hand_back(); return; }
   }
-  unsigned n = (unsigned)V;
+  unsigned n = k_on ? (unsigned)par.top_k : (unsigned)V;
   if (minp_on) n = min(n, P.pos_m);
-  if (p_on) n = min(n, P.pos_p ? P.pos_p : (unsigned)V);
+  if (p_on && P.pos_p) n = min(n, P.pos_p);
   n = max(n, 1u);
   {
     unsigned cb = ce; u64 mbef = me;
@@ -539,7 +552,7 @@ __global__ __launch_bounds__(PT, 4) void pattern_rows_kernel(const SampleArgs a)
         if (merged_bin(bin_of(raw_id))) w_id = mass_fix44(value_of(raw_id) / tau, y_max);
         simple_row_diag dg;
         dg.alpha = USE_HOT ? (double)S_H / (double)S_K : __longlong_as_double(0x7FF8000000000000ll);
-        dg.s_k = (double)s_tot / WSCALE;
+        dg.s_k = (double)s_k / WSCALE;
         dg.p_chosen = (float)((double)w_id / (double)S_K);
         dg.n_survivors = (int)n;
         dg.reserved = 0u;

@@ -291,3 +291,23 @@ def test_seeded_random_rows():
         tot["pattern"] += int(((dg["flags"] & PATTERN) > 0).sum())
     print("random rows:", tot, flush=True)
     assert tot["pattern"] > 0.8 * tot["rows"] and tot["soft"] <= 2
+
+
+@pytest.mark.parametrize("ties", [False, True])
+def test_top_k_beyond_what_the_candidate_list_certifies(ties):
+    """top-k above 1024 (alone, with top-p scaled by the mass of the top-k prefix, with min-p): exactly
+    k columns survive, the last of them the first few of their pattern in ascending id."""
+    rng = np.random.default_rng(41 + ties)
+    B, V = 12, 40_000
+    if ties:
+        z = np.round(rng.standard_normal((B, V)) * 2.5) * 0.5 + 2.25  # (no exact zeros: thousands of them would send the row back)
+    else:
+        z = _zipf_rows(rng, B, V, s=0.9, sigma=1.5)
+    bits, zf = _bf16(z)
+    params = synth.make_params(B, temperature=[1.0, 0.8, 1.5] * 4, top_k=[1025, 3000, 20000, 39999] * 3,
+                               top_p=[1.0, 0.9, 0.99, 1.0, 0.5, 1.0] * 2, min_p=[0.0, 0.0, 1e-3, 0.0] * 3)
+    hot_ids = np.sort(rng.choice(V, 5000, replace=False)).astype(np.int32)
+    w = synth.Workload("pattern-topk", B, V, "bf16", bits, params, np.zeros(B + 1, np.int64), np.zeros(0, np.int32), hot_ids=hot_ids)
+    for ids, dg, s in _run(w, steps=(0, 1, 2)):
+        assert ((dg["flags"] & PATTERN) > 0).all() and not (dg["flags"] & GENERAL).any()
+    assert (dg["n_survivors"][[0, 3]] == [1025, 39999]).all()  # top-k alone keeps exactly k
