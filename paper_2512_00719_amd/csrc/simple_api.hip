@@ -359,7 +359,7 @@ static int sample_impl(simple_ctx* ctx, const simple_state* state, const int32_t
   a.F = simple::make_fast_layout(V, dtype, with_hist ? ctx->max_nnz : 0, with_hist, vec, ctx->lds_limit,
                                  B < per_launch ? B : per_launch, ctx->n_cu);
   a.gated = (a.F.total != 0u || tail) ? 1 : 0;
-  a.pattern_on = (a.F.total != 0u && !tail && dtype == SIMPLE_BF16 && V < ((int64_t)1 << 18)) ? 1 : 0;
+  a.pattern_on = (dtype == SIMPLE_BF16 && V < ((int64_t)1 << 18)) ? (tail ? 2 : (a.F.total != 0u ? 1 : 0)) : 0;
   for (int64_t b0 = 0; b0 < B; b0 += per_launch) {
     const int64_t nb = (B - b0 < per_launch) ? (B - b0) : per_launch;
     a.B = (int)nb;
@@ -379,6 +379,7 @@ static int sample_impl(simple_ctx* ctx, const simple_state* state, const int32_t
     if (ctx->prof_ev && ctx->prof_n < PROF_MAX) { ev0 = ctx->prof_ev[2 * ctx->prof_n]; ev1 = ctx->prof_ev[2 * ctx->prof_n + 1]; ++ctx->prof_n; }
     if (tail) {  // the hot-first kernel, then the general kernel on the rows it left
       if (ev0 && hipEventRecord(ev0, st) != hipSuccess) return SIMPLE_EDEVICE;
+      if (a.pattern_on && simple::launch_pattern(a, st) != hipSuccess) return SIMPLE_EDEVICE;  // truncated bfloat16 rows
       if (simple::launch_hot_first(a, dtype, (int)H, tail + b0, st) != hipSuccess) return SIMPLE_EDEVICE;
       if (ev1 && hipEventRecord(ev1, st) != hipSuccess) return SIMPLE_EDEVICE;
       if (simple::launch_pending_rows(a, dtype, vec, st) != hipSuccess) return SIMPLE_EDEVICE;

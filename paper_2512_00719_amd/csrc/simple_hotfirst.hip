@@ -12,9 +12,10 @@
 // Rows the kernel takes itself: temperature > 0 and no truncation (no top-k, top-p, min-p) — with a
 // survivor set that is all of V, Eq. (7) needs nothing of the tail but its mass.  (A truncated
 // row's survivor set may reach into the tail, and which tail columns survive cannot be told from a
-// maximum and a sum.)  Every other row is queued for the general kernel, which serves it with the
-// hot set [0, H) as a membership mask; so each row of the call gets the ids of the speculative
-// sampler as the CPU oracle defines them.
+// maximum and a sum.)  Every other row is served with the hot set [0, H) as a membership mask: in
+// a bfloat16 call the pattern-count kernel, which runs ahead of this one, completes the truncated
+// rows without penalties; the rest is queued for the general kernel.  So each row of the call gets
+// the ids of the speculative sampler as the definition over the whole row gives them.
 //
 // One workgroup per row.  Masses are 2^44 fixed-point integers relative to the row maximum (the
 // stable softmax numerator of Eq. (2)), so sums do not depend on the order of the additions; the
@@ -135,8 +136,9 @@ __global__ __launch_bounds__(HT) void hot_first_rows_kernel(const SampleArgs a, 
   const simple_row_params par = a.params[row];
   const simple_tail_stats ts = tail[row];
   if (row == 0 && tid == 0) { a.pend[a.parity ^ 1] = 0u; a.wq[a.parity ^ 1] = 0u; }  // the previous launch's counts
-  const bool plain = par.temperature > 0.0f && !(par.top_k >= 1 && par.top_k < V) && !(par.top_p < 1.0f) && !(par.min_p > 0.0f) &&
-                     par.rep_penalty == 1.0f && par.freq_penalty == 0.0f && par.pres_penalty == 0.0f;
+  // the pattern-count kernel, when it ran before this one, has left NOT_TAKEN on every row that is still to do
+  if (a.pattern_on && a.out[row] != NOT_TAKEN) return;
+  const bool plain = hot_first_plain(par, V);
   if (!plain) {  // truncated, penalised, greedy or invalid rows: the general kernel, with [0, H) as the hot set
     if (tid == 0) { const unsigned slot = atomicAdd(&a.pend[a.parity], 1u); a.pend[2 + slot] = (uint32_t)row; a.out[row] = PENDING; }
     return;

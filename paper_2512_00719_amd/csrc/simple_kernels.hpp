@@ -79,7 +79,8 @@ struct SampleArgs {
   uint32_t st_stride;
   int max_nnz;
   int gated;       // 1: the single-pass kernel runs first and queues the rows it leaves
-  int pattern_on;  // 1: the pattern-count kernel (bfloat16 rows without top-k and penalties) ran before the single-pass kernel
+  int pattern_on;  // the pattern-count kernel (bfloat16 rows without penalties and without a short top-k) ran first: 1 before the
+                   // single-pass kernel, 2 before the hot-first kernel (it then leaves that kernel's own rows alone)
   // Queues filled by the single-pass kernel.  Word [parity] counts the entries of this launch; the
   // single-pass kernel clears word [parity ^ 1], which the previous launch on the stream used.
   uint32_t* pend;  // rows left to the general kernel: [0], [1] counts, [2 ..] row indices
@@ -143,6 +144,13 @@ __device__ __forceinline__ bool pattern_route(const simple_row_params& par, int 
   const bool small_k = par.top_k >= 1 && par.top_k < V && par.top_k <= KMAXF;
   return par.temperature > 0.0f && par.temperature < INFINITY && par.rep_penalty > 0.0f && !small_k && par.top_p > 0.0f &&
          !(nnz > 0 && pen_on) && nnz <= max_nnz;
+}
+
+// Rows that the hot-first kernel decides from the hot columns and the caller's tail statistics alone:
+// temperature sampling without truncation and without penalties.
+__device__ __forceinline__ bool hot_first_plain(const simple_row_params& par, int V) {
+  return par.temperature > 0.0f && !(par.top_k >= 1 && par.top_k < V) && !(par.top_p < 1.0f) && !(par.min_p > 0.0f) &&
+         par.rep_penalty == 1.0f && par.freq_penalty == 0.0f && par.pres_penalty == 0.0f;
 }
 
 LdsLayout make_layout(int64_t V, int64_t max_nnz, bool with_history);

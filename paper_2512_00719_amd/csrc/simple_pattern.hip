@@ -160,7 +160,8 @@ __global__ __launch_bounds__(PT, 4) void pattern_rows_kernel(const SampleArgs a)
   const simple_row_params par = a.params[row];
   {
     const RowHist rh = row_history(a, row, par.n_prompt);
-    if (!pattern_route(par, V, rh.nnz, a.max_nnz)) {  // the single-pass kernel takes the row
+    // (ahead of the hot-first kernel: not the rows that kernel decides from the hot columns alone)
+    if (!pattern_route(par, V, rh.nnz, a.max_nnz) || (a.pattern_on == 2 && hot_first_plain(par, V))) {  // the kernel behind this one takes the row
       if (threadIdx.x == 0) a.out[row] = NOT_TAKEN;
       return;
     }
