@@ -21,6 +21,7 @@ struct simple_ctx {
   int lds_limit;
   int n_cu;
   uint32_t* pend;       // device: queue of rows the single-pass kernel leaves to the general kernel
+  int32_t* order;       // device: row of each workgroup of the single-pass kernel (rows with long epilogues first)
   uint32_t* wq;         // device: queue of rows for the whole-vocabulary-nucleus kernels
   unsigned char* wws;   // device: their workspace, `slots` slots
   uint32_t ws_stride;   // bytes per slot
@@ -52,7 +53,7 @@ namespace simple {
 // Device memory of a context, carved from one block: hot-set bitmap (max_V bits), one flag word, the
 // pending-row queue (two counters, then one entry per row of a launch), the wide-row queue (a head,
 // then one 64-byte record per slot) and the slots.  Every part starts on a 256-byte boundary.
-struct CtxLayout { size_t hot_bits, hot_flags, pend, wq, wws, total; uint32_t ws_stride; };
+struct CtxLayout { size_t hot_bits, hot_flags, pend, order, wq, wws, total; uint32_t ws_stride; };
 // Maxima of simple_sample_static, whose context lives in a static device array.
 constexpr int64_t STATIC_MAX_V = ((int64_t)1 << 18) - 1;
 constexpr int64_t STATIC_MAX_NNZ = 8192;
@@ -120,6 +121,7 @@ CtxLayout ctx_layout(int64_t max_V, int64_t max_nnz, int slots, int lds_limit, i
   L.hot_bits = off;  off = align256(off + ((size_t)((max_V + 31) / 32) + 1) * 4u);
   L.hot_flags = off; off = align256(off + 4u);
   L.pend = off;      off = align256(off + (2u + (size_t)slots) * 4u);
+  L.order = off;     off = align256(off + (size_t)slots * 4u);  // the order in which the single-pass kernel takes a launch's rows
   L.wq = off;        off = align256(off + 64u + 64u * (size_t)slots);  // head, then one 64-byte record per slot
   // a slot holds the fixed part and the largest history tables the single-pass kernel can have
   const FastLayout Fm = make_fast_layout(max_V < ((int64_t)1 << 18) ? max_V : ((int64_t)1 << 18) - 1, SIMPLE_F32,
@@ -178,7 +180,7 @@ int simple_create(simple_ctx** out, int device, int64_t max_B, int64_t max_V, in
   simple_ctx* c = new (std::nothrow) simple_ctx();
   if (!c) return SIMPLE_ENOMEM;
   c->device = device; c->max_V = max_V; c->max_nnz = max_nnz_per_row; c->lds_limit = lds; c->n_cu = n_cu;
-  c->hot_V = 0; c->hot_H = 0; c->hot_is_range = false; c->hot_bits = nullptr; c->hot_flags = nullptr; c->pend = nullptr; c->wq = nullptr; c->wws = nullptr; c->ws_stride = 0; c->parity = 0;
+  c->hot_V = 0; c->hot_H = 0; c->hot_is_range = false; c->hot_bits = nullptr; c->hot_flags = nullptr; c->pend = nullptr; c->order = nullptr; c->wq = nullptr; c->wws = nullptr; c->ws_stride = 0; c->parity = 0;
   c->prof_ev = nullptr; c->prof_n = 0; c->base = nullptr; c->slots = 0; c->stats = nullptr;
   c->logprobs = nullptr; c->eos_out = nullptr; c->n_eos = 0;
   c->slots = (int)(max_B < (int64_t)simple::WIDE_SLOTS ? max_B : (int64_t)simple::WIDE_SLOTS);
@@ -192,6 +194,7 @@ int simple_create(simple_ctx** out, int device, int64_t max_B, int64_t max_V, in
   c->hot_bits = reinterpret_cast<uint32_t*>(base + CL.hot_bits);
   c->hot_flags = reinterpret_cast<uint32_t*>(base + CL.hot_flags);
   c->pend = reinterpret_cast<uint32_t*>(base + CL.pend);
+  c->order = reinterpret_cast<int32_t*>(base + CL.order);
   c->wq = reinterpret_cast<uint32_t*>(base + CL.wq);
   c->wws = base + CL.wws;
   c->ws_stride = CL.ws_stride;
@@ -351,6 +354,7 @@ static int sample_impl(simple_ctx* ctx, const simple_state* state, const int32_t
   for (int i = 0; i < 8; ++i) a.eos_ids[i] = ctx->eos_ids[i];
   a.max_nnz = (int)ctx->max_nnz;
   a.pend = ctx->pend;
+  a.order = ctx->order;
   a.n_cu = ctx->n_cu;
   a.wq = ctx->wq; a.wws = ctx->wws; a.wide_slots = ctx->slots; a.ws_stride = ctx->ws_stride;
   a.L = simple::make_layout(V, ctx->max_nnz, with_hist);
@@ -373,6 +377,7 @@ static int sample_impl(simple_ctx* ctx, const simple_state* state, const int32_t
     a.diag = diag_dev ? diag_dev + b0 : nullptr;
     a.logprobs = ctx->logprobs ? ctx->logprobs + b0 : nullptr;
     a.eos_out = ctx->eos_out ? ctx->eos_out + b0 : nullptr;
+    a.order = (a.F.total != 0u && !tail && nb > (int64_t)ctx->n_cu) ? ctx->order : nullptr;
     a.parity = ctx->parity;
     if (a.gated) ctx->parity ^= 1;
     hipEvent_t ev0 = nullptr, ev1 = nullptr;
@@ -525,6 +530,7 @@ static simple_ctx* static_ctx(int* err) {
   c->hot_bits = reinterpret_cast<uint32_t*>(ptr + L.hot_bits);
   c->hot_flags = reinterpret_cast<uint32_t*>(ptr + L.hot_flags);
   c->pend = reinterpret_cast<uint32_t*>(ptr + L.pend);
+  c->order = reinterpret_cast<int32_t*>(ptr + L.order);
   c->wq = reinterpret_cast<uint32_t*>(ptr + L.wq);
   c->wws = ptr + L.wws;
   c->ws_stride = L.ws_stride;

@@ -475,12 +475,12 @@ __global__ __launch_bounds__(NTHR, 4) void fast_rows_kernel(const SampleArgs a) 
   extern __shared__ __align__(16) unsigned char lds[];
   __shared__ FS S;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int row = blockIdx.x;
+  const int row = a.order ? a.order[blockIdx.x] : (int)blockIdx.x;  // (rows with long epilogues first: see order_rows_kernel)
   const int V = a.V;
   const DT* rowp = reinterpret_cast<const DT*>(a.logits) + (size_t)row * (size_t)a.stride;
   // the pattern-count kernel, when it ran before this one, has left NOT_TAKEN on every row that is still to do
   if (a.pattern_on && a.out[row] != NOT_TAKEN) {
-    if (row == 0 && tid == 0) { a.pend[a.parity ^ 1] = 0u; a.wq[a.parity ^ 1] = 0u; }  // the previous launch's counts
+    if (blockIdx.x == 0 && tid == 0) { a.pend[a.parity ^ 1] = 0u; a.wq[a.parity ^ 1] = 0u; }  // the previous launch's counts
     return;
   }
   // this wave's first two tiles (its threshold sample): issued before anything else
@@ -492,7 +492,7 @@ __global__ __launch_bounds__(NTHR, 4) void fast_rows_kernel(const SampleArgs a) 
 #pragma unroll
   for (int u = 0; u < UNR; ++u) Bf[u] = Io<DT>::load(rowp + (size_t)(t0 + 1) * T + u * 64 * EPL + lane * EPL);
   const simple_row_params par = a.params[row];
-  if (row == 0 && tid == 0) { a.pend[a.parity ^ 1] = 0u; a.wq[a.parity ^ 1] = 0u; }  // the previous launch's counts
+  if (blockIdx.x == 0 && tid == 0) { a.pend[a.parity ^ 1] = 0u; a.wq[a.parity ^ 1] = 0u; }  // the previous launch's counts
   uint32_t* samp = reinterpret_cast<uint32_t*>(lds + a.F.samp);
 
   // ---- row configuration (identical in every thread) ----
@@ -704,7 +704,7 @@ __global__ __launch_bounds__(NTHR, 4) void fast_rows_kernel(const SampleArgs a) 
   // Their waves go first where waves of several rows compete for a SIMD's issue slots (measured on the
   // heterogeneous batch: 3.6 us of 142; raising them in the phase before the stream as well, or every
   // row's epilogue, loses that again).
-  const bool long_row = R.need_sum || (R.k_on && R.top_k > 512);
+  const bool long_row = long_epilogue(par, V);
   if (long_row) __builtin_amdgcn_s_setprio(3);
   const int t_end = (int)(((long long)(wave + 1) * nfull) / NWV);
   const unsigned n_dyn = (unsigned)(nfull - 2 * NWV);
@@ -985,6 +985,45 @@ static hipError_t launch_fast_instance(const SampleArgs& a, int dtype, hipStream
   }
   return hipGetLastError();
 }
+// The order in which the single-pass kernel's workgroups take the rows of a launch: rows with long
+// epilogues first, the others behind them, each group in row order.  Workgroups are handed to the
+// compute units in turn, so that a compute unit holds workgroups b, b + (number of compute units),
+// ...: with the long rows at the front every compute unit gets its share of them instead of some
+// holding four (measured on the heterogeneous batch: a compute unit with four such rows finishes
+// 20 us after one with two), and a launch of several rounds starts its longest rows first.
+constexpr int ORD_T = 1024;
+__global__ __launch_bounds__(ORD_T) void order_rows_kernel(const SampleArgs a) {
+  __shared__ unsigned wsum[ORD_T / 64];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  constexpr int PER = (WIDE_SLOTS + ORD_T - 1) / ORD_T;  // rows per thread, contiguous (a launch has at most WIDE_SLOTS rows)
+  const int r0 = tid * PER;
+  unsigned flags = 0u, n_long = 0u;
+#pragma unroll
+  for (int j = 0; j < PER; ++j) {
+    const int r = r0 + j;
+    if (r < a.B && long_epilogue(a.params[r], a.V)) { flags |= 1u << j; ++n_long; }
+  }
+  const unsigned incl = wave_incl_scan(n_long);
+  if (lane == 63) wsum[wave] = incl;
+  __syncthreads();
+  unsigned before = 0u, total = 0u;
+#pragma unroll
+  for (int w = 0; w < ORD_T / 64; ++w) { const unsigned x = wsum[w]; if (w < wave) before += x; total += x; }
+  unsigned pos_long = before + incl - n_long;            // long rows before this thread's
+  unsigned pos_short = total + (unsigned)min(r0, a.B) - pos_long;  // behind all long rows: short rows before this thread's
+#pragma unroll
+  for (int j = 0; j < PER; ++j) {
+    const int r = r0 + j;
+    if (r < a.B) a.order[((flags >> j) & 1u) ? pos_long++ : pos_short++] = r;
+  }
+}
+
+hipError_t launch_order(const SampleArgs& a, hipStream_t st) {
+  if (!a.order || a.B <= 0 || a.B > WIDE_SLOTS) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(order_rows_kernel, dim3(1), dim3(ORD_T), 0, st, a);
+  return hipGetLastError();
+}
+
 hipError_t launch_fast(const SampleArgs& a, int dtype, hipStream_t st) {
   return a.st_rec ? launch_fast_instance<true>(a, dtype, st) : launch_fast_instance<false>(a, dtype, st);
 }

@@ -1596,6 +1596,10 @@ hipError_t launch_pending_rows(const SampleArgs& a, int dtype, bool vec, hipStre
 
 // ev0 / ev1 (may be null): recorded right before and after the dominant kernel of the call.
 hipError_t launch_sample(const SampleArgs& a, int dtype, bool vec, hipStream_t st, hipEvent_t ev0, hipEvent_t ev1) {
+  if (a.gated && a.order) {  // (with no more rows than compute units every row has one to itself: nothing to balance)
+    const hipError_t e = launch_order(a, st);
+    if (e != hipSuccess) return e;
+  }
   if (ev0 && hipEventRecord(ev0, st) != hipSuccess) return hipErrorUnknown;
   if (a.gated) {  // single-pass kernel first; the general kernel then completes the rows it queued
     hipError_t e = a.pattern_on ? launch_pattern(a, st) : hipSuccess;

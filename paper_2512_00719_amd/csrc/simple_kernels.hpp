@@ -84,6 +84,8 @@ struct SampleArgs {
   // Queues filled by the single-pass kernel.  Word [parity] counts the entries of this launch; the
   // single-pass kernel clears word [parity ^ 1], which the previous launch on the stream used.
   uint32_t* pend;  // rows left to the general kernel: [0], [1] counts, [2 ..] row indices
+  int32_t* order;  // row of each workgroup of the single-pass kernel (written by the ordering kernel of a launch with more rows
+                   // than compute units), or nullptr: workgroup b takes row b
   uint32_t* wq;    // rows with a whole-vocabulary nucleus wider than the list: [0], [1] counts, records from word 16
   unsigned char* wws;  // one workspace slot per queued row
   int wide_slots;
@@ -153,12 +155,22 @@ __device__ __forceinline__ bool hot_first_plain(const simple_row_params& par, in
          par.rep_penalty == 1.0f && par.freq_penalty == 0.0f && par.pres_penalty == 0.0f;
 }
 
+// Rows whose work in the single-pass kernel goes on longest after the stream: those that sum the whole row
+// (a nucleus without top-k) and top-k rows with long lists.
+__device__ __forceinline__ bool long_epilogue(const simple_row_params& par, int V) {
+  const bool greedy = par.temperature == 0.0f;
+  const bool k_on = par.top_k >= 1 && par.top_k < V;
+  const bool need_sum = !greedy && !k_on && par.top_p < 1.0f && !(par.top_p <= 0.0f);
+  return need_sum || (k_on && par.top_k > 512);
+}
+
 LdsLayout make_layout(int64_t V, int64_t max_nnz, bool with_history);
 // Layout of the single-pass kernel; total = 0 when the call cannot use it.
 FastLayout make_fast_layout(int64_t V, int dtype, int64_t max_nnz, bool with_history, bool vec, int lds_limit,
                             int64_t B, int n_cu);
 hipError_t launch_sample(const SampleArgs& a, int dtype, bool vec, hipStream_t st, hipEvent_t ev0, hipEvent_t ev1);
 hipError_t launch_fast(const SampleArgs& a, int dtype, hipStream_t st);
+hipError_t launch_order(const SampleArgs& a, hipStream_t st);  // fills a.order; before launch_fast
 hipError_t launch_pattern(const SampleArgs& a, hipStream_t st);  // before launch_fast, when a.pattern_on
 hipError_t launch_wide(const SampleArgs& a, int dtype, hipStream_t st);  // after launch_fast, before the general kernel
 hipError_t set_max_lds(unsigned bytes);
