@@ -439,7 +439,7 @@ __device__ __forceinline__ void item_fetch(ItemLoads<DT>& L, const SampleArgs& a
 
 // ---------------------------------------------------------------- bins ------------------------
 template <typename DT>
-__global__ __launch_bounds__(WT, 5) void wide_bins_kernel(const SampleArgs a) {
+__global__ __launch_bounds__(WT, (sizeof(DT) == 4 ? 4 : 5)) void wide_bins_kernel(const SampleArgs a) {
   constexpr int EPL = Io<DT>::EPL;
   constexpr int G = ItemLoads<DT>::G;
   __shared__ SliceTabs Tb;
@@ -1047,7 +1047,7 @@ hipError_t launch_wide(const SampleArgs& a, int dtype, hipStream_t st) {
   // registers and LDS; a workgroup then takes a contiguous run of slices, mostly of one row.
   const dim3 bins((unsigned)a.n_cu * 5u), cls((unsigned)a.n_cu * 4u), fin(1024), blk(fast::WT);
   if (dtype == SIMPLE_F32) {
-    hipLaunchKernelGGL((fast::wide_bins_kernel<float>), bins, blk, 0, st, a);
+    hipLaunchKernelGGL((fast::wide_bins_kernel<float>), cls, blk, 0, st, a);  // (float32: four workgroups per compute unit, no spilled register)
     if (a.hot_bits) hipLaunchKernelGGL((fast::wide_classify_kernel<float, true>), cls, blk, 0, st, a);
     else hipLaunchKernelGGL((fast::wide_classify_kernel<float, false>), cls, blk, 0, st, a);
     hipLaunchKernelGGL((fast::wide_finish_kernel<float>), fin, blk, 0, st, a);
