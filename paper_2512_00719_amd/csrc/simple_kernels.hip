@@ -991,7 +991,9 @@ __device__ __noinline__ Cut descend(const RowReader<DT>& R_in, Shared& S, uint32
     const int w = widths[lvl];
     shift -= w;
     for (int i = tid; i < NBINS; i += NT) { hcnt[i] = 0u; if (by_mass) hmass[i] = 0ull; }
-    if (tid == 0) { S.sel_found = 0u; if (lvl == 1) S.list_n = 0u; }
+    // (S.sel_found is not cleared between levels: a wave may still be reading the level before's
+    // verdict when thread 0 gets here, so each level marks its hit with its own number instead)
+    if (tid == 0) { if (lvl == 0) S.sel_found = 0u; if (lvl == 1) S.list_n = 0u; }
     __syncthreads();
     auto tally = [&](uint32_t key) {
       const unsigned d = (key >> shift) & ((1u << w) - 1u);
@@ -1058,13 +1060,14 @@ __device__ __noinline__ Cut descend(const RowReader<DT>& R_in, Shared& S, uint32
       else hit = (above_c < need) && (need <= above_c + lc[j]);
       if (hit) {
         S.sel_digit = 4 * tid + j; S.sel_above_cnt = above_c; S.sel_above_mass = above_m;
-        S.sel_cnt = lc[j]; S.sel_found = 1u;
+        S.sel_cnt = lc[j]; S.sel_found = (unsigned)lvl + 1u;
       }
       above_c += lc[j]; above_m += lm[j];
     }
     __syncthreads();
-    if (!S.sel_found) {  // cannot happen for consistent inputs; fail the row rather than guess
+    if (S.sel_found != (unsigned)lvl + 1u) {  // cannot happen for consistent inputs; fail the row rather than guess
       if (tid == 0) S.flags |= SIMPLE_DIAG_ERROR;
+      __syncthreads();  // (the caller reads the flag in every thread)
       Cut bad = {KEY_POS_INF, 0u, 0ull, 0u, 0u, 0ull};
       return bad;
     }
