@@ -700,12 +700,6 @@ __global__ __launch_bounds__(NTHR, 4) void fast_rows_kernel(const SampleArgs a) 
   // 1 % slower at four waves, 1.5 to 3 % faster at eight).  No result depends on which wave took
   // which tile (the list is ranked by value and id, the masses are integers).
   constexpr bool HAND_OUT = NWV > 4;
-  // The launch ends with its slowest rows: those that sum the whole row and those with long lists.
-  // Their waves go first where waves of several rows compete for a SIMD's issue slots (measured on the
-  // heterogeneous batch: 3.6 us of 142; raising them in the phase before the stream as well, or every
-  // row's epilogue, loses that again).
-  const bool long_row = long_epilogue(par, V);
-  if (long_row) __builtin_amdgcn_s_setprio(3);
   const int t_end = (int)(((long long)(wave + 1) * nfull) / NWV);
   const unsigned n_dyn = (unsigned)(nfull - 2 * NWV);
   int t_own = t0 + 2;  // contiguous shares: this wave's next tile
@@ -769,7 +763,6 @@ __global__ __launch_bounds__(NTHR, 4) void fast_rows_kernel(const SampleArgs a) 
       if (slot < cap) { lz[slot] = __float_as_uint(zz); li[slot] = (uint32_t)idx; }
     }
   }
-  if (long_row) __builtin_amdgcn_s_setprio(2);
   __syncthreads();
 
   // ---- epilogue ----
