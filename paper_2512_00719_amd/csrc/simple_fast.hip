@@ -987,28 +987,7 @@ static hipError_t launch_fast_instance(const SampleArgs& a, int dtype, hipStream
 constexpr int ORD_T = 1024;
 __global__ __launch_bounds__(ORD_T) void order_rows_kernel(const SampleArgs a) {
   __shared__ unsigned wsum[ORD_T / 64];
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  constexpr int PER = (WIDE_SLOTS + ORD_T - 1) / ORD_T;  // rows per thread, contiguous (a launch has at most WIDE_SLOTS rows)
-  const int r0 = tid * PER;
-  unsigned flags = 0u, n_long = 0u;
-#pragma unroll
-  for (int j = 0; j < PER; ++j) {
-    const int r = r0 + j;
-    if (r < a.B && long_epilogue(a.params[r], a.V)) { flags |= 1u << j; ++n_long; }
-  }
-  const unsigned incl = wave_incl_scan(n_long);
-  if (lane == 63) wsum[wave] = incl;
-  __syncthreads();
-  unsigned before = 0u, total = 0u;
-#pragma unroll
-  for (int w = 0; w < ORD_T / 64; ++w) { const unsigned x = wsum[w]; if (w < wave) before += x; total += x; }
-  unsigned pos_long = before + incl - n_long;            // long rows before this thread's
-  unsigned pos_short = total + (unsigned)min(r0, a.B) - pos_long;  // behind all long rows: short rows before this thread's
-#pragma unroll
-  for (int j = 0; j < PER; ++j) {
-    const int r = r0 + j;
-    if (r < a.B) a.order[((flags >> j) & 1u) ? pos_long++ : pos_short++] = r;
-  }
+  order_rows_body<ORD_T>(a, wsum);
 }
 
 hipError_t launch_order(const SampleArgs& a, hipStream_t st) {

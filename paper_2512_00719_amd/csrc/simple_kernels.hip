@@ -1599,7 +1599,8 @@ hipError_t launch_pending_rows(const SampleArgs& a, int dtype, bool vec, hipStre
 
 // ev0 / ev1 (may be null): recorded right before and after the dominant kernel of the call.
 hipError_t launch_sample(const SampleArgs& a, int dtype, bool vec, hipStream_t st, hipEvent_t ev0, hipEvent_t ev1) {
-  if (a.gated && a.order) {  // (with no more rows than compute units every row has one to itself: nothing to balance)
+  if (a.gated && a.order && !a.pattern_on) {  // (with no more rows than compute units every row has one to itself: nothing to balance;
+                                               //  ahead of a bfloat16 call's single-pass kernel the pattern-count kernel writes the order)
     const hipError_t e = launch_order(a, st);
     if (e != hipSuccess) return e;
   }

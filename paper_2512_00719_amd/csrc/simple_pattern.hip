@@ -157,6 +157,10 @@ __global__ __launch_bounds__(PT, 4) void pattern_rows_kernel(const SampleArgs a)
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int row = blockIdx.x;
   const int V = a.V;
+  if (row == a.B) {  // the workgroup behind the rows: the order in which the kernel after this one takes them
+    order_rows_body<PT>(a, reinterpret_cast<unsigned*>(tcc));
+    return;
+  }
   const simple_row_params par = a.params[row];
   {
     const RowHist rh = row_history(a, row, par.n_prompt);
@@ -572,8 +576,11 @@ __global__ __launch_bounds__(PT, 4) void pattern_rows_kernel(const SampleArgs a)
 
 hipError_t launch_pattern(const SampleArgs& a, hipStream_t st) {
   if (a.B <= 0) return hipSuccess;
-  if (a.hot_bits) hipLaunchKernelGGL((pattern::pattern_rows_kernel<true>), dim3((unsigned)a.B), dim3(pattern::PT), 0, st, a);
-  else hipLaunchKernelGGL((pattern::pattern_rows_kernel<false>), dim3((unsigned)a.B), dim3(pattern::PT), 0, st, a);
+  // (one more workgroup when the single-pass kernel behind this one takes its rows in a written order:
+  // it writes that order, which saves the launch of a kernel for it)
+  const dim3 grid((unsigned)a.B + (a.order && a.pattern_on == 1 ? 1u : 0u));
+  if (a.hot_bits) hipLaunchKernelGGL((pattern::pattern_rows_kernel<true>), grid, dim3(pattern::PT), 0, st, a);
+  else hipLaunchKernelGGL((pattern::pattern_rows_kernel<false>), grid, dim3(pattern::PT), 0, st, a);
   return hipGetLastError();
 }
 

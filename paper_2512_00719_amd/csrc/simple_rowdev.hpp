@@ -384,4 +384,34 @@ __device__ __forceinline__ uint32_t below_term_clamped(float z, const StreamCtx&
 }
 
 }  // namespace fast
+
+// The order in which the single-pass kernel's workgroups take the rows of a launch: rows with long
+// epilogues first (a stable partition of 0 .. B-1 by long_epilogue), written to a.order by one
+// workgroup of NT_ threads; `wsum` is LDS scratch of NT_ / 64 words.
+template <int NT_>
+__device__ __forceinline__ void order_rows_body(const SampleArgs& a, unsigned* wsum) {
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  constexpr int PER = (WIDE_SLOTS + NT_ - 1) / NT_;  // rows per thread, contiguous (a launch has at most WIDE_SLOTS rows)
+  const int r0 = tid * PER;
+  unsigned flags = 0u, n_long = 0u;
+#pragma unroll
+  for (int j = 0; j < PER; ++j) {
+    const int r = r0 + j;
+    if (r < a.B && long_epilogue(a.params[r], a.V)) { flags |= 1u << j; ++n_long; }
+  }
+  const unsigned incl = wave_incl_scan(n_long);
+  if (lane == 63) wsum[wave] = incl;
+  __syncthreads();
+  unsigned before = 0u, total = 0u;
+#pragma unroll
+  for (int w = 0; w < NT_ / 64; ++w) { const unsigned x = wsum[w]; if (w < wave) before += x; total += x; }
+  unsigned pos_long = before + incl - n_long;            // long rows before this thread's
+  unsigned pos_short = total + (unsigned)min(r0, a.B) - pos_long;  // behind all long rows: short rows before this thread's
+#pragma unroll
+  for (int j = 0; j < PER; ++j) {
+    const int r = r0 + j;
+    if (r < a.B) a.order[((flags >> j) & 1u) ? pos_long++ : pos_short++] = r;
+  }
+}
+
 }  // namespace simple
